@@ -1,0 +1,458 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+  - the published Philox4x32-10 known-answer vectors (tests/golden/) and an independent
+    pure-Python Philox;
+  - a pure-Python brute force of NS / LABOR-0 / Eq. (2) on tiny graphs (sets and loops);
+  - structural invariants, the full-fanout = BFS-ball reduction (App. A.1.2, last paragraph),
+    exact nestedness (Sec. 3.1 / proof of Thm 3.1), closed-form expectations;
+  - scipy's ndtr / ndtri for the Phi kit of App. A.7, and the identities n(0) = n1, n(1) = n2;
+  - numpy fancy indexing for the gather, a textbook OrderedDict LRU for the cache.
+"""
+import collections
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+from scipy.special import ndtr, ndtri
+from scipy import stats
+
+import synth
+from oracle import coopref as R
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+M32 = 0xFFFFFFFF
+
+
+# --------------------------------------------------------------------------- #
+# independent pure-Python restatements
+# --------------------------------------------------------------------------- #
+def py_philox(ctr, key, rounds=10):
+    c = [int(x) & M32 for x in ctr]
+    k = [int(x) & M32 for x in key]
+    for _ in range(rounds):
+        p0 = 0xD2511F53 * c[0]
+        p1 = 0xCD9E8D57 * c[2]
+        c = [(p1 >> 32) ^ c[1] ^ k[0], p1 & M32, (p0 >> 32) ^ c[3] ^ k[1], p0 & M32]
+        k = [(k[0] + 0x9E3779B9) & M32, (k[1] + 0xBB67AE85) & M32]
+    return c
+
+
+def py_uniform(seed, sampler, layer, g, t, s):
+    c1 = M32 if sampler == R.LABOR0 else s
+    return py_philox([t, c1, layer | (sampler << 8), g & M32], [seed & M32, seed >> 32])[0]
+
+
+def brute_sample(indptr, indices, seeds, fanouts, sampler, seed, g):
+    """Eq. (2) with sampled neighbourhoods, for c = 0 (variate = first Philox word)."""
+    out = []
+    dst = [int(x) for x in seeds]
+    for layer, k in enumerate(fanouts):
+        ptr, cols, eids = [0], [], []
+        for s in dst:
+            beg, end = int(indptr[s]), int(indptr[s + 1])
+            d = end - beg
+            nbrs = [int(indices[p]) for p in range(beg, end)]
+            if sampler == R.LABOR0:
+                keep = [j for j, t in enumerate(nbrs) if py_uniform(seed, sampler, layer, g, t, s) * d <= (k << 32)]
+            elif d <= k:
+                keep = list(range(d))
+            else:
+                ranked = sorted((py_uniform(seed, sampler, layer, g, t, s), j) for j, t in enumerate(nbrs))
+                keep = sorted(j for _, j in ranked[:k])
+            for j in keep:
+                cols.append(nbrs[j])
+                eids.append(beg + j)
+            ptr.append(len(cols))
+        src = list(dst)
+        seen = set(dst)
+        for t in cols:
+            if t not in seen:
+                seen.add(t)
+                src.append(t)
+        where = {v: i for i, v in enumerate(src)}
+        out.append(dict(dst_ids=dst, indptr=ptr, col_global=cols, eid=eids, src_ids=src,
+                        col_local=[where[t] for t in cols]))
+        dst = src
+    return out
+
+
+def small_graph(n=80, avg=7, hub=40, seed=3):
+    rng = np.random.default_rng(seed)
+    m = n * avg // 2
+    src = rng.integers(0, n, m)
+    dst = rng.integers(0, n, m)
+    src = np.concatenate([src, np.zeros(hub, dtype=np.int64)])          # vertex 0 is a hub
+    dst = np.concatenate([dst, rng.choice(np.arange(1, n), hub, replace=False)])
+    A = sp.coo_matrix((np.ones(len(src)), (src, dst)), shape=(n, n)).tocsr()
+    A = A + A.T
+    A.setdiag(0)
+    A.eliminate_zeros()
+    A.sort_indices()
+    return A.indptr.astype(np.int64), A.indices.astype(np.int32)
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    ip, ix = synth.rmat_csr()
+    return ip.numpy(), ix.numpy()
+
+
+# --------------------------------------------------------------------------- #
+# generator
+# --------------------------------------------------------------------------- #
+def test_philox_known_answers():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        assert R.philox4x32_10(w[0:4], w[4:6]) == w[6:10]
+        assert py_philox(w[0:4], w[4:6]) == w[6:10]
+
+
+def test_philox_matches_independent_python():
+    rng = np.random.default_rng(1)
+    for _ in range(300):
+        ctr = rng.integers(0, 2**32, 4).tolist()
+        key = rng.integers(0, 2**32, 2).tolist()
+        assert R.philox4x32_10(ctr, key) == py_philox(ctr, key)
+
+
+def test_variate_counter_layout():
+    rng = np.random.default_rng(2)
+    for _ in range(200):
+        seed = int(rng.integers(0, 2**63)) * 2 + int(rng.integers(0, 2))
+        sampler = int(rng.integers(0, 2))
+        layer = int(rng.integers(0, 5))
+        it = int(rng.integers(0, 2**40))
+        t, s = int(rng.integers(0, 2**31)), int(rng.integers(0, 2**31))
+        assert R.variate(seed, sampler, layer, it, 1, t, s) == py_uniform(seed, sampler, layer, it, t, s)
+    # LABOR's variate ignores s (one number per source vertex, App. A.1.2)
+    assert R.variate(5, R.LABOR0, 1, 9, 1, 123, 7) == R.variate(5, R.LABOR0, 1, 9, 1, 123, 99)
+    assert R.variate(5, R.NS, 1, 9, 1, 123, 7) != R.variate(5, R.NS, 1, 9, 1, 123, 99)
+
+
+# --------------------------------------------------------------------------- #
+# brute force on tiny graphs
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+@pytest.mark.parametrize("fanouts", [(3, 2), (1, 5, 2), (64,)])
+def test_sample_equals_brute_force(sampler, fanouts):
+    indptr, indices = small_graph()
+    rng = np.random.default_rng(11)
+    for trial in range(3):
+        seeds = rng.choice(80, 9, replace=False).astype(np.int32)
+        seed, g = 1000 + trial, 5 * trial
+        got = R.sample(indptr, indices, seeds, fanouts, sampler, it=g, kappa=1, seed=seed)
+        want = brute_sample(indptr, indices, seeds, fanouts, sampler, seed, g)
+        for b, w in zip(got, want):
+            for name in ("dst_ids", "indptr", "col_global", "eid", "src_ids", "col_local"):
+                assert b[name].tolist() == w[name], name
+
+
+def check_invariants(indptr, indices, blocks, seeds, fanouts, sampler):
+    deg = np.diff(indptr)
+    prev = np.asarray(seeds)
+    for b, k in zip(blocks, fanouts):
+        assert np.array_equal(b["dst_ids"], prev)
+        n_dst, m = len(b["dst_ids"]), len(b["col_global"])
+        assert b["indptr"][0] == 0 and b["indptr"][-1] == m and np.all(np.diff(b["indptr"]) >= 0)
+        # every sampled edge exists, under its own destination
+        assert np.array_equal(indices[b["eid"]], b["col_global"])
+        owner = np.repeat(b["dst_ids"], np.diff(b["indptr"]))
+        assert np.all(indptr[owner] <= b["eid"]) and np.all(b["eid"] < indptr[owner + 1])
+        # adjacency order inside a destination, no edge twice
+        for i in range(n_dst):
+            seg = b["eid"][b["indptr"][i]:b["indptr"][i + 1]]
+            assert np.all(np.diff(seg) > 0)
+        cnt = np.diff(b["indptr"])
+        if sampler == R.NS:
+            assert np.array_equal(cnt, np.minimum(k, deg[b["dst_ids"]]))
+        else:
+            small = deg[b["dst_ids"]] <= k
+            assert np.array_equal(cnt[small], deg[b["dst_ids"]][small])
+        # S^{l+1}: S^l first, no duplicates, the union, first-appearance order
+        src = b["src_ids"]
+        assert np.array_equal(src[:n_dst], b["dst_ids"])
+        assert len(np.unique(src)) == len(src)
+        assert set(src.tolist()) == set(b["dst_ids"].tolist()) | set(b["col_global"].tolist())
+        assert np.array_equal(src[b["col_local"]], b["col_global"])
+        cat = np.concatenate([b["dst_ids"], b["col_global"]])
+        _, first = np.unique(cat, return_index=True)
+        assert np.array_equal(src, cat[np.sort(first)])
+        prev = src
+
+
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+def test_invariants_tiny_config(tiny, sampler):
+    indptr, indices = tiny
+    seeds = synth.seed_batches(len(indptr) - 1, 1024, seed=0)(0).numpy()
+    blocks = R.sample(indptr, indices, seeds, (10, 10, 10), sampler, it=0, kappa=1, seed=0)
+    check_invariants(indptr, indices, blocks, seeds, (10, 10, 10), sampler)
+
+
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+def test_full_fanout_is_bfs_ball(tiny, sampler):
+    """k >= max degree: both samplers use full neighbourhoods, so S^l is the l-hop ball of Eq. (2)."""
+    indptr, indices = tiny
+    n = len(indptr) - 1
+    k = int(np.diff(indptr).max())
+    seeds = np.array([5, 77, 4000, 9001], dtype=np.int32)
+    blocks = R.sample(indptr, indices, seeds, (k, k), sampler, it=3, kappa=1, seed=9)
+    A = sp.csr_matrix((np.ones(len(indices), dtype=np.int8), indices, indptr), shape=(n, n))
+    x = np.zeros(n, dtype=bool)
+    x[seeds] = True
+    for b in blocks:
+        x = x | (A.T @ x.astype(np.int32) > 0)      # S ∪ N(S); the graph is symmetric
+        assert set(np.nonzero(x)[0].tolist()) == set(b["src_ids"].tolist())
+        assert len(b["col_global"]) == int(np.diff(indptr)[b["dst_ids"]].sum())
+
+
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+def test_nestedness_exact(tiny, sampler):
+    """The sampled neighbourhood of s depends on (s, layer, seed, iter) only, hence
+    (A ∪ B)^l = A^l ∪ B^l as sets, and |S^l| is monotone and sub-additive in the batch."""
+    indptr, indices = tiny
+    get = synth.seed_batches(len(indptr) - 1, 512, seed=4)
+    A, B = get(0).numpy(), get(1).numpy()
+    fan = (10, 10, 10)
+    kw = dict(it=7, kappa=1, seed=21)
+    bA = R.sample(indptr, indices, A, fan, sampler, **kw)
+    bB = R.sample(indptr, indices, B, fan, sampler, **kw)
+    bAB = R.sample(indptr, indices, np.concatenate([A, B]), fan, sampler, **kw)
+    for l in range(3):
+        sA, sB, sAB = (set(x[l]["src_ids"].tolist()) for x in (bA, bB, bAB))
+        assert sAB == sA | sB
+        assert len(sAB) <= len(sA) + len(sB) and len(sAB) >= max(len(sA), len(sB))
+
+
+def test_work_monotone_and_concave(tiny):
+    """Thm 3.1: E|S^l| / |S^0| is nonincreasing; Thm 3.2: E|S^l| is concave in the batch size."""
+    indptr, indices = tiny
+    n = len(indptr) - 1
+    sizes = [256, 512, 1024, 2048, 4096]
+    acc = np.zeros((len(sizes), 3))
+    for p in range(8):
+        perm = synth.permutation(n, 900 + p).numpy().astype(np.int32)
+        for i, b in enumerate(sizes):
+            blocks = R.sample(indptr, indices, perm[:b], (10, 10, 10), R.LABOR0, it=p, kappa=1, seed=p)
+            acc[i] += [len(x["src_ids"]) for x in blocks]
+    acc /= 8
+    ratio = acc / np.array(sizes)[:, None]
+    assert np.all(np.diff(ratio, axis=0) < 0)
+    # concavity on the doubling grid: the increment over [b, 2b] is at most twice that over [b/2, b]
+    inc = np.diff(acc, axis=0)
+    assert np.all(inc[1:] <= 2 * inc[:-1] * 1.02)
+
+
+# --------------------------------------------------------------------------- #
+# closed-form expectations (Monte Carlo over the seed)
+# --------------------------------------------------------------------------- #
+def test_labor0_and_ns_expectations():
+    indptr, indices = small_graph(n=120, avg=12, hub=80, seed=8)
+    deg = np.diff(indptr)
+    n = len(deg)
+    seeds = np.arange(0, 40, dtype=np.int32)        # includes the hub (vertex 0)
+    k, trials = 4, 1500
+    cnt_sum = np.zeros(len(seeds))
+    cnt_sq = np.zeros(len(seeds))
+    hit = {R.NS: np.zeros(n), R.LABOR0: np.zeros(n)}
+    edges = {R.NS: 0, R.LABOR0: 0}
+    for tr in range(trials):
+        for sampler in (R.NS, R.LABOR0):
+            b = R.sample(indptr, indices, seeds, (k,), sampler, it=tr, kappa=1, seed=77)[0]
+            edges[sampler] += len(b["col_global"])
+            hit[sampler][np.unique(b["col_global"])] += 1
+            if sampler == R.LABOR0:
+                c = np.diff(b["indptr"])
+                cnt_sum += c
+                cnt_sq += c * c
+    d = deg[seeds].astype(float)
+    mean_want = np.minimum(k, d)
+    var_want = np.where(d > k, k * (1 - k / d), 0.0)
+    mean = cnt_sum / trials
+    var = cnt_sq / trials - mean**2
+    # per-seed Binomial(d, k/d): mean k, variance k(1 - k/d)
+    assert np.all(np.abs(mean - mean_want) <= 4 * np.sqrt(var_want / trials) + 1e-12)
+    assert np.all(np.abs(var - var_want) <= 0.25 * var_want + 1e-12)
+    # E|E^0| = sum_s min(k, d_s) for both samplers (exact for NS)
+    assert edges[R.NS] == trials * int(mean_want.sum())
+    assert abs(edges[R.LABOR0] / trials - mean_want.sum()) <= 4 * math.sqrt(var_want.sum() / trials)
+    # P(t sampled): LABOR-0 max_s min(1, k/d_s); NS 1 - prod_s (1 - min(1, k/d_s)), over seeds s adjacent to t
+    pi_labor = np.zeros(n)
+    pi_ns_c = np.ones(n)
+    for s in seeds:
+        p = min(1.0, k / deg[s])
+        nb = indices[indptr[s]:indptr[s + 1]]
+        pi_labor[nb] = np.maximum(pi_labor[nb], p)
+        pi_ns_c[nb] *= 1 - p
+    for sampler, pi in ((R.LABOR0, pi_labor), (R.NS, 1 - pi_ns_c)):
+        f = hit[sampler] / trials
+        assert np.all(np.abs(f - pi) <= 4.5 * np.sqrt(pi * (1 - pi) / trials) + 1e-12)
+    assert pi_labor.sum() < (1 - pi_ns_c).sum()     # LABOR-0 samples fewer vertices than NS
+
+
+# --------------------------------------------------------------------------- #
+# App. A.7: dependent variates
+# --------------------------------------------------------------------------- #
+def test_kappa_group_identities(tiny):
+    indptr, indices = tiny
+    seeds = synth.seed_batches(len(indptr) - 1, 256, seed=1)(2).numpy()
+    fan = (5, 5)
+
+    def same(a, b):
+        return all(np.array_equal(x[k], y[k]) for x, y in zip(a, b) for k in x)
+
+    for sampler in (R.NS, R.LABOR0):
+        base = R.sample(indptr, indices, seeds, fan, sampler, it=3, kappa=1, seed=5)
+        assert same(base, R.sample(indptr, indices, seeds, fan, sampler, it=3 * 16, kappa=16, seed=5))
+        assert not same(base, R.sample(indptr, indices, seeds, fan, sampler, it=3 * 16 + 1, kappa=16, seed=5))
+        zero = R.sample(indptr, indices, seeds, fan, sampler, it=0, kappa=1, seed=5)
+        assert same(zero, R.sample(indptr, indices, seeds, fan, sampler, it=123456, kappa=0, seed=5))
+
+
+def test_blend_formula_against_scipy():
+    rng = np.random.default_rng(5)
+    worst = 0
+    for _ in range(3000):
+        seed, t, s = int(rng.integers(0, 2**62)), int(rng.integers(0, 2**31)), int(rng.integers(0, 2**31))
+        kappa = int(rng.integers(2, 300))
+        i = int(rng.integers(1, kappa))
+        g = int(rng.integers(0, 1000))
+        sampler, layer = int(rng.integers(0, 2)), int(rng.integers(0, 3))
+        u1 = (py_uniform(seed, sampler, layer, g, t, s) + 0.5) / 2**32
+        u2 = (py_uniform(seed, sampler, layer, g + 1, t, s) + 0.5) / 2**32
+        c = i / kappa
+        n = math.cos(c * math.pi / 2) * ndtri(u1) + math.sin(c * math.pi / 2) * ndtri(u2)
+        want = ndtr(n) * 2**32
+        got = R.variate(seed, sampler, layer, g * kappa + i, kappa, t, s)
+        worst = max(worst, abs(got - want))
+    assert worst <= 16      # Phi^-1 is good to 1.15e-9 relative: a handful of 2^-32 grid steps
+
+
+def test_blend_limits_uniformity_and_correlation():
+    ts = np.arange(20000)
+    K = 1 << 20
+    # c -> 1: the variate approaches the next group's uniform (n(1) = n2)
+    near = np.array([R.variate(3, R.LABOR0, 0, 5 * K + K - 1, K, int(t)) for t in ts[:3000]], dtype=np.float64)
+    nxt = np.array([R.variate(3, R.LABOR0, 0, 6, 1, int(t)) for t in ts[:3000]], dtype=np.float64)
+    assert np.max(np.abs(near - nxt)) / 2**32 < 1e-4
+    # c -> 0+: close to this group's uniform (n(0) = n1)
+    lo = np.array([R.variate(3, R.LABOR0, 0, 5 * K + 1, K, int(t)) for t in ts[:3000]], dtype=np.float64)
+    cur = np.array([R.variate(3, R.LABOR0, 0, 5, 1, int(t)) for t in ts[:3000]], dtype=np.float64)
+    assert np.max(np.abs(lo - cur)) / 2**32 < 1e-4
+    # uniform for every c (n(c) ~ N(0,1)), and corr(n(c1), n(c2)) = cos((c2 - c1) pi / 2) inside a group
+    kappa = 8
+    r = {i: np.array([R.variate(9, R.NS, 1, 40 + i, kappa, int(t), 17) for t in ts], dtype=np.float64) for i in (1, 3, 6)}
+    for i, x in r.items():
+        assert stats.kstest((x + 0.5) / 2**32, "uniform").pvalue > 1e-3
+    nn = {i: ndtri((x + 0.5) / 2**32) for i, x in r.items()}
+    for a, b in ((1, 3), (1, 6), (3, 6)):
+        want = math.cos((b - a) / kappa * math.pi / 2)
+        got = np.corrcoef(nn[a], nn[b])[0, 1]
+        assert abs(got - want) < 4 / math.sqrt(len(ts))
+
+
+def test_phi_kit_against_scipy():
+    L = R.lib()
+    rng = np.random.default_rng(0)
+    xs = np.concatenate([rng.uniform(0.5, 4, 1000), 10.0 ** rng.uniform(-12, 12, 1000)])
+    assert max(abs(L.coopref_rcp(x) * x - 1) for x in xs) < 1e-15
+    assert max(abs(L.coopref_rsqrt(x) ** 2 * x - 1) for x in xs) < 2e-15
+    xs = 10.0 ** rng.uniform(-11, 0, 2000)
+    assert max(abs(L.coopref_log(x) - math.log(x)) / max(abs(math.log(x)), 1e-3) for x in xs) < 1e-14
+    ys = -rng.uniform(0, 60, 2000)
+    assert max(abs(L.coopref_exp(y) / math.exp(y) - 1) for y in ys) < 1e-14
+    Us = np.concatenate([rng.integers(0, 2**32, 8000), np.arange(0, 500), 2**32 - 1 - np.arange(0, 500),
+                         rng.integers(0, 2**20, 2000), 2**31 + np.arange(-3, 3)])
+    for U in Us:
+        U = int(U)
+        x = L.coopref_phi_inv_u32(U)
+        ref = ndtri((U + 0.5) / 2**32)
+        assert abs(x - ref) <= 1.2e-9 * abs(ref) + 1e-15
+        assert L.coopref_phi_inv_u32(M32 - U) == -x                  # exact mirror symmetry
+        assert abs(L.coopref_phi_to_u32(x) - U) <= 2                 # Phi(Phi^-1(u)) = u on the grid
+    for a in np.concatenate([rng.uniform(0, 9, 5000), np.linspace(2.9, 3.1, 401), [0.0]]):
+        assert abs(L.coopref_qtail(a) / ndtr(-a) - 1) < 1e-10
+        lo, hi = L.coopref_phi_to_u32(-a), L.coopref_phi_to_u32(a)
+        assert lo + hi == M32 or a == 0.0
+    assert L.coopref_phi_to_u32(0.0) == 2**31 - 1
+    assert L.coopref_phi_to_u32(-9.5) == 0 and L.coopref_phi_to_u32(9.5) == M32
+
+
+# --------------------------------------------------------------------------- #
+# gather, cache, error paths
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("dtype,dim", [(np.float32, 64), (np.float16, 128), (np.float32, 602), (np.float16, 3)])
+def test_gather_is_fancy_indexing(dtype, dim):
+    rng = np.random.default_rng(0)
+    feat = rng.standard_normal((500, dim)).astype(dtype)
+    ids = rng.integers(0, 500, 1234).astype(np.int32)
+    out = R.gather(feat, ids)
+    assert out.tobytes() == feat[ids].tobytes()
+    assert R.gather(feat, np.zeros(0, np.int32)).shape == (0, dim)
+    with pytest.raises(R.OracleError):
+        R.gather(feat, np.array([500], np.int32))
+
+
+def textbook_lru(capacity):
+    od = collections.OrderedDict()
+
+    def access(v):
+        if v in od:
+            od.move_to_end(v)
+            return True
+        if capacity == 0:
+            return False
+        if len(od) >= capacity:
+            od.popitem(last=False)
+        od[v] = True
+        return False
+
+    return od, access
+
+
+@pytest.mark.parametrize("capacity", [0, 1, 7, 50, 400])
+def test_cache_is_textbook_lru_on_hits_then_misses(capacity):
+    rng = np.random.default_rng(capacity)
+    nV = 300
+    cache = R.Cache(capacity, nV)
+    od, access = textbook_lru(capacity)
+    seen = set()
+    for it in range(60):
+        ids = rng.choice(nV, int(rng.integers(1, 90)), replace=False).astype(np.int32)
+        before = set(od.keys())
+        n_miss, hit = cache.access(ids)
+        assert hit.tolist() == [int(v) in before for v in ids]
+        # hits are touched first: only non-hit entries can be evicted by this batch's misses
+        for v in ids[hit]:
+            assert access(int(v))
+        for v in ids[~hit]:
+            assert not access(int(v))
+        assert n_miss == int((~hit).sum())
+        assert cache.size() == len(od)
+        assert all(cache.contains(v) == (v in od) for v in range(nV))
+        if capacity == 0:
+            assert n_miss == len(ids)
+        if capacity >= nV:
+            assert n_miss == len(set(ids.tolist()) - seen)       # compulsory misses only
+        seen |= set(ids.tolist())
+
+
+def test_error_codes(tiny):
+    indptr, indices = tiny
+    ok = np.array([1, 2, 3], np.int32)
+    for bad_seeds, code in ((np.array([1, 2, 1], np.int32), R.E_DUPSEED), (np.array([1, 1 << 20], np.int32), R.E_RANGE),
+                            (np.array([-1], np.int32), R.E_RANGE)):
+        with pytest.raises(R.OracleError) as e:
+            R.sample(indptr, indices, bad_seeds, (3,), R.NS)
+        assert e.value.code == code
+    for fan in ((), (0,), (3, -1)):
+        with pytest.raises(R.OracleError) as e:
+            R.sample(indptr, indices, ok, fan, R.NS)
+        assert e.value.code == R.E_ARG
+    with pytest.raises(R.OracleError):
+        R.sample(indptr, indices, ok, (3,), 7)
+    empty = R.sample(indptr, indices, np.zeros(0, np.int32), (3, 3), R.LABOR0)
+    assert all(len(b["src_ids"]) == 0 and len(b["col_global"]) == 0 and b["indptr"].tolist() == [0] for b in empty)
