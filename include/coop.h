@@ -1,0 +1,161 @@
+/*
+ * coop.h — C ABI of libcoop: minibatch subgraph sampling and feature loading for GNN
+ * training on one AMD MI355X (gfx950), after "Cooperative Minibatching in Graph Neural
+ * Networks".  One GPU plays the single large processor that owns the whole cooperative
+ * batch (Sec. 3.1): Algorithm 1's sampling loop without the all-to-all, then its feature
+ * loading step.
+ *
+ * Conventions
+ *   - Every function returns COOP_OK (0) or a negative COOP_E_* code; nothing throws or
+ *     aborts across this boundary.  coop_strerror() names a code.
+ *   - "device" pointers are HIP device addresses valid on the current device; "host"
+ *     pointers are ordinary host memory.  All device arrays passed IN are borrowed: the
+ *     caller keeps them alive and unchanged until the call's work on `stream` is done.
+ *   - Device memory handed OUT comes from the caller's allocator callback, so the caller
+ *     (e.g. a PyTorch caching allocator) owns all of it.  The library frees none of it.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All kernels
+ *     of a call run on it.  Calls that return sizes to the host synchronise that stream.
+ *   - Vertex ids are int32 (0 <= id < n_vertices < 2^31); edge positions are int64.
+ */
+#ifndef COOP_H_
+#define COOP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* error codes */
+#define COOP_OK 0
+#define COOP_E_NULL (-1)      /* a required pointer is NULL */
+#define COOP_E_RANGE (-2)     /* a vertex id / seed is outside [0, n_vertices) */
+#define COOP_E_DUPSEED (-3)   /* the seed list holds a vertex twice */
+#define COOP_E_ARG (-4)       /* bad scalar argument (L < 1, fanout < 1, unknown sampler/dtype, ...) */
+#define COOP_E_NOMEM (-5)     /* the allocator callback returned NULL */
+#define COOP_E_CAPACITY (-6)  /* a fixed-size workspace would overflow */
+#define COOP_E_HIP (-7)       /* a HIP runtime call failed */
+#define COOP_E_GRAPH (-8)     /* COOP_VALIDATE found a malformed CSR */
+
+/* samplers (App. A.1) */
+#define COOP_NS 0       /* neighbour sampling: d_s <= k -> all neighbours, else k uniform without replacement */
+#define COOP_LABOR0 1   /* LABOR-0: edge (t->s) kept iff r_t <= k/d_s, one r_t per source vertex and layer */
+
+/* feature element types */
+#define COOP_F32 0
+#define COOP_F16 1
+
+/* coop_graph_load flags */
+#define COOP_VALIDATE 1
+
+/* allocator tags: what the requested buffer is for */
+#define COOP_TAG_OUTPUT 0   /* referenced by a coop_block; lives as long as the caller wants */
+#define COOP_TAG_SCRATCH 1  /* dead once the call that asked for it has returned */
+
+/* Returns a device pointer to at least `bytes` bytes, 256-byte aligned, or NULL. */
+typedef void* (*coop_alloc_fn)(void* ctx, size_t bytes, int tag);
+
+/* A bump allocator over one caller-provided device buffer, usable as (coop_arena_alloc, &arena)
+ * wherever a coop_alloc_fn is asked for: no allocation happens inside the sampling call.
+ * Set used = 0 to recycle the buffer once the previous call's blocks are no longer needed. */
+typedef struct {
+  void* base;    /* device, 256-byte aligned */
+  size_t bytes;  /* size of the buffer */
+  size_t used;   /* bump offset, advanced by coop_arena_alloc */
+} coop_arena;
+void* coop_arena_alloc(void* arena /* coop_arena* */, size_t bytes, int tag);
+
+typedef struct coop_graph coop_graph; /* opaque */
+typedef struct coop_cache coop_cache; /* opaque */
+
+/*
+ * Registers a graph (Sec. 2: N(s) = { t | (t -> s) in E }) given as CSR over destinations:
+ * the in-neighbours of s are indices[indptr[s] .. indptr[s+1]).
+ *   indptr  device int64 [n_vertices + 1], indptr[0] = 0, nondecreasing, indptr[n_vertices] = n_edges
+ *   indices device int32 [n_edges], each in [0, n_vertices)
+ * Both arrays are borrowed for the lifetime of the handle.  With COOP_VALIDATE the arrays are
+ * checked on the GPU (on `stream`, synchronously) and COOP_E_GRAPH is returned if malformed.
+ */
+int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_vertices, int64_t n_edges,
+                    int flags, void* stream, coop_graph** out);
+int coop_graph_free(coop_graph* g);
+
+/*
+ * One sampling layer l of Algorithm 1 as a bipartite block S^{l+1} -> S^l with edges E^l.
+ * All pointers are device memory from the allocator (tag COOP_TAG_OUTPUT).
+ */
+typedef struct {
+  int64_t n_dst;       /* |S^l|      */
+  int64_t n_src;       /* |S^{l+1}|  */
+  int64_t n_edges;     /* |E^l|      */
+  int32_t* dst_ids;    /* [n_dst]    S^l, global ids; layer 0: a copy of the seeds; layer l > 0: the previous src_ids */
+  int64_t* indptr;     /* [n_dst+1]  edges sampled for dst i are [indptr[i], indptr[i+1]), in adjacency order */
+  int32_t* col_local;  /* [n_edges]  position of the edge's source vertex in src_ids */
+  int32_t* col_global; /* [n_edges]  global id of the edge's source vertex */
+  int64_t* eid;        /* [n_edges]  position of the edge in the graph's `indices` array */
+  int32_t* src_ids;    /* [n_src]    S^{l+1} = S^l ∪ sampled sources (Eq. 2): S^l first, in order, then every new
+                                     vertex in order of first appearance in col_global */
+} coop_block;
+
+/*
+ * Multi-layer minibatch sampling: the sampling loop of Algorithm 1 on one processor.
+ * For l = 0 .. L-1, with S^0 = seeds: samples the in-neighbourhood of every s in S^l with fanout
+ * fanouts[l] (fanouts[0] is the seeds' hop) by NS (App. A.1.1) or LABOR-0 (App. A.1.2), then forms
+ * S^{l+1} (Eq. 2) and relabels the edges.
+ *
+ * Random variates (App. A.7): r = R / 2^32 where, for group g = floor(iter / kappa) and c = (iter mod kappa) / kappa,
+ *   U(g) = word 0 of Philox4x32-10 with key (seed low, seed high) and counter
+ *          (t, s for NS | 0xFFFFFFFF for LABOR-0, l | sampler << 8, g mod 2^32);
+ *   c = 0:  R = U(g);
+ *   c > 0:  R = floor(2^32 Phi(cos(c pi/2) Phi^-1(u1) + sin(c pi/2) Phi^-1(u2))), u_i = (U(g+i-1) + 1/2) / 2^32.
+ * kappa = 0 stands for kappa = infinity (g = 0, c = 0).  The result is a pure function of the arguments:
+ * the same (seeds, fanouts, sampler, iter, kappa, seed) give the same bytes on every call.
+ *
+ *   g          graph handle
+ *   seeds      device int32 [n_seeds], distinct, in range (else COOP_E_DUPSEED / COOP_E_RANGE)
+ *   fanouts    host int32 [L], each >= 1; NS needs fanout <= 1024 wherever a degree exceeds it (else COOP_E_CAPACITY)
+ *   blocks_out host coop_block [L], filled on success
+ * Synchronises `stream` (the per-layer sizes are read back).  On error blocks_out is zeroed; buffers
+ * already obtained from the allocator stay with the caller.
+ */
+int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
+                int sampler, uint64_t iter, uint32_t kappa, uint64_t seed, coop_alloc_fn alloc, void* alloc_ctx,
+                void* stream, coop_block* blocks_out);
+
+/*
+ * Feature-loading step of Algorithm 1 (the input-layer rows of the vertices in S^L): out[i, :] = feat[ids[i], :],
+ * an exact copy of bits.
+ *   feat   device (or host memory mapped into the device address space) [n_rows, dim] row-major, dtype elements
+ *   ids    device int32 [n_ids], each in [0, n_rows) (else COOP_E_RANGE, reported by coop_gather_status)
+ *   out    device [n_ids, dim]
+ * Asynchronous on `stream`: returns after the launch.  Host-checkable errors are returned at once.
+ */
+int coop_gather(const void* feat, int64_t n_rows, int32_t dim, int dtype, const int32_t* ids, int64_t n_ids,
+                void* out, void* stream);
+
+/* Synchronises `stream` and returns COOP_E_RANGE if any coop_gather since the last call of this function met an
+ * id outside [0, n_rows) (such rows of `out` are left zero-filled), else COOP_OK.  Clears the condition. */
+int coop_gather_status(void* stream);
+
+/* Name of an error code (static string). */
+const char* coop_strerror(int code);
+
+/* Library ABI version (bumped when a signature in this file changes). */
+int coop_version(void);
+
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launch of the library is bracketed
+ * by HIP events on its stream; coop_profile_read synchronises outstanding events and returns the
+ * accumulated duration and launch count of kernel `id` (0 <= id < coop_profile_kernels()).
+ */
+int coop_profile_enable(int on);
+int coop_profile_reset(void);
+int coop_profile_kernels(void);
+const char* coop_profile_name(int id);
+int coop_profile_read(int id, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COOP_H_ */

@@ -1,0 +1,248 @@
+"""ctypes binding of libcoop.so (see include/coop.h for the contract of every call)."""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcoop.so")
+
+COOP_NS, COOP_LABOR0 = 0, 1
+COOP_F32, COOP_F16 = 0, 1
+COOP_VALIDATE = 1
+TAG_OUTPUT, TAG_SCRATCH = 0, 1
+
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_void_p, C.c_size_t, C.c_int)
+
+
+class _CBlock(C.Structure):
+    _fields_ = [("n_dst", C.c_int64), ("n_src", C.c_int64), ("n_edges", C.c_int64),
+                ("dst_ids", C.c_void_p), ("indptr", C.c_void_p), ("col_local", C.c_void_p),
+                ("col_global", C.c_void_p), ("eid", C.c_void_p), ("src_ids", C.c_void_p)]
+
+
+class _CArena(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("bytes", C.c_size_t), ("used", C.c_size_t)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libcoop.so; fails loudly when it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libcoop.so is not built: run `python -m paper_2310_12403_amd.build` "
+                          "(hipcc, --offload-arch=gfx950) before using paper_2310_12403_amd")
+    L = C.CDLL(_LIB_PATH)
+    L.coop_strerror.argtypes = [C.c_int]
+    L.coop_strerror.restype = C.c_char_p
+    L.coop_version.restype = C.c_int
+    L.coop_arena_alloc.argtypes = [C.c_void_p, C.c_size_t, C.c_int]
+    L.coop_arena_alloc.restype = C.c_void_p
+    L.coop_graph_load.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p,
+                                  C.POINTER(C.c_void_p)]
+    L.coop_graph_load.restype = C.c_int
+    L.coop_graph_free.argtypes = [C.c_void_p]
+    L.coop_graph_free.restype = C.c_int
+    L.coop_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_uint64,
+                              C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_CBlock)]
+    L.coop_sample.restype = C.c_int
+    L.coop_gather.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    L.coop_gather.restype = C.c_int
+    L.coop_gather_status.argtypes = [C.c_void_p]
+    L.coop_gather_status.restype = C.c_int
+    L.coop_profile_enable.argtypes = [C.c_int]
+    L.coop_profile_reset.argtypes = []
+    L.coop_profile_kernels.restype = C.c_int
+    L.coop_profile_name.argtypes = [C.c_int]
+    L.coop_profile_name.restype = C.c_char_p
+    L.coop_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    _lib = L
+    return L
+
+
+class CoopError(RuntimeError):
+    def __init__(self, code):
+        super().__init__("libcoop: %s (%d)" % (coop_strerror(code), code))
+        self.code = code
+
+
+def _check(rc):
+    if rc != 0:
+        raise CoopError(rc)
+
+
+def coop_strerror(code):
+    return lib().coop_strerror(code).decode()
+
+
+def coop_version():
+    return lib().coop_version()
+
+
+def _stream_ptr(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dev_ptr(t, dtype):
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), (t.device, t.dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+class Graph:
+    """Handle of a CSR graph registered with coop_graph_load; keeps the tensors alive."""
+
+    def __init__(self, handle, indptr, indices):
+        self.handle, self.indptr, self.indices = handle, indptr, indices
+        self.n_vertices = indptr.numel() - 1
+        self.n_edges = indices.numel()
+
+    def close(self):
+        if self.handle:
+            lib().coop_graph_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def coop_graph_load(indptr, indices, flags=0, stream=None):
+    """indptr: cuda int64 [n+1]; indices: cuda int32 [nnz] (borrowed for the life of the Graph)."""
+    h = C.c_void_p()
+    rc = lib().coop_graph_load(_dev_ptr(indptr, torch.int64), _dev_ptr(indices, torch.int32), indptr.numel() - 1,
+                               indices.numel(), flags, _stream_ptr(stream), C.byref(h))
+    _check(rc)
+    return Graph(h, indptr, indices)
+
+
+class Arena:
+    """One preallocated device buffer handed to the library's bump allocator (coop_arena_alloc):
+    no allocation, and no Python, runs inside coop_sample.  reset() recycles it."""
+
+    def __init__(self, nbytes, device="cuda"):
+        self.buf = torch.empty(int(nbytes), dtype=torch.uint8, device=device)
+        base = self.buf.data_ptr()
+        self._off = (-base) % 256
+        self.c = _CArena(base + self._off, int(nbytes) - self._off, 0)
+        self.fn = C.cast(lib().coop_arena_alloc, C.c_void_p)
+        self.ctx = C.cast(C.pointer(self.c), C.c_void_p)
+
+    def reset(self):
+        self.c.used = 0
+
+    def view(self, ptr, count, dtype):
+        if count == 0:
+            return torch.empty(0, dtype=dtype, device=self.buf.device)
+        off = ptr - self.buf.data_ptr()
+        nbytes = count * torch.empty(0, dtype=dtype).element_size()
+        return self.buf[off:off + nbytes].view(dtype)
+
+
+class _TorchAllocator:
+    """coop_alloc_fn backed by torch.empty: every buffer is an ordinary torch tensor."""
+
+    def __init__(self, device):
+        self.device = device
+        self.tensors = {}
+        self.error = None
+
+        def _alloc(ctx, nbytes, tag):
+            try:
+                t = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device=self.device)
+                p = t.data_ptr()
+                p += (-p) % 256
+                self.tensors[p] = t
+                return p
+            except Exception as e:  # never let an exception cross the C boundary
+                self.error = e
+                return None
+
+        self.fn_obj = ALLOC_FN(_alloc)
+        self.fn = C.cast(self.fn_obj, C.c_void_p)
+        self.ctx = C.c_void_p()
+
+    def view(self, ptr, count, dtype):
+        if count == 0:
+            return torch.empty(0, dtype=dtype, device=self.device)
+        t = self.tensors[ptr]
+        off = ptr - t.data_ptr()
+        nbytes = count * torch.empty(0, dtype=dtype).element_size()
+        return t[off:off + nbytes].view(dtype)
+
+
+class Block:
+    """One sampled layer: tensors over the memory that the allocator handed out."""
+    __slots__ = ("n_dst", "n_src", "n_edges", "dst_ids", "indptr", "col_local", "col_global", "eid", "src_ids")
+
+
+def coop_sample(graph, seeds, fanouts, sampler, it=0, kappa=1, seed=0, arena=None, stream=None):
+    """Runs L = len(fanouts) sampling layers; returns a list of Block (layer 0 first).
+    With `arena` all device memory comes from that preallocated buffer (and scratch shares it)."""
+    L = len(fanouts)
+    fan = (C.c_int32 * max(L, 1))(*[int(k) for k in fanouts])
+    blocks = (_CBlock * max(L, 1))()
+    al = arena if arena is not None else _TorchAllocator(seeds.device)
+    rc = lib().coop_sample(graph.handle, _dev_ptr(seeds, torch.int32), seeds.numel(), fan, L, sampler, it, kappa, seed,
+                           al.fn, al.ctx, _stream_ptr(stream), blocks)
+    if rc != 0 and getattr(al, "error", None) is not None:
+        raise al.error
+    _check(rc)
+    out = []
+    for l in range(L):
+        b, o = blocks[l], Block()
+        o.n_dst, o.n_src, o.n_edges = b.n_dst, b.n_src, b.n_edges
+        o.dst_ids = al.view(b.dst_ids, b.n_dst, torch.int32)
+        o.indptr = al.view(b.indptr, b.n_dst + 1, torch.int64)
+        o.col_local = al.view(b.col_local, b.n_edges, torch.int32)
+        o.col_global = al.view(b.col_global, b.n_edges, torch.int32)
+        o.eid = al.view(b.eid, b.n_edges, torch.int64)
+        o.src_ids = al.view(b.src_ids, b.n_src, torch.int32)
+        out.append(o)
+    return out
+
+
+_DTYPES = {torch.float32: COOP_F32, torch.float16: COOP_F16}
+
+
+def coop_gather(feat, ids, out=None, stream=None):
+    """out[i, :] = feat[ids[i], :]; feat: [n, dim] fp32/fp16 (device, or pinned host memory mapped to the device)."""
+    assert feat.dim() == 2 and feat.is_contiguous() and feat.dtype in _DTYPES
+    n, dim = feat.shape
+    if out is None:
+        out = torch.empty((ids.numel(), dim), dtype=feat.dtype, device=ids.device)
+    assert out.is_contiguous() and out.dtype == feat.dtype and tuple(out.shape) == (ids.numel(), dim)
+    rc = lib().coop_gather(C.c_void_p(feat.data_ptr()), n, dim, _DTYPES[feat.dtype], _dev_ptr(ids, torch.int32), ids.numel(),
+                           C.c_void_p(out.data_ptr()), _stream_ptr(stream))
+    _check(rc)
+    return out
+
+
+def coop_gather_status(stream=None):
+    _check(lib().coop_gather_status(_stream_ptr(stream)))
+
+
+def profile_enable(on=True):
+    lib().coop_profile_enable(1 if on else 0)
+
+
+def profile_reset():
+    lib().coop_profile_reset()
+
+
+def profile_read_all():
+    """{kernel name: (total ms, launches)} for kernels launched while profiling was on."""
+    L = lib()
+    out = {}
+    for i in range(L.coop_profile_kernels()):
+        ms, n = C.c_double(), C.c_int64()
+        L.coop_profile_read(i, C.byref(ms), C.byref(n))
+        if n.value:
+            out[L.coop_profile_name(i).decode()] = (ms.value, n.value)
+    return out

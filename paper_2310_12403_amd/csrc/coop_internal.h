@@ -1,0 +1,94 @@
+// Host-side internals of libcoop: error helpers, the launch/profiling hook, shared prototypes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "coop.h"
+
+namespace coop {
+
+// Kernel ids for the profiling table (coop_profile_*).
+enum KernelId {
+  K_FILL = 0,        // memory fill (table clear, control words)
+  K_LABOR_COUNT,     // LABOR-0 count pass
+  K_LABOR_FILL,      // LABOR-0 fill pass
+  K_NS_COUNT,        // NS count pass (min(k, d))
+  K_NS_FILL,         // NS selection + fill pass
+  K_SCAN_REDUCE,     // scan: per-block sums
+  K_SCAN_SPINE,      // scan: scan of block sums
+  K_SCAN_APPLY,      // scan: per-block exclusive scan + offsets
+  K_UNIQ_INSERT,     // hash table insert (atomic CAS / min)
+  K_UNIQ_FLAG,       // first-occurrence lookup
+  K_UNIQ_RELABEL,    // new-id compaction + col_local
+  K_COPY_IDS,        // seed copy / src_ids prefix copy
+  K_GATHER,          // feature row gather
+  K_VALIDATE,        // CSR validation
+  K_CACHE_LOOKUP,
+  K_CACHE_SELECT,
+  K_CACHE_UPDATE,
+  K_CACHE_GATHER,
+  K_COUNT_
+};
+
+void prof_begin(int id, hipStream_t s);
+void prof_end(int id, hipStream_t s);
+
+#define COOP_HIP_TRY(expr)                         \
+  do {                                             \
+    hipError_t e__ = (expr);                       \
+    if (e__ != hipSuccess) return COOP_E_HIP;      \
+  } while (0)
+
+// Launches `kernel` on `stream`, bracketed by profiling events when profiling is on.
+#define COOP_LAUNCH(id, kernel, grid, block, shmem, stream, ...)                  \
+  do {                                                                            \
+    ::coop::prof_begin((id), (stream));                                           \
+    hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);          \
+    ::coop::prof_end((id), (stream));                                             \
+  } while (0)
+
+// Device-wide exclusive scans; `tmp` needs scan_tmp_bytes(n) bytes.  out has n + 1 entries, out[n] = total.
+size_t scan_tmp_bytes(int64_t n);
+void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, void* tmp, hipStream_t s);
+// bit flags packed 64 per word -> uint32 exclusive ranks (out has n entries) and the total in *total_out (device)
+void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
+
+void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
+
+// Per-call scratch allocator wrapper: 256-byte rounding, NULL check.
+struct Alloc {
+  coop_alloc_fn fn;
+  void* ctx;
+  bool failed = false;
+  template <typename T>
+  T* get(int64_t count, int tag) {
+    size_t bytes = (size_t)(count > 0 ? count : 1) * sizeof(T);
+    bytes = (bytes + 255) & ~(size_t)255;
+    void* p = fn(ctx, bytes, tag);
+    if (!p) failed = true;
+    return (T*)p;
+  }
+};
+
+// Control block in device memory, mirrored to pinned host memory at every size read-back.
+struct Ctl {
+  int64_t total_edges;   // m_l
+  int64_t total_new;     // |S^{l+1}| - |S^l|
+  int32_t err_range;     // a seed / id out of range
+  int32_t err_dup;       // a duplicate in the seed list
+  int32_t err_capacity;  // NS candidate buffer could not be sized
+  int32_t pad;
+};
+
+// Dedup + relabel of one layer (Eq. 2).  Inputs: dst[n_dst] (distinct), col_global[m].  Outputs: col_local[m],
+// and *src_out = freshly allocated src_ids[n_src].  Reads sizes back (synchronises the stream).
+int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, int32_t* col_local,
+                   int32_t** src_out, int64_t* n_src_out, Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
+
+}  // namespace coop
+
+struct coop_graph {
+  const int64_t* indptr;
+  const int32_t* indices;
+  int64_t n_vertices, n_edges;
+};

@@ -1,0 +1,322 @@
+// libcoop runtime pieces: error names, arena allocator, profiling table, graph handle, fill and scan kernels.
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "coop_internal.h"
+#include "device_utils.h"
+
+namespace coop {
+
+// ---- profiling ------------------------------------------------------------------------------------------------
+namespace {
+struct Pending { int id; hipEvent_t a, b; };
+struct Prof {
+  std::mutex mu;
+  bool on = false;
+  double ms[K_COUNT_] = {};
+  int64_t launches[K_COUNT_] = {};
+  std::vector<Pending> pending;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t open[K_COUNT_] = {};
+} g_prof;
+
+const char* const kKernelNames[K_COUNT_] = {
+    "fill", "labor_count", "labor_fill", "ns_count", "ns_fill", "scan_reduce", "scan_spine", "scan_apply",
+    "unique_insert", "unique_flag", "unique_relabel", "copy_ids", "gather", "validate_csr",
+    "cache_lookup", "cache_select", "cache_update", "cache_gather"};
+
+hipEvent_t take_event() {
+  if (!g_prof.pool.empty()) { hipEvent_t e = g_prof.pool.back(); g_prof.pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// folds finished event pairs into the table; caller holds the lock
+void collect_locked() {
+  for (auto& p : g_prof.pending) {
+    float ms = 0.f;
+    if (hipEventSynchronize(p.b) == hipSuccess && hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+      g_prof.ms[p.id] += ms;
+      g_prof.launches[p.id] += 1;
+    }
+    g_prof.pool.push_back(p.a);
+    g_prof.pool.push_back(p.b);
+  }
+  g_prof.pending.clear();
+}
+}  // namespace
+
+void prof_begin(int id, hipStream_t s) {
+  if (!g_prof.on) return;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  hipEvent_t a = take_event();
+  if (!a) return;
+  (void)hipEventRecord(a, s);
+  g_prof.open[id] = a;
+}
+
+void prof_end(int id, hipStream_t s) {
+  if (!g_prof.on) return;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  hipEvent_t a = g_prof.open[id];
+  if (!a) return;
+  g_prof.open[id] = nullptr;
+  hipEvent_t b = take_event();
+  if (!b) { g_prof.pool.push_back(a); return; }
+  (void)hipEventRecord(b, s);
+  g_prof.pending.push_back({id, a, b});
+  if (g_prof.pending.size() >= 4096) collect_locked();
+}
+
+// ---- fill -----------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_fill_u64(uint64_t* __restrict__ p, int64_t n, uint64_t v) {
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (; i < n; i += stride) p[i] = v;
+}
+
+void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s) {
+  if (n <= 0) return;
+  int64_t blocks = (n + kBlock - 1) / kBlock;
+  if (blocks > 256 * 64) blocks = 256 * 64;
+  COOP_LAUNCH(K_FILL, k_fill_u64, dim3((unsigned)blocks), dim3(kBlock), 0, s, p, n, v);
+}
+
+// ---- device-wide exclusive scan -------------------------------------------------------------------------------
+// Three kernels, no inter-block waiting: (1) per-tile sums, (2) one block scans the tile sums, (3) per-tile
+// exclusive scan shifted by the tile's offset.  A tile is kTile consecutive elements handled by one block.
+constexpr int kItems = 8;
+constexpr int kTile = kBlock * kItems;  // 2048
+
+// inclusive block scan of one int64 per thread; returns the thread's inclusive prefix, *total = block sum
+__device__ __forceinline__ int64_t block_incl_scan(int64_t v, int64_t* total, int64_t* lds /* [kWavesPerBlock] */) {
+  const int lane = lane_id(), w = wave_in_block();
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    int64_t o = __shfl_up(v, off, kWave);
+    if (lane >= off) v += o;
+  }
+  if (lane == kWave - 1) lds[w] = v;
+  __syncthreads();
+  int64_t base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < kWavesPerBlock; ++i) {
+    const int64_t x = lds[i];
+    if (i < w) base += x;
+    tot += x;
+  }
+  __syncthreads();
+  *total = tot;
+  return v + base;
+}
+
+struct LoadI32 {
+  const int32_t* in;
+  __device__ __forceinline__ int64_t operator()(int64_t i) const { return in[i]; }
+};
+struct LoadBit {
+  const uint64_t* bits;
+  __device__ __forceinline__ int64_t operator()(int64_t i) const { return (bits[i >> 6] >> (i & 63)) & 1ull; }
+};
+
+template <typename Load>
+__global__ __launch_bounds__(kBlock) void k_scan_reduce(Load load, int64_t n, int64_t* __restrict__ tile_sum) {
+  __shared__ int64_t lds[kWavesPerBlock];
+  const int64_t base = (int64_t)blockIdx.x * kTile;
+  int64_t v = 0;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int64_t i = base + (int64_t)j * kBlock + threadIdx.x;
+    if (i < n) v += load(i);
+  }
+  v = wave_sum_i64(v);
+  if (lane_id() == 0) lds[wave_in_block()] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int64_t t = 0;
+    for (int i = 0; i < kWavesPerBlock; ++i) t += lds[i];
+    tile_sum[blockIdx.x] = t;
+  }
+}
+
+// one block: exclusive scan of tile_sum[0..n_tiles) in place, total to *total_out
+__global__ __launch_bounds__(kBlock) void k_scan_spine(int64_t* __restrict__ tile_sum, int64_t n_tiles,
+                                                       int64_t* __restrict__ total_out) {
+  __shared__ int64_t lds[kWavesPerBlock];
+  int64_t carry = 0;
+  for (int64_t base = 0; base < n_tiles; base += kBlock) {
+    const int64_t i = base + threadIdx.x;
+    const int64_t x = i < n_tiles ? tile_sum[i] : 0;
+    int64_t tot;
+    const int64_t incl = block_incl_scan(x, &tot, lds);
+    if (i < n_tiles) tile_sum[i] = carry + incl - x;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) *total_out = carry;
+}
+
+template <typename Load, typename Out>
+__global__ __launch_bounds__(kBlock) void k_scan_apply(Load load, int64_t n, const int64_t* __restrict__ tile_off,
+                                                       Out* __restrict__ out, bool write_total) {
+  __shared__ int64_t lds[kWavesPerBlock];
+  const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;  // blocked: thread owns 8 in a row
+  int64_t x[kItems];
+  int64_t sum = 0;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int64_t i = base + j;
+    x[j] = i < n ? load(i) : 0;
+    sum += x[j];
+  }
+  int64_t tot;
+  const int64_t incl = block_incl_scan(sum, &tot, lds);
+  int64_t run = tile_off[blockIdx.x] + incl - sum;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int64_t i = base + j;
+    if (i < n) out[i] = (Out)run;
+    run += x[j];
+  }
+  // the entry one past the end holds the grand total
+  if (write_total && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) out[n] = (Out)(tile_off[blockIdx.x] + tot);
+}
+
+size_t scan_tmp_bytes(int64_t n) {
+  const int64_t tiles = (n + kTile - 1) / kTile;
+  return (size_t)(tiles + 2) * sizeof(int64_t);
+}
+
+template <typename Load, typename Out>
+static void scan_impl(Load load, int64_t n, Out* out, int64_t* total_out, bool write_total, void* tmp, hipStream_t s) {
+  int64_t* tile_sum = (int64_t*)tmp;
+  const int64_t tiles = (n + kTile - 1) / kTile;
+  int64_t* total = total_out ? total_out : tile_sum + tiles + 1;
+  if (tiles > 0) COOP_LAUNCH(K_SCAN_REDUCE, k_scan_reduce<Load>, dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, tile_sum);
+  COOP_LAUNCH(K_SCAN_SPINE, k_scan_spine, dim3(1), dim3(kBlock), 0, s, tile_sum, tiles, total);
+  if (tiles > 0)
+    COOP_LAUNCH(K_SCAN_APPLY, (k_scan_apply<Load, Out>), dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, tile_sum, out,
+                write_total);
+}
+
+__global__ void k_store_i64(int64_t* p, int64_t v) { *p = v; }
+
+void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, void* tmp, hipStream_t s) {
+  if (n <= 0) {  // out[0] = 0
+    COOP_LAUNCH(K_FILL, k_store_i64, dim3(1), dim3(1), 0, s, out, (int64_t)0);
+    return;
+  }
+  scan_impl<LoadI32, int64_t>(LoadI32{in}, n, out, nullptr, true, tmp, s);
+}
+
+void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
+  scan_impl<LoadBit, uint32_t>(LoadBit{bits}, n, out, total_out, false, tmp, s);
+}
+
+// ---- CSR validation -------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_validate_csr(const int64_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+                                                         int64_t nv, int64_t ne, int32_t* __restrict__ bad) {
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  bool b = false;
+  for (int64_t v = i; v < nv; v += stride) b |= indptr[v] > indptr[v + 1];
+  for (int64_t e = i; e < ne; e += stride) b |= (uint32_t)indices[e] >= (uint64_t)nv;
+  if (i == 0) b |= indptr[0] != 0 || indptr[nv] != ne;
+  if (b) atomicOr(bad, 1);
+}
+
+}  // namespace coop
+
+using namespace coop;
+
+extern "C" {
+
+const char* coop_strerror(int code) {
+  switch (code) {
+    case COOP_OK: return "ok";
+    case COOP_E_NULL: return "null pointer argument";
+    case COOP_E_RANGE: return "vertex id out of range";
+    case COOP_E_DUPSEED: return "duplicate seed vertex";
+    case COOP_E_ARG: return "invalid argument";
+    case COOP_E_NOMEM: return "allocator returned no memory";
+    case COOP_E_CAPACITY: return "workspace capacity exceeded";
+    case COOP_E_HIP: return "HIP runtime error";
+    case COOP_E_GRAPH: return "malformed CSR graph";
+    default: return "unknown error";
+  }
+}
+
+int coop_version(void) { return 1; }
+
+void* coop_arena_alloc(void* arena, size_t bytes, int tag) {
+  (void)tag;
+  coop_arena* a = (coop_arena*)arena;
+  if (!a || !a->base) return nullptr;
+  const size_t need = (bytes + 255) & ~(size_t)255;
+  if (a->used + need > a->bytes) return nullptr;
+  void* p = (char*)a->base + a->used;
+  a->used += need;
+  return p;
+}
+
+int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_vertices, int64_t n_edges, int flags,
+                    void* stream, coop_graph** out) {
+  if (!out) return COOP_E_NULL;
+  *out = nullptr;
+  if (!indptr || (!indices && n_edges > 0)) return COOP_E_NULL;
+  if (n_vertices < 0 || n_vertices >= ((int64_t)1 << 31) || n_edges < 0 || (flags & ~COOP_VALIDATE)) return COOP_E_ARG;
+  if (flags & COOP_VALIDATE) {
+    hipStream_t s = (hipStream_t)stream;
+    int32_t* d_bad = nullptr;
+    COOP_HIP_TRY(hipMalloc((void**)&d_bad, sizeof(int32_t)));
+    int32_t h_bad = 0;
+    hipError_t e = hipMemcpyAsync(d_bad, &h_bad, sizeof(int32_t), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) {
+      COOP_LAUNCH(K_VALIDATE, k_validate_csr, dim3(256 * 16), dim3(kBlock), 0, s, indptr, indices, n_vertices, n_edges, d_bad);
+      e = hipMemcpyAsync(&h_bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(d_bad);
+    if (e != hipSuccess) return COOP_E_HIP;
+    if (h_bad) return COOP_E_GRAPH;
+  }
+  coop_graph* g = new (std::nothrow) coop_graph{indptr, indices, n_vertices, n_edges};
+  if (!g) return COOP_E_NOMEM;
+  *out = g;
+  return COOP_OK;
+}
+
+int coop_graph_free(coop_graph* g) {
+  delete g;
+  return COOP_OK;
+}
+
+int coop_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  if (!on) collect_locked();
+  g_prof.on = on != 0;
+  return COOP_OK;
+}
+
+int coop_profile_reset(void) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  collect_locked();
+  for (int i = 0; i < K_COUNT_; ++i) { g_prof.ms[i] = 0; g_prof.launches[i] = 0; }
+  return COOP_OK;
+}
+
+int coop_profile_kernels(void) { return K_COUNT_; }
+
+const char* coop_profile_name(int id) { return (id >= 0 && id < K_COUNT_) ? kKernelNames[id] : nullptr; }
+
+int coop_profile_read(int id, double* total_ms, int64_t* launches) {
+  if (id < 0 || id >= K_COUNT_) return COOP_E_ARG;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  collect_locked();
+  if (total_ms) *total_ms = g_prof.ms[id];
+  if (launches) *launches = g_prof.launches[id];
+  return COOP_OK;
+}
+
+}  // extern "C"

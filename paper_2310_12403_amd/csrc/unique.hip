@@ -1,0 +1,139 @@
+// Frontier dedup and relabelling (Eq. 2: S^{l+1} = S^l ∪ sampled sources) with an open-addressing hash table in HBM.
+//
+// The list [S^l ; col_global] is inserted into a table of 8-byte slots (key << 32 | position in that list).  A slot is
+// claimed with atomicCAS; every further occurrence of the key lowers the slot's position with atomicMin, so after
+// the insert kernel each slot holds the FIRST position of its key, whichever thread won the race.  A vertex is
+// "new" exactly at the edge whose position equals that first position (and is not a seed position).  A device-wide
+// scan over the new-flags gives each new vertex its rank, hence its place n_dst + rank in S^{l+1}: the order is
+// "S^l, then first appearance in col_global", independent of scheduling.
+#include "coop_internal.h"
+#include "device_utils.h"
+
+namespace coop {
+
+constexpr uint64_t kEmptySlot = ~0ull;
+
+__device__ __forceinline__ uint64_t slot_of_key(uint32_t key, int shift) {
+  return ((uint64_t)key * 0x9E3779B97F4A7C15ull) >> shift;  // multiplicative (Fibonacci) hashing, top bits
+}
+
+__global__ __launch_bounds__(kBlock) void k_uniq_insert(const int32_t* __restrict__ dst, int64_t n_dst,
+                                                        const int32_t* __restrict__ col, int64_t m,
+                                                        unsigned long long* __restrict__ table, uint64_t mask, int shift,
+                                                        Ctl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_dst + m) return;
+  const uint32_t key = (uint32_t)(i < n_dst ? dst[i] : col[i - n_dst]);
+  const unsigned long long mine = ((unsigned long long)key << 32) | (uint32_t)i;
+  uint64_t h = slot_of_key(key, shift);
+  for (;;) {
+    unsigned long long cur = __hip_atomic_load(&table[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (cur == kEmptySlot) {
+      cur = atomicCAS(&table[h], (unsigned long long)kEmptySlot, mine);
+      if (cur == kEmptySlot) return;  // claimed
+    }
+    if ((uint32_t)(cur >> 32) == key) {
+      const unsigned long long old = atomicMin(&table[h], mine);
+      // two positions below n_dst with one key: the destination list holds a vertex twice
+      if (i < n_dst && (int64_t)(uint32_t)old < n_dst) atomicOr(&ctl->err_dup, 1);
+      return;
+    }
+    h = (h + 1) & mask;  // the table is at most half full, so an empty slot or the key is always reached
+  }
+}
+
+__device__ __forceinline__ uint32_t first_position(const unsigned long long* __restrict__ table, uint64_t mask, int shift,
+                                                   uint32_t key) {
+  uint64_t h = slot_of_key(key, shift);
+  for (;;) {
+    const unsigned long long cur = table[h];
+    if ((uint32_t)(cur >> 32) == key) return (uint32_t)cur;
+    if (cur == kEmptySlot) return 0xFFFFFFFFu;  // not reachable for inserted keys
+    h = (h + 1) & mask;
+  }
+}
+
+// first[e] = first position of col[e] in [S^l ; col]; bit e of `bits` = that position is this very edge
+__global__ __launch_bounds__(kBlock) void k_uniq_flag(const int32_t* __restrict__ col, int64_t m, int64_t n_dst,
+                                                      const unsigned long long* __restrict__ table, uint64_t mask, int shift,
+                                                      uint32_t* __restrict__ first, uint64_t* __restrict__ bits) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  bool is_new = false;
+  if (e < m) {
+    const uint32_t f = first_position(table, mask, shift, (uint32_t)col[e]);
+    first[e] = f;
+    is_new = (int64_t)f == n_dst + e;
+  }
+  const uint64_t b = ballot64(is_new);
+  if (lane_id() == 0 && (e & ~(int64_t)63) < m) bits[e >> 6] = b;
+}
+
+__global__ __launch_bounds__(kBlock) void k_uniq_relabel(const int32_t* __restrict__ col, int64_t m, int64_t n_dst,
+                                                         const uint32_t* __restrict__ first, const uint32_t* __restrict__ rank,
+                                                         int32_t* __restrict__ src, int32_t* __restrict__ col_local) {
+  const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e >= m) return;
+  const int64_t f = first[e];
+  int64_t local = f;
+  if (f >= n_dst) {
+    local = n_dst + rank[f - n_dst];
+    if (f == n_dst + e) src[local] = col[e];
+  }
+  col_local[e] = (int32_t)local;
+}
+
+__global__ __launch_bounds__(kBlock) void k_copy_ids(const int32_t* __restrict__ in, int32_t* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) out[i] = in[i];
+}
+
+static inline unsigned nblocks(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
+
+int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, int32_t* col_local,
+                   int32_t** src_out, int64_t* n_src_out, Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
+  const int64_t n_all = n_dst + m;
+  int log2cap = 10;
+  while (((int64_t)1 << log2cap) < 2 * n_all) ++log2cap;
+  const int64_t cap = (int64_t)1 << log2cap;
+  const uint64_t mask = (uint64_t)cap - 1;
+  const int shift = 64 - log2cap;
+
+  unsigned long long* table = alloc.get<unsigned long long>(cap, COOP_TAG_SCRATCH);
+  uint32_t* first = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
+  uint32_t* rank = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
+  uint64_t* bits = alloc.get<uint64_t>((m + 63) / 64, COOP_TAG_SCRATCH);
+  void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(m), COOP_TAG_SCRATCH);
+  if (alloc.failed) return COOP_E_NOMEM;
+
+  int64_t n_new = 0;
+  if (n_all > 0) {
+    fill_u64((uint64_t*)table, cap, kEmptySlot, s);
+    COOP_LAUNCH(K_UNIQ_INSERT, k_uniq_insert, dim3(nblocks(n_all)), dim3(kBlock), 0, s, dst, n_dst, col_global, m, table, mask,
+                shift, d_ctl);
+  }
+  if (m > 0) {
+    COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, n_dst, table, mask, shift, first,
+                bits);
+    scan_bits_to_u32(bits, m, rank, &d_ctl->total_new, scan_tmp, s);
+  }
+  // sizes (and the duplicate / range flags) back to the host
+  COOP_HIP_TRY(hipMemcpyAsync(h_ctl, d_ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s));
+  COOP_HIP_TRY(hipStreamSynchronize(s));
+  if (h_ctl->err_range) return COOP_E_RANGE;
+  if (h_ctl->err_dup) return COOP_E_DUPSEED;
+  if (h_ctl->err_capacity) return COOP_E_CAPACITY;
+  if (m > 0) n_new = h_ctl->total_new;
+
+  const int64_t n_src = n_dst + n_new;
+  int32_t* src = alloc.get<int32_t>(n_src, COOP_TAG_OUTPUT);
+  if (alloc.failed) return COOP_E_NOMEM;
+  if (n_dst > 0) COOP_LAUNCH(K_COPY_IDS, k_copy_ids, dim3(nblocks(n_dst)), dim3(kBlock), 0, s, dst, src, n_dst);
+  if (m > 0)
+    COOP_LAUNCH(K_UNIQ_RELABEL, k_uniq_relabel, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, n_dst, first, rank, src,
+                col_local);
+  *src_out = src;
+  *n_src_out = n_src;
+  return COOP_OK;
+}
+
+}  // namespace coop

@@ -1,0 +1,208 @@
+// Random variates of smoothed dependent minibatching (App. A.7), device side.
+//
+// r = R / 2^32.  U(g) is word 0 of Philox4x32-10 (Salmon et al., SC'11) keyed by the user seed, with counter
+// (t, s | 0xFFFFFFFF, layer | sampler << 8, g).  Inside a group of kappa iterations the variate moves from
+// U(g) to U(g+1) along n(c) = cos(c pi/2) n1 + sin(c pi/2) n2 in normal space, r = Phi(n(c)).
+//
+// Phi and Phi^-1 are fixed sequences of binary64 add / mul / fma and bit moves (no library calls, no division,
+// no square root), so that any IEEE machine produces the same bits.  This file must be compiled with
+// floating-point contraction off: every fused operation below is written as __builtin_fma.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace coop {
+
+struct VariateParams {
+  uint32_t key0, key1;  // user seed, low / high word
+  uint32_t c2;          // layer | sampler << 8
+  uint32_t g;           // group index floor(iter / kappa) mod 2^32
+  double cw, sw;        // cos(c pi/2), sin(c pi/2); used by the blended path only
+};
+
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                        uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+
+// ---- reproducible binary64 kit ------------------------------------------------------------------------------
+__device__ __forceinline__ double bits_to_f64(uint64_t u) { return __longlong_as_double((long long)u); }
+__device__ __forceinline__ uint64_t f64_to_bits(double x) { return (uint64_t)__double_as_longlong(x); }
+
+// 1/x, x positive and normal: exponent-flip first guess, six Newton steps
+__device__ __forceinline__ double kit_rcp(double x) {
+  double y = bits_to_f64(0x7FDE623822FC16E6ull - f64_to_bits(x));
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    const double e = __builtin_fma(-x, y, 1.0);
+    y = __builtin_fma(y, e, y);
+  }
+  return y;
+}
+
+// 1/sqrt(x), x positive and normal: shift-and-subtract first guess, five Newton steps
+__device__ __forceinline__ double kit_rsqrt(double x) {
+  double y = bits_to_f64(0x5FE6EB50C7B537A9ull - (f64_to_bits(x) >> 1));
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    double t = x * y;
+    t = t * y;
+    y = y * __builtin_fma(-0.5, t, 1.5);
+  }
+  return y;
+}
+
+// ln x, x positive and normal: mantissa folded into [1/sqrt2, sqrt2), atanh series in z = (m-1)/(m+1) up to z^17
+__device__ __forceinline__ double kit_log(double x) {
+  const uint64_t b = f64_to_bits(x);
+  long long e = (long long)(b >> 52) - 1023;
+  double m = bits_to_f64((b & 0x000FFFFFFFFFFFFFull) | 0x3FF0000000000000ull);
+  if (m > 1.4142135623730951) { m = m * 0.5; e += 1; }
+  const double z = (m - 1.0) * kit_rcp(m + 1.0);
+  const double z2 = z * z;
+  double p = 1.0 / 17.0;
+  p = __builtin_fma(p, z2, 1.0 / 15.0);
+  p = __builtin_fma(p, z2, 1.0 / 13.0);
+  p = __builtin_fma(p, z2, 1.0 / 11.0);
+  p = __builtin_fma(p, z2, 1.0 / 9.0);
+  p = __builtin_fma(p, z2, 1.0 / 7.0);
+  p = __builtin_fma(p, z2, 1.0 / 5.0);
+  p = __builtin_fma(p, z2, 1.0 / 3.0);
+  p = __builtin_fma(p, z2, 1.0);
+  const double lm = (2.0 * z) * p;
+  return __builtin_fma((double)e, 0.6931471805599453, lm);
+}
+
+// e^y for y in [-700, 0]: y = k ln2 + r with |r| <= ln2 / 2, Taylor polynomial to r^13, scaled by 2^k
+__device__ __forceinline__ double kit_exp(double y) {
+  const double magic = 6755399441055744.0;  // 1.5 * 2^52
+  const double kf = __builtin_fma(y, 1.4426950408889634, magic) - magic;
+  double r = __builtin_fma(-kf, 0.6931471803691238, y);
+  r = __builtin_fma(-kf, 1.9082149292705877e-10, r);
+  double p = 1.0 / 6227020800.0;
+  p = __builtin_fma(p, r, 1.0 / 479001600.0);
+  p = __builtin_fma(p, r, 1.0 / 39916800.0);
+  p = __builtin_fma(p, r, 1.0 / 3628800.0);
+  p = __builtin_fma(p, r, 1.0 / 362880.0);
+  p = __builtin_fma(p, r, 1.0 / 40320.0);
+  p = __builtin_fma(p, r, 1.0 / 5040.0);
+  p = __builtin_fma(p, r, 1.0 / 720.0);
+  p = __builtin_fma(p, r, 1.0 / 120.0);
+  p = __builtin_fma(p, r, 1.0 / 24.0);
+  p = __builtin_fma(p, r, 1.0 / 6.0);
+  p = __builtin_fma(p, r, 0.5);
+  p = __builtin_fma(p, r, 1.0);
+  p = __builtin_fma(p, r, 1.0);
+  const long long k = (long long)kf;
+  return p * bits_to_f64((uint64_t)(k + 1023) << 52);
+}
+
+// Phi^-1((U + 1/2) / 2^32): Acklam's rational approximation; the upper half mirrors the lower half on U.
+__device__ __forceinline__ double kit_phi_inv_u32(uint32_t U) {
+  const bool upper = U >= 0x80000000u;
+  const uint32_t Ul = upper ? (0xFFFFFFFFu - U) : U;
+  const double p = ((double)Ul + 0.5) * (1.0 / 4294967296.0);
+  double x;
+  if (p < 0.02425) {
+    const double w = -2.0 * kit_log(p);
+    const double q = w * kit_rsqrt(w);
+    double num = -7.784894002430293e-03;
+    num = __builtin_fma(num, q, -3.223964580411365e-01);
+    num = __builtin_fma(num, q, -2.400758277161838e+00);
+    num = __builtin_fma(num, q, -2.549732539343734e+00);
+    num = __builtin_fma(num, q, 4.374664141464968e+00);
+    num = __builtin_fma(num, q, 2.938163982698783e+00);
+    double den = 7.784695709041462e-03;
+    den = __builtin_fma(den, q, 3.224671290700398e-01);
+    den = __builtin_fma(den, q, 2.445134137142996e+00);
+    den = __builtin_fma(den, q, 3.754408661907416e+00);
+    den = __builtin_fma(den, q, 1.0);
+    x = num * kit_rcp(den);
+  } else {
+    const double q = p - 0.5;
+    const double r = q * q;
+    double num = -3.969683028665376e+01;
+    num = __builtin_fma(num, r, 2.209460984245205e+02);
+    num = __builtin_fma(num, r, -2.759285104469687e+02);
+    num = __builtin_fma(num, r, 1.383577518672690e+02);
+    num = __builtin_fma(num, r, -3.066479806614716e+01);
+    num = __builtin_fma(num, r, 2.506628277459239e+00);
+    double den = -5.447609879822406e+01;
+    den = __builtin_fma(den, r, 1.615858368580409e+02);
+    den = __builtin_fma(den, r, -1.556989798598866e+02);
+    den = __builtin_fma(den, r, 6.680131188771972e+01);
+    den = __builtin_fma(den, r, -1.328068155288572e+01);
+    den = __builtin_fma(den, r, 1.0);
+    x = (q * num) * kit_rcp(den);
+  }
+  return upper ? -x : x;
+}
+
+// 1 / (2n + 1), n = 0..28, each the correctly rounded quotient (folded by the compiler)
+__constant__ const double kInvOdd[29] = {
+    1.0,        1.0 / 3.0,  1.0 / 5.0,  1.0 / 7.0,  1.0 / 9.0,  1.0 / 11.0, 1.0 / 13.0, 1.0 / 15.0,
+    1.0 / 17.0, 1.0 / 19.0, 1.0 / 21.0, 1.0 / 23.0, 1.0 / 25.0, 1.0 / 27.0, 1.0 / 29.0, 1.0 / 31.0,
+    1.0 / 33.0, 1.0 / 35.0, 1.0 / 37.0, 1.0 / 39.0, 1.0 / 41.0, 1.0 / 43.0, 1.0 / 45.0, 1.0 / 47.0,
+    1.0 / 49.0, 1.0 / 51.0, 1.0 / 53.0, 1.0 / 55.0, 1.0 / 57.0};
+
+// upper tail 1 - Phi(a), a >= 0: power series below 3 (28 terms), Laplace continued fraction (depth 24) above
+__device__ __forceinline__ double kit_qtail(double a) {
+  const double a2 = a * a;
+  const double pdf = kit_exp(-0.5 * a2) * 0.3989422804014327;
+  if (a < 3.0) {
+    double s = 1.0;
+#pragma unroll
+    for (int n = 28; n >= 1; --n) s = __builtin_fma(a2 * kInvOdd[n], s, 1.0);
+    return __builtin_fma(-(pdf * a), s, 0.5);
+  } else {
+    double p = 0.0, q = 1.0;
+#pragma unroll
+    for (int n = 24; n >= 1; --n) {
+      const double pn = (double)n * q;
+      q = __builtin_fma(a, q, p);
+      p = pn;
+    }
+    const double den = __builtin_fma(a, q, p);
+    return (pdf * q) * kit_rcp(den);
+  }
+}
+
+// floor(2^32 Phi(x)) clamped to 32 bits; the upper half is the integer mirror of the lower half
+__device__ __forceinline__ uint32_t kit_phi_to_u32(double x) {
+  const bool neg = x < 0.0;
+  const double a = neg ? -x : x;
+  const double s = kit_qtail(a) * 4294967296.0;
+  unsigned long long f = (unsigned long long)s;
+  if (f > 0xFFFFFFFFull) f = 0xFFFFFFFFull;
+  const uint32_t lo = (uint32_t)f;
+  return neg ? lo : (0xFFFFFFFFu - lo);
+}
+
+// R for source vertex t (and destination s for NS; pass 0xFFFFFFFF for LABOR-0)
+template <bool BLEND>
+__device__ __forceinline__ uint32_t variate(const VariateParams& vp, uint32_t t, uint32_t c1) {
+  const uint32_t U1 = philox4x32_10_word0(t, c1, vp.c2, vp.g, vp.key0, vp.key1);
+  if constexpr (!BLEND) {
+    return U1;
+  } else {
+    const uint32_t U2 = philox4x32_10_word0(t, c1, vp.c2, vp.g + 1u, vp.key0, vp.key1);
+    const double n1 = kit_phi_inv_u32(U1);
+    const double n2 = kit_phi_inv_u32(U2);
+    return kit_phi_to_u32(__builtin_fma(vp.cw, n1, vp.sw * n2));
+  }
+}
+
+}  // namespace coop

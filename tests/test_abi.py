@@ -1,0 +1,65 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol that
+include/coop.h declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import paper_2310_12403_amd as P
+from paper_2310_12403_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "coop.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(coop_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(n for n in names if n != "coop_alloc_fn"))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"coop_graph_load", "coop_sample", "coop_gather", "coop_strerror"} <= set(names)
+    L = P.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_error_names():
+    assert P.coop_version() >= 1
+    for code in range(0, -9, -1):
+        assert P.coop_strerror(code) != "unknown error"
+    assert P.coop_strerror(-99) == "unknown error"
+
+
+def test_host_checked_arguments():
+    L = P.lib()
+    h = C.c_void_p()
+    assert L.coop_graph_load(None, None, 10, 0, 0, None, C.byref(h)) == -1          # NULL indptr
+    assert L.coop_graph_load(None, None, 10, 0, 0, None, None) == -1                # NULL out
+    fan = (C.c_int32 * 2)(3, 3)
+    blocks = (binding._CBlock * 2)()
+    assert L.coop_sample(None, None, 0, fan, 2, 0, 0, 1, 0, None, None, None, blocks) == -1   # NULL graph
+    assert L.coop_gather(None, 10, 4, 7, None, 5, None, None) == -4                 # unknown dtype
+    assert L.coop_gather(None, 10, 0, 0, None, 5, None, None) == -4                 # dim < 1
+    assert L.coop_gather(None, 10, 4, 0, None, 0, None, None) == 0                  # nothing to do
+    assert L.coop_gather(None, 10, 4, 0, None, 5, None, None) == -1                 # NULL tables
+
+
+def test_arena_bump_allocator():
+    L = P.lib()
+    a = binding._CArena(0x10000, 1000, 0)
+    p1 = L.coop_arena_alloc(C.byref(a), 10, 0)
+    p2 = L.coop_arena_alloc(C.byref(a), 300, 1)
+    assert p1 == 0x10000 and p2 == 0x10100 and a.used == 768
+    assert L.coop_arena_alloc(C.byref(a), 300, 0) is None       # would overflow: NULL, nothing consumed
+    assert a.used == 768
+    assert L.coop_arena_alloc(None, 8, 0) is None
+
+
+def test_profile_table():
+    L = P.lib()
+    n = L.coop_profile_kernels()
+    names = [L.coop_profile_name(i).decode() for i in range(n)]
+    assert len(set(names)) == n and "gather" in names and "labor_count" in names
+    assert L.coop_profile_name(n) is None

@@ -1,0 +1,175 @@
+"""GPU parity: every array that libcoop produces must equal the CPU oracle's, byte for byte,
+on the same seeded synthetic inputs.  All calls go through the C ABI (ctypes binding)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import coopref as R
+
+pytestmark = pytest.mark.gpu
+
+NAMES = ("dst_ids", "indptr", "col_global", "eid", "col_local", "src_ids")
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2310_12403_amd as P
+    return P
+
+
+class G:
+    def __init__(self, P, indptr, indices):
+        self.indptr_h = indptr.cpu().numpy()
+        self.indices_h = indices.cpu().numpy()
+        self.indptr_d = indptr.cuda()
+        self.indices_d = indices.cuda()
+        self.graph = P.coop_graph_load(self.indptr_d, self.indices_d, P.COOP_VALIDATE)
+        self.n = len(self.indptr_h) - 1
+
+
+@pytest.fixture(scope="module")
+def tiny(P):
+    return G(P, *synth.rmat_csr())
+
+
+@pytest.fixture(scope="module")
+def medium(P):
+    # products-shaped, 1/50 scale: 49,000 vertices, mean degree ~50, hubs of a few thousand
+    return G(P, *synth.chung_lu_csr(49000, 1237000, 2.1, seed=1))
+
+
+def compare(P, g, seeds, fanouts, sampler, it=0, kappa=1, seed=0, arena=None):
+    seeds_h = np.ascontiguousarray(seeds, dtype=np.int32)
+    want = R.sample(g.indptr_h, g.indices_h, seeds_h, fanouts, sampler, it=it, kappa=kappa, seed=seed)
+    got = P.coop_sample(g.graph, torch.from_numpy(seeds_h).cuda(), fanouts, sampler, it=it, kappa=kappa, seed=seed,
+                        arena=arena)
+    assert len(got) == len(want)
+    for l, (b, w) in enumerate(zip(got, want)):
+        assert (b.n_dst, b.n_edges, b.n_src) == (len(w["dst_ids"]), len(w["col_global"]), len(w["src_ids"])), l
+        for name in NAMES:
+            a = getattr(b, name).cpu().numpy()
+            assert a.dtype == w[name].dtype and np.array_equal(a, w[name]), (l, name)
+    return got
+
+
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+def test_tiny_config_three_layers(P, tiny, sampler):
+    seeds = synth.seed_batches(tiny.n, 1024, seed=0)(0).numpy()
+    compare(P, tiny, seeds, (10, 10, 10), sampler, it=0, kappa=1, seed=0)
+
+
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+@pytest.mark.parametrize("fanouts", [(1,), (3, 2), (25, 10, 10), (64, 1), (5000,), (2, 2, 2, 2)])
+def test_fanout_shapes(P, tiny, sampler, fanouts):
+    seeds = synth.seed_batches(tiny.n, 300, seed=2)(1).numpy()
+    compare(P, tiny, seeds, fanouts, sampler, it=5, kappa=1, seed=42)
+
+
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+def test_ragged_and_degenerate_batches(P, tiny, sampler):
+    deg = np.diff(tiny.indptr_h)
+    hubs = np.argsort(-deg)[:5].astype(np.int32)          # longest lists (thousands of neighbours)
+    isolated = np.nonzero(deg == 0)[0][:5].astype(np.int32)
+    assert len(isolated) > 0
+    for seeds in (np.zeros(0, np.int32), hubs[:1], isolated, np.concatenate([hubs, isolated]),
+                  np.arange(tiny.n, dtype=np.int32)[::-1][:4097]):
+        compare(P, tiny, seeds, (10, 10), sampler, it=1, kappa=1, seed=7)
+    # whole vertex set as one batch (largest batch this graph admits), one layer
+    compare(P, tiny, synth.permutation(tiny.n, 1).numpy(), (10,), sampler, it=2, kappa=1, seed=7)
+
+
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+def test_medium_graph_many_tiles(P, medium, sampler):
+    seeds = synth.seed_batches(medium.n, 4096, seed=3)(0).numpy()
+    compare(P, medium, seeds, (10, 10, 10), sampler, it=11, kappa=1, seed=2024)
+    compare(P, medium, seeds[:1000], (25, 10), sampler, it=12, kappa=1, seed=(1 << 63) + 12345)
+
+
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+@pytest.mark.parametrize("it,kappa", [(0, 16), (1, 16), (15, 16), (16, 16), (17, 16), (511, 256), (77, 0), (3, 2)])
+def test_dependent_batches(P, tiny, sampler, it, kappa):
+    seeds = synth.seed_batches(tiny.n, 512, seed=4)(3).numpy()
+    compare(P, tiny, seeds, (10, 10), sampler, it=it, kappa=kappa, seed=99)
+
+
+def test_dependent_batches_medium(P, medium):
+    seeds = synth.seed_batches(medium.n, 2048, seed=5)(2).numpy()
+    compare(P, medium, seeds, (10, 10, 10), R.LABOR0, it=37, kappa=64, seed=5)
+
+
+def test_arena_allocator_and_determinism(P, tiny):
+    seeds = synth.seed_batches(tiny.n, 1024, seed=0)(1).numpy()
+    arena = P.Arena(64 << 20)
+    a = compare(P, tiny, seeds, (10, 10, 10), R.LABOR0, it=3, seed=1, arena=arena)
+    keep = [{n: getattr(b, n).clone() for n in NAMES} for b in a]
+    arena.reset()
+    b = compare(P, tiny, seeds, (10, 10, 10), R.LABOR0, it=3, seed=1, arena=arena)
+    for x, y in zip(keep, b):
+        for n in NAMES:
+            assert torch.equal(x[n], getattr(y, n))
+    small = P.Arena(1 << 12)
+    with pytest.raises(P.CoopError) as e:
+        P.coop_sample(tiny.graph, torch.from_numpy(seeds).cuda(), (10, 10, 10), R.LABOR0, arena=small)
+    assert e.value.code == -5
+
+
+def test_error_codes(P, tiny):
+    def run(seeds, fan=(3,), sampler=0):
+        return P.coop_sample(tiny.graph, torch.tensor(seeds, dtype=torch.int32).cuda(), fan, sampler)
+
+    for seeds, code in (([1, 2, 1], -3), ([1, 1 << 20], -2), ([-1], -2)):
+        for sampler in (0, 1):
+            with pytest.raises(P.CoopError) as e:
+                run(seeds, sampler=sampler)
+            assert e.value.code == code
+    for fan in ((), (0,), (3, -1)):
+        with pytest.raises(P.CoopError) as e:
+            run([1, 2, 3], fan)
+        assert e.value.code == -4
+    with pytest.raises(P.CoopError):
+        run([1, 2, 3], sampler=7)
+    # malformed CSR is caught by COOP_VALIDATE
+    bad = tiny.indices_d.clone()
+    bad[5] = tiny.n
+    with pytest.raises(P.CoopError) as e:
+        P.coop_graph_load(tiny.indptr_d, bad, P.COOP_VALIDATE)
+    assert e.value.code == -8
+
+
+@pytest.mark.parametrize("dtype,dim", [(torch.float32, 64), (torch.float32, 100), (torch.float32, 602), (torch.float16, 128),
+                                       (torch.float16, 768), (torch.float16, 3), (torch.float32, 1), (torch.float16, 1025)])
+@pytest.mark.parametrize("n_ids", [0, 1, 63, 1000, 40000])
+def test_gather(P, dtype, dim, n_ids):
+    n = 5000
+    feat = synth.features(n, dim, dtype, seed=dim, device="cpu")
+    ids = (synth.hash_u53(torch.arange(n_ids), 31) % n).to(torch.int32)
+    want = R.gather(feat.numpy(), ids.numpy())
+    got = P.coop_gather(feat.cuda(), ids.cuda())
+    P.coop_gather_status()
+    assert got.cpu().numpy().tobytes() == want.tobytes()
+
+
+def test_gather_unaligned_views_and_range(P):
+    feat = synth.features(1000, 33, torch.float16, seed=1, device="cpu")
+    base = torch.empty(1000 * 33 + 1, dtype=torch.float16, device="cuda")
+    view = base[1:].view(1000, 33)                     # 2-byte aligned table
+    view.copy_(feat)
+    ids = torch.tensor([0, 999, 5, 5, 17], dtype=torch.int32)
+    got = P.coop_gather(view, ids.cuda())
+    assert got.cpu().numpy().tobytes() == R.gather(feat.numpy(), ids.numpy()).tobytes()
+    P.coop_gather_status()
+    P.coop_gather(view, torch.tensor([3, 1000], dtype=torch.int32).cuda())
+    with pytest.raises(P.CoopError) as e:
+        P.coop_gather_status()
+    assert e.value.code == -2
+    P.coop_gather_status()                              # the condition was cleared
+
+
+def test_sample_then_gather_end_to_end(P, tiny):
+    feat = synth.features(tiny.n, 64, torch.float32, seed=0, device="cpu")
+    seeds = synth.seed_batches(tiny.n, 1024, seed=0)(0).numpy()
+    blocks = compare(P, tiny, seeds, (10, 10, 10), R.NS)
+    rows = P.coop_gather(feat.cuda(), blocks[-1].src_ids)
+    P.coop_gather_status()
+    assert rows.cpu().numpy().tobytes() == R.gather(feat.numpy(), blocks[-1].src_ids.cpu().numpy()).tobytes()
