@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of the sampling + feature-loading hot path on one MI355X.
+
+A step = one minibatch: 3-layer LABOR-0 sampling (count, scan, fill, hash-unique, relabel per layer)
+followed by the gather of the input-layer feature rows, on the papers100M-shaped synthetic graph
+(111M vertices, ~3.2B directed edges, fp16 features of dim 128, batch 16384).  Graph, features and
+seeds are resident in HBM before the timed region.  Prints ONE JSON line on stdout; progress goes to
+stderr.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--scale-down S] [--kappa KAPPA]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # B/s, MI355X HBM3E
+# plain-ALU ceiling for 32-bit integer work: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second
+ALU_PEAK_INT32 = 256 * 4 * 16 * 2.4e9
+
+
+def log(msg):
+    print("[bench %7.1fs] %s" % (time.time() - T0, msg), file=sys.stderr, flush=True)
+
+
+T0 = time.time()
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="papers100M", choices=["tiny", "products", "reddit", "papers100M", "mag240M"])
+    ap.add_argument("--scale-down", type=int, default=1, help="shrink the graph (development only; the result is then "
+                    "labelled with the reduced workload)")
+    ap.add_argument("--kappa", type=int, default=1)
+    ap.add_argument("--sampler", default=None, choices=[None, "labor0", "ns"])
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one MI355X plays the single processor that owns the whole "
+              "cooperative batch); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2310_12403_amd as P
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = dict(synth.CONFIGS[args.config])
+    sampler_name = args.sampler or cfg["sampler"]
+    sampler = P.COOP_LABOR0 if sampler_name == "labor0" else P.COOP_NS
+    batch = args.batch or cfg["batch"]
+    fanouts = cfg["fanouts"]
+    dtype = torch.float16 if cfg["dtype"] == "f16" else torch.float32
+    esize = 2 if cfg["dtype"] == "f16" else 4
+    dim = cfg["dim"]
+
+    # ---- inputs, resident in HBM --------------------------------------------------------------------------------
+    log("building %s graph (scale_down=%d)" % (args.config, args.scale_down))
+    indptr, indices = synth.make_graph(args.config, device=dev, scale_down=args.scale_down, log=log)
+    torch.cuda.synchronize()
+    n = indptr.numel() - 1
+    nnz = indices.numel()
+    log("graph: %d vertices, %d directed edges, max degree %d" % (n, nnz, int((indptr[1:] - indptr[:-1]).max())))
+    feat = synth.features(n, dim, dtype, seed=0, device=dev)
+    torch.cuda.synchronize()
+    log("features: [%d, %d] %s = %.1f GB" % (n, dim, cfg["dtype"], n * dim * esize / 1e9))
+    get_seeds = synth.seed_batches(n, batch, seed=0, device=dev)
+    graph = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE)
+    arena = P.Arena(4 << 30)
+    deg = indptr[1:] - indptr[:-1]
+
+    def step(i, out):
+        arena.reset()
+        blocks = P.coop_sample(graph, get_seeds(i), fanouts, sampler, it=i, kappa=args.kappa, seed=0, arena=arena)
+        P.coop_gather(feat, blocks[-1].src_ids, out=out[:blocks[-1].n_src])
+        return blocks
+
+    # output buffer sized once from a dry run (allocation stays outside the timed region)
+    arena.reset()
+    probe = P.coop_sample(graph, get_seeds(0), fanouts, sampler, it=0, kappa=args.kappa, seed=0, arena=arena)
+    out = torch.empty((int(probe[-1].n_src * 1.25) + 1024, dim), dtype=dtype, device=dev)
+    log("probe: " + ", ".join("|S^%d|=%d |E^%d|=%d" % (l + 1, b.n_src, l, b.n_edges) for l, b in enumerate(probe)))
+
+    for i in range(args.warmup):
+        step(i, out)
+    P.coop_gather_status()
+    torch.cuda.synchronize()
+
+    # ---- per-kernel pass (all kernels timed with HIP events; not the timed region) -------------------------------
+    P.profile_reset()
+    P.profile_filter(None)
+    P.profile_enable(True)
+    for i in range(min(args.steps, 10)):
+        step(args.warmup + i, out)
+    torch.cuda.synchronize()
+    P.profile_enable(False)
+    per_kernel = P.profile_read_all()
+    n_prof = min(args.steps, 10)
+    breakdown = {k: round(v[0] / n_prof, 4) for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1][0])}
+    dominant = next(iter(breakdown))
+    log("per-kernel ms/step: " + json.dumps(breakdown))
+
+    # ---- timed region: exactly K steps; only the dominant kernel carries events ------------------------------------
+    P.profile_reset()
+    P.profile_filter(dominant)
+    P.profile_enable(True)
+    stats = dict(edges=0, uniq=0, n_in=0, D=[0] * len(fanouts), n_l=[0] * len(fanouts), m_l=[0] * len(fanouts),
+                 n_src=[0] * len(fanouts))
+    kept = []
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        blocks = step(args.warmup + i, out)
+        kept.append([(b.n_dst, b.n_edges, b.n_src) for b in blocks])
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+    P.profile_enable(False)
+    P.coop_gather_status()
+    dom_ms, dom_launches = P.profile_read_all()[dominant]
+    P.profile_filter(None)
+
+    for sizes in kept:
+        for l, (nd, m, ns) in enumerate(sizes):
+            stats["n_l"][l] += nd
+            stats["m_l"][l] += m
+            stats["n_src"][l] += ns
+        stats["edges"] += sum(m for _, m, _ in sizes)
+        stats["uniq"] += sum(ns for _, _, ns in sizes)
+        stats["n_in"] += sizes[-1][2]
+    K = args.steps
+    ms_per_step = t_total / K * 1e3
+
+    # neighbours examined per layer (D_l = sum of degrees over S^l), measured on the last step's blocks
+    D_last = [int(deg[b.dst_ids.long()].sum()) for b in blocks]
+    n_last = [b.n_dst for b in blocks]
+    m_last = [b.n_edges for b in blocks]
+    nL_last = blocks[-1].n_src
+    row_bytes = dim * esize
+
+    # ---- algorithmic bytes (what the method must move) -------------------------------------------------------------
+    def sample_bytes(nl, Dl, ml, nsrc):
+        count_fill = 16 * nl + 4 * nl + 4 * Dl + 8 * (nl + 1) + 4 * ml + 8 * ml
+        unique = 4 * ml + 8 * (nl + ml) + 8 * ml + 4 * (nsrc - nl) + 4 * ml
+        return count_fill + unique
+
+    alg_sample = sum(sample_bytes(n_last[l], D_last[l], m_last[l], blocks[l].n_src) for l in range(len(fanouts)))
+    alg_gather = 2 * nL_last * row_bytes + 4 * nL_last
+    step_frac = (alg_sample + alg_gather) / (ms_per_step * 1e-3) / HBM_PEAK
+
+    avg_dom_ms = dom_ms / max(dom_launches, 1)
+    if dominant == "gather":
+        alg_dom = (2 * row_bytes + 4) * (stats["n_in"] / K)           # per launch: one gather per step
+        roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
+                        unit="GB/s")
+    elif dominant in ("labor_count", "labor_fill", "ns_fill"):
+        # bytes per launch: ids + two indptr words per destination, 4 B per neighbour examined, outputs
+        per_step = sum(24 * n_last[l] + 4 * D_last[l] + (4 * n_last[l] if dominant == "labor_count" else 12 * m_last[l])
+                       for l in range(len(fanouts)))
+        alg_dom = per_step / len(fanouts)
+        roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
+                        unit="GB/s")
+    else:
+        per_step = sum(4 * m_last[l] + 8 * (n_last[l] + m_last[l]) for l in range(len(fanouts)))
+        alg_dom = per_step / len(fanouts)
+        roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
+                        unit="GB/s")
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["avg_launch_ms"] = avg_dom_ms
+    roofline["launches"] = dom_launches
+    roofline["algorithmic_bytes_per_launch"] = alg_dom
+    roofline["traffic"] = _stored_traffic(dominant, args)
+    roofline["achieved"] = round(roofline["achieved"], 2)
+    roofline["frac"] = round(roofline["frac"], 4)
+
+    workload = "%s-shaped Chung-Lu graph (%d vertices, %d directed edges), %d-layer %s fanout %s, batch %d, %s dim %d, kappa %d" % (
+        args.config, n, nnz, len(fanouts), sampler_name.upper(), "/".join(map(str, fanouts)), batch, cfg["dtype"], dim, args.kappa)
+    if args.scale_down != 1:
+        workload += " [REDUCED: scale_down=%d, development run]" % args.scale_down
+    result = {
+        "metric": "sampled edges/s + feature-gather GB/s (% HBM peak), 3-layer LABOR-0",
+        "value": round(stats["edges"] / t_total, 1),
+        "unit": "sampled edges/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 variates / int32 ids / %s rows (copied bit-exactly)" % cfg["dtype"],
+        "data": "synthetic",
+        "config": {"workload": workload, "sampler": sampler_name, "fanouts": list(fanouts), "batch": batch,
+                   "kappa": args.kappa, "feature_dim": dim, "feature_dtype": cfg["dtype"]},
+        "unique_vertices_per_s": round(stats["uniq"] / t_total, 1),
+        "input_vertices_per_step": round(stats["n_in"] / K, 1),
+        "sampled_edges_per_step": round(stats["edges"] / K, 1),
+        "sizes_last_step": {"n_dst": n_last, "neighbours_examined": D_last, "n_edges": m_last,
+                            "n_src": [b.n_src for b in blocks]},
+        "per_kernel_ms_per_step": breakdown,
+        "gather_GBps": round((2 * row_bytes) * (stats["n_in"] / K) / (breakdown.get("gather", float("nan")) * 1e-3) / 1e9, 1),
+        "step_algorithmic_bytes": alg_sample + alg_gather,
+        "step_hbm_frac": round(step_frac, 4),
+        "roofline": roofline,
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores of this machine ----------------------------------------
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args, indptr, indices, feat, get_seeds, fanouts, sampler, blocks, K, P)
+    print(json.dumps(result), flush=True)
+
+
+def _stored_traffic(kernel, args):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary for this
+    kernel and workload has been recorded under profiles/; else None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if args.scale_down != 1 or not os.path.exists(path):
+        return None
+    try:
+        table = json.load(open(path))
+        return table.get(args.config, {}).get(kernel)
+    except Exception:
+        return None
+
+
+def cpu_baseline(args, indptr, indices, feat, get_seeds, fanouts, sampler, last_blocks, K, P):
+    """Times oracle sampling + gather on a bounded sample of the same workload: whole batches, the same seeds and
+    iteration numbers as the timed region's last steps, until the time budget is used.  Also confirms that the GPU
+    blocks of the last timed step equal the oracle's (all arrays)."""
+    import numpy as np
+    from oracle import coopref as R
+
+    log("cpu baseline: copying CSR and features to the host")
+    ip_h = indptr.cpu().numpy()
+    ix_h = indices.cpu().numpy()
+    feat_h = feat.cpu().numpy()
+    log("cpu baseline: running the oracle")
+    edges, spent, batches, parity = 0, 0.0, 0, None
+    i = args.warmup + K - 1
+    while spent < args.cpu_seconds and batches < 8:
+        seeds_h = get_seeds(i).cpu().numpy()
+        t = time.perf_counter()
+        blocks = R.sample(ip_h, ix_h, seeds_h, fanouts, sampler, it=i, kappa=args.kappa, seed=0)
+        rows = R.gather(feat_h, blocks[-1]["src_ids"])
+        spent += time.perf_counter() - t
+        edges += sum(len(b["col_global"]) for b in blocks)
+        if batches == 0:
+            parity = all(np.array_equal(getattr(g, name).cpu().numpy(), w[name])
+                         for g, w in zip(last_blocks, blocks)
+                         for name in ("dst_ids", "indptr", "col_global", "eid", "col_local", "src_ids"))
+            import torch
+            got = P.coop_gather(feat, last_blocks[-1].src_ids)
+            parity = parity and got.cpu().numpy().tobytes() == rows.tobytes()
+            log("cpu baseline: GPU blocks of the last timed step equal the oracle's: %s" % parity)
+        batches += 1
+        i -= 1
+        del rows, blocks
+    return {"value": round(edges / spent, 1), "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
+            "sample": "%d whole batches of the same workload (sampling + gather), %.1f s of single-thread CPU time" % (batches, spent),
+            "matches_gpu_last_step": parity}
+
+
+if __name__ == "__main__":
+    main()

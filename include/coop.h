@@ -150,6 +150,7 @@ int coop_version(void);
  * accumulated duration and launch count of kernel `id` (0 <= id < coop_profile_kernels()).
  */
 int coop_profile_enable(int on);
+int coop_profile_filter(int id); /* time only kernel `id` while enabled; id < 0: every kernel (default) */
 int coop_profile_reset(void);
 int coop_profile_kernels(void);
 const char* coop_profile_name(int id);

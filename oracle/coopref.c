@@ -20,10 +20,18 @@
  *   - an LRU vertex cache (Sec. 4.2 names "an LRU cache" only).
  *
  * Readings where the paper is silent (each is listed in the design notes):
- *   - PRNG = Philox4x32-10 (Salmon et al., SC'11); key = (seed lo, seed hi);
- *     counter = (t, s for NS | 0xFFFFFFFF for LABOR, layer | sampler<<8, g);
- *     the variate is output word 0, read as the fixed-point number R / 2^32.
- *   - g = floor(iter/kappa) mod 2^32 names the seed z_g; z1 = z_g, z2 = z_{g+1}.
+ *   - the "PRNG initialised with z, t and s" is a keyed hash in two stages:
+ *       (K0,K1,K2,K3) = Philox4x32-10 (Salmon et al., SC'11) with key (seed lo, seed hi)
+ *                       and counter (g lo, g hi, layer | sampler<<8, 0x434F4F50);
+ *       LABOR:  U = mix(t ^ K0) ^ K1                      (one number per source vertex)
+ *       NS:     U = mix(mix(t ^ K0) ^ K1 ^ mix(s ^ K2)) ^ K3    (one number per edge)
+ *     where mix is a 32-bit mixing permutation (xorshift-multiply, two multiplies).
+ *     The variate is U read as the fixed-point number R / 2^32.  One Philox call per
+ *     (seed, group, layer, sampler) keeps the group seeds z_g independent; the
+ *     per-vertex part is an Even-Mansour keyed permutation and costs a few integer
+ *     instructions per examined neighbour, which is what lets the GPU count pass run
+ *     at memory speed rather than at the speed of ten Philox rounds.
+ *   - g = floor(iter/kappa) names the seed z_g; z1 = z_g, z2 = z_{g+1}.
  *     kappa == 0 means kappa = infinity (g = 0, c = 0 for ever).
  *   - n1, n2 are Phi^-1 of the two uniforms ((U + 1/2) / 2^32), so that c = 0
  *     gives back U exactly; that case is taken in integers.
@@ -245,37 +253,60 @@ uint32_t coopref_phi_to_u32(double x) {
 /* ------------------------------------------------------------------------- */
 /* Variates of App. A.7.                                                       */
 /* ------------------------------------------------------------------------- */
+/* 32-bit mixing permutation: xor-shift / odd-multiply rounds (each invertible). */
+uint32_t coopref_mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
+}
+
+/* The four key words of (seed, sampler, layer, group g). */
+void coopref_layer_keys(uint64_t seed, int sampler, int layer, uint64_t g, uint32_t K[4]) {
+  uint32_t ctr[4] = {(uint32_t)g, (uint32_t)(g >> 32), (uint32_t)layer | ((uint32_t)sampler << 8), 0x434F4F50u};
+  uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  coopref_philox4x32_10(ctr, key, K);
+}
+
+static uint32_t keyed_uniform(const uint32_t K[4], int sampler, uint32_t t, uint32_t s) {
+  uint32_t a = coopref_mix32(t ^ K[0]) ^ K[1];
+  if (sampler == COOPREF_LABOR0) return a;
+  return coopref_mix32(a ^ coopref_mix32(s ^ K[2])) ^ K[3];
+}
+
 typedef struct {
-  uint32_t key[2];
-  uint32_t g;      /* group index floor(iter/kappa) mod 2^32 */
+  uint64_t seed;
+  uint64_t g;      /* group index floor(iter/kappa) */
   int blend;       /* 0: c == 0, integer path */
   double cw, sw;   /* cos(c pi/2), sin(c pi/2) */
+  /* per (sampler, layer), filled by variate_layer(): keys of group g and of group g+1 */
+  int sampler;
+  uint32_t K1[4], K2[4];
 } variate_state;
 
 static void variate_setup(variate_state* st, uint64_t seed, uint64_t iter, uint32_t kappa) {
-  st->key[0] = (uint32_t)seed;
-  st->key[1] = (uint32_t)(seed >> 32);
+  st->seed = seed;
   if (kappa == 0) { st->g = 0; st->blend = 0; st->cw = 1.0; st->sw = 0.0; return; }
-  uint64_t g = iter / kappa, i = iter % kappa;
-  st->g = (uint32_t)g;
+  uint64_t i = iter % kappa;
+  st->g = iter / kappa;
   st->blend = i != 0;
   double c = (double)i / (double)kappa;
   st->cw = cos(c * 1.5707963267948966);
   st->sw = sin(c * 1.5707963267948966);
 }
 
-static uint32_t variate_draw(const variate_state* st, int sampler, int layer, uint32_t t, uint32_t s) {
-  uint32_t ctr[4], out[4];
-  ctr[0] = t;
-  ctr[1] = (sampler == COOPREF_LABOR0) ? 0xFFFFFFFFu : s;
-  ctr[2] = (uint32_t)layer | ((uint32_t)sampler << 8);
-  ctr[3] = st->g;
-  coopref_philox4x32_10(ctr, st->key, out);
-  uint32_t U1 = out[0];
+static void variate_layer(variate_state* st, int sampler, int layer) {
+  st->sampler = sampler;
+  coopref_layer_keys(st->seed, sampler, layer, st->g, st->K1);
+  coopref_layer_keys(st->seed, sampler, layer, st->g + 1, st->K2);
+}
+
+static uint32_t variate_draw(const variate_state* st, uint32_t t, uint32_t s) {
+  uint32_t U1 = keyed_uniform(st->K1, st->sampler, t, s);
   if (!st->blend) return U1;
-  ctr[3] = st->g + 1u;
-  coopref_philox4x32_10(ctr, st->key, out);
-  uint32_t U2 = out[0];
+  uint32_t U2 = keyed_uniform(st->K2, st->sampler, t, s);
   double n1 = coopref_phi_inv_u32(U1);
   double n2 = coopref_phi_inv_u32(U2);
   double n = fma(st->cw, n1, st->sw * n2);
@@ -287,7 +318,8 @@ uint32_t coopref_variate(uint64_t seed, int sampler, int layer, uint64_t iter, u
                          uint32_t t, uint32_t s) {
   variate_state st;
   variate_setup(&st, seed, iter, kappa);
-  return variate_draw(&st, sampler, layer, t, s);
+  variate_layer(&st, sampler, layer);
+  return variate_draw(&st, t, s);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -328,7 +360,7 @@ void coopref_free_blocks(coopref_block* blocks, int L) {
 /* Samples the neighbourhoods of dst[0..n_dst) with fanout k and fills one block. */
 static int sample_layer(const int64_t* g_indptr, const int32_t* g_indices, int64_t n_vertices,
                         const int32_t* dst, int64_t n_dst, int32_t k, int sampler, int layer,
-                        const variate_state* st, int32_t* pos_of /* [n_vertices], all -1 */,
+                        variate_state* st, int32_t* pos_of /* [n_vertices], all -1 */,
                         coopref_block* blk) {
   /* upper bound on kept edges: every neighbour examined */
   int64_t D = 0, dmax = 0;
@@ -348,6 +380,7 @@ static int sample_layer(const int64_t* g_indptr, const int32_t* g_indices, int64
     free(pairs); free(chosen); return COOPREF_E_NOMEM;
   }
   memcpy(blk->dst_ids, dst, sizeof(int32_t) * (size_t)n_dst);
+  variate_layer(st, sampler, layer);
 
   int64_t m = 0;
   for (int64_t i = 0; i < n_dst; ++i) {
@@ -358,7 +391,7 @@ static int sample_layer(const int64_t* g_indptr, const int32_t* g_indices, int64
       /* r_t <= k/d_s  <=>  R d_s <= k 2^32 (exact in uint64) */
       for (int64_t j = 0; j < d; ++j) {
         uint32_t t = (uint32_t)g_indices[beg + j];
-        uint64_t R = variate_draw(st, sampler, layer, t, s);
+        uint64_t R = variate_draw(st, t, s);
         if (R * (uint64_t)d <= ((uint64_t)k << 32)) {
           blk->col_global[m] = (int32_t)t; blk->eid[m] = beg + j; ++m;
         }
@@ -370,7 +403,7 @@ static int sample_layer(const int64_t* g_indptr, const int32_t* g_indices, int64
         }
       } else {
         for (int64_t j = 0; j < d; ++j) {
-          pairs[j].r = variate_draw(st, sampler, layer, (uint32_t)g_indices[beg + j], s);
+          pairs[j].r = variate_draw(st, (uint32_t)g_indices[beg + j], s);
           pairs[j].j = j;
         }
         qsort(pairs, (size_t)d, sizeof(ns_pair), ns_pair_cmp);

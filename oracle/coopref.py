@@ -44,6 +44,10 @@ def lib():
         L = C.CDLL(_LIB)
         L.coopref_philox4x32_10.argtypes = [C.POINTER(C.c_uint32)] * 3
         L.coopref_philox4x32_10.restype = None
+        L.coopref_mix32.argtypes = [C.c_uint32]
+        L.coopref_mix32.restype = C.c_uint32
+        L.coopref_layer_keys.argtypes = [C.c_uint64, C.c_int, C.c_int, C.c_uint64, C.POINTER(C.c_uint32)]
+        L.coopref_layer_keys.restype = None
         L.coopref_variate.argtypes = [C.c_uint64, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
         L.coopref_variate.restype = C.c_uint32
         for name in ("rcp", "rsqrt", "log", "exp", "qtail"):
@@ -88,6 +92,16 @@ def philox4x32_10(ctr, key):
     o = (C.c_uint32 * 4)()
     lib().coopref_philox4x32_10(c, k, o)
     return [int(x) for x in o]
+
+
+def mix32(x):
+    return int(lib().coopref_mix32(int(x) & 0xFFFFFFFF))
+
+
+def layer_keys(seed, sampler, layer, g):
+    K = (C.c_uint32 * 4)()
+    lib().coopref_layer_keys(seed, sampler, layer, g, K)
+    return [int(x) for x in K]
 
 
 def variate(seed, sampler, layer, it, kappa, t, s=0):

@@ -55,6 +55,7 @@ def lib():
     L.coop_gather_status.argtypes = [C.c_void_p]
     L.coop_gather_status.restype = C.c_int
     L.coop_profile_enable.argtypes = [C.c_int]
+    L.coop_profile_filter.argtypes = [C.c_int]
     L.coop_profile_reset.argtypes = []
     L.coop_profile_kernels.restype = C.c_int
     L.coop_profile_name.argtypes = [C.c_int]
@@ -230,6 +231,13 @@ def coop_gather_status(stream=None):
 
 def profile_enable(on=True):
     lib().coop_profile_enable(1 if on else 0)
+
+
+def profile_filter(name=None):
+    """Times only the named kernel while profiling is on (None: all kernels)."""
+    L = lib()
+    ids = {L.coop_profile_name(i).decode(): i for i in range(L.coop_profile_kernels())}
+    _check(L.coop_profile_filter(-1 if name is None else ids[name]))
 
 
 def profile_reset():

@@ -14,6 +14,7 @@ struct Pending { int id; hipEvent_t a, b; };
 struct Prof {
   std::mutex mu;
   bool on = false;
+  int only = -1;  // when >= 0, the one kernel id that is timed
   double ms[K_COUNT_] = {};
   int64_t launches[K_COUNT_] = {};
   std::vector<Pending> pending;
@@ -49,7 +50,7 @@ void collect_locked() {
 }  // namespace
 
 void prof_begin(int id, hipStream_t s) {
-  if (!g_prof.on) return;
+  if (!g_prof.on || (g_prof.only >= 0 && g_prof.only != id)) return;
   std::lock_guard<std::mutex> lk(g_prof.mu);
   hipEvent_t a = take_event();
   if (!a) return;
@@ -58,7 +59,7 @@ void prof_begin(int id, hipStream_t s) {
 }
 
 void prof_end(int id, hipStream_t s) {
-  if (!g_prof.on) return;
+  if (!g_prof.on || (g_prof.only >= 0 && g_prof.only != id)) return;
   std::lock_guard<std::mutex> lk(g_prof.mu);
   hipEvent_t a = g_prof.open[id];
   if (!a) return;
@@ -296,6 +297,13 @@ int coop_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof.mu);
   if (!on) collect_locked();
   g_prof.on = on != 0;
+  return COOP_OK;
+}
+
+int coop_profile_filter(int id) {
+  if (id >= K_COUNT_) return COOP_E_ARG;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  g_prof.only = id < 0 ? -1 : id;
   return COOP_OK;
 }
 

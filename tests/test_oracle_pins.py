@@ -39,9 +39,39 @@ def py_philox(ctr, key, rounds=10):
     return c
 
 
+def py_mix32(x):
+    x ^= x >> 16
+    x = (x * 0x7FEB352D) & M32
+    x ^= x >> 15
+    x = (x * 0x846CA68B) & M32
+    x ^= x >> 16
+    return x
+
+
+def py_unmix32(y):
+    """Inverse of py_mix32, step by step (each xor-shift and each odd multiply is invertible)."""
+    def unshift(v, s):
+        r = v
+        for _ in range(32 // s + 1):
+            r = v ^ (r >> s)
+        return r
+    y = unshift(y, 16)
+    y = (y * pow(0x846CA68B, -1, 1 << 32)) & M32
+    y = unshift(y, 15)
+    y = (y * pow(0x7FEB352D, -1, 1 << 32)) & M32
+    return unshift(y, 16)
+
+
+def py_keys(seed, sampler, layer, g):
+    return py_philox([g & M32, (g >> 32) & M32, layer | (sampler << 8), 0x434F4F50], [seed & M32, seed >> 32])
+
+
 def py_uniform(seed, sampler, layer, g, t, s):
-    c1 = M32 if sampler == R.LABOR0 else s
-    return py_philox([t, c1, layer | (sampler << 8), g & M32], [seed & M32, seed >> 32])[0]
+    K = py_keys(seed, sampler, layer, g)
+    a = py_mix32(t ^ K[0]) ^ K[1]
+    if sampler == R.LABOR0:
+        return a
+    return py_mix32(a ^ py_mix32(s ^ K[2])) ^ K[3]
 
 
 def brute_sample(indptr, indices, seeds, fanouts, sampler, seed, g):
@@ -117,6 +147,41 @@ def test_philox_matches_independent_python():
         ctr = rng.integers(0, 2**32, 4).tolist()
         key = rng.integers(0, 2**32, 2).tolist()
         assert R.philox4x32_10(ctr, key) == py_philox(ctr, key)
+
+
+def test_mixer_is_a_well_mixing_permutation():
+    rng = np.random.default_rng(7)
+    xs = rng.integers(0, 2**32, 4000).tolist() + [0, 1, M32, 2**31]
+    for x in xs:
+        y = R.mix32(x)
+        assert y == py_mix32(x) and py_unmix32(y) == x          # a bijection: the inverse exists
+    # avalanche: flipping any input bit flips every output bit about half the time
+    xs = rng.integers(0, 2**32, 20000, dtype=np.uint64)
+
+    def mix_np(x):
+        x = x ^ (x >> 16)
+        x = (x * 0x7FEB352D) & M32
+        x = x ^ (x >> 15)
+        x = (x * 0x846CA68B) & M32
+        return x ^ (x >> 16)
+
+    base = mix_np(xs)
+    assert int(base[5]) == R.mix32(int(xs[5]))
+    for i in range(32):
+        diff = base ^ mix_np(xs ^ np.uint64(1 << i))
+        for o in range(32):
+            assert abs(float(((diff >> np.uint64(o)) & np.uint64(1)).mean()) - 0.5) < 0.03
+
+
+def test_layer_keys_are_philox_words():
+    rng = np.random.default_rng(3)
+    for _ in range(100):
+        seed = int(rng.integers(0, 2**63)) * 2 + 1
+        sampler, layer, g = int(rng.integers(0, 2)), int(rng.integers(0, 200)), int(rng.integers(0, 2**62))
+        assert R.layer_keys(seed, sampler, layer, g) == py_keys(seed, sampler, layer, g)
+    # distinct (seed, sampler, layer, group) give unrelated keys
+    ks = {tuple(R.layer_keys(1, sa, la, g)) for sa in (0, 1) for la in range(4) for g in range(50)}
+    assert len(ks) == 400
 
 
 def test_variate_counter_layout():
