@@ -141,6 +141,13 @@ int coop_gather_status(void* stream);
 /* Name of an error code (static string). */
 const char* coop_strerror(int code);
 
+/*
+ * Tuning knobs (process-wide; for experiments and tests, results never depend on them).
+ *   COOP_TUNE_STAGE_CAP  entries per LABOR-0 staging row (power of two, 1..4096; 0 = automatic)
+ */
+#define COOP_TUNE_STAGE_CAP 1
+int coop_tune(int knob, int64_t value);
+
 /* Library ABI version (bumped when a signature in this file changes). */
 int coop_version(void);
 

@@ -54,6 +54,8 @@ def lib():
     L.coop_gather.restype = C.c_int
     L.coop_gather_status.argtypes = [C.c_void_p]
     L.coop_gather_status.restype = C.c_int
+    L.coop_tune.argtypes = [C.c_int, C.c_int64]
+    L.coop_tune.restype = C.c_int
     L.coop_profile_enable.argtypes = [C.c_int]
     L.coop_profile_filter.argtypes = [C.c_int]
     L.coop_profile_reset.argtypes = []
@@ -227,6 +229,13 @@ def coop_gather(feat, ids, out=None, stream=None):
 
 def coop_gather_status(stream=None):
     _check(lib().coop_gather_status(_stream_ptr(stream)))
+
+
+COOP_TUNE_STAGE_CAP = 1
+
+
+def coop_tune(knob, value):
+    _check(lib().coop_tune(knob, value))
 
 
 def profile_enable(on=True):

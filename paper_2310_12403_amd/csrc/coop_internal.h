@@ -11,7 +11,8 @@ namespace coop {
 enum KernelId {
   K_FILL = 0,        // memory fill (table clear, control words)
   K_LABOR_COUNT,     // LABOR-0 count pass
-  K_LABOR_FILL,      // LABOR-0 fill pass
+  K_LABOR_FILL,      // LABOR-0 fill pass (copy of the staged rows)
+  K_LABOR_OVERFLOW,  // LABOR-0 second scan of overflowed rows
   K_NS_COUNT,        // NS count pass (min(k, d))
   K_NS_FILL,         // NS selection + fill pass
   K_SCAN_REDUCE,     // scan: per-block sums
@@ -77,7 +78,7 @@ struct Ctl {
   int32_t err_range;     // a seed / id out of range
   int32_t err_dup;       // a duplicate in the seed list
   int32_t err_capacity;  // NS candidate buffer could not be sized
-  int32_t pad;
+  int32_t n_overflow;    // LABOR-0 destinations whose staging row overflowed (this layer and earlier)
 };
 
 // Dedup + relabel of one layer (Eq. 2).  Inputs: dst[n_dst] (distinct), col_global[m].  Outputs: col_local[m],

@@ -1,10 +1,15 @@
-// Sampling layers of Algorithm 1 on one GPU: per layer a count pass, a device-wide scan and a fill pass
-// (one wave64 per destination vertex, coalesced reads of its neighbour list), then dedup + relabel.
+// Sampling layers of Algorithm 1 on one GPU.  Per layer: a neighbour-scan pass (one wave64 per destination vertex,
+// 16-byte coalesced reads of its neighbour list), a device-wide scan of the per-destination counts, a fill pass,
+// then dedup + relabel (unique.hip).
 //
 //   LABOR-0 (App. A.1.2): edge (t -> s) is kept iff r_t <= k / d_s, i.e. R_t * d_s <= k * 2^32 in integers,
 //                         which for d_s > k is R_t <= floor(k * 2^32 / d_s).
 //   NS      (App. A.1.1): d_s <= k keeps N(s); otherwise the k neighbours with the smallest (R_ts, position).
 // Kept edges leave in (destination order, adjacency order).
+//
+// LABOR-0 examines every neighbour once: the scan pass parks the kept (vertex, position) pairs of each destination
+// in a small per-destination staging row, so the fill pass is a copy and the adjacency is not read again.  A row
+// that overflows (more kept edges than the row holds) is rare and handled by a second scan of just those lists.
 #include <math.h>
 
 #include "coop_internal.h"
@@ -13,12 +18,76 @@
 
 namespace coop {
 
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// Visits the neighbour list [beg, beg + d) of one destination with the whole wave, VEC entries per lane and step,
+// and calls emit(rank, t, j) for every kept neighbour t at list position j; rank counts kept neighbours in
+// adjacency order.  `all` keeps everything (d <= k).  Returns the number kept (same value in every lane).
+template <bool BLEND, int VEC, typename Emit>
+__device__ __forceinline__ uint32_t labor_scan_list(const int32_t* __restrict__ g_indices, int64_t n_edges_total, int64_t beg,
+                                                    int64_t d, bool all, uint32_t thr, const VariateParams& vp, Emit emit) {
+  const int lane = lane_id();
+  const int64_t end = beg + d;
+  uint32_t count = 0;
+  if constexpr (VEC == 4) {
+    for (int64_t base = beg & ~(int64_t)3; base < end; base += kWave * 4) {
+      const int64_t q = base + (int64_t)lane * 4;  // multiple of 4: a 16-byte aligned group of the indices array
+      i32x4 v = {0, 0, 0, 0};
+      if (q < end) {
+        if (q + 3 < n_edges_total) {
+          v = *reinterpret_cast<const i32x4*>(g_indices + q);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (q + e < n_edges_total) v[e] = g_indices[q + e];
+        }
+      }
+      bool keep[4];
+      uint64_t m[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int64_t pos = q + e;
+        bool kp = pos >= beg && pos < end;
+        if (kp && !all) kp = variate<false, BLEND>(vp, (uint32_t)v[e], 0u, 0u) <= thr;
+        keep[e] = kp;
+        m[e] = ballot64(kp);
+      }
+      uint32_t rank = count + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (keep[e]) {
+          emit(rank, v[e], (uint32_t)(q + e - beg));
+          ++rank;
+        }
+      }
+      count += (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
+    }
+  } else {
+    for (int64_t base = 0; base < d; base += kWave) {
+      const int64_t j = base + lane;
+      bool kp = j < d;
+      int32_t t = 0;
+      if (kp) {
+        t = g_indices[beg + j];
+        if (!all) kp = variate<false, BLEND>(vp, (uint32_t)t, 0u, 0u) <= thr;
+      }
+      const uint64_t m = ballot64(kp);
+      if (kp) emit(count + lanes_below(m), t, (uint32_t)j);
+      count += (uint32_t)__popcll(m);
+    }
+  }
+  return count;
+}
+
+struct StageEntry { int32_t t; uint32_t j; };  // kept source vertex, its position in the destination's list
+
 // ---- LABOR-0 --------------------------------------------------------------------------------------------------
-template <bool BLEND>
+template <bool BLEND, int VEC>
 __global__ __launch_bounds__(kBlock) void k_labor_count(const int64_t* __restrict__ g_indptr,
                                                         const int32_t* __restrict__ g_indices, int64_t n_vertices,
-                                                        const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
-                                                        VariateParams vp, int32_t* __restrict__ cnt, Ctl* ctl) {
+                                                        int64_t n_edges_total, const int32_t* __restrict__ dst, int64_t n_dst,
+                                                        uint32_t k, VariateParams vp, uint32_t stage_cap,
+                                                        StageEntry* __restrict__ stage, int32_t* __restrict__ cnt, Ctl* ctl) {
   const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
   if (w >= n_dst) return;
   const int lane = lane_id();
@@ -29,64 +98,58 @@ __global__ __launch_bounds__(kBlock) void k_labor_count(const int64_t* __restric
   }
   const int64_t beg = g_indptr[s];
   const int64_t d = g_indptr[s + 1] - beg;
-  uint32_t c;
-  if (d <= (int64_t)k) {
-    c = (uint32_t)d;
-  } else {
-    const uint32_t thr = (uint32_t)(((uint64_t)k << 32) / (uint64_t)d);
-    c = 0;
-    for (int64_t base = 0; base < d; base += kWave) {
-      const int64_t j = base + lane;
-      bool keep = false;
-      if (j < d) {
-        const uint32_t t = (uint32_t)g_indices[beg + j];
-        keep = variate<BLEND>(vp, t, 0xFFFFFFFFu) <= thr;
-      }
-      c += (uint32_t)__popcll(ballot64(keep));
-    }
+  const bool all = d <= (int64_t)k;
+  const uint32_t thr = all ? 0xFFFFFFFFu : (uint32_t)(((uint64_t)k << 32) / (uint64_t)d);
+  StageEntry* row = stage + (size_t)w * stage_cap;
+  const uint32_t c = labor_scan_list<BLEND, VEC>(g_indices, n_edges_total, beg, d, all, thr, vp,
+                                                 [&](uint32_t rank, int32_t t, uint32_t j) {
+                                                   if (rank < stage_cap) row[rank] = StageEntry{t, j};
+                                                 });
+  if (lane == 0) {
+    cnt[w] = (int32_t)c;
+    if (c > stage_cap) atomicAdd(&ctl->n_overflow, 1);
   }
-  if (lane == 0) cnt[w] = (int32_t)c;
 }
 
-template <bool BLEND>
-__global__ __launch_bounds__(kBlock) void k_labor_fill(const int64_t* __restrict__ g_indptr,
-                                                       const int32_t* __restrict__ g_indices,
-                                                       const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
-                                                       VariateParams vp, const int64_t* __restrict__ eptr,
-                                                       int32_t* __restrict__ col_global, int64_t* __restrict__ eid) {
+// copy of the staged rows into the block's edge arrays: one thread per (destination, row slot)
+__global__ __launch_bounds__(kBlock) void k_labor_fill_staged(const int64_t* __restrict__ g_indptr,
+                                                              const int32_t* __restrict__ dst, int64_t n_dst,
+                                                              int stage_cap_log2, const StageEntry* __restrict__ stage,
+                                                              const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
+                                                              int64_t* __restrict__ eid) {
+  const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t w = idx >> stage_cap_log2;
+  if (w >= n_dst) return;
+  const int64_t slot = idx & (((int64_t)1 << stage_cap_log2) - 1);
+  const int64_t o = eptr[w];
+  const int64_t c = eptr[w + 1] - o;
+  if (slot >= c || c > ((int64_t)1 << stage_cap_log2)) return;
+  const StageEntry e = stage[idx];
+  col_global[o + slot] = e.t;
+  eid[o + slot] = g_indptr[dst[w]] + e.j;
+}
+
+// second scan of the (rare) destinations whose staging row overflowed, writing straight to the edge arrays
+template <bool BLEND, int VEC>
+__global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int64_t* __restrict__ g_indptr,
+                                                                const int32_t* __restrict__ g_indices, int64_t n_edges_total,
+                                                                const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
+                                                                VariateParams vp, uint32_t stage_cap,
+                                                                const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
+                                                                int64_t* __restrict__ eid) {
   const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
   if (w >= n_dst) return;
-  const int lane = lane_id();
-  int64_t o = eptr[w];
-  const int64_t o_end = eptr[w + 1];
-  if (o == o_end) return;  // nothing kept (also covers out-of-range seeds, whose count is 0)
+  const int64_t o = eptr[w];
+  if (eptr[w + 1] - o <= (int64_t)stage_cap) return;
   const int32_t s = dst[w];
   const int64_t beg = g_indptr[s];
   const int64_t d = g_indptr[s + 1] - beg;
-  if (d <= (int64_t)k) {
-    for (int64_t j = lane; j < d; j += kWave) {
-      col_global[o + j] = g_indices[beg + j];
-      eid[o + j] = beg + j;
-    }
-    return;
-  }
-  const uint32_t thr = (uint32_t)(((uint64_t)k << 32) / (uint64_t)d);
-  for (int64_t base = 0; base < d; base += kWave) {
-    const int64_t j = base + lane;
-    bool keep = false;
-    uint32_t t = 0;
-    if (j < d) {
-      t = (uint32_t)g_indices[beg + j];
-      keep = variate<BLEND>(vp, t, 0xFFFFFFFFu) <= thr;
-    }
-    const uint64_t mask = ballot64(keep);
-    if (keep) {
-      const int64_t p = o + lanes_below(mask);
-      col_global[p] = (int32_t)t;
-      eid[p] = beg + j;
-    }
-    o += __popcll(mask);
-  }
+  const bool all = d <= (int64_t)k;
+  const uint32_t thr = all ? 0xFFFFFFFFu : (uint32_t)(((uint64_t)k << 32) / (uint64_t)d);
+  labor_scan_list<BLEND, VEC>(g_indices, n_edges_total, beg, d, all, thr, vp, [&](uint32_t rank, int32_t t, uint32_t j) {
+    col_global[o + rank] = t;
+    eid[o + rank] = beg + j;
+  });
 }
 
 // ---- NS -------------------------------------------------------------------------------------------------------
@@ -143,6 +206,8 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
   }
   uint32_t* cand_r = (uint32_t*)(lds_keys + (size_t)wib * cap);  // [cap] variates
   uint32_t* cand_j = cand_r + cap;                               // [cap] positions (d < 2^31)
+  const uint32_t sigma_a = ns_sigma(vp.Ka, (uint32_t)s);
+  const uint32_t sigma_b = BLEND ? ns_sigma(vp.Kb, (uint32_t)s) : 0u;
 
   // bound such that E[#candidates] = target: R <= bound with probability (bound + 1) / 2^32
   uint64_t lo = 0, hi = 0xFFFFFFFFull;  // bisection bracket on the bound, used only after a failed pass
@@ -156,7 +221,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
       bool in = false;
       uint32_t r = 0;
       if (j < d) {
-        r = variate<BLEND>(vp, (uint32_t)g_indices[beg + j], (uint32_t)s);
+        r = variate<true, BLEND>(vp, (uint32_t)g_indices[beg + j], sigma_a, sigma_b);
         in = r <= (uint32_t)bound;
       }
       const uint64_t mask = ballot64(in);
@@ -207,17 +272,17 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
   }
 }
 
-// ---- small copies ---------------------------------------------------------------------------------------------
+// ---- small kernels --------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_copy_i32(const int32_t* __restrict__ in, int32_t* __restrict__ out, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i < n) out[i] = in[i];
 }
 
-__global__ void k_clear_ctl(Ctl* ctl) {
-  ctl->total_edges = 0; ctl->total_new = 0; ctl->err_range = 0; ctl->err_dup = 0; ctl->err_capacity = 0; ctl->pad = 0;
-}
+__global__ void k_clear_ctl(Ctl* ctl) { *ctl = Ctl{}; }
 
-static inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+__global__ void k_publish_edges(Ctl* ctl, const int64_t* __restrict__ total) { ctl->total_edges = *total; }
+
+static inline unsigned blocks_for(int64_t n, int64_t per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
 static int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
   COOP_HIP_TRY(hipMemcpyAsync(h_ctl, d_ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s));
@@ -228,9 +293,34 @@ static int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
   return COOP_OK;
 }
 
+int g_stage_cap_override = 0;  // COOP_TUNE_STAGE_CAP
+
 }  // namespace coop
 
 using namespace coop;
+
+extern "C" int coop_tune(int knob, int64_t value) {
+  switch (knob) {
+    case COOP_TUNE_STAGE_CAP:
+      if (value != 0 && (value < 1 || value > 4096 || (value & (value - 1)))) return COOP_E_ARG;
+      g_stage_cap_override = (int)value;
+      return COOP_OK;
+    default:
+      return COOP_E_ARG;
+  }
+}
+
+// dispatch on (BLEND, VEC)
+#define COOP_LABOR_DISPATCH(id, name, grid, ...)                                                                    \
+  do {                                                                                                              \
+    if (blend) {                                                                                                    \
+      if (vec4) COOP_LAUNCH(id, (name<true, 4>), grid, dim3(kBlock), 0, s, __VA_ARGS__);                            \
+      else COOP_LAUNCH(id, (name<true, 1>), grid, dim3(kBlock), 0, s, __VA_ARGS__);                                 \
+    } else {                                                                                                        \
+      if (vec4) COOP_LAUNCH(id, (name<false, 4>), grid, dim3(kBlock), 0, s, __VA_ARGS__);                           \
+      else COOP_LAUNCH(id, (name<false, 1>), grid, dim3(kBlock), 0, s, __VA_ARGS__);                                \
+    }                                                                                                               \
+  } while (0)
 
 extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
                            int sampler, uint64_t iter, uint32_t kappa, uint64_t seed, coop_alloc_fn alloc_fn,
@@ -244,16 +334,16 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
 
   hipStream_t s = (hipStream_t)stream;
   Alloc alloc{alloc_fn, alloc_ctx};
+  const bool vec4 = ((uintptr_t)g->indices & 15) == 0;
 
-  // group / interpolation state of App. A.7
+  // group / interpolation state of App. A.7: g = floor(iter / kappa), c = (iter mod kappa) / kappa
   VariateParams vp{};
-  vp.key0 = (uint32_t)seed;
-  vp.key1 = (uint32_t)(seed >> 32);
+  uint64_t group = 0;
   bool blend = false;
-  vp.g = 0; vp.cw = 1.0; vp.sw = 0.0;
+  vp.cw = 1.0; vp.sw = 0.0;
   if (kappa != 0) {
     const uint64_t i = iter % kappa;
-    vp.g = (uint32_t)(iter / kappa);
+    group = iter / kappa;
     blend = i != 0;
     const double c = (double)i / (double)kappa;
     vp.cw = cos(c * 1.5707963267948966);
@@ -275,33 +365,45 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
   int rc = COOP_OK;
   for (int l = 0; l < L && rc == COOP_OK; ++l) {
     const uint32_t k = (uint32_t)fanouts[l];
-    vp.c2 = (uint32_t)l | ((uint32_t)sampler << 8);
+    layer_keys(seed, sampler, l, group, vp.Ka);
+    layer_keys(seed, sampler, l, group + 1, vp.Kb);
     coop_block blk{};
     blk.n_dst = n_dst;
     blk.dst_ids = const_cast<int32_t*>(dst);
     blk.indptr = alloc.get<int64_t>(n_dst + 1, COOP_TAG_OUTPUT);
     int32_t* cnt = alloc.get<int32_t>(n_dst, COOP_TAG_SCRATCH);
     void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
+
+    // LABOR-0 staging rows: room for 2k + 16 kept edges (a row overflows with probability < 1e-8 at k = 10),
+    // between 32 and 256 entries, shrunk while the whole staging area would exceed 1 GiB
+    uint32_t stage_cap = 32;
+    int stage_cap_log2 = 5;
+    StageEntry* stage = nullptr;
+    if (sampler == COOP_LABOR0) {
+      while (stage_cap < 2 * (uint64_t)k + 16 && stage_cap < 256) { stage_cap <<= 1; ++stage_cap_log2; }
+      while (stage_cap > 32 && (uint64_t)n_dst * stage_cap * sizeof(StageEntry) > ((uint64_t)1 << 30)) { stage_cap >>= 1; --stage_cap_log2; }
+      if (g_stage_cap_override) {
+        stage_cap = (uint32_t)g_stage_cap_override;
+        stage_cap_log2 = 0;
+        while ((1u << stage_cap_log2) < stage_cap) ++stage_cap_log2;
+      }
+      stage = alloc.get<StageEntry>(n_dst * (int64_t)stage_cap, COOP_TAG_SCRATCH);
+    }
     if (alloc.failed) { rc = COOP_E_NOMEM; break; }
 
-    // count pass
+    // neighbour scan / count pass
     if (n_dst > 0) {
       if (sampler == COOP_LABOR0) {
         const dim3 grid(blocks_for(n_dst, kWavesPerBlock));
-        if (blend)
-          COOP_LAUNCH(K_LABOR_COUNT, k_labor_count<true>, grid, dim3(kBlock), 0, s, g->indptr, g->indices, g->n_vertices, dst,
-                      n_dst, k, vp, cnt, d_ctl);
-        else
-          COOP_LAUNCH(K_LABOR_COUNT, k_labor_count<false>, grid, dim3(kBlock), 0, s, g->indptr, g->indices, g->n_vertices, dst,
-                      n_dst, k, vp, cnt, d_ctl);
+        COOP_LABOR_DISPATCH(K_LABOR_COUNT, k_labor_count, grid, g->indptr, g->indices, g->n_vertices, g->n_edges, dst, n_dst, k,
+                            vp, stage_cap, stage, cnt, d_ctl);
       } else {
         COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, g->indptr, g->n_vertices, dst,
                     n_dst, k, cnt, d_ctl);
       }
     }
     scan_i32_to_i64(cnt, n_dst, blk.indptr, scan_tmp, s);
-    // m_l = indptr[n_dst]
-    COOP_HIP_TRY(hipMemcpyAsync(&d_ctl->total_edges, blk.indptr + n_dst, sizeof(int64_t), hipMemcpyDeviceToDevice, s));
+    COOP_LAUNCH(K_FILL, k_publish_edges, dim3(1), dim3(1), 0, s, d_ctl, blk.indptr + n_dst);  // m_l = indptr[n_dst]
     rc = read_ctl(d_ctl, h_ctl, s);
     if (rc != COOP_OK) break;
     const int64_t m = h_ctl->total_edges;
@@ -315,13 +417,13 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
     // fill pass
     if (m > 0) {
       if (sampler == COOP_LABOR0) {
-        const dim3 grid(blocks_for(n_dst, kWavesPerBlock));
-        if (blend)
-          COOP_LAUNCH(K_LABOR_FILL, k_labor_fill<true>, grid, dim3(kBlock), 0, s, g->indptr, g->indices, dst, n_dst, k, vp,
-                      blk.indptr, blk.col_global, blk.eid);
-        else
-          COOP_LAUNCH(K_LABOR_FILL, k_labor_fill<false>, grid, dim3(kBlock), 0, s, g->indptr, g->indices, dst, n_dst, k, vp,
-                      blk.indptr, blk.col_global, blk.eid);
+        COOP_LAUNCH(K_LABOR_FILL, k_labor_fill_staged, dim3(blocks_for(n_dst * (int64_t)stage_cap, kBlock)), dim3(kBlock), 0, s,
+                    g->indptr, dst, n_dst, stage_cap_log2, stage, blk.indptr, blk.col_global, blk.eid);
+        if (h_ctl->n_overflow > 0) {
+          const dim3 grid(blocks_for(n_dst, kWavesPerBlock));
+          COOP_LABOR_DISPATCH(K_LABOR_OVERFLOW, k_labor_fill_overflow, grid, g->indptr, g->indices, g->n_edges, dst, n_dst, k, vp,
+                              stage_cap, blk.indptr, blk.col_global, blk.eid);
+        }
       } else {
         // candidate buffer: cap >= 4k (power of two, at least 256); expected candidates: 3k + 24.  A fanout above
         // kNsMaxSelect is served only while no degree exceeds it (the kernel reports the first that does).

@@ -33,6 +33,9 @@ __global__ __launch_bounds__(kBlock) void k_uniq_insert(const int32_t* __restric
       if (cur == kEmptySlot) return;  // claimed
     }
     if ((uint32_t)(cur >> 32) == key) {
+      // an edge position above the one already recorded cannot lower it: no atomic needed (this is what keeps a
+      // hub that shows up in thousands of lists from serialising thousands of atomics on one slot)
+      if (i >= n_dst && cur < mine) return;
       const unsigned long long old = atomicMin(&table[h], mine);
       // two positions below n_dst with one key: the destination list holds a vertex twice
       if (i < n_dst && (int64_t)(uint32_t)old < n_dst) atomicOr(&ctl->err_dup, 1);

@@ -1,8 +1,13 @@
 // Random variates of smoothed dependent minibatching (App. A.7), device side.
 //
-// r = R / 2^32.  U(g) is word 0 of Philox4x32-10 (Salmon et al., SC'11) keyed by the user seed, with counter
-// (t, s | 0xFFFFFFFF, layer | sampler << 8, g).  Inside a group of kappa iterations the variate moves from
-// U(g) to U(g+1) along n(c) = cos(c pi/2) n1 + sin(c pi/2) n2 in normal space, r = Phi(n(c)).
+// r = R / 2^32.  The "PRNG initialised with (z, t, s)" is a keyed hash: four key words K0..K3 per
+// (seed, group, layer, sampler) come from one Philox4x32-10 call on the host; per source vertex t (and destination
+// s for NS) the uniform is
+//     LABOR-0:  U = mix(t ^ K0) ^ K1
+//     NS:       U = mix(mix(t ^ K0) ^ K1 ^ mix(s ^ K2)) ^ K3
+// with mix a 32-bit xorshift-multiply permutation (two multiplies): a few integer instructions per examined
+// neighbour, so that the neighbour scan runs at memory speed.  Inside a group of kappa iterations the variate moves
+// from U(g) to U(g+1) along n(c) = cos(c pi/2) n1 + sin(c pi/2) n2 in normal space, r = Phi(n(c)).
 //
 // Phi and Phi^-1 are fixed sequences of binary64 add / mul / fma and bit moves (no library calls, no division,
 // no square root), so that any IEEE machine produces the same bits.  This file must be compiled with
@@ -14,15 +19,23 @@
 namespace coop {
 
 struct VariateParams {
-  uint32_t key0, key1;  // user seed, low / high word
-  uint32_t c2;          // layer | sampler << 8
-  uint32_t g;           // group index floor(iter / kappa) mod 2^32
-  double cw, sw;        // cos(c pi/2), sin(c pi/2); used by the blended path only
+  uint32_t Ka[4];  // key words of group g
+  uint32_t Kb[4];  // key words of group g + 1 (blended path only)
+  double cw, sw;   // cos(c pi/2), sin(c pi/2) (blended path only)
 };
 
-__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                                        uint32_t k0, uint32_t k1) {
-#pragma unroll
+__host__ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
+}
+
+// Philox4x32-10 (Salmon et al., SC'11); host side, once per layer, for the key words.
+inline void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
     const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
@@ -35,7 +48,13 @@ __device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }
-  return c0;
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+inline void layer_keys(uint64_t seed, int sampler, int layer, uint64_t g, uint32_t K[4]) {
+  const uint32_t ctr[4] = {(uint32_t)g, (uint32_t)(g >> 32), (uint32_t)layer | ((uint32_t)sampler << 8), 0x434F4F50u};
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  philox4x32_10(ctr, key, K);
 }
 
 // ---- reproducible binary64 kit ------------------------------------------------------------------------------
@@ -191,14 +210,24 @@ __device__ __forceinline__ uint32_t kit_phi_to_u32(double x) {
   return neg ? lo : (0xFFFFFFFFu - lo);
 }
 
-// R for source vertex t (and destination s for NS; pass 0xFFFFFFFF for LABOR-0)
-template <bool BLEND>
-__device__ __forceinline__ uint32_t variate(const VariateParams& vp, uint32_t t, uint32_t c1) {
-  const uint32_t U1 = philox4x32_10_word0(t, c1, vp.c2, vp.g, vp.key0, vp.key1);
+// sigma = mix(s ^ K2) of the destination, wave-uniform; NS only
+__device__ __forceinline__ uint32_t ns_sigma(const uint32_t K[4], uint32_t s) { return mix32(s ^ K[2]); }
+
+template <bool NS>
+__device__ __forceinline__ uint32_t keyed_uniform(const uint32_t K[4], uint32_t t, uint32_t sigma) {
+  const uint32_t a = mix32(t ^ K[0]) ^ K[1];
+  if constexpr (!NS) return a;
+  else return mix32(a ^ sigma) ^ K[3];
+}
+
+// R for source vertex t; for NS, sigma_a / sigma_b are ns_sigma(Ka, s) / ns_sigma(Kb, s) of the destination s
+template <bool NS, bool BLEND>
+__device__ __forceinline__ uint32_t variate(const VariateParams& vp, uint32_t t, uint32_t sigma_a, uint32_t sigma_b) {
+  const uint32_t U1 = keyed_uniform<NS>(vp.Ka, t, sigma_a);
   if constexpr (!BLEND) {
     return U1;
   } else {
-    const uint32_t U2 = philox4x32_10_word0(t, c1, vp.c2, vp.g + 1u, vp.key0, vp.key1);
+    const uint32_t U2 = keyed_uniform<NS>(vp.Kb, t, sigma_b);
     const double n1 = kit_phi_inv_u32(U1);
     const double n2 = kit_phi_inv_u32(U2);
     return kit_phi_to_u32(__builtin_fma(vp.cw, n1, vp.sw * n2));

@@ -173,3 +173,35 @@ def test_sample_then_gather_end_to_end(P, tiny):
     rows = P.coop_gather(feat.cuda(), blocks[-1].src_ids)
     P.coop_gather_status()
     assert rows.cpu().numpy().tobytes() == R.gather(feat.numpy(), blocks[-1].src_ids.cpu().numpy()).tobytes()
+
+
+def test_labor_stage_overflow_path(P, tiny, medium):
+    """Staging rows far smaller than the kept-edge counts: every destination takes the second-scan path."""
+    try:
+        for cap in (1, 4):
+            P.coop_tune(P.COOP_TUNE_STAGE_CAP, cap)
+            seeds = synth.seed_batches(tiny.n, 700, seed=6)(0).numpy()
+            compare(P, tiny, seeds, (10, 10), R.LABOR0, it=2, kappa=1, seed=3)
+            compare(P, tiny, seeds[:100], (10, 10), R.LABOR0, it=5, kappa=4, seed=3)
+            compare(P, medium, synth.seed_batches(medium.n, 2000, seed=6)(0).numpy(), (25, 10), R.LABOR0, it=2, seed=8)
+    finally:
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 0)
+
+
+def test_unaligned_indices_base(P, tiny):
+    """A CSR whose indices array is only 4-byte aligned takes the scalar-load scan."""
+    base = torch.empty(tiny.indices_d.numel() + 1, dtype=torch.int32, device="cuda")
+    view = base[1:]
+    view.copy_(tiny.indices_d)
+    assert view.data_ptr() % 16 != 0
+    g2 = P.coop_graph_load(tiny.indptr_d, view, P.COOP_VALIDATE)
+    seeds = synth.seed_batches(tiny.n, 512, seed=8)(0)
+    a = P.coop_sample(tiny.graph, seeds.cuda(), (10, 10), R.LABOR0, it=1, seed=4)
+    b = P.coop_sample(g2, seeds.cuda(), (10, 10), R.LABOR0, it=1, seed=4)
+    for x, y in zip(a, b):
+        for n in NAMES:
+            assert torch.equal(getattr(x, n), getattr(y, n))
+    want = R.sample(tiny.indptr_h, tiny.indices_h, seeds.numpy(), (10, 10), R.LABOR0, it=1, seed=4)
+    for x, w in zip(b, want):
+        for n in NAMES:
+            assert np.array_equal(getattr(x, n).cpu().numpy(), w[n])
