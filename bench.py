@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--sampler", default=None, choices=[None, "labor0", "ns"])
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (a known-size reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -90,6 +92,14 @@ def main():
     probe = P.coop_sample(graph, get_seeds(0), fanouts, sampler, it=0, kappa=args.kappa, seed=0, arena=arena)
     out = torch.empty((int(probe[-1].n_src * 1.25) + 1024, dim), dtype=dtype, device=dev)
     log("probe: " + ", ".join("|S^%d|=%d |E^%d|=%d" % (l + 1, b.n_src, l, b.n_edges) for l, b in enumerate(probe)))
+
+    if args.copy_calibration:
+        a = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
 
     for i in range(args.warmup):
         step(i, out)

@@ -20,51 +20,22 @@ namespace coop {
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-// Visits the neighbour list [beg, beg + d) of one destination with the whole wave, VEC entries per lane and step,
-// and calls emit(rank, t, j) for every kept neighbour t at list position j; rank counts kept neighbours in
-// adjacency order.  `all` keeps everything (d <= k).  Returns the number kept (same value in every lane).
+// Visits the neighbour list [beg, beg + d) of one destination with the whole wave and calls emit(rank, t, j) for
+// every kept neighbour t at list position j; rank counts kept neighbours in adjacency order.  `all` keeps
+// everything (d <= k).  Returns the number kept (same value in every lane).
+//
+// VEC == 4: the list is read as 16-byte aligned groups of four entries, two groups per lane and step (2 KiB per
+// wave and step), with the next step's groups requested before the current ones are hashed.  Positions are kept
+// relative to the first aligned group, so one unsigned compare tells whether an entry belongs to the list.
 template <bool BLEND, int VEC, typename Emit>
 __device__ __forceinline__ uint32_t labor_scan_list(const int32_t* __restrict__ g_indices, int64_t n_edges_total, int64_t beg,
-                                                    int64_t d, bool all, uint32_t thr, const VariateParams& vp, Emit emit) {
+                                                    int64_t d64, bool all, uint32_t thr, const VariateParams& vp, Emit emit) {
   const int lane = lane_id();
-  const int64_t end = beg + d;
+  const uint32_t d = (uint32_t)d64;
   uint32_t count = 0;
-  if constexpr (VEC == 4) {
-    for (int64_t base = beg & ~(int64_t)3; base < end; base += kWave * 4) {
-      const int64_t q = base + (int64_t)lane * 4;  // multiple of 4: a 16-byte aligned group of the indices array
-      i32x4 v = {0, 0, 0, 0};
-      if (q < end) {
-        if (q + 3 < n_edges_total) {
-          v = *reinterpret_cast<const i32x4*>(g_indices + q);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (q + e < n_edges_total) v[e] = g_indices[q + e];
-        }
-      }
-      bool keep[4];
-      uint64_t m[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int64_t pos = q + e;
-        bool kp = pos >= beg && pos < end;
-        if (kp && !all) kp = variate<false, BLEND>(vp, (uint32_t)v[e], 0u, 0u) <= thr;
-        keep[e] = kp;
-        m[e] = ballot64(kp);
-      }
-      uint32_t rank = count + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (keep[e]) {
-          emit(rank, v[e], (uint32_t)(q + e - beg));
-          ++rank;
-        }
-      }
-      count += (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
-    }
-  } else {
-    for (int64_t base = 0; base < d; base += kWave) {
-      const int64_t j = base + lane;
+  if (all || VEC == 1) {
+    for (uint32_t base = 0; base < d; base += kWave) {
+      const uint32_t j = base + lane;
       bool kp = j < d;
       int32_t t = 0;
       if (kp) {
@@ -72,8 +43,68 @@ __device__ __forceinline__ uint32_t labor_scan_list(const int32_t* __restrict__ 
         if (!all) kp = variate<false, BLEND>(vp, (uint32_t)t, 0u, 0u) <= thr;
       }
       const uint64_t m = ballot64(kp);
-      if (kp) emit(count + lanes_below(m), t, (uint32_t)j);
+      if (kp) emit(count + lanes_below(m), t, j);
       count += (uint32_t)__popcll(m);
+    }
+    return count;
+  }
+  constexpr int kGroups = 2;                    // 16-byte groups per lane and step
+  constexpr uint32_t kStep = kWave * 4 * kGroups;
+  const int64_t abeg = beg & ~(int64_t)3;       // first aligned group
+  const uint32_t head = (uint32_t)(beg - abeg); // entries of that group that precede the list
+  const uint32_t total = head + d;              // list end, relative to abeg
+  const int32_t* __restrict__ p = g_indices + abeg;
+  // entries readable from p without leaving the array (the last group of the whole array may be partial)
+  const int64_t avail = n_edges_total - abeg;
+
+  auto load_group = [&](uint32_t r) -> i32x4 {  // r: relative index of the group's first entry, multiple of 4
+    i32x4 v = {0, 0, 0, 0};
+    if (r < total) {
+      if ((int64_t)r + 3 < avail) {
+        v = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if ((int64_t)r + e < avail) v[e] = p[r + e];
+      }
+    }
+    return v;
+  };
+
+  i32x4 nxt[kGroups];
+#pragma unroll
+  for (int gq = 0; gq < kGroups; ++gq) nxt[gq] = load_group((uint32_t)(gq * kWave * 4 + lane * 4));
+  for (uint32_t base = 0; base < total; base += kStep) {
+    i32x4 cur[kGroups];
+#pragma unroll
+    for (int gq = 0; gq < kGroups; ++gq) cur[gq] = nxt[gq];
+    if (base + kStep < total) {
+#pragma unroll
+      for (int gq = 0; gq < kGroups; ++gq) nxt[gq] = load_group(base + kStep + (uint32_t)(gq * kWave * 4 + lane * 4));
+    }
+#pragma unroll
+    for (int gq = 0; gq < kGroups; ++gq) {
+      const uint32_t r = base + (uint32_t)(gq * kWave * 4 + lane * 4);
+      bool keep[4];
+      uint64_t m[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t j = r + e - head;  // position in the list; wraps to a huge value in front of the list
+        const uint32_t R = variate<false, BLEND>(vp, (uint32_t)cur[gq][e], 0u, 0u);
+        keep[e] = (j < d) & (R <= thr);
+        m[e] = ballot64(keep[e]);
+      }
+      if ((m[0] | m[1] | m[2] | m[3]) != 0) {
+        uint32_t rank = count + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (keep[e]) {
+            emit(rank, cur[gq][e], r + e - head);
+            ++rank;
+          }
+        }
+        count += (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
+      }
     }
   }
   return count;
