@@ -138,6 +138,44 @@ int coop_gather(const void* feat, int64_t n_rows, int32_t dim, int dtype, const 
  * id outside [0, n_rows) (such rows of `out` are left zero-filled), else COOP_OK.  Clears the condition. */
 int coop_gather_status(void* stream);
 
+/*
+ * LRU vertex cache on the GPU in front of a feature table that the device can read but that is slow to read
+ * (pinned host memory over the host link; Sec. 4.2 measures this cache's miss rate as kappa grows).
+ *
+ * Semantics: a textbook LRU fed, per call, first the ids that are cached when the call starts, then the ids
+ * that are not, each in list order.  Hits are served from the cache and become most recent; misses are read
+ * from `table`; after the call the cache holds the `capacity_rows` most recently touched vertices.
+ *
+ * coop_cache_create: all device memory (slot map int32[n_vertices], capacity_rows rows, stamps, and scratch for
+ * up to max_ids ids per call) comes from the allocator once; later calls allocate nothing.
+ * Synchronises `stream`.
+ */
+int coop_cache_create(int64_t capacity_rows, int64_t n_vertices, int32_t dim, int dtype, int64_t max_ids,
+                      coop_alloc_fn alloc, void* alloc_ctx, void* stream, coop_cache** out);
+int coop_cache_free(coop_cache* c);
+
+/*
+ * out[i, :] = table[ids[i], :] through the cache.
+ *   table      [n_vertices, dim] rows of the dtype given at creation: device memory, or pinned host memory
+ *              mapped into the device address space (read by the kernels directly, no staging copy)
+ *   ids        device int32 [n_ids], DISTINCT, each in [0, n_vertices) (else COOP_E_RANGE); n_ids <= max_ids
+ *              (else COOP_E_CAPACITY)
+ *   out        device [n_ids, dim]
+ *   n_miss_out host, number of ids that were not cached when the call started (may be NULL)
+ * Synchronises `stream`.  Calls on one cache must not overlap.  After COOP_E_RANGE the in-range cached ids of the
+ * call count as touched and nothing was inserted; `out` is then unspecified.
+ */
+int coop_cache_gather(coop_cache* c, const void* table, const int32_t* ids, int64_t n_ids, void* out,
+                      int64_t* n_miss_out, void* stream);
+
+/* Device-side address of pinned (page-locked, mapped) host memory, for use as `table` / `feat` above.
+ * COOP_E_ARG if `host` is not such memory: nothing is ever dereferenced that the device cannot read. */
+int coop_map_host_pointer(const void* host, void** device_out);
+
+/* Device pointer to the cache's slot table (vertex id per slot, -1 = empty, int32 [capacity_rows]) and the
+ * number of cached vertices; valid until coop_cache_free.  For inspection and tests. */
+int coop_cache_vertices(const coop_cache* c, const int32_t** vertex_of_out, int64_t* size_out);
+
 /* Name of an error code (static string). */
 const char* coop_strerror(int code);
 

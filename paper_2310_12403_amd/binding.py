@@ -54,6 +54,16 @@ def lib():
     L.coop_gather.restype = C.c_int
     L.coop_gather_status.argtypes = [C.c_void_p]
     L.coop_gather_status.restype = C.c_int
+    L.coop_cache_create.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.POINTER(C.c_void_p)]
+    L.coop_cache_create.restype = C.c_int
+    L.coop_cache_free.argtypes = [C.c_void_p]
+    L.coop_cache_gather.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]
+    L.coop_cache_gather.restype = C.c_int
+    L.coop_cache_vertices.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
+    L.coop_cache_vertices.restype = C.c_int
+    L.coop_map_host_pointer.argtypes = [C.c_void_p, C.POINTER(C.c_void_p)]
+    L.coop_map_host_pointer.restype = C.c_int
     L.coop_tune.argtypes = [C.c_int, C.c_int64]
     L.coop_tune.restype = C.c_int
     L.coop_profile_enable.argtypes = [C.c_int]
@@ -229,6 +239,69 @@ def coop_gather(feat, ids, out=None, stream=None):
 
 def coop_gather_status(stream=None):
     _check(lib().coop_gather_status(_stream_ptr(stream)))
+
+
+def coop_map_host_pointer(t):
+    """Device-side address of a pinned host tensor (raises CoopError if the memory is not mapped)."""
+    d = C.c_void_p()
+    _check(lib().coop_map_host_pointer(C.c_void_p(t.data_ptr()), C.byref(d)))
+    return d.value
+
+
+class Cache:
+    """LRU vertex cache (coop_cache_*).  The backing table may be a cuda tensor or a pinned host tensor."""
+
+    def __init__(self, capacity_rows, n_vertices, dim, dtype, max_ids, device="cuda", stream=None):
+        self._alloc = _TorchAllocator(torch.device(device))
+        self.capacity, self.n_vertices, self.dim, self.dtype, self.max_ids = capacity_rows, n_vertices, dim, dtype, max_ids
+        h = C.c_void_p()
+        rc = lib().coop_cache_create(capacity_rows, n_vertices, dim, _DTYPES[dtype], max_ids, self._alloc.fn, self._alloc.ctx,
+                                     _stream_ptr(stream), C.byref(h))
+        if rc != 0 and self._alloc.error is not None:
+            raise self._alloc.error
+        _check(rc)
+        self.handle = h
+        self._tables = {}
+
+    def _table_ptr(self, table):
+        assert table.dim() == 2 and table.is_contiguous() and table.dtype == self.dtype and table.shape[1] == self.dim
+        if table.is_cuda:
+            return table.data_ptr()
+        key = table.data_ptr()
+        if key not in self._tables:
+            assert table.is_pinned(), "a host feature table must be pinned (page-locked)"
+            self._tables[key] = coop_map_host_pointer(table)
+        return self._tables[key]
+
+    def gather(self, table, ids, out=None, stream=None):
+        """Returns (out, n_miss)."""
+        if out is None:
+            out = torch.empty((ids.numel(), self.dim), dtype=self.dtype, device=ids.device)
+        n_miss = C.c_int64()
+        rc = lib().coop_cache_gather(self.handle, C.c_void_p(self._table_ptr(table)), _dev_ptr(ids, torch.int32), ids.numel(),
+                                     C.c_void_p(out.data_ptr()), C.byref(n_miss), _stream_ptr(stream))
+        _check(rc)
+        return out, n_miss.value
+
+    def vertices(self):
+        """Sorted tensor of the vertex ids currently cached."""
+        p, n = C.c_void_p(), C.c_int64()
+        _check(lib().coop_cache_vertices(self.handle, C.byref(p), C.byref(n)))
+        v = self._alloc.view(p.value, self.capacity, torch.int32)
+        v = v[v >= 0]
+        assert v.numel() == n.value
+        return torch.sort(v).values
+
+    def close(self):
+        if self.handle:
+            lib().coop_cache_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 COOP_TUNE_STAGE_CAP = 1

@@ -1,0 +1,428 @@
+// On-GPU LRU vertex cache in front of a feature table that lives in pinned host memory (or anywhere the device can
+// read): the cached variant of Algorithm 1's feature-loading step (Sec. 4.2 measures its miss rate under kappa).
+//
+// Semantics (exact): a textbook LRU fed, per batch of distinct ids, first the ids that are cached when the batch
+// starts, then the ids that are not, each group in batch order.  Equivalently: every access gets a stamp from a
+// global counter (hits first, then misses); after the batch the cache holds the `capacity` entries with the largest
+// stamps.  So, with H hits and M misses and `size` entries before the batch,
+//     inserted misses  = the last min(M, capacity) misses,
+//     evicted entries  = the E = max(0, size + min(M, capacity) - capacity) smallest stamps among current entries
+//                        (hits were just re-stamped, so they go last).
+// The E-th smallest stamp is found exactly by a most-significant-digit radix select over the stamp array (12 bits
+// per pass; all live stamps lie in [previous eviction threshold, clock), so two or three passes are typical).
+//
+// Data layout: slot_of[n_vertices] (int32, -1 = not cached), vertex_of[capacity], stamp[capacity] (0 = free),
+// rows[capacity][row_bytes], free_list[capacity] (stack of free slots).  Which free slot a miss lands in is
+// unspecified; contents, stamps and outputs are deterministic.
+#include <new>
+
+#include "coop_internal.h"
+#include "device_utils.h"
+
+namespace coop {
+
+constexpr int kSelBits = 12;
+constexpr int kSelBins = 1 << kSelBits;
+constexpr int kRowUnroll = 2;
+
+struct CacheCtl {
+  uint64_t prefix;     // radix select: digits chosen so far; after the last pass, the E-th smallest (stamp - base)
+  uint64_t remaining;  // radix select: rank still to be located inside the current prefix
+  int64_t n_hit;
+  int32_t n_push;      // slots pushed on the free list by the current eviction
+  int32_t err_range;
+};
+
+// ---- lookup ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_cache_lookup(const int32_t* __restrict__ ids, int64_t n_ids, int64_t n_vertices,
+                                                         const int32_t* __restrict__ slot_of, int32_t* __restrict__ slot_i,
+                                                         uint64_t* __restrict__ hit_bits, CacheCtl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  bool hit = false;
+  if (i < n_ids) {
+    const int32_t v = ids[i];
+    int32_t slot = -1;
+    if ((uint64_t)(uint32_t)v < (uint64_t)n_vertices) slot = slot_of[v];
+    else atomicOr(&ctl->err_range, 1);
+    slot_i[i] = slot;
+    hit = slot >= 0;
+  }
+  const uint64_t b = ballot64(hit);
+  if (lane_id() == 0 && (i & ~(int64_t)63) < n_ids) hit_bits[i >> 6] = b;
+}
+
+// ---- row movers -----------------------------------------------------------------------------------------------
+// Rows are moved by lpr = 2^lpr_log2 adjacent lanes, V-sized vectors, kRowUnroll rows per thread in flight.
+template <typename V>
+__global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ rows, int32_t vecs, int lpr_log2,
+                                                       const int32_t* __restrict__ slot_i, const uint32_t* __restrict__ rank_h,
+                                                       int64_t n_ids, V* __restrict__ out, uint64_t* __restrict__ stamp,
+                                                       uint64_t clock) {
+  const int lpr = 1 << lpr_log2;
+  const int rows_per_block = kBlock >> lpr_log2;
+  const int sub = threadIdx.x & (lpr - 1);
+  const int64_t row0 = ((int64_t)blockIdx.x * kRowUnroll) * rows_per_block + (threadIdx.x >> lpr_log2);
+  int64_t src[kRowUnroll];
+#pragma unroll
+  for (int u = 0; u < kRowUnroll; ++u) {
+    const int64_t r = row0 + (int64_t)u * rows_per_block;
+    src[u] = -1;
+    if (r < n_ids) {
+      const int32_t slot = slot_i[r];
+      if (slot >= 0) {
+        src[u] = slot;
+        if (sub == 0) stamp[slot] = clock + rank_h[r];
+      }
+    }
+  }
+  for (int32_t v = sub; v < vecs; v += lpr) {
+    V x[kRowUnroll];
+#pragma unroll
+    for (int u = 0; u < kRowUnroll; ++u)
+      if (src[u] >= 0) x[u] = rows[src[u] * vecs + v];
+#pragma unroll
+    for (int u = 0; u < kRowUnroll; ++u) {
+      const int64_t r = row0 + (int64_t)u * rows_per_block;
+      if (src[u] >= 0) __builtin_nontemporal_store(x[u], out + r * vecs + v);
+    }
+  }
+}
+
+template <typename V>
+__global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ table, int32_t vecs, int lpr_log2,
+                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ slot_i,
+                                                         const uint32_t* __restrict__ rank_h, int64_t n_ids, V* __restrict__ out,
+                                                         V* __restrict__ rows, int32_t* __restrict__ slot_of,
+                                                         int32_t* __restrict__ vertex_of, uint64_t* __restrict__ stamp,
+                                                         const int32_t* __restrict__ free_list, int64_t n_free, int64_t n_miss,
+                                                         int64_t n_ins, uint64_t clock_miss) {
+  const int lpr = 1 << lpr_log2;
+  const int rows_per_block = kBlock >> lpr_log2;
+  const int sub = threadIdx.x & (lpr - 1);
+  const int64_t row0 = ((int64_t)blockIdx.x * kRowUnroll) * rows_per_block + (threadIdx.x >> lpr_log2);
+  int64_t src[kRowUnroll], dst_slot[kRowUnroll];
+#pragma unroll
+  for (int u = 0; u < kRowUnroll; ++u) {
+    const int64_t r = row0 + (int64_t)u * rows_per_block;
+    src[u] = -1;
+    dst_slot[u] = -1;
+    if (r < n_ids && slot_i[r] < 0) {
+      const int32_t id = ids[r];
+      if (id >= 0) {  // ids out of range were reported by the lookup; negative ones are skipped here
+        src[u] = id;
+        const int64_t rank_m = r - (int64_t)rank_h[r];
+        const int64_t q = rank_m - (n_miss - n_ins);  // the last n_ins misses enter the cache
+        if (q >= 0) {
+          const int32_t slot = free_list[n_free - 1 - q];
+          dst_slot[u] = slot;
+          if (sub == 0) {
+            slot_of[id] = slot;
+            vertex_of[slot] = id;
+            stamp[slot] = clock_miss + (uint64_t)rank_m;
+          }
+        }
+      }
+    }
+  }
+  for (int32_t v = sub; v < vecs; v += lpr) {
+    V x[kRowUnroll];
+#pragma unroll
+    for (int u = 0; u < kRowUnroll; ++u)
+      if (src[u] >= 0) x[u] = __builtin_nontemporal_load(table + src[u] * vecs + v);
+#pragma unroll
+    for (int u = 0; u < kRowUnroll; ++u) {
+      const int64_t r = row0 + (int64_t)u * rows_per_block;
+      if (src[u] >= 0) {
+        __builtin_nontemporal_store(x[u], out + r * vecs + v);
+        if (dst_slot[u] >= 0) rows[dst_slot[u] * vecs + v] = x[u];
+      }
+    }
+  }
+}
+
+// ---- eviction: radix select of the E-th smallest stamp, then sweep -----------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_cache_sel_hist(const uint64_t* __restrict__ stamp, int64_t capacity, uint64_t base,
+                                                           int shift, int prev_shift, const CacheCtl* __restrict__ ctl,
+                                                           uint32_t* __restrict__ hist) {
+  __shared__ uint32_t lh[kSelBins];
+  for (int b = threadIdx.x; b < kSelBins; b += kBlock) lh[b] = 0;
+  __syncthreads();
+  const uint64_t prefix = ctl->prefix;
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (; i < capacity; i += stride) {
+    const uint64_t st = stamp[i];
+    if (st == 0) continue;
+    const uint64_t x = st - base;
+    if (prev_shift >= 0 && (x >> prev_shift) != prefix) continue;
+    atomicAdd(&lh[(x >> shift) & (kSelBins - 1)], 1u);
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < kSelBins; b += kBlock) {
+    const uint32_t c = lh[b];
+    if (c) atomicAdd(&hist[b], c);
+  }
+}
+
+// one block: the bin that holds the `remaining`-th entry; extends the prefix, clears the histogram
+__global__ __launch_bounds__(kBlock) void k_cache_sel_pick(uint32_t* __restrict__ hist, CacheCtl* ctl) {
+  __shared__ uint64_t part[kBlock];
+  constexpr int per = kSelBins / kBlock;  // 16 consecutive bins per thread
+  uint64_t s = 0;
+  for (int j = 0; j < per; ++j) s += hist[threadIdx.x * per + j];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint64_t remaining = ctl->remaining, cum = 0;
+    int t = 0;
+    while (t < kBlock - 1 && cum + part[t] < remaining) { cum += part[t]; ++t; }
+    int b = t * per;
+    while (b < t * per + per - 1 && cum + hist[b] < remaining) { cum += hist[b]; ++b; }
+    ctl->prefix = (ctl->prefix << kSelBits) | (uint64_t)b;
+    ctl->remaining = remaining - cum;
+  }
+  __syncthreads();
+  for (int j = 0; j < per; ++j) hist[threadIdx.x * per + j] = 0;
+}
+
+// evicts every entry with stamp - base <= threshold (or every entry, if evict_all)
+__global__ __launch_bounds__(kBlock) void k_cache_evict(uint64_t* __restrict__ stamp, int32_t* __restrict__ vertex_of,
+                                                        int32_t* __restrict__ slot_of, int32_t* __restrict__ free_list,
+                                                        int64_t capacity, uint64_t base, bool evict_all, int64_t n_free,
+                                                        CacheCtl* ctl) {
+  const uint64_t thr = ctl->prefix;
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (; i < capacity; i += stride) {
+    const uint64_t st = stamp[i];
+    if (st == 0) continue;
+    if (evict_all || st - base <= thr) {
+      const int32_t v = vertex_of[i];
+      slot_of[v] = -1;
+      vertex_of[i] = -1;
+      stamp[i] = 0;
+      const int32_t p = atomicAdd(&ctl->n_push, 1);
+      if (n_free + p < capacity) free_list[n_free + p] = (int32_t)i;  // always true: exactly n_evict entries qualify
+    }
+  }
+}
+
+__global__ void k_cache_ctl_set(CacheCtl* ctl, uint64_t remaining) {
+  ctl->prefix = 0; ctl->remaining = remaining; ctl->n_push = 0;
+}
+
+__global__ void k_cache_clear_err(CacheCtl* ctl) { ctl->err_range = 0; }
+
+__global__ __launch_bounds__(kBlock) void k_fill_i32(int32_t* __restrict__ p, int64_t n, int32_t v, bool iota) {
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (; i < n; i += stride) p[i] = iota ? (int32_t)i : v;
+}
+
+}  // namespace coop
+
+using namespace coop;
+
+struct coop_cache {
+  int64_t capacity, n_vertices, max_ids, row_bytes;
+  int vec_bytes;          // 16 / 8 / 4 / 2: widest vector that divides the row and the buffers' alignment
+  int32_t* slot_of;
+  int32_t* vertex_of;
+  uint64_t* stamp;
+  void* rows;
+  int32_t* free_list;
+  // per-call scratch, sized for max_ids
+  int32_t* slot_i;
+  uint64_t* hit_bits;
+  uint32_t* rank_h;
+  void* scan_tmp;
+  uint32_t* hist;
+  CacheCtl* d_ctl;
+  CacheCtl* h_ctl;        // pinned
+  // host-side state
+  int64_t size;           // entries held
+  uint64_t clock;         // next stamp
+  uint64_t base;          // every live stamp is >= base (last eviction threshold + 1)
+};
+
+static unsigned grid_for(int64_t n) {
+  int64_t b = (n + kBlock - 1) / kBlock;
+  if (b > 256 * 32) b = 256 * 32;
+  return (unsigned)(b > 0 ? b : 1);
+}
+
+extern "C" int coop_cache_create(int64_t capacity_rows, int64_t n_vertices, int32_t dim, int dtype, int64_t max_ids,
+                                 coop_alloc_fn alloc_fn, void* alloc_ctx, void* stream, coop_cache** out) {
+  if (!out) return COOP_E_NULL;
+  *out = nullptr;
+  if (!alloc_fn) return COOP_E_NULL;
+  if (dtype != COOP_F32 && dtype != COOP_F16) return COOP_E_ARG;
+  if (capacity_rows < 0 || capacity_rows >= ((int64_t)1 << 31) || n_vertices < 0 || n_vertices >= ((int64_t)1 << 31) ||
+      dim < 1 || max_ids < 0 || max_ids >= ((int64_t)1 << 31))
+    return COOP_E_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  coop_cache* c = new (std::nothrow) coop_cache{};
+  if (!c) return COOP_E_NOMEM;
+  c->capacity = capacity_rows; c->n_vertices = n_vertices; c->max_ids = max_ids;
+  c->row_bytes = (int64_t)dim * (dtype == COOP_F32 ? 4 : 2);
+  Alloc alloc{alloc_fn, alloc_ctx};
+  c->slot_of = alloc.get<int32_t>(n_vertices, COOP_TAG_OUTPUT);
+  c->vertex_of = alloc.get<int32_t>(capacity_rows, COOP_TAG_OUTPUT);
+  c->stamp = alloc.get<uint64_t>(capacity_rows, COOP_TAG_OUTPUT);
+  c->rows = alloc.get<char>(capacity_rows * c->row_bytes, COOP_TAG_OUTPUT);
+  c->free_list = alloc.get<int32_t>(capacity_rows, COOP_TAG_OUTPUT);
+  c->slot_i = alloc.get<int32_t>(max_ids, COOP_TAG_OUTPUT);
+  c->hit_bits = alloc.get<uint64_t>((max_ids + 63) / 64, COOP_TAG_OUTPUT);
+  c->rank_h = alloc.get<uint32_t>(max_ids, COOP_TAG_OUTPUT);
+  c->scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(max_ids), COOP_TAG_OUTPUT);
+  c->hist = alloc.get<uint32_t>(kSelBins, COOP_TAG_OUTPUT);
+  c->d_ctl = alloc.get<CacheCtl>(1, COOP_TAG_OUTPUT);
+  if (alloc.failed) { delete c; return COOP_E_NOMEM; }
+  if (hipHostMalloc((void**)&c->h_ctl, sizeof(CacheCtl), hipHostMallocDefault) != hipSuccess) { delete c; return COOP_E_HIP; }
+  c->size = 0; c->clock = 1; c->base = 1;
+  if (n_vertices > 0) COOP_LAUNCH(K_FILL, k_fill_i32, dim3(grid_for(n_vertices)), dim3(kBlock), 0, s, c->slot_of, n_vertices, -1, false);
+  if (capacity_rows > 0) {
+    COOP_LAUNCH(K_FILL, k_fill_i32, dim3(grid_for(capacity_rows)), dim3(kBlock), 0, s, c->vertex_of, capacity_rows, -1, false);
+    COOP_LAUNCH(K_FILL, k_fill_i32, dim3(grid_for(capacity_rows)), dim3(kBlock), 0, s, c->free_list, capacity_rows, 0, true);
+    fill_u64(c->stamp, capacity_rows, 0, s);
+  }
+  fill_u64((uint64_t*)c->hist, kSelBins / 2, 0, s);
+  COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)0);
+  COOP_LAUNCH(K_FILL, k_cache_clear_err, dim3(1), dim3(1), 0, s, c->d_ctl);
+  if (hipStreamSynchronize(s) != hipSuccess) { (void)hipHostFree(c->h_ctl); delete c; return COOP_E_HIP; }
+  *out = c;
+  return COOP_OK;
+}
+
+extern "C" int coop_cache_free(coop_cache* c) {
+  if (!c) return COOP_OK;
+  (void)hipHostFree(c->h_ctl);
+  delete c;
+  return COOP_OK;
+}
+
+extern "C" int coop_map_host_pointer(const void* host, void** device_out) {
+  if (!host || !device_out) return COOP_E_NULL;
+  void* d = nullptr;
+  if (hipHostGetDevicePointer(&d, const_cast<void*>(host), 0) != hipSuccess || !d) {
+    (void)hipGetLastError();
+    return COOP_E_ARG;
+  }
+  *device_out = d;
+  return COOP_OK;
+}
+
+extern "C" int coop_cache_vertices(const coop_cache* c, const int32_t** vertex_of_out, int64_t* size_out) {
+  if (!c) return COOP_E_NULL;
+  if (vertex_of_out) *vertex_of_out = c->vertex_of;
+  if (size_out) *size_out = c->size;
+  return COOP_OK;
+}
+
+namespace {
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename V>
+void launch_rows(coop_cache* c, const void* table, const int32_t* ids, int64_t n_ids, void* out, int64_t n_free, int64_t n_miss,
+                 int64_t n_ins, int64_t n_hit, bool hits, hipStream_t s) {
+  const int32_t vecs = (int32_t)(c->row_bytes / (int64_t)sizeof(V));
+  int lpr_log2 = 0;
+  while ((1 << lpr_log2) < vecs && lpr_log2 < 8) ++lpr_log2;
+  const int64_t rows_per_launch_block = (int64_t)(kBlock >> lpr_log2) * kRowUnroll;
+  const unsigned grid = (unsigned)((n_ids + rows_per_launch_block - 1) / rows_per_launch_block);
+  if (hits)
+    COOP_LAUNCH(K_CACHE_GATHER, k_cache_hits<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)c->rows, vecs, lpr_log2, c->slot_i,
+                c->rank_h, n_ids, (V*)out, c->stamp, c->clock);
+  else
+    COOP_LAUNCH(K_CACHE_UPDATE, k_cache_misses<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)table, vecs, lpr_log2, ids, c->slot_i,
+                c->rank_h, n_ids, (V*)out, (V*)c->rows, c->slot_of, c->vertex_of, c->stamp, c->free_list, n_free, n_miss, n_ins,
+                c->clock + (uint64_t)n_hit);
+}
+
+void dispatch_rows(coop_cache* c, int vec_bytes, const void* table, const int32_t* ids, int64_t n_ids, void* out, int64_t n_free,
+                   int64_t n_miss, int64_t n_ins, int64_t n_hit, bool hits, hipStream_t s) {
+  switch (vec_bytes) {
+    case 16: launch_rows<u32x4>(c, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
+    case 8: launch_rows<u32x2>(c, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
+    case 4: launch_rows<uint32_t>(c, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
+    default: launch_rows<uint16_t>(c, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
+  }
+}
+}  // namespace
+
+extern "C" int coop_cache_gather(coop_cache* c, const void* table, const int32_t* ids, int64_t n_ids, void* out,
+                                 int64_t* n_miss_out, void* stream) {
+  if (!c) return COOP_E_NULL;
+  if (n_ids < 0 || n_ids > c->max_ids) return COOP_E_CAPACITY;
+  if (n_miss_out) *n_miss_out = 0;
+  if (n_ids == 0) return COOP_OK;
+  if (!table || !ids || !out) return COOP_E_NULL;
+  hipStream_t s = (hipStream_t)stream;
+  const uintptr_t align = (uintptr_t)table | (uintptr_t)out | (uintptr_t)c->rows | (uintptr_t)c->row_bytes;
+  const int vec_bytes = align % 16 == 0 ? 16 : align % 8 == 0 ? 8 : align % 4 == 0 ? 4 : 2;
+  if (align % 2 != 0) return COOP_E_ARG;
+
+  // 1. lookup, hit ranks
+  COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)0);
+  COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_lookup, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, ids, n_ids,
+              c->n_vertices, c->slot_of, c->slot_i, c->hit_bits, c->d_ctl);
+  scan_bits_to_u32(c->hit_bits, n_ids, c->rank_h, &c->d_ctl->n_hit, c->scan_tmp, s);
+  COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
+  // 2. hits: rows out of the cache, new stamps (runs while the host waits for the counts)
+  dispatch_rows(c, vec_bytes, table, ids, n_ids, out, 0, 0, 0, 0, true, s);
+  COOP_HIP_TRY(hipStreamSynchronize(s));
+  if (c->h_ctl->err_range) {
+    // the cached ids of this call were already served and re-stamped: keep the stamps unique, insert nothing
+    COOP_LAUNCH(K_FILL, k_cache_clear_err, dim3(1), dim3(1), 0, s, c->d_ctl);
+    c->clock += (uint64_t)n_ids;
+    (void)hipStreamSynchronize(s);
+    return COOP_E_RANGE;
+  }
+  const int64_t n_hit = c->h_ctl->n_hit;
+  const int64_t n_miss = n_ids - n_hit;
+  const int64_t n_ins = n_miss < c->capacity ? n_miss : c->capacity;
+  int64_t n_evict = c->size + n_ins - c->capacity;
+  if (n_evict < 0) n_evict = 0;
+  int64_t n_free = c->capacity - c->size;
+
+  // 3. eviction
+  const uint64_t clock_after = c->clock + (uint64_t)n_ids;
+  bool threshold_known = false;
+  if (n_evict > 0) {
+    const bool evict_all = n_evict >= c->size;
+    if (!evict_all) {
+      uint64_t range = clock_after - c->base;  // live stamps minus base lie in [0, range)
+      int nbits = 1;
+      while (nbits < 64 && (range >> nbits) != 0) ++nbits;
+      const int passes = (nbits + kSelBits - 1) / kSelBits;
+      COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)n_evict);
+      int prev_shift = -1;
+      for (int p = passes - 1; p >= 0; --p) {
+        const int shift = p * kSelBits;
+        COOP_LAUNCH(K_CACHE_SELECT, k_cache_sel_hist, dim3(grid_for(c->capacity)), dim3(kBlock), 0, s, c->stamp, c->capacity, c->base,
+                    shift, prev_shift, c->d_ctl, c->hist);
+        COOP_LAUNCH(K_CACHE_SELECT, k_cache_sel_pick, dim3(1), dim3(kBlock), 0, s, c->hist, c->d_ctl);
+        prev_shift = shift;
+      }
+      threshold_known = true;
+    }
+    COOP_LAUNCH(K_CACHE_SELECT, k_cache_evict, dim3(grid_for(c->capacity)), dim3(kBlock), 0, s, c->stamp, c->vertex_of, c->slot_of,
+                c->free_list, c->capacity, c->base, evict_all, n_free, c->d_ctl);
+    n_free += n_evict;
+    c->size -= n_evict;
+  }
+
+  // 4. misses: rows from the backing table to `out`, the last n_ins of them also into free slots
+  if (n_miss > 0) dispatch_rows(c, vec_bytes, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, false, s);
+  c->size += n_ins;
+  c->clock = clock_after;
+
+  if (threshold_known) {
+    COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
+    COOP_HIP_TRY(hipStreamSynchronize(s));
+    c->base += c->h_ctl->prefix + 1;  // everything at or below the threshold is gone
+  }
+  if (n_miss_out) *n_miss_out = n_miss;
+  return COOP_OK;
+}

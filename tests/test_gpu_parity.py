@@ -205,3 +205,75 @@ def test_unaligned_indices_base(P, tiny):
     for x, w in zip(b, want):
         for n in NAMES:
             assert np.array_equal(getattr(x, n).cpu().numpy(), w[n])
+
+
+# --------------------------------------------------------------------------------------------------------------- #
+# LRU vertex cache (cached / pinned-host feature loading)
+# --------------------------------------------------------------------------------------------------------------- #
+def run_cache_sequence(P, cap, n, dim, dtype, batches, table_dev):
+    feat = synth.features(n, dim, dtype, seed=5, device="cpu")
+    table = feat.cuda() if table_dev == "cuda" else feat.pin_memory()
+    cache = P.Cache(cap, n, dim, dtype, max(len(b) for b in batches) + 7)
+    oracle = R.Cache(cap, n)
+    for it, ids in enumerate(batches):
+        ids_t = torch.from_numpy(ids).cuda()
+        out, n_miss = cache.gather(table, ids_t)
+        want_miss, _ = oracle.access(ids)
+        assert n_miss == want_miss, (it, n_miss, want_miss)
+        assert out.cpu().numpy().tobytes() == R.gather(feat.numpy(), ids).tobytes(), it
+        held = cache.vertices().cpu().numpy()
+        assert len(held) == oracle.size(), it
+        assert all(oracle.contains(int(v)) for v in held), it
+    cache.close()
+
+
+@pytest.mark.parametrize("cap", [0, 1, 50, 700, 5000])
+@pytest.mark.parametrize("table_dev", ["cuda", "pinned"])
+def test_cache_matches_textbook_lru(P, cap, table_dev):
+    n = 3000
+    rng = np.random.default_rng(cap + 1)
+    batches = [rng.choice(n, int(rng.integers(1, 900)), replace=False).astype(np.int32) for _ in range(25)]
+    batches.append(np.arange(n, dtype=np.int32))           # a batch larger than most capacities
+    batches += [rng.choice(n, 300, replace=False).astype(np.int32) for _ in range(5)]
+    run_cache_sequence(P, cap, n, 64, torch.float32, batches, table_dev)
+
+
+def test_cache_on_sampled_batches_with_kappa(P, medium):
+    """Input sets of consecutive dependent LABOR-0 batches through the cache: misses equal the oracle's on every
+    iteration, and a larger kappa lowers the miss count (temporal locality of Sec. 4.2)."""
+    get = synth.seed_batches(medium.n, 512, seed=9)
+    feat = synth.features(medium.n, 128, torch.float16, seed=3, device="cpu")
+    table = feat.pin_memory()
+    totals = {}
+    for kappa in (1, 16):
+        cache = P.Cache(8000, medium.n, 128, torch.float16, medium.n)
+        oracle = R.Cache(8000, medium.n)
+        miss = 0
+        for it in range(24):
+            blocks = P.coop_sample(medium.graph, get(it).cuda(), (10, 10), R.LABOR0, it=it, kappa=kappa, seed=1)
+            ids = blocks[-1].src_ids
+            out, n_miss = cache.gather(table, ids)
+            want, _ = oracle.access(ids.cpu().numpy())
+            assert n_miss == want
+            if it % 8 == 0:
+                assert out.cpu().numpy().tobytes() == R.gather(feat.numpy(), ids.cpu().numpy()).tobytes()
+            miss += n_miss
+        totals[kappa] = miss
+        cache.close()
+    assert totals[16] < totals[1]
+
+
+def test_cache_errors(P):
+    cache = P.Cache(10, 100, 8, torch.float32, 50)
+    table = synth.features(100, 8, torch.float32, seed=1).cuda()
+    with pytest.raises(P.CoopError) as e:
+        cache.gather(table, torch.arange(60, dtype=torch.int32).cuda())
+    assert e.value.code == -6
+    with pytest.raises(P.CoopError) as e:
+        cache.gather(table, torch.tensor([1, 100], dtype=torch.int32).cuda())
+    assert e.value.code == -2
+    out, n_miss = cache.gather(table, torch.tensor([5, 1], dtype=torch.int32).cuda())
+    assert n_miss == 2 and torch.equal(out, table[[5, 1]])      # the failed call inserted nothing
+    not_pinned = synth.features(100, 8, torch.float32, seed=1)
+    with pytest.raises((P.CoopError, AssertionError)):
+        cache.gather(not_pinned, torch.tensor([5], dtype=torch.int32).cuda())
