@@ -181,9 +181,11 @@ const char* coop_strerror(int code);
 
 /*
  * Tuning knobs (process-wide; for experiments and tests, results never depend on them).
- *   COOP_TUNE_STAGE_CAP  entries per LABOR-0 staging row (power of two, 1..4096; 0 = automatic)
+ *   COOP_TUNE_STAGE_CAP    entries per LABOR-0 staging row (power of two, 1..64; 0 = automatic)
+ *   COOP_TUNE_LISTS_PER_WAVE  see below
  */
 #define COOP_TUNE_STAGE_CAP 1
+#define COOP_TUNE_LISTS_PER_WAVE 2 /* neighbour lists handled by one wave of the LABOR-0 scan: 1..64, 0 = automatic */
 int coop_tune(int knob, int64_t value);
 
 /* Library ABI version (bumped when a signature in this file changes). */

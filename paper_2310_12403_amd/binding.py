@@ -305,6 +305,7 @@ class Cache:
 
 
 COOP_TUNE_STAGE_CAP = 1
+COOP_TUNE_LISTS_PER_WAVE = 2
 
 
 def coop_tune(knob, value):

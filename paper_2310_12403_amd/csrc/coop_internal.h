@@ -13,7 +13,7 @@ enum KernelId {
   K_LABOR_COUNT,     // LABOR-0 count pass
   K_LABOR_FILL,      // LABOR-0 fill pass (copy of the staged rows)
   K_LABOR_OVERFLOW,  // LABOR-0 second scan of overflowed rows
-  K_NS_COUNT,        // NS count pass (min(k, d))
+  K_SEGMENTS,        // per-destination list records (start, length, threshold; NS counts)
   K_NS_FILL,         // NS selection + fill pass
   K_SCAN_REDUCE,     // scan: per-block sums
   K_SCAN_SPINE,      // scan: scan of block sums

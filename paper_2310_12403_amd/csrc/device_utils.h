@@ -11,6 +11,8 @@ constexpr int kWavesPerBlock = kBlock / kWave;
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_in_block() { return threadIdx.x >> 6; }
+// the same value, but known to the compiler to be wave-uniform: addresses and loop bounds derived from it stay scalar
+__device__ __forceinline__ int uniform_wave_in_block() { return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); }
 
 // number of set bits of `mask` strictly below this lane
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {

@@ -23,7 +23,7 @@ struct Prof {
 } g_prof;
 
 const char* const kKernelNames[K_COUNT_] = {
-    "fill", "labor_count", "labor_fill", "labor_fill_overflow", "ns_count", "ns_fill", "scan_reduce", "scan_spine", "scan_apply",
+    "fill", "labor_count", "labor_fill", "labor_fill_overflow", "segments", "ns_fill", "scan_reduce", "scan_spine", "scan_apply",
     "unique_insert", "unique_flag", "unique_relabel", "copy_ids", "gather", "validate_csr",
     "cache_lookup", "cache_select", "cache_update", "cache_gather"};
 

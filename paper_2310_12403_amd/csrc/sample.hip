@@ -20,134 +20,182 @@ namespace coop {
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-// Visits the neighbour list [beg, beg + d) of one destination with the whole wave and calls emit(rank, t, j) for
-// every kept neighbour t at list position j; rank counts kept neighbours in adjacency order.  `all` keeps
-// everything (d <= k).  Returns the number kept (same value in every lane).
-//
-// VEC == 4: the list is read as 16-byte aligned groups of four entries, two groups per lane and step (2 KiB per
-// wave and step), with the next step's groups requested before the current ones are hashed.  Positions are kept
-// relative to the first aligned group, so one unsigned compare tells whether an entry belongs to the list.
-template <bool BLEND, int VEC, typename Emit>
-__device__ __forceinline__ uint32_t labor_scan_list(const int32_t* __restrict__ g_indices, int64_t n_edges_total, int64_t beg,
-                                                    int64_t d64, bool all, uint32_t thr, const VariateParams& vp, Emit emit) {
-  const int lane = lane_id();
-  const uint32_t d = (uint32_t)d64;
-  uint32_t count = 0;
-  if (all || VEC == 1) {
-    for (uint32_t base = 0; base < d; base += kWave) {
-      const uint32_t j = base + lane;
-      bool kp = j < d;
-      int32_t t = 0;
-      if (kp) {
-        t = g_indices[beg + j];
-        if (!all) kp = variate<false, BLEND>(vp, (uint32_t)t, 0u, 0u) <= thr;
-      }
-      const uint64_t m = ballot64(kp);
-      if (kp) emit(count + lanes_below(m), t, j);
-      count += (uint32_t)__popcll(m);
-    }
-    return count;
+// One destination's neighbour list as the scan kernels see it: where it starts, how long it is, and the LABOR-0
+// keep threshold floor(k 2^32 / d) (all ones when d <= k: everything is kept).  Built by k_segments, one coalesced
+// 16-byte record per destination, so that a wave can fetch the records of all its lists with one load.
+struct Segment { int64_t beg; uint32_t d; uint32_t thr; };
+
+struct StageEntry { int32_t t; uint32_t j; };  // kept source vertex, its position in the destination's list
+
+constexpr uint32_t kAllThr = 0xFFFFFFFFu;
+constexpr int kScanGroups = 4;  // 16-byte groups per lane and step of the fast scan (4 KiB per wave and step)
+
+__global__ __launch_bounds__(kBlock) void k_segments(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
+                                                     const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
+                                                     Segment* __restrict__ seg, int32_t* __restrict__ ns_cnt, Ctl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_dst) return;
+  const int32_t s = dst[i];
+  Segment g{0, 0, kAllThr};
+  if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
+    atomicOr(&ctl->err_range, 1);
+  } else {
+    g.beg = g_indptr[s];
+    g.d = (uint32_t)(g_indptr[s + 1] - g.beg);
+    if (g.d > k) g.thr = (uint32_t)(((uint64_t)k << 32) / (uint64_t)g.d);
   }
-  constexpr int kGroups = 2;                    // 16-byte groups per lane and step
-  constexpr uint32_t kStep = kWave * 4 * kGroups;
-  const int64_t abeg = beg & ~(int64_t)3;       // first aligned group
-  const uint32_t head = (uint32_t)(beg - abeg); // entries of that group that precede the list
-  const uint32_t total = head + d;              // list end, relative to abeg
-  const int32_t* __restrict__ p = g_indices + abeg;
-  // entries readable from p without leaving the array (the last group of the whole array may be partial)
-  const int64_t avail = n_edges_total - abeg;
+  seg[i] = g;
+  if (ns_cnt) ns_cnt[i] = (int32_t)(g.d < k ? g.d : k);  // NS: min(k, d) edges
+}
 
-  auto load_group = [&](uint32_t r) -> i32x4 {  // r: relative index of the group's first entry, multiple of 4
-    i32x4 v = {0, 0, 0, 0};
-    if (r < total) {
-      if ((int64_t)r + 3 < avail) {
-        v = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if ((int64_t)r + e < avail) v[e] = p[r + e];
-      }
+// Ordered visit of the neighbour list [beg, beg + d) of one destination by the whole wave, one entry per lane and
+// step: calls emit(rank, t, j) for every kept neighbour t at list position j, rank counting kept neighbours in
+// adjacency order.  `all` keeps everything (d <= k).  Returns the number kept (same value in every lane).
+// Used for short lists, for an indices array that is not 16-byte aligned, and for the overflow pass.
+template <bool BLEND, typename Emit>
+__device__ __forceinline__ uint32_t labor_scan_ordered(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, bool all,
+                                                       uint32_t thr, const VariateParams& vp, Emit emit) {
+  const int lane = lane_id();
+  uint32_t count = 0;
+  for (uint32_t base = 0; base < d; base += kWave) {
+    const uint32_t j = base + lane;
+    bool kp = j < d;
+    int32_t t = 0;
+    if (kp) {
+      t = g_indices[beg + j];
+      if (!all) kp = variate<false, BLEND>(vp, (uint32_t)t, 0u, 0u) <= thr;
     }
-    return v;
-  };
-
-  i32x4 nxt[kGroups];
-#pragma unroll
-  for (int gq = 0; gq < kGroups; ++gq) nxt[gq] = load_group((uint32_t)(gq * kWave * 4 + lane * 4));
-  for (uint32_t base = 0; base < total; base += kStep) {
-    i32x4 cur[kGroups];
-#pragma unroll
-    for (int gq = 0; gq < kGroups; ++gq) cur[gq] = nxt[gq];
-    if (base + kStep < total) {
-#pragma unroll
-      for (int gq = 0; gq < kGroups; ++gq) nxt[gq] = load_group(base + kStep + (uint32_t)(gq * kWave * 4 + lane * 4));
-    }
-#pragma unroll
-    for (int gq = 0; gq < kGroups; ++gq) {
-      const uint32_t r = base + (uint32_t)(gq * kWave * 4 + lane * 4);
-      bool keep[4];
-      uint64_t m[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t j = r + e - head;  // position in the list; wraps to a huge value in front of the list
-        const uint32_t R = variate<false, BLEND>(vp, (uint32_t)cur[gq][e], 0u, 0u);
-        keep[e] = (j < d) & (R <= thr);
-        m[e] = ballot64(keep[e]);
-      }
-      if ((m[0] | m[1] | m[2] | m[3]) != 0) {
-        uint32_t rank = count + lanes_below(m[0]) + lanes_below(m[1]) + lanes_below(m[2]) + lanes_below(m[3]);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (keep[e]) {
-            emit(rank, cur[gq][e], r + e - head);
-            ++rank;
-          }
-        }
-        count += (uint32_t)(__popcll(m[0]) + __popcll(m[1]) + __popcll(m[2]) + __popcll(m[3]));
-      }
-    }
+    const uint64_t m = ballot64(kp);
+    if (kp) emit(count + lanes_below(m), t, j);
+    count += (uint32_t)__popcll(m);
   }
   return count;
 }
 
-struct StageEntry { int32_t t; uint32_t j; };  // kept source vertex, its position in the destination's list
-
-// ---- LABOR-0 --------------------------------------------------------------------------------------------------
-template <bool BLEND, int VEC>
-__global__ __launch_bounds__(kBlock) void k_labor_count(const int64_t* __restrict__ g_indptr,
-                                                        const int32_t* __restrict__ g_indices, int64_t n_vertices,
-                                                        int64_t n_edges_total, const int32_t* __restrict__ dst, int64_t n_dst,
-                                                        uint32_t k, VariateParams vp, uint32_t stage_cap,
-                                                        StageEntry* __restrict__ stage, int32_t* __restrict__ cnt, Ctl* ctl) {
-  const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
-  if (w >= n_dst) return;
-  const int lane = lane_id();
-  const int32_t s = dst[w];
-  if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
-    if (lane == 0) { atomicOr(&ctl->err_range, 1); cnt[w] = 0; }
-    return;
-  }
-  const int64_t beg = g_indptr[s];
-  const int64_t d = g_indptr[s + 1] - beg;
-  const bool all = d <= (int64_t)k;
-  const uint32_t thr = all ? 0xFFFFFFFFu : (uint32_t)(((uint64_t)k << 32) / (uint64_t)d);
-  StageEntry* row = stage + (size_t)w * stage_cap;
-  const uint32_t c = labor_scan_list<BLEND, VEC>(g_indices, n_edges_total, beg, d, all, thr, vp,
-                                                 [&](uint32_t rank, int32_t t, uint32_t j) {
-                                                   if (rank < stage_cap) row[rank] = StageEntry{t, j};
-                                                 });
-  if (lane == 0) {
-    cnt[w] = (int32_t)c;
-    if (c > stage_cap) atomicAdd(&ctl->n_overflow, 1);
+// Fast scan of a long list.  The list is read as 16-byte aligned groups of four entries, kScanGroups groups per lane
+// and step (4 KiB per wave and step), all requested before the first is hashed.  Positions are relative to the first
+// aligned group; steps that lie wholly inside the list (all but the first and the last) need no bounds test.  Per
+// entry the hot loop is the mixer and one compare; one ballot per group tells whether any lane kept anything.  Only
+// then are the (few) kept entries picked off per-entry ballot masks by a wave-uniform loop and parked in lane
+// `count` of a register pair (ent_t, ent_j): up to 64 kept entries per list, in no particular order.
+template <bool CHECK, bool BLEND>
+__device__ __forceinline__ void labor_stage_step(const i32x4 (&cur)[kScanGroups], uint32_t base, uint32_t head, uint32_t d,
+                                                 uint32_t thr, const VariateParams& vp, int32_t& ent_t, int32_t& ent_j,
+                                                 uint32_t& count) {
+  const uint32_t lane = (uint32_t)lane_id();
+#pragma unroll
+  for (int gq = 0; gq < kScanGroups; ++gq) {
+    const uint32_t r0 = base + (uint32_t)(gq * kWave * 4);  // wave-uniform
+    bool f[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t R = variate<false, BLEND>(vp, (uint32_t)cur[gq][e], 0u, 0u);
+      f[e] = R <= thr;
+      if (CHECK) f[e] &= (r0 + lane * 4 + e - head) < d;  // position in the list; wraps to a huge value in front of it
+    }
+    if (ballot64(f[0] | f[1] | f[2] | f[3]) != 0) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        uint64_t mm = ballot64(f[e]);
+        while (mm != 0) {
+          const int src_lane = __builtin_ctzll(mm);
+          mm &= mm - 1;
+          const int32_t t = __builtin_amdgcn_readlane(cur[gq][e], src_lane);
+          const int32_t j = (int32_t)(r0 + (uint32_t)src_lane * 4 + e - head);
+          if (lane == (count & 63u)) { ent_t = t; ent_j = j; }
+          ++count;
+        }
+      }
+    }
   }
 }
 
-// copy of the staged rows into the block's edge arrays: one thread per (destination, row slot)
-__global__ __launch_bounds__(kBlock) void k_labor_fill_staged(const int64_t* __restrict__ g_indptr,
-                                                              const int32_t* __restrict__ dst, int64_t n_dst,
-                                                              int stage_cap_log2, const StageEntry* __restrict__ stage,
-                                                              const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
-                                                              int64_t* __restrict__ eid) {
+// returns the number kept; if it is at most min(stage_cap, 64) the kept entries are written to `row` in adjacency order
+template <bool BLEND>
+__device__ __forceinline__ uint32_t labor_scan_staged(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t thr,
+                                                      const VariateParams& vp, StageEntry* __restrict__ row, uint32_t stage_cap) {
+  constexpr uint32_t kStep = kWave * 4 * kScanGroups;
+  const int64_t abeg = beg & ~(int64_t)3;         // first aligned group
+  const uint32_t head = (uint32_t)(beg - abeg);   // entries of that group that precede the list
+  const uint32_t total = head + d;                // list end, relative to abeg
+  const uint32_t vec_end = total & ~3u;           // groups that start below this end inside the list
+  const int32_t* __restrict__ p = g_indices + abeg;
+  const uint32_t lane = (uint32_t)lane_id();
+  const uint32_t lane4 = lane * 4;
+  uint32_t count = 0;
+  int32_t ent_t = 0, ent_j = 0;
+
+  for (uint32_t base = 0; base < total; base += kStep) {
+    i32x4 buf[kScanGroups];
+#pragma unroll
+    for (int gq = 0; gq < kScanGroups; ++gq) {
+      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane4;
+      i32x4 v = {0, 0, 0, 0};
+      if (r < vec_end) {
+        v = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+      } else if (r < total) {  // the list's last, partial group: entry by entry, never past the list
+#pragma unroll
+        for (int e = 0; e < 3; ++e)
+          if (r + e < total) v[e] = p[r + e];
+      }
+      buf[gq] = v;
+    }
+    if (base >= head && base + kStep <= total) labor_stage_step<false, BLEND>(buf, base, head, d, thr, vp, ent_t, ent_j, count);
+    else labor_stage_step<true, BLEND>(buf, base, head, d, thr, vp, ent_t, ent_j, count);
+  }
+  // adjacency order: an entry's place is the number of kept entries in front of it in the list
+  if (count <= stage_cap && count <= (uint32_t)kWave) {
+    uint32_t rank = 0;
+    for (uint32_t q = 0; q < count; ++q) rank += (uint32_t)(__builtin_amdgcn_readlane(ent_j, (int)q) < ent_j);
+    if (lane < count) row[rank] = StageEntry{ent_t, (uint32_t)ent_j};
+  }
+  return count;
+}
+
+// ---- LABOR-0 --------------------------------------------------------------------------------------------------
+// Each wave takes `lists_per_wave` consecutive destinations: their segment records are fetched by one coalesced load
+// (lane i holds record i), so the pointer chase destination -> list start is paid once per wave, not once per list.
+template <bool BLEND, int VEC>
+__global__ __launch_bounds__(kBlock) void k_labor_count(const int32_t* __restrict__ g_indices, const Segment* __restrict__ seg,
+                                                        int64_t n_dst, int lists_per_wave, VariateParams vp, uint32_t stage_cap,
+                                                        StageEntry* __restrict__ stage, int32_t* __restrict__ cnt, Ctl* ctl) {
+  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + uniform_wave_in_block();
+  const int64_t first = wave * lists_per_wave;
+  if (first >= n_dst) return;
+  const int lane = lane_id();
+  const int64_t mine = first + lane;
+  const bool has = lane < lists_per_wave && mine < n_dst;
+  Segment g{0, 0, kAllThr};
+  if (has) g = seg[mine];
+  const uint32_t beg_lo = (uint32_t)g.beg, beg_hi = (uint32_t)((uint64_t)g.beg >> 32);
+  uint32_t my_count = 0;
+  const int n_lists = (int)(n_dst - first < lists_per_wave ? n_dst - first : lists_per_wave);
+  for (int i = 0; i < n_lists; ++i) {
+    const int64_t beg = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)beg_hi, i) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readlane((int)beg_lo, i));
+    const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)g.d, i);
+    const uint32_t thr = (uint32_t)__builtin_amdgcn_readlane((int)g.thr, i);
+    StageEntry* row = stage + (size_t)(first + i) * stage_cap;
+    uint32_t c;
+    if (VEC == 4 && thr != kAllThr && d > (uint32_t)kWave) {
+      c = labor_scan_staged<BLEND>(g_indices, beg, d, thr, vp, row, stage_cap);
+    } else {
+      c = labor_scan_ordered<BLEND>(g_indices, beg, d, thr == kAllThr, thr, vp, [&](uint32_t rank, int32_t t, uint32_t j) {
+        if (rank < stage_cap) row[rank] = StageEntry{t, j};
+      });
+    }
+    if (lane == i) my_count = c;
+  }
+  if (has) {
+    cnt[mine] = (int32_t)my_count;
+    if (my_count > stage_cap) atomicAdd(&ctl->n_overflow, 1);
+  }
+}
+
+// staged rows -> the block's edge arrays: one thread per (destination, row slot)
+__global__ __launch_bounds__(kBlock) void k_labor_fill_staged(const Segment* __restrict__ seg, int64_t n_dst, int stage_cap_log2,
+                                                              const StageEntry* __restrict__ stage, const int64_t* __restrict__ eptr,
+                                                              int32_t* __restrict__ col_global, int64_t* __restrict__ eid) {
   const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int64_t w = idx >> stage_cap_log2;
   if (w >= n_dst) return;
@@ -157,48 +205,27 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_staged(const int64_t* __r
   if (slot >= c || c > ((int64_t)1 << stage_cap_log2)) return;
   const StageEntry e = stage[idx];
   col_global[o + slot] = e.t;
-  eid[o + slot] = g_indptr[dst[w]] + e.j;
+  eid[o + slot] = seg[w].beg + e.j;
 }
 
-// second scan of the (rare) destinations whose staging row overflowed, writing straight to the edge arrays
-template <bool BLEND, int VEC>
-__global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int64_t* __restrict__ g_indptr,
-                                                                const int32_t* __restrict__ g_indices, int64_t n_edges_total,
-                                                                const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
-                                                                VariateParams vp, uint32_t stage_cap,
+// second, ordered scan of the (rare) destinations whose staging row overflowed, writing straight to the edge arrays
+template <bool BLEND>
+__global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int32_t* __restrict__ g_indices, const Segment* __restrict__ seg,
+                                                                int64_t n_dst, VariateParams vp, uint32_t stage_cap,
                                                                 const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
                                                                 int64_t* __restrict__ eid) {
-  const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + wave_in_block();
+  const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + uniform_wave_in_block();
   if (w >= n_dst) return;
   const int64_t o = eptr[w];
   if (eptr[w + 1] - o <= (int64_t)stage_cap) return;
-  const int32_t s = dst[w];
-  const int64_t beg = g_indptr[s];
-  const int64_t d = g_indptr[s + 1] - beg;
-  const bool all = d <= (int64_t)k;
-  const uint32_t thr = all ? 0xFFFFFFFFu : (uint32_t)(((uint64_t)k << 32) / (uint64_t)d);
-  labor_scan_list<BLEND, VEC>(g_indices, n_edges_total, beg, d, all, thr, vp, [&](uint32_t rank, int32_t t, uint32_t j) {
+  const Segment g = seg[w];
+  labor_scan_ordered<BLEND>(g_indices, g.beg, g.d, g.thr == kAllThr, g.thr, vp, [&](uint32_t rank, int32_t t, uint32_t j) {
     col_global[o + rank] = t;
-    eid[o + rank] = beg + j;
+    eid[o + rank] = g.beg + j;
   });
 }
 
 // ---- NS -------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
-                                                     const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
-                                                     int32_t* __restrict__ cnt, Ctl* ctl) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= n_dst) return;
-  const int32_t s = dst[i];
-  if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
-    atomicOr(&ctl->err_range, 1);
-    cnt[i] = 0;
-    return;
-  }
-  const int64_t d = g_indptr[s + 1] - g_indptr[s];
-  cnt[i] = (int32_t)(d < (int64_t)k ? d : (int64_t)k);
-}
-
 constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list can be subsampled
 
 // Selection of the k smallest (R, j) among d > k neighbours, one wave per destination:
@@ -325,6 +352,7 @@ static int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
 }
 
 int g_stage_cap_override = 0;  // COOP_TUNE_STAGE_CAP
+int g_lists_per_wave = 0;      // COOP_TUNE_LISTS_PER_WAVE (0 = automatic)
 
 }  // namespace coop
 
@@ -333,25 +361,17 @@ using namespace coop;
 extern "C" int coop_tune(int knob, int64_t value) {
   switch (knob) {
     case COOP_TUNE_STAGE_CAP:
-      if (value != 0 && (value < 1 || value > 4096 || (value & (value - 1)))) return COOP_E_ARG;
+      if (value != 0 && (value < 1 || value > kWave || (value & (value - 1)))) return COOP_E_ARG;
       g_stage_cap_override = (int)value;
+      return COOP_OK;
+    case COOP_TUNE_LISTS_PER_WAVE:
+      if (value < 0 || value > kWave) return COOP_E_ARG;
+      g_lists_per_wave = (int)value;
       return COOP_OK;
     default:
       return COOP_E_ARG;
   }
 }
-
-// dispatch on (BLEND, VEC)
-#define COOP_LABOR_DISPATCH(id, name, grid, ...)                                                                    \
-  do {                                                                                                              \
-    if (blend) {                                                                                                    \
-      if (vec4) COOP_LAUNCH(id, (name<true, 4>), grid, dim3(kBlock), 0, s, __VA_ARGS__);                            \
-      else COOP_LAUNCH(id, (name<true, 1>), grid, dim3(kBlock), 0, s, __VA_ARGS__);                                 \
-    } else {                                                                                                        \
-      if (vec4) COOP_LAUNCH(id, (name<false, 4>), grid, dim3(kBlock), 0, s, __VA_ARGS__);                           \
-      else COOP_LAUNCH(id, (name<false, 1>), grid, dim3(kBlock), 0, s, __VA_ARGS__);                                \
-    }                                                                                                               \
-  } while (0)
 
 extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
                            int sampler, uint64_t iter, uint32_t kappa, uint64_t seed, coop_alloc_fn alloc_fn,
@@ -405,14 +425,14 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
     int32_t* cnt = alloc.get<int32_t>(n_dst, COOP_TAG_SCRATCH);
     void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
 
-    // LABOR-0 staging rows: room for 2k + 16 kept edges (a row overflows with probability < 1e-8 at k = 10),
-    // between 32 and 256 entries, shrunk while the whole staging area would exceed 1 GiB
+    // LABOR-0 staging rows: room for 2k + 16 kept edges (a row overflows with probability < 1e-8 at k = 10), 32 or
+    // 64 entries (what one wave can hold in a register pair); a row that overflows is redone by the overflow pass
     uint32_t stage_cap = 32;
     int stage_cap_log2 = 5;
     StageEntry* stage = nullptr;
+    Segment* seg = alloc.get<Segment>(n_dst, COOP_TAG_SCRATCH);
     if (sampler == COOP_LABOR0) {
-      while (stage_cap < 2 * (uint64_t)k + 16 && stage_cap < 256) { stage_cap <<= 1; ++stage_cap_log2; }
-      while (stage_cap > 32 && (uint64_t)n_dst * stage_cap * sizeof(StageEntry) > ((uint64_t)1 << 30)) { stage_cap >>= 1; --stage_cap_log2; }
+      if (2 * (uint64_t)k + 16 > 32) { stage_cap = 64; stage_cap_log2 = 6; }
       if (g_stage_cap_override) {
         stage_cap = (uint32_t)g_stage_cap_override;
         stage_cap_log2 = 0;
@@ -422,15 +442,27 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
     }
     if (alloc.failed) { rc = COOP_E_NOMEM; break; }
 
-    // neighbour scan / count pass
+    // list records (and, for NS, the counts min(k, d)); then the LABOR-0 neighbour scan
     if (n_dst > 0) {
+      COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, g->indptr, g->n_vertices, dst, n_dst, k,
+                  seg, sampler == COOP_NS ? cnt : nullptr, d_ctl);
       if (sampler == COOP_LABOR0) {
-        const dim3 grid(blocks_for(n_dst, kWavesPerBlock));
-        COOP_LABOR_DISPATCH(K_LABOR_COUNT, k_labor_count, grid, g->indptr, g->indices, g->n_vertices, g->n_edges, dst, n_dst, k,
-                            vp, stage_cap, stage, cnt, d_ctl);
-      } else {
-        COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, g->indptr, g->n_vertices, dst,
-                    n_dst, k, cnt, d_ctl);
+        // lists per wave: one measured as good as several on the papers100M-shaped graph (the knob stays for tuning)
+        int lpw = g_lists_per_wave;
+        if (lpw == 0) {
+          lpw = 1;
+        }
+        const int64_t n_waves = (n_dst + lpw - 1) / lpw;
+        const dim3 grid(blocks_for(n_waves, kWavesPerBlock));
+#define COOP_COUNT_ARGS g->indices, seg, n_dst, lpw, vp, stage_cap, stage, cnt, d_ctl
+        if (blend) {
+          if (vec4) COOP_LAUNCH(K_LABOR_COUNT, (k_labor_count<true, 4>), grid, dim3(kBlock), 0, s, COOP_COUNT_ARGS);
+          else COOP_LAUNCH(K_LABOR_COUNT, (k_labor_count<true, 1>), grid, dim3(kBlock), 0, s, COOP_COUNT_ARGS);
+        } else {
+          if (vec4) COOP_LAUNCH(K_LABOR_COUNT, (k_labor_count<false, 4>), grid, dim3(kBlock), 0, s, COOP_COUNT_ARGS);
+          else COOP_LAUNCH(K_LABOR_COUNT, (k_labor_count<false, 1>), grid, dim3(kBlock), 0, s, COOP_COUNT_ARGS);
+        }
+#undef COOP_COUNT_ARGS
       }
     }
     scan_i32_to_i64(cnt, n_dst, blk.indptr, scan_tmp, s);
@@ -448,12 +480,16 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
     // fill pass
     if (m > 0) {
       if (sampler == COOP_LABOR0) {
-        COOP_LAUNCH(K_LABOR_FILL, k_labor_fill_staged, dim3(blocks_for(n_dst * (int64_t)stage_cap, kBlock)), dim3(kBlock), 0, s,
-                    g->indptr, dst, n_dst, stage_cap_log2, stage, blk.indptr, blk.col_global, blk.eid);
+        COOP_LAUNCH(K_LABOR_FILL, k_labor_fill_staged, dim3(blocks_for(n_dst * (int64_t)stage_cap, kBlock)), dim3(kBlock), 0, s, seg,
+                    n_dst, stage_cap_log2, stage, blk.indptr, blk.col_global, blk.eid);
         if (h_ctl->n_overflow > 0) {
           const dim3 grid(blocks_for(n_dst, kWavesPerBlock));
-          COOP_LABOR_DISPATCH(K_LABOR_OVERFLOW, k_labor_fill_overflow, grid, g->indptr, g->indices, g->n_edges, dst, n_dst, k, vp,
-                              stage_cap, blk.indptr, blk.col_global, blk.eid);
+          if (blend)
+            COOP_LAUNCH(K_LABOR_OVERFLOW, k_labor_fill_overflow<true>, grid, dim3(kBlock), 0, s, g->indices, seg, n_dst, vp, stage_cap,
+                        blk.indptr, blk.col_global, blk.eid);
+          else
+            COOP_LAUNCH(K_LABOR_OVERFLOW, k_labor_fill_overflow<false>, grid, dim3(kBlock), 0, s, g->indices, seg, n_dst, vp, stage_cap,
+                        blk.indptr, blk.col_global, blk.eid);
         }
       } else {
         // candidate buffer: cap >= 4k (power of two, at least 256); expected candidates: 3k + 24.  A fanout above
