@@ -15,9 +15,8 @@ enum KernelId {
   K_LABOR_OVERFLOW,  // LABOR-0 second scan of overflowed rows
   K_SEGMENTS,        // per-destination list records (start, length, threshold; NS counts)
   K_NS_FILL,         // NS selection + fill pass
-  K_SCAN_REDUCE,     // scan: per-block sums
-  K_SCAN_SPINE,      // scan: scan of block sums
-  K_SCAN_APPLY,      // scan: per-block exclusive scan + offsets
+  K_SCAN_LOCAL,      // scan: per-tile exclusive scan + tile sums
+  K_SCAN_OFFSET,     // scan: add the sum of the preceding tiles
   K_UNIQ_INSERT,     // hash table insert (atomic CAS / min)
   K_UNIQ_FLAG,       // first-occurrence lookup
   K_UNIQ_RELABEL,    // new-id compaction + col_local
@@ -48,9 +47,10 @@ void prof_end(int id, hipStream_t s);
     ::coop::prof_end((id), (stream));                                             \
   } while (0)
 
-// Device-wide exclusive scans; `tmp` needs scan_tmp_bytes(n) bytes.  out has n + 1 entries, out[n] = total.
+// Device-wide exclusive scans; `tmp` needs scan_tmp_bytes(n) bytes.  out has n + 1 entries, out[n] = total;
+// the total also goes to *total_out (device) when that is not null.
 size_t scan_tmp_bytes(int64_t n);
-void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, void* tmp, hipStream_t s);
+void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s);
 // bit flags packed 64 per word -> uint32 exclusive ranks (out has n entries) and the total in *total_out (device)
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
 

@@ -23,7 +23,7 @@ struct Prof {
 } g_prof;
 
 const char* const kKernelNames[K_COUNT_] = {
-    "fill", "labor_count", "labor_fill", "labor_fill_overflow", "segments", "ns_fill", "scan_reduce", "scan_spine", "scan_apply",
+    "fill", "labor_count", "labor_fill", "labor_fill_overflow", "segments", "ns_fill", "scan_local", "scan_offset",
     "unique_insert", "unique_flag", "unique_relabel", "copy_ids", "gather", "validate_csr",
     "cache_lookup", "cache_select", "cache_update", "cache_gather"};
 
@@ -72,22 +72,30 @@ void prof_end(int id, hipStream_t s) {
 }
 
 // ---- fill -----------------------------------------------------------------------------------------------------
+typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+
 __global__ __launch_bounds__(kBlock) void k_fill_u64(uint64_t* __restrict__ p, int64_t n, uint64_t v) {
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  // 16-byte stores over the even part when the base allows it, single words for the rest
+  const bool wide = ((uintptr_t)p & 15) == 0;
+  const int64_t n2 = wide ? n / 2 : 0;
   const int64_t stride = (int64_t)gridDim.x * kBlock;
-  for (; i < n; i += stride) p[i] = v;
+  const u64x2 vv = {v, v};
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n2; i += stride) reinterpret_cast<u64x2*>(p)[i] = vv;
+  for (int64_t i = 2 * n2 + (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) p[i] = v;
 }
 
 void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s) {
   if (n <= 0) return;
-  int64_t blocks = (n + kBlock - 1) / kBlock;
+  int64_t blocks = (n / 2 + kBlock - 1) / kBlock;
   if (blocks > 256 * 64) blocks = 256 * 64;
+  if (blocks < 1) blocks = 1;
   COOP_LAUNCH(K_FILL, k_fill_u64, dim3((unsigned)blocks), dim3(kBlock), 0, s, p, n, v);
 }
 
 // ---- device-wide exclusive scan -------------------------------------------------------------------------------
-// Three kernels, no inter-block waiting: (1) per-tile sums, (2) one block scans the tile sums, (3) per-tile
-// exclusive scan shifted by the tile's offset.  A tile is kTile consecutive elements handled by one block.
+// Two kernels, no inter-block waiting: (1) every block scans its own tile of kTile consecutive elements and records
+// the tile's sum; (2) every block adds up the sums of the tiles in front of it (a few thousand words at most, read
+// from L2) and shifts its tile by that offset; the last block also publishes the grand total.
 constexpr int kItems = 8;
 constexpr int kTile = kBlock * kItems;  // 2048
 
@@ -122,47 +130,10 @@ struct LoadBit {
   __device__ __forceinline__ int64_t operator()(int64_t i) const { return (bits[i >> 6] >> (i & 63)) & 1ull; }
 };
 
-template <typename Load>
-__global__ __launch_bounds__(kBlock) void k_scan_reduce(Load load, int64_t n, int64_t* __restrict__ tile_sum) {
-  __shared__ int64_t lds[kWavesPerBlock];
-  const int64_t base = (int64_t)blockIdx.x * kTile;
-  int64_t v = 0;
-#pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    const int64_t i = base + (int64_t)j * kBlock + threadIdx.x;
-    if (i < n) v += load(i);
-  }
-  v = wave_sum_i64(v);
-  if (lane_id() == 0) lds[wave_in_block()] = v;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int64_t t = 0;
-    for (int i = 0; i < kWavesPerBlock; ++i) t += lds[i];
-    tile_sum[blockIdx.x] = t;
-  }
-}
-
-// one block: exclusive scan of tile_sum[0..n_tiles) in place, total to *total_out
-__global__ __launch_bounds__(kBlock) void k_scan_spine(int64_t* __restrict__ tile_sum, int64_t n_tiles,
-                                                       int64_t* __restrict__ total_out) {
-  __shared__ int64_t lds[kWavesPerBlock];
-  int64_t carry = 0;
-  for (int64_t base = 0; base < n_tiles; base += kBlock) {
-    const int64_t i = base + threadIdx.x;
-    const int64_t x = i < n_tiles ? tile_sum[i] : 0;
-    int64_t tot;
-    const int64_t incl = block_incl_scan(x, &tot, lds);
-    if (i < n_tiles) tile_sum[i] = carry + incl - x;
-    carry += tot;
-  }
-  if (threadIdx.x == 0) *total_out = carry;
-}
-
 template <typename Load, typename Out>
-__global__ __launch_bounds__(kBlock) void k_scan_apply(Load load, int64_t n, const int64_t* __restrict__ tile_off,
-                                                       Out* __restrict__ out, bool write_total) {
+__global__ __launch_bounds__(kBlock) void k_scan_local(Load load, int64_t n, Out* __restrict__ out, int64_t* __restrict__ tile_sum) {
   __shared__ int64_t lds[kWavesPerBlock];
-  const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;  // blocked: thread owns 8 in a row
+  const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;  // a thread owns 8 in a row
   int64_t x[kItems];
   int64_t sum = 0;
 #pragma unroll
@@ -173,15 +144,41 @@ __global__ __launch_bounds__(kBlock) void k_scan_apply(Load load, int64_t n, con
   }
   int64_t tot;
   const int64_t incl = block_incl_scan(sum, &tot, lds);
-  int64_t run = tile_off[blockIdx.x] + incl - sum;
+  int64_t run = incl - sum;
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     const int64_t i = base + j;
     if (i < n) out[i] = (Out)run;
     run += x[j];
   }
-  // the entry one past the end holds the grand total
-  if (write_total && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) out[n] = (Out)(tile_off[blockIdx.x] + tot);
+  if (threadIdx.x == 0) tile_sum[blockIdx.x] = tot;
+}
+
+template <typename Out>
+__global__ __launch_bounds__(kBlock) void k_scan_offset(int64_t n, Out* __restrict__ out, const int64_t* __restrict__ tile_sum,
+                                                        Out* __restrict__ end_out, int64_t* __restrict__ total_out) {
+  __shared__ int64_t lds[kWavesPerBlock];
+  int64_t part = 0;
+  for (int64_t t = threadIdx.x; t < (int64_t)blockIdx.x; t += kBlock) part += tile_sum[t];
+  part = wave_sum_i64(part);
+  if (lane_id() == 0) lds[wave_in_block()] = part;
+  __syncthreads();
+  int64_t off = 0;
+#pragma unroll
+  for (int i = 0; i < kWavesPerBlock; ++i) off += lds[i];
+  const int64_t base = (int64_t)blockIdx.x * kTile;
+  if (off != 0) {
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      const int64_t i = base + (int64_t)j * kBlock + threadIdx.x;
+      if (i < n) out[i] = (Out)((int64_t)out[i] + off);
+    }
+  }
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+    const int64_t total = off + tile_sum[blockIdx.x];
+    if (end_out) *end_out = (Out)total;  // the entry one past the end holds the grand total
+    if (total_out) *total_out = total;
+  }
 }
 
 size_t scan_tmp_bytes(int64_t n) {
@@ -190,29 +187,28 @@ size_t scan_tmp_bytes(int64_t n) {
 }
 
 template <typename Load, typename Out>
-static void scan_impl(Load load, int64_t n, Out* out, int64_t* total_out, bool write_total, void* tmp, hipStream_t s) {
+static void scan_impl(Load load, int64_t n, Out* out, Out* end_out, int64_t* total_out, void* tmp, hipStream_t s) {
   int64_t* tile_sum = (int64_t*)tmp;
   const int64_t tiles = (n + kTile - 1) / kTile;
-  int64_t* total = total_out ? total_out : tile_sum + tiles + 1;
-  if (tiles > 0) COOP_LAUNCH(K_SCAN_REDUCE, k_scan_reduce<Load>, dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, tile_sum);
-  COOP_LAUNCH(K_SCAN_SPINE, k_scan_spine, dim3(1), dim3(kBlock), 0, s, tile_sum, tiles, total);
-  if (tiles > 0)
-    COOP_LAUNCH(K_SCAN_APPLY, (k_scan_apply<Load, Out>), dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, tile_sum, out,
-                write_total);
+  COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_local<Load, Out>), dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, out, tile_sum);
+  COOP_LAUNCH(K_SCAN_OFFSET, k_scan_offset<Out>, dim3((unsigned)tiles), dim3(kBlock), 0, s, n, out, tile_sum, end_out, total_out);
 }
 
-__global__ void k_store_i64(int64_t* p, int64_t v) { *p = v; }
+__global__ void k_store_total(int64_t* p, int64_t* total_out) {
+  *p = 0;
+  if (total_out) *total_out = 0;
+}
 
-void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, void* tmp, hipStream_t s) {
+void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
   if (n <= 0) {  // out[0] = 0
-    COOP_LAUNCH(K_FILL, k_store_i64, dim3(1), dim3(1), 0, s, out, (int64_t)0);
+    COOP_LAUNCH(K_FILL, k_store_total, dim3(1), dim3(1), 0, s, out, total_out);
     return;
   }
-  scan_impl<LoadI32, int64_t>(LoadI32{in}, n, out, nullptr, true, tmp, s);
+  scan_impl<LoadI32, int64_t>(LoadI32{in}, n, out, out + n, total_out, tmp, s);
 }
 
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
-  scan_impl<LoadBit, uint32_t>(LoadBit{bits}, n, out, total_out, false, tmp, s);
+  scan_impl<LoadBit, uint32_t>(LoadBit{bits}, n, out, (uint32_t*)nullptr, total_out, tmp, s);
 }
 
 // ---- CSR validation -------------------------------------------------------------------------------------------

@@ -192,20 +192,24 @@ __global__ __launch_bounds__(kBlock) void k_labor_count(const int32_t* __restric
   }
 }
 
-// staged rows -> the block's edge arrays: one thread per (destination, row slot)
-__global__ __launch_bounds__(kBlock) void k_labor_fill_staged(const Segment* __restrict__ seg, int64_t n_dst, int stage_cap_log2,
+// staged rows -> the block's edge arrays: kFillLanes threads per destination, each taking every kFillLanes-th slot
+constexpr int kFillLanesLog2 = 3;
+__global__ __launch_bounds__(kBlock) void k_labor_fill_staged(const Segment* __restrict__ seg, int64_t n_dst, uint32_t stage_cap,
                                                               const StageEntry* __restrict__ stage, const int64_t* __restrict__ eptr,
                                                               int32_t* __restrict__ col_global, int64_t* __restrict__ eid) {
   const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const int64_t w = idx >> stage_cap_log2;
+  const int64_t w = idx >> kFillLanesLog2;
   if (w >= n_dst) return;
-  const int64_t slot = idx & (((int64_t)1 << stage_cap_log2) - 1);
   const int64_t o = eptr[w];
   const int64_t c = eptr[w + 1] - o;
-  if (slot >= c || c > ((int64_t)1 << stage_cap_log2)) return;
-  const StageEntry e = stage[idx];
-  col_global[o + slot] = e.t;
-  eid[o + slot] = seg[w].beg + e.j;
+  if (c > (int64_t)stage_cap) return;  // overflowed row: the overflow pass writes these edges
+  const StageEntry* __restrict__ row = stage + (size_t)w * stage_cap;
+  const int64_t beg = seg[w].beg;
+  for (int64_t slot = idx & ((1 << kFillLanesLog2) - 1); slot < c; slot += 1 << kFillLanesLog2) {
+    const StageEntry e = row[slot];
+    col_global[o + slot] = e.t;
+    eid[o + slot] = beg + e.j;
+  }
 }
 
 // second, ordered scan of the (rare) destinations whose staging row overflowed, writing straight to the edge arrays
@@ -338,8 +342,6 @@ __global__ __launch_bounds__(kBlock) void k_copy_i32(const int32_t* __restrict__
 
 __global__ void k_clear_ctl(Ctl* ctl) { *ctl = Ctl{}; }
 
-__global__ void k_publish_edges(Ctl* ctl, const int64_t* __restrict__ total) { ctl->total_edges = *total; }
-
 static inline unsigned blocks_for(int64_t n, int64_t per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
 static int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
@@ -428,16 +430,11 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
     // LABOR-0 staging rows: room for 2k + 16 kept edges (a row overflows with probability < 1e-8 at k = 10), 32 or
     // 64 entries (what one wave can hold in a register pair); a row that overflows is redone by the overflow pass
     uint32_t stage_cap = 32;
-    int stage_cap_log2 = 5;
     StageEntry* stage = nullptr;
     Segment* seg = alloc.get<Segment>(n_dst, COOP_TAG_SCRATCH);
     if (sampler == COOP_LABOR0) {
-      if (2 * (uint64_t)k + 16 > 32) { stage_cap = 64; stage_cap_log2 = 6; }
-      if (g_stage_cap_override) {
-        stage_cap = (uint32_t)g_stage_cap_override;
-        stage_cap_log2 = 0;
-        while ((1u << stage_cap_log2) < stage_cap) ++stage_cap_log2;
-      }
+      if (2 * (uint64_t)k + 16 > 32) stage_cap = 64;
+      if (g_stage_cap_override) stage_cap = (uint32_t)g_stage_cap_override;
       stage = alloc.get<StageEntry>(n_dst * (int64_t)stage_cap, COOP_TAG_SCRATCH);
     }
     if (alloc.failed) { rc = COOP_E_NOMEM; break; }
@@ -465,8 +462,7 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
 #undef COOP_COUNT_ARGS
       }
     }
-    scan_i32_to_i64(cnt, n_dst, blk.indptr, scan_tmp, s);
-    COOP_LAUNCH(K_FILL, k_publish_edges, dim3(1), dim3(1), 0, s, d_ctl, blk.indptr + n_dst);  // m_l = indptr[n_dst]
+    scan_i32_to_i64(cnt, n_dst, blk.indptr, &d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
     rc = read_ctl(d_ctl, h_ctl, s);
     if (rc != COOP_OK) break;
     const int64_t m = h_ctl->total_edges;
@@ -480,8 +476,8 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
     // fill pass
     if (m > 0) {
       if (sampler == COOP_LABOR0) {
-        COOP_LAUNCH(K_LABOR_FILL, k_labor_fill_staged, dim3(blocks_for(n_dst * (int64_t)stage_cap, kBlock)), dim3(kBlock), 0, s, seg,
-                    n_dst, stage_cap_log2, stage, blk.indptr, blk.col_global, blk.eid);
+        COOP_LAUNCH(K_LABOR_FILL, k_labor_fill_staged, dim3(blocks_for(n_dst << kFillLanesLog2, kBlock)), dim3(kBlock), 0, s, seg, n_dst,
+                    stage_cap, stage, blk.indptr, blk.col_global, blk.eid);
         if (h_ctl->n_overflow > 0) {
           const dim3 grid(blocks_for(n_dst, kWavesPerBlock));
           if (blend)
