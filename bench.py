@@ -172,10 +172,21 @@ def main():
         alg_dom = (2 * row_bytes + 4) * (stats["n_in"] / K)           # per launch: one gather per step
         roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
                         unit="GB/s")
-    elif dominant in ("labor_count", "labor_fill", "ns_fill"):
-        # bytes per launch: ids + two indptr words per destination, 4 B per neighbour examined, outputs
-        per_step = sum(24 * n_last[l] + 4 * D_last[l] + (4 * n_last[l] if dominant == "labor_count" else 12 * m_last[l])
-                       for l in range(len(fanouts)))
+    elif dominant == "labor_scan":
+        # The scan reads every neighbour list once per minibatch: pass l covers the destinations new at layer l and
+        # evaluates layers l..L-1 together.  Per launch: a 16-byte list record and (threshold + count) per covered layer
+        # for each new destination, 4 bytes per neighbour examined.
+        Lf = len(fanouts)
+        per_step = 0
+        for l in range(Lf):
+            n_new = n_last[l] - (n_last[l - 1] if l else 0)
+            D_new = D_last[l] - (D_last[l - 1] if l else 0)
+            per_step += 16 * n_new + 8 * (Lf - l) * n_new + 4 * D_new
+        alg_dom = per_step / Lf
+        roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
+                        unit="GB/s")
+    elif dominant in ("labor_fill", "ns_fill"):
+        per_step = sum(24 * n_last[l] + (4 * D_last[l] if dominant == "ns_fill" else 0) + 12 * m_last[l] for l in range(len(fanouts)))
         alg_dom = per_step / len(fanouts)
         roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
                         unit="GB/s")

@@ -306,6 +306,7 @@ class Cache:
 
 COOP_TUNE_STAGE_CAP = 1
 COOP_TUNE_LISTS_PER_WAVE = 2
+COOP_TUNE_FUSE_LAYERS = 3
 
 
 def coop_tune(knob, value):

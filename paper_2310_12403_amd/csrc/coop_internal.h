@@ -13,7 +13,8 @@ enum KernelId {
   K_LABOR_COUNT,     // LABOR-0 count pass
   K_LABOR_FILL,      // LABOR-0 fill pass (copy of the staged rows)
   K_LABOR_OVERFLOW,  // LABOR-0 second scan of overflowed rows
-  K_SEGMENTS,        // per-destination list records (start, length, threshold; NS counts)
+  K_SEGMENTS,        // LABOR-0 per-destination list records and keep thresholds
+  K_NS_COUNT,        // NS count pass (min(k, d))
   K_NS_FILL,         // NS selection + fill pass
   K_SCAN_LOCAL,      // scan: per-tile exclusive scan + tile sums
   K_SCAN_OFFSET,     // scan: add the sum of the preceding tiles
@@ -51,6 +52,13 @@ void prof_end(int id, hipStream_t s);
 // the total also goes to *total_out (device) when that is not null.
 size_t scan_tmp_bytes(int64_t n);
 void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s);
+// the same over an input that lies in up to four pieces: element i is ptr[p][i - start[p]] for the last p with start[p] <= i
+struct ChunkedI32 {
+  const int32_t* ptr[4];
+  int64_t start[4];
+  int n_chunks;
+};
+void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s);
 // bit flags packed 64 per word -> uint32 exclusive ranks (out has n entries) and the total in *total_out (device)
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
 

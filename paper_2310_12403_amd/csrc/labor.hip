@@ -1,0 +1,416 @@
+// LABOR-0 layers (App. A.1.2): edge (t -> s) is kept iff r_t <= k / d_s, i.e. R_t * d_s <= k * 2^32 in integers,
+// which for d_s > k is R_t <= floor(k * 2^32 / d_s).  Kept edges leave in (destination order, adjacency order).
+//
+// Every neighbour list is read ONCE per minibatch.  S^l is a prefix of S^{l+1} (Eq. 2), so a vertex that becomes a
+// destination at layer l is a destination at every later layer too, with the same list and a different key: the scan
+// pass of layer l therefore covers only the vertices new at layer l and evaluates, for each neighbour, the keep tests
+// of layers l .. L-1 at once (one mixer evaluation per layer, one read of the entry).  The kept (vertex, position)
+// pairs are parked in small per-destination staging rows, one row set per covered layer; building layer l' later is
+// a scan over the kept-edge counts and a copy of the rows.  A row that overflows is rare; those lists are scanned a
+// second time, in order, straight into the edge arrays.
+#include "device_utils.h"
+#include "sample_internal.h"
+
+namespace coop {
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kAllThr = 0xFFFFFFFFu;  // threshold of a list no longer than the fanout: everything is kept
+constexpr int kScanGroups = 4;             // 16-byte groups per lane and step of the fast scan (4 KiB per wave and step)
+
+struct FusedKeys {
+  LayerKeys K[kMaxFuse];
+  double cw, sw;
+};
+
+struct ScanOut {
+  StageEntry* stage[kMaxFuse];
+  int32_t* cnt[kMaxFuse];
+};
+
+// The pieces of one layer's destinations, by the pass that scanned them.
+struct LayerChunks {
+  const Segment* seg[kMaxFuse];
+  const uint32_t* thr[kMaxFuse];
+  const StageEntry* stage[kMaxFuse];
+  int64_t start[kMaxFuse];
+  int n_chunks;
+  __device__ __forceinline__ int find(int64_t w) const {
+    int p = 0;
+#pragma unroll
+    for (int q = 1; q < kMaxFuse; ++q)
+      if (q < n_chunks && w >= start[q]) p = q;
+    return p;
+  }
+};
+
+// list records of the destinations scanned in this pass, and their keep thresholds for the nf covered layers
+__global__ __launch_bounds__(kBlock) void k_segments(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
+                                                     const int32_t* __restrict__ dst, int64_t n, int nf,
+                                                     uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, Segment* __restrict__ seg,
+                                                     uint32_t* __restrict__ thr, Ctl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  const int32_t s = dst[i];
+  Segment g{0, 0, 0};
+  if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
+    atomicOr(&ctl->err_range, 1);
+  } else {
+    g.beg = g_indptr[s];
+    g.d = (uint32_t)(g_indptr[s + 1] - g.beg);
+  }
+  seg[i] = g;
+  const uint32_t ks[kMaxFuse] = {k0, k1, k2, k3};
+#pragma unroll
+  for (int f = 0; f < kMaxFuse; ++f)
+    if (f < nf) thr[(int64_t)f * n + i] = g.d > ks[f] ? (uint32_t)(((uint64_t)ks[f] << 32) / (uint64_t)g.d) : kAllThr;
+}
+
+// Ordered visit of the neighbour list [beg, beg + d) of one destination by the whole wave, one entry per lane and
+// step: calls emit(rank, t, j) for every kept neighbour t at list position j, rank counting kept neighbours in
+// adjacency order.  Returns the number kept (same value in every lane).  Used for short lists, for an indices array
+// that is not 16-byte aligned, and for the overflow pass.
+template <bool BLEND, typename Emit>
+__device__ __forceinline__ uint32_t labor_scan_ordered(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t thr,
+                                                       const LayerKeys& K, double cw, double sw, Emit emit) {
+  const int lane = lane_id();
+  const bool all = thr == kAllThr;
+  uint32_t count = 0;
+  for (uint32_t base = 0; base < d; base += kWave) {
+    const uint32_t j = base + lane;
+    bool kp = j < d;
+    int32_t t = 0;
+    if (kp) {
+      t = g_indices[beg + j];
+      if (!all) kp = variate<false, BLEND>(K, cw, sw, (uint32_t)t, 0u, 0u) <= thr;
+    }
+    const uint64_t m = ballot64(kp);
+    if (kp) emit(count + lanes_below(m), t, j);
+    count += (uint32_t)__popcll(m);
+  }
+  return count;
+}
+
+// Kept entries of one list and one layer, parked in registers: lane q holds the q-th kept entry.
+struct KeptRegs {
+  int32_t ent_t = 0, ent_j = 0;
+  uint32_t count = 0;  // wave-uniform
+  __device__ __forceinline__ void push(uint32_t lane, int32_t t, int32_t j) {
+    if (lane == (count & 63u)) { ent_t = t; ent_j = j; }
+    ++count;
+  }
+  // writes the entries to `row` in adjacency order if there are at most min(cap, 64) of them
+  __device__ __forceinline__ void flush(uint32_t lane, StageEntry* __restrict__ row, uint32_t cap) const {
+    if (count <= cap && count <= (uint32_t)kWave) {
+      uint32_t rank = 0;  // an entry's place is the number of kept entries in front of it in the list
+      for (uint32_t q = 0; q < count; ++q) rank += (uint32_t)(__builtin_amdgcn_readlane(ent_j, (int)q) < ent_j);
+      if (lane < count) row[rank] = StageEntry{ent_t, (uint32_t)ent_j};
+    }
+  }
+};
+
+// Fast scan of a long list (d > 64) for NF layers at once.  The list is read as 16-byte aligned groups of four
+// entries, kScanGroups groups per lane and step, all requested before the first is hashed.  Only groups that lie
+// wholly inside the list go through the main loop, so validity is one compare per group, not per entry; the up to
+// three entries in front of the first whole group and behind the last one are handled by one extra step.  Per entry
+// and layer the hot loop is the mixer and one compare; one ballot per group tells whether any lane kept anything for
+// any layer.  Only then are the (few) kept entries picked off per-entry ballot masks by a wave-uniform loop and
+// parked in registers, in no particular order (they are ranked when the list is done).
+template <bool BLEND, int NF>
+__device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, const uint32_t (&thr)[NF],
+                                                const FusedKeys& keys, KeptRegs (&kept)[NF]) {
+  constexpr uint32_t kStep = kWave * 4 * kScanGroups;
+  const int64_t abeg = beg & ~(int64_t)3;        // first aligned group
+  const uint32_t head = (uint32_t)(beg - abeg);  // entries of that group that precede the list
+  const uint32_t total = head + d;               // list end, relative to abeg
+  const uint32_t vec_end = total & ~3u;          // whole groups end here
+  const uint32_t vec_beg = head ? 4u : 0u;       // whole groups start here
+  const int32_t* __restrict__ p = g_indices + abeg;
+  const uint32_t lane = (uint32_t)lane_id();
+
+  for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
+    i32x4 buf[kScanGroups];
+    bool ok[kScanGroups];
+#pragma unroll
+    for (int gq = 0; gq < kScanGroups; ++gq) {
+      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
+      ok[gq] = r < vec_end;
+      buf[gq] = i32x4{0, 0, 0, 0};
+      if (ok[gq]) buf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+    }
+#pragma unroll
+    for (int gq = 0; gq < kScanGroups; ++gq) {
+      const uint32_t r0 = base + (uint32_t)(gq * kWave * 4);  // wave-uniform
+      bool f[NF][4];
+      bool any = false;
+#pragma unroll
+      for (int l = 0; l < NF; ++l) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          f[l][e] = ok[gq] & (variate<false, BLEND>(keys.K[l], keys.cw, keys.sw, (uint32_t)buf[gq][e], 0u, 0u) <= thr[l]);
+          any |= f[l][e];
+        }
+      }
+      if (ballot64(any) != 0) {
+#pragma unroll
+        for (int l = 0; l < NF; ++l) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            uint64_t mm = ballot64(f[l][e]);
+            while (mm != 0) {
+              const int src_lane = __builtin_ctzll(mm);
+              mm &= mm - 1;
+              kept[l].push(lane, __builtin_amdgcn_readlane(buf[gq][e], src_lane), (int32_t)(r0 + (uint32_t)src_lane * 4 + e - head));
+            }
+          }
+        }
+      }
+    }
+  }
+  {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
+    const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
+    const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
+    int32_t t = 0;
+    if (valid) t = p[pos];
+#pragma unroll
+    for (int l = 0; l < NF; ++l) {
+      const bool fl = valid && variate<false, BLEND>(keys.K[l], keys.cw, keys.sw, (uint32_t)t, 0u, 0u) <= thr[l];
+      uint64_t mm = ballot64(fl);
+      while (mm != 0) {
+        const int src_lane = __builtin_ctzll(mm);
+        mm &= mm - 1;
+        const uint32_t src_pos = src_lane < 3 ? head + (uint32_t)src_lane : vec_end + (uint32_t)(src_lane - 3);
+        kept[l].push(lane, __builtin_amdgcn_readlane(t, src_lane), (int32_t)(src_pos - head));
+      }
+    }
+  }
+}
+
+// Scan pass.  Each wave takes `lists_per_wave` consecutive destinations; their records are fetched by one coalesced
+// load (lane i holds record i), so the pointer chase destination -> list start is paid once per wave.
+template <bool BLEND, int VEC, int NF>
+__global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict__ g_indices, const Segment* __restrict__ seg,
+                                                       const uint32_t* __restrict__ thr_all, int64_t n, int lists_per_wave,
+                                                       FusedKeys keys, uint32_t stage_cap, ScanOut out, Ctl* ctl) {
+  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + uniform_wave_in_block();
+  const int64_t first = wave * lists_per_wave;
+  if (first >= n) return;
+  const uint32_t lane = (uint32_t)lane_id();
+  const int64_t mine = first + lane;
+  const bool has = (int)lane < lists_per_wave && mine < n;
+  Segment g{0, 0, 0};
+  uint32_t my_thr[NF];
+#pragma unroll
+  for (int l = 0; l < NF; ++l) my_thr[l] = kAllThr;
+  if (has) {
+    g = seg[mine];
+#pragma unroll
+    for (int l = 0; l < NF; ++l) my_thr[l] = thr_all[(int64_t)l * n + mine];
+  }
+  const uint32_t beg_lo = (uint32_t)g.beg, beg_hi = (uint32_t)((uint64_t)g.beg >> 32);
+  uint32_t my_count[NF];
+#pragma unroll
+  for (int l = 0; l < NF; ++l) my_count[l] = 0;
+  const int n_lists = (int)(n - first < lists_per_wave ? n - first : lists_per_wave);
+  for (int i = 0; i < n_lists; ++i) {
+    const int64_t beg = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)beg_hi, i) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readlane((int)beg_lo, i));
+    const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)g.d, i);
+    uint32_t thr[NF];
+    bool any_all = false;
+#pragma unroll
+    for (int l = 0; l < NF; ++l) {
+      thr[l] = (uint32_t)__builtin_amdgcn_readlane((int)my_thr[l], i);
+      any_all |= thr[l] == kAllThr;
+    }
+    if (VEC == 4 && !any_all && d > (uint32_t)kWave) {
+      KeptRegs kept[NF];
+      labor_scan_fast<BLEND, NF>(g_indices, beg, d, thr, keys, kept);
+#pragma unroll
+      for (int l = 0; l < NF; ++l) {
+        kept[l].flush(lane, out.stage[l] + (size_t)(first + i) * stage_cap, stage_cap);
+        if ((int)lane == i) my_count[l] = kept[l].count;
+      }
+    } else {
+#pragma unroll
+      for (int l = 0; l < NF; ++l) {
+        StageEntry* row = out.stage[l] + (size_t)(first + i) * stage_cap;
+        const uint32_t c = labor_scan_ordered<BLEND>(g_indices, beg, d, thr[l], keys.K[l], keys.cw, keys.sw,
+                                                     [&](uint32_t rank, int32_t t, uint32_t j) {
+                                                       if (rank < stage_cap) row[rank] = StageEntry{t, j};
+                                                     });
+        if ((int)lane == i) my_count[l] = c;
+      }
+    }
+  }
+  if (has) {
+#pragma unroll
+    for (int l = 0; l < NF; ++l) {
+      out.cnt[l][mine] = (int32_t)my_count[l];
+      if (my_count[l] > stage_cap) atomicAdd(&ctl->n_overflow, 1);
+    }
+  }
+}
+
+// staged rows -> the block's edge arrays: kFillLanes threads per destination, each taking every kFillLanes-th slot
+constexpr int kFillLanesLog2 = 3;
+__global__ __launch_bounds__(kBlock) void k_labor_fill_staged(LayerChunks ch, int64_t n_dst, uint32_t stage_cap,
+                                                              const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
+                                                              int64_t* __restrict__ eid) {
+  const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t w = idx >> kFillLanesLog2;
+  if (w >= n_dst) return;
+  const int64_t o = eptr[w];
+  const int64_t c = eptr[w + 1] - o;
+  if (c > (int64_t)stage_cap) return;  // overflowed row: the overflow pass writes these edges
+  const int p = ch.find(w);
+  const int64_t local = w - ch.start[p];
+  const StageEntry* __restrict__ row = ch.stage[p] + (size_t)local * stage_cap;
+  const int64_t beg = ch.seg[p][local].beg;
+  for (int64_t slot = idx & ((1 << kFillLanesLog2) - 1); slot < c; slot += 1 << kFillLanesLog2) {
+    const StageEntry e = row[slot];
+    col_global[o + slot] = e.t;
+    eid[o + slot] = beg + e.j;
+  }
+}
+
+// second, ordered scan of the (rare) destinations whose staging row overflowed, writing straight to the edge arrays
+template <bool BLEND>
+__global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int32_t* __restrict__ g_indices, LayerChunks ch, int64_t n_dst,
+                                                                LayerKeys K, double cw, double sw, uint32_t stage_cap,
+                                                                const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
+                                                                int64_t* __restrict__ eid) {
+  const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + uniform_wave_in_block();
+  if (w >= n_dst) return;
+  const int64_t o = eptr[w];
+  if (eptr[w + 1] - o <= (int64_t)stage_cap) return;
+  const int p = ch.find(w);
+  const int64_t local = w - ch.start[p];
+  const Segment g = ch.seg[p][local];
+  const uint32_t thr = ch.thr[p][local];
+  labor_scan_ordered<BLEND>(g_indices, g.beg, g.d, thr, K, cw, sw, [&](uint32_t rank, int32_t t, uint32_t j) {
+    col_global[o + rank] = t;
+    eid[o + rank] = g.beg + j;
+  });
+}
+
+template <bool BLEND, int VEC>
+static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, int64_t n,
+                        int lpw, const FusedKeys& keys, uint32_t cap, const ScanOut& out, Ctl* ctl) {
+  switch (nf) {
+    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, n, lpw, keys, cap, out, ctl); break;
+    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, n, lpw, keys, cap, out, ctl); break;
+    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, n, lpw, keys, cap, out, ctl); break;
+    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, n, lpw, keys, cap, out, ctl); break;
+  }
+}
+
+int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk) {
+  hipStream_t s = cx.s;
+  Alloc& alloc = *cx.alloc;
+  if (l == 0) {
+    // fuse when every remaining layer fits one scan (GNNs have 2-3 layers); otherwise scan layer by layer
+    st.fuse = cx.L <= kMaxFuse && g_fuse_layers != 0;
+    uint32_t kmax = 0;
+    for (int i = 0; i < cx.L; ++i) kmax = (uint32_t)cx.fanouts[i] > kmax ? (uint32_t)cx.fanouts[i] : kmax;
+    // staging rows: room for 2k + 16 kept edges (a row overflows with probability < 1e-8 at k = 10), 32 or 64 entries
+    // (what one wave parks in a register pair); a row that overflows is redone by the overflow pass
+    st.stage_cap = 2 * (uint64_t)kmax + 16 > 32 ? 64 : 32;
+    if (g_stage_cap_override) st.stage_cap = (uint32_t)g_stage_cap_override;
+    st.n_prev = 0;
+  }
+  const uint32_t cap = st.stage_cap;
+
+  // ---- scan pass over the destinations that are new at this layer (all of them when not fusing) ------------------
+  const int pi = st.fuse ? l : 0;
+  LaborPass& ps = st.pass[pi];
+  ps.start = st.fuse ? st.n_prev : 0;
+  ps.n_new = n_dst - ps.start;
+  ps.nf = st.fuse ? cx.L - l : 1;
+  const int64_t n_new = ps.n_new;
+  ps.seg = alloc.get<Segment>(n_new, COOP_TAG_SCRATCH);
+  ps.thr = alloc.get<uint32_t>(n_new * ps.nf, COOP_TAG_SCRATCH);
+  for (int f = 0; f < ps.nf; ++f) {
+    ps.stage[f] = alloc.get<StageEntry>(n_new * (int64_t)cap, COOP_TAG_SCRATCH);
+    ps.cnt[f] = alloc.get<int32_t>(n_new, COOP_TAG_SCRATCH);
+  }
+  blk->indptr = alloc.get<int64_t>(n_dst + 1, COOP_TAG_OUTPUT);
+  void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
+  if (alloc.failed) return COOP_E_NOMEM;
+
+  FusedKeys keys{};
+  keys.cw = cx.cw;
+  keys.sw = cx.sw;
+  uint32_t ks[kMaxFuse] = {1, 1, 1, 1};
+  for (int f = 0; f < ps.nf; ++f) {
+    layer_keys(cx.seed, COOP_LABOR0, l + f, cx.group, keys.K[f].Ka);
+    layer_keys(cx.seed, COOP_LABOR0, l + f, cx.group + 1, keys.K[f].Kb);
+    ks[f] = (uint32_t)cx.fanouts[l + f];
+  }
+  if (n_new > 0) {
+    COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
+                dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, cx.d_ctl);
+    // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
+    int lpw = g_lists_per_wave;
+    if (lpw == 0) lpw = n_new >= 65536 ? 4 : 1;
+    const int64_t n_waves = (n_new + lpw - 1) / lpw;
+    const dim3 grid(blocks_for(n_waves, kWavesPerBlock));
+    ScanOut out{};
+    for (int f = 0; f < ps.nf; ++f) { out.stage[f] = ps.stage[f]; out.cnt[f] = ps.cnt[f]; }
+    if (cx.blend) {
+      if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, n_new, lpw, keys, cap, out, cx.d_ctl);
+      else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, n_new, lpw, keys, cap, out, cx.d_ctl);
+    } else {
+      if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, n_new, lpw, keys, cap, out, cx.d_ctl);
+      else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, n_new, lpw, keys, cap, out, cx.d_ctl);
+    }
+  }
+
+  // ---- this layer's destinations, piece by piece: pass p covered it as its (l - p)-th layer ------------------------
+  LayerChunks ch{};
+  ChunkedI32 counts{};
+  ch.n_chunks = counts.n_chunks = st.fuse ? l + 1 : 1;
+  for (int p = 0; p < ch.n_chunks; ++p) {
+    const LaborPass& q = st.pass[st.fuse ? p : 0];
+    const int f = st.fuse ? l - p : 0;
+    ch.seg[p] = q.seg;
+    ch.thr[p] = q.thr + (int64_t)f * q.n_new;
+    ch.stage[p] = q.stage[f];
+    ch.start[p] = counts.start[p] = q.start;
+    counts.ptr[p] = q.cnt[f];
+  }
+  // chunks that scanned nothing (a layer that added no vertex) must not shadow their predecessors
+  for (int p = 1; p < ch.n_chunks; ++p)
+    if (st.pass[st.fuse ? p : 0].n_new == 0) { ch.start[p] = counts.start[p] = INT64_MAX; }
+
+  scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
+  int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
+  if (rc != COOP_OK) return rc;
+  const int64_t m = cx.h_ctl->total_edges;
+  blk->n_edges = m;
+  blk->col_global = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
+  blk->eid = alloc.get<int64_t>(m, COOP_TAG_OUTPUT);
+  blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
+  if (alloc.failed) return COOP_E_NOMEM;
+
+  if (m > 0) {
+    COOP_LAUNCH(K_LABOR_FILL, k_labor_fill_staged, dim3(blocks_for(n_dst << kFillLanesLog2, kBlock)), dim3(kBlock), 0, s, ch, n_dst, cap,
+                blk->indptr, blk->col_global, blk->eid);
+    if (cx.h_ctl->n_overflow > 0) {
+      LayerKeys K{};
+      layer_keys(cx.seed, COOP_LABOR0, l, cx.group, K.Ka);
+      layer_keys(cx.seed, COOP_LABOR0, l, cx.group + 1, K.Kb);
+      const dim3 grid(blocks_for(n_dst, kWavesPerBlock));
+      if (cx.blend)
+        COOP_LAUNCH(K_LABOR_OVERFLOW, k_labor_fill_overflow<true>, grid, dim3(kBlock), 0, s, cx.g->indices, ch, n_dst, K, cx.cw, cx.sw,
+                    cap, blk->indptr, blk->col_global, blk->eid);
+      else
+        COOP_LAUNCH(K_LABOR_OVERFLOW, k_labor_fill_overflow<false>, grid, dim3(kBlock), 0, s, cx.g->indices, ch, n_dst, K, cx.cw, cx.sw,
+                    cap, blk->indptr, blk->col_global, blk->eid);
+    }
+  }
+  st.n_prev = n_dst;
+  return COOP_OK;
+}
+
+}  // namespace coop

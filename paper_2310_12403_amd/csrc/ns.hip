@@ -1,0 +1,174 @@
+// NS layers (App. A.1.1): a destination of degree d <= k keeps all of N(s); otherwise it keeps the k neighbours with
+// the smallest (R_ts, list position), a uniform k-subset.  Kept edges leave in (destination order, adjacency order).
+// The count is known without looking at the list (min(k, d)), so every list is read once, by the fill pass.
+#include "device_utils.h"
+#include "sample_internal.h"
+
+namespace coop {
+
+__global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
+                                                     const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
+                                                     int32_t* __restrict__ cnt, Ctl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_dst) return;
+  const int32_t s = dst[i];
+  if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
+    atomicOr(&ctl->err_range, 1);
+    cnt[i] = 0;
+    return;
+  }
+  const int64_t d = g_indptr[s + 1] - g_indptr[s];
+  cnt[i] = (int32_t)(d < (int64_t)k ? d : (int64_t)k);
+}
+
+constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list can be subsampled
+
+// Selection of the k smallest (R, j) among d > k neighbours, one wave per destination:
+//   1. one pass over the list keeps, in LDS and in adjacency order, the candidates with R <= bound, where bound is
+//      chosen so that about `target` of them are expected (target > k, target < cap);
+//   2. if fewer than k or more than cap candidates turn up, the bound is bisected and the pass repeated (rare);
+//   3. each candidate's rank among the candidates is counted; ranks below k are emitted, still in adjacency order.
+template <bool BLEND>
+__global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ g_indptr,
+                                                    const int32_t* __restrict__ g_indices,
+                                                    const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
+                                                    uint32_t cap, uint32_t target, int waves_per_block, VariateParams vp,
+                                                    const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
+                                                    int64_t* __restrict__ eid, Ctl* ctl) {
+  extern __shared__ uint64_t lds_keys[];  // per wave: cap variates (u32) followed by cap list positions (u32)
+  const int wib = wave_in_block();
+  if (wib >= waves_per_block) return;
+  const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
+  if (w >= n_dst) return;
+  const int lane = lane_id();
+  int64_t o = eptr[w];
+  if (o == eptr[w + 1]) return;
+  const int32_t s = dst[w];
+  const int64_t beg = g_indptr[s];
+  const int64_t d = g_indptr[s + 1] - beg;
+  if (d <= (int64_t)k) {
+    for (int64_t j = lane; j < d; j += kWave) {
+      col_global[o + j] = g_indices[beg + j];
+      eid[o + j] = beg + j;
+    }
+    return;
+  }
+  if (k > kNsMaxSelect) {  // a degree above a fanout that the candidate buffer cannot serve
+    if (lane == 0) atomicOr(&ctl->err_capacity, 1);
+    return;
+  }
+  uint32_t* cand_r = (uint32_t*)(lds_keys + (size_t)wib * cap);  // [cap] variates
+  uint32_t* cand_j = cand_r + cap;                               // [cap] positions (d < 2^31)
+  const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)s);
+  const uint32_t sigma_b = BLEND ? ns_sigma(vp.K.Kb, (uint32_t)s) : 0u;
+
+  // bound such that E[#candidates] = target: R <= bound with probability (bound + 1) / 2^32
+  uint64_t lo = 0, hi = 0xFFFFFFFFull;  // bisection bracket on the bound, used only after a failed pass
+  uint64_t bound = ((uint64_t)target << 32) / (uint64_t)d;
+  if (bound > 0xFFFFFFFFull || (uint64_t)d <= cap) bound = 0xFFFFFFFFull;
+  uint32_t n_c = 0;
+  for (int attempt = 0; attempt < 40; ++attempt) {
+    n_c = 0;
+    for (int64_t base = 0; base < d; base += kWave) {
+      const int64_t j = base + lane;
+      bool in = false;
+      uint32_t r = 0;
+      if (j < d) {
+        r = variate<true, BLEND>(vp, (uint32_t)g_indices[beg + j], sigma_a, sigma_b);
+        in = r <= (uint32_t)bound;
+      }
+      const uint64_t mask = ballot64(in);
+      const uint32_t p = n_c + lanes_below(mask);
+      if (in && p < cap) { cand_r[p] = r; cand_j[p] = (uint32_t)j; }
+      n_c += (uint32_t)__popcll(mask);
+    }
+    if (n_c >= k && n_c <= cap) break;
+    // cannot be bracketed (more than cap - k equal variates): report instead of guessing
+    if (n_c < k) {
+      if (bound >= 0xFFFFFFFFull) { n_c = 0; break; }
+      lo = bound + 1;
+    } else {
+      if (bound == 0) { n_c = 0; break; }
+      hi = bound - 1;
+    }
+    if (lo > hi) { n_c = 0; break; }
+    bound = lo + (hi - lo) / 2;
+  }
+  if (n_c < k || n_c > cap) {
+    if (lane == 0) atomicOr(&ctl->err_capacity, 1);
+    return;
+  }
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
+  // rank counting; candidates are in adjacency order, so ties on R are broken by list position for free
+  for (uint32_t base = 0; base < n_c; base += kWave) {
+    const uint32_t i = base + lane;
+    bool keep = false;
+    uint32_t my_j = 0;
+    if (i < n_c) {
+      const uint32_t my_r = cand_r[i];
+      my_j = cand_j[i];
+      uint32_t rank = 0;
+      for (uint32_t q = 0; q < n_c; ++q) {
+        const uint32_t r = cand_r[q];
+        rank += (r < my_r) || (r == my_r && q < i);
+      }
+      keep = rank < k;
+    }
+    const uint64_t mask = ballot64(keep);
+    if (keep) {
+      const int64_t p = o + lanes_below(mask);
+      col_global[p] = g_indices[beg + my_j];
+      eid[p] = beg + my_j;
+    }
+    o += __popcll(mask);
+  }
+}
+
+int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk) {
+  hipStream_t s = cx.s;
+  Alloc& alloc = *cx.alloc;
+  const uint32_t k = (uint32_t)cx.fanouts[l];
+  VariateParams vp{};
+  layer_keys(cx.seed, COOP_NS, l, cx.group, vp.K.Ka);
+  layer_keys(cx.seed, COOP_NS, l, cx.group + 1, vp.K.Kb);
+  vp.cw = cx.cw;
+  vp.sw = cx.sw;
+  blk->indptr = alloc.get<int64_t>(n_dst + 1, COOP_TAG_OUTPUT);
+  int32_t* cnt = alloc.get<int32_t>(n_dst, COOP_TAG_SCRATCH);
+  void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
+  if (alloc.failed) return COOP_E_NOMEM;
+  if (n_dst > 0)
+    COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices, dst, n_dst,
+                k, cnt, cx.d_ctl);
+  scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
+  int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
+  if (rc != COOP_OK) return rc;
+  const int64_t m = cx.h_ctl->total_edges;
+  blk->n_edges = m;
+  blk->col_global = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
+  blk->eid = alloc.get<int64_t>(m, COOP_TAG_OUTPUT);
+  blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
+  if (alloc.failed) return COOP_E_NOMEM;
+  if (m > 0) {
+    // candidate buffer: cap >= 4k (power of two, at least 256); expected candidates: 3k + 24.  A fanout above
+    // kNsMaxSelect is served only while no degree exceeds it (the kernel reports the first that does).
+    const uint32_t k_sel = k < kNsMaxSelect ? k : kNsMaxSelect;
+    uint32_t cap = 256;
+    while (cap < 4 * k_sel) cap <<= 1;
+    const uint32_t target = 3 * k_sel + 24;
+    int wpb = kWavesPerBlock;
+    while (wpb > 1 && (size_t)wpb * cap * 8 > 32768) wpb >>= 1;
+    const size_t shmem = (size_t)wpb * cap * 8;
+    const dim3 grid(blocks_for(n_dst, wpb));
+    if (cx.blend)
+      COOP_LAUNCH(K_NS_FILL, k_ns_fill<true>, grid, dim3(kBlock), shmem, s, cx.g->indptr, cx.g->indices, dst, n_dst, k, cap, target, wpb,
+                  vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl);
+    else
+      COOP_LAUNCH(K_NS_FILL, k_ns_fill<false>, grid, dim3(kBlock), shmem, s, cx.g->indptr, cx.g->indices, dst, n_dst, k, cap, target, wpb,
+                  vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl);
+  }
+  return COOP_OK;
+}
+
+}  // namespace coop

@@ -23,7 +23,7 @@ struct Prof {
 } g_prof;
 
 const char* const kKernelNames[K_COUNT_] = {
-    "fill", "labor_count", "labor_fill", "labor_fill_overflow", "segments", "ns_fill", "scan_local", "scan_offset",
+    "fill", "labor_scan", "labor_fill", "labor_fill_overflow", "segments", "ns_count", "ns_fill", "scan_local", "scan_offset",
     "unique_insert", "unique_flag", "unique_relabel", "copy_ids", "gather", "validate_csr",
     "cache_lookup", "cache_select", "cache_update", "cache_gather"};
 
@@ -125,6 +125,16 @@ struct LoadI32 {
   const int32_t* in;
   __device__ __forceinline__ int64_t operator()(int64_t i) const { return in[i]; }
 };
+struct LoadChunks {
+  ChunkedI32 c;
+  __device__ __forceinline__ int64_t operator()(int64_t i) const {
+    int p = 0;
+#pragma unroll
+    for (int q = 1; q < 4; ++q)
+      if (q < c.n_chunks && i >= c.start[q]) p = q;
+    return c.ptr[p][i - c.start[p]];
+  }
+};
 struct LoadBit {
   const uint64_t* bits;
   __device__ __forceinline__ int64_t operator()(int64_t i) const { return (bits[i >> 6] >> (i & 63)) & 1ull; }
@@ -205,6 +215,14 @@ void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* total_
     return;
   }
   scan_impl<LoadI32, int64_t>(LoadI32{in}, n, out, out + n, total_out, tmp, s);
+}
+
+void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
+  if (n <= 0) {
+    COOP_LAUNCH(K_FILL, k_store_total, dim3(1), dim3(1), 0, s, out, total_out);
+    return;
+  }
+  scan_impl<LoadChunks, int64_t>(LoadChunks{in}, n, out, out + n, total_out, tmp, s);
 }
 
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {

@@ -1,0 +1,63 @@
+// Pieces shared by the sampling driver (sample.hip) and the two samplers (labor.hip, ns.hip).
+#pragma once
+#include "coop_internal.h"
+#include "variates.h"
+
+namespace coop {
+
+constexpr int kMaxFuse = 4;  // LABOR-0: most layers whose keep tests are evaluated in one scan of a list
+
+// Everything a sampler needs to know about the call.
+struct SampleCtx {
+  const coop_graph* g;
+  hipStream_t s;
+  Alloc* alloc;
+  Ctl* d_ctl;
+  Ctl* h_ctl;
+  const int32_t* fanouts;
+  int L;
+  int sampler;
+  uint64_t seed;   // user seed
+  uint64_t group;  // g = floor(iter / kappa)
+  bool blend;      // c > 0
+  double cw, sw;   // cos(c pi/2), sin(c pi/2)
+  bool vec4;       // the graph's indices array is 16-byte aligned
+};
+
+// One destination's neighbour list as the scan kernels see it.
+struct Segment { int64_t beg; uint32_t d; uint32_t pad; };
+
+struct StageEntry { int32_t t; uint32_t j; };  // kept source vertex, its position in the destination's list
+
+// What one LABOR-0 scan pass leaves behind for the layers it covered (f = 0 is the pass's own layer).
+struct LaborPass {
+  int64_t start = 0, n_new = 0;      // destinations [start, start + n_new) of the layer were scanned in this pass
+  Segment* seg = nullptr;            // [n_new]
+  uint32_t* thr = nullptr;           // [nf][n_new] keep thresholds, layer-major
+  int nf = 0;                        // layers covered: l .. l + nf - 1
+  StageEntry* stage[kMaxFuse] = {};  // [n_new][stage_cap] kept edges per covered layer
+  int32_t* cnt[kMaxFuse] = {};       // [n_new] kept-edge counts per covered layer
+};
+
+struct LaborState {
+  LaborPass pass[kMaxFuse];
+  bool fuse = false;
+  uint32_t stage_cap = 32;
+  int64_t n_prev = 0;  // |S^{l-1}| while layer l is being built
+};
+
+int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
+
+// Each fills blk->indptr, n_edges, col_global, eid and allocates col_local for layer l over dst[0..n_dst).
+// Synchronises the stream once (the edge count is read back).
+int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);
+int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);
+
+// tuning knobs (coop_tune)
+extern int g_stage_cap_override;
+extern int g_lists_per_wave;
+extern int g_fuse_layers;
+
+static inline unsigned blocks_for(int64_t n, int64_t per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+}  // namespace coop

@@ -13,19 +13,20 @@ namespace coop {
 
 constexpr uint64_t kEmptySlot = ~0ull;
 
-__device__ __forceinline__ uint64_t slot_of_key(uint32_t key, int shift) {
-  return ((uint64_t)key * 0x9E3779B97F4A7C15ull) >> shift;  // multiplicative (Fibonacci) hashing, top bits
+// multiplicative (Fibonacci) hashing of the key to 32 bits, then multiply-high range reduction onto [0, cap)
+__device__ __forceinline__ uint64_t slot_of_key(uint32_t key, uint64_t cap) {
+  const uint32_t h = (uint32_t)(((uint64_t)key * 0x9E3779B97F4A7C15ull) >> 32);
+  return ((uint64_t)h * cap) >> 32;
 }
 
 __global__ __launch_bounds__(kBlock) void k_uniq_insert(const int32_t* __restrict__ dst, int64_t n_dst,
                                                         const int32_t* __restrict__ col, int64_t m,
-                                                        unsigned long long* __restrict__ table, uint64_t mask, int shift,
-                                                        Ctl* ctl) {
+                                                        unsigned long long* __restrict__ table, uint64_t cap, Ctl* ctl) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_dst + m) return;
   const uint32_t key = (uint32_t)(i < n_dst ? dst[i] : col[i - n_dst]);
   const unsigned long long mine = ((unsigned long long)key << 32) | (uint32_t)i;
-  uint64_t h = slot_of_key(key, shift);
+  uint64_t h = slot_of_key(key, cap);
   for (;;) {
     unsigned long long cur = __hip_atomic_load(&table[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (cur == kEmptySlot) {
@@ -41,29 +42,28 @@ __global__ __launch_bounds__(kBlock) void k_uniq_insert(const int32_t* __restric
       if (i < n_dst && (int64_t)(uint32_t)old < n_dst) atomicOr(&ctl->err_dup, 1);
       return;
     }
-    h = (h + 1) & mask;  // the table is at most half full, so an empty slot or the key is always reached
+    if (++h == cap) h = 0;  // the table is at most half full, so an empty slot or the key is always reached
   }
 }
 
-__device__ __forceinline__ uint32_t first_position(const unsigned long long* __restrict__ table, uint64_t mask, int shift,
-                                                   uint32_t key) {
-  uint64_t h = slot_of_key(key, shift);
+__device__ __forceinline__ uint32_t first_position(const unsigned long long* __restrict__ table, uint64_t cap, uint32_t key) {
+  uint64_t h = slot_of_key(key, cap);
   for (;;) {
     const unsigned long long cur = table[h];
     if ((uint32_t)(cur >> 32) == key) return (uint32_t)cur;
     if (cur == kEmptySlot) return 0xFFFFFFFFu;  // not reachable for inserted keys
-    h = (h + 1) & mask;
+    if (++h == cap) h = 0;
   }
 }
 
 // first[e] = first position of col[e] in [S^l ; col]; bit e of `bits` = that position is this very edge
 __global__ __launch_bounds__(kBlock) void k_uniq_flag(const int32_t* __restrict__ col, int64_t m, int64_t n_dst,
-                                                      const unsigned long long* __restrict__ table, uint64_t mask, int shift,
+                                                      const unsigned long long* __restrict__ table, uint64_t cap,
                                                       uint32_t* __restrict__ first, uint64_t* __restrict__ bits) {
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   bool is_new = false;
   if (e < m) {
-    const uint32_t f = first_position(table, mask, shift, (uint32_t)col[e]);
+    const uint32_t f = first_position(table, cap, (uint32_t)col[e]);
     first[e] = f;
     is_new = (int64_t)f == n_dst + e;
   }
@@ -95,11 +95,8 @@ static inline unsigned nblocks(int64_t n) { return (unsigned)((n + kBlock - 1) /
 int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, int32_t* col_local,
                    int32_t** src_out, int64_t* n_src_out, Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
   const int64_t n_all = n_dst + m;
-  int log2cap = 10;
-  while (((int64_t)1 << log2cap) < 2 * n_all) ++log2cap;
-  const int64_t cap = (int64_t)1 << log2cap;
-  const uint64_t mask = (uint64_t)cap - 1;
-  const int shift = 64 - log2cap;
+  // at most half full; an even number of slots (the clear uses 16-byte stores)
+  int64_t cap = 2 * n_all + 1024;
 
   unsigned long long* table = alloc.get<unsigned long long>(cap, COOP_TAG_SCRATCH);
   uint32_t* first = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
@@ -111,11 +108,11 @@ int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global,
   int64_t n_new = 0;
   if (n_all > 0) {
     fill_u64((uint64_t*)table, cap, kEmptySlot, s);
-    COOP_LAUNCH(K_UNIQ_INSERT, k_uniq_insert, dim3(nblocks(n_all)), dim3(kBlock), 0, s, dst, n_dst, col_global, m, table, mask,
-                shift, d_ctl);
+    COOP_LAUNCH(K_UNIQ_INSERT, k_uniq_insert, dim3(nblocks(n_all)), dim3(kBlock), 0, s, dst, n_dst, col_global, m, table,
+                (uint64_t)cap, d_ctl);
   }
   if (m > 0) {
-    COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, n_dst, table, mask, shift, first,
+    COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, n_dst, table, (uint64_t)cap, first,
                 bits);
     scan_bits_to_u32(bits, m, rank, &d_ctl->total_new, scan_tmp, s);
   }

@@ -18,9 +18,13 @@
 
 namespace coop {
 
-struct VariateParams {
+struct LayerKeys {
   uint32_t Ka[4];  // key words of group g
   uint32_t Kb[4];  // key words of group g + 1 (blended path only)
+};
+
+struct VariateParams {
+  LayerKeys K;
   double cw, sw;   // cos(c pi/2), sin(c pi/2) (blended path only)
 };
 
@@ -222,16 +226,22 @@ __device__ __forceinline__ uint32_t keyed_uniform(const uint32_t K[4], uint32_t 
 
 // R for source vertex t; for NS, sigma_a / sigma_b are ns_sigma(Ka, s) / ns_sigma(Kb, s) of the destination s
 template <bool NS, bool BLEND>
-__device__ __forceinline__ uint32_t variate(const VariateParams& vp, uint32_t t, uint32_t sigma_a, uint32_t sigma_b) {
-  const uint32_t U1 = keyed_uniform<NS>(vp.Ka, t, sigma_a);
+__device__ __forceinline__ uint32_t variate(const LayerKeys& K, double cw, double sw, uint32_t t, uint32_t sigma_a,
+                                            uint32_t sigma_b) {
+  const uint32_t U1 = keyed_uniform<NS>(K.Ka, t, sigma_a);
   if constexpr (!BLEND) {
     return U1;
   } else {
-    const uint32_t U2 = keyed_uniform<NS>(vp.Kb, t, sigma_b);
+    const uint32_t U2 = keyed_uniform<NS>(K.Kb, t, sigma_b);
     const double n1 = kit_phi_inv_u32(U1);
     const double n2 = kit_phi_inv_u32(U2);
-    return kit_phi_to_u32(__builtin_fma(vp.cw, n1, vp.sw * n2));
+    return kit_phi_to_u32(__builtin_fma(cw, n1, sw * n2));
   }
+}
+
+template <bool NS, bool BLEND>
+__device__ __forceinline__ uint32_t variate(const VariateParams& vp, uint32_t t, uint32_t sigma_a, uint32_t sigma_b) {
+  return variate<NS, BLEND>(vp.K, vp.cw, vp.sw, t, sigma_a, sigma_b);
 }
 
 }  // namespace coop

@@ -61,5 +61,5 @@ def test_profile_table():
     L = P.lib()
     n = L.coop_profile_kernels()
     names = [L.coop_profile_name(i).decode() for i in range(n)]
-    assert len(set(names)) == n and "gather" in names and "labor_count" in names
+    assert len(set(names)) == n and "gather" in names and "labor_scan" in names
     assert L.coop_profile_name(n) is None
