@@ -23,6 +23,18 @@ struct FusedKeys {
   double cw, sw;
 };
 
+// Blended variates (c > 0) cost two Phi^-1 and one Phi per neighbour, ~40 times the integer path.  A cheap necessary
+// condition keeps them off almost every neighbour: R <= thr needs n = cw n1 + sw n2 below tau = Phi^-1(thr / 2^32),
+// and since cw, sw >= 0, n >= (cw + sw) min(n1, n2); so min(U1, U2) must lie below 2^32 Phi(tau / (cw + sw)).  That
+// bound ("pre-threshold"), widened by 1e-6 relative and a few units so that the approximation errors of the kit
+// (1.2e-9) can never matter, is computed once per list and layer; only neighbours that pass it are evaluated exactly.
+__device__ __forceinline__ uint32_t blend_pre_threshold(uint32_t thr, double inv_cs /* (1 - 1e-6) / (cw + sw) */) {
+  if (thr >= 0x7FFFFFF0u) return 0xFFFFFFFFu;           // k / d near or above 1/2: no useful bound
+  const double tau = kit_phi_inv_u32(thr + 8u);          // < 0; Phi^-1 of slightly more than (thr + 1) / 2^32
+  const double lim = (double)kit_phi_to_u32(tau * inv_cs) * 1.000001 + 16.0;
+  return lim >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)lim;
+}
+
 struct ScanOut {
   StageEntry* stage[kMaxFuse];
   int32_t* cnt[kMaxFuse];
@@ -45,10 +57,11 @@ struct LayerChunks {
 };
 
 // list records of the destinations scanned in this pass, and their keep thresholds for the nf covered layers
+// (pthr: the blended path's pre-thresholds, null when c = 0)
 __global__ __launch_bounds__(kBlock) void k_segments(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
                                                      const int32_t* __restrict__ dst, int64_t n, int nf,
                                                      uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, Segment* __restrict__ seg,
-                                                     uint32_t* __restrict__ thr, Ctl* ctl) {
+                                                     uint32_t* __restrict__ thr, uint32_t* __restrict__ pthr, double inv_cs, Ctl* ctl) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n) return;
   const int32_t s = dst[i];
@@ -63,7 +76,11 @@ __global__ __launch_bounds__(kBlock) void k_segments(const int64_t* __restrict__
   const uint32_t ks[kMaxFuse] = {k0, k1, k2, k3};
 #pragma unroll
   for (int f = 0; f < kMaxFuse; ++f)
-    if (f < nf) thr[(int64_t)f * n + i] = g.d > ks[f] ? (uint32_t)(((uint64_t)ks[f] << 32) / (uint64_t)g.d) : kAllThr;
+    if (f < nf) {
+      const uint32_t t = g.d > ks[f] ? (uint32_t)(((uint64_t)ks[f] << 32) / (uint64_t)g.d) : kAllThr;
+      thr[(int64_t)f * n + i] = t;
+      if (pthr) pthr[(int64_t)f * n + i] = blend_pre_threshold(t, inv_cs);
+    }
 }
 
 // Ordered visit of the neighbour list [beg, beg + d) of one destination by the whole wave, one entry per lane and
@@ -186,12 +203,154 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
   }
 }
 
+// Candidate queue of the blended fast scan, one per wave, in LDS: neighbours that passed the pre-threshold and
+// wait for an exact evaluation.  Evaluating them 64 at a time keeps every lane busy in the expensive part.
+constexpr int kQueueCap = 2 * kWave;
+struct BlendQueue {
+  int32_t t[kQueueCap];
+  int32_t j[kQueueCap];
+  uint32_t u1[kQueueCap];
+  uint32_t u2[kQueueCap];
+  uint32_t layer[kQueueCap];
+};
+
+// exact evaluation of queue entries [0, n_eval) (n_eval <= 64), kept ones go to the register lists
+template <int NF>
+__device__ __forceinline__ void blend_eval(const BlendQueue* __restrict__ q, uint32_t n_eval, const uint32_t (&thr)[NF],
+                                           const FusedKeys& keys, KeptRegs (&kept)[NF]) {
+  const uint32_t lane = (uint32_t)lane_id();
+  int32_t t = 0, j = 0;
+  uint32_t l = 0;
+  bool keep = false;
+  if (lane < n_eval) {
+    t = q->t[lane];
+    j = q->j[lane];
+    l = q->layer[lane];
+    const double n1 = kit_phi_inv_u32(q->u1[lane]);
+    const double n2 = kit_phi_inv_u32(q->u2[lane]);
+    const uint32_t R = kit_phi_to_u32(__builtin_fma(keys.cw, n1, keys.sw * n2));
+    uint32_t my_thr = thr[0];
+#pragma unroll
+    for (int f = 1; f < NF; ++f)
+      if (l == (uint32_t)f) my_thr = thr[f];
+    keep = R <= my_thr;
+  }
+#pragma unroll
+  for (int f = 0; f < NF; ++f) {
+    uint64_t mm = ballot64(keep && l == (uint32_t)f);
+    while (mm != 0) {
+      const int src_lane = __builtin_ctzll(mm);
+      mm &= mm - 1;
+      kept[f].push(lane, __builtin_amdgcn_readlane(t, src_lane), __builtin_amdgcn_readlane(j, src_lane));
+    }
+  }
+}
+
+// appends the lanes with `pre` set to the queue; evaluates a full wave of candidates whenever 64 are waiting
+template <int NF>
+__device__ __forceinline__ void blend_enqueue(BlendQueue* __restrict__ q, uint32_t& qn, bool pre, int32_t t, int32_t j, uint32_t u1,
+                                              uint32_t u2, uint32_t layer, const uint32_t (&thr)[NF], const FusedKeys& keys,
+                                              KeptRegs (&kept)[NF]) {
+  const uint64_t mask = ballot64(pre);
+  if (mask == 0) return;
+  const uint32_t lane = (uint32_t)lane_id();
+  if (pre) {
+    const uint32_t pos = qn + lanes_below(mask);  // < 128: fewer than 64 wait, at most 64 arrive
+    q->t[pos] = t; q->j[pos] = j; q->u1[pos] = u1; q->u2[pos] = u2; q->layer[pos] = layer;
+  }
+  qn += (uint32_t)__popcll(mask);
+  __builtin_amdgcn_wave_barrier();
+  if (qn >= (uint32_t)kWave) {
+    blend_eval<NF>(q, kWave, thr, keys, kept);
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t rest = qn - kWave;  // < 64: move the tail to the front
+    int32_t mt = 0, mj = 0;
+    uint32_t m1 = 0, m2 = 0, ml = 0;
+    if (lane < rest) { mt = q->t[kWave + lane]; mj = q->j[kWave + lane]; m1 = q->u1[kWave + lane]; m2 = q->u2[kWave + lane]; ml = q->layer[kWave + lane]; }
+    __builtin_amdgcn_wave_barrier();
+    if (lane < rest) { q->t[lane] = mt; q->j[lane] = mj; q->u1[lane] = m1; q->u2[lane] = m2; q->layer[lane] = ml; }
+    qn = rest;
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// Blended fast scan: same traversal as labor_scan_fast; per entry and layer two mixer evaluations and one compare
+// against the pre-threshold, exact evaluation only for the candidates.
+template <int NF>
+__device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d,
+                                                      const uint32_t (&thr)[NF], const uint32_t (&pthr)[NF], const FusedKeys& keys,
+                                                      BlendQueue* __restrict__ q, KeptRegs (&kept)[NF]) {
+  constexpr uint32_t kStep = kWave * 4 * kScanGroups;
+  const int64_t abeg = beg & ~(int64_t)3;
+  const uint32_t head = (uint32_t)(beg - abeg);
+  const uint32_t total = head + d;
+  const uint32_t vec_end = total & ~3u;
+  const uint32_t vec_beg = head ? 4u : 0u;
+  const int32_t* __restrict__ p = g_indices + abeg;
+  const uint32_t lane = (uint32_t)lane_id();
+  uint32_t qn = 0;
+
+  for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
+    i32x4 buf[kScanGroups];
+    bool ok[kScanGroups];
+#pragma unroll
+    for (int gq = 0; gq < kScanGroups; ++gq) {
+      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
+      ok[gq] = r < vec_end;
+      buf[gq] = i32x4{0, 0, 0, 0};
+      if (ok[gq]) buf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+    }
+#pragma unroll
+    for (int gq = 0; gq < kScanGroups; ++gq) {
+      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
+      uint32_t u1[NF][4], u2[NF][4];
+      bool pre[NF][4];
+      bool any = false;
+#pragma unroll
+      for (int l = 0; l < NF; ++l) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          u1[l][e] = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)buf[gq][e], 0u);
+          u2[l][e] = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)buf[gq][e], 0u);
+          const uint32_t lo = u1[l][e] < u2[l][e] ? u1[l][e] : u2[l][e];
+          pre[l][e] = ok[gq] & (lo <= pthr[l]);
+          any |= pre[l][e];
+        }
+      }
+      if (ballot64(any) != 0) {
+#pragma unroll
+        for (int l = 0; l < NF; ++l) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            blend_enqueue<NF>(q, qn, pre[l][e], buf[gq][e], (int32_t)(r + e - head), u1[l][e], u2[l][e], (uint32_t)l, thr, keys, kept);
+        }
+      }
+    }
+  }
+  {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
+    const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
+    const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
+    int32_t t = 0;
+    if (valid) t = p[pos];
+#pragma unroll
+    for (int l = 0; l < NF; ++l) {
+      const uint32_t a = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)t, 0u);
+      const uint32_t b = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)t, 0u);
+      blend_enqueue<NF>(q, qn, valid && (a < b ? a : b) <= pthr[l], t, (int32_t)(pos - head), a, b, (uint32_t)l, thr, keys, kept);
+    }
+  }
+  if (qn != 0) blend_eval<NF>(q, qn, thr, keys, kept);
+  __builtin_amdgcn_wave_barrier();
+}
+
 // Scan pass.  Each wave takes `lists_per_wave` consecutive destinations; their records are fetched by one coalesced
 // load (lane i holds record i), so the pointer chase destination -> list start is paid once per wave.
 template <bool BLEND, int VEC, int NF>
 __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict__ g_indices, const Segment* __restrict__ seg,
-                                                       const uint32_t* __restrict__ thr_all, int64_t n, int lists_per_wave,
-                                                       FusedKeys keys, uint32_t stage_cap, ScanOut out, Ctl* ctl) {
+                                                       const uint32_t* __restrict__ thr_all, const uint32_t* __restrict__ pthr_all,
+                                                       int64_t n, int lists_per_wave, FusedKeys keys, uint32_t stage_cap, ScanOut out,
+                                                       Ctl* ctl) {
+  __shared__ BlendQueue queues[BLEND && VEC == 4 ? kWavesPerBlock : 1];
   const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + uniform_wave_in_block();
   const int64_t first = wave * lists_per_wave;
   if (first >= n) return;
@@ -199,13 +358,16 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
   const int64_t mine = first + lane;
   const bool has = (int)lane < lists_per_wave && mine < n;
   Segment g{0, 0, 0};
-  uint32_t my_thr[NF];
+  uint32_t my_thr[NF], my_pthr[NF];
 #pragma unroll
-  for (int l = 0; l < NF; ++l) my_thr[l] = kAllThr;
+  for (int l = 0; l < NF; ++l) { my_thr[l] = kAllThr; my_pthr[l] = kAllThr; }
   if (has) {
     g = seg[mine];
 #pragma unroll
-    for (int l = 0; l < NF; ++l) my_thr[l] = thr_all[(int64_t)l * n + mine];
+    for (int l = 0; l < NF; ++l) {
+      my_thr[l] = thr_all[(int64_t)l * n + mine];
+      if (BLEND) my_pthr[l] = pthr_all[(int64_t)l * n + mine];
+    }
   }
   const uint32_t beg_lo = (uint32_t)g.beg, beg_hi = (uint32_t)((uint64_t)g.beg >> 32);
   uint32_t my_count[NF];
@@ -225,7 +387,14 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
     }
     if (VEC == 4 && !any_all && d > (uint32_t)kWave) {
       KeptRegs kept[NF];
-      labor_scan_fast<BLEND, NF>(g_indices, beg, d, thr, keys, kept);
+      if constexpr (BLEND) {
+        uint32_t pthr[NF];
+#pragma unroll
+        for (int l = 0; l < NF; ++l) pthr[l] = (uint32_t)__builtin_amdgcn_readlane((int)my_pthr[l], i);
+        labor_scan_fast_blend<NF>(g_indices, beg, d, thr, pthr, keys, &queues[uniform_wave_in_block()], kept);
+      } else {
+        labor_scan_fast<BLEND, NF>(g_indices, beg, d, thr, keys, kept);
+      }
 #pragma unroll
       for (int l = 0; l < NF; ++l) {
         kept[l].flush(lane, out.stage[l] + (size_t)(first + i) * stage_cap, stage_cap);
@@ -295,13 +464,13 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int32_t* _
 }
 
 template <bool BLEND, int VEC>
-static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, int64_t n,
+static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, const uint32_t* pthr, int64_t n,
                         int lpw, const FusedKeys& keys, uint32_t cap, const ScanOut& out, Ctl* ctl) {
   switch (nf) {
-    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, n, lpw, keys, cap, out, ctl); break;
-    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, n, lpw, keys, cap, out, ctl); break;
-    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, n, lpw, keys, cap, out, ctl); break;
-    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, n, lpw, keys, cap, out, ctl); break;
+    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl); break;
+    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl); break;
+    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl); break;
+    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl); break;
   }
 }
 
@@ -330,6 +499,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
   const int64_t n_new = ps.n_new;
   ps.seg = alloc.get<Segment>(n_new, COOP_TAG_SCRATCH);
   ps.thr = alloc.get<uint32_t>(n_new * ps.nf, COOP_TAG_SCRATCH);
+  uint32_t* pthr = cx.blend ? alloc.get<uint32_t>(n_new * ps.nf, COOP_TAG_SCRATCH) : nullptr;
   for (int f = 0; f < ps.nf; ++f) {
     ps.stage[f] = alloc.get<StageEntry>(n_new * (int64_t)cap, COOP_TAG_SCRATCH);
     ps.cnt[f] = alloc.get<int32_t>(n_new, COOP_TAG_SCRATCH);
@@ -349,7 +519,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
   }
   if (n_new > 0) {
     COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
-                dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, cx.d_ctl);
+                dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, (1.0 - 1e-6) / (cx.cw + cx.sw), cx.d_ctl);
     // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
     int lpw = g_lists_per_wave;
     if (lpw == 0) lpw = n_new >= 65536 ? 4 : 1;
@@ -358,11 +528,11 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     ScanOut out{};
     for (int f = 0; f < ps.nf; ++f) { out.stage[f] = ps.stage[f]; out.cnt[f] = ps.cnt[f]; }
     if (cx.blend) {
-      if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, n_new, lpw, keys, cap, out, cx.d_ctl);
-      else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, n_new, lpw, keys, cap, out, cx.d_ctl);
+      if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl);
+      else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl);
     } else {
-      if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, n_new, lpw, keys, cap, out, cx.d_ctl);
-      else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, n_new, lpw, keys, cap, out, cx.d_ctl);
+      if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl);
+      else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl);
     }
   }
 
