@@ -23,31 +23,114 @@ __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__
 
 constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list can be subsampled
 
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+constexpr int kNsGroups = 4;  // 16-byte groups per lane and step of the fast traversal
+
+// One pass over the list [beg, beg + d): every neighbour whose variate is <= bound is appended to the candidate
+// arrays (variate, list position) in LDS, in no particular order; returns how many qualified (entries beyond `cap`
+// are counted but not stored).  Long lists in a 16-byte aligned array are read as aligned groups of four entries,
+// kNsGroups groups per lane and step, whole groups in the main loop and the ragged ends in one extra step.
+template <bool BLEND, bool VEC4>
+__device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t bound,
+                                               const VariateParams& vp, uint32_t sigma_a, uint32_t sigma_b,
+                                               uint32_t* __restrict__ cand_r, uint32_t* __restrict__ cand_j, uint32_t cap) {
+  const uint32_t lane = (uint32_t)lane_id();
+  uint32_t n_c = 0;
+  auto append = [&](bool in, uint32_t r, uint32_t j) {
+    const uint64_t mask = ballot64(in);
+    if (mask == 0) return;
+    const uint32_t p = n_c + lanes_below(mask);
+    if (in && p < cap) { cand_r[p] = r; cand_j[p] = j; }
+    n_c += (uint32_t)__popcll(mask);
+  };
+  if (!VEC4 || d <= (uint32_t)kWave) {
+    for (uint32_t base = 0; base < d; base += kWave) {
+      const uint32_t j = base + lane;
+      uint32_t r = 0;
+      bool in = false;
+      if (j < d) {
+        r = variate<true, BLEND>(vp, (uint32_t)g_indices[beg + j], sigma_a, sigma_b);
+        in = r <= bound;
+      }
+      append(in, r, j);
+    }
+    return n_c;
+  }
+  constexpr uint32_t kStep = kWave * 4 * kNsGroups;
+  const int64_t abeg = beg & ~(int64_t)3;        // first aligned group
+  const uint32_t head = (uint32_t)(beg - abeg);  // entries of that group that precede the list
+  const uint32_t total = head + d;               // list end, relative to abeg
+  const uint32_t vec_end = total & ~3u;          // whole groups end here
+  const uint32_t vec_beg = head ? 4u : 0u;       // whole groups start here
+  const int32_t* __restrict__ p = g_indices + abeg;
+  for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
+    i32x4 buf[kNsGroups];
+    bool ok[kNsGroups];
+#pragma unroll
+    for (int gq = 0; gq < kNsGroups; ++gq) {
+      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
+      ok[gq] = r < vec_end;
+      buf[gq] = i32x4{0, 0, 0, 0};
+      if (ok[gq]) buf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+    }
+#pragma unroll
+    for (int gq = 0; gq < kNsGroups; ++gq) {
+      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
+      uint32_t R[4];
+      bool in[4];
+      bool any = false;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        R[e] = variate<true, BLEND>(vp, (uint32_t)buf[gq][e], sigma_a, sigma_b);
+        in[e] = ok[gq] & (R[e] <= bound);
+        any |= in[e];
+      }
+      if (ballot64(any) != 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) append(in[e], R[e], r + e - head);
+      }
+    }
+  }
+  {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
+    const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
+    const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
+    uint32_t r = 0;
+    bool in = false;
+    if (valid) {
+      r = variate<true, BLEND>(vp, (uint32_t)p[pos], sigma_a, sigma_b);
+      in = r <= bound;
+    }
+    append(in, r, pos - head);
+  }
+  return n_c;
+}
+
 // Selection of the k smallest (R, j) among d > k neighbours, one wave per destination:
-//   1. one pass over the list keeps, in LDS and in adjacency order, the candidates with R <= bound, where bound is
-//      chosen so that about `target` of them are expected (target > k, target < cap);
+//   1. one pass over the list collects, in LDS, the candidates with R <= bound, where bound is chosen so that about
+//      `target` of them are expected (target > k, target < cap);
 //   2. if fewer than k or more than cap candidates turn up, the bound is bisected and the pass repeated (rare);
-//   3. each candidate's rank among the candidates is counted; ranks below k are emitted, still in adjacency order.
-template <bool BLEND>
+//   3. every candidate's rank by (R, j) among the candidates is counted: ranks below k are kept;
+//   4. every kept candidate's place is the number of kept candidates in front of it in the list.
+template <bool BLEND, bool VEC4>
 __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ g_indptr,
                                                     const int32_t* __restrict__ g_indices,
                                                     const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
                                                     uint32_t cap, uint32_t target, int waves_per_block, VariateParams vp,
                                                     const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
                                                     int64_t* __restrict__ eid, Ctl* ctl) {
-  extern __shared__ uint64_t lds_keys[];  // per wave: cap variates (u32) followed by cap list positions (u32)
-  const int wib = wave_in_block();
+  extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags
+  const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
   const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
   if (w >= n_dst) return;
-  const int lane = lane_id();
-  int64_t o = eptr[w];
+  const uint32_t lane = (uint32_t)lane_id();
+  const int64_t o = eptr[w];
   if (o == eptr[w + 1]) return;
   const int32_t s = dst[w];
   const int64_t beg = g_indptr[s];
-  const int64_t d = g_indptr[s + 1] - beg;
-  if (d <= (int64_t)k) {
-    for (int64_t j = lane; j < d; j += kWave) {
+  const uint32_t d = (uint32_t)(g_indptr[s + 1] - beg);
+  if (d <= k) {
+    for (uint32_t j = lane; j < d; j += kWave) {
       col_global[o + j] = g_indices[beg + j];
       eid[o + j] = beg + j;
     }
@@ -57,31 +140,19 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
     if (lane == 0) atomicOr(&ctl->err_capacity, 1);
     return;
   }
-  uint32_t* cand_r = (uint32_t*)(lds_keys + (size_t)wib * cap);  // [cap] variates
-  uint32_t* cand_j = cand_r + cap;                               // [cap] positions (d < 2^31)
+  uint32_t* cand_r = lds_words + (size_t)wib * cap * 3;  // [cap] variates
+  uint32_t* cand_j = cand_r + cap;                       // [cap] positions (d < 2^31)
+  uint32_t* cand_k = cand_j + cap;                       // [cap] 1 = among the k smallest
   const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)s);
   const uint32_t sigma_b = BLEND ? ns_sigma(vp.K.Kb, (uint32_t)s) : 0u;
 
   // bound such that E[#candidates] = target: R <= bound with probability (bound + 1) / 2^32
   uint64_t lo = 0, hi = 0xFFFFFFFFull;  // bisection bracket on the bound, used only after a failed pass
   uint64_t bound = ((uint64_t)target << 32) / (uint64_t)d;
-  if (bound > 0xFFFFFFFFull || (uint64_t)d <= cap) bound = 0xFFFFFFFFull;
+  if (bound > 0xFFFFFFFFull || d <= cap) bound = 0xFFFFFFFFull;
   uint32_t n_c = 0;
   for (int attempt = 0; attempt < 40; ++attempt) {
-    n_c = 0;
-    for (int64_t base = 0; base < d; base += kWave) {
-      const int64_t j = base + lane;
-      bool in = false;
-      uint32_t r = 0;
-      if (j < d) {
-        r = variate<true, BLEND>(vp, (uint32_t)g_indices[beg + j], sigma_a, sigma_b);
-        in = r <= (uint32_t)bound;
-      }
-      const uint64_t mask = ballot64(in);
-      const uint32_t p = n_c + lanes_below(mask);
-      if (in && p < cap) { cand_r[p] = r; cand_j[p] = (uint32_t)j; }
-      n_c += (uint32_t)__popcll(mask);
-    }
+    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, vp, sigma_a, sigma_b, cand_r, cand_j, cap);
     if (n_c >= k && n_c <= cap) break;
     // cannot be bracketed (more than cap - k equal variates): report instead of guessing
     if (n_c < k) {
@@ -93,6 +164,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
     }
     if (lo > hi) { n_c = 0; break; }
     bound = lo + (hi - lo) / 2;
+    __builtin_amdgcn_wave_barrier();
   }
   if (n_c < k || n_c > cap) {
     if (lane == 0) atomicOr(&ctl->err_capacity, 1);
@@ -100,28 +172,24 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
   }
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
-  // rank counting; candidates are in adjacency order, so ties on R are broken by list position for free
-  for (uint32_t base = 0; base < n_c; base += kWave) {
-    const uint32_t i = base + lane;
-    bool keep = false;
-    uint32_t my_j = 0;
-    if (i < n_c) {
-      const uint32_t my_r = cand_r[i];
-      my_j = cand_j[i];
-      uint32_t rank = 0;
-      for (uint32_t q = 0; q < n_c; ++q) {
-        const uint32_t r = cand_r[q];
-        rank += (r < my_r) || (r == my_r && q < i);
-      }
-      keep = rank < k;
+  for (uint32_t i = lane; i < n_c; i += kWave) {
+    const uint32_t my_r = cand_r[i], my_j = cand_j[i];
+    uint32_t rank = 0;
+    for (uint32_t q = 0; q < n_c; ++q) {
+      const uint32_t r = cand_r[q];
+      rank += (r < my_r) || (r == my_r && cand_j[q] < my_j);
     }
-    const uint64_t mask = ballot64(keep);
-    if (keep) {
-      const int64_t p = o + lanes_below(mask);
-      col_global[p] = g_indices[beg + my_j];
-      eid[p] = beg + my_j;
-    }
-    o += __popcll(mask);
+    cand_k[i] = rank < k;
+  }
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
+  for (uint32_t i = lane; i < n_c; i += kWave) {
+    if (!cand_k[i]) continue;
+    const uint32_t my_j = cand_j[i];
+    uint32_t place = 0;
+    for (uint32_t q = 0; q < n_c; ++q) place += cand_k[q] && cand_j[q] < my_j;
+    col_global[o + place] = g_indices[beg + my_j];
+    eid[o + place] = beg + my_j;
   }
 }
 
@@ -151,22 +219,25 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
   if (m > 0) {
-    // candidate buffer: cap >= 4k (power of two, at least 256); expected candidates: 3k + 24.  A fanout above
+    // candidate buffer: cap >= 4k (power of two, at least 256); expected candidates: 2k + 16.  A fanout above
     // kNsMaxSelect is served only while no degree exceeds it (the kernel reports the first that does).
     const uint32_t k_sel = k < kNsMaxSelect ? k : kNsMaxSelect;
     uint32_t cap = 256;
     while (cap < 4 * k_sel) cap <<= 1;
-    const uint32_t target = 3 * k_sel + 24;
+    const uint32_t target = 2 * k_sel + 16;
     int wpb = kWavesPerBlock;
-    while (wpb > 1 && (size_t)wpb * cap * 8 > 32768) wpb >>= 1;
-    const size_t shmem = (size_t)wpb * cap * 8;
+    while (wpb > 1 && (size_t)wpb * cap * 12 > 49152) wpb >>= 1;
+    const size_t shmem = (size_t)wpb * cap * 12;
     const dim3 grid(blocks_for(n_dst, wpb));
-    if (cx.blend)
-      COOP_LAUNCH(K_NS_FILL, k_ns_fill<true>, grid, dim3(kBlock), shmem, s, cx.g->indptr, cx.g->indices, dst, n_dst, k, cap, target, wpb,
-                  vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl);
-    else
-      COOP_LAUNCH(K_NS_FILL, k_ns_fill<false>, grid, dim3(kBlock), shmem, s, cx.g->indptr, cx.g->indices, dst, n_dst, k, cap, target, wpb,
-                  vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl);
+#define COOP_NS_ARGS cx.g->indptr, cx.g->indices, dst, n_dst, k, cap, target, wpb, vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl
+    if (cx.blend) {
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
+      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
+    } else {
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
+      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
+    }
+#undef COOP_NS_ARGS
   }
   return COOP_OK;
 }
