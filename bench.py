@@ -41,6 +41,12 @@ def main():
     ap.add_argument("--kappa", type=int, default=1)
     ap.add_argument("--sampler", default=None, choices=[None, "labor0", "ns"])
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--mode", default="step", choices=["step", "batch-sweep", "kappa-cache", "host-cache"],
+                    help="step: the benchmark contract (default).  batch-sweep: |S^l| against batch size on nested seed prefixes "
+                         "(products-shaped).  kappa-cache: LRU miss rate against kappa over consecutive dependent batches "
+                         "(papers100M-shaped, 4M-row cache).  host-cache: pinned-host feature table behind a 32M-row cache "
+                         "(mag240M-shaped), host-link bytes saved by kappa.")
+    ap.add_argument("--iters", type=int, default=None, help="iterations per kappa for the cache modes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a known-size reference for rocprofv3 --pmc byte counters)")
@@ -56,6 +62,8 @@ def main():
     import paper_2310_12403_amd as P
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.mode != "step":
+        return REPORTS[args.mode](args, torch, synth, P)
     dev = torch.device("cuda:0")
     cfg = dict(synth.CONFIGS[args.config])
     sampler_name = args.sampler or cfg["sampler"]
@@ -233,6 +241,152 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, indptr, indices, feat, get_seeds, fanouts, sampler, blocks, K, P)
     print(json.dumps(result), flush=True)
+
+
+def report_batch_sweep(args, torch, synth, P):
+    """|S^l| against batch size (Thm 3.1 / 3.2 and the paper's first experiment): products-shaped graph, 3-layer
+    LABOR-0, batches that are nested prefixes of one seed permutation, several permutations."""
+    import numpy as np
+    dev = torch.device("cuda:0")
+    name = "products" if args.config == "papers100M" else args.config
+    cfg = synth.CONFIGS[name]
+    indptr, indices = synth.make_graph(name, device=dev, scale_down=args.scale_down, log=log)
+    n = indptr.numel() - 1
+    graph = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE)
+    arena = P.Arena(2 << 30)
+    sizes = [1024, 4096, 16384, 65536]
+    perms = 8
+    acc = np.zeros((len(sizes), len(cfg["fanouts"])))
+    ms = np.zeros(len(sizes))
+    nested_ok = True
+    for p in range(perms):
+        perm = synth.permutation(n, 900 + p, device=dev).to(torch.int32)
+        prev_sets = None
+        for i, b in enumerate(sizes):
+            arena.reset()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            blocks = P.coop_sample(graph, perm[:b].contiguous(), cfg["fanouts"], P.COOP_LABOR0, it=p, kappa=1, seed=p, arena=arena)
+            torch.cuda.synchronize()
+            ms[i] += (time.perf_counter() - t) * 1e3
+            acc[i] += [blk.n_src for blk in blocks]
+            if p == 0:      # exact nestedness: the smaller batch's S^l is a subset of the larger batch's
+                sets = [blk.src_ids.clone() for blk in blocks]
+                if prev_sets is not None:
+                    for small, big in zip(prev_sets, sets):
+                        nested_ok = nested_ok and bool(torch.isin(small, big).all())
+                prev_sets = sets
+    acc /= perms
+    ms /= perms
+    ratio = acc / np.array(sizes)[:, None]
+    result = {"report": "batch-sweep", "workload": "%s-shaped Chung-Lu graph (%d vertices, %d directed edges), 3-layer LABOR-0 %s, kappa 1" % (
+                  name, n, indices.numel(), "/".join(map(str, cfg["fanouts"]))),
+              "batch_sizes": sizes, "mean_S_l": acc.round(1).tolist(), "S_l_per_seed": ratio.round(3).tolist(),
+              "work_per_seed_nonincreasing": bool((np.diff(ratio, axis=0) < 0).all()),
+              "increments_concave": bool((np.diff(acc, axis=0)[1:] <= 4 * np.diff(acc, axis=0)[:-1] * 1.02).all()),
+              "nested_exactly": nested_ok, "ms_per_batch": ms.round(3).tolist(), "permutations": perms}
+    print(json.dumps(result), flush=True)
+
+
+def _cache_run(args, torch, synth, P, graph, n, get_seeds, fanouts, table, cache_rows, dim, dtype, kappas, iters, check_iters):
+    from oracle import coopref as R
+    out_rows = None
+    res = {}
+    for kappa in kappas:
+        arena = P.Arena(6 << 30)
+        cache = P.Cache(cache_rows, n, dim, dtype, max_ids=16 << 20)
+        oracle = R.Cache(cache_rows, n) if check_iters else None
+        misses, totals, t_sample, t_gather, agree = [], [], 0.0, 0.0, True
+        for it in range(iters):
+            arena.reset()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            blocks = P.coop_sample(graph, get_seeds(it), fanouts, P.COOP_LABOR0, it=it, kappa=kappa, seed=0, arena=arena)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            ids = blocks[-1].src_ids
+            if out_rows is None or out_rows.shape[0] < ids.numel():
+                out_rows = torch.empty((int(ids.numel() * 1.3), dim), dtype=dtype, device=ids.device)
+            _, n_miss = cache.gather(table, ids, out=out_rows[:ids.numel()])
+            torch.cuda.synchronize()     # the miss rows may still be streaming in when the call returns
+            t2 = time.perf_counter()
+            if it >= iters // 4:
+                t_sample += t1 - t0
+                t_gather += t2 - t1
+            misses.append(n_miss)
+            totals.append(ids.numel())
+            if oracle is not None and it < check_iters:
+                want, _ = oracle.access(ids.cpu().numpy())
+                agree = agree and want == n_miss
+        tail = iters // 4
+        res[str(kappa)] = {"miss_rate_all": round(sum(misses) / sum(totals), 4),
+                           "miss_rate_steady": round(sum(misses[tail:]) / sum(totals[tail:]), 4),
+                           "mean_input_vertices": round(sum(totals) / iters, 1),
+                           "misses_per_iter_steady": round(sum(misses[tail:]) / (iters - tail), 1),
+                           "ms_sample_steady": round(t_sample / (iters - tail) * 1e3, 3),
+                           "ms_cache_gather_steady": round(t_gather / (iters - tail) * 1e3, 3),
+                           "oracle_lru_agrees_first_%d_iters" % check_iters: agree}
+        log("kappa %d: %s" % (kappa, json.dumps(res[str(kappa)])))
+        cache.close()
+        del cache, arena
+    return res
+
+
+def report_kappa_cache(args, torch, synth, P):
+    """LRU miss rate against kappa (Sec. 4.2): papers100M-shaped graph, LABOR-0 10/10/10, batch 16384, consecutive
+    dependent batches, 4M-row vertex cache in front of the HBM-resident feature table."""
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["papers100M"]
+    indptr, indices = synth.make_graph("papers100M", device=dev, scale_down=args.scale_down, log=log)
+    n = indptr.numel() - 1
+    graph = P.coop_graph_load(indptr, indices)
+    feat = synth.features(n, cfg["dim"], torch.float16, seed=0, device=dev)
+    get_seeds = synth.seed_batches(n, cfg["batch"], seed=0, device=dev)
+    iters = args.iters or 512
+    cache_rows = 4000000 // args.scale_down
+    res = _cache_run(args, torch, synth, P, graph, n, get_seeds, cfg["fanouts"], feat, cache_rows, cfg["dim"], torch.float16,
+                     (1, 16, 256), iters, check_iters=8)
+    print(json.dumps({"report": "kappa-cache", "workload": "papers100M-shaped graph (%d vertices, %d directed edges), 3-layer LABOR-0 "
+                      "10/10/10, batch %d, %d consecutive iterations per kappa, %d-row LRU cache, fp16 x %d rows in HBM; 'steady' skips "
+                      "the first quarter of the iterations" % (n, indices.numel(), cfg["batch"], iters, cache_rows, cfg["dim"]),
+                      "by_kappa": res}), flush=True)
+
+
+def report_host_cache(args, torch, synth, P):
+    """Pinned-host feature table behind an on-GPU cache: mag240M-shaped graph, LABOR-0 10/10/10, batch 32768, kappa 1 and 64.
+    The full fp16 x 768 table (375 GB) does not fit this machine's host memory: a shorter pinned table is aliased (vertex v
+    reads row v mod R) while the cache is keyed by v, so miss counts and bytes per miss are those of the full table."""
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["mag240M"]
+    indptr, indices = synth.make_graph("mag240M", device=dev, scale_down=args.scale_down, log=log)
+    n = indptr.numel() - 1
+    graph = P.coop_graph_load(indptr, indices)
+    R_rows = (32 << 20) // args.scale_down
+    log("pinned host table: %d rows x %d fp16 = %.1f GB" % (R_rows, cfg["dim"], R_rows * cfg["dim"] * 2 / 1e9))
+    table = torch.empty((R_rows, cfg["dim"]), dtype=torch.float16, pin_memory=True)
+    chunk = 1 << 19
+    g = torch.Generator(device=dev)
+    g.manual_seed(5)
+    for lo in range(0, R_rows, chunk):   # N(0,1) rows drawn on the GPU, copied down into the pinned table
+        rows = min(chunk, R_rows - lo)
+        table[lo:lo + rows].copy_(torch.randn((rows, cfg["dim"]), generator=g, device=dev).to(torch.float16))
+    get_seeds = synth.seed_batches(n, cfg["batch"], seed=0, device=dev)
+    iters = args.iters or 48
+    cache_rows = 32000000 // args.scale_down
+    res = _cache_run(args, torch, synth, P, graph, n, get_seeds, cfg["fanouts"], table, cache_rows, cfg["dim"], torch.float16,
+                     (1, 64), iters, check_iters=4)
+    row_bytes = cfg["dim"] * 2
+    for k, v in res.items():
+        v["host_link_GB_per_iter_steady"] = round(v["misses_per_iter_steady"] * row_bytes / 1e9, 4)
+        v["host_link_GBps_steady"] = round(v["misses_per_iter_steady"] * row_bytes / (v["ms_cache_gather_steady"] * 1e-3) / 1e9, 2)
+    saved = (res["1"]["misses_per_iter_steady"] - res["64"]["misses_per_iter_steady"]) * row_bytes / 1e9
+    print(json.dumps({"report": "host-cache", "workload": "mag240M-shaped graph (%d vertices, %d directed edges), 3-layer LABOR-0 "
+                      "10/10/10, batch %d, %d iterations per kappa, %d-row cache, fp16 x %d rows read from a %d-row pinned host table "
+                      "(aliased)" % (n, indices.numel(), cfg["batch"], iters, cache_rows, cfg["dim"], R_rows),
+                      "by_kappa": res, "host_link_GB_saved_per_iter_kappa64_vs_1": round(saved, 4)}), flush=True)
+
+
+REPORTS = {"batch-sweep": report_batch_sweep, "kappa-cache": report_kappa_cache, "host-cache": report_host_cache}
 
 
 def _stored_traffic(kernel, args):

@@ -156,16 +156,20 @@ int coop_cache_free(coop_cache* c);
 
 /*
  * out[i, :] = table[ids[i], :] through the cache.
- *   table      [n_vertices, dim] rows of the dtype given at creation: device memory, or pinned host memory
+ *   table      [table_rows, dim] rows of the dtype given at creation: device memory, or pinned host memory
  *              mapped into the device address space (read by the kernels directly, no staging copy)
+ *   table_rows rows in `table` (>= 1).  Vertex v reads row v mod table_rows: pass n_vertices for a full table; a
+ *              shorter table aliases rows (for benchmarks whose full table would not fit in host memory: miss
+ *              counts and bytes per miss are those of the full table)
  *   ids        device int32 [n_ids], DISTINCT, each in [0, n_vertices) (else COOP_E_RANGE); n_ids <= max_ids
  *              (else COOP_E_CAPACITY)
  *   out        device [n_ids, dim]
  *   n_miss_out host, number of ids that were not cached when the call started (may be NULL)
- * Synchronises `stream`.  Calls on one cache must not overlap.  After COOP_E_RANGE the in-range cached ids of the
+ * Returns once the hit / miss counts are known (it synchronises `stream` for that); the kernel that moves the miss
+ * rows may still be running on `stream` when it returns.  Calls on one cache must not overlap.  After COOP_E_RANGE the in-range cached ids of the
  * call count as touched and nothing was inserted; `out` is then unspecified.
  */
-int coop_cache_gather(coop_cache* c, const void* table, const int32_t* ids, int64_t n_ids, void* out,
+int coop_cache_gather(coop_cache* c, const void* table, int64_t table_rows, const int32_t* ids, int64_t n_ids, void* out,
                       int64_t* n_miss_out, void* stream);
 
 /* Device-side address of pinned (page-locked, mapped) host memory, for use as `table` / `feat` above.

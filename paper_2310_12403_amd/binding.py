@@ -58,7 +58,7 @@ def lib():
                                     C.POINTER(C.c_void_p)]
     L.coop_cache_create.restype = C.c_int
     L.coop_cache_free.argtypes = [C.c_void_p]
-    L.coop_cache_gather.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]
+    L.coop_cache_gather.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]
     L.coop_cache_gather.restype = C.c_int
     L.coop_cache_vertices.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
     L.coop_cache_vertices.restype = C.c_int
@@ -278,7 +278,7 @@ class Cache:
         if out is None:
             out = torch.empty((ids.numel(), self.dim), dtype=self.dtype, device=ids.device)
         n_miss = C.c_int64()
-        rc = lib().coop_cache_gather(self.handle, C.c_void_p(self._table_ptr(table)), _dev_ptr(ids, torch.int32), ids.numel(),
+        rc = lib().coop_cache_gather(self.handle, C.c_void_p(self._table_ptr(table)), table.shape[0], _dev_ptr(ids, torch.int32), ids.numel(),
                                      C.c_void_p(out.data_ptr()), C.byref(n_miss), _stream_ptr(stream))
         _check(rc)
         return out, n_miss.value

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
                                                          V* __restrict__ rows, int32_t* __restrict__ slot_of,
                                                          int32_t* __restrict__ vertex_of, uint64_t* __restrict__ stamp,
                                                          const int32_t* __restrict__ free_list, int64_t n_free, int64_t n_miss,
-                                                         int64_t n_ins, uint64_t clock_miss) {
+                                                         int64_t n_ins, uint64_t clock_miss, int64_t table_rows) {
   const int lpr = 1 << lpr_log2;
   const int rows_per_block = kBlock >> lpr_log2;
   const int sub = threadIdx.x & (lpr - 1);
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
     if (r < n_ids && slot_i[r] < 0) {
       const int32_t id = ids[r];
       if (id >= 0) {  // ids out of range were reported by the lookup; negative ones are skipped here
-        src[u] = id;
+        src[u] = id < table_rows ? id : id % table_rows;
         const int64_t rank_m = r - (int64_t)rank_h[r];
         const int64_t q = rank_m - (n_miss - n_ins);  // the last n_ins misses enter the cache
         if (q >= 0) {
@@ -324,8 +324,8 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 template <typename V>
-void launch_rows(coop_cache* c, const void* table, const int32_t* ids, int64_t n_ids, void* out, int64_t n_free, int64_t n_miss,
-                 int64_t n_ins, int64_t n_hit, bool hits, hipStream_t s) {
+void launch_rows(coop_cache* c, const void* table, int64_t table_rows, const int32_t* ids, int64_t n_ids, void* out, int64_t n_free,
+                 int64_t n_miss, int64_t n_ins, int64_t n_hit, bool hits, hipStream_t s) {
   const int32_t vecs = (int32_t)(c->row_bytes / (int64_t)sizeof(V));
   int lpr_log2 = 0;
   while ((1 << lpr_log2) < vecs && lpr_log2 < 8) ++lpr_log2;
@@ -337,23 +337,24 @@ void launch_rows(coop_cache* c, const void* table, const int32_t* ids, int64_t n
   else
     COOP_LAUNCH(K_CACHE_UPDATE, k_cache_misses<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)table, vecs, lpr_log2, ids, c->slot_i,
                 c->rank_h, n_ids, (V*)out, (V*)c->rows, c->slot_of, c->vertex_of, c->stamp, c->free_list, n_free, n_miss, n_ins,
-                c->clock + (uint64_t)n_hit);
+                c->clock + (uint64_t)n_hit, table_rows);
 }
 
-void dispatch_rows(coop_cache* c, int vec_bytes, const void* table, const int32_t* ids, int64_t n_ids, void* out, int64_t n_free,
-                   int64_t n_miss, int64_t n_ins, int64_t n_hit, bool hits, hipStream_t s) {
+void dispatch_rows(coop_cache* c, int vec_bytes, const void* table, int64_t table_rows, const int32_t* ids, int64_t n_ids, void* out,
+                   int64_t n_free, int64_t n_miss, int64_t n_ins, int64_t n_hit, bool hits, hipStream_t s) {
   switch (vec_bytes) {
-    case 16: launch_rows<u32x4>(c, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
-    case 8: launch_rows<u32x2>(c, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
-    case 4: launch_rows<uint32_t>(c, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
-    default: launch_rows<uint16_t>(c, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
+    case 16: launch_rows<u32x4>(c, table, table_rows, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
+    case 8: launch_rows<u32x2>(c, table, table_rows, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
+    case 4: launch_rows<uint32_t>(c, table, table_rows, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
+    default: launch_rows<uint16_t>(c, table, table_rows, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, hits, s); break;
   }
 }
 }  // namespace
 
-extern "C" int coop_cache_gather(coop_cache* c, const void* table, const int32_t* ids, int64_t n_ids, void* out,
+extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table_rows, const int32_t* ids, int64_t n_ids, void* out,
                                  int64_t* n_miss_out, void* stream) {
   if (!c) return COOP_E_NULL;
+  if (table_rows < 1) return COOP_E_ARG;
   if (n_ids < 0 || n_ids > c->max_ids) return COOP_E_CAPACITY;
   if (n_miss_out) *n_miss_out = 0;
   if (n_ids == 0) return COOP_OK;
@@ -370,7 +371,7 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, const int32_t
   scan_bits_to_u32(c->hit_bits, n_ids, c->rank_h, &c->d_ctl->n_hit, c->scan_tmp, s);
   COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
   // 2. hits: rows out of the cache, new stamps (runs while the host waits for the counts)
-  dispatch_rows(c, vec_bytes, table, ids, n_ids, out, 0, 0, 0, 0, true, s);
+  dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, 0, 0, 0, 0, true, s);
   COOP_HIP_TRY(hipStreamSynchronize(s));
   if (c->h_ctl->err_range) {
     // the cached ids of this call were already served and re-stamped: keep the stamps unique, insert nothing
@@ -414,7 +415,7 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, const int32_t
   }
 
   // 4. misses: rows from the backing table to `out`, the last n_ins of them also into free slots
-  if (n_miss > 0) dispatch_rows(c, vec_bytes, table, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, false, s);
+  if (n_miss > 0) dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, n_free, n_miss, n_ins, n_hit, false, s);
   c->size += n_ins;
   c->clock = clock_after;
 
