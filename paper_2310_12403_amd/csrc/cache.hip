@@ -8,8 +8,9 @@
 //     inserted misses  = the last min(M, capacity) misses,
 //     evicted entries  = the E = max(0, size + min(M, capacity) - capacity) smallest stamps among current entries
 //                        (hits were just re-stamped, so they go last).
-// The E-th smallest stamp is found exactly by a most-significant-digit radix select over the stamp array (12 bits
-// per pass; all live stamps lie in [previous eviction threshold, clock), so two or three passes are typical).
+// The E-th smallest stamp is found exactly by a most-significant-digit radix select over the stamp array (up to 13
+// bits per pass, the bits of the live range split evenly over the passes; all live stamps lie in [previous eviction
+// threshold, clock), so two passes are typical).
 //
 // Data layout: slot_of[n_vertices] (int32, -1 = not cached), vertex_of[capacity], stamp[capacity] (0 = free),
 // rows[capacity][row_bytes], free_list[capacity] (stack of free slots).  Which free slot a miss lands in is
@@ -21,7 +22,7 @@
 
 namespace coop {
 
-constexpr int kSelBits = 12;
+constexpr int kSelBits = 13;  // most bits per radix-select pass (8192 LDS counters)
 constexpr int kSelBins = 1 << kSelBits;
 constexpr int kRowUnroll = 2;
 
@@ -51,28 +52,42 @@ __global__ __launch_bounds__(kBlock) void k_cache_lookup(const int32_t* __restri
   if (lane_id() == 0 && (i & ~(int64_t)63) < n_ids) hit_bits[i >> 6] = b;
 }
 
+// order[r] = index of the r-th hit for r < n_hit; order[n_ids - 1 - q] = index of the q-th miss: the row movers then
+// run over dense lists of hits and of misses instead of idling through the other kind
+__global__ __launch_bounds__(kBlock) void k_cache_split(const int32_t* __restrict__ slot_i, const uint32_t* __restrict__ rank_h,
+                                                        int64_t n_ids, int32_t* __restrict__ order) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n_ids) return;
+  const int64_t h = rank_h[i];
+  if (slot_i[i] >= 0) order[h] = (int32_t)i;
+  else order[n_ids - 1 - (i - h)] = (int32_t)i;
+}
+
 // ---- row movers -----------------------------------------------------------------------------------------------
 // Rows are moved by lpr = 2^lpr_log2 adjacent lanes, V-sized vectors, kRowUnroll rows per thread in flight.
 template <typename V>
 __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ rows, int32_t vecs, int lpr_log2,
-                                                       const int32_t* __restrict__ slot_i, const uint32_t* __restrict__ rank_h,
-                                                       int64_t n_ids, V* __restrict__ out, uint64_t* __restrict__ stamp,
-                                                       uint64_t clock) {
+                                                       const int32_t* __restrict__ slot_i, const int32_t* __restrict__ order,
+                                                       const CacheCtl* __restrict__ ctl, V* __restrict__ out,
+                                                       uint64_t* __restrict__ stamp, uint64_t clock) {
+  const int64_t n_hit = ctl->n_hit;  // known on the device before the host has read it
   const int lpr = 1 << lpr_log2;
   const int rows_per_block = kBlock >> lpr_log2;
   const int sub = threadIdx.x & (lpr - 1);
   const int64_t row0 = ((int64_t)blockIdx.x * kRowUnroll) * rows_per_block + (threadIdx.x >> lpr_log2);
-  int64_t src[kRowUnroll];
+  if ((int64_t)blockIdx.x * kRowUnroll * rows_per_block >= n_hit) return;
+  int64_t src[kRowUnroll], dst[kRowUnroll];
 #pragma unroll
   for (int u = 0; u < kRowUnroll; ++u) {
-    const int64_t r = row0 + (int64_t)u * rows_per_block;
+    const int64_t r = row0 + (int64_t)u * rows_per_block;  // r-th hit
     src[u] = -1;
-    if (r < n_ids) {
-      const int32_t slot = slot_i[r];
-      if (slot >= 0) {
-        src[u] = slot;
-        if (sub == 0) stamp[slot] = clock + rank_h[r];
-      }
+    dst[u] = 0;
+    if (r < n_hit) {
+      const int32_t i = order[r];
+      const int32_t slot = slot_i[i];
+      src[u] = slot;
+      dst[u] = i;
+      if (sub == 0) stamp[slot] = clock + (uint64_t)r;
     }
   }
   for (int32_t v = sub; v < vecs; v += lpr) {
@@ -81,36 +96,36 @@ __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ row
     for (int u = 0; u < kRowUnroll; ++u)
       if (src[u] >= 0) x[u] = rows[src[u] * vecs + v];
 #pragma unroll
-    for (int u = 0; u < kRowUnroll; ++u) {
-      const int64_t r = row0 + (int64_t)u * rows_per_block;
-      if (src[u] >= 0) __builtin_nontemporal_store(x[u], out + r * vecs + v);
-    }
+    for (int u = 0; u < kRowUnroll; ++u)
+      if (src[u] >= 0) __builtin_nontemporal_store(x[u], out + dst[u] * vecs + v);
   }
 }
 
 template <typename V>
 __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ table, int32_t vecs, int lpr_log2,
-                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ slot_i,
-                                                         const uint32_t* __restrict__ rank_h, int64_t n_ids, V* __restrict__ out,
-                                                         V* __restrict__ rows, int32_t* __restrict__ slot_of,
-                                                         int32_t* __restrict__ vertex_of, uint64_t* __restrict__ stamp,
-                                                         const int32_t* __restrict__ free_list, int64_t n_free, int64_t n_miss,
-                                                         int64_t n_ins, uint64_t clock_miss, int64_t table_rows) {
+                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ order,
+                                                         int64_t n_ids, V* __restrict__ out, V* __restrict__ rows,
+                                                         int32_t* __restrict__ slot_of, int32_t* __restrict__ vertex_of,
+                                                         uint64_t* __restrict__ stamp, const int32_t* __restrict__ free_list,
+                                                         int64_t n_free, int64_t n_miss, int64_t n_ins, uint64_t clock_miss,
+                                                         int64_t table_rows) {
   const int lpr = 1 << lpr_log2;
   const int rows_per_block = kBlock >> lpr_log2;
   const int sub = threadIdx.x & (lpr - 1);
   const int64_t row0 = ((int64_t)blockIdx.x * kRowUnroll) * rows_per_block + (threadIdx.x >> lpr_log2);
-  int64_t src[kRowUnroll], dst_slot[kRowUnroll];
+  int64_t src[kRowUnroll], dst[kRowUnroll], dst_slot[kRowUnroll];
 #pragma unroll
   for (int u = 0; u < kRowUnroll; ++u) {
-    const int64_t r = row0 + (int64_t)u * rows_per_block;
+    const int64_t rank_m = row0 + (int64_t)u * rows_per_block;  // rank_m-th miss
     src[u] = -1;
+    dst[u] = 0;
     dst_slot[u] = -1;
-    if (r < n_ids && slot_i[r] < 0) {
-      const int32_t id = ids[r];
+    if (rank_m < n_miss) {
+      const int32_t i = order[n_ids - 1 - rank_m];
+      const int32_t id = ids[i];
       if (id >= 0) {  // ids out of range were reported by the lookup; negative ones are skipped here
         src[u] = id < table_rows ? id : id % table_rows;
-        const int64_t rank_m = r - (int64_t)rank_h[r];
+        dst[u] = i;
         const int64_t q = rank_m - (n_miss - n_ins);  // the last n_ins misses enter the cache
         if (q >= 0) {
           const int32_t slot = free_list[n_free - 1 - q];
@@ -131,9 +146,8 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
       if (src[u] >= 0) x[u] = __builtin_nontemporal_load(table + src[u] * vecs + v);
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u) {
-      const int64_t r = row0 + (int64_t)u * rows_per_block;
       if (src[u] >= 0) {
-        __builtin_nontemporal_store(x[u], out + r * vecs + v);
+        __builtin_nontemporal_store(x[u], out + dst[u] * vecs + v);
         if (dst_slot[u] >= 0) rows[dst_slot[u] * vecs + v] = x[u];
       }
     }
@@ -142,7 +156,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
 
 // ---- eviction: radix select of the E-th smallest stamp, then sweep -----------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_cache_sel_hist(const uint64_t* __restrict__ stamp, int64_t capacity, uint64_t base,
-                                                           int shift, int prev_shift, const CacheCtl* __restrict__ ctl,
+                                                           int shift, int bits, int prev_shift, const CacheCtl* __restrict__ ctl,
                                                            uint32_t* __restrict__ hist) {
   __shared__ uint32_t lh[kSelBins];
   for (int b = threadIdx.x; b < kSelBins; b += kBlock) lh[b] = 0;
@@ -155,7 +169,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_sel_hist(const uint64_t* __res
     if (st == 0) continue;
     const uint64_t x = st - base;
     if (prev_shift >= 0 && (x >> prev_shift) != prefix) continue;
-    atomicAdd(&lh[(x >> shift) & (kSelBins - 1)], 1u);
+    atomicAdd(&lh[(x >> shift) & ((1u << bits) - 1)], 1u);
   }
   __syncthreads();
   for (int b = threadIdx.x; b < kSelBins; b += kBlock) {
@@ -165,9 +179,9 @@ __global__ __launch_bounds__(kBlock) void k_cache_sel_hist(const uint64_t* __res
 }
 
 // one block: the bin that holds the `remaining`-th entry; extends the prefix, clears the histogram
-__global__ __launch_bounds__(kBlock) void k_cache_sel_pick(uint32_t* __restrict__ hist, CacheCtl* ctl) {
+__global__ __launch_bounds__(kBlock) void k_cache_sel_pick(uint32_t* __restrict__ hist, int bits, CacheCtl* ctl) {
   __shared__ uint64_t part[kBlock];
-  constexpr int per = kSelBins / kBlock;  // 16 consecutive bins per thread
+  constexpr int per = kSelBins / kBlock;  // consecutive bins per thread
   uint64_t s = 0;
   for (int j = 0; j < per; ++j) s += hist[threadIdx.x * per + j];
   part[threadIdx.x] = s;
@@ -178,32 +192,68 @@ __global__ __launch_bounds__(kBlock) void k_cache_sel_pick(uint32_t* __restrict_
     while (t < kBlock - 1 && cum + part[t] < remaining) { cum += part[t]; ++t; }
     int b = t * per;
     while (b < t * per + per - 1 && cum + hist[b] < remaining) { cum += hist[b]; ++b; }
-    ctl->prefix = (ctl->prefix << kSelBits) | (uint64_t)b;
+    ctl->prefix = (ctl->prefix << bits) | (uint64_t)b;
     ctl->remaining = remaining - cum;
   }
   __syncthreads();
   for (int j = 0; j < per; ++j) hist[threadIdx.x * per + j] = 0;
 }
 
-// evicts every entry with stamp - base <= threshold (or every entry, if evict_all)
+// Evicts every entry with stamp - base <= threshold (or every entry, if evict_all) and pushes the freed slots on the
+// free list.  Each block owns a contiguous chunk of slots: it first counts its evictions, reserves that many free-list
+// places with ONE atomic, then sweeps the chunk again handing out the places by ballot and a running offset.
 __global__ __launch_bounds__(kBlock) void k_cache_evict(uint64_t* __restrict__ stamp, int32_t* __restrict__ vertex_of,
                                                         int32_t* __restrict__ slot_of, int32_t* __restrict__ free_list,
-                                                        int64_t capacity, uint64_t base, bool evict_all, int64_t n_free,
-                                                        CacheCtl* ctl) {
+                                                        int64_t capacity, int64_t chunk, uint64_t base, bool evict_all,
+                                                        int64_t n_free, CacheCtl* ctl) {
+  __shared__ int32_t wave_cnt[kWavesPerBlock];
+  __shared__ int32_t block_base;
   const uint64_t thr = ctl->prefix;
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const int64_t stride = (int64_t)gridDim.x * kBlock;
-  for (; i < capacity; i += stride) {
+  const int64_t lo = (int64_t)blockIdx.x * chunk;
+  const int64_t hi = lo + chunk < capacity ? lo + chunk : capacity;
+  const int lane = lane_id(), wib = wave_in_block();
+  auto is_out = [&](int64_t i) {
+    if (i >= hi) return false;
     const uint64_t st = stamp[i];
-    if (st == 0) continue;
-    if (evict_all || st - base <= thr) {
+    return st != 0 && (evict_all || st - base <= thr);
+  };
+  // pass 1: how many
+  int32_t mine = 0;
+  for (int64_t i = lo + threadIdx.x; i < hi; i += kBlock) mine += is_out(i);
+  mine = (int32_t)wave_sum_i64(mine);
+  if (lane == 0) wave_cnt[wib] = mine;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int32_t total = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) total += wave_cnt[w];
+    block_base = total ? atomicAdd(&ctl->n_push, total) : 0;
+  }
+  __syncthreads();
+  int64_t run = n_free + block_base;
+  // pass 2: hand out the places (chunk is a multiple of the block size, so every thread runs every round)
+  for (int64_t r = lo; r < hi; r += kBlock) {
+    const int64_t i = r + threadIdx.x;
+    const bool out = is_out(i);
+    const uint64_t mask = ballot64(out);
+    __syncthreads();
+    if (lane == 0) wave_cnt[wib] = (int32_t)__popcll(mask);
+    __syncthreads();
+    int32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+      const int32_t cw = wave_cnt[w];
+      if (w < wib) before += cw;
+      total += cw;
+    }
+    if (out) {
       const int32_t v = vertex_of[i];
       slot_of[v] = -1;
       vertex_of[i] = -1;
       stamp[i] = 0;
-      const int32_t p = atomicAdd(&ctl->n_push, 1);
-      if (n_free + p < capacity) free_list[n_free + p] = (int32_t)i;  // always true: exactly n_evict entries qualify
+      const int64_t p = run + before + (int64_t)lanes_below(mask);
+      if (p < capacity) free_list[p] = (int32_t)i;  // always true: exactly n_evict entries qualify
     }
+    run += total;
   }
 }
 
@@ -235,6 +285,7 @@ struct coop_cache {
   int32_t* slot_i;
   uint64_t* hit_bits;
   uint32_t* rank_h;
+  int32_t* order;         // hits from the front, misses from the back
   void* scan_tmp;
   uint32_t* hist;
   CacheCtl* d_ctl;
@@ -274,6 +325,7 @@ extern "C" int coop_cache_create(int64_t capacity_rows, int64_t n_vertices, int3
   c->slot_i = alloc.get<int32_t>(max_ids, COOP_TAG_OUTPUT);
   c->hit_bits = alloc.get<uint64_t>((max_ids + 63) / 64, COOP_TAG_OUTPUT);
   c->rank_h = alloc.get<uint32_t>(max_ids, COOP_TAG_OUTPUT);
+  c->order = alloc.get<int32_t>(max_ids, COOP_TAG_OUTPUT);
   c->scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(max_ids), COOP_TAG_OUTPUT);
   c->hist = alloc.get<uint32_t>(kSelBins, COOP_TAG_OUTPUT);
   c->d_ctl = alloc.get<CacheCtl>(1, COOP_TAG_OUTPUT);
@@ -331,13 +383,15 @@ void launch_rows(coop_cache* c, const void* table, int64_t table_rows, const int
   while ((1 << lpr_log2) < vecs && lpr_log2 < 8) ++lpr_log2;
   const int64_t rows_per_launch_block = (int64_t)(kBlock >> lpr_log2) * kRowUnroll;
   const unsigned grid = (unsigned)((n_ids + rows_per_launch_block - 1) / rows_per_launch_block);
-  if (hits)
-    COOP_LAUNCH(K_CACHE_GATHER, k_cache_hits<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)c->rows, vecs, lpr_log2, c->slot_i,
-                c->rank_h, n_ids, (V*)out, c->stamp, c->clock);
-  else
-    COOP_LAUNCH(K_CACHE_UPDATE, k_cache_misses<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)table, vecs, lpr_log2, ids, c->slot_i,
-                c->rank_h, n_ids, (V*)out, (V*)c->rows, c->slot_of, c->vertex_of, c->stamp, c->free_list, n_free, n_miss, n_ins,
+  if (hits) {
+    COOP_LAUNCH(K_CACHE_GATHER, k_cache_hits<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)c->rows, vecs, lpr_log2, c->slot_i, c->order,
+                c->d_ctl, (V*)out, c->stamp, c->clock);
+  } else {
+    const unsigned grid_m = (unsigned)((n_miss + rows_per_launch_block - 1) / rows_per_launch_block);
+    COOP_LAUNCH(K_CACHE_UPDATE, k_cache_misses<V>, dim3(grid_m), dim3(kBlock), 0, s, (const V*)table, vecs, lpr_log2, ids, c->order, n_ids,
+                (V*)out, (V*)c->rows, c->slot_of, c->vertex_of, c->stamp, c->free_list, n_free, n_miss, n_ins,
                 c->clock + (uint64_t)n_hit, table_rows);
+  }
 }
 
 void dispatch_rows(coop_cache* c, int vec_bytes, const void* table, int64_t table_rows, const int32_t* ids, int64_t n_ids, void* out,
@@ -369,6 +423,8 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
   COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_lookup, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, ids, n_ids,
               c->n_vertices, c->slot_of, c->slot_i, c->hit_bits, c->d_ctl);
   scan_bits_to_u32(c->hit_bits, n_ids, c->rank_h, &c->d_ctl->n_hit, c->scan_tmp, s);
+  COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_split, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, c->slot_i, c->rank_h,
+              n_ids, c->order);
   COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
   // 2. hits: rows out of the cache, new stamps (runs while the host waits for the counts)
   dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, 0, 0, 0, 0, true, s);
@@ -398,18 +454,30 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
       while (nbits < 64 && (range >> nbits) != 0) ++nbits;
       const int passes = (nbits + kSelBits - 1) / kSelBits;
       COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)n_evict);
-      int prev_shift = -1;
-      for (int p = passes - 1; p >= 0; --p) {
-        const int shift = p * kSelBits;
-        COOP_LAUNCH(K_CACHE_SELECT, k_cache_sel_hist, dim3(grid_for(c->capacity)), dim3(kBlock), 0, s, c->stamp, c->capacity, c->base,
-                    shift, prev_shift, c->d_ctl, c->hist);
-        COOP_LAUNCH(K_CACHE_SELECT, k_cache_sel_pick, dim3(1), dim3(kBlock), 0, s, c->hist, c->d_ctl);
+      // the bits of the range are split evenly over the passes, so that every pass spreads the entries over many
+      // counters (a narrow leading digit would pile every entry onto a handful of LDS words)
+      int prev_shift = -1, shift = nbits;
+      for (int p = 0; p < passes; ++p) {
+        const int bits = (shift + (passes - p) - 1) / (passes - p);
+        shift -= bits;
+        int64_t blocks = (c->capacity + kBlock * 64 - 1) / (kBlock * 64);  // >= 64 entries per thread: few flushes of the counters
+        if (blocks > 1024) blocks = 1024;
+        COOP_LAUNCH(K_CACHE_SELECT, k_cache_sel_hist, dim3((unsigned)(blocks > 0 ? blocks : 1)), dim3(kBlock), 0, s, c->stamp, c->capacity,
+                    c->base, shift, bits, prev_shift, c->d_ctl, c->hist);
+        COOP_LAUNCH(K_CACHE_PICK, k_cache_sel_pick, dim3(1), dim3(kBlock), 0, s, c->hist, bits, c->d_ctl);
         prev_shift = shift;
       }
       threshold_known = true;
     }
-    COOP_LAUNCH(K_CACHE_SELECT, k_cache_evict, dim3(grid_for(c->capacity)), dim3(kBlock), 0, s, c->stamp, c->vertex_of, c->slot_of,
-                c->free_list, c->capacity, c->base, evict_all, n_free, c->d_ctl);
+    {
+      int64_t blocks = (c->capacity + kBlock - 1) / kBlock;
+      if (blocks > 2048) blocks = 2048;
+      int64_t chunk = (c->capacity + blocks - 1) / blocks;
+      chunk = (chunk + kBlock - 1) / kBlock * kBlock;
+      blocks = (c->capacity + chunk - 1) / chunk;
+      COOP_LAUNCH(K_CACHE_EVICT, k_cache_evict, dim3((unsigned)blocks), dim3(kBlock), 0, s, c->stamp, c->vertex_of, c->slot_of,
+                  c->free_list, c->capacity, chunk, c->base, evict_all, n_free, c->d_ctl);
+    }
     n_free += n_evict;
     c->size -= n_evict;
   }

@@ -26,6 +26,8 @@ enum KernelId {
   K_VALIDATE,        // CSR validation
   K_CACHE_LOOKUP,
   K_CACHE_SELECT,
+  K_CACHE_PICK,
+  K_CACHE_EVICT,
   K_CACHE_UPDATE,
   K_CACHE_GATHER,
   K_COUNT_

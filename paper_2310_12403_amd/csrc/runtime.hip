@@ -25,7 +25,7 @@ struct Prof {
 const char* const kKernelNames[K_COUNT_] = {
     "fill", "labor_scan", "labor_fill", "labor_fill_overflow", "segments", "ns_count", "ns_fill", "scan_local", "scan_offset",
     "unique_insert", "unique_flag", "unique_relabel", "copy_ids", "gather", "validate_csr",
-    "cache_lookup", "cache_select", "cache_update", "cache_gather"};
+    "cache_lookup", "cache_select_hist", "cache_select_pick", "cache_evict", "cache_miss_rows", "cache_hit_rows"};
 
 hipEvent_t take_event() {
   if (!g_prof.pool.empty()) { hipEvent_t e = g_prof.pool.back(); g_prof.pool.pop_back(); return e; }
