@@ -52,16 +52,22 @@ __global__ __launch_bounds__(kBlock) void k_gather(const V* __restrict__ feat, i
 }
 
 namespace {
+constexpr int kMaxDevices = 64;
 std::mutex g_bad_mu;
-int32_t* g_bad_flag = nullptr;  // device word, sticky "an id was out of range"
+int32_t* g_bad_flag[kMaxDevices] = {};  // per device: a device word, sticky "an id was out of range"
 
+// the current device's flag word, created on first use (a few bytes, kept for the life of the process)
 int32_t* bad_flag() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
   std::lock_guard<std::mutex> lk(g_bad_mu);
-  if (!g_bad_flag) {
-    if (hipMalloc((void**)&g_bad_flag, sizeof(int32_t)) != hipSuccess) return nullptr;
-    if (hipMemset(g_bad_flag, 0, sizeof(int32_t)) != hipSuccess) return nullptr;
+  if (!g_bad_flag[dev]) {
+    int32_t* p = nullptr;
+    if (hipMalloc((void**)&p, sizeof(int32_t)) != hipSuccess) return nullptr;
+    if (hipMemset(p, 0, sizeof(int32_t)) != hipSuccess) { (void)hipFree(p); return nullptr; }
+    g_bad_flag[dev] = p;
   }
-  return g_bad_flag;
+  return g_bad_flag[dev];
 }
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
