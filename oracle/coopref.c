@@ -16,7 +16,8 @@
  *     minibatching): a PRNG keyed by (z, t, s) whose first output is the
  *     variate, two seeds z1, z2 per group of kappa iterations blended in normal
  *     space, n(c) = cos(c pi/2) n1 + sin(c pi/2) n2, r = Phi(n(c)), c = i/kappa;
- *   - the feature loading of Algorithm 1: out[i,:] = feat[S^L[i],:];
+ *   - the feature loading of Algorithm 1: out[i,:] = feat[S^L[i],:], and the neighbour mean of
+ *     Eq. (1) over a sampled block (what a mean-aggregating first layer does with those rows);
  *   - an LRU vertex cache (Sec. 4.2 names "an LRU cache" only).
  *
  * Readings where the paper is silent (each is listed in the design notes):
@@ -479,6 +480,39 @@ int coopref_gather(const void* feat, int64_t n_rows, int64_t row_bytes, const in
   for (int64_t i = 0; i < n_ids; ++i) {
     if (ids[i] < 0 || ids[i] >= n_rows) return COOPREF_E_RANGE;
     memcpy((char*)out + i * row_bytes, (const char*)feat + (int64_t)ids[i] * row_bytes, (size_t)row_bytes);
+  }
+  return COOPREF_OK;
+}
+
+/* IEEE binary16 -> double, from the bit fields (no compiler half type needed). */
+static double half_to_double(uint16_t h) {
+  int sign = h >> 15, ex = (h >> 10) & 31, man = h & 1023;
+  double v;
+  if (ex == 0) v = ldexp((double)man, -24);                    /* subnormal or zero */
+  else if (ex == 31) v = man ? NAN : INFINITY;
+  else v = ldexp((double)(man | 1024), ex - 25);
+  return sign ? -v : v;
+}
+
+/* Neighbour mean of Eq. (1) with a mean aggregator over one sampled block:
+ * out[i, c] = (1/deg_i) sum_{e in [indptr[i], indptr[i+1])} feat[col[e], c] in binary64 (0 when deg_i = 0).
+ * dtype: 0 = float rows, 1 = binary16 rows. */
+int coopref_gather_mean(const void* feat, int64_t n_rows, int32_t dim, int dtype, const int64_t* indptr,
+                        const int32_t* col, int64_t n_dst, double* out) {
+  if (!feat || !indptr || (!out && n_dst > 0)) return COOPREF_E_NULL;
+  if (dim < 1 || (dtype != 0 && dtype != 1) || n_dst < 0) return COOPREF_E_ARG;
+  for (int64_t i = 0; i < n_dst; ++i) {
+    int64_t beg = indptr[i], end = indptr[i + 1];
+    for (int32_t c = 0; c < dim; ++c) {
+      double acc = 0.0;
+      for (int64_t e = beg; e < end; ++e) {
+        int64_t t = col[e];
+        if (t < 0 || t >= n_rows) return COOPREF_E_RANGE;
+        acc += dtype == 0 ? (double)((const float*)feat)[t * dim + c]
+                          : half_to_double(((const uint16_t*)feat)[t * dim + c]);
+      }
+      out[i * dim + c] = end > beg ? acc / (double)(end - beg) : 0.0;
+    }
   }
   return COOPREF_OK;
 }

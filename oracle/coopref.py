@@ -66,6 +66,8 @@ def lib():
         L.coopref_free_blocks.restype = None
         L.coopref_gather.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
         L.coopref_gather.restype = C.c_int
+        L.coopref_gather_mean.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        L.coopref_gather_mean.restype = C.c_int
         L.coopref_cache_create.argtypes = [C.c_int64, C.c_int64]
         L.coopref_cache_create.restype = C.c_void_p
         L.coopref_cache_free.argtypes = [C.c_void_p]
@@ -147,6 +149,21 @@ def gather(feat, ids):
     row_bytes = feat.strides[0]
     rc = lib().coopref_gather(feat.ctypes.data, feat.shape[0], row_bytes, ids.ctypes.data, len(ids),
                               out.ctypes.data)
+    if rc != OK:
+        raise OracleError(rc)
+    return out
+
+
+def gather_mean(feat, indptr, col):
+    """float64 [n_dst, dim]: mean of feat[col[e], :] over the edges of every destination (0 where there are none)."""
+    feat = np.ascontiguousarray(feat)
+    assert feat.dtype in (np.float32, np.float16) and feat.ndim == 2
+    indptr = np.ascontiguousarray(indptr, dtype=np.int64)
+    col = np.ascontiguousarray(col, dtype=np.int32)
+    n_dst = len(indptr) - 1
+    out = np.zeros((n_dst, feat.shape[1]), dtype=np.float64)
+    rc = lib().coopref_gather_mean(feat.ctypes.data, feat.shape[0], feat.shape[1], 0 if feat.dtype == np.float32 else 1,
+                                   indptr.ctypes.data, col.ctypes.data, n_dst, out.ctypes.data)
     if rc != OK:
         raise OracleError(rc)
     return out

@@ -461,6 +461,30 @@ def test_gather_is_fancy_indexing(dtype, dim):
         R.gather(feat, np.array([500], np.int32))
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_gather_mean_is_segment_mean(dtype):
+    """Eq. (1) with a mean aggregator: against numpy's own segmented sum, plus the degenerate rows."""
+    rng = np.random.default_rng(3)
+    feat = (rng.standard_normal((300, 37)) * 3).astype(dtype)
+    if dtype == np.float16:
+        feat[0, 0] = np.float16(6e-8)                      # a subnormal half
+    deg = rng.integers(0, 9, 120)
+    deg[:3] = [0, 1, 0]
+    indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    col = rng.integers(0, 300, indptr[-1]).astype(np.int32)
+    col[0] = 0
+    got = R.gather_mean(feat, indptr, col)
+    rows = feat[col].astype(np.float64)
+    want = np.zeros((120, 37))
+    nz = deg > 0
+    want[nz] = np.add.reduceat(rows, indptr[:-1][nz], axis=0) / deg[nz][:, None]
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-300)
+    assert np.all(got[0] == 0) and np.all(got[2] == 0)                       # no edges -> zero row
+    assert np.array_equal(got[1], feat[col[indptr[1]]].astype(np.float64))   # one edge -> that row, exactly
+    with pytest.raises(R.OracleError):
+        R.gather_mean(feat, np.array([0, 1], np.int64), np.array([300], np.int32))
+
+
 def textbook_lru(capacity):
     od = collections.OrderedDict()
 
