@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--kappa", type=int, default=1)
     ap.add_argument("--sampler", default=None, choices=[None, "labor0", "ns"])
     ap.add_argument("--batch", type=int, default=None)
-    ap.add_argument("--mode", default="step", choices=["step", "batch-sweep", "kappa-cache", "host-cache"],
+    ap.add_argument("--mode", default="step", choices=["step", "batch-sweep", "kappa-cache", "host-cache", "mean-agg"],
                     help="step: the benchmark contract (default).  batch-sweep: |S^l| against batch size on nested seed prefixes "
                          "(products-shaped).  kappa-cache: LRU miss rate against kappa over consecutive dependent batches "
                          "(papers100M-shaped, 4M-row cache).  host-cache: pinned-host feature table behind a 32M-row cache "
@@ -386,7 +386,51 @@ def report_host_cache(args, torch, synth, P):
                       "by_kappa": res, "host_link_GB_saved_per_iter_kappa64_vs_1": round(saved, 4)}), flush=True)
 
 
-REPORTS = {"batch-sweep": report_batch_sweep, "kappa-cache": report_kappa_cache, "host-cache": report_host_cache}
+def report_mean_agg(args, torch, synth, P):
+    """Neighbour mean over the last block fused with the feature load, against gather-then-nothing: papers100M-shaped."""
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["papers100M"]
+    indptr, indices = synth.make_graph("papers100M", device=dev, scale_down=args.scale_down, log=log)
+    n = indptr.numel() - 1
+    graph = P.coop_graph_load(indptr, indices)
+    feat = synth.features(n, cfg["dim"], torch.float16, seed=0, device=dev)
+    get_seeds = synth.seed_batches(n, cfg["batch"], seed=0, device=dev)
+    arena = P.Arena(4 << 30)
+    blocks = P.coop_sample(graph, get_seeds(0), cfg["fanouts"], P.COOP_LABOR0, it=0, kappa=1, seed=0, arena=arena)
+    blk = blocks[-1]
+    out_mean = torch.empty((blk.n_dst, cfg["dim"]), dtype=torch.float16, device=dev)
+    out_rows = torch.empty((blk.n_src, cfg["dim"]), dtype=torch.float16, device=dev)
+    row_bytes = cfg["dim"] * 2
+    res = {}
+    for name, fn, nbytes in (("gather_mean", lambda: P.coop_gather_mean(feat, blk.indptr, blk.col_global, out=out_mean),
+                              blk.n_edges * (row_bytes + 4) + blk.n_dst * (row_bytes + 8)),
+                             ("gather", lambda: P.coop_gather(feat, blk.src_ids, out=out_rows), blk.n_src * (2 * row_bytes + 4))):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t) / 20 * 1e3
+        res[name] = {"ms": round(ms, 4), "algorithmic_GB": round(nbytes / 1e9, 4), "GBps": round(nbytes / ms / 1e6, 1),
+                     "hbm_frac": round(nbytes / (ms * 1e-3) / HBM_PEAK, 4)}
+    P.coop_gather_status()
+    if not args.no_cpu_baseline:
+        from oracle import coopref as R
+        import numpy as np
+        k = 2000   # the first destinations of the block against the oracle's fp64 mean
+        ip = blk.indptr[:k + 1].cpu().numpy()
+        want = R.gather_mean(feat.cpu().numpy(), ip, blk.col_global[:int(ip[-1])].cpu().numpy())
+        got = out_mean[:k].float().cpu().numpy().astype(np.float64)
+        scale = np.maximum(np.abs(want).max(axis=1, keepdims=True), 1e-30)
+        res["max_rel_err_vs_oracle_first_%d_rows" % k] = float(np.max(np.abs(got - want) / scale))
+    print(json.dumps({"report": "mean-agg", "workload": "papers100M-shaped graph, last block of a 3-layer LABOR-0 batch of %d: "
+                      "%d destinations, %d edges, %d source rows, fp16 x %d" % (cfg["batch"], blk.n_dst, blk.n_edges, blk.n_src, cfg["dim"]),
+                      "kernels": res}), flush=True)
+
+
+REPORTS = {"mean-agg": report_mean_agg, "batch-sweep": report_batch_sweep, "kappa-cache": report_kappa_cache, "host-cache": report_host_cache}
 
 
 def _stored_traffic(kernel, args):

@@ -134,7 +134,20 @@ int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, cons
 int coop_gather(const void* feat, int64_t n_rows, int32_t dim, int dtype, const int32_t* ids, int64_t n_ids,
                 void* out, void* stream);
 
-/* Synchronises `stream` and returns COOP_E_RANGE if any coop_gather since the last call of this function met an
+/*
+ * Neighbour mean fused with the feature load: the aggregation of Eq. (1) with a mean aggregator over one sampled
+ * block (normally the last one, whose sources are S^L), without materialising the gathered rows:
+ *   out[i, :] = (1 / deg_i) * sum over e in [indptr[i], indptr[i+1]) of feat[col_global[e], :],   0 if deg_i = 0.
+ * Sums are accumulated in fp32 in edge order; `out` has the dtype of `feat`.
+ *   feat        device (or mapped pinned host) [n_rows, dim]
+ *   indptr      device int64 [n_dst + 1] (a coop_block's indptr), col_global device int32 [indptr[n_dst]], global ids
+ *   out         device [n_dst, dim]
+ * Asynchronous on `stream`; ids out of range are skipped and reported by coop_gather_status.
+ */
+int coop_gather_mean(const void* feat, int64_t n_rows, int32_t dim, int dtype, const int64_t* indptr,
+                     const int32_t* col_global, int64_t n_dst, void* out, void* stream);
+
+/* Synchronises `stream` and returns COOP_E_RANGE if any coop_gather / coop_gather_mean since the last call of this function met an
  * id outside [0, n_rows) (such rows of `out` are left zero-filled), else COOP_OK.  Clears the condition. */
 int coop_gather_status(void* stream);
 

