@@ -193,8 +193,25 @@ class _TorchAllocator:
 
 
 class Block:
-    """One sampled layer: tensors over the memory that the allocator handed out."""
-    __slots__ = ("n_dst", "n_src", "n_edges", "dst_ids", "indptr", "col_local", "col_global", "eid", "src_ids")
+    """One sampled layer.  n_dst / n_src / n_edges are plain ints; dst_ids, indptr, col_local, col_global, eid and
+    src_ids are tensors over the memory that the allocator handed out, built on first access (so that a caller
+    that only needs the input vertex set pays for one view, not six per layer)."""
+    _FIELDS = {"dst_ids": ("n_dst", 0, torch.int32), "indptr": ("n_dst", 1, torch.int64), "col_local": ("n_edges", 0, torch.int32),
+               "col_global": ("n_edges", 0, torch.int32), "eid": ("n_edges", 0, torch.int64), "src_ids": ("n_src", 0, torch.int32)}
+
+    def __init__(self, cblock, allocator):
+        self.n_dst, self.n_src, self.n_edges = cblock.n_dst, cblock.n_src, cblock.n_edges
+        self._ptr = {name: getattr(cblock, name) for name in self._FIELDS}
+        self._alloc = allocator
+
+    def __getattr__(self, name):
+        fields = type(self)._FIELDS
+        if name not in fields:
+            raise AttributeError(name)
+        count_of, extra, dtype = fields[name]
+        t = self._alloc.view(self._ptr[name], getattr(self, count_of) + extra, dtype)
+        self.__dict__[name] = t
+        return t
 
 
 def coop_sample(graph, seeds, fanouts, sampler, it=0, kappa=1, seed=0, arena=None, stream=None):
@@ -209,18 +226,7 @@ def coop_sample(graph, seeds, fanouts, sampler, it=0, kappa=1, seed=0, arena=Non
     if rc != 0 and getattr(al, "error", None) is not None:
         raise al.error
     _check(rc)
-    out = []
-    for l in range(L):
-        b, o = blocks[l], Block()
-        o.n_dst, o.n_src, o.n_edges = b.n_dst, b.n_src, b.n_edges
-        o.dst_ids = al.view(b.dst_ids, b.n_dst, torch.int32)
-        o.indptr = al.view(b.indptr, b.n_dst + 1, torch.int64)
-        o.col_local = al.view(b.col_local, b.n_edges, torch.int32)
-        o.col_global = al.view(b.col_global, b.n_edges, torch.int32)
-        o.eid = al.view(b.eid, b.n_edges, torch.int64)
-        o.src_ids = al.view(b.src_ids, b.n_src, torch.int32)
-        out.append(o)
-    return out
+    return [Block(blocks[l], al) for l in range(L)]
 
 
 _DTYPES = {torch.float32: COOP_F32, torch.float16: COOP_F16}
