@@ -116,8 +116,10 @@ typedef struct {
  *   seeds      device int32 [n_seeds], distinct, in range (else COOP_E_DUPSEED / COOP_E_RANGE)
  *   fanouts    host int32 [L], each >= 1; NS needs fanout <= 1024 wherever a degree exceeds it (else COOP_E_CAPACITY)
  *   blocks_out host coop_block [L], filled on success
- * Synchronises `stream` (the per-layer sizes are read back).  On error blocks_out is zeroed; buffers
- * already obtained from the allocator stay with the caller.
+ * Waits on `stream` twice per layer (the per-layer sizes are read back to size the outputs); when it returns all
+ * sizes in blocks_out are final, while the kernels that fill the last layer's col_local / src_ids may still be running
+ * on `stream`: work queued on the same stream sees complete blocks, anything else must synchronise the stream first.
+ * On error blocks_out is zeroed; buffers already obtained from the allocator stay with the caller.
  */
 int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
                 int sampler, uint64_t iter, uint32_t kappa, uint64_t seed, coop_alloc_fn alloc, void* alloc_ctx,

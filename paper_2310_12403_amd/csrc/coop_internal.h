@@ -92,6 +92,15 @@ struct Ctl {
   int32_t n_overflow;    // LABOR-0 destinations whose staging row overflowed (this layer and earlier)
 };
 
+// Landing pad of the control block in mapped pinned host memory (see read_ctl).
+struct HostCtl {
+  Ctl ctl;               // must stay the first member
+  uint64_t ticket;       // written by the device after ctl
+  uint64_t next_ticket;  // host side only
+};
+
+int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
+
 // Dedup + relabel of one layer (Eq. 2).  Inputs: dst[n_dst] (distinct), col_global[m].  Outputs: col_local[m],
 // and *src_out = freshly allocated src_ids[n_src].  Reads sizes back (synchronises the stream).
 int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, int32_t* col_local,

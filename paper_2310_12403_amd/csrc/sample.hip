@@ -14,9 +14,31 @@ __global__ __launch_bounds__(kBlock) void k_copy_i32(const int32_t* __restrict__
 
 __global__ void k_clear_ctl(Ctl* ctl) { *ctl = Ctl{}; }
 
+// The control block travels to the host by a one-thread kernel that stores it into mapped pinned memory and then a
+// ticket; the host polls the ticket.  That is a few microseconds quicker per read-back than an asynchronous copy
+// followed by a stream synchronisation, and a sampling call has two read-backs per layer.  The wait is bounded: after
+// a while the host falls back to synchronising the stream.
+__global__ void k_publish_ctl(const Ctl* __restrict__ d_ctl, HostCtl* h, uint64_t ticket) {
+  h->ctl = *d_ctl;
+  __threadfence_system();
+  __hip_atomic_store(&h->ticket, ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
-  if (hipMemcpyAsync(h_ctl, d_ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s) != hipSuccess) return COOP_E_HIP;
-  if (hipStreamSynchronize(s) != hipSuccess) return COOP_E_HIP;
+  HostCtl* h = reinterpret_cast<HostCtl*>(h_ctl);  // h_ctl is the first member of a HostCtl in mapped pinned memory
+  const uint64_t ticket = ++h->next_ticket;
+  hipLaunchKernelGGL(k_publish_ctl, dim3(1), dim3(1), 0, s, d_ctl, h, ticket);
+  if (hipGetLastError() != hipSuccess) return COOP_E_HIP;
+  bool seen = false;
+  for (int64_t spin = 0; spin < ((int64_t)1 << 26); ++spin) {
+    if (__atomic_load_n(&h->ticket, __ATOMIC_ACQUIRE) == ticket) { seen = true; break; }
+    if ((spin & 0xFFFF) == 0xFFFF && hipStreamQuery(s) == hipSuccess) break;  // the stream ran dry: look once more below
+    __builtin_ia32_pause();
+  }
+  if (!seen) {
+    if (hipStreamSynchronize(s) != hipSuccess) return COOP_E_HIP;
+    if (__atomic_load_n(&h->ticket, __ATOMIC_ACQUIRE) != ticket) return COOP_E_HIP;
+  }
   if (h_ctl->err_range) return COOP_E_RANGE;
   if (h_ctl->err_dup) return COOP_E_DUPSEED;
   if (h_ctl->err_capacity) return COOP_E_CAPACITY;
@@ -78,8 +100,12 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
   }
 
   // pinned landing pad for the size read-backs, one per calling thread, kept for the life of the process
-  static thread_local Ctl* h_ctl = nullptr;
-  if (!h_ctl) COOP_HIP_TRY(hipHostMalloc((void**)&h_ctl, sizeof(Ctl), hipHostMallocDefault));
+  static thread_local HostCtl* h_pad = nullptr;
+  if (!h_pad) {
+    COOP_HIP_TRY(hipHostMalloc((void**)&h_pad, sizeof(HostCtl), hipHostMallocMapped | hipHostMallocCoherent));
+    *h_pad = HostCtl{};
+  }
+  Ctl* h_ctl = &h_pad->ctl;
   cx.h_ctl = h_ctl;
   cx.d_ctl = alloc.get<Ctl>(1, COOP_TAG_SCRATCH);
   int32_t* seed_copy = alloc.get<int32_t>(n_seeds, COOP_TAG_OUTPUT);

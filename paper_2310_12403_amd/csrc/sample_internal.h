@@ -46,8 +46,6 @@ struct LaborState {
   int64_t n_prev = 0;  // |S^{l-1}| while layer l is being built
 };
 
-int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
-
 // Each fills blk->indptr, n_edges, col_global, eid and allocates col_local for layer l over dst[0..n_dst).
 // Synchronises the stream once (the edge count is read back).
 int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);

@@ -117,11 +117,8 @@ int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global,
     scan_bits_to_u32(bits, m, rank, &d_ctl->total_new, scan_tmp, s);
   }
   // sizes (and the duplicate / range flags) back to the host
-  COOP_HIP_TRY(hipMemcpyAsync(h_ctl, d_ctl, sizeof(Ctl), hipMemcpyDeviceToHost, s));
-  COOP_HIP_TRY(hipStreamSynchronize(s));
-  if (h_ctl->err_range) return COOP_E_RANGE;
-  if (h_ctl->err_dup) return COOP_E_DUPSEED;
-  if (h_ctl->err_capacity) return COOP_E_CAPACITY;
+  const int rc = read_ctl(d_ctl, h_ctl, s);
+  if (rc != COOP_OK) return rc;
   if (m > 0) n_new = h_ctl->total_new;
 
   const int64_t n_src = n_dst + n_new;
