@@ -486,16 +486,22 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     // (what one wave parks in a register pair); a row that overflows is redone by the overflow pass
     st.stage_cap = 2 * (uint64_t)kmax + 16 > 32 ? 64 : 32;
     if (g_stage_cap_override) st.stage_cap = (uint32_t)g_stage_cap_override;
-    st.n_prev = 0;
+    st.n_pass = 0;
+    st.covered = 0;
   }
   const uint32_t cap = st.stage_cap;
 
-  // ---- scan pass over the destinations that are new at this layer (all of them when not fusing) ------------------
-  const int pi = st.fuse ? l : 0;
-  LaborPass& ps = st.pass[pi];
-  ps.start = st.fuse ? st.n_prev : 0;
+  // ---- scan pass over the destinations not covered yet ------------------------------------------------------------
+  // Normally the pass evaluates every remaining layer and is recorded.  A pass over only a few lists (the seeds'
+  // hop) is not worth a many-layer kernel: it evaluates this layer alone and leaves its destinations to the next pass.
+  constexpr int64_t kFuseMinLists = 32768;
+  const bool record = st.fuse && (n_dst - st.covered >= kFuseMinLists || l == cx.L - 1 || g_fuse_layers == 2);
+  LaborPass local;
+  LaborPass& ps = record ? st.pass[st.n_pass] : local;
+  ps.first_layer = l;
+  ps.start = st.covered;
   ps.n_new = n_dst - ps.start;
-  ps.nf = st.fuse ? cx.L - l : 1;
+  ps.nf = record ? cx.L - l : 1;
   const int64_t n_new = ps.n_new;
   ps.seg = alloc.get<Segment>(n_new, COOP_TAG_SCRATCH);
   ps.thr = alloc.get<uint32_t>(n_new * ps.nf, COOP_TAG_SCRATCH);
@@ -536,22 +542,25 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     }
   }
 
-  // ---- this layer's destinations, piece by piece: pass p covered it as its (l - p)-th layer ------------------------
+  // ---- this layer's destinations, piece by piece: a recorded pass covered it as its (l - first_layer)-th layer ------
+  if (record) { st.n_pass += 1; st.covered = n_dst; }
   LayerChunks ch{};
   ChunkedI32 counts{};
-  ch.n_chunks = counts.n_chunks = st.fuse ? l + 1 : 1;
-  for (int p = 0; p < ch.n_chunks; ++p) {
-    const LaborPass& q = st.pass[st.fuse ? p : 0];
-    const int f = st.fuse ? l - p : 0;
-    ch.seg[p] = q.seg;
-    ch.thr[p] = q.thr + (int64_t)f * q.n_new;
-    ch.stage[p] = q.stage[f];
-    ch.start[p] = counts.start[p] = q.start;
-    counts.ptr[p] = q.cnt[f];
-  }
-  // chunks that scanned nothing (a layer that added no vertex) must not shadow their predecessors
-  for (int p = 1; p < ch.n_chunks; ++p)
-    if (st.pass[st.fuse ? p : 0].n_new == 0) { ch.start[p] = counts.start[p] = INT64_MAX; }
+  int nc = 0;
+  auto add_chunk = [&](const LaborPass& q) {
+    if (q.n_new == 0) return;  // a pass that scanned nothing (a layer that added no vertex) contributes no piece
+    const int f = l - q.first_layer;
+    ch.seg[nc] = q.seg;
+    ch.thr[nc] = q.thr + (int64_t)f * q.n_new;
+    ch.stage[nc] = q.stage[f];
+    ch.start[nc] = counts.start[nc] = q.start;
+    counts.ptr[nc] = q.cnt[f];
+    ++nc;
+  };
+  for (int p = 0; p < st.n_pass; ++p) add_chunk(st.pass[p]);
+  if (!record) add_chunk(local);
+  if (nc == 0) { ch.seg[0] = ps.seg; ch.thr[0] = ps.thr; ch.stage[0] = ps.stage[0]; counts.ptr[0] = ps.cnt[0]; nc = 1; }  // n_dst == 0
+  ch.n_chunks = counts.n_chunks = nc;
 
   scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
   int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
@@ -579,7 +588,6 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
                     cap, blk->indptr, blk->col_global, blk->eid);
     }
   }
-  st.n_prev = n_dst;
   return COOP_OK;
 }
 

@@ -64,7 +64,7 @@ extern "C" int coop_tune(int knob, int64_t value) {
       g_lists_per_wave = (int)value;
       return COOP_OK;
     case COOP_TUNE_FUSE_LAYERS:
-      if (value != 0 && value != 1) return COOP_E_ARG;
+      if (value < 0 || value > 2) return COOP_E_ARG;
       g_fuse_layers = (int)value;
       return COOP_OK;
     default:

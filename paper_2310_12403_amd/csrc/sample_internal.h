@@ -31,6 +31,7 @@ struct StageEntry { int32_t t; uint32_t j; };  // kept source vertex, its positi
 
 // What one LABOR-0 scan pass leaves behind for the layers it covered (f = 0 is the pass's own layer).
 struct LaborPass {
+  int first_layer = 0;               // the layer at which the pass ran
   int64_t start = 0, n_new = 0;      // destinations [start, start + n_new) of the layer were scanned in this pass
   Segment* seg = nullptr;            // [n_new]
   uint32_t* thr = nullptr;           // [nf][n_new] keep thresholds, layer-major
@@ -40,10 +41,11 @@ struct LaborPass {
 };
 
 struct LaborState {
-  LaborPass pass[kMaxFuse];
+  LaborPass pass[kMaxFuse];  // the passes that covered all remaining layers of their destinations
+  int n_pass = 0;
+  int64_t covered = 0;       // destinations [0, covered) have every remaining layer staged by those passes
   bool fuse = false;
   uint32_t stage_cap = 32;
-  int64_t n_prev = 0;  // |S^{l-1}| while layer l is being built
 };
 
 // Each fills blk->indptr, n_edges, col_global, eid and allocates col_local for layer l over dst[0..n_dst).

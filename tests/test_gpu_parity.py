@@ -333,3 +333,19 @@ def test_nested_dependent_minibatching(P, medium):
             union[l] |= set(child[l].src_ids.cpu().tolist())
     for l in range(3):
         assert union[l] == set(big[l].src_ids.cpu().tolist())
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_labor_fusion_modes(P, tiny, medium, mode):
+    """LABOR-0 with the scan fused over all remaining layers (2), per layer (0) and the default mix (1): same bytes."""
+    try:
+        P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, mode)
+        seeds = synth.seed_batches(tiny.n, 900, seed=13)(0).numpy()
+        compare(P, tiny, seeds, (10, 10, 10), R.LABOR0, it=4, kappa=1, seed=6)
+        compare(P, tiny, seeds[:200], (7, 3, 5, 2), R.LABOR0, it=9, kappa=8, seed=6)          # four layers, blended
+        compare(P, tiny, seeds[:50], (3, 3, 3, 3, 3), R.LABOR0, it=2, kappa=1, seed=6)          # five layers: never fused
+        compare(P, medium, synth.seed_batches(medium.n, 3000, seed=13)(1).numpy(), (25, 10, 10), R.LABOR0, it=1, seed=6)
+        isolated = np.nonzero(np.diff(tiny.indptr_h) == 0)[0][:3].astype(np.int32)
+        compare(P, tiny, isolated, (10, 10, 10), R.LABOR0, it=1, seed=6)                        # layers that add no vertex
+    finally:
+        P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, 1)
