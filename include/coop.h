@@ -187,6 +187,23 @@ int coop_cache_free(coop_cache* c);
 int coop_cache_gather(coop_cache* c, const void* table, int64_t table_rows, const int32_t* ids, int64_t n_ids, void* out,
                       int64_t* n_miss_out, void* stream);
 
+/*
+ * Checkpoint / resume of a cache.  coop_cache_export writes the cached vertices and their recency stamps (in no
+ * particular order; state_out->size of them) to two caller-owned device arrays of `capacity_rows` entries each and
+ * the scalar state to state_out; it synchronises `stream`.  coop_cache_import puts a cache created with the same
+ * capacity (or a larger one) into exactly that state, reading the rows again from `table`; duplicate vertices or
+ * vertices out of range in the list give COOP_E_RANGE (the cache is then empty).  After an import the cache answers
+ * every later coop_cache_gather as the exported one would have.
+ */
+typedef struct {
+  int64_t size;    /* cached vertices */
+  uint64_t clock;  /* next recency stamp */
+  uint64_t base;   /* lower bound of the live stamps */
+} coop_cache_state;
+int coop_cache_export(coop_cache* c, int32_t* vertices_out, uint64_t* stamps_out, coop_cache_state* state_out, void* stream);
+int coop_cache_import(coop_cache* c, const void* table, int64_t table_rows, const int32_t* vertices, const uint64_t* stamps,
+                      const coop_cache_state* state, void* stream);
+
 /* Device-side address of pinned (page-locked, mapped) host memory, for use as `table` / `feat` above.
  * COOP_E_ARG if `host` is not such memory: nothing is ever dereferenced that the device cannot read. */
 int coop_map_host_pointer(const void* host, void** device_out);

@@ -25,6 +25,10 @@ class _CArena(C.Structure):
     _fields_ = [("base", C.c_void_p), ("bytes", C.c_size_t), ("used", C.c_size_t)]
 
 
+class _CCacheState(C.Structure):
+    _fields_ = [("size", C.c_int64), ("clock", C.c_uint64), ("base", C.c_uint64)]
+
+
 _lib = None
 
 
@@ -64,6 +68,10 @@ def lib():
     L.coop_cache_gather.restype = C.c_int
     L.coop_cache_vertices.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_int64)]
     L.coop_cache_vertices.restype = C.c_int
+    L.coop_cache_export.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_CCacheState), C.c_void_p]
+    L.coop_cache_export.restype = C.c_int
+    L.coop_cache_import.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.POINTER(_CCacheState), C.c_void_p]
+    L.coop_cache_import.restype = C.c_int
     L.coop_map_host_pointer.argtypes = [C.c_void_p, C.POINTER(C.c_void_p)]
     L.coop_map_host_pointer.restype = C.c_int
     L.coop_tune.argtypes = [C.c_int, C.c_int64]
@@ -313,6 +321,20 @@ class Cache:
         v = v[v >= 0]
         assert v.numel() == n.value
         return torch.sort(v).values
+
+    def export_state(self, stream=None):
+        """(vertices int32 [size], stamps int64 [size] (bit pattern of the uint64 stamps), (size, clock, base))."""
+        v = torch.empty(max(self.capacity, 1), dtype=torch.int32, device=self._alloc.device)
+        st = torch.empty(max(self.capacity, 1), dtype=torch.int64, device=self._alloc.device)
+        state = _CCacheState()
+        _check(lib().coop_cache_export(self.handle, C.c_void_p(v.data_ptr()), C.c_void_p(st.data_ptr()), C.byref(state),
+                                       _stream_ptr(stream)))
+        return v[:state.size].clone(), st[:state.size].clone(), (state.size, state.clock, state.base)
+
+    def import_state(self, table, vertices, stamps, state, stream=None):
+        cs = _CCacheState(*state)
+        _check(lib().coop_cache_import(self.handle, C.c_void_p(self._table_ptr(table)), table.shape[0],
+                                       _dev_ptr(vertices, torch.int32), _dev_ptr(stamps, torch.int64), C.byref(cs), _stream_ptr(stream)))
 
     def close(self):
         if self.handle:

@@ -20,6 +20,9 @@
 #include "coop_internal.h"
 #include "device_utils.h"
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
 namespace coop {
 
 constexpr int kSelBits = 13;  // most bits per radix-select pass (8192 LDS counters)
@@ -353,6 +356,127 @@ extern "C" int coop_cache_free(coop_cache* c) {
   return COOP_OK;
 }
 
+// ---- export / import (checkpoint and resume) --------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_cache_export(const int32_t* __restrict__ vertex_of, const uint64_t* __restrict__ stamp,
+                                                         int64_t capacity, int32_t* __restrict__ vertices_out,
+                                                         uint64_t* __restrict__ stamps_out, CacheCtl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool live = i < capacity && stamp[i] != 0;
+  const uint64_t mask = ballot64(live);
+  if (mask == 0) return;
+  int32_t first = 0;
+  if (lane_id() == 0) first = atomicAdd(&ctl->n_push, (int32_t)__popcll(mask));
+  first = __builtin_amdgcn_readfirstlane(first);
+  if (live) {
+    const int64_t p = first + (int64_t)lanes_below(mask);
+    vertices_out[p] = vertex_of[i];
+    stamps_out[p] = stamp[i];
+  }
+}
+
+// entry i of the exported lists goes to slot i; its row is read again from the backing table
+template <typename V>
+__global__ __launch_bounds__(kBlock) void k_cache_import(const V* __restrict__ table, int64_t table_rows, int32_t vecs, int lpr_log2,
+                                                         const int32_t* __restrict__ vertices, const uint64_t* __restrict__ stamps,
+                                                         int64_t n, int64_t n_vertices, V* __restrict__ rows,
+                                                         int32_t* __restrict__ slot_of, int32_t* __restrict__ vertex_of,
+                                                         uint64_t* __restrict__ stamp, CacheCtl* ctl) {
+  const int lpr = 1 << lpr_log2;
+  const int sub = threadIdx.x & (lpr - 1);
+  const int64_t i = (int64_t)blockIdx.x * (kBlock >> lpr_log2) + (threadIdx.x >> lpr_log2);
+  if (i >= n) return;
+  const int32_t v = vertices[i];
+  if ((uint64_t)(uint32_t)v >= (uint64_t)n_vertices || stamps[i] == 0) {
+    if (sub == 0) atomicOr(&ctl->err_range, 1);
+    return;
+  }
+  if (sub == 0) {
+    slot_of[v] = (int32_t)i;
+    vertex_of[i] = v;
+    stamp[i] = stamps[i];
+  }
+  const int64_t src = v < table_rows ? v : v % table_rows;
+  for (int32_t c = sub; c < vecs; c += lpr) rows[i * vecs + c] = table[src * vecs + c];
+}
+
+// every listed vertex must own its slot: a vertex listed twice owns only one of the two
+__global__ __launch_bounds__(kBlock) void k_cache_import_check(const int32_t* __restrict__ slot_of, const int32_t* __restrict__ vertex_of,
+                                                               int64_t n, CacheCtl* ctl) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  const int32_t v = vertex_of[i];
+  if (v < 0 || slot_of[v] != (int32_t)i) atomicOr(&ctl->err_range, 1);
+}
+
+__global__ __launch_bounds__(kBlock) void k_cache_free_tail(int32_t* __restrict__ free_list, int64_t n_live, int64_t capacity) {
+  // free slots are n_live .. capacity-1; the stack pops from its top, any order will do
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < capacity - n_live) free_list[i] = (int32_t)(n_live + i);
+}
+
+extern "C" int coop_cache_export(coop_cache* c, int32_t* vertices_out, uint64_t* stamps_out, coop_cache_state* state_out, void* stream) {
+  if (!c || !state_out || (c->capacity > 0 && (!vertices_out || !stamps_out))) return COOP_E_NULL;
+  hipStream_t s = (hipStream_t)stream;
+  COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)0);
+  if (c->capacity > 0)
+    COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_export, dim3((unsigned)((c->capacity + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, c->vertex_of,
+                c->stamp, c->capacity, vertices_out, stamps_out, c->d_ctl);
+  COOP_HIP_TRY(hipStreamSynchronize(s));
+  state_out->size = c->size;
+  state_out->clock = c->clock;
+  state_out->base = c->base;
+  return COOP_OK;
+}
+
+extern "C" int coop_cache_import(coop_cache* c, const void* table, int64_t table_rows, const int32_t* vertices, const uint64_t* stamps,
+                                 const coop_cache_state* state, void* stream) {
+  if (!c || !state) return COOP_E_NULL;
+  if (state->size < 0 || state->size > c->capacity || table_rows < 1 || state->clock == 0 || state->base == 0) return COOP_E_ARG;
+  if (state->size > 0 && (!table || !vertices || !stamps)) return COOP_E_NULL;
+  hipStream_t s = (hipStream_t)stream;
+  // back to the empty state (n_live slots reserved at the front), then the listed entries into slots 0 .. size-1
+  auto reset = [&](int64_t n_live) {
+    if (c->n_vertices > 0) COOP_LAUNCH(K_FILL, k_fill_i32, dim3(grid_for(c->n_vertices)), dim3(kBlock), 0, s, c->slot_of, c->n_vertices, -1, false);
+    if (c->capacity > 0) {
+      COOP_LAUNCH(K_FILL, k_fill_i32, dim3(grid_for(c->capacity)), dim3(kBlock), 0, s, c->vertex_of, c->capacity, -1, false);
+      fill_u64(c->stamp, c->capacity, 0, s);
+      COOP_LAUNCH(K_FILL, k_cache_free_tail, dim3(grid_for(c->capacity)), dim3(kBlock), 0, s, c->free_list, n_live, c->capacity);
+    }
+    COOP_LAUNCH(K_FILL, k_cache_clear_err, dim3(1), dim3(1), 0, s, c->d_ctl);
+  };
+  reset(state->size);
+  if (state->size > 0) {
+    const uintptr_t align = (uintptr_t)table | (uintptr_t)c->rows | (uintptr_t)c->row_bytes;
+    const int vb = align % 16 == 0 ? 16 : align % 8 == 0 ? 8 : align % 4 == 0 ? 4 : 2;
+    const int32_t vecs = (int32_t)(c->row_bytes / vb);
+    int lpr_log2 = 0;
+    while ((1 << lpr_log2) < vecs && lpr_log2 < 8) ++lpr_log2;
+    const unsigned grid = (unsigned)((state->size + (kBlock >> lpr_log2) - 1) / (kBlock >> lpr_log2));
+#define COOP_IMPORT(V) COOP_LAUNCH(K_CACHE_UPDATE, k_cache_import<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)table, table_rows, vecs, \
+                                   lpr_log2, vertices, stamps, state->size, c->n_vertices, (V*)c->rows, c->slot_of, c->vertex_of,     \
+                                   c->stamp, c->d_ctl)
+    if (vb == 16) COOP_IMPORT(u32x4);
+    else if (vb == 8) COOP_IMPORT(u32x2);
+    else if (vb == 4) COOP_IMPORT(uint32_t);
+    else COOP_IMPORT(uint16_t);
+#undef COOP_IMPORT
+    COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_import_check, dim3(grid_for(state->size)), dim3(kBlock), 0, s, c->slot_of, c->vertex_of, state->size,
+                c->d_ctl);
+  }
+  COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
+  COOP_HIP_TRY(hipStreamSynchronize(s));
+  if (c->h_ctl->err_range) {  // a bad list (vertex out of range or listed twice, zero stamp): leave an empty cache
+    reset(0);
+    COOP_HIP_TRY(hipStreamSynchronize(s));
+    c->size = 0; c->clock = 1; c->base = 1;
+    return COOP_E_RANGE;
+  }
+  c->size = state->size;
+  c->clock = state->clock;
+  c->base = state->base;
+  return COOP_OK;
+}
+
 extern "C" int coop_map_host_pointer(const void* host, void** device_out) {
   if (!host || !device_out) return COOP_E_NULL;
   void* d = nullptr;
@@ -372,9 +496,6 @@ extern "C" int coop_cache_vertices(const coop_cache* c, const int32_t** vertex_o
 }
 
 namespace {
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
 template <typename V>
 void launch_rows(coop_cache* c, const void* table, int64_t table_rows, const int32_t* ids, int64_t n_ids, void* out, int64_t n_free,
                  int64_t n_miss, int64_t n_ins, int64_t n_hit, bool hits, hipStream_t s) {

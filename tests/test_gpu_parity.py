@@ -349,3 +349,41 @@ def test_labor_fusion_modes(P, tiny, medium, mode):
         compare(P, tiny, isolated, (10, 10, 10), R.LABOR0, it=1, seed=6)                        # layers that add no vertex
     finally:
         P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, 1)
+
+
+def test_cache_export_import_resumes_exactly(P):
+    """A cache rebuilt from an export answers the following batches exactly as the original does."""
+    n, dim = 4000, 32
+    rng = np.random.default_rng(21)
+    feat = synth.features(n, dim, torch.float16, seed=4, device="cpu")
+    table = feat.cuda()
+    batches = [rng.choice(n, int(rng.integers(50, 700)), replace=False).astype(np.int32) for _ in range(30)]
+    a = P.Cache(900, n, dim, torch.float16, 1000)
+    for ids in batches[:15]:
+        a.gather(table, torch.from_numpy(ids).cuda())
+    vertices, stamps, state = a.export_state()
+    assert vertices.numel() == state[0] == a.vertices().numel()
+    b = P.Cache(1200, n, dim, torch.float16, 1000)                  # a larger capacity may import a smaller cache
+    c = P.Cache(900, n, dim, torch.float16, 1000)
+    c.import_state(table, vertices, stamps, state)
+    assert torch.equal(c.vertices(), a.vertices())
+    for ids in batches[15:]:
+        t = torch.from_numpy(ids).cuda()
+        out_a, miss_a = a.gather(table, t)
+        out_c, miss_c = c.gather(table, t)
+        assert miss_a == miss_c and torch.equal(out_a, out_c)
+        assert torch.equal(a.vertices(), c.vertices())
+    b.import_state(table, vertices, stamps, state)
+    assert torch.equal(b.vertices(), torch.sort(vertices).values)
+    bad = vertices.clone()
+    bad[0] = n
+    with pytest.raises(P.CoopError) as e:
+        b.import_state(table, bad, stamps, state)
+    assert e.value.code == -2 and b.vertices().numel() == 0
+    dup = vertices.clone()
+    dup[1] = dup[0]
+    with pytest.raises(P.CoopError) as e:
+        b.import_state(table, dup, stamps, state)
+    assert e.value.code == -2 and b.vertices().numel() == 0
+    out, n_miss = b.gather(table, torch.from_numpy(batches[0]).cuda())       # still usable, and empty
+    assert n_miss == len(batches[0]) and torch.equal(out.cpu(), feat[torch.from_numpy(batches[0]).long()])
