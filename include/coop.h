@@ -224,6 +224,9 @@ const char* coop_strerror(int code);
 #define COOP_TUNE_LISTS_PER_WAVE 2 /* neighbour lists handled by one wave of the LABOR-0 scan: 1..64, 0 = automatic */
 #define COOP_TUNE_FUSE_LAYERS 3    /* 1 (default): a LABOR-0 list is scanned once for all remaining layers, except that a
                                       pass over fewer than 32768 lists covers its own layer only; 2: always fused; 0: never */
+#define COOP_TUNE_PIECE_LEN 4      /* a LABOR-0 list longer than twice this many entries is cut into pieces of about this
+                                      many entries, each scanned by a wave of its own: multiple of 4 in 256..2^24
+                                      (default 4096); 0: lists are never cut */
 int coop_tune(int knob, int64_t value);
 
 /* Library ABI version (bumped when a signature in this file changes). */

@@ -18,6 +18,11 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr uint32_t kAllThr = 0xFFFFFFFFu;  // threshold of a list no longer than the fanout: everything is kept
 constexpr int kScanGroups = 4;             // 16-byte groups per lane and step of the fast scan (4 KiB per wave and step)
 
+struct ScanOut {
+  StageEntry* stage[kMaxFuse];
+  int32_t* cnt[kMaxFuse];
+};
+
 struct FusedKeys {
   LayerKeys K[kMaxFuse];
   double cw, sw;
@@ -34,11 +39,6 @@ __device__ __forceinline__ uint32_t blend_pre_threshold(uint32_t thr, double inv
   const double lim = (double)kit_phi_to_u32(tau * inv_cs) * 1.000001 + 16.0;
   return lim >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)lim;
 }
-
-struct ScanOut {
-  StageEntry* stage[kMaxFuse];
-  int32_t* cnt[kMaxFuse];
-};
 
 // The pieces of one layer's destinations, by the pass that scanned them.
 struct LayerChunks {
@@ -58,29 +58,83 @@ struct LayerChunks {
 
 // list records of the destinations scanned in this pass, and their keep thresholds for the nf covered layers
 // (pthr: the blended path's pre-thresholds, null when c = 0)
-__global__ __launch_bounds__(kBlock) void k_segments(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
+constexpr int kSegBlock = 1024;  // large blocks: one queue reservation (a same-address atomic) per 1024 destinations
+__global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
                                                      const int32_t* __restrict__ dst, int64_t n, int nf,
                                                      uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, Segment* __restrict__ seg,
-                                                     uint32_t* __restrict__ thr, uint32_t* __restrict__ pthr, double inv_cs, Ctl* ctl) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= n) return;
-  const int32_t s = dst[i];
+                                                     uint32_t* __restrict__ thr, uint32_t* __restrict__ pthr, double inv_cs, Ctl* ctl,
+                                                     uint32_t piece_len, Piece* __restrict__ pieces, uint32_t piece_cap,
+                                                     uint32_t* __restrict__ piece_count, ScanOut out) {
+  __shared__ uint32_t s_wave_at[kSegBlock / kWave];
+  __shared__ uint32_t s_base, s_total;
+  const int64_t i = (int64_t)blockIdx.x * kSegBlock + threadIdx.x;
+  const bool live = i < n;
   Segment g{0, 0, 0};
-  if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
-    atomicOr(&ctl->err_range, 1);
-  } else {
-    g.beg = g_indptr[s];
-    g.d = (uint32_t)(g_indptr[s + 1] - g.beg);
-  }
-  seg[i] = g;
-  const uint32_t ks[kMaxFuse] = {k0, k1, k2, k3};
-#pragma unroll
-  for (int f = 0; f < kMaxFuse; ++f)
-    if (f < nf) {
-      const uint32_t t = g.d > ks[f] ? (uint32_t)(((uint64_t)ks[f] << 32) / (uint64_t)g.d) : kAllThr;
-      thr[(int64_t)f * n + i] = t;
-      if (pthr) pthr[(int64_t)f * n + i] = blend_pre_threshold(t, inv_cs);
+  bool sampled = live;  // every covered layer keeps a proper subset (d > k)
+  if (live) {
+    const int32_t s = dst[i];
+    if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
+      atomicOr(&ctl->err_range, 1);
+    } else {
+      g.beg = g_indptr[s];
+      g.d = (uint32_t)(g_indptr[s + 1] - g.beg);
     }
+    const uint32_t ks[kMaxFuse] = {k0, k1, k2, k3};
+#pragma unroll
+    for (int f = 0; f < kMaxFuse; ++f)
+      if (f < nf) {
+        const uint32_t t = g.d > ks[f] ? (uint32_t)(((uint64_t)ks[f] << 32) / (uint64_t)g.d) : kAllThr;
+        sampled &= t != kAllThr;
+        thr[(int64_t)f * n + i] = t;
+        if (pthr) pthr[(int64_t)f * n + i] = blend_pre_threshold(t, inv_cs);
+      }
+  }
+  if (piece_len == 0) {  // wave-uniform
+    if (live) seg[i] = g;
+    return;
+  }
+  // A long list is cut into pieces of about piece_len entries (equal lengths, multiples of 4), each scanned by a wave
+  // of its own: the waves of the scan then all have about the same amount of work whatever the degree distribution.
+  // The block reserves queue slots for all its long lists with one atomic; each wave then writes its pieces together.
+  uint32_t np = sampled && g.d > 2 * piece_len ? (g.d + piece_len - 1) / piece_len : 0u;
+  if (np > (1u << 20)) np = 0;  // keeps the block's sum below 2^30 (only lists of 2^28 entries and more, at the smallest piece length)
+  const uint32_t incl = wave_incl_scan(np);
+  const uint32_t lane = (uint32_t)lane_id();
+  const int wv = uniform_wave_in_block();
+  if (lane == kWave - 1) s_wave_at[wv] = incl;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t sum = 0;
+    for (int q = 0; q < kSegBlock / kWave; ++q) { const uint32_t t = s_wave_at[q]; s_wave_at[q] = sum; sum += t; }
+    s_total = sum;
+    s_base = sum != 0 ? atomicAdd(piece_count, sum) : 0u;
+  }
+  __syncthreads();
+  const uint32_t total = s_total;
+  if (total != 0) {  // block-uniform
+    const uint32_t block_base = s_base;
+    // room always suffices for distinct destinations (the queue holds a piece for every piece_len edges of the graph);
+    // a seed list with duplicates may run out: its lists then stay whole and what was reserved becomes empty slots
+    const bool fits = block_base <= piece_cap && total <= piece_cap - block_base;
+    const uint32_t base = block_base + s_wave_at[wv];
+    uint64_t todo = ballot64(np != 0);
+    while (todo != 0) {
+      const int src = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const uint32_t np_s = (uint32_t)__builtin_amdgcn_readlane((int)np, src);
+      const uint32_t at = base + (uint32_t)__builtin_amdgcn_readlane((int)incl, src) - np_s;
+      const uint32_t list = (uint32_t)((int64_t)blockIdx.x * kSegBlock + (threadIdx.x & ~(kWave - 1)) + src);
+      for (uint32_t q = lane; q < np_s; q += kWave)
+        if (at + q < piece_cap) pieces[at + q] = fits ? Piece{list, q} : Piece{kNoPiece, 0u};
+    }
+    if (fits && np != 0) {
+      g.split = 1;
+#pragma unroll
+      for (int f = 0; f < kMaxFuse; ++f)
+        if (f < nf) out.cnt[f][i] = 0;  // the pieces add their counts
+    }
+  }
+  if (live) seg[i] = g;
 }
 
 // Ordered visit of the neighbour list [beg, beg + d) of one destination by the whole wave, one entry per lane and
@@ -134,8 +188,8 @@ struct KeptRegs {
 // any layer.  Only then are the (few) kept entries picked off per-entry ballot masks by a wave-uniform loop and
 // parked in registers, in no particular order (they are ranked when the list is done).
 template <bool BLEND, int NF>
-__device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, const uint32_t (&thr)[NF],
-                                                const FusedKeys& keys, KeptRegs (&kept)[NF]) {
+__device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t j0,
+                                                const uint32_t (&thr)[NF], const FusedKeys& keys, KeptRegs (&kept)[NF]) {
   constexpr uint32_t kStep = kWave * 4 * kScanGroups;
   const int64_t abeg = beg & ~(int64_t)3;        // first aligned group
   const uint32_t head = (uint32_t)(beg - abeg);  // entries of that group that precede the list
@@ -158,6 +212,7 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
 #pragma unroll
     for (int gq = 0; gq < kScanGroups; ++gq) {
       const uint32_t r0 = base + (uint32_t)(gq * kWave * 4);  // wave-uniform
+      if (r0 >= vec_end) break;                                // the rest of this step lies behind the list
       bool f[NF][4];
       bool any = false;
 #pragma unroll
@@ -177,7 +232,7 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
             while (mm != 0) {
               const int src_lane = __builtin_ctzll(mm);
               mm &= mm - 1;
-              kept[l].push(lane, __builtin_amdgcn_readlane(buf[gq][e], src_lane), (int32_t)(r0 + (uint32_t)src_lane * 4 + e - head));
+              kept[l].push(lane, __builtin_amdgcn_readlane(buf[gq][e], src_lane), (int32_t)(r0 + (uint32_t)src_lane * 4 + e - head + j0));
             }
           }
         }
@@ -186,7 +241,7 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
   }
   {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
     const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
-    const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
+    const bool valid = lane < 3 ? (head != 0 && pos < 4 && pos < total) : (lane < 6 && pos < total && vec_end >= vec_beg);
     int32_t t = 0;
     if (valid) t = p[pos];
 #pragma unroll
@@ -197,7 +252,7 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
         const int src_lane = __builtin_ctzll(mm);
         mm &= mm - 1;
         const uint32_t src_pos = src_lane < 3 ? head + (uint32_t)src_lane : vec_end + (uint32_t)(src_lane - 3);
-        kept[l].push(lane, __builtin_amdgcn_readlane(t, src_lane), (int32_t)(src_pos - head));
+        kept[l].push(lane, __builtin_amdgcn_readlane(t, src_lane), (int32_t)(src_pos - head + j0));
       }
     }
   }
@@ -277,7 +332,7 @@ __device__ __forceinline__ void blend_enqueue(BlendQueue* __restrict__ q, uint32
 // Blended fast scan: same traversal as labor_scan_fast; per entry and layer two mixer evaluations and one compare
 // against the pre-threshold, exact evaluation only for the candidates.
 template <int NF>
-__device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d,
+__device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t j0,
                                                       const uint32_t (&thr)[NF], const uint32_t (&pthr)[NF], const FusedKeys& keys,
                                                       BlendQueue* __restrict__ q, KeptRegs (&kept)[NF]) {
   constexpr uint32_t kStep = kWave * 4 * kScanGroups;
@@ -302,6 +357,7 @@ __device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict_
     }
 #pragma unroll
     for (int gq = 0; gq < kScanGroups; ++gq) {
+      if (base + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the rest of this step lies behind the list
       const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
       uint32_t u1[NF][4], u2[NF][4];
       bool pre[NF][4];
@@ -322,21 +378,21 @@ __device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict_
         for (int l = 0; l < NF; ++l) {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            blend_enqueue<NF>(q, qn, pre[l][e], buf[gq][e], (int32_t)(r + e - head), u1[l][e], u2[l][e], (uint32_t)l, thr, keys, kept);
+            blend_enqueue<NF>(q, qn, pre[l][e], buf[gq][e], (int32_t)(r + e - head + j0), u1[l][e], u2[l][e], (uint32_t)l, thr, keys, kept);
         }
       }
     }
   }
   {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
     const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
-    const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
+    const bool valid = lane < 3 ? (head != 0 && pos < 4 && pos < total) : (lane < 6 && pos < total && vec_end >= vec_beg);
     int32_t t = 0;
     if (valid) t = p[pos];
 #pragma unroll
     for (int l = 0; l < NF; ++l) {
       const uint32_t a = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)t, 0u);
       const uint32_t b = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)t, 0u);
-      blend_enqueue<NF>(q, qn, valid && (a < b ? a : b) <= pthr[l], t, (int32_t)(pos - head), a, b, (uint32_t)l, thr, keys, kept);
+      blend_enqueue<NF>(q, qn, valid && (a < b ? a : b) <= pthr[l], t, (int32_t)(pos - head + j0), a, b, (uint32_t)l, thr, keys, kept);
     }
   }
   if (qn != 0) blend_eval<NF>(q, qn, thr, keys, kept);
@@ -345,16 +401,70 @@ __device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict_
 
 // Scan pass.  Each wave takes `lists_per_wave` consecutive destinations; their records are fetched by one coalesced
 // load (lane i holds record i), so the pointer chase destination -> list start is paid once per wave.
+// The first `piece_blocks` blocks of the grid take the pieces of the long lists (wave w takes pieces w, w + W, ... of
+// the queue, W = their number of waves; the queue length is read from device memory, so every wave ends after a
+// bounded number of steps).  A piece adds its kept-edge counts to the list's counters and puts its entries wherever
+// that leaves them in the staging row; the fill pass sorts the rows of cut lists by list position.
 template <bool BLEND, int VEC, int NF>
 __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict__ g_indices, const Segment* __restrict__ seg,
                                                        const uint32_t* __restrict__ thr_all, const uint32_t* __restrict__ pthr_all,
                                                        int64_t n, int lists_per_wave, FusedKeys keys, uint32_t stage_cap, ScanOut out,
-                                                       Ctl* ctl) {
+                                                       Ctl* ctl, int piece_blocks, const Piece* __restrict__ pieces,
+                                                       const uint32_t* __restrict__ piece_count, uint32_t piece_cap, uint32_t piece_len) {
   __shared__ BlendQueue queues[BLEND && VEC == 4 ? kWavesPerBlock : 1];
-  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + uniform_wave_in_block();
+  const uint32_t lane = (uint32_t)lane_id();
+  if constexpr (VEC == 4) {
+    if ((int)blockIdx.x < piece_blocks) {
+      uint32_t n_pieces = *piece_count;
+      if (n_pieces > piece_cap) n_pieces = piece_cap;
+      const uint32_t n_waves = (uint32_t)piece_blocks * kWavesPerBlock;
+      for (uint32_t p = blockIdx.x * kWavesPerBlock + (uint32_t)uniform_wave_in_block(); p < n_pieces; p += n_waves) {
+        const Piece pc = pieces[p];
+        const uint32_t list = (uint32_t)__builtin_amdgcn_readfirstlane((int)pc.list);
+        if (list == kNoPiece) continue;
+        const uint32_t q = (uint32_t)__builtin_amdgcn_readfirstlane((int)pc.q);
+        const Segment g = seg[list];
+        const int64_t beg = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)((uint64_t)g.beg >> 32)) << 32) |
+                                      (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)g.beg));
+        const uint32_t d = (uint32_t)__builtin_amdgcn_readfirstlane((int)g.d);
+        const uint32_t np = (d + piece_len - 1) / piece_len;  // as in k_segments
+        const uint32_t plen = ((d + np - 1) / np + 3u) & ~3u;
+        const uint64_t j0_64 = (uint64_t)q * plen;
+        if (j0_64 >= d) continue;  // rounding the piece length up can leave the last slots of a very long list empty
+        const uint32_t j0 = (uint32_t)j0_64;
+        const uint32_t len = d - j0 < plen ? d - j0 : plen;
+        uint32_t thr[NF];
+#pragma unroll
+        for (int l = 0; l < NF; ++l) thr[l] = (uint32_t)__builtin_amdgcn_readfirstlane((int)thr_all[(int64_t)l * n + list]);
+        KeptRegs kept[NF];
+        if constexpr (BLEND) {
+          uint32_t pthr[NF];
+#pragma unroll
+          for (int l = 0; l < NF; ++l) pthr[l] = (uint32_t)__builtin_amdgcn_readfirstlane((int)pthr_all[(int64_t)l * n + list]);
+          labor_scan_fast_blend<NF>(g_indices, beg + j0, len, j0, thr, pthr, keys, &queues[uniform_wave_in_block()], kept);
+        } else {
+          labor_scan_fast<BLEND, NF>(g_indices, beg + j0, len, j0, thr, keys, kept);
+        }
+#pragma unroll
+        for (int l = 0; l < NF; ++l) {
+          const uint32_t c = kept[l].count;
+          if (c == 0) continue;
+          uint32_t at = 0;
+          if (lane == 0) at = (uint32_t)atomicAdd(&out.cnt[l][list], (int32_t)c);
+          at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+          if (at + c <= stage_cap) {  // c <= stage_cap <= 64: every entry is still in its register
+            if (lane < c) out.stage[l][(size_t)list * stage_cap + at + lane] = StageEntry{kept[l].ent_t, (uint32_t)kept[l].ent_j};
+          } else if (at <= stage_cap && lane == 0) {
+            atomicAdd(&ctl->n_overflow, 1);  // the one piece that takes the row over its capacity reports the list
+          }
+        }
+      }
+      return;
+    }
+  }
+  const int64_t wave = ((int64_t)blockIdx.x - piece_blocks) * kWavesPerBlock + uniform_wave_in_block();
   const int64_t first = wave * lists_per_wave;
   if (first >= n) return;
-  const uint32_t lane = (uint32_t)lane_id();
   const int64_t mine = first + lane;
   const bool has = (int)lane < lists_per_wave && mine < n;
   Segment g{0, 0, 0};
@@ -378,6 +488,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
     const int64_t beg = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)beg_hi, i) << 32) |
                                   (uint32_t)__builtin_amdgcn_readlane((int)beg_lo, i));
     const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)g.d, i);
+    if (__builtin_amdgcn_readlane((int)g.split, i) != 0) continue;  // cut into pieces, scanned by other waves
     uint32_t thr[NF];
     bool any_all = false;
 #pragma unroll
@@ -391,9 +502,9 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
         uint32_t pthr[NF];
 #pragma unroll
         for (int l = 0; l < NF; ++l) pthr[l] = (uint32_t)__builtin_amdgcn_readlane((int)my_pthr[l], i);
-        labor_scan_fast_blend<NF>(g_indices, beg, d, thr, pthr, keys, &queues[uniform_wave_in_block()], kept);
+        labor_scan_fast_blend<NF>(g_indices, beg, d, 0u, thr, pthr, keys, &queues[uniform_wave_in_block()], kept);
       } else {
-        labor_scan_fast<BLEND, NF>(g_indices, beg, d, thr, keys, kept);
+        labor_scan_fast<BLEND, NF>(g_indices, beg, d, 0u, thr, keys, kept);
       }
 #pragma unroll
       for (int l = 0; l < NF; ++l) {
@@ -412,7 +523,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
       }
     }
   }
-  if (has) {
+  if (has && g.split == 0) {
 #pragma unroll
     for (int l = 0; l < NF; ++l) {
       out.cnt[l][mine] = (int32_t)my_count[l];
@@ -426,6 +537,7 @@ constexpr int kFillLanesLog2 = 3;
 __global__ __launch_bounds__(kBlock) void k_labor_fill_staged(LayerChunks ch, int64_t n_dst, uint32_t stage_cap,
                                                               const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
                                                               int64_t* __restrict__ eid) {
+  __shared__ uint32_t row_j[kBlock >> kFillLanesLog2][kWave];  // list positions of one staged row per lane group
   const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int64_t w = idx >> kFillLanesLog2;
   if (w >= n_dst) return;
@@ -435,11 +547,39 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_staged(LayerChunks ch, in
   const int p = ch.find(w);
   const int64_t local = w - ch.start[p];
   const StageEntry* __restrict__ row = ch.stage[p] + (size_t)local * stage_cap;
-  const int64_t beg = ch.seg[p][local].beg;
-  for (int64_t slot = idx & ((1 << kFillLanesLog2) - 1); slot < c; slot += 1 << kFillLanesLog2) {
-    const StageEntry e = row[slot];
-    col_global[o + slot] = e.t;
-    eid[o + slot] = beg + e.j;
+  const Segment g = ch.seg[p][local];
+  const int sub = (int)(idx & ((1 << kFillLanesLog2) - 1));
+  if (g.split == 0) {
+    for (int64_t slot = sub; slot < c; slot += 1 << kFillLanesLog2) {
+      const StageEntry e = row[slot];
+      col_global[o + slot] = e.t;
+      eid[o + slot] = g.beg + e.j;
+    }
+    return;
+  }
+  // The pieces of a cut list left their entries in no particular order: an entry's place is its rank by list
+  // position.  The lane group (all in one wave) shares the positions through LDS.
+  uint32_t* js = row_j[threadIdx.x >> kFillLanesLog2];
+  constexpr int kPerLane = kWave >> kFillLanesLog2;
+  StageEntry mine[kPerLane];
+#pragma unroll
+  for (int i = 0; i < kPerLane; ++i) {
+    const int slot = sub + (i << kFillLanesLog2);
+    mine[i] = StageEntry{0, 0xFFFFFFFFu};
+    if (slot < c) mine[i] = row[slot];
+    js[slot] = mine[i].j;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+  for (int i = 0; i < kPerLane; ++i) {
+    const int slot = sub + (i << kFillLanesLog2);
+    if (slot >= c) break;
+    int64_t place = 0;
+    for (int q = 0; q < (int)c; ++q) place += js[q] < mine[i].j;
+    col_global[o + place] = mine[i].t;
+    eid[o + place] = g.beg + mine[i].j;
   }
 }
 
@@ -465,12 +605,13 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int32_t* _
 
 template <bool BLEND, int VEC>
 static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, const uint32_t* pthr, int64_t n,
-                        int lpw, const FusedKeys& keys, uint32_t cap, const ScanOut& out, Ctl* ctl) {
+                        int lpw, const FusedKeys& keys, uint32_t cap, const ScanOut& out, Ctl* ctl, int piece_blocks, const Piece* pieces,
+                        const uint32_t* piece_count, uint32_t piece_cap, uint32_t piece_len) {
   switch (nf) {
-    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl); break;
-    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl); break;
-    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl); break;
-    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl); break;
+    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
+    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
+    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
+    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
   }
 }
 
@@ -523,22 +664,39 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     layer_keys(cx.seed, COOP_LABOR0, l + f, cx.group + 1, keys.K[f].Kb);
     ks[f] = (uint32_t)cx.fanouts[l + f];
   }
+  // long lists are cut into pieces (k_segments queues them); room for every piece the graph's edges could make
+  const uint32_t piece_len = cx.vec4 ? (uint32_t)g_piece_len : 0u;
+  uint32_t piece_cap = 0;
+  Piece* pieces = nullptr;
+  if (piece_len != 0 && n_new > 0) {
+    const int64_t by_edges = cx.g->n_edges / piece_len;
+    const int64_t long_lists = cx.g->n_edges / (2 * (int64_t)piece_len) + 1;
+    const int64_t cap64 = by_edges + (n_new < long_lists ? n_new : long_lists) + 1;
+    piece_cap = (uint32_t)(cap64 < ((int64_t)1 << 30) ? cap64 : ((int64_t)1 << 30));
+    pieces = alloc.get<Piece>(piece_cap, COOP_TAG_SCRATCH);
+    if (alloc.failed) return COOP_E_NOMEM;
+  }
   if (n_new > 0) {
-    COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
-                dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, (1.0 - 1e-6) / (cx.cw + cx.sw), cx.d_ctl);
+    ScanOut out{};
+    for (int f = 0; f < ps.nf; ++f) { out.stage[f] = ps.stage[f]; out.cnt[f] = ps.cnt[f]; }
+    COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
+                dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, (1.0 - 1e-6) / (cx.cw + cx.sw), cx.d_ctl,
+                piece_len, pieces, piece_cap, cx.d_piece_count + l, out);
     // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
     int lpw = g_lists_per_wave;
     if (lpw == 0) lpw = n_new >= 65536 ? 4 : 1;
     const int64_t n_waves = (n_new + lpw - 1) / lpw;
-    const dim3 grid(blocks_for(n_waves, kWavesPerBlock));
-    ScanOut out{};
-    for (int f = 0; f < ps.nf; ++f) { out.stage[f] = ps.stage[f]; out.cnt[f] = ps.cnt[f]; }
+    // the piece waves come first in the grid: one round of resident blocks, fewer if there cannot be that many pieces
+    constexpr int64_t kPieceBlocks = 2048;
+    const int piece_blocks = (int)(blocks_for(piece_cap, kWavesPerBlock) < kPieceBlocks ? blocks_for(piece_cap, kWavesPerBlock) : kPieceBlocks);
+    const dim3 grid(blocks_for(n_waves, kWavesPerBlock) + (unsigned)piece_blocks);
+    const uint32_t* pcount = cx.d_piece_count + l;
     if (cx.blend) {
-      if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl);
-      else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl);
+      if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len);
+      else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u);
     } else {
-      if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl);
-      else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl);
+      if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len);
+      else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u);
     }
   }
 

@@ -12,7 +12,10 @@ __global__ __launch_bounds__(kBlock) void k_copy_i32(const int32_t* __restrict__
   if (i < n) out[i] = in[i];
 }
 
-__global__ void k_clear_ctl(Ctl* ctl) { *ctl = Ctl{}; }
+__global__ void k_clear_ctl(Ctl* ctl, uint32_t* piece_count, int L) {
+  *ctl = Ctl{};
+  for (int l = 0; l < L; ++l) piece_count[l] = 0;
+}
 
 // The control block travels to the host by a one-thread kernel that stores it into mapped pinned memory and then a
 // ticket; the host polls the ticket.  That is a few microseconds quicker per read-back than an asynchronous copy
@@ -48,6 +51,7 @@ int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
 int g_stage_cap_override = 0;  // COOP_TUNE_STAGE_CAP
 int g_lists_per_wave = 0;      // COOP_TUNE_LISTS_PER_WAVE (0 = automatic)
 int g_fuse_layers = 1;         // COOP_TUNE_FUSE_LAYERS
+int g_piece_len = 4096;        // COOP_TUNE_PIECE_LEN
 
 }  // namespace coop
 
@@ -66,6 +70,10 @@ extern "C" int coop_tune(int knob, int64_t value) {
     case COOP_TUNE_FUSE_LAYERS:
       if (value < 0 || value > 2) return COOP_E_ARG;
       g_fuse_layers = (int)value;
+      return COOP_OK;
+    case COOP_TUNE_PIECE_LEN:
+      if (value != 0 && (value < 256 || value > ((int64_t)1 << 24) || (value & 3))) return COOP_E_ARG;
+      g_piece_len = (int)value;
       return COOP_OK;
     default:
       return COOP_E_ARG;
@@ -108,9 +116,10 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
   Ctl* h_ctl = &h_pad->ctl;
   cx.h_ctl = h_ctl;
   cx.d_ctl = alloc.get<Ctl>(1, COOP_TAG_SCRATCH);
+  cx.d_piece_count = alloc.get<uint32_t>(L, COOP_TAG_SCRATCH);
   int32_t* seed_copy = alloc.get<int32_t>(n_seeds, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
-  COOP_LAUNCH(K_FILL, k_clear_ctl, dim3(1), dim3(1), 0, s, cx.d_ctl);
+  COOP_LAUNCH(K_FILL, k_clear_ctl, dim3(1), dim3(1), 0, s, cx.d_ctl, cx.d_piece_count, L);
   if (n_seeds > 0)
     COOP_LAUNCH(K_COPY_IDS, k_copy_i32, dim3(blocks_for(n_seeds, kBlock)), dim3(kBlock), 0, s, seeds, seed_copy, n_seeds);
 

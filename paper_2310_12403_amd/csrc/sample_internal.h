@@ -14,6 +14,7 @@ struct SampleCtx {
   Alloc* alloc;
   Ctl* d_ctl;
   Ctl* h_ctl;
+  uint32_t* d_piece_count;  // [L] zeroed at the start of the call: pieces queued by the LABOR-0 pass that ran at layer l
   const int32_t* fanouts;
   int L;
   int sampler;
@@ -25,7 +26,11 @@ struct SampleCtx {
 };
 
 // One destination's neighbour list as the scan kernels see it.
-struct Segment { int64_t beg; uint32_t d; uint32_t pad; };
+struct Segment { int64_t beg; uint32_t d; uint32_t split; };  // split != 0: scanned piecewise by several waves
+
+// The q-th stretch of a long list, scanned by one wave (LABOR-0).  list == kNoPiece: an empty queue slot.
+struct Piece { uint32_t list, q; };
+constexpr uint32_t kNoPiece = 0xFFFFFFFFu;
 
 struct StageEntry { int32_t t; uint32_t j; };  // kept source vertex, its position in the destination's list
 
@@ -57,6 +62,7 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
 extern int g_stage_cap_override;
 extern int g_lists_per_wave;
 extern int g_fuse_layers;
+extern int g_piece_len;
 
 static inline unsigned blocks_for(int64_t n, int64_t per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 

@@ -351,6 +351,30 @@ def test_labor_fusion_modes(P, tiny, medium, mode):
         P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, 1)
 
 
+@pytest.mark.parametrize("piece_len", [0, 256, 300, 512])
+def test_labor_long_lists_cut_into_pieces(P, tiny, medium, piece_len):
+    """Lists longer than twice the piece length are scanned by several waves; the bytes do not change."""
+    try:
+        P.coop_tune(P.COOP_TUNE_PIECE_LEN, piece_len)
+        hubs_t = np.argsort(-np.diff(tiny.indptr_h))[:40].astype(np.int32)
+        hubs_m = np.argsort(-np.diff(medium.indptr_h))[:300].astype(np.int32)
+        assert np.diff(tiny.indptr_h)[hubs_t[0]] > 3000 and np.diff(medium.indptr_h)[hubs_m[0]] > 1400
+        for mode in (1, 2):
+            P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, mode)
+            compare(P, tiny, hubs_t, (10, 10, 10), R.LABOR0, it=3, kappa=1, seed=21)
+            compare(P, tiny, hubs_t, (5, 30), R.LABOR0, it=7, kappa=4, seed=21)                      # blended
+            compare(P, medium, hubs_m, (25, 10, 10), R.LABOR0, it=1, seed=22)
+            compare(P, medium, synth.seed_batches(medium.n, 3000, seed=14)(2).numpy(), (10, 10, 10), R.LABOR0, it=5, kappa=16, seed=22)
+            compare(P, medium, hubs_m[:20], (1450, 2), R.LABOR0, it=1, seed=22)                      # fanout above some hub degrees
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 4)                                                        # rows overflow across pieces
+        compare(P, medium, hubs_m[:50], (10, 10), R.LABOR0, it=2, seed=23)
+        compare(P, tiny, hubs_t, (10, 10), R.LABOR0, it=6, kappa=4, seed=23)
+    finally:
+        P.coop_tune(P.COOP_TUNE_PIECE_LEN, 4096)
+        P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, 1)
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 0)
+
+
 def test_cache_export_import_resumes_exactly(P):
     """A cache rebuilt from an export answers the following batches exactly as the original does."""
     n, dim = 4000, 32
