@@ -75,6 +75,7 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
     }
 #pragma unroll
     for (int gq = 0; gq < kNsGroups; ++gq) {
+      if (base + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the rest of this step lies behind the list
       const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
       uint32_t R[4];
       bool in[4];
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
   // bound such that E[#candidates] = target: R <= bound with probability (bound + 1) / 2^32
   uint64_t lo = 0, hi = 0xFFFFFFFFull;  // bisection bracket on the bound, used only after a failed pass
   uint64_t bound = ((uint64_t)target << 32) / (uint64_t)d;
-  if (bound > 0xFFFFFFFFull || d <= cap) bound = 0xFFFFFFFFull;
+  if (bound > 0xFFFFFFFFull) bound = 0xFFFFFFFFull;  // d <= target: every neighbour is a candidate
   uint32_t n_c = 0;
   for (int attempt = 0; attempt < 40; ++attempt) {
     n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, vp, sigma_a, sigma_b, cand_r, cand_j, cap);
