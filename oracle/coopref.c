@@ -12,6 +12,8 @@
  *       NS       (App. A.1.1): d_s <= k -> all of N(s), else k random neighbours,
  *       LABOR-0  (App. A.1.2): edge (t->s) kept iff r_t <= k / d_s, r_t shared by
  *                              every seed of the layer;
+ *       RW       (App. A.1.3): a random walks of length o from s with restart
+ *                              probability p, the k most visited vertices;
  *   - the random variates r_t / r_ts of App. A.7 (smoothed dependent
  *     minibatching): a PRNG keyed by (z, t, s) whose first output is the
  *     variate, two seeds z1, z2 per group of kappa iterations blended in normal
@@ -40,6 +42,15 @@
  *   - NS keeps the k smallest (R_ts, position) pairs.
  *   - edges are emitted in (seed order, adjacency order); S^{l+1} lists S^l
  *     first (same order) and then every new vertex in order of first appearance.
+ *   - RW (the paper gives it no dependent variates): draw number c of destination s at
+ *     layer l of iteration iter is U = mix(mix(c ^ K0) ^ K1 ^ mix(s ^ K2)) ^ K3 with the keys
+ *     of (seed, sampler 2, layer, g = iter); step i of walk w picks neighbour
+ *     floor(U_{2(w o + i)} d / 2^32) of its base vertex and, for i >= 1, restarts (base = s
+ *     instead of the current vertex) iff U_{2(w o + i) + 1} < floor(p 2^32); a walk that
+ *     reaches a vertex without neighbours ends; the walk's start s counts as visited only
+ *     when a step lands on it; ties in the visit counts go to the smaller vertex id; the
+ *     kept sources leave in that order (count descending, id ascending) and a block's eid
+ *     holds the visit count (these edges are edges of sum_i A^i, not of the graph).
  *   - Phi and Phi^-1 are *defined* as fixed sequences of IEEE binary64
  *     add / mul / fma and bit operations (no libm, no division, no sqrt), so
  *     that any IEEE machine reproduces them bit for bit.
@@ -57,6 +68,7 @@
 
 #define COOPREF_NS 0
 #define COOPREF_LABOR0 1
+#define COOPREF_RW 2
 
 #define COOPREF_OK 0
 #define COOPREF_E_NULL (-1)
@@ -358,6 +370,24 @@ void coopref_free_blocks(coopref_block* blocks, int L) {
   }
 }
 
+/* S^{l+1}: S^l in order, then new sources by first appearance (Eq. 2); col_local. */
+static int finish_block(const int32_t* dst, int64_t n_dst, coopref_block* blk, int32_t* pos_of /* all -1 */) {
+  const int64_t m = blk->n_edges;
+  blk->src_ids = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_dst + m > 0 ? n_dst + m : 1));
+  blk->col_local = (int32_t*)malloc(sizeof(int32_t) * (size_t)(m > 0 ? m : 1));
+  if (!blk->src_ids || !blk->col_local) return COOPREF_E_NOMEM;
+  int64_t n_src = 0;
+  for (int64_t i = 0; i < n_dst; ++i) { pos_of[dst[i]] = (int32_t)n_src; blk->src_ids[n_src++] = dst[i]; }
+  for (int64_t e = 0; e < m; ++e) {
+    int32_t t = blk->col_global[e];
+    if (pos_of[t] < 0) { pos_of[t] = (int32_t)n_src; blk->src_ids[n_src++] = t; }
+    blk->col_local[e] = pos_of[t];
+  }
+  blk->n_src = n_src;
+  for (int64_t i = 0; i < n_src; ++i) pos_of[blk->src_ids[i]] = -1; /* leave pos_of all -1 */
+  return COOPREF_OK;
+}
+
 /* Samples the neighbourhoods of dst[0..n_dst) with fanout k and fills one block. */
 static int sample_layer(const int64_t* g_indptr, const int32_t* g_indices, int64_t n_vertices,
                         const int32_t* dst, int64_t n_dst, int32_t k, int sampler, int layer,
@@ -419,22 +449,8 @@ static int sample_layer(const int64_t* g_indptr, const int32_t* g_indices, int64
   blk->indptr[n_dst] = m;
   blk->n_edges = m;
   free(pairs); free(chosen);
-
-  /* S^{l+1}: S^l in order, then new sources by first appearance (Eq. 2). */
-  blk->src_ids = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_dst + m > 0 ? n_dst + m : 1));
-  blk->col_local = (int32_t*)malloc(sizeof(int32_t) * (size_t)(m > 0 ? m : 1));
-  if (!blk->src_ids || !blk->col_local) return COOPREF_E_NOMEM;
-  int64_t n_src = 0;
-  for (int64_t i = 0; i < n_dst; ++i) { pos_of[dst[i]] = (int32_t)n_src; blk->src_ids[n_src++] = dst[i]; }
-  for (int64_t e = 0; e < m; ++e) {
-    int32_t t = blk->col_global[e];
-    if (pos_of[t] < 0) { pos_of[t] = (int32_t)n_src; blk->src_ids[n_src++] = t; }
-    blk->col_local[e] = pos_of[t];
-  }
-  blk->n_src = n_src;
-  for (int64_t i = 0; i < n_src; ++i) pos_of[blk->src_ids[i]] = -1; /* leave pos_of all -1 */
   (void)n_vertices;
-  return COOPREF_OK;
+  return finish_block(dst, n_dst, blk, pos_of);
 }
 
 int coopref_sample(const int64_t* g_indptr, const int32_t* g_indices, int64_t n_vertices,
@@ -470,6 +486,119 @@ int coopref_sample(const int64_t* g_indptr, const int32_t* g_indices, int64_t n_
   }
   free(pos_of);
   return COOPREF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Random-walk sampling (App. A.1.3).                                          */
+/* ------------------------------------------------------------------------- */
+typedef struct { int32_t v; int64_t count; } rw_visit;
+
+static int i32_cmp(const void* a, const void* b) {
+  int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+  return x < y ? -1 : (x > y ? 1 : 0);
+}
+static int rw_visit_cmp(const void* a, const void* b) { /* count descending, then id ascending */
+  const rw_visit* x = (const rw_visit*)a; const rw_visit* y = (const rw_visit*)b;
+  if (x->count != y->count) return x->count > y->count ? -1 : 1;
+  return x->v < y->v ? -1 : (x->v > y->v ? 1 : 0);
+}
+
+/* draw number c of destination s */
+static uint32_t rw_draw(const uint32_t K[4], uint32_t c, uint32_t s) {
+  return coopref_mix32(coopref_mix32(c ^ K[0]) ^ K[1] ^ coopref_mix32(s ^ K[2])) ^ K[3];
+}
+uint32_t coopref_rw_draw(uint64_t seed, int layer, uint64_t iter, uint32_t s, uint32_t c) {
+  uint32_t K[4];
+  coopref_layer_keys(seed, COOPREF_RW, layer, iter, K);
+  return rw_draw(K, c, s);
+}
+static uint64_t rw_restart_threshold(double p) { /* restart iff U < floor(p 2^32) */
+  if (p >= 1.0) return (uint64_t)1 << 32;
+  if (!(p > 0.0)) return 0;
+  return (uint64_t)(p * 4294967296.0);
+}
+
+int coopref_sample_rw(const int64_t* g_indptr, const int32_t* g_indices, int64_t n_vertices,
+                      int64_t n_edges, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts,
+                      int L, int32_t walk_length, int32_t n_walks, double restart_p, uint64_t iter,
+                      uint64_t seed, coopref_block* blocks_out) {
+  if (!g_indptr || (!g_indices && n_edges > 0) || (!seeds && n_seeds > 0) || !fanouts || !blocks_out)
+    return COOPREF_E_NULL;
+  if (L < 1 || L > 255 || n_seeds < 0 || n_vertices < 0) return COOPREF_E_ARG;
+  if (walk_length < 1 || n_walks < 1 || (int64_t)walk_length * n_walks > 1024) return COOPREF_E_ARG;
+  if (!(restart_p >= 0.0 && restart_p <= 1.0)) return COOPREF_E_ARG;
+  for (int l = 0; l < L; ++l) if (fanouts[l] < 1) return COOPREF_E_ARG;
+  memset(blocks_out, 0, sizeof(coopref_block) * (size_t)L);
+
+  int32_t* pos_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_vertices > 0 ? n_vertices : 1));
+  const int64_t n_steps = (int64_t)walk_length * n_walks;
+  int32_t* visited = (int32_t*)malloc(sizeof(int32_t) * (size_t)n_steps);
+  rw_visit* tally = (rw_visit*)malloc(sizeof(rw_visit) * (size_t)n_steps);
+  if (!pos_of || !visited || !tally) { free(pos_of); free(visited); free(tally); return COOPREF_E_NOMEM; }
+  for (int64_t v = 0; v < n_vertices; ++v) pos_of[v] = -1;
+  for (int64_t i = 0; i < n_seeds; ++i) {
+    if (seeds[i] < 0 || seeds[i] >= n_vertices) { free(pos_of); free(visited); free(tally); return COOPREF_E_RANGE; }
+    if (pos_of[seeds[i]] >= 0) { free(pos_of); free(visited); free(tally); return COOPREF_E_DUPSEED; }
+    pos_of[seeds[i]] = 1;
+  }
+  for (int64_t i = 0; i < n_seeds; ++i) pos_of[seeds[i]] = -1;
+
+  const uint64_t P = rw_restart_threshold(restart_p);
+  const int32_t* dst = seeds; int64_t n_dst = n_seeds;
+  int rc = COOPREF_OK;
+  for (int l = 0; l < L && rc == COOPREF_OK; ++l) {
+    coopref_block* blk = &blocks_out[l];
+    const int32_t k = fanouts[l];
+    uint32_t K[4];
+    coopref_layer_keys(seed, COOPREF_RW, l, iter, K);
+    const int64_t cap = n_dst * (int64_t)(k < n_steps ? k : n_steps);
+    blk->n_dst = n_dst;
+    blk->dst_ids = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_dst > 0 ? n_dst : 1));
+    blk->indptr = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n_dst + 1));
+    blk->col_global = (int32_t*)malloc(sizeof(int32_t) * (size_t)(cap > 0 ? cap : 1));
+    blk->eid = (int64_t*)malloc(sizeof(int64_t) * (size_t)(cap > 0 ? cap : 1));
+    if (!blk->dst_ids || !blk->indptr || !blk->col_global || !blk->eid) { rc = COOPREF_E_NOMEM; break; }
+    memcpy(blk->dst_ids, dst, sizeof(int32_t) * (size_t)n_dst);
+    int64_t m = 0;
+    for (int64_t i = 0; i < n_dst; ++i) {
+      const uint32_t s = (uint32_t)dst[i];
+      const int64_t s_beg = g_indptr[s], s_d = g_indptr[s + 1] - s_beg;
+      blk->indptr[i] = m;
+      if (s_d == 0) continue;
+      int64_t n_vis = 0;
+      for (int32_t w = 0; w < n_walks; ++w) {
+        uint32_t cur = s;
+        for (int32_t step = 0; step < walk_length; ++step) {
+          const uint32_t c = 2u * (uint32_t)(w * walk_length + step);
+          int restart = step == 0 || (uint64_t)rw_draw(K, c + 1u, s) < P; /* the first step leaves from s */
+          const uint32_t base = restart ? s : cur;
+          const int64_t beg = g_indptr[base], d = g_indptr[base + 1] - beg;
+          if (d == 0) break; /* dead end: the walk ends */
+          const uint64_t pick = ((uint64_t)rw_draw(K, c, s) * (uint64_t)d) >> 32;
+          cur = (uint32_t)g_indices[beg + (int64_t)pick];
+          visited[n_vis++] = (int32_t)cur;
+        }
+      }
+      /* tally: sort the visits by id, run lengths are the counts */
+      qsort(visited, (size_t)n_vis, sizeof(int32_t), i32_cmp);
+      int64_t n_t = 0;
+      for (int64_t q = 0; q < n_vis; ++q) {
+        if (n_t > 0 && tally[n_t - 1].v == visited[q]) tally[n_t - 1].count += 1;
+        else { tally[n_t].v = visited[q]; tally[n_t].count = 1; ++n_t; }
+      }
+      qsort(tally, (size_t)n_t, sizeof(rw_visit), rw_visit_cmp);
+      for (int64_t q = 0; q < n_t && q < k; ++q) {
+        blk->col_global[m] = tally[q].v; blk->eid[m] = tally[q].count; ++m;
+      }
+    }
+    blk->indptr[n_dst] = m;
+    blk->n_edges = m;
+    rc = finish_block(dst, n_dst, blk, pos_of);
+    dst = blk->src_ids; n_dst = blk->n_src;
+  }
+  if (rc != COOPREF_OK) coopref_free_blocks(blocks_out, L);
+  free(pos_of); free(visited); free(tally);
+  return rc;
 }
 
 /* Feature loading of Algorithm 1: out[i,:] = feat[ids[i],:], rows are opaque bytes. */

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "coopref.c")
 _LIB = os.path.join(_HERE, "libcoopref.so")
 
-NS, LABOR0 = 0, 1
+NS, LABOR0, RW = 0, 1, 2
 OK, E_NULL, E_RANGE, E_DUPSEED, E_ARG, E_NOMEM = 0, -1, -2, -3, -4, -5
 
 
@@ -62,6 +62,12 @@ def lib():
                                      C.c_void_p, C.c_int, C.c_int, C.c_uint64, C.c_uint32, C.c_uint64,
                                      C.POINTER(_Block)]
         L.coopref_sample.restype = C.c_int
+        L.coopref_sample_rw.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
+                                        C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_double, C.c_uint64, C.c_uint64,
+                                        C.POINTER(_Block)]
+        L.coopref_sample_rw.restype = C.c_int
+        L.coopref_rw_draw.argtypes = [C.c_uint64, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32]
+        L.coopref_rw_draw.restype = C.c_uint32
         L.coopref_free_blocks.argtypes = [C.POINTER(_Block), C.c_int]
         L.coopref_free_blocks.restype = None
         L.coopref_gather.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
@@ -116,18 +122,29 @@ def _arr(ptr, n, dtype):
     return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dtype, copy=True)
 
 
-def sample(indptr, indices, seeds, fanouts, sampler, it=0, kappa=1, seed=0):
+def rw_draw(seed, layer, it, s, c):
+    return int(lib().coopref_rw_draw(seed, layer, it, int(s) & 0xFFFFFFFF, int(c) & 0xFFFFFFFF))
+
+
+def sample(indptr, indices, seeds, fanouts, sampler, it=0, kappa=1, seed=0, rw=None):
     """Runs L = len(fanouts) sampling layers.  Returns a list of dicts, one per layer, with
-    dst_ids, indptr, col_local, col_global, eid, src_ids as numpy arrays."""
+    dst_ids, indptr, col_local, col_global, eid, src_ids as numpy arrays.
+    sampler RW takes rw = (walk_length, n_walks, restart_p); kappa plays no role there and eid holds visit counts."""
     indptr = np.ascontiguousarray(indptr, dtype=np.int64)
     indices = np.ascontiguousarray(indices, dtype=np.int32)
     seeds = np.ascontiguousarray(seeds, dtype=np.int32)
     fan = np.ascontiguousarray(fanouts, dtype=np.int32)
     L = len(fan)
     blocks = (_Block * max(L, 1))()
-    rc = lib().coopref_sample(indptr.ctypes.data, indices.ctypes.data, len(indptr) - 1, len(indices),
-                              seeds.ctypes.data, len(seeds), fan.ctypes.data, L, sampler, it, kappa, seed,
-                              blocks)
+    if sampler == RW:
+        o, a, p = rw
+        rc = lib().coopref_sample_rw(indptr.ctypes.data, indices.ctypes.data, len(indptr) - 1, len(indices),
+                                     seeds.ctypes.data, len(seeds), fan.ctypes.data, L, int(o), int(a), float(p), it, seed,
+                                     blocks)
+    else:
+        rc = lib().coopref_sample(indptr.ctypes.data, indices.ctypes.data, len(indptr) - 1, len(indices),
+                                  seeds.ctypes.data, len(seeds), fan.ctypes.data, L, sampler, it, kappa, seed,
+                                  blocks)
     if rc != OK:
         raise OracleError(rc)
     out = []

@@ -545,3 +545,161 @@ def test_error_codes(tiny):
         R.sample(indptr, indices, ok, (3,), 7)
     empty = R.sample(indptr, indices, np.zeros(0, np.int32), (3, 3), R.LABOR0)
     assert all(len(b["src_ids"]) == 0 and len(b["col_global"]) == 0 and b["indptr"].tolist() == [0] for b in empty)
+
+
+# --------------------------------------------------------------------------- #
+# Random-walk sampler (App. A.1.3)
+# --------------------------------------------------------------------------- #
+def py_rw_draw(K, c, s):
+    return py_mix32(py_mix32(c ^ K[0]) ^ K[1] ^ py_mix32(s ^ K[2])) ^ K[3]
+
+
+def brute_rw(indptr, indices, seeds, fanouts, o, a, p, seed, it):
+    """a walks of length o per destination, restart with probability p, the k most visited vertices; written from
+    the definition with Python containers (Counter, sorted), no shared arithmetic with the C oracle."""
+    P = (1 << 32) if p >= 1.0 else int(p * 4294967296.0)
+    out = []
+    dst = [int(x) for x in seeds]
+    for layer, k in enumerate(fanouts):
+        K = py_keys(seed, R.RW, layer, it)
+        ptr, cols, counts = [0], [], []
+        for s in dst:
+            nbr = lambda v: [int(x) for x in indices[int(indptr[v]):int(indptr[v + 1])]]
+            visits = collections.Counter()
+            if nbr(s):
+                for w in range(a):
+                    cur = s
+                    for step in range(o):
+                        c = 2 * (w * o + step)
+                        base = s if step == 0 or py_rw_draw(K, c + 1, s) < P else cur
+                        cand = nbr(base)
+                        if not cand:
+                            break
+                        cur = cand[(py_rw_draw(K, c, s) * len(cand)) >> 32]
+                        visits[cur] += 1
+            top = sorted(visits.items(), key=lambda vc: (-vc[1], vc[0]))[:k]
+            cols += [v for v, _ in top]
+            counts += [n for _, n in top]
+            ptr.append(len(cols))
+        src = list(dst)
+        seen = set(dst)
+        for t in cols:
+            if t not in seen:
+                seen.add(t)
+                src.append(t)
+        where = {v: i for i, v in enumerate(src)}
+        out.append(dict(dst_ids=dst, indptr=ptr, col_global=cols, eid=counts, src_ids=src, col_local=[where[t] for t in cols]))
+        dst = src
+    return out
+
+
+@pytest.mark.parametrize("o,a,p,fanouts", [(3, 100, 0.5, (10, 10)), (1, 7, 0.0, (3,)), (4, 20, 0.25, (5, 2, 4)), (2, 50, 1.0, (8,))])
+def test_rw_equals_brute_force(o, a, p, fanouts):
+    indptr, indices = small_graph()
+    seeds = np.array([5, 0, 17, 33, 60, 2], dtype=np.int32)
+    got = R.sample(indptr, indices, seeds, fanouts, R.RW, it=11, seed=77, rw=(o, a, p))
+    want = brute_rw(indptr, indices, seeds, fanouts, o, a, p, 77, 11)
+    for b, w in zip(got, want):
+        for name in ("dst_ids", "indptr", "col_global", "eid", "src_ids", "col_local"):
+            assert list(b[name]) == list(w[name]), name
+
+
+def test_rw_draw_layout():
+    K = py_keys(9, R.RW, 2, 123456789012)
+    for s, c in [(0, 0), (5, 1), (1 << 31, 599), (77, 2 * 1023 + 1)]:
+        assert R.rw_draw(9, 2, 123456789012, s, c) == py_rw_draw(K, c, s)
+    assert R.layer_keys(9, R.RW, 2, 5) != R.layer_keys(9, R.NS, 2, 5)
+
+
+def test_rw_invariants_and_reach(tiny):
+    """Every kept source lies within o hops of its destination; counts are sorted, positive, sum to at most a*o (to
+    exactly a*o when the fanout keeps everything and no walk meets a dead end); a vertex without neighbours keeps none."""
+    indptr, indices = tiny
+    n = len(indptr) - 1
+    A = sp.csr_matrix((np.ones(len(indices), dtype=np.int64), indices, indptr), shape=(n, n))
+    o, a = 3, 40
+    reach = A.copy()
+    step = A.copy()
+    for _ in range(o - 1):
+        step = (step @ A)
+        step.data[:] = 1
+        reach = reach + step
+    reach = reach.tocsr()
+    deg = np.diff(indptr)
+    seeds = synth.seed_batches(n, 300, seed=4)(0).numpy()
+    iso = np.nonzero(deg == 0)[0][:2].astype(np.int32)
+    seeds = np.unique(np.concatenate([seeds, iso])).astype(np.int32)
+    for k in (5, 1000):
+        b = R.sample(indptr, indices, seeds, (k,), R.RW, it=2, seed=8, rw=(o, a, 0.5))[0]
+        for i, s in enumerate(seeds):
+            lo, hi = b["indptr"][i], b["indptr"][i + 1]
+            cols, cnt = b["col_global"][lo:hi], b["eid"][lo:hi]
+            assert hi - lo <= k and len(set(cols)) == len(cols)
+            if deg[s] == 0:
+                assert hi == lo
+                continue
+            allowed = set(reach.indices[reach.indptr[s]:reach.indptr[s + 1]])
+            assert set(cols) <= allowed
+            assert all(c >= 1 for c in cnt) and cnt.sum() <= a * o
+            order = sorted(zip(-cnt, cols))
+            assert [v for _, v in order] == list(cols)
+            if k == 1000:   # symmetric graph: no dead ends, every step visits something
+                assert cnt.sum() == a * o
+        assert np.array_equal(b["src_ids"][:len(seeds)], seeds)
+        assert np.array_equal(b["src_ids"][b["col_local"]], b["col_global"])
+
+
+def test_rw_restart_probability_and_first_step():
+    """Path 0-1-2-3 from s = 1 with o = 2: the second step lands on s itself exactly when the walk does not restart
+    (N(0) = {1}, N(2) = {1, 3}); restarts land on 0 or 2.  So visits(0)+visits(2) = a + #restarts, and the number of
+    restarts is Binomial(a, p).  Star graph from a leaf with p = 0: the centre is visited exactly a times."""
+    indptr = np.array([0, 1, 3, 5, 6], dtype=np.int64)
+    indices = np.array([1, 0, 2, 1, 3, 2], dtype=np.int32)
+    a = 500
+    for p in (0.0, 0.25, 0.5, 1.0):
+        tot = 0
+        runs = 20
+        for it in range(runs):
+            b = R.sample(indptr, indices, np.array([1], dtype=np.int32), (10,), R.RW, it=it, seed=3, rw=(2, a, p))[0]
+            visits = dict(zip(b["col_global"].tolist(), b["eid"].tolist()))
+            assert sum(visits.values()) == 2 * a
+            first_and_restarts = visits.get(0, 0) + visits.get(2, 0)
+            tot += first_and_restarts - a
+            if p == 0.0:
+                assert first_and_restarts == a
+            if p == 1.0:
+                assert first_and_restarts == 2 * a
+        mean, sd = runs * a * p, math.sqrt(runs * a * p * (1 - p))
+        assert abs(tot - mean) <= 4 * sd + 1e-9
+    # first step uniform over N(s): vertex 2 has neighbours {1, 3}
+    c1 = 0
+    for it in range(20):
+        b = R.sample(indptr, indices, np.array([2], dtype=np.int32), (10,), R.RW, it=it, seed=4, rw=(1, a, 0.0))[0]
+        visits = dict(zip(b["col_global"].tolist(), b["eid"].tolist()))
+        assert sum(visits.values()) == a and set(visits) <= {1, 3}
+        c1 += visits.get(1, 0)
+    assert abs(c1 - 10 * a) <= 4 * math.sqrt(20 * a * 0.25)
+    # star: centre 0, leaves 1..6
+    leaves = 6
+    ip = np.array([0, leaves] + [leaves + i + 1 for i in range(leaves)], dtype=np.int64)
+    ix = np.array(list(range(1, leaves + 1)) + [0] * leaves, dtype=np.int32)
+    b = R.sample(ip, ix, np.array([3], dtype=np.int32), (10,), R.RW, it=0, seed=1, rw=(2, 500, 0.0))[0]
+    visits = dict(zip(b["col_global"].tolist(), b["eid"].tolist()))
+    assert visits[0] == 500 and b["col_global"][0] == 0 and sum(visits.values()) == 1000
+    per_leaf = np.array([visits.get(v, 0) for v in range(1, leaves + 1)])
+    assert stats.chisquare(per_leaf).pvalue > 1e-4
+
+
+def test_rw_error_codes_and_kappa_free(tiny):
+    indptr, indices = tiny
+    seeds = np.array([1, 2, 3], dtype=np.int32)
+    for bad in ((0, 10, 0.5), (3, 0, 0.5), (3, 10, 1.5), (3, 10, -0.1), (33, 32, 0.5)):
+        with pytest.raises(R.OracleError) as e:
+            R.sample(indptr, indices, seeds, (5,), R.RW, rw=bad)
+        assert e.value.code == R.E_ARG
+    with pytest.raises(R.OracleError) as e:
+        R.sample(indptr, indices, np.array([1, 1], dtype=np.int32), (5,), R.RW, rw=(3, 10, 0.5))
+    assert e.value.code == R.E_DUPSEED
+    a = R.sample(indptr, indices, seeds, (5, 5), R.RW, it=3, seed=1, rw=(3, 10, 0.5))
+    b = R.sample(indptr, indices, seeds, (5, 5), R.RW, it=4, seed=1, rw=(3, 10, 0.5))
+    assert any(not np.array_equal(x["col_global"], y["col_global"]) for x, y in zip(a, b))   # fresh draws per iteration
