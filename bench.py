@@ -39,7 +39,8 @@ def main():
     ap.add_argument("--scale-down", type=int, default=1, help="shrink the graph (development only; the result is then "
                     "labelled with the reduced workload)")
     ap.add_argument("--kappa", type=int, default=1)
-    ap.add_argument("--sampler", default=None, choices=[None, "labor0", "ns"])
+    ap.add_argument("--sampler", default=None, choices=[None, "labor0", "ns", "rw"],
+                    help="rw: random walks with the paper's parameters (length 3, 100 walks, restart probability 0.5)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--mode", default="step", choices=["step", "batch-sweep", "kappa-cache", "host-cache", "mean-agg"],
                     help="step: the benchmark contract (default).  batch-sweep: |S^l| against batch size on nested seed prefixes "
@@ -67,7 +68,7 @@ def main():
     dev = torch.device("cuda:0")
     cfg = dict(synth.CONFIGS[args.config])
     sampler_name = args.sampler or cfg["sampler"]
-    sampler = P.COOP_LABOR0 if sampler_name == "labor0" else P.COOP_NS
+    sampler = {"labor0": P.COOP_LABOR0, "ns": P.COOP_NS, "rw": P.COOP_RW}[sampler_name]
     batch = args.batch or cfg["batch"]
     fanouts = cfg["fanouts"]
     dtype = torch.float16 if cfg["dtype"] == "f16" else torch.float32
@@ -89,15 +90,20 @@ def main():
     arena = P.Arena(4 << 30)
     deg = indptr[1:] - indptr[:-1]
 
+    def sample(i):
+        if sampler == P.COOP_RW:
+            return P.coop_sample_rw(graph, get_seeds(i), fanouts, *RW_PARAMS, it=i, seed=0, arena=arena)
+        return P.coop_sample(graph, get_seeds(i), fanouts, sampler, it=i, kappa=args.kappa, seed=0, arena=arena)
+
     def step(i, out):
         arena.reset()
-        blocks = P.coop_sample(graph, get_seeds(i), fanouts, sampler, it=i, kappa=args.kappa, seed=0, arena=arena)
+        blocks = sample(i)
         P.coop_gather(feat, blocks[-1].src_ids, out=out[:blocks[-1].n_src])
         return blocks
 
     # output buffer sized once from a dry run (allocation stays outside the timed region)
     arena.reset()
-    probe = P.coop_sample(graph, get_seeds(0), fanouts, sampler, it=0, kappa=args.kappa, seed=0, arena=arena)
+    probe = sample(0)
     out = torch.empty((int(probe[-1].n_src * 1.25) + 1024, dim), dtype=dtype, device=dev)
     log("probe: " + ", ".join("|S^%d|=%d |E^%d|=%d" % (l + 1, b.n_src, l, b.n_edges) for l, b in enumerate(probe)))
 
@@ -166,8 +172,14 @@ def main():
     row_bytes = dim * esize
 
     # ---- algorithmic bytes (what the method must move) -------------------------------------------------------------
+    def rw_walk_bytes(nl):   # per destination: id + list record, 4 B per step, a 16 B list record per step that does not restart
+        o, a, p = RW_PARAMS
+        return nl * (20 + 4 * o * a + 16 * a * (o - 1) * (1 - p))
+
     def sample_bytes(nl, Dl, ml, nsrc):
         count_fill = 16 * nl + 4 * nl + 4 * Dl + 8 * (nl + 1) + 4 * ml + 8 * ml
+        if sampler == P.COOP_RW:
+            count_fill = rw_walk_bytes(nl) + 8 * (nl + 1) + 12 * ml
         unique = 4 * ml + 8 * (nl + ml) + 8 * ml + 4 * (nsrc - nl) + 4 * ml
         return count_fill + unique
 
@@ -197,6 +209,10 @@ def main():
         alg_dom = per_step / Lf
         roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
                         unit="GB/s")
+    elif dominant == "rw_walk":
+        alg_dom = sum(rw_walk_bytes(n_last[l]) + 4 * n_last[l] + 8 * m_last[l] for l in range(len(fanouts))) / len(fanouts)
+        roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
+                        unit="GB/s")
     elif dominant in ("labor_fill", "ns_fill"):
         per_step = sum(24 * n_last[l] + (4 * D_last[l] if dominant == "ns_fill" else 0) + 12 * m_last[l] for l in range(len(fanouts)))
         alg_dom = per_step / len(fanouts)
@@ -220,7 +236,7 @@ def main():
     if args.scale_down != 1:
         workload += " [REDUCED: scale_down=%d, development run]" % args.scale_down
     result = {
-        "metric": "sampled edges/s + feature-gather GB/s (% HBM peak), 3-layer LABOR-0",
+        "metric": "sampled edges/s + feature-gather GB/s (% HBM peak), 3-layer " + {"labor0": "LABOR-0", "ns": "NS", "rw": "RW"}[sampler_name],
         "value": round(stats["edges"] / t_total, 1),
         "unit": "sampled edges/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -450,6 +466,9 @@ def _stored_traffic(kernel, args):
         return None
 
 
+RW_PARAMS = (3, 100, 0.5)   # walk length, walks per destination, restart probability (the paper's experimental setup)
+
+
 def cpu_baseline(args, indptr, indices, feat, get_seeds, fanouts, sampler, last_blocks, K, P):
     """Times oracle sampling + gather on a bounded sample of the same workload: whole batches, the same seeds and
     iteration numbers as the timed region's last steps, until the time budget is used.  Also confirms that the GPU
@@ -467,7 +486,7 @@ def cpu_baseline(args, indptr, indices, feat, get_seeds, fanouts, sampler, last_
     while spent < args.cpu_seconds and batches < 8:
         seeds_h = get_seeds(i).cpu().numpy()
         t = time.perf_counter()
-        blocks = R.sample(ip_h, ix_h, seeds_h, fanouts, sampler, it=i, kappa=args.kappa, seed=0)
+        blocks = R.sample(ip_h, ix_h, seeds_h, fanouts, sampler, it=i, kappa=args.kappa, seed=0, rw=RW_PARAMS)
         rows = R.gather(feat_h, blocks[-1]["src_ids"])
         spent += time.perf_counter() - t
         edges += sum(len(b["col_global"]) for b in blocks)

@@ -41,6 +41,7 @@ extern "C" {
 /* samplers (App. A.1) */
 #define COOP_NS 0       /* neighbour sampling: d_s <= k -> all neighbours, else k uniform without replacement */
 #define COOP_LABOR0 1   /* LABOR-0: edge (t->s) kept iff r_t <= k/d_s, one r_t per source vertex and layer */
+#define COOP_RW 2       /* random walks (coop_sample_rw only) */
 
 /* feature element types */
 #define COOP_F32 0
@@ -93,7 +94,8 @@ typedef struct {
   int64_t* indptr;     /* [n_dst+1]  edges sampled for dst i are [indptr[i], indptr[i+1]), in adjacency order */
   int32_t* col_local;  /* [n_edges]  position of the edge's source vertex in src_ids */
   int32_t* col_global; /* [n_edges]  global id of the edge's source vertex */
-  int64_t* eid;        /* [n_edges]  position of the edge in the graph's `indices` array */
+  int64_t* eid;        /* [n_edges]  position of the edge in the graph's `indices` array (NS, LABOR-0); for random
+                                     walks, whose sampled edges are edges of A + A^2 + .. + A^o, the visit count */
   int32_t* src_ids;    /* [n_src]    S^{l+1} = S^l ∪ sampled sources (Eq. 2): S^l first, in order, then every new
                                      vertex in order of first appearance in col_global */
 } coop_block;
@@ -105,8 +107,10 @@ typedef struct {
  * S^{l+1} (Eq. 2) and relabels the edges.
  *
  * Random variates (App. A.7): r = R / 2^32 where, for group g = floor(iter / kappa) and c = (iter mod kappa) / kappa,
- *   U(g) = word 0 of Philox4x32-10 with key (seed low, seed high) and counter
- *          (t, s for NS | 0xFFFFFFFF for LABOR-0, l | sampler << 8, g mod 2^32);
+ *   (K0..K3)(g) = Philox4x32-10 with key (seed low, seed high) and counter (g low, g high, l | sampler << 8, 0x434F4F50);
+ *   U(g) = mix(t ^ K0) ^ K1 for LABOR-0 (one number per source vertex t and layer),
+ *          mix(mix(t ^ K0) ^ K1 ^ mix(s ^ K2)) ^ K3 for NS (one number per edge t -> s),
+ *          mix(x): x ^= x >> 16; x *= 0x7FEB352D; x ^= x >> 15; x *= 0x846CA68B; x ^= x >> 16  (32-bit);
  *   c = 0:  R = U(g);
  *   c > 0:  R = floor(2^32 Phi(cos(c pi/2) Phi^-1(u1) + sin(c pi/2) Phi^-1(u2))), u_i = (U(g+i-1) + 1/2) / 2^32.
  * kappa = 0 stands for kappa = infinity (g = 0, c = 0).  The result is a pure function of the arguments:
@@ -124,6 +128,26 @@ typedef struct {
 int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
                 int sampler, uint64_t iter, uint32_t kappa, uint64_t seed, coop_alloc_fn alloc, void* alloc_ctx,
                 void* stream, coop_block* blocks_out);
+
+/*
+ * Multi-layer minibatch sampling with the random-walk sampler (App. A.1.3): as coop_sample, but the neighbourhood of
+ * every s in S^l is formed by n_walks random walks of walk_length steps from s.  The first step of a walk goes to a
+ * uniformly drawn in-neighbour of s; each later step goes to a uniformly drawn in-neighbour of the current vertex or,
+ * with probability restart_p, of s; a walk that reaches a vertex without in-neighbours ends.  The fanouts[l] most
+ * visited vertices (ties: smaller id first; s itself counts only when a step lands on it) become the sources of s,
+ * emitted in that order; eid holds their visit counts.
+ *
+ * Draws: the paper defines no dependent variates for random walks, so every iteration draws afresh.  With
+ * (K0..K3) = the key words above for sampler COOP_RW, layer l and g = iter, draw number c of destination s is
+ * U_c = mix(mix(c ^ K0) ^ K1 ^ mix(s ^ K2)) ^ K3; step i of walk w picks neighbour floor(U_{2(w o + i)} d / 2^32) of
+ * its base vertex (d = that vertex's degree) and, for i >= 1, restarts iff U_{2(w o + i) + 1} < floor(restart_p 2^32).
+ *
+ *   walk_length >= 1, n_walks >= 1, walk_length * n_walks <= 1024, 0 <= restart_p <= 1 (else COOP_E_ARG)
+ * Everything else (arguments, ownership, synchronisation, errors) is as for coop_sample.
+ */
+int coop_sample_rw(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
+                   int32_t walk_length, int32_t n_walks, double restart_p, uint64_t iter, uint64_t seed,
+                   coop_alloc_fn alloc, void* alloc_ctx, void* stream, coop_block* blocks_out);
 
 /*
  * Feature-loading step of Algorithm 1 (the input-layer rows of the vertices in S^L): out[i, :] = feat[ids[i], :],

@@ -7,7 +7,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libcoop.so")
 
-COOP_NS, COOP_LABOR0 = 0, 1
+COOP_NS, COOP_LABOR0, COOP_RW = 0, 1, 2
 COOP_F32, COOP_F16 = 0, 1
 COOP_VALIDATE = 1
 TAG_OUTPUT, TAG_SCRATCH = 0, 1
@@ -54,6 +54,9 @@ def lib():
     L.coop_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_uint64,
                               C.c_uint32, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_CBlock)]
     L.coop_sample.restype = C.c_int
+    L.coop_sample_rw.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_int32, C.c_int32, C.c_double,
+                                 C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_CBlock)]
+    L.coop_sample_rw.restype = C.c_int
     L.coop_gather.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     L.coop_gather.restype = C.c_int
     L.coop_gather_mean.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
@@ -231,6 +234,21 @@ def coop_sample(graph, seeds, fanouts, sampler, it=0, kappa=1, seed=0, arena=Non
     al = arena if arena is not None else _TorchAllocator(seeds.device)
     rc = lib().coop_sample(graph.handle, _dev_ptr(seeds, torch.int32), seeds.numel(), fan, L, sampler, it, kappa, seed,
                            al.fn, al.ctx, _stream_ptr(stream), blocks)
+    if rc != 0 and getattr(al, "error", None) is not None:
+        raise al.error
+    _check(rc)
+    return [Block(blocks[l], al) for l in range(L)]
+
+
+def coop_sample_rw(graph, seeds, fanouts, walk_length, n_walks, restart_p, it=0, seed=0, arena=None, stream=None):
+    """Random-walk sampling: as coop_sample, with n_walks walks of walk_length steps per destination and restart
+    probability restart_p; a block's eid holds visit counts."""
+    L = len(fanouts)
+    fan = (C.c_int32 * max(L, 1))(*[int(k) for k in fanouts])
+    blocks = (_CBlock * max(L, 1))()
+    al = arena if arena is not None else _TorchAllocator(seeds.device)
+    rc = lib().coop_sample_rw(graph.handle, _dev_ptr(seeds, torch.int32), seeds.numel(), fan, L, int(walk_length), int(n_walks),
+                              float(restart_p), it, seed, al.fn, al.ctx, _stream_ptr(stream), blocks)
     if rc != 0 and getattr(al, "error", None) is not None:
         raise al.error
     _check(rc)

@@ -16,6 +16,8 @@ enum KernelId {
   K_SEGMENTS,        // LABOR-0 per-destination list records and keep thresholds
   K_NS_COUNT,        // NS count pass (min(k, d))
   K_NS_FILL,         // NS selection + fill pass
+  K_RW_WALK,         // random walks + visit tally + top-k
+  K_RW_FILL,         // random-walk fill pass
   K_SCAN_LOCAL,      // scan: per-tile exclusive scan + tile sums
   K_SCAN_OFFSET,     // scan: add the sum of the preceding tiles
   K_UNIQ_INSERT,     // hash table insert (atomic CAS / min)

@@ -1,0 +1,197 @@
+// Random-walk sampling (App. A.1.3): from every destination s, a walks of o steps; the first step goes to a uniform
+// neighbour of s, every later step to a uniform neighbour of the current vertex, or, with the restart probability p,
+// of s; the k most visited vertices become the sampled neighbours of s.
+//
+// One wave per destination.  Lanes walk (two walks per lane at a time, so that their dependent loads overlap) and
+// tally every visit in a small open-addressing table in LDS (vertex, count).  Each lane then holds its share of the
+// table in registers as keys (count << 32 | ~vertex) and the k largest keys are peeled off by wave-wide maxima:
+// count descending, vertex ascending, the order in which the sources are emitted.  The draws are keyed hashes of
+// (destination, draw counter), so the result does not depend on which lane walks which walk.
+#include "device_utils.h"
+#include "sample_internal.h"
+
+namespace coop {
+
+constexpr uint32_t kRwEmpty = 0xFFFFFFFFu;
+constexpr int kRwMaxSteps = 1024;  // largest walk_length * n_walks
+
+struct RwParams {
+  uint32_t K[4];         // key words of (seed, sampler RW, layer, iteration)
+  int32_t walk_length;   // o
+  int32_t n_walks;       // a
+  uint64_t restart_thr;  // restart iff draw < floor(p 2^32)
+  uint32_t k_eff;        // min(fanout, o * a): slots of a staged row
+};
+
+__device__ __forceinline__ uint32_t rw_draw(const uint32_t (&K)[4], uint32_t sigma, uint32_t c) {
+  return mix32(mix32(c ^ K[0]) ^ K[1] ^ sigma) ^ K[3];  // sigma = mix32(s ^ K[2])
+}
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) {
+    const unsigned long long o = __shfl_xor(v, off, kWave);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+// E = table slots per lane (table of 64 E slots, at most 3/4 full)
+template <int E>
+__global__ __launch_bounds__(kBlock) void k_rw_walk(const int64_t* __restrict__ g_indptr, const int32_t* __restrict__ g_indices,
+                                                    int64_t n_vertices, const int32_t* __restrict__ dst, int64_t n_dst, RwParams rp,
+                                                    int waves_per_block, StageEntry* __restrict__ rows, int32_t* __restrict__ cnt,
+                                                    Ctl* ctl) {
+  extern __shared__ uint32_t rw_lds[];  // per wave: 64 E vertex keys, 64 E counts
+  constexpr uint32_t T = (uint32_t)kWave * E;
+  const int wib = uniform_wave_in_block();
+  if (wib >= waves_per_block) return;
+  const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
+  if (w >= n_dst) return;
+  const uint32_t lane = (uint32_t)lane_id();
+  uint32_t* keys = rw_lds + (size_t)wib * 2 * T;
+  uint32_t* counts = keys + T;
+#pragma unroll
+  for (int e = 0; e < E; ++e) { keys[e * kWave + lane] = kRwEmpty; counts[e * kWave + lane] = 0; }
+  const int32_t s = dst[w];
+  if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
+    if (lane == 0) { atomicOr(&ctl->err_range, 1); cnt[w] = 0; }
+    return;
+  }
+  const int64_t s_beg = g_indptr[s];
+  const uint32_t s_d = (uint32_t)(g_indptr[s + 1] - s_beg);
+  if (s_d == 0) {  // wave-uniform
+    if (lane == 0) cnt[w] = 0;
+    return;
+  }
+  __builtin_amdgcn_wave_barrier();
+  const uint32_t sigma = mix32((uint32_t)s ^ rp.K[2]);
+  const int o = rp.walk_length, a = rp.n_walks;
+
+  for (int w0 = 0; w0 < a; w0 += 2 * kWave) {
+    int walk[2] = {w0 + (int)lane, w0 + kWave + (int)lane};
+    bool alive[2] = {walk[0] < a, walk[1] < a};
+    uint32_t cur[2] = {(uint32_t)s, (uint32_t)s};
+    for (int step = 0; step < o; ++step) {
+      int64_t beg[2];
+      uint32_t d[2], u[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const uint32_t c = 2u * (uint32_t)(walk[q] * o + step);
+        u[q] = rw_draw(rp.K, sigma, c);
+        const bool restart = step == 0 || (uint64_t)rw_draw(rp.K, sigma, c + 1u) < rp.restart_thr;
+        beg[q] = s_beg;
+        d[q] = s_d;
+        if (alive[q] && !restart) {
+          beg[q] = g_indptr[cur[q]];
+          d[q] = (uint32_t)(g_indptr[cur[q] + 1] - beg[q]);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        if (d[q] == 0) alive[q] = false;  // dead end: the walk ends
+        if (alive[q]) cur[q] = (uint32_t)g_indices[beg[q] + (int64_t)(((uint64_t)u[q] * (uint64_t)d[q]) >> 32)];
+      }
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        if (alive[q] && (uint64_t)cur[q] >= (uint64_t)n_vertices) {  // a neighbour id outside the graph
+          atomicOr(&ctl->err_range, 1);
+          alive[q] = false;
+        }
+        if (alive[q]) {  // tally the visit
+          uint32_t h = (cur[q] * 0x9E3779B1u) >> 7 & (T - 1);
+          for (;;) {
+            const uint32_t old = atomicCAS(&keys[h], kRwEmpty, cur[q]);
+            if (old == kRwEmpty || old == cur[q]) { atomicAdd(&counts[h], 1u); break; }
+            h = (h + 1) & (T - 1);  // at most o a <= 3 T / 4 distinct vertices: an empty slot is always reached
+          }
+        }
+      }
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  unsigned long long key[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const uint32_t v = keys[e * kWave + lane];
+    const uint32_t c = counts[e * kWave + lane];
+    key[e] = v != kRwEmpty ? ((unsigned long long)c << 32) | (unsigned long long)(0xFFFFFFFFu - v) : 0ull;
+  }
+  StageEntry* row = rows + (size_t)w * rp.k_eff;
+  uint32_t kept = 0;
+  for (; kept < rp.k_eff; ++kept) {
+    unsigned long long best = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) best = key[e] > best ? key[e] : best;
+    const unsigned long long top = wave_max_u64(best);
+    if (top == 0) break;  // fewer than k distinct vertices were visited
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if (key[e] == top) key[e] = 0;  // vertices are distinct: exactly one lane holds it
+    if (lane == 0) row[kept] = StageEntry{(int32_t)(0xFFFFFFFFu - (uint32_t)top), (uint32_t)(top >> 32)};
+  }
+  if (lane == 0) cnt[w] = (int32_t)kept;
+}
+
+// staged rows -> the block's edge arrays; eid carries the visit count (these are edges of sum_i A^i, not of the graph)
+__global__ __launch_bounds__(kBlock) void k_rw_fill(const StageEntry* __restrict__ rows, uint32_t k_eff, int64_t n_dst,
+                                                    const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
+                                                    int64_t* __restrict__ eid) {
+  const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t w = idx / k_eff;
+  if (w >= n_dst) return;
+  const int64_t slot = idx - w * k_eff;
+  const int64_t o = eptr[w];
+  if (slot >= eptr[w + 1] - o) return;
+  const StageEntry e = rows[idx];
+  col_global[o + slot] = e.t;
+  eid[o + slot] = (int64_t)e.j;
+}
+
+int rw_layer(const SampleCtx& cx, const RwConfig& rw, int l, const int32_t* dst, int64_t n_dst, coop_block* blk) {
+  hipStream_t s = cx.s;
+  Alloc& alloc = *cx.alloc;
+  RwParams rp{};
+  layer_keys(cx.seed, COOP_RW, l, cx.group, rp.K);
+  rp.walk_length = rw.walk_length;
+  rp.n_walks = rw.n_walks;
+  rp.restart_thr = rw.restart_thr;
+  const int64_t n_steps = (int64_t)rw.walk_length * rw.n_walks;
+  rp.k_eff = (uint32_t)((int64_t)cx.fanouts[l] < n_steps ? cx.fanouts[l] : n_steps);
+
+  blk->indptr = alloc.get<int64_t>(n_dst + 1, COOP_TAG_OUTPUT);
+  int32_t* cnt = alloc.get<int32_t>(n_dst, COOP_TAG_SCRATCH);
+  StageEntry* rows = alloc.get<StageEntry>(n_dst * (int64_t)rp.k_eff, COOP_TAG_SCRATCH);
+  void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
+  if (alloc.failed) return COOP_E_NOMEM;
+  if (n_dst > 0) {
+    // table of 512 slots (up to 384 visits per destination, the paper's 3 x 100 included), else 2048
+    if (n_steps <= 384) {
+      const int wpb = kWavesPerBlock;
+      COOP_LAUNCH(K_RW_WALK, k_rw_walk<8>, dim3(blocks_for(n_dst, wpb)), dim3(kBlock), (size_t)wpb * 2 * 512 * 4, s, cx.g->indptr,
+                  cx.g->indices, cx.g->n_vertices, dst, n_dst, rp, wpb, rows, cnt, cx.d_ctl);
+    } else {
+      const int wpb = 2;
+      COOP_LAUNCH(K_RW_WALK, k_rw_walk<32>, dim3(blocks_for(n_dst, wpb)), dim3(kBlock), (size_t)wpb * 2 * 2048 * 4, s, cx.g->indptr,
+                  cx.g->indices, cx.g->n_vertices, dst, n_dst, rp, wpb, rows, cnt, cx.d_ctl);
+    }
+  }
+  scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
+  int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
+  if (rc != COOP_OK) return rc;
+  const int64_t m = cx.h_ctl->total_edges;
+  blk->n_edges = m;
+  blk->col_global = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
+  blk->eid = alloc.get<int64_t>(m, COOP_TAG_OUTPUT);
+  blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
+  if (alloc.failed) return COOP_E_NOMEM;
+  if (m > 0)
+    COOP_LAUNCH(K_RW_FILL, k_rw_fill, dim3(blocks_for(n_dst * (int64_t)rp.k_eff, kBlock)), dim3(kBlock), 0, s, rows, rp.k_eff, n_dst,
+                blk->indptr, blk->col_global, blk->eid);
+  return COOP_OK;
+}
+
+}  // namespace coop

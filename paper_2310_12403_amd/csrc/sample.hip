@@ -80,12 +80,12 @@ extern "C" int coop_tune(int knob, int64_t value) {
   }
 }
 
-extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
-                           int sampler, uint64_t iter, uint32_t kappa, uint64_t seed, coop_alloc_fn alloc_fn,
-                           void* alloc_ctx, void* stream, coop_block* blocks_out) {
+static int sample_layers(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
+                         int sampler, const RwConfig* rw, uint64_t iter, uint32_t kappa, uint64_t seed, coop_alloc_fn alloc_fn,
+                         void* alloc_ctx, void* stream, coop_block* blocks_out) {
   if (!g || !fanouts || !blocks_out || !alloc_fn || (!seeds && n_seeds > 0)) return COOP_E_NULL;
   if (L < 1 || L > 255 || n_seeds < 0 || n_seeds >= ((int64_t)1 << 31)) return COOP_E_ARG;
-  if (sampler != COOP_NS && sampler != COOP_LABOR0) return COOP_E_ARG;
+  if (sampler != COOP_NS && sampler != COOP_LABOR0 && !(sampler == COOP_RW && rw)) return COOP_E_ARG;
   for (int l = 0; l < L; ++l)
     if (fanouts[l] < 1) return COOP_E_ARG;
   for (int l = 0; l < L; ++l) blocks_out[l] = coop_block{};
@@ -131,7 +131,9 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
     coop_block blk{};
     blk.n_dst = n_dst;
     blk.dst_ids = const_cast<int32_t*>(dst);
-    rc = sampler == COOP_LABOR0 ? labor_layer(labor, cx, l, dst, n_dst, &blk) : ns_layer(cx, l, dst, n_dst, &blk);
+    rc = sampler == COOP_LABOR0 ? labor_layer(labor, cx, l, dst, n_dst, &blk)
+         : sampler == COOP_NS   ? ns_layer(cx, l, dst, n_dst, &blk)
+                                : rw_layer(cx, *rw, l, dst, n_dst, &blk);
     if (rc != COOP_OK) break;
     if (n_dst + blk.n_edges >= ((int64_t)1 << 32) - 1) { rc = COOP_E_CAPACITY; break; }
 
@@ -151,4 +153,24 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
     for (int l = 0; l < L; ++l) blocks_out[l] = coop_block{};
   }
   return rc;
+}
+
+extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
+                           int sampler, uint64_t iter, uint32_t kappa, uint64_t seed, coop_alloc_fn alloc_fn,
+                           void* alloc_ctx, void* stream, coop_block* blocks_out) {
+  if (sampler == COOP_RW) return COOP_E_ARG;  // the random-walk sampler has parameters of its own: coop_sample_rw
+  return sample_layers(g, seeds, n_seeds, fanouts, L, sampler, nullptr, iter, kappa, seed, alloc_fn, alloc_ctx, stream, blocks_out);
+}
+
+extern "C" int coop_sample_rw(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
+                              int32_t walk_length, int32_t n_walks, double restart_p, uint64_t iter, uint64_t seed,
+                              coop_alloc_fn alloc_fn, void* alloc_ctx, void* stream, coop_block* blocks_out) {
+  if (walk_length < 1 || n_walks < 1 || (int64_t)walk_length * n_walks > 1024) return COOP_E_ARG;
+  if (!(restart_p >= 0.0 && restart_p <= 1.0)) return COOP_E_ARG;
+  RwConfig rw{};
+  rw.walk_length = walk_length;
+  rw.n_walks = n_walks;
+  rw.restart_thr = restart_p >= 1.0 ? (uint64_t)1 << 32 : (uint64_t)(restart_p * 4294967296.0);
+  // the paper defines no dependent variates for random walks: every iteration draws afresh (group = iteration)
+  return sample_layers(g, seeds, n_seeds, fanouts, L, COOP_RW, &rw, iter, 1u, seed, alloc_fn, alloc_ctx, stream, blocks_out);
 }

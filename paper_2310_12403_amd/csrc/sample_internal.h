@@ -53,10 +53,18 @@ struct LaborState {
   uint32_t stage_cap = 32;
 };
 
+// Parameters of the random-walk sampler (App. A.1.3).
+struct RwConfig {
+  int32_t walk_length;   // o
+  int32_t n_walks;       // a
+  uint64_t restart_thr;  // floor(p 2^32); a step restarts iff its draw is below
+};
+
 // Each fills blk->indptr, n_edges, col_global, eid and allocates col_local for layer l over dst[0..n_dst).
 // Synchronises the stream once (the edge count is read back).
 int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);
 int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);
+int rw_layer(const SampleCtx& cx, const RwConfig& rw, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);
 
 // tuning knobs (coop_tune)
 extern int g_stage_cap_override;

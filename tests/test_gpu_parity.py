@@ -411,3 +411,58 @@ def test_cache_export_import_resumes_exactly(P):
     assert e.value.code == -2 and b.vertices().numel() == 0
     out, n_miss = b.gather(table, torch.from_numpy(batches[0]).cuda())       # still usable, and empty
     assert n_miss == len(batches[0]) and torch.equal(out.cpu(), feat[torch.from_numpy(batches[0]).long()])
+
+
+def compare_rw(P, g, seeds, fanouts, o, a, p, it=0, seed=0, arena=None):
+    seeds_h = np.ascontiguousarray(seeds, dtype=np.int32)
+    want = R.sample(g.indptr_h, g.indices_h, seeds_h, fanouts, R.RW, it=it, seed=seed, rw=(o, a, p))
+    got = P.coop_sample_rw(g.graph, torch.from_numpy(seeds_h).cuda(), fanouts, o, a, p, it=it, seed=seed, arena=arena)
+    assert len(got) == len(want)
+    for l, (b, w) in enumerate(zip(got, want)):
+        assert (b.n_dst, b.n_edges, b.n_src) == (len(w["dst_ids"]), len(w["col_global"]), len(w["src_ids"])), l
+        for name in NAMES:
+            a_ = getattr(b, name).cpu().numpy()
+            assert a_.dtype == w[name].dtype and np.array_equal(a_, w[name]), (l, name)
+    return got
+
+
+@pytest.mark.parametrize("o,a,p,fanouts", [(3, 100, 0.5, (10, 10, 10)), (1, 7, 0.0, (3, 3)), (4, 20, 0.25, (5, 2, 4)),
+                                           (2, 50, 1.0, (8,)), (3, 128, 0.5, (10,)), (2, 192, 0.1, (400,)),
+                                           (4, 256, 0.5, (10, 1000)), (1024, 1, 0.3, (2000,)), (1, 1, 0.5, (1,))])
+def test_random_walk_sampler(P, tiny, o, a, p, fanouts):
+    """App. A.1.3: walks, tallies and the top-k order equal the oracle's on every array (eid = visit counts)."""
+    n_seeds = 300 if o * a <= 384 else 60
+    seeds = synth.seed_batches(tiny.n, n_seeds, seed=31)(1).numpy()
+    compare_rw(P, tiny, seeds, fanouts, o, a, p, it=5, seed=17)
+
+
+def test_random_walk_sampler_medium_and_degenerate(P, tiny, medium):
+    compare_rw(P, medium, synth.seed_batches(medium.n, 2500, seed=32)(0).numpy(), (10, 10), 3, 100, 0.5, it=2, seed=9)
+    compare_rw(P, tiny, np.zeros(0, dtype=np.int32), (10, 10), 3, 100, 0.5)                         # empty batch
+    isolated = np.nonzero(np.diff(tiny.indptr_h) == 0)[0][:3].astype(np.int32)
+    compare_rw(P, tiny, isolated, (10, 10), 3, 100, 0.5)                                            # no neighbours at all
+    hubs = np.argsort(-np.diff(tiny.indptr_h))[:5].astype(np.int32)
+    compare_rw(P, tiny, np.concatenate([hubs, isolated]), (10, 10), 3, 100, 0.5, it=1 << 40, seed=(1 << 63) + 5)
+    arena = P.Arena(64 << 20)
+    a = compare_rw(P, tiny, hubs, (10, 10), 3, 100, 0.5, it=3, seed=1, arena=arena)
+    first = [b.col_global.clone() for b in a]
+    arena.reset()
+    b = compare_rw(P, tiny, hubs, (10, 10), 3, 100, 0.5, it=3, seed=1, arena=arena)
+    assert all(torch.equal(x, y.col_global) for x, y in zip(first, b))
+
+
+def test_random_walk_sampler_errors(P, tiny):
+    seeds = torch.arange(4, dtype=torch.int32).cuda()
+    for bad in ((0, 10, 0.5), (3, 0, 0.5), (3, 10, 1.5), (3, 10, -0.1), (33, 32, 0.5), (3, 10, float("nan"))):
+        with pytest.raises(P.CoopError) as e:
+            P.coop_sample_rw(tiny.graph, seeds, (5,), *bad)
+        assert e.value.code == -4
+    with pytest.raises(P.CoopError) as e:
+        P.coop_sample(tiny.graph, seeds, (5,), P.COOP_RW)
+    assert e.value.code == -4
+    with pytest.raises(P.CoopError) as e:
+        P.coop_sample_rw(tiny.graph, torch.tensor([1, 1], dtype=torch.int32).cuda(), (5,), 3, 10, 0.5)
+    assert e.value.code == -3
+    with pytest.raises(P.CoopError) as e:
+        P.coop_sample_rw(tiny.graph, torch.tensor([tiny.n], dtype=torch.int32).cuda(), (5,), 3, 10, 0.5)
+    assert e.value.code == -2
