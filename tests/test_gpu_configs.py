@@ -84,6 +84,16 @@ def test_papers100m_shaped_full_batch(P):
     compare(P, g, ip, ix, get(7), (10, 10, 10), R.LABOR0, it=7, kappa=1, seed=0, arena=arena)
     compare(P, g, ip, ix, get(8)[:1024].contiguous(), (10, 10), R.LABOR0, it=8 * 16 + 5, kappa=16, seed=0)
     compare(P, g, ip, ix, get(9)[:512].contiguous(), (10, 10), R.NS, it=9, kappa=1, seed=0)
+    # dependent batches around group boundaries and at the last iteration of a 512-iteration run
+    for it, kappa in ((15, 16), (16, 16), (17, 16), (255, 256), (256, 256), (257, 256), (511, 16), (511, 256)):
+        compare(P, g, ip, ix, get(it)[:96].contiguous(), (10, 10), R.LABOR0, it=it, kappa=kappa, seed=0)
+    # random walks at full scale (a smaller batch: the oracle walks 300 steps per destination)
+    seeds = get(10)[:2048].contiguous()
+    got = P.coop_sample_rw(g, seeds, (10, 10), 3, 100, 0.5, it=10, seed=0, arena=arena)
+    want = R.sample(ip, ix, seeds.cpu().numpy(), (10, 10), R.RW, it=10, seed=0, rw=(3, 100, 0.5))
+    for l, (b, w) in enumerate(zip(got, want)):
+        for name in NAMES:
+            assert np.array_equal(getattr(b, name).cpu().numpy(), w[name]), (l, name)
 
 
 def test_mag240m_shaped_batch_and_host_cache(P):
