@@ -6,19 +6,26 @@
 
 namespace coop {
 
+// One destination's neighbour list as the fill pass sees it (written by the count pass, so that the fill pass
+// reaches the list with one dependent load instead of three).
+struct NsRecord { int64_t beg; uint32_t d; int32_t s; };
+
 __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
                                                      const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
-                                                     int32_t* __restrict__ cnt, Ctl* ctl) {
+                                                     int32_t* __restrict__ cnt, NsRecord* __restrict__ rec, Ctl* ctl) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_dst) return;
   const int32_t s = dst[i];
   if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
     atomicOr(&ctl->err_range, 1);
     cnt[i] = 0;
+    rec[i] = NsRecord{0, 0u, 0};
     return;
   }
-  const int64_t d = g_indptr[s + 1] - g_indptr[s];
+  const int64_t beg = g_indptr[s];
+  const int64_t d = g_indptr[s + 1] - beg;
   cnt[i] = (int32_t)(d < (int64_t)k ? d : (int64_t)k);
+  rec[i] = NsRecord{beg, (uint32_t)d, s};
 }
 
 constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list can be subsampled
@@ -33,26 +40,29 @@ constexpr int kNsGroups = 4;  // 16-byte groups per lane and step of the fast tr
 template <bool BLEND, bool VEC4>
 __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t bound,
                                                const VariateParams& vp, uint32_t sigma_a, uint32_t sigma_b,
-                                               uint32_t* __restrict__ cand_r, uint32_t* __restrict__ cand_j, uint32_t cap) {
+                                               uint32_t* __restrict__ cand_r, uint32_t* __restrict__ cand_j,
+                                               int32_t* __restrict__ cand_t, uint32_t cap) {
   const uint32_t lane = (uint32_t)lane_id();
   uint32_t n_c = 0;
-  auto append = [&](bool in, uint32_t r, uint32_t j) {
+  auto append = [&](bool in, uint32_t r, uint32_t j, int32_t t) {
     const uint64_t mask = ballot64(in);
     if (mask == 0) return;
     const uint32_t p = n_c + lanes_below(mask);
-    if (in && p < cap) { cand_r[p] = r; cand_j[p] = j; }
+    if (in && p < cap) { cand_r[p] = r; cand_j[p] = j; cand_t[p] = t; }
     n_c += (uint32_t)__popcll(mask);
   };
   if (!VEC4 || d <= (uint32_t)kWave) {
     for (uint32_t base = 0; base < d; base += kWave) {
       const uint32_t j = base + lane;
       uint32_t r = 0;
+      int32_t t = 0;
       bool in = false;
       if (j < d) {
-        r = variate<true, BLEND>(vp, (uint32_t)g_indices[beg + j], sigma_a, sigma_b);
+        t = g_indices[beg + j];
+        r = variate<true, BLEND>(vp, (uint32_t)t, sigma_a, sigma_b);
         in = r <= bound;
       }
-      append(in, r, j);
+      append(in, r, j, t);
     }
     return n_c;
   }
@@ -88,7 +98,7 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
       }
       if (ballot64(any) != 0) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) append(in[e], R[e], r + e - head);
+        for (int e = 0; e < 4; ++e) append(in[e], R[e], r + e - head, buf[gq][e]);
       }
     }
   }
@@ -96,12 +106,14 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
     const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
     const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
     uint32_t r = 0;
+    int32_t t = 0;
     bool in = false;
     if (valid) {
-      r = variate<true, BLEND>(vp, (uint32_t)p[pos], sigma_a, sigma_b);
+      t = p[pos];
+      r = variate<true, BLEND>(vp, (uint32_t)t, sigma_a, sigma_b);
       in = r <= bound;
     }
-    append(in, r, pos - head);
+    append(in, r, pos - head, t);
   }
   return n_c;
 }
@@ -113,23 +125,23 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
 //   3. every candidate's rank by (R, j) among the candidates is counted: ranks below k are kept;
 //   4. every kept candidate's place is the number of kept candidates in front of it in the list.
 template <bool BLEND, bool VEC4>
-__global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ g_indptr,
-                                                    const int32_t* __restrict__ g_indices,
-                                                    const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
+__global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ g_indices,
+                                                    const NsRecord* __restrict__ rec, int64_t n_dst, uint32_t k,
                                                     uint32_t cap, uint32_t target, int waves_per_block, VariateParams vp,
                                                     const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
                                                     int64_t* __restrict__ eid, Ctl* ctl) {
-  extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags
+  extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
   const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
   if (w >= n_dst) return;
   const uint32_t lane = (uint32_t)lane_id();
   const int64_t o = eptr[w];
-  if (o == eptr[w + 1]) return;
-  const int32_t s = dst[w];
-  const int64_t beg = g_indptr[s];
-  const uint32_t d = (uint32_t)(g_indptr[s + 1] - beg);
+  const NsRecord g = rec[w];
+  const int32_t s = g.s;
+  const int64_t beg = g.beg;
+  const uint32_t d = g.d;
+  if (d == 0) return;
   if (d <= k) {
     for (uint32_t j = lane; j < d; j += kWave) {
       col_global[o + j] = g_indices[beg + j];
@@ -141,9 +153,10 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
     if (lane == 0) atomicOr(&ctl->err_capacity, 1);
     return;
   }
-  uint32_t* cand_r = lds_words + (size_t)wib * cap * 3;  // [cap] variates
+  uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;  // [cap] variates
   uint32_t* cand_j = cand_r + cap;                       // [cap] positions (d < 2^31)
   uint32_t* cand_k = cand_j + cap;                       // [cap] 1 = among the k smallest
+  int32_t* cand_t = reinterpret_cast<int32_t*>(cand_k + cap);  // [cap] the neighbours themselves
   const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)s);
   const uint32_t sigma_b = BLEND ? ns_sigma(vp.K.Kb, (uint32_t)s) : 0u;
 
@@ -153,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
   if (bound > 0xFFFFFFFFull) bound = 0xFFFFFFFFull;  // d <= target: every neighbour is a candidate
   uint32_t n_c = 0;
   for (int attempt = 0; attempt < 40; ++attempt) {
-    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, vp, sigma_a, sigma_b, cand_r, cand_j, cap);
+    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap);
     if (n_c >= k && n_c <= cap) break;
     // cannot be bracketed (more than cap - k equal variates): report instead of guessing
     if (n_c < k) {
@@ -164,7 +177,8 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
       hi = bound - 1;
     }
     if (lo > hi) { n_c = 0; break; }
-    bound = lo + (hi - lo) / 2;
+    // too few and no upper failure yet: double the bound (a midpoint of the whole range would flood the buffer)
+    bound = (hi == 0xFFFFFFFFull && n_c < k) ? (2 * bound + 1 < hi ? 2 * bound + 1 : hi) : lo + (hi - lo) / 2;
     __builtin_amdgcn_wave_barrier();
   }
   if (n_c < k || n_c > cap) {
@@ -173,6 +187,34 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
   }
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
+  if (n_c <= (uint32_t)kWave) {
+    // the usual case: one candidate per lane, ranked through lane reads (no LDS round trips in the loops)
+    const bool has = lane < n_c;
+    const uint32_t my_r = has ? cand_r[lane] : 0xFFFFFFFFu;
+    const uint32_t my_j = has ? cand_j[lane] : 0xFFFFFFFFu;
+    const int32_t my_t = has ? cand_t[lane] : 0;
+    const uint64_t my_key = ((uint64_t)my_r << 32) | my_j;  // order by (variate, list position)
+    uint32_t rank = 0;
+    for (uint32_t q = 0; q < n_c; ++q) {
+      const uint64_t key = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)my_r, (int)q) << 32) |
+                           (uint32_t)__builtin_amdgcn_readlane((int)my_j, (int)q);
+      rank += key < my_key;
+    }
+    const bool keep = has && rank < k;
+    const uint64_t kept = ballot64(keep);
+    uint32_t place = 0;  // kept candidates in front of this one in the list
+    uint64_t rest = kept;
+    while (rest != 0) {
+      const int q = __builtin_ctzll(rest);
+      rest &= rest - 1;
+      place += (uint32_t)__builtin_amdgcn_readlane((int)my_j, q) < my_j;
+    }
+    if (keep) {
+      col_global[o + place] = my_t;
+      eid[o + place] = beg + my_j;
+    }
+    return;
+  }
   for (uint32_t i = lane; i < n_c; i += kWave) {
     const uint32_t my_r = cand_r[i], my_j = cand_j[i];
     uint32_t rank = 0;
@@ -189,7 +231,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int64_t* __restrict__ 
     const uint32_t my_j = cand_j[i];
     uint32_t place = 0;
     for (uint32_t q = 0; q < n_c; ++q) place += cand_k[q] && cand_j[q] < my_j;
-    col_global[o + place] = g_indices[beg + my_j];
+    col_global[o + place] = cand_t[i];
     eid[o + place] = beg + my_j;
   }
 }
@@ -205,11 +247,12 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   vp.sw = cx.sw;
   blk->indptr = alloc.get<int64_t>(n_dst + 1, COOP_TAG_OUTPUT);
   int32_t* cnt = alloc.get<int32_t>(n_dst, COOP_TAG_SCRATCH);
+  NsRecord* rec = alloc.get<NsRecord>(n_dst, COOP_TAG_SCRATCH);
   void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
   if (alloc.failed) return COOP_E_NOMEM;
   if (n_dst > 0)
     COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices, dst, n_dst,
-                k, cnt, cx.d_ctl);
+                k, cnt, rec, cx.d_ctl);
   scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
   int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
   if (rc != COOP_OK) return rc;
@@ -225,12 +268,17 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
     const uint32_t k_sel = k < kNsMaxSelect ? k : kNsMaxSelect;
     uint32_t cap = 256;
     while (cap < 4 * k_sel) cap <<= 1;
-    const uint32_t target = 2 * k_sel + 16;
+    // expected candidates: k + 4 sqrt(k) + 4 (at most 2k + 16).  A list that turns up fewer than k candidates (about one
+    // in 10^4) is simply collected again with a bisected bound; every candidate beyond the k-th costs ranking work.
+    uint32_t root = 1;
+    while (root * root < k_sel) ++root;
+    uint32_t target = k_sel + 4 * root + 4;
+    if (target > 2 * k_sel + 16) target = 2 * k_sel + 16;
     int wpb = kWavesPerBlock;
-    while (wpb > 1 && (size_t)wpb * cap * 12 > 49152) wpb >>= 1;
-    const size_t shmem = (size_t)wpb * cap * 12;
+    while (wpb > 1 && (size_t)wpb * cap * 16 > 65536) wpb >>= 1;
+    const size_t shmem = (size_t)wpb * cap * 16;
     const dim3 grid(blocks_for(n_dst, wpb));
-#define COOP_NS_ARGS cx.g->indptr, cx.g->indices, dst, n_dst, k, cap, target, wpb, vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl
+#define COOP_NS_ARGS cx.g->indices, rec, n_dst, k, cap, target, wpb, vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl
     if (cx.blend) {
       if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
       else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
