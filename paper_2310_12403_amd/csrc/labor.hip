@@ -18,6 +18,18 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr uint32_t kAllThr = 0xFFFFFFFFu;  // threshold of a list no longer than the fanout: everything is kept
 constexpr int kScanGroups = 4;             // 16-byte groups per lane and step of the fast scan (4 KiB per wave and step)
 
+// Second filter of the blended path: the blend itself in fp32.  A kept edge has n = cw n1 + sw n2 below
+// tau = Phi^-1 of slightly more than (thr + 1) / 2^32; the fp32 estimate of n (two approx_phi_inv_f32, each within 4e-4
+// of the kit's value; 4e-3 is allowed for) must therefore lie below the value returned here, rounded up to a float.
+__device__ __forceinline__ float blend_second_threshold(uint32_t thr, double cs /* cw + sw */) {
+  if (thr >= 0x7FFFFFF0u) return __builtin_inff();
+  const double tau = kit_phi_inv_u32(thr + 8u);
+  const double lim = __builtin_fma(cs, 4e-3, tau * (1.0 - 1e-6)) + 1e-5;
+  float t = (float)lim;
+  if ((double)t < lim) t = __uint_as_float(t >= 0.0f ? __float_as_uint(t) + 1u : __float_as_uint(t) - 1u);  // next float up
+  return t;
+}
+
 struct ScanOut {
   StageEntry* stage[kMaxFuse];
   int32_t* cnt[kMaxFuse];
@@ -62,7 +74,8 @@ constexpr int kSegBlock = 1024;  // large blocks: one queue reservation (a same-
 __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
                                                      const int32_t* __restrict__ dst, int64_t n, int nf,
                                                      uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, Segment* __restrict__ seg,
-                                                     uint32_t* __restrict__ thr, uint32_t* __restrict__ pthr, double inv_cs, Ctl* ctl,
+                                                     uint32_t* __restrict__ thr, uint32_t* __restrict__ pthr, float* __restrict__ lim2,
+                                                     double inv_cs, double cs, int queued, Ctl* ctl,
                                                      uint32_t piece_len, Piece* __restrict__ pieces, uint32_t piece_cap,
                                                      uint32_t* __restrict__ piece_count, ScanOut out) {
   __shared__ uint32_t s_wave_at[kSegBlock / kWave];
@@ -86,8 +99,13 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
         const uint32_t t = g.d > ks[f] ? (uint32_t)(((uint64_t)ks[f] << 32) / (uint64_t)g.d) : kAllThr;
         sampled &= t != kAllThr;
         thr[(int64_t)f * n + i] = t;
-        if (pthr) pthr[(int64_t)f * n + i] = blend_pre_threshold(t, inv_cs);
+        if (pthr) {
+          pthr[(int64_t)f * n + i] = blend_pre_threshold(t, inv_cs);
+          lim2[(int64_t)f * n + i] = blend_second_threshold(t, cs);
+        }
+        if (queued) out.cnt[f][i] = 0;  // kept edges are counted by atomics
       }
+    if (queued) g.split = 2;  // the row is filled in no particular order: the fill pass ranks it
   }
   if (piece_len == 0) {  // wave-uniform
     if (live) seg[i] = g;
@@ -128,7 +146,7 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
         if (at + q < piece_cap) pieces[at + q] = fits ? Piece{list, q} : Piece{kNoPiece, 0u};
     }
     if (fits && np != 0) {
-      g.split = 1;
+      g.split |= 1;
 #pragma unroll
       for (int f = 0; f < kMaxFuse; ++f)
         if (f < nf) out.cnt[f][i] = 0;  // the pieces add their counts
@@ -258,83 +276,187 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
   }
 }
 
-// Candidate queue of the blended fast scan, one per wave, in LDS: neighbours that passed the pre-threshold and
-// wait for an exact evaluation.  Evaluating them 64 at a time keeps every lane busy in the expensive part.
+// ---- blended variates (c > 0) -------------------------------------------------------------------------------------
+// The exact blend (two Phi^-1 and a Phi in binary64) costs about a hundred times the integer path, so it is reached
+// in three stages, each working on a full wave of candidates taken from a per-wave queue in LDS:
+//   1. min(U1, U2) <= pre-threshold (per list and layer; integer compare in the traversal loop);
+//   2. the blend in fp32 below the second threshold (a few dozen instructions; discards all but about the kept ones);
+//   3. the exact blend; a kept edge takes the next free slot of its destination's staging row with an atomic on the
+//      row's counter.  Rows filled this way are unordered: the fill pass ranks them by list position.
+// The stage-3 queue lives across the lists (or pieces) of a wave, so that the expensive stage runs on full waves.
 constexpr int kQueueCap = 2 * kWave;
 struct BlendQueue {
   int32_t t[kQueueCap];
-  int32_t j[kQueueCap];
+  uint32_t j[kQueueCap];
   uint32_t u1[kQueueCap];
   uint32_t u2[kQueueCap];
-  uint32_t layer[kQueueCap];
+  uint32_t list[kQueueCap];   // destination, index within the pass
+  uint32_t layer[kQueueCap];  // covered layer, 0 .. NF-1
+  uint32_t thr[kQueueCap];    // keep threshold of (list, layer)
+  float lim2[kQueueCap];      // second threshold of (list, layer)
 };
 
-// exact evaluation of queue entries [0, n_eval) (n_eval <= 64), kept ones go to the register lists
-template <int NF>
-__device__ __forceinline__ void blend_eval(const BlendQueue* __restrict__ q, uint32_t n_eval, const uint32_t (&thr)[NF],
-                                           const FusedKeys& keys, KeptRegs (&kept)[NF]) {
+struct BlendEntry {
+  int32_t t;
+  uint32_t j, u1, u2, list, layer, thr;
+  float lim2;
+};
+
+// Stage-1 queue: one per covered layer, three words per candidate: the neighbour, its list position, and which of
+// the wave's lists it belongs to (everything else is recomputed from t or looked up per list at stage 2).
+struct FirstQueue {
+  int32_t t[kMaxFuse][kQueueCap];
+  uint32_t j[kMaxFuse][kQueueCap];
+  uint32_t slot[kMaxFuse][kQueueCap];
+};
+
+struct BlendState {
+  FirstQueue* q1;  // passed stage 1 (any list of this wave)
+  BlendQueue* q2;  // passed stage 2 (any list of this wave)
+  uint32_t n1[kMaxFuse] = {0, 0, 0, 0};
+  uint32_t n2 = 0;  // wave-uniform fill levels (each below 64 between calls)
+};
+
+__device__ __forceinline__ BlendEntry queue_get(const BlendQueue* __restrict__ q, uint32_t i) {
+  return BlendEntry{q->t[i], q->j[i], q->u1[i], q->u2[i], q->list[i], q->layer[i], q->thr[i], q->lim2[i]};
+}
+__device__ __forceinline__ void queue_put(BlendQueue* __restrict__ q, uint32_t i, const BlendEntry& e) {
+  q->t[i] = e.t; q->j[i] = e.j; q->u1[i] = e.u1; q->u2[i] = e.u2; q->list[i] = e.list; q->layer[i] = e.layer; q->thr[i] = e.thr;
+  q->lim2[i] = e.lim2;
+}
+// appends the entries of the lanes with `in` set (fill level below 64 before, so at most 128 after)
+__device__ __forceinline__ void queue_push(BlendQueue* __restrict__ q, uint32_t& qn, bool in, const BlendEntry& e) {
+  const uint64_t mask = ballot64(in);
+  if (mask == 0) return;
+  if (in) queue_put(q, qn + lanes_below(mask), e);
+  qn += (uint32_t)__popcll(mask);
+  __builtin_amdgcn_wave_barrier();
+}
+// drops the first 64 entries: the rest (fewer than 64) moves to the front
+__device__ __forceinline__ void queue_pop_wave(BlendQueue* __restrict__ q, uint32_t& qn) {
   const uint32_t lane = (uint32_t)lane_id();
-  int32_t t = 0, j = 0;
-  uint32_t l = 0;
-  bool keep = false;
-  if (lane < n_eval) {
-    t = q->t[lane];
-    j = q->j[lane];
-    l = q->layer[lane];
-    const double n1 = kit_phi_inv_u32(q->u1[lane]);
-    const double n2 = kit_phi_inv_u32(q->u2[lane]);
+  const uint32_t rest = qn - kWave;
+  BlendEntry e{};
+  if (lane < rest) e = queue_get(q, kWave + lane);
+  __builtin_amdgcn_wave_barrier();
+  if (lane < rest) queue_put(q, lane, e);
+  qn = rest;
+  __builtin_amdgcn_wave_barrier();
+}
+
+// stage 3 on entries [0, n) of q2 (n <= 64)
+template <int NF>
+__device__ __forceinline__ void blend_exact(const BlendState& st, uint32_t n, const FusedKeys& keys, uint32_t stage_cap, const ScanOut& out,
+                                            Ctl* ctl) {
+  const uint32_t lane = (uint32_t)lane_id();
+  if (lane < n) {
+    const BlendEntry e = queue_get(st.q2, lane);
+    const double n1 = kit_phi_inv_u32(e.u1);
+    const double n2 = kit_phi_inv_u32(e.u2);
     const uint32_t R = kit_phi_to_u32(__builtin_fma(keys.cw, n1, keys.sw * n2));
-    uint32_t my_thr = thr[0];
+    if (R <= e.thr) {
+      int32_t* cnt = out.cnt[0];
+      StageEntry* stage = out.stage[0];
 #pragma unroll
-    for (int f = 1; f < NF; ++f)
-      if (l == (uint32_t)f) my_thr = thr[f];
-    keep = R <= my_thr;
-  }
-#pragma unroll
-  for (int f = 0; f < NF; ++f) {
-    uint64_t mm = ballot64(keep && l == (uint32_t)f);
-    while (mm != 0) {
-      const int src_lane = __builtin_ctzll(mm);
-      mm &= mm - 1;
-      kept[f].push(lane, __builtin_amdgcn_readlane(t, src_lane), __builtin_amdgcn_readlane(j, src_lane));
+      for (int f = 1; f < NF; ++f)
+        if (e.layer == (uint32_t)f) { cnt = out.cnt[f]; stage = out.stage[f]; }
+      const uint32_t at = (uint32_t)atomicAdd(&cnt[e.list], 1);
+      if (at < stage_cap) stage[(size_t)e.list * stage_cap + at] = StageEntry{e.t, e.j};
+      else if (at == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
     }
   }
 }
 
-// appends the lanes with `pre` set to the queue; evaluates a full wave of candidates whenever 64 are waiting
+// What stage 2 needs to know about the wave's lists: lane i holds the thresholds of list first + i.
 template <int NF>
-__device__ __forceinline__ void blend_enqueue(BlendQueue* __restrict__ q, uint32_t& qn, bool pre, int32_t t, int32_t j, uint32_t u1,
-                                              uint32_t u2, uint32_t layer, const uint32_t (&thr)[NF], const FusedKeys& keys,
-                                              KeptRegs (&kept)[NF]) {
+struct ListBlend {
+  uint32_t first;
+  uint32_t thr[NF];
+  float lim2[NF];
+};
+
+// stage 2 on entries [first, first + n) of layer l's stage-1 queue (n <= 64): the two uniforms again, the blend in
+// fp32; survivors go to q2, which is drained whenever a full wave waits
+template <int NF>
+__device__ __forceinline__ void blend_second(BlendState& st, int l, uint32_t first, uint32_t n, const ListBlend<NF>& lb, const FusedKeys& keys,
+                                             float cwf, float swf, uint32_t stage_cap, const ScanOut& out, Ctl* ctl) {
+  const uint32_t lane = (uint32_t)lane_id();
+  BlendEntry e{};
+  bool pass = false;
+  uint32_t slot = 0;
+  if (lane < n) {
+    e.t = st.q1->t[l][first + lane];
+    e.j = st.q1->j[l][first + lane];
+    slot = st.q1->slot[l][first + lane];
+  }
+  // thresholds of the candidate's list: from the lane that holds them (every lane takes part in the exchange)
+  e.thr = (uint32_t)__shfl((int)lb.thr[l], (int)slot, kWave);
+  e.lim2 = __shfl(lb.lim2[l], (int)slot, kWave);
+  if (lane < n) {
+    e.u1 = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)e.t, 0u);
+    e.u2 = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)e.t, 0u);
+    e.list = lb.first + slot;
+    e.layer = (uint32_t)l;
+    const float est = __builtin_fmaf(cwf, approx_phi_inv_f32(e.u1), swf * approx_phi_inv_f32(e.u2));
+    pass = est <= e.lim2;
+  }
+  queue_push(st.q2, st.n2, pass, e);
+  if (st.n2 >= (uint32_t)kWave) {
+    blend_exact<NF>(st, kWave, keys, stage_cap, out, ctl);
+    __builtin_amdgcn_wave_barrier();
+    queue_pop_wave(st.q2, st.n2);
+  }
+}
+
+// stage-1 passers of layer l join its queue; a full wave of them goes through stage 2 at once
+template <int NF>
+__device__ __forceinline__ void blend_first(BlendState& st, int l, bool pre, int32_t t, uint32_t j, uint32_t slot, const ListBlend<NF>& lb,
+                                            const FusedKeys& keys, float cwf, float swf, uint32_t stage_cap, const ScanOut& out, Ctl* ctl) {
   const uint64_t mask = ballot64(pre);
   if (mask == 0) return;
-  const uint32_t lane = (uint32_t)lane_id();
   if (pre) {
-    const uint32_t pos = qn + lanes_below(mask);  // < 128: fewer than 64 wait, at most 64 arrive
-    q->t[pos] = t; q->j[pos] = j; q->u1[pos] = u1; q->u2[pos] = u2; q->layer[pos] = layer;
+    const uint32_t at = st.n1[l] + lanes_below(mask);  // below 128
+    st.q1->t[l][at] = t;
+    st.q1->j[l][at] = j;
+    st.q1->slot[l][at] = slot;
   }
-  qn += (uint32_t)__popcll(mask);
+  st.n1[l] += (uint32_t)__popcll(mask);
   __builtin_amdgcn_wave_barrier();
-  if (qn >= (uint32_t)kWave) {
-    blend_eval<NF>(q, kWave, thr, keys, kept);
+  if (st.n1[l] >= (uint32_t)kWave) {
+    blend_second<NF>(st, l, 0u, kWave, lb, keys, cwf, swf, stage_cap, out, ctl);
+    const uint32_t lane = (uint32_t)lane_id();
+    const uint32_t rest = st.n1[l] - kWave;  // fewer than 64: to the front
+    int32_t mt = 0;
+    uint32_t mj = 0, ms = 0;
+    if (lane < rest) { mt = st.q1->t[l][kWave + lane]; mj = st.q1->j[l][kWave + lane]; ms = st.q1->slot[l][kWave + lane]; }
     __builtin_amdgcn_wave_barrier();
-    const uint32_t rest = qn - kWave;  // < 64: move the tail to the front
-    int32_t mt = 0, mj = 0;
-    uint32_t m1 = 0, m2 = 0, ml = 0;
-    if (lane < rest) { mt = q->t[kWave + lane]; mj = q->j[kWave + lane]; m1 = q->u1[kWave + lane]; m2 = q->u2[kWave + lane]; ml = q->layer[kWave + lane]; }
-    __builtin_amdgcn_wave_barrier();
-    if (lane < rest) { q->t[lane] = mt; q->j[lane] = mj; q->u1[lane] = m1; q->u2[lane] = m2; q->layer[lane] = ml; }
-    qn = rest;
+    if (lane < rest) { st.q1->t[l][lane] = mt; st.q1->j[l][lane] = mj; st.q1->slot[l][lane] = ms; }
+    st.n1[l] = rest;
     __builtin_amdgcn_wave_barrier();
   }
 }
 
-// Blended fast scan: same traversal as labor_scan_fast; per entry and layer two mixer evaluations and one compare
-// against the pre-threshold, exact evaluation only for the candidates.
+// what still waits in the stage-1 queues goes through stage 2
 template <int NF>
-__device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t j0,
-                                                      const uint32_t (&thr)[NF], const uint32_t (&pthr)[NF], const FusedKeys& keys,
-                                                      BlendQueue* __restrict__ q, KeptRegs (&kept)[NF]) {
+__device__ __forceinline__ void blend_flush_first(BlendState& st, const ListBlend<NF>& lb, const FusedKeys& keys, uint32_t stage_cap,
+                                                  const ScanOut& out, Ctl* ctl) {
+  const float cwf = (float)keys.cw, swf = (float)keys.sw;
+#pragma unroll
+  for (int l = 0; l < NF; ++l)
+    if (st.n1[l] != 0) {
+      blend_second<NF>(st, l, 0u, st.n1[l], lb, keys, cwf, swf, stage_cap, out, ctl);
+      st.n1[l] = 0;
+      __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Blended scan of entries [beg, beg + d) of the wave's list number `slot` (a whole list, or the piece that starts at
+// list position j0): same traversal as labor_scan_fast; per entry and layer two mixer evaluations and the stage-1
+// compare against pthr.  Candidates may still wait in the queues on return.
+template <int NF>
+__device__ __forceinline__ void labor_scan_blend(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t j0, uint32_t slot,
+                                                 const uint32_t (&pthr)[NF], const ListBlend<NF>& lb, const FusedKeys& keys, BlendState& st,
+                                                 uint32_t stage_cap, const ScanOut& out, Ctl* ctl) {
   constexpr uint32_t kStep = kWave * 4 * kScanGroups;
   const int64_t abeg = beg & ~(int64_t)3;
   const uint32_t head = (uint32_t)(beg - abeg);
@@ -343,7 +465,7 @@ __device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict_
   const uint32_t vec_beg = head ? 4u : 0u;
   const int32_t* __restrict__ p = g_indices + abeg;
   const uint32_t lane = (uint32_t)lane_id();
-  uint32_t qn = 0;
+  const float cwf = (float)keys.cw, swf = (float)keys.sw;
 
   for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
     i32x4 buf[kScanGroups];
@@ -359,17 +481,15 @@ __device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict_
     for (int gq = 0; gq < kScanGroups; ++gq) {
       if (base + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the rest of this step lies behind the list
       const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
-      uint32_t u1[NF][4], u2[NF][4];
       bool pre[NF][4];
       bool any = false;
 #pragma unroll
       for (int l = 0; l < NF; ++l) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          u1[l][e] = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)buf[gq][e], 0u);
-          u2[l][e] = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)buf[gq][e], 0u);
-          const uint32_t lo = u1[l][e] < u2[l][e] ? u1[l][e] : u2[l][e];
-          pre[l][e] = ok[gq] & (lo <= pthr[l]);
+          const uint32_t u1 = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)buf[gq][e], 0u);
+          const uint32_t u2 = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)buf[gq][e], 0u);
+          pre[l][e] = ok[gq] & ((u1 < u2 ? u1 : u2) <= pthr[l]);
           any |= pre[l][e];
         }
       }
@@ -377,8 +497,7 @@ __device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict_
 #pragma unroll
         for (int l = 0; l < NF; ++l) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            blend_enqueue<NF>(q, qn, pre[l][e], buf[gq][e], (int32_t)(r + e - head + j0), u1[l][e], u2[l][e], (uint32_t)l, thr, keys, kept);
+          for (int e = 0; e < 4; ++e) blend_first<NF>(st, l, pre[l][e], buf[gq][e], r + e - head + j0, slot, lb, keys, cwf, swf, stage_cap, out, ctl);
         }
       }
     }
@@ -392,15 +511,11 @@ __device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict_
     for (int l = 0; l < NF; ++l) {
       const uint32_t a = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)t, 0u);
       const uint32_t b = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)t, 0u);
-      blend_enqueue<NF>(q, qn, valid && (a < b ? a : b) <= pthr[l], t, (int32_t)(pos - head + j0), a, b, (uint32_t)l, thr, keys, kept);
+      blend_first<NF>(st, l, valid && (a < b ? a : b) <= pthr[l], t, pos - head + j0, slot, lb, keys, cwf, swf, stage_cap, out, ctl);
     }
   }
-  if (qn != 0) blend_eval<NF>(q, qn, thr, keys, kept);
-  __builtin_amdgcn_wave_barrier();
 }
 
-// Scan pass.  Each wave takes `lists_per_wave` consecutive destinations; their records are fetched by one coalesced
-// load (lane i holds record i), so the pointer chase destination -> list start is paid once per wave.
 // The first `piece_blocks` blocks of the grid take the pieces of the long lists (wave w takes pieces w, w + W, ... of
 // the queue, W = their number of waves; the queue length is read from device memory, so every wave ends after a
 // bounded number of steps).  A piece adds its kept-edge counts to the list's counters and puts its entries wherever
@@ -408,10 +523,18 @@ __device__ __forceinline__ void labor_scan_fast_blend(const int32_t* __restrict_
 template <bool BLEND, int VEC, int NF>
 __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict__ g_indices, const Segment* __restrict__ seg,
                                                        const uint32_t* __restrict__ thr_all, const uint32_t* __restrict__ pthr_all,
-                                                       int64_t n, int lists_per_wave, FusedKeys keys, uint32_t stage_cap, ScanOut out,
+                                                       const float* __restrict__ lim2_all, int64_t n, int lists_per_wave, FusedKeys keys,
+                                                       uint32_t stage_cap, ScanOut out,
                                                        Ctl* ctl, int piece_blocks, const Piece* __restrict__ pieces,
                                                        const uint32_t* __restrict__ piece_count, uint32_t piece_cap, uint32_t piece_len) {
-  __shared__ BlendQueue queues[BLEND && VEC == 4 ? kWavesPerBlock : 1];
+  constexpr bool kQueued = BLEND && VEC == 4;  // blended variates through the staged queues
+  __shared__ FirstQueue first_queues[kQueued ? kWavesPerBlock : 1];
+  __shared__ BlendQueue second_queues[kQueued ? kWavesPerBlock : 1];
+  BlendState bst{};
+  if constexpr (kQueued) {
+    bst.q1 = &first_queues[uniform_wave_in_block()];
+    bst.q2 = &second_queues[uniform_wave_in_block()];
+  }
   const uint32_t lane = (uint32_t)lane_id();
   if constexpr (VEC == 4) {
     if ((int)blockIdx.x < piece_blocks) {
@@ -436,15 +559,22 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
         uint32_t thr[NF];
 #pragma unroll
         for (int l = 0; l < NF; ++l) thr[l] = (uint32_t)__builtin_amdgcn_readfirstlane((int)thr_all[(int64_t)l * n + list]);
-        KeptRegs kept[NF];
-        if constexpr (BLEND) {
+        if constexpr (kQueued) {
           uint32_t pthr[NF];
+          ListBlend<NF> lb;
+          lb.first = list;  // every lane holds this list's thresholds: slot 0
 #pragma unroll
-          for (int l = 0; l < NF; ++l) pthr[l] = (uint32_t)__builtin_amdgcn_readfirstlane((int)pthr_all[(int64_t)l * n + list]);
-          labor_scan_fast_blend<NF>(g_indices, beg + j0, len, j0, thr, pthr, keys, &queues[uniform_wave_in_block()], kept);
-        } else {
-          labor_scan_fast<BLEND, NF>(g_indices, beg + j0, len, j0, thr, keys, kept);
+          for (int l = 0; l < NF; ++l) {
+            pthr[l] = (uint32_t)__builtin_amdgcn_readfirstlane((int)pthr_all[(int64_t)l * n + list]);
+            lb.thr[l] = thr[l];
+            lb.lim2[l] = lim2_all[(int64_t)l * n + list];
+          }
+          labor_scan_blend<NF>(g_indices, beg + j0, len, j0, 0u, pthr, lb, keys, bst, stage_cap, out, ctl);
+          blend_flush_first<NF>(bst, lb, keys, stage_cap, out, ctl);
+          continue;
         }
+        KeptRegs kept[NF];
+        labor_scan_fast<BLEND, NF>(g_indices, beg + j0, len, j0, thr, keys, kept);
 #pragma unroll
         for (int l = 0; l < NF; ++l) {
           const uint32_t c = kept[l].count;
@@ -459,6 +589,9 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
           }
         }
       }
+      if constexpr (kQueued) {
+        if (bst.n2 != 0) blend_exact<NF>(bst, bst.n2, keys, stage_cap, out, ctl);  // what still waits for the exact stage
+      }
       return;
     }
   }
@@ -469,26 +602,31 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
   const bool has = (int)lane < lists_per_wave && mine < n;
   Segment g{0, 0, 0};
   uint32_t my_thr[NF], my_pthr[NF];
+  float my_lim2[NF];
 #pragma unroll
-  for (int l = 0; l < NF; ++l) { my_thr[l] = kAllThr; my_pthr[l] = kAllThr; }
+  for (int l = 0; l < NF; ++l) { my_thr[l] = kAllThr; my_pthr[l] = kAllThr; my_lim2[l] = 0.0f; }
   if (has) {
     g = seg[mine];
 #pragma unroll
     for (int l = 0; l < NF; ++l) {
       my_thr[l] = thr_all[(int64_t)l * n + mine];
-      if (BLEND) my_pthr[l] = pthr_all[(int64_t)l * n + mine];
+      if constexpr (kQueued) { my_pthr[l] = pthr_all[(int64_t)l * n + mine]; my_lim2[l] = lim2_all[(int64_t)l * n + mine]; }
     }
   }
   const uint32_t beg_lo = (uint32_t)g.beg, beg_hi = (uint32_t)((uint64_t)g.beg >> 32);
   uint32_t my_count[NF];
 #pragma unroll
   for (int l = 0; l < NF; ++l) my_count[l] = 0;
+  ListBlend<NF> lbw;  // lane i: thresholds of list first + i
+  lbw.first = (uint32_t)first;
+#pragma unroll
+  for (int l = 0; l < NF; ++l) { lbw.thr[l] = my_thr[l]; lbw.lim2[l] = my_lim2[l]; }
   const int n_lists = (int)(n - first < lists_per_wave ? n - first : lists_per_wave);
   for (int i = 0; i < n_lists; ++i) {
     const int64_t beg = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)beg_hi, i) << 32) |
                                   (uint32_t)__builtin_amdgcn_readlane((int)beg_lo, i));
     const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)g.d, i);
-    if (__builtin_amdgcn_readlane((int)g.split, i) != 0) continue;  // cut into pieces, scanned by other waves
+    if ((__builtin_amdgcn_readlane((int)g.split, i) & 1) != 0) continue;  // cut into pieces, scanned by other waves
     uint32_t thr[NF];
     bool any_all = false;
 #pragma unroll
@@ -496,16 +634,16 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
       thr[l] = (uint32_t)__builtin_amdgcn_readlane((int)my_thr[l], i);
       any_all |= thr[l] == kAllThr;
     }
+    if constexpr (kQueued) {  // every list, whatever its length: kept edges reach the rows through the queues
+      uint32_t pthr[NF];
+#pragma unroll
+      for (int l = 0; l < NF; ++l) pthr[l] = (uint32_t)__builtin_amdgcn_readlane((int)my_pthr[l], i);
+      if (d != 0) labor_scan_blend<NF>(g_indices, beg, d, 0u, (uint32_t)i, pthr, lbw, keys, bst, stage_cap, out, ctl);
+      continue;
+    }
     if (VEC == 4 && !any_all && d > (uint32_t)kWave) {
       KeptRegs kept[NF];
-      if constexpr (BLEND) {
-        uint32_t pthr[NF];
-#pragma unroll
-        for (int l = 0; l < NF; ++l) pthr[l] = (uint32_t)__builtin_amdgcn_readlane((int)my_pthr[l], i);
-        labor_scan_fast_blend<NF>(g_indices, beg, d, 0u, thr, pthr, keys, &queues[uniform_wave_in_block()], kept);
-      } else {
-        labor_scan_fast<BLEND, NF>(g_indices, beg, d, 0u, thr, keys, kept);
-      }
+      labor_scan_fast<BLEND, NF>(g_indices, beg, d, 0u, thr, keys, kept);
 #pragma unroll
       for (int l = 0; l < NF; ++l) {
         kept[l].flush(lane, out.stage[l] + (size_t)(first + i) * stage_cap, stage_cap);
@@ -522,6 +660,11 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
         if ((int)lane == i) my_count[l] = c;
       }
     }
+  }
+  if constexpr (kQueued) {
+    blend_flush_first<NF>(bst, lbw, keys, stage_cap, out, ctl);
+    if (bst.n2 != 0) blend_exact<NF>(bst, bst.n2, keys, stage_cap, out, ctl);  // what still waits for the exact stage
+    return;                                                                   // (the counters were kept by atomics)
   }
   if (has && g.split == 0) {
 #pragma unroll
@@ -604,14 +747,14 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int32_t* _
 }
 
 template <bool BLEND, int VEC>
-static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, const uint32_t* pthr, int64_t n,
+static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, const uint32_t* pthr, const float* lim2, int64_t n,
                         int lpw, const FusedKeys& keys, uint32_t cap, const ScanOut& out, Ctl* ctl, int piece_blocks, const Piece* pieces,
                         const uint32_t* piece_count, uint32_t piece_cap, uint32_t piece_len) {
   switch (nf) {
-    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
-    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
-    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
-    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
+    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
+    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
+    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
+    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
   }
 }
 
@@ -647,6 +790,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
   ps.seg = alloc.get<Segment>(n_new, COOP_TAG_SCRATCH);
   ps.thr = alloc.get<uint32_t>(n_new * ps.nf, COOP_TAG_SCRATCH);
   uint32_t* pthr = cx.blend ? alloc.get<uint32_t>(n_new * ps.nf, COOP_TAG_SCRATCH) : nullptr;
+  float* lim2 = cx.blend ? alloc.get<float>(n_new * ps.nf, COOP_TAG_SCRATCH) : nullptr;
   for (int f = 0; f < ps.nf; ++f) {
     ps.stage[f] = alloc.get<StageEntry>(n_new * (int64_t)cap, COOP_TAG_SCRATCH);
     ps.cnt[f] = alloc.get<int32_t>(n_new, COOP_TAG_SCRATCH);
@@ -680,11 +824,12 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     ScanOut out{};
     for (int f = 0; f < ps.nf; ++f) { out.stage[f] = ps.stage[f]; out.cnt[f] = ps.cnt[f]; }
     COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
-                dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, (1.0 - 1e-6) / (cx.cw + cx.sw), cx.d_ctl,
+                dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, (1.0 - 1e-6) / (cx.cw + cx.sw), cx.cw + cx.sw,
+                cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
                 piece_len, pieces, piece_cap, cx.d_piece_count + l, out);
     // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
     int lpw = g_lists_per_wave;
-    if (lpw == 0) lpw = n_new >= 65536 ? 4 : 1;
+    if (lpw == 0) lpw = n_new >= 65536 ? (cx.blend && cx.vec4 ? 8 : 4) : 1;  // blended: fuller waves at the exact stage
     const int64_t n_waves = (n_new + lpw - 1) / lpw;
     // the piece waves come first in the grid: one round of resident blocks, fewer if there cannot be that many pieces
     constexpr int64_t kPieceBlocks = 2048;
@@ -692,11 +837,11 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     const dim3 grid(blocks_for(n_waves, kWavesPerBlock) + (unsigned)piece_blocks);
     const uint32_t* pcount = cx.d_piece_count + l;
     if (cx.blend) {
-      if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len);
-      else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u);
+      if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len);
+      else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u);
     } else {
-      if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len);
-      else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u);
+      if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len);
+      else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u);
     }
   }
 

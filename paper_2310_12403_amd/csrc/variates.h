@@ -174,6 +174,48 @@ __device__ __forceinline__ double kit_phi_inv_u32(uint32_t U) {
   return upper ? -x : x;
 }
 
+// The same rational form in fp32 with the hardware's logarithm, square root and reciprocal: within 4e-4 of
+// kit_phi_inv_u32 (the central branch's large alternating coefficients cancel in fp32).  Only ever used to discard
+// candidates that are safely outside a threshold; never decides anything by itself.
+__device__ __forceinline__ float approx_phi_inv_f32(uint32_t U) {
+  const bool upper = U >= 0x80000000u;
+  const uint32_t Ul = upper ? (0xFFFFFFFFu - U) : U;
+  const float p = ((float)Ul + 0.5f) * 2.3283064365386963e-10f;
+  float x;
+  if (p < 0.02425f) {
+    const float q = __builtin_amdgcn_sqrtf(-2.0f * __logf(p));
+    float num = -7.784894002430293e-03f;
+    num = __builtin_fmaf(num, q, -3.223964580411365e-01f);
+    num = __builtin_fmaf(num, q, -2.400758277161838e+00f);
+    num = __builtin_fmaf(num, q, -2.549732539343734e+00f);
+    num = __builtin_fmaf(num, q, 4.374664141464968e+00f);
+    num = __builtin_fmaf(num, q, 2.938163982698783e+00f);
+    float den = 7.784695709041462e-03f;
+    den = __builtin_fmaf(den, q, 3.224671290700398e-01f);
+    den = __builtin_fmaf(den, q, 2.445134137142996e+00f);
+    den = __builtin_fmaf(den, q, 3.754408661907416e+00f);
+    den = __builtin_fmaf(den, q, 1.0f);
+    x = num * __builtin_amdgcn_rcpf(den);
+  } else {
+    const float q = p - 0.5f;
+    const float r = q * q;
+    float num = -3.969683028665376e+01f;
+    num = __builtin_fmaf(num, r, 2.209460984245205e+02f);
+    num = __builtin_fmaf(num, r, -2.759285104469687e+02f);
+    num = __builtin_fmaf(num, r, 1.383577518672690e+02f);
+    num = __builtin_fmaf(num, r, -3.066479806614716e+01f);
+    num = __builtin_fmaf(num, r, 2.506628277459239e+00f);
+    float den = -5.447609879822406e+01f;
+    den = __builtin_fmaf(den, r, 1.615858368580409e+02f);
+    den = __builtin_fmaf(den, r, -1.556989798598866e+02f);
+    den = __builtin_fmaf(den, r, 6.680131188771972e+01f);
+    den = __builtin_fmaf(den, r, -1.328068155288572e+01f);
+    den = __builtin_fmaf(den, r, 1.0f);
+    x = (q * num) * __builtin_amdgcn_rcpf(den);
+  }
+  return upper ? -x : x;
+}
+
 // 1 / (2n + 1), n = 0..28, each the correctly rounded quotient (folded by the compiler)
 __constant__ const double kInvOdd[29] = {
     1.0,        1.0 / 3.0,  1.0 / 5.0,  1.0 / 7.0,  1.0 / 9.0,  1.0 / 11.0, 1.0 / 13.0, 1.0 / 15.0,

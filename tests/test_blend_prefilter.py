@@ -67,3 +67,112 @@ def test_pre_threshold_is_selective():
         P = pre_threshold(L, thr, cw, sw)
         frac = 1 - (1 - P / 2**32) ** 2
         assert thr < P and frac < 0.1
+
+
+# --------------------------------------------------------------------------- #
+# Second filter: the blend itself in fp32 with a safety margin
+# --------------------------------------------------------------------------- #
+EPS2 = 4e-3          # allowance for one fp32 Phi^-1 against the fp64 kit's (the measured gap is below 4e-4: the
+                     # central branch's large alternating coefficients cancel in fp32)
+
+
+def approx_phi_inv_f32(U):
+    """Restatement of approx_phi_inv_f32() in csrc/variates.h: Acklam's rational form of Phi^-1((U + 1/2) / 2^32)
+    evaluated in fp32 (the GPU uses its hardware log2 / sqrt / reciprocal, each good to about one ulp; numpy's are
+    correctly rounded: the difference is far inside EPS2)."""
+    f = np.float32
+    upper = U >= 0x80000000
+    Ul = (M32 - U) if upper else U
+    p = (f(Ul) + f(0.5)) * f(1.0 / 4294967296.0)
+    if p < f(0.02425):
+        q = np.sqrt(f(-2.0) * np.log(p, dtype=np.float32), dtype=np.float32)
+        num = f(-7.784894002430293e-03)
+        for c in (-3.223964580411365e-01, -2.400758277161838e+00, -2.549732539343734e+00, 4.374664141464968e+00, 2.938163982698783e+00):
+            num = f(num * q + f(c))
+        den = f(7.784695709041462e-03)
+        for c in (3.224671290700398e-01, 2.445134137142996e+00, 3.754408661907416e+00, 1.0):
+            den = f(den * q + f(c))
+        x = f(num / den)
+    else:
+        q = f(p - f(0.5))
+        r = f(q * q)
+        num = f(-3.969683028665376e+01)
+        for c in (2.209460984245205e+02, -2.759285104469687e+02, 1.383577518672690e+02, -3.066479806614716e+01, 2.506628277459239e+00):
+            num = f(num * r + f(c))
+        den = f(-5.447609879822406e+01)
+        for c in (1.615858368580409e+02, -1.556989798598866e+02, 6.680131188771972e+01, -1.328068155288572e+01, 1.0):
+            den = f(den * r + f(c))
+        x = f(f(q * num) / den)
+    return f(-x) if upper else x
+
+
+def second_threshold(L, thr, cw, sw):
+    """Restatement of blend_second_threshold() in csrc/labor.hip: keep needs n = cw n1 + sw n2 below this."""
+    if thr >= 0x7FFFFFF0:
+        return np.float32(np.inf)
+    tau = L.coopref_phi_inv_u32(thr + 8)
+    lim = tau * (1.0 - 1e-6) + (cw + sw) * EPS2 + 1e-5
+    t = np.float32(lim)
+    return np.nextafter(t, np.float32(np.inf)) if float(t) < lim else t
+
+
+def test_fp32_phi_inv_is_close_to_the_kit():
+    L = R.lib()
+    rng = np.random.default_rng(1)
+    worst = 0.0
+    Us = [0, 1, 2, 3, 100, M32, M32 - 1, 0x7FFFFFFF, 0x80000000, int(0.02425 * 2**32), int(0.02425 * 2**32) + 1]
+    Us += [int(x) for x in rng.integers(0, 1 << 32, 20000)]
+    Us += [int(10 ** rng.uniform(0, 9.6)) for _ in range(20000)]
+    for U in Us:
+        worst = max(worst, abs(float(approx_phi_inv_f32(U)) - L.coopref_phi_inv_u32(U)))
+    assert worst < 4e-4, worst
+
+
+def test_second_filter_never_rejects_a_kept_edge():
+    from scipy.special import ndtr, ndtri
+    L = R.lib()
+    rng = np.random.default_rng(2)
+    checked = kept = rejected = 0
+    for trial in range(300):
+        k = int(rng.integers(1, 60))
+        d = int(k + 1 + 10 ** rng.uniform(0, 5))
+        thr = (k << 32) // d
+        kappa = int(rng.integers(2, 300))
+        i = int(rng.integers(1, kappa))
+        c = i / kappa
+        cw, sw = math.cos(c * 1.5707963267948966), math.sin(c * 1.5707963267948966)
+        T2 = second_threshold(L, thr, cw, sw)
+        tau = float(ndtri((thr + 0.5) / 2**32))
+        cands = []
+        for _ in range(40):
+            # pairs whose blend lands near the keep boundary: pick n1, solve n2, perturb a little
+            n1 = float(rng.normal())
+            n2 = (tau - cw * n1) / sw + float(rng.normal()) * 10 ** rng.uniform(-6, -1)
+            U1 = int(min(M32, max(0, ndtr(n1) * 2**32)))
+            U2 = int(min(M32, max(0, ndtr(n2) * 2**32)))
+            cands.append((U1, U2))
+            cands.append((int(rng.integers(0, 1 << 32)), int(rng.integers(0, 1 << 32))))
+        for U1, U2 in cands:
+            n = np.float64(cw) * np.float64(L.coopref_phi_inv_u32(U1)) + np.float64(sw) * np.float64(L.coopref_phi_inv_u32(U2))
+            n_hat = np.float32(np.float32(cw) * approx_phi_inv_f32(U1)) + np.float32(np.float32(sw) * approx_phi_inv_f32(U2))
+            passes = bool(n_hat <= T2)
+            for nn in (float(n), float(np.nextafter(n, -np.inf)), float(np.nextafter(n, np.inf))):
+                checked += 1
+                if L.coopref_phi_to_u32(nn) <= thr:
+                    kept += 1
+                    assert passes, (thr, c, U1, U2, float(n), float(n_hat), float(T2))
+                elif not passes:
+                    rejected += 1
+    assert kept > 3000 and rejected > 3000 and checked > 60000
+
+
+def test_second_filter_is_selective():
+    """At k/d = 10/1400 and c = 1/2 the second filter passes little more than the edges that are kept."""
+    from scipy.special import ndtri
+    L = R.lib()
+    thr = (10 << 32) // 1400
+    cw = sw = math.cos(math.pi / 4)
+    T2 = float(second_threshold(L, thr, cw, sw))
+    tau = float(ndtri(thr / 2**32))
+    from scipy.special import ndtr
+    assert ndtr(T2) / ndtr(tau) < 1.03       # n ~ N(0, 1): pass probability against keep probability
