@@ -50,7 +50,8 @@ def main():
     ap.add_argument("--iters", type=int, default=None, help="iterations per kappa for the cache modes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run three plain 1 GiB device copies (a known-size reference for rocprofv3 --pmc byte counters)")
+                    help="also run three plain 1 GiB copies with the library's copy kernel (coop::k_copy_i32): the known-size "
+                         "reference that rocprofv3 --pmc byte counters are scaled by")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -111,7 +112,7 @@ def main():
         a = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
         b = torch.empty_like(a)
         for _ in range(3):
-            b.copy_(a)          # reads 1 GiB, writes 1 GiB
+            P.coop_copy_ids(a, out=b)          # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del a, b
 

@@ -253,6 +253,10 @@ const char* coop_strerror(int code);
                                       (default 4096); 0: lists are never cut */
 int coop_tune(int knob, int64_t value);
 
+/* out[i] = in[i] for a device id list (a plain streaming copy on `stream`: 4n bytes read, 4n written).  Besides its
+ * use for snapshotting seed lists it is the known-size reference that the byte counters of a profiler are scaled by. */
+int coop_copy_ids(const int32_t* in, int32_t* out, int64_t n, void* stream);
+
 /* Library ABI version (bumped when a signature in this file changes). */
 int coop_version(void);
 

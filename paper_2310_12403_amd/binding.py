@@ -57,6 +57,8 @@ def lib():
     L.coop_sample_rw.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_int32, C.c_int32, C.c_double,
                                  C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_CBlock)]
     L.coop_sample_rw.restype = C.c_int
+    L.coop_copy_ids.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    L.coop_copy_ids.restype = C.c_int
     L.coop_gather.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     L.coop_gather.restype = C.c_int
     L.coop_gather_mean.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
@@ -253,6 +255,15 @@ def coop_sample_rw(graph, seeds, fanouts, walk_length, n_walks, restart_p, it=0,
         raise al.error
     _check(rc)
     return [Block(blocks[l], al) for l in range(L)]
+
+
+def coop_copy_ids(ids, out=None, stream=None):
+    """A plain copy of a device int32 list on the stream."""
+    if out is None:
+        out = torch.empty_like(ids)
+    assert out.numel() == ids.numel()
+    _check(lib().coop_copy_ids(_dev_ptr(ids, torch.int32), _dev_ptr(out, torch.int32), ids.numel(), _stream_ptr(stream)))
+    return out
 
 
 _DTYPES = {torch.float32: COOP_F32, torch.float16: COOP_F16}

@@ -66,6 +66,7 @@ struct ChunkedI32 {
 void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s);
 // bit flags packed 64 per word -> uint32 exclusive ranks (out has n entries) and the total in *total_out (device)
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
+void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
 
 void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
 

@@ -139,6 +139,10 @@ struct LoadBit {
   const uint64_t* bits;
   __device__ __forceinline__ int64_t operator()(int64_t i) const { return (bits[i >> 6] >> (i & 63)) & 1ull; }
 };
+struct LoadPopc {  // element i = number of set bits of word i
+  const uint64_t* bits;
+  __device__ __forceinline__ int64_t operator()(int64_t i) const { return __popcll(bits[i]); }
+};
 
 template <typename Load, typename Out>
 __global__ __launch_bounds__(kBlock) void k_scan_local(Load load, int64_t n, Out* __restrict__ out, int64_t* __restrict__ tile_sum) {
@@ -227,6 +231,10 @@ void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* 
 
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
   scan_impl<LoadBit, uint32_t>(LoadBit{bits}, n, out, (uint32_t*)nullptr, total_out, tmp, s);
+}
+
+void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
+  scan_impl<LoadPopc, uint32_t>(LoadPopc{bits}, n_words, out, (uint32_t*)nullptr, total_out, tmp, s);
 }
 
 // ---- CSR validation -------------------------------------------------------------------------------------------

@@ -174,3 +174,11 @@ extern "C" int coop_sample_rw(const coop_graph* g, const int32_t* seeds, int64_t
   // the paper defines no dependent variates for random walks: every iteration draws afresh (group = iteration)
   return sample_layers(g, seeds, n_seeds, fanouts, L, COOP_RW, &rw, iter, 1u, seed, alloc_fn, alloc_ctx, stream, blocks_out);
 }
+
+extern "C" int coop_copy_ids(const int32_t* in, int32_t* out, int64_t n, void* stream) {
+  if ((!in || !out) && n > 0) return COOP_E_NULL;
+  if (n < 0 || n >= ((int64_t)1 << 39)) return COOP_E_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  if (n > 0) COOP_LAUNCH(K_COPY_IDS, k_copy_i32, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, s, in, out, n);
+  return COOP_OK;
+}

@@ -3,9 +3,10 @@
 // The list [S^l ; col_global] is inserted into a table of 8-byte slots (key << 32 | position in that list).  A slot is
 // claimed with atomicCAS; every further occurrence of the key lowers the slot's position with atomicMin, so after
 // the insert kernel each slot holds the FIRST position of its key, whichever thread won the race.  A vertex is
-// "new" exactly at the edge whose position equals that first position (and is not a seed position).  A device-wide
-// scan over the new-flags gives each new vertex its rank, hence its place n_dst + rank in S^{l+1}: the order is
-// "S^l, then first appearance in col_global", independent of scheduling.
+// "new" exactly at the edge whose position equals that first position (and is not a seed position).  The new-flags
+// are kept as a bit per edge; a device-wide scan over the words' bit counts plus a bit count inside the word gives each
+// new vertex its rank, hence its place n_dst + rank in S^{l+1}: the order is "S^l, then first appearance in
+// col_global", independent of scheduling.
 #include "coop_internal.h"
 #include "device_utils.h"
 
@@ -71,23 +72,23 @@ __global__ __launch_bounds__(kBlock) void k_uniq_flag(const int32_t* __restrict_
   if (lane_id() == 0 && (e & ~(int64_t)63) < m) bits[e >> 6] = b;
 }
 
-__global__ __launch_bounds__(kBlock) void k_uniq_relabel(const int32_t* __restrict__ col, int64_t m, int64_t n_dst,
-                                                         const uint32_t* __restrict__ first, const uint32_t* __restrict__ rank,
+// col_local and the tail of src_ids; the threads of the first n_dst positions also copy S^l to the front of src_ids
+__global__ __launch_bounds__(kBlock) void k_uniq_relabel(const int32_t* __restrict__ dst, const int32_t* __restrict__ col, int64_t m,
+                                                         int64_t n_dst, const uint32_t* __restrict__ first,
+                                                         const uint64_t* __restrict__ bits, const uint32_t* __restrict__ word_rank,
                                                          int32_t* __restrict__ src, int32_t* __restrict__ col_local) {
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (e < n_dst) src[e] = dst[e];
   if (e >= m) return;
   const int64_t f = first[e];
   int64_t local = f;
   if (f >= n_dst) {
-    local = n_dst + rank[f - n_dst];
-    if (f == n_dst + e) src[local] = col[e];
+    const int64_t at = f - n_dst;  // the edge at which this vertex first appears
+    const uint64_t below = bits[at >> 6] & ((1ull << (at & 63)) - 1ull);
+    local = n_dst + word_rank[at >> 6] + __popcll(below);
+    if (at == e) src[local] = col[e];
   }
   col_local[e] = (int32_t)local;
-}
-
-__global__ __launch_bounds__(kBlock) void k_copy_ids(const int32_t* __restrict__ in, int32_t* __restrict__ out, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < n) out[i] = in[i];
 }
 
 static inline unsigned nblocks(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
@@ -100,9 +101,10 @@ int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global,
 
   unsigned long long* table = alloc.get<unsigned long long>(cap, COOP_TAG_SCRATCH);
   uint32_t* first = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
-  uint32_t* rank = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
-  uint64_t* bits = alloc.get<uint64_t>((m + 63) / 64, COOP_TAG_SCRATCH);
-  void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(m), COOP_TAG_SCRATCH);
+  const int64_t n_words = (m + 63) / 64;
+  uint32_t* word_rank = alloc.get<uint32_t>(n_words, COOP_TAG_SCRATCH);
+  uint64_t* bits = alloc.get<uint64_t>(n_words, COOP_TAG_SCRATCH);
+  void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_words), COOP_TAG_SCRATCH);
   if (alloc.failed) return COOP_E_NOMEM;
 
   int64_t n_new = 0;
@@ -114,7 +116,7 @@ int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global,
   if (m > 0) {
     COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, n_dst, table, (uint64_t)cap, first,
                 bits);
-    scan_bits_to_u32(bits, m, rank, &d_ctl->total_new, scan_tmp, s);
+    scan_popc_to_u32(bits, n_words, word_rank, &d_ctl->total_new, scan_tmp, s);
   }
   // sizes (and the duplicate / range flags) back to the host
   const int rc = read_ctl(d_ctl, h_ctl, s);
@@ -124,10 +126,10 @@ int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global,
   const int64_t n_src = n_dst + n_new;
   int32_t* src = alloc.get<int32_t>(n_src, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
-  if (n_dst > 0) COOP_LAUNCH(K_COPY_IDS, k_copy_ids, dim3(nblocks(n_dst)), dim3(kBlock), 0, s, dst, src, n_dst);
-  if (m > 0)
-    COOP_LAUNCH(K_UNIQ_RELABEL, k_uniq_relabel, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, n_dst, first, rank, src,
-                col_local);
+  const int64_t n_threads = m > n_dst ? m : n_dst;
+  if (n_threads > 0)
+    COOP_LAUNCH(K_UNIQ_RELABEL, k_uniq_relabel, dim3(nblocks(n_threads)), dim3(kBlock), 0, s, dst, col_global, m, n_dst, first, bits,
+                word_rank, src, col_local);
   *src_out = src;
   *n_src_out = n_src;
   return COOP_OK;
