@@ -466,3 +466,17 @@ def test_random_walk_sampler_errors(P, tiny):
     with pytest.raises(P.CoopError) as e:
         P.coop_sample_rw(tiny.graph, torch.tensor([tiny.n], dtype=torch.int32).cuda(), (5,), 3, 10, 0.5)
     assert e.value.code == -2
+
+
+def test_limits_of_the_interface(P, tiny):
+    """Deepest model the interface takes (L = 255), fanouts far above every degree, the largest walk budget."""
+    seeds = synth.seed_batches(tiny.n, 8, seed=41)(0).numpy()
+    compare(P, tiny, seeds[:2], (1,) * 255, R.LABOR0, it=1, seed=4)
+    compare(P, tiny, seeds[:2], (1,) * 255, R.NS, it=1, seed=4)
+    compare(P, tiny, seeds, (1 << 30, 1 << 30), R.LABOR0, it=2, seed=4)          # keeps every neighbour: two-hop ball
+    compare(P, tiny, seeds, ((1 << 31) - 1,), R.NS, it=2, seed=4)
+    compare_rw(P, tiny, seeds, ((1 << 31) - 1,), 1024, 1, 0.0, it=3, seed=4)
+    compare_rw(P, tiny, seeds, (7,), 1, 1024, 1.0, it=3, seed=4)
+    with pytest.raises(P.CoopError) as e:
+        P.coop_sample(tiny.graph, torch.from_numpy(seeds).cuda(), (1,) * 256, P.COOP_LABOR0)
+    assert e.value.code == -4
