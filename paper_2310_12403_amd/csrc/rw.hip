@@ -4,8 +4,8 @@
 //
 // One wave per destination.  Lanes walk (two walks per lane at a time, so that their dependent loads overlap) and
 // tally every visit in a small open-addressing table in LDS (vertex, count).  Each lane then holds its share of the
-// table in registers as keys (count << 32 | ~vertex) and the k largest keys are peeled off by wave-wide maxima:
-// count descending, vertex ascending, the order in which the sources are emitted.  The draws are keyed hashes of
+// table in registers; the k best entries by (count descending, vertex ascending), the order in which the sources
+// are emitted, are found by two bisections over wave-wide ballot tallies and ranked among themselves.  The draws are keyed hashes of
 // (destination, draw counter), so the result does not depend on which lane walks which walk.
 #include "device_utils.h"
 #include "sample_internal.h"
@@ -25,15 +25,6 @@ struct RwParams {
 
 __device__ __forceinline__ uint32_t rw_draw(const uint32_t (&K)[4], uint32_t sigma, uint32_t c) {
   return mix32(mix32(c ^ K[0]) ^ K[1] ^ sigma) ^ K[3];  // sigma = mix32(s ^ K[2])
-}
-
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
-#pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) {
-    const unsigned long long o = __shfl_xor(v, off, kWave);
-    v = o > v ? o : v;
-  }
-  return v;
 }
 
 // E = table slots per lane (table of 64 E slots, at most 3/4 full)
@@ -113,27 +104,73 @@ __global__ __launch_bounds__(kBlock) void k_rw_walk(const int64_t* __restrict__ 
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-  unsigned long long key[E];
+  // Each lane takes its E slots of the table into registers; the k best by (count descending, vertex ascending) are
+  // found without sorting: the count of the k-th best by bisection over wave-wide tallies (ballots), then, among
+  // the vertices visited exactly that often, the id below which just enough of them lie, again by bisection.
+  uint32_t cnt_e[E], id_e[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    const uint32_t v = keys[e * kWave + lane];
-    const uint32_t c = counts[e * kWave + lane];
-    key[e] = v != kRwEmpty ? ((unsigned long long)c << 32) | (unsigned long long)(0xFFFFFFFFu - v) : 0ull;
+    id_e[e] = keys[e * kWave + lane];
+    cnt_e[e] = id_e[e] != kRwEmpty ? counts[e * kWave + lane] : 0u;
   }
+  __builtin_amdgcn_wave_barrier();  // the table's memory is reused below
+  auto n_with_count_at_least = [&](uint32_t c) {
+    uint32_t n = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) n += (uint32_t)__popcll(ballot64(cnt_e[e] >= c));
+    return n;
+  };
+  const uint32_t k = rp.k_eff;
+  uint32_t cut = 0;  // 0: fewer than k distinct vertices, all are kept
+  if (n_with_count_at_least(1u) > k) {
+    uint32_t lo = 1, hi = (uint32_t)(o * a);  // the largest c with at least k vertices visited c times or more
+    while (lo < hi) {
+      const uint32_t mid = lo + (hi - lo + 1) / 2;
+      if (n_with_count_at_least(mid) >= k) lo = mid; else hi = mid - 1;
+    }
+    cut = lo;
+  }
+  bool keep[E];
+  if (cut == 0) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) keep[e] = cnt_e[e] != 0;
+  } else {
+    const uint32_t need = k - n_with_count_at_least(cut + 1);  // of the vertices visited exactly that often, the `need` smallest ids
+    uint32_t tie[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) tie[e] = cnt_e[e] == cut ? id_e[e] : kRwEmpty;
+    uint32_t lo = 0, hi = 0x7FFFFFFFu;  // the smallest X with at least `need` tie ids <= X (ids are distinct: exactly `need`)
+    while (lo < hi) {
+      const uint32_t mid = lo + (hi - lo) / 2;
+      uint32_t n = 0;
+#pragma unroll
+      for (int e = 0; e < E; ++e) n += (uint32_t)__popcll(ballot64(tie[e] <= mid));
+      if (n >= need) hi = mid; else lo = mid + 1;
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) keep[e] = cnt_e[e] > cut || tie[e] <= lo;
+  }
+  // the kept entries, compacted into LDS as keys (count << 32 | ~vertex); an entry's place in the row is the number of
+  // larger keys
+  unsigned long long* kept_keys = reinterpret_cast<unsigned long long*>(keys);  // 64 E words of 8 bytes: the table's memory
+  uint32_t n_kept = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const uint64_t mask = ballot64(keep[e]);
+    if (keep[e]) kept_keys[n_kept + lanes_below(mask)] = ((unsigned long long)cnt_e[e] << 32) | (unsigned long long)(0xFFFFFFFFu - id_e[e]);
+    n_kept += (uint32_t)__popcll(mask);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   StageEntry* row = rows + (size_t)w * rp.k_eff;
-  uint32_t kept = 0;
-  for (; kept < rp.k_eff; ++kept) {
-    unsigned long long best = 0;
-#pragma unroll
-    for (int e = 0; e < E; ++e) best = key[e] > best ? key[e] : best;
-    const unsigned long long top = wave_max_u64(best);
-    if (top == 0) break;  // fewer than k distinct vertices were visited
-#pragma unroll
-    for (int e = 0; e < E; ++e)
-      if (key[e] == top) key[e] = 0;  // vertices are distinct: exactly one lane holds it
-    if (lane == 0) row[kept] = StageEntry{(int32_t)(0xFFFFFFFFu - (uint32_t)top), (uint32_t)(top >> 32)};
+  for (uint32_t i = lane; i < n_kept; i += kWave) {
+    const unsigned long long mine = kept_keys[i];
+    uint32_t place = 0;
+    for (uint32_t q = 0; q < n_kept; ++q) place += kept_keys[q] > mine;
+    row[place] = StageEntry{(int32_t)(0xFFFFFFFFu - (uint32_t)mine), (uint32_t)(mine >> 32)};
   }
-  if (lane == 0) cnt[w] = (int32_t)kept;
+  if (lane == 0) cnt[w] = (int32_t)n_kept;
 }
 
 // staged rows -> the block's edge arrays; eid carries the visit count (these are edges of sum_i A^i, not of the graph)
