@@ -8,10 +8,16 @@ namespace coop {
 
 // One destination's neighbour list as the fill pass sees it (written by the count pass, so that the fill pass
 // reaches the list with one dependent load instead of three).
-struct NsRecord { int64_t beg; uint32_t d; int32_t s; };
+struct NsRecord {
+  int64_t beg;
+  uint32_t d;
+  int32_t s;
+  uint32_t bound;  // first candidate bound: about `target` of the d variates are expected below it
+  uint32_t pad;
+};
 
 __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
-                                                     const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k,
+                                                     const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k, uint32_t target,
                                                      int32_t* __restrict__ cnt, NsRecord* __restrict__ rec, Ctl* ctl) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_dst) return;
@@ -19,13 +25,17 @@ __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__
   if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
     atomicOr(&ctl->err_range, 1);
     cnt[i] = 0;
-    rec[i] = NsRecord{0, 0u, 0};
+    rec[i] = NsRecord{0, 0u, 0, 0u, 0u};
     return;
   }
   const int64_t beg = g_indptr[s];
   const int64_t d = g_indptr[s + 1] - beg;
   cnt[i] = (int32_t)(d < (int64_t)k ? d : (int64_t)k);
-  rec[i] = NsRecord{beg, (uint32_t)d, s};
+  // bound such that E[#candidates] = target: R <= bound with probability (bound + 1) / 2^32 (one 64-bit division per
+  // list, here where every lane has a list of its own)
+  uint64_t bound = d > 0 ? ((uint64_t)target << 32) / (uint64_t)d : 0xFFFFFFFFull;
+  if (bound > 0xFFFFFFFFull) bound = 0xFFFFFFFFull;  // d <= target: every neighbour is a candidate
+  rec[i] = NsRecord{beg, (uint32_t)d, s, (uint32_t)bound, 0u};
 }
 
 constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list can be subsampled
@@ -127,7 +137,7 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
 template <bool BLEND, bool VEC4>
 __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ g_indices,
                                                     const NsRecord* __restrict__ rec, int64_t n_dst, uint32_t k,
-                                                    uint32_t cap, uint32_t target, int waves_per_block, VariateParams vp,
+                                                    uint32_t cap, int waves_per_block, VariateParams vp,
                                                     const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
                                                     int64_t* __restrict__ eid, Ctl* ctl) {
   extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
@@ -160,10 +170,8 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
   const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)s);
   const uint32_t sigma_b = BLEND ? ns_sigma(vp.K.Kb, (uint32_t)s) : 0u;
 
-  // bound such that E[#candidates] = target: R <= bound with probability (bound + 1) / 2^32
   uint64_t lo = 0, hi = 0xFFFFFFFFull;  // bisection bracket on the bound, used only after a failed pass
-  uint64_t bound = ((uint64_t)target << 32) / (uint64_t)d;
-  if (bound > 0xFFFFFFFFull) bound = 0xFFFFFFFFull;  // d <= target: every neighbour is a candidate
+  uint64_t bound = g.bound;
   uint32_t n_c = 0;
   for (int attempt = 0; attempt < 40; ++attempt) {
     n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap);
@@ -250,9 +258,20 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   NsRecord* rec = alloc.get<NsRecord>(n_dst, COOP_TAG_SCRATCH);
   void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
   if (alloc.failed) return COOP_E_NOMEM;
+  // candidate buffer: cap >= 4k (power of two, at least 256).  A fanout above kNsMaxSelect is served only while no
+  // degree exceeds it (the fill kernel reports the first that does).
+  const uint32_t k_sel = k < kNsMaxSelect ? k : kNsMaxSelect;
+  uint32_t cap = 256;
+  while (cap < 4 * k_sel) cap <<= 1;
+  // expected candidates: k + 4 sqrt(k) + 4 (at most 2k + 16).  A list that turns up fewer than k candidates (about one
+  // in 10^4) is simply collected again with a larger bound; every candidate beyond the k-th costs ranking work.
+  uint32_t root = 1;
+  while (root * root < k_sel) ++root;
+  uint32_t target = k_sel + 4 * root + 4;
+  if (target > 2 * k_sel + 16) target = 2 * k_sel + 16;
   if (n_dst > 0)
     COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices, dst, n_dst,
-                k, cnt, rec, cx.d_ctl);
+                k, target, cnt, rec, cx.d_ctl);
   scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
   int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
   if (rc != COOP_OK) return rc;
@@ -263,22 +282,11 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
   if (m > 0) {
-    // candidate buffer: cap >= 4k (power of two, at least 256); expected candidates: 2k + 16.  A fanout above
-    // kNsMaxSelect is served only while no degree exceeds it (the kernel reports the first that does).
-    const uint32_t k_sel = k < kNsMaxSelect ? k : kNsMaxSelect;
-    uint32_t cap = 256;
-    while (cap < 4 * k_sel) cap <<= 1;
-    // expected candidates: k + 4 sqrt(k) + 4 (at most 2k + 16).  A list that turns up fewer than k candidates (about one
-    // in 10^4) is simply collected again with a bisected bound; every candidate beyond the k-th costs ranking work.
-    uint32_t root = 1;
-    while (root * root < k_sel) ++root;
-    uint32_t target = k_sel + 4 * root + 4;
-    if (target > 2 * k_sel + 16) target = 2 * k_sel + 16;
     int wpb = kWavesPerBlock;
     while (wpb > 1 && (size_t)wpb * cap * 16 > 65536) wpb >>= 1;
     const size_t shmem = (size_t)wpb * cap * 16;
     const dim3 grid(blocks_for(n_dst, wpb));
-#define COOP_NS_ARGS cx.g->indices, rec, n_dst, k, cap, target, wpb, vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl
+#define COOP_NS_ARGS cx.g->indices, rec, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl
     if (cx.blend) {
       if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
       else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
