@@ -195,6 +195,40 @@ __global__ __launch_bounds__(kBlock) void k_scan_offset(int64_t n, Out* __restri
   }
 }
 
+// Short inputs: one block walks over the tiles with a running carry (one launch instead of two).
+constexpr int64_t kScanSmall = 8 * kTile;  // 16384 elements
+template <typename Load, typename Out>
+__global__ __launch_bounds__(kBlock) void k_scan_small(Load load, int64_t n, Out* __restrict__ out, Out* __restrict__ end_out,
+                                                       int64_t* __restrict__ total_out) {
+  __shared__ int64_t lds[kWavesPerBlock];
+  int64_t carry = 0;
+  for (int64_t tile = 0; tile < n; tile += kTile) {
+    const int64_t base = tile + (int64_t)threadIdx.x * kItems;
+    int64_t x[kItems];
+    int64_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      const int64_t i = base + j;
+      x[j] = i < n ? load(i) : 0;
+      sum += x[j];
+    }
+    int64_t tot;
+    const int64_t incl = block_incl_scan(sum, &tot, lds);
+    int64_t run = carry + incl - sum;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      const int64_t i = base + j;
+      if (i < n) out[i] = (Out)run;
+      run += x[j];
+    }
+    carry += tot;
+  }
+  if (threadIdx.x == 0) {
+    if (end_out) *end_out = (Out)carry;
+    if (total_out) *total_out = carry;
+  }
+}
+
 size_t scan_tmp_bytes(int64_t n) {
   const int64_t tiles = (n + kTile - 1) / kTile;
   return (size_t)(tiles + 2) * sizeof(int64_t);
@@ -202,6 +236,10 @@ size_t scan_tmp_bytes(int64_t n) {
 
 template <typename Load, typename Out>
 static void scan_impl(Load load, int64_t n, Out* out, Out* end_out, int64_t* total_out, void* tmp, hipStream_t s) {
+  if (n <= kScanSmall) {
+    COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_small<Load, Out>), dim3(1), dim3(kBlock), 0, s, load, n, out, end_out, total_out);
+    return;
+  }
   int64_t* tile_sum = (int64_t*)tmp;
   const int64_t tiles = (n + kTile - 1) / kTile;
   COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_local<Load, Out>), dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, out, tile_sum);
