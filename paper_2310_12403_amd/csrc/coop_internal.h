@@ -53,20 +53,48 @@ void prof_end(int id, hipStream_t s);
     ::coop::prof_end((id), (stream));                                             \
   } while (0)
 
+// Control block in device memory, mirrored to pinned host memory at every size read-back.
+struct Ctl {
+  int64_t total_edges;   // m_l
+  int64_t total_new;     // |S^{l+1}| - |S^l|
+  int32_t err_range;     // a seed / id out of range
+  int32_t err_dup;       // a duplicate in the seed list
+  int32_t err_capacity;  // NS candidate buffer could not be sized
+  int32_t n_overflow;    // LABOR-0 destinations whose staging row overflowed (this layer and earlier)
+};
+
+// Landing pad of the control block in mapped pinned host memory (see read_ctl).
+struct HostCtl {
+  Ctl ctl;               // must stay the first member
+  uint64_t ticket;       // written by the device after ctl
+  uint64_t next_ticket;  // host side only
+};
+
+// A size read-back in flight: the device stores the control block and then `ticket` into the landing pad.
+struct Publish {
+  const Ctl* d_ctl = nullptr;
+  HostCtl* h = nullptr;
+  uint64_t ticket = 0;
+};
+
 // Device-wide exclusive scans; `tmp` needs scan_tmp_bytes(n) bytes.  out has n + 1 entries, out[n] = total;
-// the total also goes to *total_out (device) when that is not null.
+// the total also goes to *total_out (device) when that is not null.  With `pub`, the thread that stores the total then
+// publishes the control block (total_out normally points into it), which saves the read-back a kernel of its own.
 size_t scan_tmp_bytes(int64_t n);
-void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s);
+void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s,
+                     const Publish* pub = nullptr);
 // the same over an input that lies in up to four pieces: element i is ptr[p][i - start[p]] for the last p with start[p] <= i
 struct ChunkedI32 {
   const int32_t* ptr[4];
   int64_t start[4];
   int n_chunks;
 };
-void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s);
+void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s,
+                        const Publish* pub = nullptr);
 // bit flags packed 64 per word -> uint32 exclusive ranks (out has n entries) and the total in *total_out (device)
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
-void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
+void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s,
+                      const Publish* pub = nullptr);
 
 void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
 
@@ -85,23 +113,12 @@ struct Alloc {
   }
 };
 
-// Control block in device memory, mirrored to pinned host memory at every size read-back.
-struct Ctl {
-  int64_t total_edges;   // m_l
-  int64_t total_new;     // |S^{l+1}| - |S^l|
-  int32_t err_range;     // a seed / id out of range
-  int32_t err_dup;       // a duplicate in the seed list
-  int32_t err_capacity;  // NS candidate buffer could not be sized
-  int32_t n_overflow;    // LABOR-0 destinations whose staging row overflowed (this layer and earlier)
-};
-
-// Landing pad of the control block in mapped pinned host memory (see read_ctl).
-struct HostCtl {
-  Ctl ctl;               // must stay the first member
-  uint64_t ticket;       // written by the device after ctl
-  uint64_t next_ticket;  // host side only
-};
-
+// Size read-back: read_ctl = begin_publish + a one-thread publishing kernel + wait_ctl.  A caller whose last kernel
+// is a scan hands the Publish to the scan instead of launching that kernel.  wait_ctl returns the error the control
+// block reports (range, duplicate, capacity), COOP_E_HIP, or COOP_OK.
+Publish begin_publish(Ctl* d_ctl, Ctl* h_ctl);
+int launch_publish(const Publish& pub, hipStream_t s);
+int wait_ctl(const Publish& pub, Ctl* h_ctl, hipStream_t s);
 int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
 
 // Dedup + relabel of one layer (Eq. 2).  Inputs: dst[n_dst] (distinct), col_global[m].  Outputs: col_local[m],

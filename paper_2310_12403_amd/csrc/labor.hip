@@ -865,8 +865,9 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
   if (nc == 0) { ch.seg[0] = ps.seg; ch.thr[0] = ps.thr; ch.stage[0] = ps.stage[0]; counts.ptr[0] = ps.cnt[0]; nc = 1; }  // n_dst == 0
   ch.n_chunks = counts.n_chunks = nc;
 
-  scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
-  int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
+  const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
+  scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
+  int rc = wait_ctl(pub, cx.h_ctl, s);
   if (rc != COOP_OK) return rc;
   const int64_t m = cx.h_ctl->total_edges;
   blk->n_edges = m;

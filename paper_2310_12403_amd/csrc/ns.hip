@@ -272,8 +272,9 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   if (n_dst > 0)
     COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices, dst, n_dst,
                 k, target, cnt, rec, cx.d_ctl);
-  scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
-  int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
+  const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
+  scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
+  int rc = wait_ctl(pub, cx.h_ctl, s);
   if (rc != COOP_OK) return rc;
   const int64_t m = cx.h_ctl->total_edges;
   blk->n_edges = m;

@@ -121,6 +121,14 @@ __device__ __forceinline__ int64_t block_incl_scan(int64_t v, int64_t* total, in
   return v + base;
 }
 
+// what a one-thread publishing kernel would do, done by the thread that has just stored the scan's total
+__device__ __forceinline__ void publish_ctl(const Publish& pub) {
+  if (pub.h == nullptr) return;
+  pub.h->ctl = *pub.d_ctl;
+  __threadfence_system();
+  __hip_atomic_store(&pub.h->ticket, pub.ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 struct LoadI32 {
   const int32_t* in;
   __device__ __forceinline__ int64_t operator()(int64_t i) const { return in[i]; }
@@ -170,7 +178,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_local(Load load, int64_t n, Out
 
 template <typename Out>
 __global__ __launch_bounds__(kBlock) void k_scan_offset(int64_t n, Out* __restrict__ out, const int64_t* __restrict__ tile_sum,
-                                                        Out* __restrict__ end_out, int64_t* __restrict__ total_out) {
+                                                        Out* __restrict__ end_out, int64_t* total_out, Publish pub) {
   __shared__ int64_t lds[kWavesPerBlock];
   int64_t part = 0;
   for (int64_t t = threadIdx.x; t < (int64_t)blockIdx.x; t += kBlock) part += tile_sum[t];
@@ -192,6 +200,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_offset(int64_t n, Out* __restri
     const int64_t total = off + tile_sum[blockIdx.x];
     if (end_out) *end_out = (Out)total;  // the entry one past the end holds the grand total
     if (total_out) *total_out = total;
+    publish_ctl(pub);
   }
 }
 
@@ -199,7 +208,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_offset(int64_t n, Out* __restri
 constexpr int64_t kScanSmall = 8 * kTile;  // 16384 elements
 template <typename Load, typename Out>
 __global__ __launch_bounds__(kBlock) void k_scan_small(Load load, int64_t n, Out* __restrict__ out, Out* __restrict__ end_out,
-                                                       int64_t* __restrict__ total_out) {
+                                                       int64_t* total_out, Publish pub) {
   __shared__ int64_t lds[kWavesPerBlock];
   int64_t carry = 0;
   for (int64_t tile = 0; tile < n; tile += kTile) {
@@ -226,6 +235,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_small(Load load, int64_t n, Out
   if (threadIdx.x == 0) {
     if (end_out) *end_out = (Out)carry;
     if (total_out) *total_out = carry;
+    publish_ctl(pub);
   }
 }
 
@@ -235,44 +245,47 @@ size_t scan_tmp_bytes(int64_t n) {
 }
 
 template <typename Load, typename Out>
-static void scan_impl(Load load, int64_t n, Out* out, Out* end_out, int64_t* total_out, void* tmp, hipStream_t s) {
+static void scan_impl(Load load, int64_t n, Out* out, Out* end_out, int64_t* total_out, void* tmp, hipStream_t s, const Publish* p) {
+  const Publish pub = p ? *p : Publish{};
   if (n <= kScanSmall) {
-    COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_small<Load, Out>), dim3(1), dim3(kBlock), 0, s, load, n, out, end_out, total_out);
+    COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_small<Load, Out>), dim3(1), dim3(kBlock), 0, s, load, n, out, end_out, total_out, pub);
     return;
   }
   int64_t* tile_sum = (int64_t*)tmp;
   const int64_t tiles = (n + kTile - 1) / kTile;
   COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_local<Load, Out>), dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, out, tile_sum);
-  COOP_LAUNCH(K_SCAN_OFFSET, k_scan_offset<Out>, dim3((unsigned)tiles), dim3(kBlock), 0, s, n, out, tile_sum, end_out, total_out);
+  COOP_LAUNCH(K_SCAN_OFFSET, k_scan_offset<Out>, dim3((unsigned)tiles), dim3(kBlock), 0, s, n, out, tile_sum, end_out, total_out, pub);
 }
 
-__global__ void k_store_total(int64_t* p, int64_t* total_out) {
+__global__ void k_store_total(int64_t* p, int64_t* total_out, Publish pub) {
   *p = 0;
   if (total_out) *total_out = 0;
+  publish_ctl(pub);
 }
 
-void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
+void scan_i32_to_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s, const Publish* pub) {
   if (n <= 0) {  // out[0] = 0
-    COOP_LAUNCH(K_FILL, k_store_total, dim3(1), dim3(1), 0, s, out, total_out);
+    COOP_LAUNCH(K_FILL, k_store_total, dim3(1), dim3(1), 0, s, out, total_out, pub ? *pub : Publish{});
     return;
   }
-  scan_impl<LoadI32, int64_t>(LoadI32{in}, n, out, out + n, total_out, tmp, s);
+  scan_impl<LoadI32, int64_t>(LoadI32{in}, n, out, out + n, total_out, tmp, s, pub);
 }
 
-void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
+void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s, const Publish* pub) {
   if (n <= 0) {
-    COOP_LAUNCH(K_FILL, k_store_total, dim3(1), dim3(1), 0, s, out, total_out);
+    COOP_LAUNCH(K_FILL, k_store_total, dim3(1), dim3(1), 0, s, out, total_out, pub ? *pub : Publish{});
     return;
   }
-  scan_impl<LoadChunks, int64_t>(LoadChunks{in}, n, out, out + n, total_out, tmp, s);
+  scan_impl<LoadChunks, int64_t>(LoadChunks{in}, n, out, out + n, total_out, tmp, s, pub);
 }
 
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
-  scan_impl<LoadBit, uint32_t>(LoadBit{bits}, n, out, (uint32_t*)nullptr, total_out, tmp, s);
+  scan_impl<LoadBit, uint32_t>(LoadBit{bits}, n, out, (uint32_t*)nullptr, total_out, tmp, s, nullptr);
 }
 
-void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
-  scan_impl<LoadPopc, uint32_t>(LoadPopc{bits}, n_words, out, (uint32_t*)nullptr, total_out, tmp, s);
+void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s,
+                      const Publish* pub) {
+  scan_impl<LoadPopc, uint32_t>(LoadPopc{bits}, n_words, out, (uint32_t*)nullptr, total_out, tmp, s, pub);
 }
 
 // ---- CSR validation -------------------------------------------------------------------------------------------

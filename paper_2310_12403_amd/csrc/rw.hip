@@ -216,8 +216,9 @@ int rw_layer(const SampleCtx& cx, const RwConfig& rw, int l, const int32_t* dst,
                   cx.g->indices, cx.g->n_vertices, dst, n_dst, rp, wpb, rows, cnt, cx.d_ctl);
     }
   }
-  scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s);  // m_l = indptr[n_dst]
-  int rc = read_ctl(cx.d_ctl, cx.h_ctl, s);
+  const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
+  scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
+  int rc = wait_ctl(pub, cx.h_ctl, s);
   if (rc != COOP_OK) return rc;
   const int64_t m = cx.h_ctl->total_edges;
   blk->n_edges = m;

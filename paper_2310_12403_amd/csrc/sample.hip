@@ -27,11 +27,19 @@ __global__ void k_publish_ctl(const Ctl* __restrict__ d_ctl, HostCtl* h, uint64_
   __hip_atomic_store(&h->ticket, ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
-int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
+Publish begin_publish(Ctl* d_ctl, Ctl* h_ctl) {
   HostCtl* h = reinterpret_cast<HostCtl*>(h_ctl);  // h_ctl is the first member of a HostCtl in mapped pinned memory
-  const uint64_t ticket = ++h->next_ticket;
-  hipLaunchKernelGGL(k_publish_ctl, dim3(1), dim3(1), 0, s, d_ctl, h, ticket);
-  if (hipGetLastError() != hipSuccess) return COOP_E_HIP;
+  return Publish{d_ctl, h, ++h->next_ticket};
+}
+
+int launch_publish(const Publish& pub, hipStream_t s) {
+  hipLaunchKernelGGL(k_publish_ctl, dim3(1), dim3(1), 0, s, pub.d_ctl, pub.h, pub.ticket);
+  return hipGetLastError() == hipSuccess ? COOP_OK : COOP_E_HIP;
+}
+
+int wait_ctl(const Publish& pub, Ctl* h_ctl, hipStream_t s) {
+  HostCtl* h = pub.h;
+  const uint64_t ticket = pub.ticket;
   bool seen = false;
   for (int64_t spin = 0; spin < ((int64_t)1 << 26); ++spin) {
     if (__atomic_load_n(&h->ticket, __ATOMIC_ACQUIRE) == ticket) { seen = true; break; }
@@ -46,6 +54,12 @@ int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
   if (h_ctl->err_dup) return COOP_E_DUPSEED;
   if (h_ctl->err_capacity) return COOP_E_CAPACITY;
   return COOP_OK;
+}
+
+int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
+  const Publish pub = begin_publish(d_ctl, h_ctl);
+  if (launch_publish(pub, s) != COOP_OK) return COOP_E_HIP;
+  return wait_ctl(pub, h_ctl, s);
 }
 
 int g_stage_cap_override = 0;  // COOP_TUNE_STAGE_CAP

@@ -116,10 +116,12 @@ int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global,
   if (m > 0) {
     COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, n_dst, table, (uint64_t)cap, first,
                 bits);
-    scan_popc_to_u32(bits, n_words, word_rank, &d_ctl->total_new, scan_tmp, s);
   }
-  // sizes (and the duplicate / range flags) back to the host
-  const int rc = read_ctl(d_ctl, h_ctl, s);
+  // sizes (and the duplicate / range flags) back to the host, sent by the scan's last thread when there is a scan
+  const Publish pub = begin_publish(d_ctl, h_ctl);
+  if (m > 0) scan_popc_to_u32(bits, n_words, word_rank, &d_ctl->total_new, scan_tmp, s, &pub);
+  else if (launch_publish(pub, s) != COOP_OK) return COOP_E_HIP;
+  const int rc = wait_ctl(pub, h_ctl, s);
   if (rc != COOP_OK) return rc;
   if (m > 0) n_new = h_ctl->total_new;
 
