@@ -205,7 +205,7 @@ __global__ __launch_bounds__(kBlock) void k_scan_offset(int64_t n, Out* __restri
 }
 
 // Short inputs: one block walks over the tiles with a running carry (one launch instead of two).
-constexpr int64_t kScanSmall = 8 * kTile;  // 16384 elements
+constexpr int64_t kScanSmall = 2 * kTile;  // 4096 elements (beyond that two parallel launches are quicker)
 template <typename Load, typename Out>
 __global__ __launch_bounds__(kBlock) void k_scan_small(Load load, int64_t n, Out* __restrict__ out, Out* __restrict__ end_out,
                                                        int64_t* total_out, Publish pub) {
