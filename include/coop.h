@@ -251,6 +251,9 @@ const char* coop_strerror(int code);
 #define COOP_TUNE_PIECE_LEN 4      /* a LABOR-0 list longer than twice this many entries is cut into pieces of about this
                                       many entries, each scanned by a wave of its own: multiple of 4 in 256..2^24
                                       (default 4096); 0: lists are never cut */
+#define COOP_TUNE_BLEND_CANDIDATES 5 /* first size (entries) of the buffer that holds the candidates of the exact blend of a
+                                      LABOR-0 pass with c > 0; a pass that overflows it is redone with 8 times the size;
+                                      0 (default): k / 2 entries per destination and layer plus 65536 */
 int coop_tune(int knob, int64_t value);
 
 /* out[i] = in[i] for a device id list (a plain streaming copy on `stream`: 4n bytes read, 4n written).  Besides its

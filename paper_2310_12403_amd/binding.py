@@ -381,6 +381,7 @@ COOP_TUNE_STAGE_CAP = 1
 COOP_TUNE_LISTS_PER_WAVE = 2
 COOP_TUNE_FUSE_LAYERS = 3
 COOP_TUNE_PIECE_LEN = 4
+COOP_TUNE_BLEND_CANDIDATES = 5
 
 
 def coop_tune(knob, value):

@@ -13,6 +13,7 @@ enum KernelId {
   K_LABOR_COUNT,     // LABOR-0 count pass
   K_LABOR_FILL,      // LABOR-0 fill pass (copy of the staged rows)
   K_LABOR_OVERFLOW,  // LABOR-0 second scan of overflowed rows
+  K_LABOR_EXACT,     // LABOR-0, c > 0: exact blend of the candidates
   K_SEGMENTS,        // LABOR-0 per-destination list records and keep thresholds
   K_NS_COUNT,        // NS count pass (min(k, d))
   K_NS_FILL,         // NS selection + fill pass
@@ -61,6 +62,8 @@ struct Ctl {
   int32_t err_dup;       // a duplicate in the seed list
   int32_t err_capacity;  // NS candidate buffer could not be sized
   int32_t n_overflow;    // LABOR-0 destinations whose staging row overflowed (this layer and earlier)
+  int32_t cand_overflow; // blended LABOR-0: the candidate buffer of the exact stage was too small (the pass is redone)
+  int32_t pad;
 };
 
 // Landing pad of the control block in mapped pinned host memory (see read_ctl).

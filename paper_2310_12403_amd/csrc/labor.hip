@@ -30,6 +30,18 @@ __device__ __forceinline__ float blend_second_threshold(uint32_t thr, double cs 
   return t;
 }
 
+// The other side of the second filter: an fp32 estimate at or below this value means that the exact blend keeps the
+// edge (tau_lo = Phi^-1 of slightly less than thr / 2^32, less the same allowances, rounded down to a float).
+__device__ __forceinline__ float blend_keep_threshold(uint32_t thr, double cs /* cw + sw */) {
+  if (thr == 0xFFFFFFFFu) return __builtin_inff();  // the whole list is kept
+  if (thr < 64u) return -__builtin_inff();
+  const double tau_lo = kit_phi_inv_u32(thr - 8u);
+  const double lim = tau_lo - 1e-6 * (tau_lo < 0.0 ? -tau_lo : tau_lo) - cs * 4e-3 - 1e-5;
+  float t = (float)lim;
+  if ((double)t > lim) t = __uint_as_float(t > 0.0f ? __float_as_uint(t) - 1u : __float_as_uint(t) + 1u);  // next float down
+  return t;
+}
+
 struct ScanOut {
   StageEntry* stage[kMaxFuse];
   int32_t* cnt[kMaxFuse];
@@ -40,16 +52,40 @@ struct FusedKeys {
   double cw, sw;
 };
 
-// Blended variates (c > 0) cost two Phi^-1 and one Phi per neighbour, ~40 times the integer path.  A cheap necessary
-// condition keeps them off almost every neighbour: R <= thr needs n = cw n1 + sw n2 below tau = Phi^-1(thr / 2^32),
-// and since cw, sw >= 0, n >= (cw + sw) min(n1, n2); so min(U1, U2) must lie below 2^32 Phi(tau / (cw + sw)).  That
-// bound ("pre-threshold"), widened by 1e-6 relative and a few units so that the approximation errors of the kit
-// (1.2e-9) can never matter, is computed once per list and layer; only neighbours that pass it are evaluated exactly.
-__device__ __forceinline__ uint32_t blend_pre_threshold(uint32_t thr, double inv_cs /* (1 - 1e-6) / (cw + sw) */) {
-  if (thr >= 0x7FFFFFF0u) return 0xFFFFFFFFu;           // k / d near or above 1/2: no useful bound
-  const double tau = kit_phi_inv_u32(thr + 8u);          // < 0; Phi^-1 of slightly more than (thr + 1) / 2^32
-  const double lim = (double)kit_phi_to_u32(tau * inv_cs) * 1.000001 + 16.0;
+// Blended variates (c > 0) cost two Phi^-1 and one Phi per neighbour, about a hundred times the integer path.  A cheap
+// necessary condition in integers keeps them off almost every neighbour.  A kept edge has n = cw n1 + sw n2 below
+// tau = Phi^-1 of slightly more than (thr + 1) / 2^32.  With lo = min(U1, U2), hi = max(U1, U2) and cM >= cm the two
+// weights, n >= cM Phi^-1(lo) + cm Phi^-1(hi) >= (cw + sw) Phi^-1(lo).  So the edge lies in the L-shaped region
+// lo <= a2 = 2^32 Phi(tau / (cw + sw)); and inside it either in the strip lo <= a1 (a1 < a2), or, with x1 = Phi^-1(a1),
+// below hi <= b2 = 2^32 Phi((tau - cM x1) / cm).  The bounds are widened by 1e-6 relative and a few units so that the
+// approximation errors of the kit (1.2e-9) can never matter; they are computed once per list and layer.
+struct PreThr {
+  uint32_t a2;  // lo <= a2 is necessary
+  uint32_t a1;  // lo <= a1 is sufficient for a candidate
+  uint32_t b2;  // otherwise hi <= b2 is necessary as well
+  float keep2;  // second filter: an fp32 blend at or below this is kept without the exact stage
+};
+constexpr double kStripShift = 0.6;  // the strip's edge lies this many standard deviations below the L-shape's
+
+__device__ __forceinline__ uint32_t blend_widen(uint32_t R) {
+  const double lim = (double)R * 1.000001 + 16.0;
   return lim >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)lim;
+}
+
+__device__ __forceinline__ PreThr blend_first_thresholds(uint32_t thr, double cw, double sw) {
+  if (thr >= 0x7FFFFFF0u) return PreThr{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0.0f};  // k / d near or above 1/2: no useful bound
+  const double tau_s = kit_phi_inv_u32(thr + 8u) * (1.0 - 1e-6);  // < 0
+  const double x2 = tau_s * kit_rcp(cw + sw);
+  PreThr p;
+  p.a2 = blend_widen(kit_phi_to_u32(x2));
+  p.a1 = kit_phi_to_u32(x2 - kStripShift);
+  const double x1 = kit_phi_inv_u32(p.a1);
+  const double cM = cw > sw ? cw : sw, cm = cw > sw ? sw : cw;
+  double y2 = (tau_s - cM * x1) * kit_rcp(cm);
+  y2 = y2 + 1e-6 * (y2 < 0.0 ? -y2 : y2) + 1e-9;
+  p.b2 = y2 >= 6.0 ? 0xFFFFFFFFu : blend_widen(kit_phi_to_u32(y2));
+  p.keep2 = 0.0f;
+  return p;
 }
 
 // The pieces of one layer's destinations, by the pass that scanned them.
@@ -69,13 +105,13 @@ struct LayerChunks {
 };
 
 // list records of the destinations scanned in this pass, and their keep thresholds for the nf covered layers
-// (pthr: the blended path's pre-thresholds, null when c = 0)
+// (pthr, lim2: the blended path's first and second filter thresholds, null when c = 0)
 constexpr int kSegBlock = 1024;  // large blocks: one queue reservation (a same-address atomic) per 1024 destinations
 __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
                                                      const int32_t* __restrict__ dst, int64_t n, int nf,
                                                      uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, Segment* __restrict__ seg,
-                                                     uint32_t* __restrict__ thr, uint32_t* __restrict__ pthr, float* __restrict__ lim2,
-                                                     double inv_cs, double cs, int queued, Ctl* ctl,
+                                                     uint32_t* __restrict__ thr, PreThr* __restrict__ pthr, float* __restrict__ lim2,
+                                                     double cw, double sw, int queued, Ctl* ctl,
                                                      uint32_t piece_len, Piece* __restrict__ pieces, uint32_t piece_cap,
                                                      uint32_t* __restrict__ piece_count, ScanOut out) {
   __shared__ uint32_t s_wave_at[kSegBlock / kWave];
@@ -100,8 +136,10 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
         sampled &= t != kAllThr;
         thr[(int64_t)f * n + i] = t;
         if (pthr) {
-          pthr[(int64_t)f * n + i] = blend_pre_threshold(t, inv_cs);
-          lim2[(int64_t)f * n + i] = blend_second_threshold(t, cs);
+          PreThr pt = blend_first_thresholds(t, cw, sw);
+          pt.keep2 = blend_keep_threshold(t, cw + sw);
+          pthr[(int64_t)f * n + i] = pt;
+          lim2[(int64_t)f * n + i] = blend_second_threshold(t, cw + sw);
         }
         if (queued) out.cnt[f][i] = 0;  // kept edges are counted by atomics
       }
@@ -277,29 +315,33 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
 }
 
 // ---- blended variates (c > 0) -------------------------------------------------------------------------------------
-// The exact blend (two Phi^-1 and a Phi in binary64) costs about a hundred times the integer path, so it is reached
-// in three stages, each working on a full wave of candidates taken from a per-wave queue in LDS:
-//   1. min(U1, U2) <= pre-threshold (per list and layer; integer compare in the traversal loop);
-//   2. the blend in fp32 below the second threshold (a few dozen instructions; discards all but about the kept ones);
-//   3. the exact blend; a kept edge takes the next free slot of its destination's staging row with an atomic on the
-//      row's counter.  Rows filled this way are unordered: the fill pass ranks them by list position.
-// The stage-3 queue lives across the lists (or pieces) of a wave, so that the expensive stage runs on full waves.
+// The exact blend (two Phi^-1 and a Phi in binary64) costs about a hundred times the integer path and needs four
+// times the registers of the traversal, so it is reached in three stages:
+//   1. integer bounds on min(U1, U2) and max(U1, U2) (per list and layer; in the traversal loop);
+//   2. the blend in fp32, for a full wave of stage-1 passers at a time, taken from a per-wave queue in LDS that lives
+//      across the wave's lists: an estimate safely above the keep threshold is dropped, one safely below is a kept
+//      edge, and only the narrow band in between (a few percent of the kept edges) is left undecided;
+//   3. the exact blend for the undecided, in a kernel of its own (k_labor_exact) over a buffer in device memory that
+//      the scan kernel appended them to: the scan kernel keeps the occupancy of a streaming kernel, the exact stage
+//      runs with every lane busy.
+// A kept edge takes the next free slot of its destination's staging row with an atomic on the row's counter; rows
+// filled this way are unordered and the fill pass ranks them by list position.
 constexpr int kQueueCap = 2 * kWave;
-struct BlendQueue {
-  int32_t t[kQueueCap];
-  uint32_t j[kQueueCap];
-  uint32_t u1[kQueueCap];
-  uint32_t u2[kQueueCap];
-  uint32_t list[kQueueCap];   // destination, index within the pass
-  uint32_t layer[kQueueCap];  // covered layer, 0 .. NF-1
-  uint32_t thr[kQueueCap];    // keep threshold of (list, layer)
-  float lim2[kQueueCap];      // second threshold of (list, layer)
-};
 
-struct BlendEntry {
-  int32_t t;
-  uint32_t j, u1, u2, list, layer, thr;
-  float lim2;
+// A candidate for the exact blend.
+struct Cand {
+  int32_t t;       // neighbour
+  uint32_t j;      // its position in the destination's list
+  uint32_t list;   // destination, index within the pass
+  uint32_t layer;  // covered layer, 0 .. NF-1
+};
+// The buffer is split into kCandSub sub-buffers with a counter each (a block appends to sub-buffer blockIdx mod
+// kCandSub): appending costs an atomic with a returned value, and a single counter would serialise them.
+constexpr int kCandSub = 256;
+struct CandOut {
+  Cand* buf;          // [kCandSub][cap_each]
+  uint32_t* count;    // [kCandSub] entries appended so far (may run past cap_each: the excess is dropped, the pass redone)
+  uint32_t cap_each;
 };
 
 // Stage-1 queue: one per covered layer, three words per candidate: the neighbour, its list position, and which of
@@ -312,77 +354,27 @@ struct FirstQueue {
 
 struct BlendState {
   FirstQueue* q1;  // passed stage 1 (any list of this wave)
-  BlendQueue* q2;  // passed stage 2 (any list of this wave)
-  uint32_t n1[kMaxFuse] = {0, 0, 0, 0};
-  uint32_t n2 = 0;  // wave-uniform fill levels (each below 64 between calls)
+  CandOut cand;    // where the stage-2 survivors go
+  uint32_t n1[kMaxFuse] = {0, 0, 0, 0};  // wave-uniform fill levels (each below 64 between calls)
 };
-
-__device__ __forceinline__ BlendEntry queue_get(const BlendQueue* __restrict__ q, uint32_t i) {
-  return BlendEntry{q->t[i], q->j[i], q->u1[i], q->u2[i], q->list[i], q->layer[i], q->thr[i], q->lim2[i]};
-}
-__device__ __forceinline__ void queue_put(BlendQueue* __restrict__ q, uint32_t i, const BlendEntry& e) {
-  q->t[i] = e.t; q->j[i] = e.j; q->u1[i] = e.u1; q->u2[i] = e.u2; q->list[i] = e.list; q->layer[i] = e.layer; q->thr[i] = e.thr;
-  q->lim2[i] = e.lim2;
-}
-// appends the entries of the lanes with `in` set (fill level below 64 before, so at most 128 after)
-__device__ __forceinline__ void queue_push(BlendQueue* __restrict__ q, uint32_t& qn, bool in, const BlendEntry& e) {
-  const uint64_t mask = ballot64(in);
-  if (mask == 0) return;
-  if (in) queue_put(q, qn + lanes_below(mask), e);
-  qn += (uint32_t)__popcll(mask);
-  __builtin_amdgcn_wave_barrier();
-}
-// drops the first 64 entries: the rest (fewer than 64) moves to the front
-__device__ __forceinline__ void queue_pop_wave(BlendQueue* __restrict__ q, uint32_t& qn) {
-  const uint32_t lane = (uint32_t)lane_id();
-  const uint32_t rest = qn - kWave;
-  BlendEntry e{};
-  if (lane < rest) e = queue_get(q, kWave + lane);
-  __builtin_amdgcn_wave_barrier();
-  if (lane < rest) queue_put(q, lane, e);
-  qn = rest;
-  __builtin_amdgcn_wave_barrier();
-}
-
-// stage 3 on entries [0, n) of q2 (n <= 64)
-template <int NF>
-__device__ __forceinline__ void blend_exact(const BlendState& st, uint32_t n, const FusedKeys& keys, uint32_t stage_cap, const ScanOut& out,
-                                            Ctl* ctl) {
-  const uint32_t lane = (uint32_t)lane_id();
-  if (lane < n) {
-    const BlendEntry e = queue_get(st.q2, lane);
-    const double n1 = kit_phi_inv_u32(e.u1);
-    const double n2 = kit_phi_inv_u32(e.u2);
-    const uint32_t R = kit_phi_to_u32(__builtin_fma(keys.cw, n1, keys.sw * n2));
-    if (R <= e.thr) {
-      int32_t* cnt = out.cnt[0];
-      StageEntry* stage = out.stage[0];
-#pragma unroll
-      for (int f = 1; f < NF; ++f)
-        if (e.layer == (uint32_t)f) { cnt = out.cnt[f]; stage = out.stage[f]; }
-      const uint32_t at = (uint32_t)atomicAdd(&cnt[e.list], 1);
-      if (at < stage_cap) stage[(size_t)e.list * stage_cap + at] = StageEntry{e.t, e.j};
-      else if (at == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
-    }
-  }
-}
 
 // What stage 2 needs to know about the wave's lists: lane i holds the thresholds of list first + i.
 template <int NF>
 struct ListBlend {
   uint32_t first;
-  uint32_t thr[NF];
   float lim2[NF];
+  float keep2[NF];
 };
 
 // stage 2 on entries [first, first + n) of layer l's stage-1 queue (n <= 64): the two uniforms again, the blend in
-// fp32; survivors go to q2, which is drained whenever a full wave waits
+// fp32.  An estimate safely below the threshold is a kept edge (it takes the next free slot of its destination's
+// staging row); one safely above is dropped; the few in between are appended to the candidate buffer of the exact
+// stage (one atomic per call).
 template <int NF>
 __device__ __forceinline__ void blend_second(BlendState& st, int l, uint32_t first, uint32_t n, const ListBlend<NF>& lb, const FusedKeys& keys,
                                              float cwf, float swf, uint32_t stage_cap, const ScanOut& out, Ctl* ctl) {
   const uint32_t lane = (uint32_t)lane_id();
-  BlendEntry e{};
-  bool pass = false;
+  Cand e{};
   uint32_t slot = 0;
   if (lane < n) {
     e.t = st.q1->t[l][first + lane];
@@ -390,21 +382,32 @@ __device__ __forceinline__ void blend_second(BlendState& st, int l, uint32_t fir
     slot = st.q1->slot[l][first + lane];
   }
   // thresholds of the candidate's list: from the lane that holds them (every lane takes part in the exchange)
-  e.thr = (uint32_t)__shfl((int)lb.thr[l], (int)slot, kWave);
-  e.lim2 = __shfl(lb.lim2[l], (int)slot, kWave);
+  const float lim2 = __shfl(lb.lim2[l], (int)slot, kWave);
+  const float keep2 = __shfl(lb.keep2[l], (int)slot, kWave);
+  bool keep = false, maybe = false;
   if (lane < n) {
-    e.u1 = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)e.t, 0u);
-    e.u2 = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)e.t, 0u);
+    const uint32_t u1 = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)e.t, 0u);
+    const uint32_t u2 = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)e.t, 0u);
     e.list = lb.first + slot;
     e.layer = (uint32_t)l;
-    const float est = __builtin_fmaf(cwf, approx_phi_inv_f32(e.u1), swf * approx_phi_inv_f32(e.u2));
-    pass = est <= e.lim2;
+    const float est = __builtin_fmaf(cwf, approx_phi_inv_f32(u1), swf * approx_phi_inv_f32(u2));
+    keep = est <= keep2;
+    maybe = !keep && est <= lim2;
   }
-  queue_push(st.q2, st.n2, pass, e);
-  if (st.n2 >= (uint32_t)kWave) {
-    blend_exact<NF>(st, kWave, keys, stage_cap, out, ctl);
-    __builtin_amdgcn_wave_barrier();
-    queue_pop_wave(st.q2, st.n2);
+  if (keep) {
+    const uint32_t at = (uint32_t)atomicAdd(&out.cnt[l][e.list], 1);
+    if (at < stage_cap) out.stage[l][(size_t)e.list * stage_cap + at] = StageEntry{e.t, e.j};
+    else if (at == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
+  }
+  const uint64_t mask = ballot64(maybe);
+  if (mask == 0) return;
+  const uint32_t sub = blockIdx.x & (kCandSub - 1);
+  uint32_t at = 0;
+  if (lane == 0) at = atomicAdd(&st.cand.count[sub], (uint32_t)__popcll(mask));
+  at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at) + lanes_below(mask);
+  if (maybe) {
+    if (at < st.cand.cap_each) st.cand.buf[(size_t)sub * st.cand.cap_each + at] = e;
+    else atomicOr(&ctl->cand_overflow, 1);
   }
 }
 
@@ -452,10 +455,10 @@ __device__ __forceinline__ void blend_flush_first(BlendState& st, const ListBlen
 
 // Blended scan of entries [beg, beg + d) of the wave's list number `slot` (a whole list, or the piece that starts at
 // list position j0): same traversal as labor_scan_fast; per entry and layer two mixer evaluations and the stage-1
-// compare against pthr.  Candidates may still wait in the queues on return.
+// compare against pthr.  Candidates may still wait in the stage-1 queues on return.
 template <int NF>
 __device__ __forceinline__ void labor_scan_blend(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t j0, uint32_t slot,
-                                                 const uint32_t (&pthr)[NF], const ListBlend<NF>& lb, const FusedKeys& keys, BlendState& st,
+                                                 const PreThr (&pthr)[NF], const ListBlend<NF>& lb, const FusedKeys& keys, BlendState& st,
                                                  uint32_t stage_cap, const ScanOut& out, Ctl* ctl) {
   constexpr uint32_t kStep = kWave * 4 * kScanGroups;
   const int64_t abeg = beg & ~(int64_t)3;
@@ -489,7 +492,8 @@ __device__ __forceinline__ void labor_scan_blend(const int32_t* __restrict__ g_i
         for (int e = 0; e < 4; ++e) {
           const uint32_t u1 = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)buf[gq][e], 0u);
           const uint32_t u2 = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)buf[gq][e], 0u);
-          pre[l][e] = ok[gq] & ((u1 < u2 ? u1 : u2) <= pthr[l]);
+          const uint32_t lo = u1 < u2 ? u1 : u2, hi = u1 < u2 ? u2 : u1;
+          pre[l][e] = ok[gq] & ((lo <= pthr[l].a1) | ((lo <= pthr[l].a2) & (hi <= pthr[l].b2)));
           any |= pre[l][e];
         }
       }
@@ -511,7 +515,9 @@ __device__ __forceinline__ void labor_scan_blend(const int32_t* __restrict__ g_i
     for (int l = 0; l < NF; ++l) {
       const uint32_t a = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)t, 0u);
       const uint32_t b = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)t, 0u);
-      blend_first<NF>(st, l, valid && (a < b ? a : b) <= pthr[l], t, pos - head + j0, slot, lb, keys, cwf, swf, stage_cap, out, ctl);
+      const uint32_t lo = a < b ? a : b, hi = a < b ? b : a;
+      blend_first<NF>(st, l, valid && (lo <= pthr[l].a1 || (lo <= pthr[l].a2 && hi <= pthr[l].b2)), t, pos - head + j0, slot, lb, keys, cwf,
+                      swf, stage_cap, out, ctl);
     }
   }
 }
@@ -522,18 +528,18 @@ __device__ __forceinline__ void labor_scan_blend(const int32_t* __restrict__ g_i
 // that leaves them in the staging row; the fill pass sorts the rows of cut lists by list position.
 template <bool BLEND, int VEC, int NF>
 __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict__ g_indices, const Segment* __restrict__ seg,
-                                                       const uint32_t* __restrict__ thr_all, const uint32_t* __restrict__ pthr_all,
+                                                       const uint32_t* __restrict__ thr_all, const PreThr* __restrict__ pthr_all,
                                                        const float* __restrict__ lim2_all, int64_t n, int lists_per_wave, FusedKeys keys,
                                                        uint32_t stage_cap, ScanOut out,
                                                        Ctl* ctl, int piece_blocks, const Piece* __restrict__ pieces,
-                                                       const uint32_t* __restrict__ piece_count, uint32_t piece_cap, uint32_t piece_len) {
-  constexpr bool kQueued = BLEND && VEC == 4;  // blended variates through the staged queues
+                                                       const uint32_t* __restrict__ piece_count, uint32_t piece_cap, uint32_t piece_len,
+                                                       CandOut cand) {
+  constexpr bool kQueued = BLEND && VEC == 4;  // blended variates through the staged filters
   __shared__ FirstQueue first_queues[kQueued ? kWavesPerBlock : 1];
-  __shared__ BlendQueue second_queues[kQueued ? kWavesPerBlock : 1];
   BlendState bst{};
   if constexpr (kQueued) {
     bst.q1 = &first_queues[uniform_wave_in_block()];
-    bst.q2 = &second_queues[uniform_wave_in_block()];
+    bst.cand = cand;
   }
   const uint32_t lane = (uint32_t)lane_id();
   if constexpr (VEC == 4) {
@@ -560,13 +566,17 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
 #pragma unroll
         for (int l = 0; l < NF; ++l) thr[l] = (uint32_t)__builtin_amdgcn_readfirstlane((int)thr_all[(int64_t)l * n + list]);
         if constexpr (kQueued) {
-          uint32_t pthr[NF];
+          PreThr pthr[NF];
           ListBlend<NF> lb;
           lb.first = list;  // every lane holds this list's thresholds: slot 0
 #pragma unroll
           for (int l = 0; l < NF; ++l) {
-            pthr[l] = (uint32_t)__builtin_amdgcn_readfirstlane((int)pthr_all[(int64_t)l * n + list]);
-            lb.thr[l] = thr[l];
+            const PreThr pt = pthr_all[(int64_t)l * n + list];
+            pthr[l].a2 = (uint32_t)__builtin_amdgcn_readfirstlane((int)pt.a2);
+            pthr[l].a1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)pt.a1);
+            pthr[l].b2 = (uint32_t)__builtin_amdgcn_readfirstlane((int)pt.b2);
+            pthr[l].keep2 = pt.keep2;
+            lb.keep2[l] = pt.keep2;
             lb.lim2[l] = lim2_all[(int64_t)l * n + list];
           }
           labor_scan_blend<NF>(g_indices, beg + j0, len, j0, 0u, pthr, lb, keys, bst, stage_cap, out, ctl);
@@ -589,9 +599,6 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
           }
         }
       }
-      if constexpr (kQueued) {
-        if (bst.n2 != 0) blend_exact<NF>(bst, bst.n2, keys, stage_cap, out, ctl);  // what still waits for the exact stage
-      }
       return;
     }
   }
@@ -601,10 +608,11 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
   const int64_t mine = first + lane;
   const bool has = (int)lane < lists_per_wave && mine < n;
   Segment g{0, 0, 0};
-  uint32_t my_thr[NF], my_pthr[NF];
+  uint32_t my_thr[NF];
+  PreThr my_pthr[NF];
   float my_lim2[NF];
 #pragma unroll
-  for (int l = 0; l < NF; ++l) { my_thr[l] = kAllThr; my_pthr[l] = kAllThr; my_lim2[l] = 0.0f; }
+  for (int l = 0; l < NF; ++l) { my_thr[l] = kAllThr; my_pthr[l] = PreThr{kAllThr, kAllThr, kAllThr, 0.0f}; my_lim2[l] = 0.0f; }
   if (has) {
     g = seg[mine];
 #pragma unroll
@@ -620,7 +628,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
   ListBlend<NF> lbw;  // lane i: thresholds of list first + i
   lbw.first = (uint32_t)first;
 #pragma unroll
-  for (int l = 0; l < NF; ++l) { lbw.thr[l] = my_thr[l]; lbw.lim2[l] = my_lim2[l]; }
+  for (int l = 0; l < NF; ++l) { lbw.lim2[l] = my_lim2[l]; lbw.keep2[l] = my_pthr[l].keep2; }
   const int n_lists = (int)(n - first < lists_per_wave ? n - first : lists_per_wave);
   for (int i = 0; i < n_lists; ++i) {
     const int64_t beg = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)beg_hi, i) << 32) |
@@ -635,9 +643,14 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
       any_all |= thr[l] == kAllThr;
     }
     if constexpr (kQueued) {  // every list, whatever its length: kept edges reach the rows through the queues
-      uint32_t pthr[NF];
+      PreThr pthr[NF];
 #pragma unroll
-      for (int l = 0; l < NF; ++l) pthr[l] = (uint32_t)__builtin_amdgcn_readlane((int)my_pthr[l], i);
+      for (int l = 0; l < NF; ++l) {
+        pthr[l].a2 = (uint32_t)__builtin_amdgcn_readlane((int)my_pthr[l].a2, i);
+        pthr[l].a1 = (uint32_t)__builtin_amdgcn_readlane((int)my_pthr[l].a1, i);
+        pthr[l].b2 = (uint32_t)__builtin_amdgcn_readlane((int)my_pthr[l].b2, i);
+        pthr[l].keep2 = 0.0f;  // (stage 2 takes it from the lane that holds the list)
+      }
       if (d != 0) labor_scan_blend<NF>(g_indices, beg, d, 0u, (uint32_t)i, pthr, lbw, keys, bst, stage_cap, out, ctl);
       continue;
     }
@@ -663,8 +676,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
   }
   if constexpr (kQueued) {
     blend_flush_first<NF>(bst, lbw, keys, stage_cap, out, ctl);
-    if (bst.n2 != 0) blend_exact<NF>(bst, bst.n2, keys, stage_cap, out, ctl);  // what still waits for the exact stage
-    return;                                                                   // (the counters were kept by atomics)
+    return;  // (the exact stage, a kernel of its own, keeps the counters by atomics)
   }
   if (has && g.split == 0) {
 #pragma unroll
@@ -673,6 +685,43 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
       if (my_count[l] > stage_cap) atomicAdd(&ctl->n_overflow, 1);
     }
   }
+}
+
+// Stage 3 of the blended path: the exact blend for every candidate the scan kernel appended, one candidate per thread
+// (grid-stride; the count is read from device memory).  A kept edge takes the next free slot of its destination's
+// staging row.
+__global__ __launch_bounds__(kBlock) void k_labor_exact(CandOut cand, const uint32_t* __restrict__ thr_all, int64_t n, int nf, FusedKeys keys,
+                                                        uint32_t stage_cap, ScanOut out, Ctl* ctl) {
+  uint32_t total = cand.count[blockIdx.y];  // blockIdx.y: the sub-buffer
+  if (total > cand.cap_each) total = cand.cap_each;
+  const Cand* __restrict__ mine = cand.buf + (size_t)blockIdx.y * cand.cap_each;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (uint64_t)gridDim.x * kBlock) {
+    const Cand e = mine[i];
+    if (e.layer >= (uint32_t)nf || (int64_t)e.list >= n) continue;  // (never: the scan kernel wrote it)
+    LayerKeys K = keys.K[0];
+    int32_t* cnt = out.cnt[0];
+    StageEntry* stage = out.stage[0];
+#pragma unroll
+    for (int f = 1; f < kMaxFuse; ++f)
+      if (e.layer == (uint32_t)f) { K = keys.K[f]; cnt = out.cnt[f]; stage = out.stage[f]; }
+    const uint32_t thr = thr_all[(int64_t)e.layer * n + e.list];
+    const double n1 = kit_phi_inv_u32(keyed_uniform<false>(K.Ka, (uint32_t)e.t, 0u));
+    const double n2 = kit_phi_inv_u32(keyed_uniform<false>(K.Kb, (uint32_t)e.t, 0u));
+    const uint32_t R = kit_phi_to_u32(__builtin_fma(keys.cw, n1, keys.sw * n2));
+    if (R <= thr) {
+      const uint32_t at = (uint32_t)atomicAdd(&cnt[e.list], 1);
+      if (at < stage_cap) stage[(size_t)e.list * stage_cap + at] = StageEntry{e.t, e.j};
+      else if (at == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
+    }
+  }
+}
+
+__global__ void k_labor_redo(Ctl* ctl, uint32_t* piece_count, uint32_t* cand_count) {  // kCandSub threads
+  if (threadIdx.x == 0) {
+    ctl->cand_overflow = 0;
+    *piece_count = 0;
+  }
+  cand_count[threadIdx.x] = 0;
 }
 
 // staged rows -> the block's edge arrays: kFillLanes threads per destination, each taking every kFillLanes-th slot
@@ -747,14 +796,14 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int32_t* _
 }
 
 template <bool BLEND, int VEC>
-static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, const uint32_t* pthr, const float* lim2, int64_t n,
+static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, const PreThr* pthr, const float* lim2, int64_t n,
                         int lpw, const FusedKeys& keys, uint32_t cap, const ScanOut& out, Ctl* ctl, int piece_blocks, const Piece* pieces,
-                        const uint32_t* piece_count, uint32_t piece_cap, uint32_t piece_len) {
+                        const uint32_t* piece_count, uint32_t piece_cap, uint32_t piece_len, const CandOut& cand) {
   switch (nf) {
-    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
-    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
-    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
-    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len); break;
+    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
   }
 }
 
@@ -789,7 +838,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
   const int64_t n_new = ps.n_new;
   ps.seg = alloc.get<Segment>(n_new, COOP_TAG_SCRATCH);
   ps.thr = alloc.get<uint32_t>(n_new * ps.nf, COOP_TAG_SCRATCH);
-  uint32_t* pthr = cx.blend ? alloc.get<uint32_t>(n_new * ps.nf, COOP_TAG_SCRATCH) : nullptr;
+  PreThr* pthr = cx.blend ? alloc.get<PreThr>(n_new * ps.nf, COOP_TAG_SCRATCH) : nullptr;
   float* lim2 = cx.blend ? alloc.get<float>(n_new * ps.nf, COOP_TAG_SCRATCH) : nullptr;
   for (int f = 0; f < ps.nf; ++f) {
     ps.stage[f] = alloc.get<StageEntry>(n_new * (int64_t)cap, COOP_TAG_SCRATCH);
@@ -820,31 +869,20 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     pieces = alloc.get<Piece>(piece_cap, COOP_TAG_SCRATCH);
     if (alloc.failed) return COOP_E_NOMEM;
   }
-  if (n_new > 0) {
-    ScanOut out{};
-    for (int f = 0; f < ps.nf; ++f) { out.stage[f] = ps.stage[f]; out.cnt[f] = ps.cnt[f]; }
-    COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
-                dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, (1.0 - 1e-6) / (cx.cw + cx.sw), cx.cw + cx.sw,
-                cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
-                piece_len, pieces, piece_cap, cx.d_piece_count + l, out);
-    // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
-    int lpw = g_lists_per_wave;
-    if (lpw == 0) lpw = n_new >= 65536 ? (cx.blend && cx.vec4 ? 8 : 4) : 1;  // blended: fuller waves at the exact stage
-    const int64_t n_waves = (n_new + lpw - 1) / lpw;
-    // the piece waves come first in the grid: one round of resident blocks, fewer if there cannot be that many pieces
-    constexpr int64_t kPieceBlocks = 2048;
-    const int piece_blocks = (int)(blocks_for(piece_cap, kWavesPerBlock) < kPieceBlocks ? blocks_for(piece_cap, kWavesPerBlock) : kPieceBlocks);
-    const dim3 grid(blocks_for(n_waves, kWavesPerBlock) + (unsigned)piece_blocks);
-    const uint32_t* pcount = cx.d_piece_count + l;
-    if (cx.blend) {
-      if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len);
-      else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u);
-    } else {
-      if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len);
-      else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u);
-    }
+  // blended variates: stage 3 works from a buffer of the candidates that the fp32 blend left undecided, a few percent
+  // of the k kept edges per destination and layer; k / 2 each is ample (a pass that overflows it is redone with more)
+  const bool queued = cx.blend && cx.vec4 && n_new > 0;
+  int64_t cand_cap = 0;
+  uint32_t* cand_count = nullptr;
+  if (queued) {
+    uint32_t kpass = 1;
+    for (int f = 0; f < ps.nf; ++f) kpass = ks[f] > kpass ? ks[f] : kpass;
+    cand_cap = g_blend_candidates ? g_blend_candidates : (int64_t)kpass * n_new * ps.nf / 2 + 65536;
+    if (cand_cap > ((int64_t)1 << 30)) cand_cap = (int64_t)1 << 30;
+    cand_count = alloc.get<uint32_t>(kCandSub, COOP_TAG_SCRATCH);
+    if (alloc.failed) return COOP_E_NOMEM;
+    fill_u64((uint64_t*)cand_count, kCandSub / 2, 0, s);
   }
-
   // ---- this layer's destinations, piece by piece: a recorded pass covered it as its (l - first_layer)-th layer ------
   if (record) { st.n_pass += 1; st.covered = n_dst; }
   LayerChunks ch{};
@@ -865,10 +903,54 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
   if (nc == 0) { ch.seg[0] = ps.seg; ch.thr[0] = ps.thr; ch.stage[0] = ps.stage[0]; counts.ptr[0] = ps.cnt[0]; nc = 1; }  // n_dst == 0
   ch.n_chunks = counts.n_chunks = nc;
 
-  const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
-  scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
-  int rc = wait_ctl(pub, cx.h_ctl, s);
-  if (rc != COOP_OK) return rc;
+  for (;;) {
+    if (n_new > 0) {
+      ScanOut out{};
+      for (int f = 0; f < ps.nf; ++f) { out.stage[f] = ps.stage[f]; out.cnt[f] = ps.cnt[f]; }
+      CandOut cand{};
+      if (queued) {
+        cand.cap_each = (uint32_t)((cand_cap + kCandSub - 1) / kCandSub);
+        cand.buf = alloc.get<Cand>((int64_t)cand.cap_each * kCandSub, COOP_TAG_SCRATCH);
+        cand.count = cand_count;
+        if (alloc.failed) return COOP_E_NOMEM;
+      }
+      COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
+                  dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, cx.cw, cx.sw,
+                  cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
+                  piece_len, pieces, piece_cap, cx.d_piece_count + l, out);
+      // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
+      int lpw = g_lists_per_wave;
+      if (lpw == 0) lpw = n_new >= 65536 ? (cx.blend && cx.vec4 ? 8 : 4) : 1;  // blended: fuller waves at the exact stage
+      const int64_t n_waves = (n_new + lpw - 1) / lpw;
+      // the piece waves come first in the grid: one round of resident blocks, fewer if there cannot be that many pieces
+      constexpr int64_t kPieceBlocks = 2048;
+      const int piece_blocks = (int)(blocks_for(piece_cap, kWavesPerBlock) < kPieceBlocks ? blocks_for(piece_cap, kWavesPerBlock) : kPieceBlocks);
+      const dim3 grid(blocks_for(n_waves, kWavesPerBlock) + (unsigned)piece_blocks);
+      const uint32_t* pcount = cx.d_piece_count + l;
+      if (cx.blend) {
+        if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len, cand);
+        else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u, cand);
+      } else {
+        if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len, cand);
+        else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u, cand);
+      }
+      if (queued) {  // stage 3: the exact blend for the candidates that the scan appended
+        const unsigned blocks = blocks_for(cand.cap_each, kBlock) < 16 ? blocks_for(cand.cap_each, kBlock) : 16;
+        COOP_LAUNCH(K_LABOR_EXACT, k_labor_exact, dim3(blocks, kCandSub), dim3(kBlock), 0, s, cand, ps.thr, n_new, ps.nf, keys, cap, out,
+                    cx.d_ctl);
+      }
+    }
+
+    const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
+    scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
+    const int rc = wait_ctl(pub, cx.h_ctl, s);
+    if (rc != COOP_OK) return rc;
+    if (!queued || cx.h_ctl->cand_overflow == 0) break;
+    // the candidate buffer of the exact stage was too small (counts are incomplete): once more with 8 times the room
+    if (cand_cap >= ((int64_t)1 << 30)) return COOP_E_CAPACITY;
+    cand_cap = cand_cap * 8 < ((int64_t)1 << 30) ? cand_cap * 8 : ((int64_t)1 << 30);
+    hipLaunchKernelGGL(k_labor_redo, dim3(1), dim3(kCandSub), 0, s, cx.d_ctl, cx.d_piece_count + l, cand_count);
+  }
   const int64_t m = cx.h_ctl->total_edges;
   blk->n_edges = m;
   blk->col_global = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);

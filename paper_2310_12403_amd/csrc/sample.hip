@@ -66,6 +66,7 @@ int g_stage_cap_override = 0;  // COOP_TUNE_STAGE_CAP
 int g_lists_per_wave = 0;      // COOP_TUNE_LISTS_PER_WAVE (0 = automatic)
 int g_fuse_layers = 1;         // COOP_TUNE_FUSE_LAYERS
 int g_piece_len = 4096;        // COOP_TUNE_PIECE_LEN
+int64_t g_blend_candidates = 0;  // COOP_TUNE_BLEND_CANDIDATES (0 = automatic)
 
 }  // namespace coop
 
@@ -88,6 +89,10 @@ extern "C" int coop_tune(int knob, int64_t value) {
     case COOP_TUNE_PIECE_LEN:
       if (value != 0 && (value < 256 || value > ((int64_t)1 << 24) || (value & 3))) return COOP_E_ARG;
       g_piece_len = (int)value;
+      return COOP_OK;
+    case COOP_TUNE_BLEND_CANDIDATES:
+      if (value < 0 || value > ((int64_t)1 << 30)) return COOP_E_ARG;
+      g_blend_candidates = value;
       return COOP_OK;
     default:
       return COOP_E_ARG;

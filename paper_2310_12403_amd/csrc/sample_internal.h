@@ -71,6 +71,7 @@ extern int g_stage_cap_override;
 extern int g_lists_per_wave;
 extern int g_fuse_layers;
 extern int g_piece_len;
+extern int64_t g_blend_candidates;
 
 static inline unsigned blocks_for(int64_t n, int64_t per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 

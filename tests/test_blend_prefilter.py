@@ -1,7 +1,8 @@
-"""The GPU's blended LABOR-0 scan skips the exact Phi / Phi^-1 evaluation for neighbours whose two uniforms both lie
-above a per-list "pre-threshold".  This checks, on the CPU and with the oracle's bit-identical arithmetic kit, that the
-pre-threshold formula is a necessary condition: whenever the exact variate keeps an edge, the pre-filter passes it.
-(The GPU parity tests then check the kernel that uses it.)"""
+"""The GPU's blended LABOR-0 scan reaches the exact Phi / Phi^-1 evaluation through two cheap filters: integer bounds
+on the two uniforms (an L-shaped region, refined to a strip and a corner rectangle) and the blend in fp32 with a
+safety margin.  This checks, on the CPU and with the oracle's bit-identical arithmetic kit, that each filter is a
+necessary condition: whenever the exact variate keeps an edge, the filter passes it.  (The GPU parity tests then check
+the kernel that uses them.)"""
 import math
 
 import numpy as np
@@ -12,13 +13,8 @@ M32 = 0xFFFFFFFF
 
 
 def pre_threshold(L, thr, cw, sw):
-    """Restatement of blend_pre_threshold() in csrc/labor.hip."""
-    if thr >= 0x7FFFFFF0:
-        return M32
-    tau = L.coopref_phi_inv_u32(thr + 8)
-    inv_cs = (1.0 - 1e-6) / (cw + sw)
-    lim = float(L.coopref_phi_to_u32(tau * inv_cs)) * 1.000001 + 16.0
-    return M32 if lim >= 4294967295.0 else int(lim)
+    """The L-shaped region alone: min(U1, U2) <= a2 of first_thresholds() below."""
+    return first_thresholds(L, thr, cw, sw)[1]
 
 
 def test_pre_threshold_never_rejects_a_kept_edge():
@@ -176,3 +172,135 @@ def test_second_filter_is_selective():
     tau = float(ndtri(thr / 2**32))
     from scipy.special import ndtr
     assert ndtr(T2) / ndtr(tau) < 1.03       # n ~ N(0, 1): pass probability against keep probability
+
+
+# --------------------------------------------------------------------------- #
+# First filter, refined: a strip and a corner rectangle instead of the L-shaped region
+# --------------------------------------------------------------------------- #
+STRIP_SHIFT = 0.6     # the strip's edge lies this far (in standard deviations) below the L-shape's
+
+
+def first_thresholds(L, thr, cw, sw):
+    """Restatement of blend_first_thresholds() in csrc/labor.hip: with lo = min(U1, U2), hi = max(U1, U2), a kept edge
+    has lo <= a1, or lo <= a2 and hi <= b2."""
+    if thr >= 0x7FFFFFF0:
+        return M32, M32, M32
+    tau_s = L.coopref_phi_inv_u32(thr + 8) * (1.0 - 1e-6)
+    widen = lambda R: M32 if float(R) * 1.000001 + 16.0 >= 4294967295.0 else int(float(R) * 1.000001 + 16.0)
+    x2 = tau_s * L.coopref_rcp(cw + sw)
+    a2 = widen(L.coopref_phi_to_u32(x2))
+    a1 = L.coopref_phi_to_u32(x2 - STRIP_SHIFT)
+    x1 = L.coopref_phi_inv_u32(a1)
+    cM, cm = max(cw, sw), min(cw, sw)
+    y2 = (tau_s - cM * x1) * L.coopref_rcp(cm)
+    y2 = y2 + 1e-6 * abs(y2) + 1e-9
+    b2 = M32 if y2 >= 6.0 else widen(L.coopref_phi_to_u32(y2))
+    return a1, a2, b2
+
+
+def test_refined_first_filter_never_rejects_a_kept_edge():
+    from scipy.special import ndtr, ndtri
+    L = R.lib()
+    rng = np.random.default_rng(3)
+    checked = kept = rejected = 0
+    for trial in range(400):
+        k = int(rng.integers(1, 60))
+        d = int(k + 1 + 10 ** rng.uniform(0, 5))
+        thr = (k << 32) // d
+        kappa = int(rng.integers(2, 300))
+        i = int(rng.integers(1, kappa))
+        c = i / kappa
+        cw, sw = math.cos(c * 1.5707963267948966), math.sin(c * 1.5707963267948966)
+        a1, a2, b2 = first_thresholds(L, thr, cw, sw)
+        assert a1 <= a2
+        tau = float(ndtri((thr + 0.5) / 2**32))
+        cands = []
+        for _ in range(40):
+            n1 = float(rng.normal()) - (2.0 if rng.random() < 0.5 else 0.0)
+            n2 = (tau - cw * n1) / sw + float(rng.normal()) * 10 ** rng.uniform(-6, -1)
+            if rng.random() < 0.5:      # also the mirror image: the small uniform in the other seat
+                n2b = float(rng.normal()) - 2.0
+                n1, n2 = (tau - sw * n2b) / cw + float(rng.normal()) * 10 ** rng.uniform(-6, -1), n2b
+            cands.append((int(min(M32, max(0, ndtr(n1) * 2**32))), int(min(M32, max(0, ndtr(n2) * 2**32)))))
+        for base in (a1, a2, b2):       # the rectangle's corners and their neighbours
+            for dl in range(-2, 3):
+                v = max(0, min(M32, base + dl))
+                cands += [(v, min(M32, b2 + 1)), (min(M32, b2 + 1), v), (v, v), (v, b2), (b2, v)]
+        for U1, U2 in cands:
+            n = np.float64(cw) * np.float64(L.coopref_phi_inv_u32(U1)) + np.float64(sw) * np.float64(L.coopref_phi_inv_u32(U2))
+            lo, hi = min(U1, U2), max(U1, U2)
+            passes = lo <= a1 or (lo <= a2 and hi <= b2)
+            for nn in (float(n), float(np.nextafter(n, -np.inf)), float(np.nextafter(n, np.inf))):
+                checked += 1
+                if L.coopref_phi_to_u32(nn) <= thr:
+                    kept += 1
+                    assert passes, (thr, c, U1, U2, float(n), a1, a2, b2)
+                elif not passes:
+                    rejected += 1
+    assert kept > 3000 and rejected > 3000 and checked > 60000
+
+
+def test_refined_first_filter_is_more_selective():
+    """At k/d = 10/1400 and c = 1/2 the strip + rectangle passes less than a third of what the L-shape passes."""
+    L = R.lib()
+    thr = (10 << 32) // 1400
+    cw = sw = math.cos(math.pi / 4)
+    a1, a2, b2 = first_thresholds(L, thr, cw, sw)
+    p1, p2, q = a1 / 2**32, a2 / 2**32, b2 / 2**32
+    old = 1 - (1 - p2) ** 2
+    new = (1 - (1 - p1) ** 2) + 2 * (p2 - p1) * q - (p2 - p1) ** 2
+    assert new < old / 3, (old, new)
+
+
+# --------------------------------------------------------------------------- #
+# The fp32 blend also settles most candidates the other way: safely below the threshold means kept
+# --------------------------------------------------------------------------- #
+def keep_threshold(L, thr, cw, sw):
+    """Restatement of blend_keep_threshold() in csrc/labor.hip: an fp32 estimate at or below this means the exact blend
+    keeps the edge."""
+    if thr == M32:
+        return np.float32(np.inf)           # the whole list is kept
+    if thr < 64:
+        return np.float32(-np.inf)
+    tau_lo = L.coopref_phi_inv_u32(thr - 8)
+    lim = tau_lo - 1e-6 * abs(tau_lo) - (cw + sw) * EPS2 - 1e-5
+    t = np.float32(lim)
+    return np.nextafter(t, np.float32(-np.inf)) if float(t) > lim else t
+
+
+def test_fp32_blend_below_the_keep_threshold_means_kept():
+    from scipy.special import ndtr, ndtri
+    L = R.lib()
+    rng = np.random.default_rng(4)
+    certain = band = checked = 0
+    for trial in range(400):
+        k = int(rng.integers(1, 60))
+        d = int(k + 1 + 10 ** rng.uniform(0, 5))
+        thr = (k << 32) // d
+        kappa = int(rng.integers(2, 300))
+        i = int(rng.integers(1, kappa))
+        c = i / kappa
+        cw, sw = math.cos(c * 1.5707963267948966), math.sin(c * 1.5707963267948966)
+        Tk, T2 = keep_threshold(L, thr, cw, sw), second_threshold(L, thr, cw, sw)
+        assert Tk < T2
+        tau = float(ndtri((thr + 0.5) / 2**32))
+        for _ in range(60):
+            n1 = float(rng.normal()) - (2.0 if rng.random() < 0.5 else 0.0)
+            n2 = (tau - cw * n1) / sw + float(rng.normal()) * 10 ** rng.uniform(-6, -1) * (1 if rng.random() < 0.7 else -3)
+            U1 = int(min(M32, max(0, ndtr(n1) * 2**32)))
+            U2 = int(min(M32, max(0, ndtr(n2) * 2**32)))
+            n = np.float64(cw) * np.float64(L.coopref_phi_inv_u32(U1)) + np.float64(sw) * np.float64(L.coopref_phi_inv_u32(U2))
+            n_hat = np.float32(np.float32(cw) * approx_phi_inv_f32(U1)) + np.float32(np.float32(sw) * approx_phi_inv_f32(U2))
+            checked += 1
+            if n_hat <= Tk:
+                certain += 1
+                for nn in (float(n), float(np.nextafter(n, -np.inf)), float(np.nextafter(n, np.inf))):
+                    assert L.coopref_phi_to_u32(nn) <= thr, (thr, c, U1, U2, float(n), float(n_hat), float(Tk))
+            elif n_hat <= T2:
+                band += 1
+    assert certain > 3000 and band > 300 and checked > 20000
+    # the band that still needs the exact blend is narrow: at k/d = 10/1400, c = 1/2, a few percent of the kept edges
+    thr = (10 << 32) // 1400
+    cw = sw = math.cos(math.pi / 4)
+    lo, hi = float(keep_threshold(L, thr, cw, sw)), float(second_threshold(L, thr, cw, sw))
+    assert (ndtr(hi) - ndtr(lo)) / ndtr(lo) < 0.06

@@ -480,3 +480,18 @@ def test_limits_of_the_interface(P, tiny):
     with pytest.raises(P.CoopError) as e:
         P.coop_sample(tiny.graph, torch.from_numpy(seeds).cuda(), (1,) * 256, P.COOP_LABOR0)
     assert e.value.code == -4
+
+
+def test_blend_candidate_buffer_overflow_is_redone(P, tiny, medium):
+    """A candidate buffer far too small for the exact stage of a dependent batch: the pass is repeated with more room
+    until it fits, and the bytes do not change."""
+    try:
+        P.coop_tune(P.COOP_TUNE_BLEND_CANDIDATES, 64)
+        seeds = synth.seed_batches(medium.n, 3000, seed=51)(0).numpy()
+        compare(P, medium, seeds, (10, 10, 10), R.LABOR0, it=5, kappa=16, seed=31)
+        P.coop_tune(P.COOP_TUNE_PIECE_LEN, 256)
+        compare(P, medium, seeds[:500], (25, 10), R.LABOR0, it=21, kappa=4, seed=32)
+        compare(P, tiny, synth.seed_batches(tiny.n, 600, seed=52)(0).numpy(), (7, 3, 5, 2), R.LABOR0, it=9, kappa=8, seed=33)
+    finally:
+        P.coop_tune(P.COOP_TUNE_BLEND_CANDIDATES, 0)
+        P.coop_tune(P.COOP_TUNE_PIECE_LEN, 4096)
