@@ -676,7 +676,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
   }
   if constexpr (kQueued) {
     blend_flush_first<NF>(bst, lbw, keys, stage_cap, out, ctl);
-    return;  // (the exact stage, a kernel of its own, keeps the counters by atomics)
+    return;  // (the counters were kept by atomics, here and in the exact stage)
   }
   if (has && g.split == 0) {
 #pragma unroll
@@ -920,7 +920,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
                   piece_len, pieces, piece_cap, cx.d_piece_count + l, out);
       // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
       int lpw = g_lists_per_wave;
-      if (lpw == 0) lpw = n_new >= 65536 ? (cx.blend && cx.vec4 ? 8 : 4) : 1;  // blended: fuller waves at the exact stage
+      if (lpw == 0) lpw = n_new >= 65536 ? (cx.blend && cx.vec4 ? 8 : 4) : 1;  // blended: fuller waves at the fp32 stage
       const int64_t n_waves = (n_new + lpw - 1) / lpw;
       // the piece waves come first in the grid: one round of resident blocks, fewer if there cannot be that many pieces
       constexpr int64_t kPieceBlocks = 2048;
