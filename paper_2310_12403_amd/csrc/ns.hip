@@ -1,10 +1,21 @@
 // NS layers (App. A.1.1): a destination of degree d <= k keeps all of N(s); otherwise it keeps the k neighbours with
 // the smallest (R_ts, list position), a uniform k-subset.  Kept edges leave in (destination order, adjacency order).
 // The count is known without looking at the list (min(k, d)), so every list is read once, by the fill pass.
+#include "blend_filters.h"
 #include "device_utils.h"
 #include "sample_internal.h"
 
 namespace coop {
+
+// Filters between a blended NS variate and its exact evaluation, for the candidate test R <= bound (c > 0 only).
+struct NsBlendThr {
+  uint32_t a2, a1, b2;  // integer bounds on min(U1, U2) and max(U1, U2), as for LABOR-0
+  float lim2;           // the blend in fp32 above this cannot be a candidate
+};
+__device__ __forceinline__ NsBlendThr ns_blend_thresholds(uint32_t bound, double cw, double sw) {
+  const PreThr p = blend_first_thresholds(bound, cw, sw);
+  return NsBlendThr{p.a2, p.a1, p.b2, blend_second_threshold(bound, cw + sw)};
+}
 
 // One destination's neighbour list as the fill pass sees it (written by the count pass, so that the fill pass
 // reaches the list with one dependent load instead of three).
@@ -18,7 +29,8 @@ struct NsRecord {
 
 __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
                                                      const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k, uint32_t target,
-                                                     int32_t* __restrict__ cnt, NsRecord* __restrict__ rec, Ctl* ctl) {
+                                                     int32_t* __restrict__ cnt, NsRecord* __restrict__ rec,
+                                                     NsBlendThr* __restrict__ bthr /* null when c = 0 */, double cw, double sw, Ctl* ctl) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_dst) return;
   const int32_t s = dst[i];
@@ -26,6 +38,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__
     atomicOr(&ctl->err_range, 1);
     cnt[i] = 0;
     rec[i] = NsRecord{0, 0u, 0, 0u, 0u};
+    if (bthr) bthr[i] = NsBlendThr{0u, 0u, 0u, 0.0f};
     return;
   }
   const int64_t beg = g_indptr[s];
@@ -36,6 +49,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__
   uint64_t bound = d > 0 ? ((uint64_t)target << 32) / (uint64_t)d : 0xFFFFFFFFull;
   if (bound > 0xFFFFFFFFull) bound = 0xFFFFFFFFull;  // d <= target: every neighbour is a candidate
   rec[i] = NsRecord{beg, (uint32_t)d, s, (uint32_t)bound, 0u};
+  if (bthr) bthr[i] = d > (int64_t)k ? ns_blend_thresholds((uint32_t)bound, cw, sw) : NsBlendThr{0u, 0u, 0u, 0.0f};
 }
 
 constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list can be subsampled
@@ -43,15 +57,26 @@ constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer li
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int kNsGroups = 4;  // 16-byte groups per lane and step of the fast traversal
 
+// Stage-1 passers of the blended path wait here (per wave, in LDS) until 64 of them can be evaluated together.
+constexpr int kNsQueueCap = 2 * kWave;
+struct NsQueue {
+  int32_t t[kNsQueueCap];
+  uint32_t j[kNsQueueCap];
+  uint32_t u1[kNsQueueCap];
+  uint32_t u2[kNsQueueCap];
+};
+
 // One pass over the list [beg, beg + d): every neighbour whose variate is <= bound is appended to the candidate
-// arrays (variate, list position) in LDS, in no particular order; returns how many qualified (entries beyond `cap`
-// are counted but not stored).  Long lists in a 16-byte aligned array are read as aligned groups of four entries,
-// kNsGroups groups per lane and step, whole groups in the main loop and the ragged ends in one extra step.
+// arrays (variate, list position, vertex) in LDS, in no particular order; returns how many qualified (entries beyond
+// `cap` are counted but not stored).  Long lists in a 16-byte aligned array are read as aligned groups of four
+// entries, kNsGroups groups per lane and step, whole groups in the main loop and the ragged ends in one extra step.
+// With c > 0 the variate of an entry is evaluated exactly only if the integer bounds and then the fp32 blend cannot
+// rule it out; the survivors of the integer bounds are evaluated 64 at a time.
 template <bool BLEND, bool VEC4>
 __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t bound,
-                                               const VariateParams& vp, uint32_t sigma_a, uint32_t sigma_b,
+                                               const NsBlendThr& bt, const VariateParams& vp, uint32_t sigma_a, uint32_t sigma_b,
                                                uint32_t* __restrict__ cand_r, uint32_t* __restrict__ cand_j,
-                                               int32_t* __restrict__ cand_t, uint32_t cap) {
+                                               int32_t* __restrict__ cand_t, uint32_t cap, NsQueue* __restrict__ q) {
   const uint32_t lane = (uint32_t)lane_id();
   uint32_t n_c = 0;
   auto append = [&](bool in, uint32_t r, uint32_t j, int32_t t) {
@@ -61,69 +86,119 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
     if (in && p < cap) { cand_r[p] = r; cand_j[p] = j; cand_t[p] = t; }
     n_c += (uint32_t)__popcll(mask);
   };
+  // ---- blended path: queue, and evaluation of its first n entries --------------------------------------------------
+  uint32_t qn = 0;
+  const float cwf = (float)vp.cw, swf = (float)vp.sw;
+  auto evaluate = [&](uint32_t n) {
+    int32_t t = 0;
+    uint32_t j = 0, R = 0;
+    bool in = false;
+    if (lane < n) {
+      t = q->t[lane];
+      j = q->j[lane];
+      const uint32_t u1 = q->u1[lane], u2 = q->u2[lane];
+      if (__builtin_fmaf(cwf, approx_phi_inv_f32(u1), swf * approx_phi_inv_f32(u2)) <= bt.lim2) {
+        R = kit_phi_to_u32(__builtin_fma(vp.cw, kit_phi_inv_u32(u1), vp.sw * kit_phi_inv_u32(u2)));
+        in = R <= bound;
+      }
+    }
+    append(in, R, j, t);
+  };
+  auto enqueue = [&](bool pre, int32_t t, uint32_t j, uint32_t u1, uint32_t u2) {
+    const uint64_t mask = ballot64(pre);
+    if (mask == 0) return;
+    if (pre) {
+      const uint32_t at = qn + lanes_below(mask);  // below 128
+      q->t[at] = t; q->j[at] = j; q->u1[at] = u1; q->u2[at] = u2;
+    }
+    qn += (uint32_t)__popcll(mask);
+    __builtin_amdgcn_wave_barrier();
+    if (qn >= (uint32_t)kWave) {
+      evaluate(kWave);
+      const uint32_t rest = qn - kWave;  // fewer than 64: to the front
+      int32_t mt = 0;
+      uint32_t mj = 0, m1 = 0, m2 = 0;
+      if (lane < rest) { mt = q->t[kWave + lane]; mj = q->j[kWave + lane]; m1 = q->u1[kWave + lane]; m2 = q->u2[kWave + lane]; }
+      __builtin_amdgcn_wave_barrier();
+      if (lane < rest) { q->t[lane] = mt; q->j[lane] = mj; q->u1[lane] = m1; q->u2[lane] = m2; }
+      qn = rest;
+      __builtin_amdgcn_wave_barrier();
+    }
+  };
+  // first look at one entry: its variate (c = 0) or the integer bounds on its two uniforms (c > 0)
+  auto first_look = [&](bool valid, int32_t t, uint32_t& r, uint32_t& u2) -> bool {
+    r = keyed_uniform<true>(vp.K.Ka, (uint32_t)t, sigma_a);
+    if constexpr (!BLEND) {
+      return valid & (r <= bound);
+    } else {
+      u2 = keyed_uniform<true>(vp.K.Kb, (uint32_t)t, sigma_b);
+      const uint32_t lo = r < u2 ? r : u2, hi = r < u2 ? u2 : r;
+      return valid & ((lo <= bt.a1) | ((lo <= bt.a2) & (hi <= bt.b2)));
+    }
+  };
+  auto take = [&](bool flag, int32_t t, uint32_t j, uint32_t r, uint32_t u2) {
+    if constexpr (!BLEND) append(flag, r, j, t);
+    else enqueue(flag, t, j, r, u2);
+  };
+
   if (!VEC4 || d <= (uint32_t)kWave) {
     for (uint32_t base = 0; base < d; base += kWave) {
       const uint32_t j = base + lane;
-      uint32_t r = 0;
       int32_t t = 0;
-      bool in = false;
-      if (j < d) {
-        t = g_indices[beg + j];
-        r = variate<true, BLEND>(vp, (uint32_t)t, sigma_a, sigma_b);
-        in = r <= bound;
-      }
-      append(in, r, j, t);
+      if (j < d) t = g_indices[beg + j];
+      uint32_t r = 0, u2 = 0;
+      const bool flag = first_look(j < d, t, r, u2);
+      take(flag, t, j, r, u2);
     }
-    return n_c;
+  } else {
+    constexpr uint32_t kStep = kWave * 4 * kNsGroups;
+    const int64_t abeg = beg & ~(int64_t)3;        // first aligned group
+    const uint32_t head = (uint32_t)(beg - abeg);  // entries of that group that precede the list
+    const uint32_t total = head + d;               // list end, relative to abeg
+    const uint32_t vec_end = total & ~3u;          // whole groups end here
+    const uint32_t vec_beg = head ? 4u : 0u;       // whole groups start here
+    const int32_t* __restrict__ p = g_indices + abeg;
+    for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
+      i32x4 buf[kNsGroups];
+      bool ok[kNsGroups];
+#pragma unroll
+      for (int gq = 0; gq < kNsGroups; ++gq) {
+        const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
+        ok[gq] = r < vec_end;
+        buf[gq] = i32x4{0, 0, 0, 0};
+        if (ok[gq]) buf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+      }
+#pragma unroll
+      for (int gq = 0; gq < kNsGroups; ++gq) {
+        if (base + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the rest of this step lies behind the list
+        const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
+        uint32_t R[4], U2[4];
+        bool flag[4];
+        bool any = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          flag[e] = first_look(ok[gq], buf[gq][e], R[e], U2[e]);
+          any |= flag[e];
+        }
+        if (ballot64(any) != 0) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) take(flag[e], buf[gq][e], r + e - head, R[e], U2[e]);
+        }
+      }
+    }
+    {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
+      const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
+      const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
+      int32_t t = 0;
+      if (valid) t = p[pos];
+      uint32_t r = 0, u2 = 0;
+      const bool flag = first_look(valid, t, r, u2);
+      take(flag, t, pos - head, r, u2);
+    }
   }
-  constexpr uint32_t kStep = kWave * 4 * kNsGroups;
-  const int64_t abeg = beg & ~(int64_t)3;        // first aligned group
-  const uint32_t head = (uint32_t)(beg - abeg);  // entries of that group that precede the list
-  const uint32_t total = head + d;               // list end, relative to abeg
-  const uint32_t vec_end = total & ~3u;          // whole groups end here
-  const uint32_t vec_beg = head ? 4u : 0u;       // whole groups start here
-  const int32_t* __restrict__ p = g_indices + abeg;
-  for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
-    i32x4 buf[kNsGroups];
-    bool ok[kNsGroups];
-#pragma unroll
-    for (int gq = 0; gq < kNsGroups; ++gq) {
-      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
-      ok[gq] = r < vec_end;
-      buf[gq] = i32x4{0, 0, 0, 0};
-      if (ok[gq]) buf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
-    }
-#pragma unroll
-    for (int gq = 0; gq < kNsGroups; ++gq) {
-      if (base + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the rest of this step lies behind the list
-      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
-      uint32_t R[4];
-      bool in[4];
-      bool any = false;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        R[e] = variate<true, BLEND>(vp, (uint32_t)buf[gq][e], sigma_a, sigma_b);
-        in[e] = ok[gq] & (R[e] <= bound);
-        any |= in[e];
-      }
-      if (ballot64(any) != 0) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) append(in[e], R[e], r + e - head, buf[gq][e]);
-      }
-    }
-  }
-  {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
-    const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
-    const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
-    uint32_t r = 0;
-    int32_t t = 0;
-    bool in = false;
-    if (valid) {
-      t = p[pos];
-      r = variate<true, BLEND>(vp, (uint32_t)t, sigma_a, sigma_b);
-      in = r <= bound;
-    }
-    append(in, r, pos - head, t);
+  if constexpr (BLEND) {
+    if (qn != 0) evaluate(qn);
+    __builtin_amdgcn_wave_barrier();
   }
   return n_c;
 }
@@ -136,11 +211,13 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
 //   4. every kept candidate's place is the number of kept candidates in front of it in the list.
 template <bool BLEND, bool VEC4>
 __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ g_indices,
-                                                    const NsRecord* __restrict__ rec, int64_t n_dst, uint32_t k,
+                                                    const NsRecord* __restrict__ rec, const NsBlendThr* __restrict__ bthr,
+                                                    int64_t n_dst, uint32_t k,
                                                     uint32_t cap, int waves_per_block, VariateParams vp,
                                                     const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
                                                     int64_t* __restrict__ eid, Ctl* ctl) {
   extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
+  __shared__ NsQueue queues[BLEND ? kWavesPerBlock : 1];
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
   const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
@@ -172,9 +249,11 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
 
   uint64_t lo = 0, hi = 0xFFFFFFFFull;  // bisection bracket on the bound, used only after a failed pass
   uint64_t bound = g.bound;
+  NsBlendThr bt{0u, 0u, 0u, 0.0f};
+  if constexpr (BLEND) bt = bthr[w];
   uint32_t n_c = 0;
   for (int attempt = 0; attempt < 40; ++attempt) {
-    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap);
+    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, bt, vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap, &queues[BLEND ? wib : 0]);
     if (n_c >= k && n_c <= cap) break;
     // cannot be bracketed (more than cap - k equal variates): report instead of guessing
     if (n_c < k) {
@@ -187,6 +266,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
     if (lo > hi) { n_c = 0; break; }
     // too few and no upper failure yet: double the bound (a midpoint of the whole range would flood the buffer)
     bound = (hi == 0xFFFFFFFFull && n_c < k) ? (2 * bound + 1 < hi ? 2 * bound + 1 : hi) : lo + (hi - lo) / 2;
+    if constexpr (BLEND) bt = ns_blend_thresholds((uint32_t)bound, vp.cw, vp.sw);  // (every lane computes the same)
     __builtin_amdgcn_wave_barrier();
   }
   if (n_c < k || n_c > cap) {
@@ -256,6 +336,7 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   blk->indptr = alloc.get<int64_t>(n_dst + 1, COOP_TAG_OUTPUT);
   int32_t* cnt = alloc.get<int32_t>(n_dst, COOP_TAG_SCRATCH);
   NsRecord* rec = alloc.get<NsRecord>(n_dst, COOP_TAG_SCRATCH);
+  NsBlendThr* bthr = cx.blend ? alloc.get<NsBlendThr>(n_dst, COOP_TAG_SCRATCH) : nullptr;
   void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
   if (alloc.failed) return COOP_E_NOMEM;
   // candidate buffer: cap >= 4k (power of two, at least 256).  A fanout above kNsMaxSelect is served only while no
@@ -271,7 +352,7 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   if (target > 2 * k_sel + 16) target = 2 * k_sel + 16;
   if (n_dst > 0)
     COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices, dst, n_dst,
-                k, target, cnt, rec, cx.d_ctl);
+                k, target, cnt, rec, bthr, cx.cw, cx.sw, cx.d_ctl);
   const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
   scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
   int rc = wait_ctl(pub, cx.h_ctl, s);
@@ -287,7 +368,7 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
     while (wpb > 1 && (size_t)wpb * cap * 16 > 65536) wpb >>= 1;
     const size_t shmem = (size_t)wpb * cap * 16;
     const dim3 grid(blocks_for(n_dst, wpb));
-#define COOP_NS_ARGS cx.g->indices, rec, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl
+#define COOP_NS_ARGS cx.g->indices, rec, bthr, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl
     if (cx.blend) {
       if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
       else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);

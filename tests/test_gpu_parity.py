@@ -495,3 +495,15 @@ def test_blend_candidate_buffer_overflow_is_redone(P, tiny, medium):
     finally:
         P.coop_tune(P.COOP_TUNE_BLEND_CANDIDATES, 0)
         P.coop_tune(P.COOP_TUNE_PIECE_LEN, 4096)
+
+
+def test_ns_dependent_batches_go_through_the_filters(P, tiny, medium):
+    """NS with c > 0: candidates reach the exact blend through the integer bounds and the fp32 blend; hubs, short lists,
+    fanouts on both sides of the candidate target, a failing first bound (fanout close to the degrees)."""
+    seeds = synth.seed_batches(medium.n, 1500, seed=61)(0).numpy()
+    hubs = np.argsort(-np.diff(medium.indptr_h))[:200].astype(np.int32)
+    for it, kappa in ((5, 16), (255, 256), (3, 2)):
+        compare(P, medium, seeds, (10, 10), R.NS, it=it, kappa=kappa, seed=41)
+        compare(P, medium, hubs, (25, 3), R.NS, it=it, kappa=kappa, seed=42)
+    compare(P, medium, hubs[:40], (1000, 2), R.NS, it=9, kappa=4, seed=43)      # fanout close to the degrees
+    compare(P, tiny, synth.seed_batches(tiny.n, 400, seed=62)(0).numpy(), (1, 40, 7), R.NS, it=7, kappa=8, seed=44)
