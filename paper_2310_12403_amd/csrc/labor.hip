@@ -196,16 +196,26 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
   const int32_t* __restrict__ p = g_indices + abeg;
   const uint32_t lane = (uint32_t)lane_id();
 
+  // the loads of the next step are issued before this step's entries are hashed
+  i32x4 nbuf[kScanGroups];
+  auto fetch = [&](uint32_t at) {
+#pragma unroll
+    for (int gq = 0; gq < kScanGroups; ++gq) {
+      const uint32_t r = at + (uint32_t)(gq * kWave * 4) + lane * 4;
+      nbuf[gq] = i32x4{0, 0, 0, 0};
+      if (r < vec_end) nbuf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+    }
+  };
+  if (vec_beg < vec_end) fetch(vec_beg);
   for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
     i32x4 buf[kScanGroups];
     bool ok[kScanGroups];
 #pragma unroll
     for (int gq = 0; gq < kScanGroups; ++gq) {
-      const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
-      ok[gq] = r < vec_end;
-      buf[gq] = i32x4{0, 0, 0, 0};
-      if (ok[gq]) buf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+      buf[gq] = nbuf[gq];
+      ok[gq] = base + (uint32_t)(gq * kWave * 4) + lane * 4 < vec_end;
     }
+    if (base + kStep < vec_end) fetch(base + kStep);
 #pragma unroll
     for (int gq = 0; gq < kScanGroups; ++gq) {
       const uint32_t r0 = base + (uint32_t)(gq * kWave * 4);  // wave-uniform

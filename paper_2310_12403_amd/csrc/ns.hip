@@ -158,16 +158,28 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
     const uint32_t vec_end = total & ~3u;          // whole groups end here
     const uint32_t vec_beg = head ? 4u : 0u;       // whole groups start here
     const int32_t* __restrict__ p = g_indices + abeg;
+    // the loads of the next step are issued before this step's entries are hashed
+    i32x4 nbuf[kNsGroups];
+    auto fetch = [&](uint32_t at) {
+#pragma unroll
+      for (int gq = 0; gq < kNsGroups; ++gq) {
+        const uint32_t r = at + (uint32_t)(gq * kWave * 4) + lane * 4;
+        nbuf[gq] = i32x4{0, 0, 0, 0};
+        if (r < vec_end) nbuf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+      }
+    };
+    // (not with c > 0: the blended path needs the registers more than the overlap)
+    if (!BLEND && vec_beg < vec_end) fetch(vec_beg);
     for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
+      if (BLEND) fetch(base);
       i32x4 buf[kNsGroups];
       bool ok[kNsGroups];
 #pragma unroll
       for (int gq = 0; gq < kNsGroups; ++gq) {
-        const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
-        ok[gq] = r < vec_end;
-        buf[gq] = i32x4{0, 0, 0, 0};
-        if (ok[gq]) buf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+        buf[gq] = nbuf[gq];
+        ok[gq] = base + (uint32_t)(gq * kWave * 4) + lane * 4 < vec_end;
       }
+      if (!BLEND && base + kStep < vec_end) fetch(base + kStep);
 #pragma unroll
       for (int gq = 0; gq < kNsGroups; ++gq) {
         if (base + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the rest of this step lies behind the list
