@@ -99,7 +99,7 @@ def main():
     def step(i, out):
         arena.reset()
         blocks = sample(i)
-        P.coop_gather(feat, blocks[-1].src_ids, out=out[:blocks[-1].n_src])
+        P.coop_gather(feat, blocks[-1].src_ids, out=out)        # writes the first n_src rows of the preallocated buffer
         return blocks
 
     # output buffer sized once from a dry run (allocation stays outside the timed region)

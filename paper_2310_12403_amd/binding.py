@@ -275,7 +275,8 @@ def coop_gather(feat, ids, out=None, stream=None):
     n, dim = feat.shape
     if out is None:
         out = torch.empty((ids.numel(), dim), dtype=feat.dtype, device=ids.device)
-    assert out.is_contiguous() and out.dtype == feat.dtype and tuple(out.shape) == (ids.numel(), dim)
+    # `out` may have more rows than there are ids (a buffer sized once and reused): the first ids.numel() rows are written
+    assert out.is_contiguous() and out.dtype == feat.dtype and out.dim() == 2 and out.shape[1] == dim and out.shape[0] >= ids.numel()
     rc = lib().coop_gather(C.c_void_p(feat.data_ptr()), n, dim, _DTYPES[feat.dtype], _dev_ptr(ids, torch.int32), ids.numel(),
                            C.c_void_p(out.data_ptr()), _stream_ptr(stream))
     _check(rc)
