@@ -120,7 +120,9 @@ typedef struct {
  *   seeds      device int32 [n_seeds], distinct, in range (else COOP_E_DUPSEED / COOP_E_RANGE)
  *   fanouts    host int32 [L], each >= 1; NS needs fanout <= 1024 wherever a degree exceeds it (else COOP_E_CAPACITY)
  *   blocks_out host coop_block [L], filled on success
- * Waits on `stream` twice per layer (the per-layer sizes are read back to size the outputs); when it returns all
+ * Waits on `stream` once per layer, for |E^l| and |S^{l+1}| together (the edge arrays are obtained from the allocator
+ * with room for a bound on |E^l|, so they may be a little longer than n_edges entries; a layer whose bound falls
+ * short is redone with a second wait); when it returns all
  * sizes in blocks_out are final, while the kernels that fill the last layer's col_local / src_ids may still be running
  * on `stream`: work queued on the same stream sees complete blocks, anything else must synchronise the stream first.
  * On error blocks_out is zeroed; buffers already obtained from the allocator stay with the caller.
@@ -254,6 +256,10 @@ const char* coop_strerror(int code);
 #define COOP_TUNE_BLEND_CANDIDATES 5 /* first size (entries) of the buffer that holds the candidates of the exact blend of a
                                       LABOR-0 pass with c > 0; a pass that overflows it is redone with 8 times the size;
                                       0 (default): k / 2 entries per destination and layer plus 65536 */
+#define COOP_TUNE_DEFER_SIZES 6    /* 1 (default): a layer's edge arrays are sized from a bound on |E^l| and the exact size
+                                      is read back together with |S^{l+1}|; 0: |E^l| is read back first and the arrays have
+                                      exactly that size; 2: as 1 with a bound that falls short, so that every layer is redone
+                                      (exercises the fallback) */
 int coop_tune(int knob, int64_t value);
 
 /* out[i] = in[i] for a device id list (a plain streaming copy on `stream`: 4n bytes read, 4n written).  Besides its

@@ -383,6 +383,7 @@ COOP_TUNE_LISTS_PER_WAVE = 2
 COOP_TUNE_FUSE_LAYERS = 3
 COOP_TUNE_PIECE_LEN = 4
 COOP_TUNE_BLEND_CANDIDATES = 5
+COOP_TUNE_DEFER_SIZES = 6
 
 
 def coop_tune(knob, value):

@@ -96,8 +96,9 @@ void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* 
                         const Publish* pub = nullptr);
 // bit flags packed 64 per word -> uint32 exclusive ranks (out has n entries) and the total in *total_out (device)
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
+// (n_bits_dev, device, optional: only bits [0, *n_bits_dev) count; n_words is then an upper bound known to the host)
 void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s,
-                      const Publish* pub = nullptr);
+                      const Publish* pub = nullptr, const int64_t* n_bits_dev = nullptr);
 
 void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
 
@@ -124,10 +125,23 @@ int launch_publish(const Publish& pub, hipStream_t s);
 int wait_ctl(const Publish& pub, Ctl* h_ctl, hipStream_t s);
 int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
 
-// Dedup + relabel of one layer (Eq. 2).  Inputs: dst[n_dst] (distinct), col_global[m].  Outputs: col_local[m],
-// and *src_out = freshly allocated src_ids[n_src].  Reads sizes back (synchronises the stream).
-int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, int32_t* col_local,
-                   int32_t** src_out, int64_t* n_src_out, Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
+// Dedup + relabel of one layer (Eq. 2), in two halves around the size read-back.
+//   front: inserts [dst ; col_global] into a hash table, finds every edge's first occurrence and counts the new
+//          vertices; ends by reading the control block back (synchronises the stream).  `m` is the number of edges, or,
+//          when m_dev is given, an upper bound of it known to the host (the exact number is then *m_dev, on the device,
+//          and comes back in the control block's total_edges together with everything else: one read-back serves the
+//          sampler and the dedup).
+//   back:  with the exact m: allocates src_ids[n_src] and writes it and col_local[m].
+struct UniqueWork {
+  uint32_t* first = nullptr;
+  uint64_t* bits = nullptr;
+  uint32_t* word_rank = nullptr;
+  int64_t n_new = 0;
+};
+int unique_front(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w, Alloc& alloc,
+                 Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
+int unique_back(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const UniqueWork& w, int32_t* col_local,
+                int32_t** src_out, int64_t* n_src_out, Alloc& alloc, hipStream_t s);
 
 }  // namespace coop
 

@@ -677,9 +677,10 @@ __global__ void k_labor_redo(Ctl* ctl, uint32_t* piece_count, uint32_t* cand_cou
 
 // staged rows -> the block's edge arrays: kFillLanes threads per destination, each taking every kFillLanes-th slot
 constexpr int kFillLanesLog2 = 3;
+// (edge_limit: entries of col_global / eid; nothing is written beyond them)
 __global__ __launch_bounds__(kBlock) void k_labor_fill_staged(LayerChunks ch, int64_t n_dst, uint32_t stage_cap,
                                                               const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
-                                                              int64_t* __restrict__ eid) {
+                                                              int64_t* __restrict__ eid, int64_t edge_limit) {
   __shared__ uint32_t row_j[kBlock >> kFillLanesLog2][kWave];  // list positions of one staged row per lane group
   const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int64_t w = idx >> kFillLanesLog2;
@@ -695,8 +696,10 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_staged(LayerChunks ch, in
   if (g.split == 0) {
     for (int64_t slot = sub; slot < c; slot += 1 << kFillLanesLog2) {
       const StageEntry e = row[slot];
-      col_global[o + slot] = e.t;
-      eid[o + slot] = g.beg + e.j;
+      if (o + slot < edge_limit) {
+        col_global[o + slot] = e.t;
+        eid[o + slot] = g.beg + e.j;
+      }
     }
     return;
   }
@@ -721,8 +724,10 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_staged(LayerChunks ch, in
     if (slot >= c) break;
     int64_t place = 0;
     for (int q = 0; q < (int)c; ++q) place += js[q] < mine[i].j;
-    col_global[o + place] = mine[i].t;
-    eid[o + place] = g.beg + mine[i].j;
+    if (o + place < edge_limit) {
+      col_global[o + place] = mine[i].t;
+      eid[o + place] = g.beg + mine[i].j;
+    }
   }
 }
 
@@ -758,7 +763,8 @@ static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices
   }
 }
 
-int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk) {
+int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk, int64_t edge_cap) {
+  const bool defer = edge_cap > 0;
   hipStream_t s = cx.s;
   Alloc& alloc = *cx.alloc;
   if (l == 0) {
@@ -892,6 +898,10 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       }
     }
 
+    if (defer) {  // the count stays on the device; an overflow of the candidate buffer is the caller's to notice
+      scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, nullptr);
+      break;
+    }
     const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
     scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
     const int rc = wait_ctl(pub, cx.h_ctl, s);
@@ -902,17 +912,17 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     cand_cap = cand_cap * 8 < ((int64_t)1 << 30) ? cand_cap * 8 : ((int64_t)1 << 30);
     hipLaunchKernelGGL(k_labor_redo, dim3(1), dim3(kCandSub), 0, s, cx.d_ctl, cx.d_piece_count + l, cand_count);
   }
-  const int64_t m = cx.h_ctl->total_edges;
-  blk->n_edges = m;
+  const int64_t m = defer ? edge_cap : cx.h_ctl->total_edges;  // entries of the edge arrays
+  blk->n_edges = defer ? -1 : m;
   blk->col_global = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   blk->eid = alloc.get<int64_t>(m, COOP_TAG_OUTPUT);
   blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
 
-  if (m > 0) {
+  if (m > 0 && n_dst > 0) {
     COOP_LAUNCH(K_LABOR_FILL, k_labor_fill_staged, dim3(blocks_for(n_dst << kFillLanesLog2, kBlock)), dim3(kBlock), 0, s, ch, n_dst, cap,
-                blk->indptr, blk->col_global, blk->eid);
-    if (cx.h_ctl->n_overflow > 0) {
+                blk->indptr, blk->col_global, blk->eid, m);
+    if (!defer && cx.h_ctl->n_overflow > 0) {
       LayerKeys K{};
       layer_keys(cx.seed, COOP_LABOR0, l, cx.group, K.Ka);
       layer_keys(cx.seed, COOP_LABOR0, l, cx.group + 1, K.Kb);

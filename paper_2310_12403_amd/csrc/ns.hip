@@ -227,7 +227,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
                                                     int64_t n_dst, uint32_t k,
                                                     uint32_t cap, int waves_per_block, VariateParams vp,
                                                     const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
-                                                    int64_t* __restrict__ eid, Ctl* ctl) {
+                                                    int64_t* __restrict__ eid, int64_t edge_limit, Ctl* ctl) {
   extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
   __shared__ NsQueue queues[BLEND ? kWavesPerBlock : 1];
   const int wib = uniform_wave_in_block();
@@ -236,6 +236,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
   if (w >= n_dst) return;
   const uint32_t lane = (uint32_t)lane_id();
   const int64_t o = eptr[w];
+  if (eptr[w + 1] > edge_limit) return;  // the wave writes [o, eptr[w + 1]) only; no room: the caller redoes the layer
   const NsRecord g = rec[w];
   const int32_t s = g.s;
   const int64_t beg = g.beg;
@@ -336,7 +337,8 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
   }
 }
 
-int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk) {
+int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk, int64_t edge_cap) {
+  const bool defer = edge_cap > 0;
   hipStream_t s = cx.s;
   Alloc& alloc = *cx.alloc;
   const uint32_t k = (uint32_t)cx.fanouts[l];
@@ -365,22 +367,26 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   if (n_dst > 0)
     COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices, dst, n_dst,
                 k, target, cnt, rec, bthr, cx.cw, cx.sw, cx.d_ctl);
-  const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
-  scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
-  int rc = wait_ctl(pub, cx.h_ctl, s);
-  if (rc != COOP_OK) return rc;
-  const int64_t m = cx.h_ctl->total_edges;
-  blk->n_edges = m;
+  if (defer) {
+    scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, nullptr);  // the count stays on the device
+  } else {
+    const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
+    scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
+    const int rc = wait_ctl(pub, cx.h_ctl, s);
+    if (rc != COOP_OK) return rc;
+  }
+  const int64_t m = defer ? edge_cap : cx.h_ctl->total_edges;  // entries of the edge arrays
+  blk->n_edges = defer ? -1 : m;
   blk->col_global = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   blk->eid = alloc.get<int64_t>(m, COOP_TAG_OUTPUT);
   blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
-  if (m > 0) {
+  if (m > 0 && n_dst > 0) {
     int wpb = kWavesPerBlock;
     while (wpb > 1 && (size_t)wpb * cap * 16 > 65536) wpb >>= 1;
     const size_t shmem = (size_t)wpb * cap * 16;
     const dim3 grid(blocks_for(n_dst, wpb));
-#define COOP_NS_ARGS cx.g->indices, rec, bthr, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, cx.d_ctl
+#define COOP_NS_ARGS cx.g->indices, rec, bthr, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, m, cx.d_ctl
     if (cx.blend) {
       if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
       else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);

@@ -149,7 +149,11 @@ struct LoadBit {
 };
 struct LoadPopc {  // element i = number of set bits of word i
   const uint64_t* bits;
-  __device__ __forceinline__ int64_t operator()(int64_t i) const { return __popcll(bits[i]); }
+  const int64_t* n_bits;  // when not null: only the words that hold bits [0, *n_bits) count (a size that the host does not know yet)
+  __device__ __forceinline__ int64_t operator()(int64_t i) const {
+    if (n_bits != nullptr && i >= ((*n_bits + 63) >> 6)) return 0;
+    return __popcll(bits[i]);
+  }
 };
 
 template <typename Load, typename Out>
@@ -284,8 +288,8 @@ void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* t
 }
 
 void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s,
-                      const Publish* pub) {
-  scan_impl<LoadPopc, uint32_t>(LoadPopc{bits}, n_words, out, (uint32_t*)nullptr, total_out, tmp, s, pub);
+                      const Publish* pub, const int64_t* n_bits_dev) {
+  scan_impl<LoadPopc, uint32_t>(LoadPopc{bits, n_bits_dev}, n_words, out, (uint32_t*)nullptr, total_out, tmp, s, pub);
 }
 
 // ---- CSR validation -------------------------------------------------------------------------------------------

@@ -176,19 +176,20 @@ __global__ __launch_bounds__(kBlock) void k_rw_walk(const int64_t* __restrict__ 
 // staged rows -> the block's edge arrays; eid carries the visit count (these are edges of sum_i A^i, not of the graph)
 __global__ __launch_bounds__(kBlock) void k_rw_fill(const StageEntry* __restrict__ rows, uint32_t k_eff, int64_t n_dst,
                                                     const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
-                                                    int64_t* __restrict__ eid) {
+                                                    int64_t* __restrict__ eid, int64_t edge_limit) {
   const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int64_t w = idx / k_eff;
   if (w >= n_dst) return;
   const int64_t slot = idx - w * k_eff;
   const int64_t o = eptr[w];
-  if (slot >= eptr[w + 1] - o) return;
+  if (slot >= eptr[w + 1] - o || o + slot >= edge_limit) return;
   const StageEntry e = rows[idx];
   col_global[o + slot] = e.t;
   eid[o + slot] = (int64_t)e.j;
 }
 
-int rw_layer(const SampleCtx& cx, const RwConfig& rw, int l, const int32_t* dst, int64_t n_dst, coop_block* blk) {
+int rw_layer(const SampleCtx& cx, const RwConfig& rw, int l, const int32_t* dst, int64_t n_dst, coop_block* blk, int64_t edge_cap) {
+  const bool defer = edge_cap > 0;
   hipStream_t s = cx.s;
   Alloc& alloc = *cx.alloc;
   RwParams rp{};
@@ -216,19 +217,23 @@ int rw_layer(const SampleCtx& cx, const RwConfig& rw, int l, const int32_t* dst,
                   cx.g->indices, cx.g->n_vertices, dst, n_dst, rp, wpb, rows, cnt, cx.d_ctl);
     }
   }
-  const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
-  scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
-  int rc = wait_ctl(pub, cx.h_ctl, s);
-  if (rc != COOP_OK) return rc;
-  const int64_t m = cx.h_ctl->total_edges;
-  blk->n_edges = m;
+  if (defer) {
+    scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, nullptr);  // the count stays on the device
+  } else {
+    const Publish pub = begin_publish(cx.d_ctl, cx.h_ctl);  // the scan's last thread also sends the sizes to the host
+    scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
+    const int rc = wait_ctl(pub, cx.h_ctl, s);
+    if (rc != COOP_OK) return rc;
+  }
+  const int64_t m = defer ? edge_cap : cx.h_ctl->total_edges;  // entries of the edge arrays
+  blk->n_edges = defer ? -1 : m;
   blk->col_global = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   blk->eid = alloc.get<int64_t>(m, COOP_TAG_OUTPUT);
   blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
-  if (m > 0)
+  if (m > 0 && n_dst > 0)
     COOP_LAUNCH(K_RW_FILL, k_rw_fill, dim3(blocks_for(n_dst * (int64_t)rp.k_eff, kBlock)), dim3(kBlock), 0, s, rows, rp.k_eff, n_dst,
-                blk->indptr, blk->col_global, blk->eid);
+                blk->indptr, blk->col_global, blk->eid, m);
   return COOP_OK;
 }
 

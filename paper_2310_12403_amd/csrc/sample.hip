@@ -67,6 +67,13 @@ int g_lists_per_wave = 0;      // COOP_TUNE_LISTS_PER_WAVE (0 = automatic)
 int g_fuse_layers = 1;         // COOP_TUNE_FUSE_LAYERS
 int g_piece_len = 4096;        // COOP_TUNE_PIECE_LEN
 int64_t g_blend_candidates = 0;  // COOP_TUNE_BLEND_CANDIDATES (0 = automatic)
+int g_defer_sizes = 1;         // COOP_TUNE_DEFER_SIZES
+
+// puts back what a LABOR-0 pass at layer l changed in the control data, before the pass is run again
+__global__ void k_reset_layer(Ctl* ctl, uint32_t* piece_count) {
+  ctl->cand_overflow = 0;
+  *piece_count = 0;
+}
 
 }  // namespace coop
 
@@ -93,6 +100,10 @@ extern "C" int coop_tune(int knob, int64_t value) {
     case COOP_TUNE_BLEND_CANDIDATES:
       if (value < 0 || value > ((int64_t)1 << 30)) return COOP_E_ARG;
       g_blend_candidates = value;
+      return COOP_OK;
+    case COOP_TUNE_DEFER_SIZES:
+      if (value < 0 || value > 2) return COOP_E_ARG;
+      g_defer_sizes = (int)value;
       return COOP_OK;
     default:
       return COOP_E_ARG;
@@ -143,6 +154,7 @@ static int sample_layers(const coop_graph* g, const int32_t* seeds, int64_t n_se
     COOP_LAUNCH(K_COPY_IDS, k_copy_i32, dim3(blocks_for(n_seeds, kBlock)), dim3(kBlock), 0, s, seeds, seed_copy, n_seeds);
 
   LaborState labor;
+  bool defer_ok = true;
   const int32_t* dst = seed_copy;
   int64_t n_dst = n_seeds;
   int rc = COOP_OK;
@@ -150,16 +162,57 @@ static int sample_layers(const coop_graph* g, const int32_t* seeds, int64_t n_se
     coop_block blk{};
     blk.n_dst = n_dst;
     blk.dst_ids = const_cast<int32_t*>(dst);
-    rc = sampler == COOP_LABOR0 ? labor_layer(labor, cx, l, dst, n_dst, &blk)
-         : sampler == COOP_NS   ? ns_layer(cx, l, dst, n_dst, &blk)
-                                : rw_layer(cx, *rw, l, dst, n_dst, &blk);
-    if (rc != COOP_OK) break;
-    if (n_dst + blk.n_edges >= ((int64_t)1 << 32) - 1) { rc = COOP_E_CAPACITY; break; }
+    // Edge arrays sized from a bound on m_l instead of m_l itself: the layer then needs one read-back (after the
+    // dedup's scan, which brings m_l along) instead of two.  NS and random walks keep at most k per destination; LABOR-0
+    // keeps sum min(d, k) in expectation with a variance below k per destination, so 8 standard deviations of room
+    // all but never fall short, and when they do (or a staging row or the candidate buffer overflows) the layer is
+    // redone the slow way.
+    const int64_t k_l = sampler == COOP_RW ? (fanouts[l] < rw->walk_length * rw->n_walks ? fanouts[l] : rw->walk_length * rw->n_walks)
+                                           : fanouts[l];
+    int64_t edge_cap = 0;
+    if (g_defer_sizes != 0 && defer_ok && n_dst > 0 && k_l * n_dst <= ((int64_t)1 << 28)) {
+      edge_cap = k_l * n_dst;
+      if (sampler == COOP_LABOR0) edge_cap += 8 * (int64_t)sqrt((double)edge_cap) + 4096;
+      if (g_defer_sizes == 2) edge_cap = edge_cap / 2 + 1;  // (test knob) a bound that falls short
+      if (n_dst + edge_cap >= ((int64_t)1 << 32) - 1) edge_cap = 0;
+    }
+    const LaborState labor_before = labor;
+    auto sample_layer = [&](int64_t cap) {
+      return sampler == COOP_LABOR0 ? labor_layer(labor, cx, l, dst, n_dst, &blk, cap)
+             : sampler == COOP_NS   ? ns_layer(cx, l, dst, n_dst, &blk, cap)
+                                    : rw_layer(cx, *rw, l, dst, n_dst, &blk, cap);
+    };
+    UniqueWork uw{};
+    bool done = false;
+    if (edge_cap > 0) {
+      rc = sample_layer(edge_cap);
+      if (rc != COOP_OK) break;
+      rc = unique_front(dst, n_dst, blk.col_global, edge_cap, &cx.d_ctl->total_edges, &uw, alloc, cx.d_ctl, h_ctl, s);
+      if (rc != COOP_OK) break;
+      if (h_ctl->n_overflow > 0) defer_ok = false;  // the counter is never reset: the overflow pass runs from here on
+      if (h_ctl->total_edges <= edge_cap && h_ctl->n_overflow == 0 && h_ctl->cand_overflow == 0) {
+        blk.n_edges = h_ctl->total_edges;
+        done = true;
+      } else {
+        labor = labor_before;
+        hipLaunchKernelGGL(k_reset_layer, dim3(1), dim3(1), 0, s, cx.d_ctl, cx.d_piece_count + l);
+        blk = coop_block{};
+        blk.n_dst = n_dst;
+        blk.dst_ids = const_cast<int32_t*>(dst);
+      }
+    }
+    if (!done) {
+      rc = sample_layer(0);
+      if (rc != COOP_OK) break;
+      if (n_dst + blk.n_edges >= ((int64_t)1 << 32) - 1) { rc = COOP_E_CAPACITY; break; }
+      rc = unique_front(dst, n_dst, blk.col_global, blk.n_edges, nullptr, &uw, alloc, cx.d_ctl, h_ctl, s);
+      if (rc != COOP_OK) break;
+    }
 
     // S^{l+1} and local ids (Eq. 2)
     int32_t* src = nullptr;
     int64_t n_src = 0;
-    rc = unique_relabel(dst, n_dst, blk.col_global, blk.n_edges, blk.col_local, &src, &n_src, alloc, cx.d_ctl, h_ctl, s);
+    rc = unique_back(dst, n_dst, blk.col_global, blk.n_edges, uw, blk.col_local, &src, &n_src, alloc, s);
     if (rc != COOP_OK) break;
     blk.src_ids = src;
     blk.n_src = n_src;

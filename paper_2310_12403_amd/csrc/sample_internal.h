@@ -61,10 +61,14 @@ struct RwConfig {
 };
 
 // Each fills blk->indptr, n_edges, col_global, eid and allocates col_local for layer l over dst[0..n_dst).
-// Synchronises the stream once (the edge count is read back).
-int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);
-int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);
-int rw_layer(const SampleCtx& cx, const RwConfig& rw, int l, const int32_t* dst, int64_t n_dst, coop_block* blk);
+// With edge_cap == 0 the edge count is read back (the stream is synchronised once) and the arrays have its size.
+// With edge_cap > 0 nothing is read back: the arrays get edge_cap entries, the fill writes no edge beyond them, the
+// exact count stays on the device (control block, total_edges) and blk->n_edges is left at -1; the caller learns the
+// count with its next read-back and must redo the layer with edge_cap == 0 if the count exceeds edge_cap, if LABOR-0
+// reports a staging-row or candidate-buffer overflow, or whenever it prefers to.
+int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk, int64_t edge_cap);
+int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk, int64_t edge_cap);
+int rw_layer(const SampleCtx& cx, const RwConfig& rw, int l, const int32_t* dst, int64_t n_dst, coop_block* blk, int64_t edge_cap);
 
 // tuning knobs (coop_tune)
 extern int g_stage_cap_override;
@@ -72,6 +76,7 @@ extern int g_lists_per_wave;
 extern int g_fuse_layers;
 extern int g_piece_len;
 extern int64_t g_blend_candidates;
+extern int g_defer_sizes;
 
 static inline unsigned blocks_for(int64_t n, int64_t per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 

@@ -20,10 +20,12 @@ __device__ __forceinline__ uint64_t slot_of_key(uint32_t key, uint64_t cap) {
   return ((uint64_t)h * cap) >> 32;
 }
 
+// (m_dev, optional: the exact number of edges, on the device; m is then the capacity of col)
 __global__ __launch_bounds__(kBlock) void k_uniq_insert(const int32_t* __restrict__ dst, int64_t n_dst,
-                                                        const int32_t* __restrict__ col, int64_t m,
+                                                        const int32_t* __restrict__ col, int64_t m, const int64_t* __restrict__ m_dev,
                                                         unsigned long long* __restrict__ table, uint64_t cap, Ctl* ctl) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (m_dev != nullptr && *m_dev < m) m = *m_dev;
   if (i >= n_dst + m) return;
   const uint32_t key = (uint32_t)(i < n_dst ? dst[i] : col[i - n_dst]);
   const unsigned long long mine = ((unsigned long long)key << 32) | (uint32_t)i;
@@ -58,10 +60,11 @@ __device__ __forceinline__ uint32_t first_position(const unsigned long long* __r
 }
 
 // first[e] = first position of col[e] in [S^l ; col]; bit e of `bits` = that position is this very edge
-__global__ __launch_bounds__(kBlock) void k_uniq_flag(const int32_t* __restrict__ col, int64_t m, int64_t n_dst,
-                                                      const unsigned long long* __restrict__ table, uint64_t cap,
+__global__ __launch_bounds__(kBlock) void k_uniq_flag(const int32_t* __restrict__ col, int64_t m, const int64_t* __restrict__ m_dev,
+                                                      int64_t n_dst, const unsigned long long* __restrict__ table, uint64_t cap,
                                                       uint32_t* __restrict__ first, uint64_t* __restrict__ bits) {
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (m_dev != nullptr && *m_dev < m) m = *m_dev;
   bool is_new = false;
   if (e < m) {
     const uint32_t f = first_position(table, cap, (uint32_t)col[e]);
@@ -93,45 +96,48 @@ __global__ __launch_bounds__(kBlock) void k_uniq_relabel(const int32_t* __restri
 
 static inline unsigned nblocks(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
 
-int unique_relabel(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, int32_t* col_local,
-                   int32_t** src_out, int64_t* n_src_out, Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
+int unique_front(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w, Alloc& alloc,
+                 Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
   const int64_t n_all = n_dst + m;
   // at most half full; an even number of slots (the clear uses 16-byte stores)
   int64_t cap = 2 * n_all + 1024;
 
   unsigned long long* table = alloc.get<unsigned long long>(cap, COOP_TAG_SCRATCH);
-  uint32_t* first = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
+  w->first = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
   const int64_t n_words = (m + 63) / 64;
-  uint32_t* word_rank = alloc.get<uint32_t>(n_words, COOP_TAG_SCRATCH);
-  uint64_t* bits = alloc.get<uint64_t>(n_words, COOP_TAG_SCRATCH);
+  w->word_rank = alloc.get<uint32_t>(n_words, COOP_TAG_SCRATCH);
+  w->bits = alloc.get<uint64_t>(n_words, COOP_TAG_SCRATCH);
   void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_words), COOP_TAG_SCRATCH);
   if (alloc.failed) return COOP_E_NOMEM;
 
-  int64_t n_new = 0;
   if (n_all > 0) {
     fill_u64((uint64_t*)table, cap, kEmptySlot, s);
-    COOP_LAUNCH(K_UNIQ_INSERT, k_uniq_insert, dim3(nblocks(n_all)), dim3(kBlock), 0, s, dst, n_dst, col_global, m, table,
+    COOP_LAUNCH(K_UNIQ_INSERT, k_uniq_insert, dim3(nblocks(n_all)), dim3(kBlock), 0, s, dst, n_dst, col_global, m, m_dev, table,
                 (uint64_t)cap, d_ctl);
   }
   if (m > 0) {
-    COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, n_dst, table, (uint64_t)cap, first,
-                bits);
+    COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, m_dev, n_dst, table, (uint64_t)cap,
+                w->first, w->bits);
   }
   // sizes (and the duplicate / range flags) back to the host, sent by the scan's last thread when there is a scan
   const Publish pub = begin_publish(d_ctl, h_ctl);
-  if (m > 0) scan_popc_to_u32(bits, n_words, word_rank, &d_ctl->total_new, scan_tmp, s, &pub);
+  if (m > 0) scan_popc_to_u32(w->bits, n_words, w->word_rank, &d_ctl->total_new, scan_tmp, s, &pub, m_dev);
   else if (launch_publish(pub, s) != COOP_OK) return COOP_E_HIP;
   const int rc = wait_ctl(pub, h_ctl, s);
   if (rc != COOP_OK) return rc;
-  if (m > 0) n_new = h_ctl->total_new;
+  w->n_new = m > 0 ? h_ctl->total_new : 0;
+  return COOP_OK;
+}
 
-  const int64_t n_src = n_dst + n_new;
+int unique_back(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const UniqueWork& w, int32_t* col_local,
+                int32_t** src_out, int64_t* n_src_out, Alloc& alloc, hipStream_t s) {
+  const int64_t n_src = n_dst + w.n_new;
   int32_t* src = alloc.get<int32_t>(n_src, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
   const int64_t n_threads = m > n_dst ? m : n_dst;
   if (n_threads > 0)
-    COOP_LAUNCH(K_UNIQ_RELABEL, k_uniq_relabel, dim3(nblocks(n_threads)), dim3(kBlock), 0, s, dst, col_global, m, n_dst, first, bits,
-                word_rank, src, col_local);
+    COOP_LAUNCH(K_UNIQ_RELABEL, k_uniq_relabel, dim3(nblocks(n_threads)), dim3(kBlock), 0, s, dst, col_global, m, n_dst, w.first, w.bits,
+                w.word_rank, src, col_local);
   *src_out = src;
   *n_src_out = n_src;
   return COOP_OK;

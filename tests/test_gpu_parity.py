@@ -507,3 +507,34 @@ def test_ns_dependent_batches_go_through_the_filters(P, tiny, medium):
         compare(P, medium, hubs, (25, 3), R.NS, it=it, kappa=kappa, seed=42)
     compare(P, medium, hubs[:40], (1000, 2), R.NS, it=9, kappa=4, seed=43)      # fanout close to the degrees
     compare(P, tiny, synth.seed_batches(tiny.n, 400, seed=62)(0).numpy(), (1, 40, 7), R.NS, it=7, kappa=8, seed=44)
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_edge_count_read_back_modes(P, tiny, medium, mode):
+    """The edge arrays sized from the exact count (0), from a bound with the count read back later (1), and from a
+    bound that falls short so that every layer is run again the slow way (2): the same bytes, for all three samplers,
+    with staging-row and candidate-buffer overflows in the mix."""
+    try:
+        P.coop_tune(P.COOP_TUNE_DEFER_SIZES, mode)
+        seeds = synth.seed_batches(medium.n, 3000, seed=71)(0).numpy()
+        small = synth.seed_batches(tiny.n, 500, seed=72)(0).numpy()
+        for sampler in (R.NS, R.LABOR0):
+            compare(P, medium, seeds, (10, 10, 10), sampler, it=3, kappa=1, seed=61)
+            compare(P, medium, seeds[:700], (25, 10), sampler, it=5, kappa=16, seed=62)
+            compare(P, tiny, small, (5000, 3), sampler, it=1, seed=63)             # every neighbour, then a small fanout
+            compare(P, tiny, small[:0], (10, 10), sampler, seed=64)                # empty batch
+            compare(P, tiny, small[:1], (3, 3, 3, 3, 3), sampler, it=9, kappa=4, seed=65)
+        compare_rw(P, medium, seeds[:1500], (10, 5), 3, 50, 0.5, it=2, seed=66)
+        compare_rw(P, tiny, small, (4, 40), 2, 9, 0.1, it=2, seed=67)
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 4)                                      # rows overflow: LABOR-0 leaves the fast mode
+        compare(P, medium, seeds[:900], (10, 10, 10), R.LABOR0, it=4, kappa=1, seed=68)
+        compare(P, tiny, small, (10, 10), R.LABOR0, it=6, kappa=8, seed=69)
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 0)
+        P.coop_tune(P.COOP_TUNE_BLEND_CANDIDATES, 64)                              # the exact stage's buffer overflows
+        compare(P, medium, seeds, (10, 10, 10), R.LABOR0, it=5, kappa=16, seed=70)
+        arena = P.Arena(1 << 28)                                                   # bump allocator: abandoned buffers stay
+        compare(P, medium, seeds, (10, 10, 10), R.LABOR0, it=7, kappa=1, seed=71, arena=arena)
+    finally:
+        P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 0)
+        P.coop_tune(P.COOP_TUNE_BLEND_CANDIDATES, 0)
