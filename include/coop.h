@@ -260,6 +260,11 @@ const char* coop_strerror(int code);
                                       is read back together with |S^{l+1}|; 0: |E^l| is read back first and the arrays have
                                       exactly that size; 2: as 1 with a bound that falls short, so that every layer is redone
                                       (exercises the fallback) */
+#define COOP_TUNE_UNIQUE 7         /* how the frontier is deduplicated.  0 (default): lists of 262,144 entries or more (S^l and
+                                      the sampled edges together) by partition into buckets that are deduplicated in LDS,
+                                      shorter ones through a hash table in HBM; 1: always the table in HBM; 2: by partition
+                                      whatever the length; 3: as 2 with buckets 16 times too large, so that buckets overflow
+                                      and the call falls back to the table (exercises the fallback) */
 int coop_tune(int knob, int64_t value);
 
 /* out[i] = in[i] for a device id list (a plain streaming copy on `stream`: 4n bytes read, 4n written).  Besides its

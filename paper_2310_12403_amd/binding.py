@@ -384,6 +384,7 @@ COOP_TUNE_FUSE_LAYERS = 3
 COOP_TUNE_PIECE_LEN = 4
 COOP_TUNE_BLEND_CANDIDATES = 5
 COOP_TUNE_DEFER_SIZES = 6
+COOP_TUNE_UNIQUE = 7
 
 
 def coop_tune(knob, value):

@@ -24,6 +24,9 @@ enum KernelId {
   K_UNIQ_INSERT,     // hash table insert (atomic CAS / min)
   K_UNIQ_FLAG,       // first-occurrence lookup
   K_UNIQ_RELABEL,    // new-id compaction + col_local
+  K_PART_COUNT,      // dedup by partition: bucket sizes per block
+  K_PART_SCATTER,    // dedup by partition: (key, position) pairs to their buckets
+  K_PART_FIRST,      // dedup by partition: first positions through a table in LDS, one bucket per block
   K_COPY_IDS,        // seed copy / src_ids prefix copy
   K_GATHER,          // feature row gather
   K_GATHER_MEAN,     // neighbour mean fused with the feature load
@@ -63,7 +66,7 @@ struct Ctl {
   int32_t err_capacity;  // NS candidate buffer could not be sized
   int32_t n_overflow;    // LABOR-0 destinations whose staging row overflowed (this layer and earlier)
   int32_t cand_overflow; // blended LABOR-0: the candidate buffer of the exact stage was too small (the pass is redone)
-  int32_t pad;
+  int32_t uniq_overflow; // dedup by partition: a bucket held more distinct vertices than its table (redone with the table in HBM)
 };
 
 // Landing pad of the control block in mapped pinned host memory (see read_ctl).
@@ -94,6 +97,8 @@ struct ChunkedI32 {
 };
 void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* total_out, void* tmp, hipStream_t s,
                         const Publish* pub = nullptr);
+// exclusive scan of n uint32 (sum below 2^32); out has n + 1 entries, the last one the total
+void scan_u32_to_u32(const uint32_t* in, int64_t n, uint32_t* out, void* tmp, hipStream_t s);
 // bit flags packed 64 per word -> uint32 exclusive ranks (out has n entries) and the total in *total_out (device)
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
 // (n_bits_dev, device, optional: only bits [0, *n_bits_dev) count; n_words is then an upper bound known to the host)
@@ -132,6 +137,7 @@ int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
 //          and comes back in the control block's total_edges together with everything else: one read-back serves the
 //          sampler and the dedup).
 //   back:  with the exact m: allocates src_ids[n_src] and writes it and col_local[m].
+extern int g_unique_mode;  // COOP_TUNE_UNIQUE
 struct UniqueWork {
   uint32_t* first = nullptr;
   uint64_t* bits = nullptr;

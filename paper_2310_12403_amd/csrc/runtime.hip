@@ -24,7 +24,7 @@ struct Prof {
 
 const char* const kKernelNames[K_COUNT_] = {
     "fill", "labor_scan", "labor_fill", "labor_fill_overflow", "labor_exact", "segments", "ns_count", "ns_fill", "rw_walk", "rw_fill", "scan_local", "scan_offset",
-    "unique_insert", "unique_flag", "unique_relabel", "copy_ids", "gather", "gather_mean", "validate_csr",
+    "unique_insert", "unique_flag", "unique_relabel", "unique_part_count", "unique_part_scatter", "unique_part_first", "copy_ids", "gather", "gather_mean", "validate_csr",
     "cache_lookup", "cache_select_hist", "cache_select_pick", "cache_evict", "cache_miss_rows", "cache_hit_rows"};
 
 hipEvent_t take_event() {
@@ -142,6 +142,10 @@ struct LoadChunks {
       if (q < c.n_chunks && i >= c.start[q]) p = q;
     return c.ptr[p][i - c.start[p]];
   }
+};
+struct LoadU32 {
+  const uint32_t* in;
+  __device__ __forceinline__ int64_t operator()(int64_t i) const { return in[i]; }
 };
 struct LoadBit {
   const uint64_t* bits;
@@ -281,6 +285,10 @@ void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* 
     return;
   }
   scan_impl<LoadChunks, int64_t>(LoadChunks{in}, n, out, out + n, total_out, tmp, s, pub);
+}
+
+void scan_u32_to_u32(const uint32_t* in, int64_t n, uint32_t* out, void* tmp, hipStream_t s) {
+  scan_impl<LoadU32, uint32_t>(LoadU32{in}, n, out, out + n, nullptr, tmp, s, nullptr);
 }
 
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {

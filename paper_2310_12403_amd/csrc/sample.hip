@@ -19,7 +19,7 @@ __global__ void k_clear_ctl(Ctl* ctl, uint32_t* piece_count, int L) {
 
 // The control block travels to the host by a one-thread kernel that stores it into mapped pinned memory and then a
 // ticket; the host polls the ticket.  That is a few microseconds quicker per read-back than an asynchronous copy
-// followed by a stream synchronisation, and a sampling call has two read-backs per layer.  The wait is bounded: after
+// followed by a stream synchronisation, and a sampling call has one or two read-backs per layer.  The wait is bounded: after
 // a while the host falls back to synchronising the stream.
 __global__ void k_publish_ctl(const Ctl* __restrict__ d_ctl, HostCtl* h, uint64_t ticket) {
   h->ctl = *d_ctl;
@@ -100,6 +100,10 @@ extern "C" int coop_tune(int knob, int64_t value) {
     case COOP_TUNE_BLEND_CANDIDATES:
       if (value < 0 || value > ((int64_t)1 << 30)) return COOP_E_ARG;
       g_blend_candidates = value;
+      return COOP_OK;
+    case COOP_TUNE_UNIQUE:
+      if (value < 0 || value > 3) return COOP_E_ARG;
+      g_unique_mode = (int)value;
       return COOP_OK;
     case COOP_TUNE_DEFER_SIZES:
       if (value < 0 || value > 2) return COOP_E_ARG;

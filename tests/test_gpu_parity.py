@@ -538,3 +538,34 @@ def test_edge_count_read_back_modes(P, tiny, medium, mode):
         P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
         P.coop_tune(P.COOP_TUNE_STAGE_CAP, 0)
         P.coop_tune(P.COOP_TUNE_BLEND_CANDIDATES, 0)
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_frontier_dedup_modes(P, tiny, medium, mode):
+    """S^{l+1} and the local ids through the hash table in HBM (1), through the partition into buckets with tables in
+    LDS (2), and through buckets so large that their tables overflow and the call falls back (3): the same bytes,
+    including the seed-list checks, with both ways of reading the edge count back."""
+    try:
+        P.coop_tune(P.COOP_TUNE_UNIQUE, mode)
+        seeds = synth.seed_batches(medium.n, 6000, seed=81)(0).numpy()
+        small = synth.seed_batches(tiny.n, 500, seed=82)(0).numpy()
+        for defer in (1, 0):
+            P.coop_tune(P.COOP_TUNE_DEFER_SIZES, defer)
+            P.profile_reset()
+            P.profile_enable(True)
+            compare(P, medium, seeds, (10, 10, 10), R.LABOR0, it=3, seed=81)       # last layer: several buckets, most vertices
+            P.profile_enable(False)
+            ran = P.profile_read_all()
+            assert ("unique_part_first" in ran) == (mode != 1) and ("unique_insert" in ran) == (mode != 2), ran.keys()
+            compare(P, medium, seeds[:2500], (25, 10), R.NS, it=4, seed=82)
+            compare(P, tiny, small, (5, 5, 5), R.LABOR0, it=5, kappa=4, seed=83)   # a bucket or two
+            compare(P, tiny, small[:1], (2, 2), R.NS, seed=84)
+            compare(P, tiny, small[:0], (3,), R.NS, seed=85)
+            compare_rw(P, medium, seeds[:1500], (10, 5), 3, 50, 0.5, it=2, seed=86)
+        for bad, code in (([1, 2, 1], -3), (list(range(300)) + [299], -3), ([5, 1 << 20], -2)):
+            with pytest.raises(P.CoopError) as e:
+                P.coop_sample(tiny.graph, torch.tensor(bad, dtype=torch.int32).cuda(), (3, 3), R.LABOR0)
+            assert e.value.code == code
+    finally:
+        P.coop_tune(P.COOP_TUNE_UNIQUE, 0)
+        P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
