@@ -87,6 +87,10 @@ def test_papers100m_shaped_full_batch(P):
     # dependent batches around group boundaries and at the last iteration of a 512-iteration run
     for it, kappa in ((15, 16), (16, 16), (17, 16), (255, 256), (256, 256), (257, 256), (511, 16), (511, 256)):
         compare(P, g, ip, ix, get(it)[:96].contiguous(), (10, 10), R.LABOR0, it=it, kappa=kappa, seed=0)
+    # four times the batch: the last layer's frontier has some twenty million entries, thousands of dedup buckets
+    big = synth.seed_batches(n, 65536, seed=1, device="cuda")(0)
+    got = compare(P, g, ip, ix, big, (10, 10, 10), R.LABOR0, it=3, kappa=1, seed=0)
+    assert got[2].n_dst + got[2].n_edges > 16_000_000
     # random walks at full scale (a smaller batch: the oracle walks 300 steps per destination)
     seeds = get(10)[:2048].contiguous()
     got = P.coop_sample_rw(g, seeds, (10, 10), 3, 100, 0.5, it=10, seed=0, arena=arena)
