@@ -106,10 +106,11 @@ constexpr int kPartBlock = 1024;        // threads of a counting / scattering bl
 constexpr int kPartMaxBlocks = 512;     // blocks of those two kernels (two per compute unit)
 constexpr int kPartPairs = 4096;        // mean pairs of a bucket
 constexpr uint32_t kPartMaxBuckets = 8192;  // counters of a block in LDS: 32 KB
-constexpr int kFirstBlock = 512;        // threads of a bucket's block
+constexpr int kFirstBlock = 1024;       // threads of a bucket's block
 constexpr uint32_t kPartSlots = 8192;   // slots of a bucket's table in LDS (64 KB): at most half full when every pair of a
                                         // mean bucket is distinct, a quarter or less with the usual share of repeats
 constexpr uint32_t kPartFull = kPartSlots / 4 * 3;  // distinct keys at which a bucket gives up
+static_assert(kPartFull + 1 + kFirstBlock < kPartSlots, "a probe must always reach an empty slot");
 
 __device__ __forceinline__ uint32_t hash_of_key(uint32_t key) { return (uint32_t)(((uint64_t)key * 0x9E3779B97F4A7C15ull) >> 32); }
 __device__ __forceinline__ uint32_t bucket_of_hash(uint32_t h, uint32_t n_buckets) { return (uint32_t)(((uint64_t)h * n_buckets) >> 32); }
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(kFirstBlock) void k_part_first(const unsigned long 
   for (uint32_t i = threadIdx.x; i < kPartSlots; i += kFirstBlock) table[i] = kEmptySlot;
   if (threadIdx.x == 0) { n_claimed = 0; full = 0; }
   __syncthreads();
-  constexpr int U = 8;  // pairs per thread and round, loaded together
+  constexpr int U = 4;  // pairs per thread and round, loaded together
   for (uint32_t base = lo; base < hi; base += U * kFirstBlock) {
     if (*(volatile uint32_t*)&full) break;
     unsigned long long mine[U];
