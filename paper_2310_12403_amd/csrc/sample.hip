@@ -174,7 +174,8 @@ static int sample_layers(const coop_graph* g, const int32_t* seeds, int64_t n_se
     const int64_t k_l = sampler == COOP_RW ? (fanouts[l] < rw->walk_length * rw->n_walks ? fanouts[l] : rw->walk_length * rw->n_walks)
                                            : fanouts[l];
     int64_t edge_cap = 0;
-    if (g_defer_sizes != 0 && defer_ok && n_dst > 0 && k_l * n_dst <= ((int64_t)1 << 28)) {
+    // (only for the small fanouts of GNN training: with a large one the bound can exceed the count many times over)
+    if (g_defer_sizes != 0 && defer_ok && n_dst > 0 && k_l <= 64 && k_l * n_dst <= ((int64_t)1 << 28)) {
       edge_cap = k_l * n_dst;
       if (sampler == COOP_LABOR0) edge_cap += 8 * (int64_t)sqrt((double)edge_cap) + 4096;
       if (g_defer_sizes == 2) edge_cap = edge_cap / 2 + 1;  // (test knob) a bound that falls short

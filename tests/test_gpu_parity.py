@@ -523,6 +523,7 @@ def test_edge_count_read_back_modes(P, tiny, medium, mode):
             compare(P, medium, seeds[:700], (25, 10), sampler, it=5, kappa=16, seed=62)
             compare(P, tiny, small, (5000, 3), sampler, it=1, seed=63)             # every neighbour, then a small fanout
             compare(P, tiny, small[:0], (10, 10), sampler, seed=64)                # empty batch
+            compare(P, tiny, small[:200], (64, 65), sampler, it=2, seed=60)        # the largest fanout with a bound, the first without
             compare(P, tiny, small[:1], (3, 3, 3, 3, 3), sampler, it=9, kappa=4, seed=65)
         compare_rw(P, medium, seeds[:1500], (10, 5), 3, 50, 0.5, it=2, seed=66)
         compare_rw(P, tiny, small, (4, 40), 2, 9, 0.1, it=2, seed=67)
