@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
                                                      const int32_t* __restrict__ dst, int64_t n, int nf,
                                                      uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, Segment* __restrict__ seg,
                                                      uint32_t* __restrict__ thr, PreThr* __restrict__ pthr, float* __restrict__ lim2,
-                                                     double cw, double sw, int queued, Ctl* ctl,
+                                                     double cw, double sw, int queued, int fast_rows, Ctl* ctl,
                                                      uint32_t piece_len, Piece* __restrict__ pieces, uint32_t piece_cap,
                                                      uint32_t* __restrict__ piece_count, ScanOut out) {
   __shared__ uint32_t s_wave_at[kSegBlock / kWave];
@@ -84,7 +84,9 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
         }
         if (queued) out.cnt[f][i] = 0;  // kept edges are counted by atomics
       }
-    if (queued) g.split = 2;  // the row is filled in no particular order: the fill pass ranks it
+    // the row is filled in no particular order (blended passes; the fast scan of lists longer than a wave step): the
+    // fill pass ranks it
+    if (queued || (fast_rows && sampled && g.d > (uint32_t)kWave)) g.split = 2;
   }
   if (piece_len == 0) {  // wave-uniform
     if (live) seg[i] = g;
@@ -167,13 +169,36 @@ struct KeptRegs {
     if (lane == (count & 63u)) { ent_t = t; ent_j = j; }
     ++count;
   }
-  // writes the entries to `row` in adjacency order if there are at most min(cap, 64) of them
-  __device__ __forceinline__ void flush(uint32_t lane, StageEntry* __restrict__ row, uint32_t cap) const {
-    if (count <= cap && count <= (uint32_t)kWave) {
-      uint32_t rank = 0;  // an entry's place is the number of kept entries in front of it in the list
-      for (uint32_t q = 0; q < count; ++q) rank += (uint32_t)(__builtin_amdgcn_readlane(ent_j, (int)q) < ent_j);
-      if (lane < count) row[rank] = StageEntry{ent_t, (uint32_t)ent_j};
+};
+
+// Where the fast scan puts the kept entries of a list.  take(l, mm, f, t, j): in this wave step the lanes of mask mm
+// (f = this lane is one of them) keep entry t at list position j for layer l.
+//
+// RegSink parks them in registers, one entry per lane (for the pieces of a cut list: a piece learns its place in the
+// destination's staging row only when it knows how many entries it keeps).
+template <int NF>
+struct RegSink {
+  KeptRegs kept[NF];
+  __device__ __forceinline__ void take(int l, uint64_t mm, bool, int32_t t, int32_t j, uint32_t lane) {
+    while (mm != 0) {
+      const int src_lane = __builtin_ctzll(mm);
+      mm &= mm - 1;
+      kept[l].push(lane, __builtin_amdgcn_readlane(t, src_lane), __builtin_amdgcn_readlane(j, src_lane));
     }
+  }
+};
+// RowSink writes them straight to the destination's staging row, each lane its own entry at the next free slots
+// (running count plus the lane's rank in the mask): no loop over the entries, and no particular order in the row
+// (the fill pass ranks such rows by list position).  Entries beyond the row's capacity are counted, not stored.
+template <int NF>
+struct RowSink {
+  StageEntry* row[NF];
+  uint32_t count[NF];  // wave-uniform
+  uint32_t cap;
+  __device__ __forceinline__ void take(int l, uint64_t mm, bool f, int32_t t, int32_t j, uint32_t) {
+    const uint32_t slot = count[l] + lanes_below(mm);
+    if (f && slot < cap) row[l][slot] = StageEntry{t, (uint32_t)j};
+    count[l] += (uint32_t)__popcll(mm);
   }
 };
 
@@ -184,9 +209,9 @@ struct KeptRegs {
 // and layer the hot loop is the mixer and one compare; one ballot per group tells whether any lane kept anything for
 // any layer.  Only then are the (few) kept entries picked off per-entry ballot masks by a wave-uniform loop and
 // parked in registers, in no particular order (they are ranked when the list is done).
-template <bool BLEND, int NF>
+template <bool BLEND, int NF, typename Sink>
 __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t j0,
-                                                const uint32_t (&thr)[NF], const FusedKeys& keys, KeptRegs (&kept)[NF]) {
+                                                const uint32_t (&thr)[NF], const FusedKeys& keys, Sink& sink) {
   constexpr uint32_t kStep = kWave * 4 * kScanGroups;
   const int64_t abeg = beg & ~(int64_t)3;        // first aligned group
   const uint32_t head = (uint32_t)(beg - abeg);  // entries of that group that precede the list
@@ -195,17 +220,22 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
   const uint32_t vec_beg = head ? 4u : 0u;       // whole groups start here
   const int32_t* __restrict__ p = g_indices + abeg;
   const uint32_t lane = (uint32_t)lane_id();
+  const int32_t j_lane = (int32_t)(lane * 4 + j0) - (int32_t)head;  // list position of this lane's first entry at r0 = 0
 
-  // the loads of the next step are issued before this step's entries are hashed
+  // The loads of the next step are issued before this step's entries are hashed.  A lane whose group lies behind the
+  // list loads the last whole group instead (in bounds, and cheaper than switching lanes off); `ok` discards it.
   i32x4 nbuf[kScanGroups];
   auto fetch = [&](uint32_t at) {
 #pragma unroll
     for (int gq = 0; gq < kScanGroups; ++gq) {
-      const uint32_t r = at + (uint32_t)(gq * kWave * 4) + lane * 4;
-      nbuf[gq] = i32x4{0, 0, 0, 0};
-      if (r < vec_end) nbuf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
+      if (at + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the whole slot lies behind the list
+      uint32_t r = at + (uint32_t)(gq * kWave * 4) + lane * 4;
+      r = r < vec_end - 4 ? r : vec_end - 4;
+      nbuf[gq] = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p + r));
     }
   };
+#pragma unroll
+  for (int gq = 0; gq < kScanGroups; ++gq) nbuf[gq] = i32x4{0, 0, 0, 0};
   if (vec_beg < vec_end) fetch(vec_beg);
   for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
     i32x4 buf[kScanGroups];
@@ -235,12 +265,8 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
         for (int l = 0; l < NF; ++l) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            uint64_t mm = ballot64(f[l][e]);
-            while (mm != 0) {
-              const int src_lane = __builtin_ctzll(mm);
-              mm &= mm - 1;
-              kept[l].push(lane, __builtin_amdgcn_readlane(buf[gq][e], src_lane), (int32_t)(r0 + (uint32_t)src_lane * 4 + e - head + j0));
-            }
+            const uint64_t mm = ballot64(f[l][e]);
+            if (mm != 0) sink.take(l, mm, f[l][e], buf[gq][e], j_lane + (int32_t)(r0 + e), lane);
           }
         }
       }
@@ -254,13 +280,8 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
 #pragma unroll
     for (int l = 0; l < NF; ++l) {
       const bool fl = valid && variate<false, BLEND>(keys.K[l], keys.cw, keys.sw, (uint32_t)t, 0u, 0u) <= thr[l];
-      uint64_t mm = ballot64(fl);
-      while (mm != 0) {
-        const int src_lane = __builtin_ctzll(mm);
-        mm &= mm - 1;
-        const uint32_t src_pos = src_lane < 3 ? head + (uint32_t)src_lane : vec_end + (uint32_t)(src_lane - 3);
-        kept[l].push(lane, __builtin_amdgcn_readlane(t, src_lane), (int32_t)(src_pos - head + j0));
-      }
+      const uint64_t mm = ballot64(fl);
+      if (mm != 0) sink.take(l, mm, fl, t, (int32_t)(pos - head + j0), lane);
     }
   }
 }
@@ -534,8 +555,9 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
           blend_flush_first<NF>(bst, lb, keys, stage_cap, out, ctl);
           continue;
         }
-        KeptRegs kept[NF];
-        labor_scan_fast<BLEND, NF>(g_indices, beg + j0, len, j0, thr, keys, kept);
+        RegSink<NF> sink;
+        KeptRegs (&kept)[NF] = sink.kept;
+        labor_scan_fast<BLEND, NF>(g_indices, beg + j0, len, j0, thr, keys, sink);
 #pragma unroll
         for (int l = 0; l < NF; ++l) {
           const uint32_t c = kept[l].count;
@@ -606,13 +628,14 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
       continue;
     }
     if (VEC == 4 && !any_all && d > (uint32_t)kWave) {
-      KeptRegs kept[NF];
-      labor_scan_fast<BLEND, NF>(g_indices, beg, d, 0u, thr, keys, kept);
+      RowSink<NF> sink;
+      sink.cap = stage_cap;
 #pragma unroll
-      for (int l = 0; l < NF; ++l) {
-        kept[l].flush(lane, out.stage[l] + (size_t)(first + i) * stage_cap, stage_cap);
-        if ((int)lane == i) my_count[l] = kept[l].count;
-      }
+      for (int l = 0; l < NF; ++l) { sink.row[l] = out.stage[l] + (size_t)(first + i) * stage_cap; sink.count[l] = 0; }
+      labor_scan_fast<BLEND, NF>(g_indices, beg, d, 0u, thr, keys, sink);
+#pragma unroll
+      for (int l = 0; l < NF; ++l)
+        if ((int)lane == i) my_count[l] = sink.count[l];
     } else {
 #pragma unroll
       for (int l = 0; l < NF; ++l) {
@@ -629,7 +652,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
     blend_flush_first<NF>(bst, lbw, keys, stage_cap, out, ctl);
     return;  // (the counters were kept by atomics, here and in the exact stage)
   }
-  if (has && g.split == 0) {
+  if (has && (g.split & 1) == 0) {  // (the pieces of a cut list add their counts themselves)
 #pragma unroll
     for (int l = 0; l < NF; ++l) {
       out.cnt[l][mine] = (int32_t)my_count[l];
@@ -873,7 +896,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       }
       COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
                   dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, cx.cw, cx.sw,
-                  cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
+                  cx.blend && cx.vec4 ? 1 : 0, cx.vec4 ? 1 : 0, cx.d_ctl,
                   piece_len, pieces, piece_cap, cx.d_piece_count + l, out);
       // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
       int lpw = g_lists_per_wave;
