@@ -17,6 +17,7 @@ enum KernelId {
   K_SEGMENTS,        // LABOR-0 per-destination list records and keep thresholds
   K_NS_COUNT,        // NS count pass (min(k, d))
   K_NS_FILL,         // NS selection + fill pass
+  K_NS_SELECT,       // NS, c > 0: exact blend of the candidates + selection
   K_RW_WALK,         // random walks + visit tally + top-k
   K_RW_FILL,         // random-walk fill pass
   K_SCAN_LOCAL,      // scan: per-tile exclusive scan + tile sums

@@ -53,6 +53,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__
 }
 
 constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list can be subsampled
+constexpr uint32_t kNsRedo = 0xFFFFFFFFu;  // candidate count of a destination that the two-kernel path leaves to k_ns_fill
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int kNsGroups = 4;  // 16-byte groups per lane and step of the fast traversal
@@ -72,7 +73,9 @@ struct NsQueue {
 // entries, kNsGroups groups per lane and step, whole groups in the main loop and the ragged ends in one extra step.
 // With c > 0 the variate of an entry is evaluated exactly only if the integer bounds and then the fp32 blend cannot
 // rule it out; the survivors of the integer bounds are evaluated 64 at a time.
-template <bool BLEND, bool VEC4>
+// STAGED (with c > 0): the exact evaluation is left to a later kernel; everything that the fp32 blend cannot rule out
+// is stored as a candidate (variate 0).
+template <bool BLEND, bool VEC4, bool STAGED = false>
 __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t bound,
                                                const NsBlendThr& bt, const VariateParams& vp, uint32_t sigma_a, uint32_t sigma_b,
                                                uint32_t* __restrict__ cand_r, uint32_t* __restrict__ cand_j,
@@ -98,8 +101,12 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
       j = q->j[lane];
       const uint32_t u1 = q->u1[lane], u2 = q->u2[lane];
       if (__builtin_fmaf(cwf, approx_phi_inv_f32(u1), swf * approx_phi_inv_f32(u2)) <= bt.lim2) {
-        R = kit_phi_to_u32(__builtin_fma(vp.cw, kit_phi_inv_u32(u1), vp.sw * kit_phi_inv_u32(u2)));
-        in = R <= bound;
+        if constexpr (STAGED) {
+          in = true;
+        } else {
+          R = kit_phi_to_u32(__builtin_fma(vp.cw, kit_phi_inv_u32(u1), vp.sw * kit_phi_inv_u32(u2)));
+          in = R <= bound;
+        }
       }
     }
     append(in, R, j, t);
@@ -215,6 +222,64 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
   return n_c;
 }
 
+// The k smallest by (variate, list position) among the n_c candidates in LDS (k <= n_c <= cap), written to the edge arrays
+// from o on in adjacency order: every candidate's rank among the candidates is counted, ranks below k are kept, and a
+// kept candidate's place is the number of kept candidates in front of it in the list.
+__device__ __forceinline__ void ns_rank_write(uint32_t n_c, uint32_t k, const uint32_t* cand_r, const uint32_t* cand_j, uint32_t* cand_k,
+                                              const int32_t* cand_t, int64_t o, int64_t beg, int32_t* __restrict__ col_global,
+                                              int64_t* __restrict__ eid) {
+  const uint32_t lane = (uint32_t)lane_id();
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
+  if (n_c <= (uint32_t)kWave) {
+    // the usual case: one candidate per lane, ranked through lane reads (no LDS round trips in the loops)
+    const bool has = lane < n_c;
+    const uint32_t my_r = has ? cand_r[lane] : 0xFFFFFFFFu;
+    const uint32_t my_j = has ? cand_j[lane] : 0xFFFFFFFFu;
+    const int32_t my_t = has ? cand_t[lane] : 0;
+    const uint64_t my_key = ((uint64_t)my_r << 32) | my_j;  // order by (variate, list position)
+    uint32_t rank = 0;
+    for (uint32_t q = 0; q < n_c; ++q) {
+      const uint64_t key = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)my_r, (int)q) << 32) |
+                           (uint32_t)__builtin_amdgcn_readlane((int)my_j, (int)q);
+      rank += key < my_key;
+    }
+    const bool keep = has && rank < k;
+    const uint64_t kept = ballot64(keep);
+    uint32_t place = 0;  // kept candidates in front of this one in the list
+    uint64_t rest = kept;
+    while (rest != 0) {
+      const int q = __builtin_ctzll(rest);
+      rest &= rest - 1;
+      place += (uint32_t)__builtin_amdgcn_readlane((int)my_j, q) < my_j;
+    }
+    if (keep) {
+      col_global[o + place] = my_t;
+      eid[o + place] = beg + my_j;
+    }
+    return;
+  }
+  for (uint32_t i = lane; i < n_c; i += kWave) {
+    const uint32_t my_r = cand_r[i], my_j = cand_j[i];
+    uint32_t rank = 0;
+    for (uint32_t q = 0; q < n_c; ++q) {
+      const uint32_t r = cand_r[q];
+      rank += (r < my_r) || (r == my_r && cand_j[q] < my_j);
+    }
+    cand_k[i] = rank < k;
+  }
+  __builtin_amdgcn_wave_barrier();
+  __threadfence_block();
+  for (uint32_t i = lane; i < n_c; i += kWave) {
+    if (!cand_k[i]) continue;
+    const uint32_t my_j = cand_j[i];
+    uint32_t place = 0;
+    for (uint32_t q = 0; q < n_c; ++q) place += cand_k[q] && cand_j[q] < my_j;
+    col_global[o + place] = cand_t[i];
+    eid[o + place] = beg + my_j;
+  }
+}
+
 // Selection of the k smallest (R, j) among d > k neighbours, one wave per destination:
 //   1. one pass over the list collects, in LDS, the candidates with R <= bound, where bound is chosen so that about
 //      `target` of them are expected (target > k, target < cap);
@@ -227,13 +292,15 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
                                                     int64_t n_dst, uint32_t k,
                                                     uint32_t cap, int waves_per_block, VariateParams vp,
                                                     const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
-                                                    int64_t* __restrict__ eid, int64_t edge_limit, Ctl* ctl) {
+                                                    int64_t* __restrict__ eid, int64_t edge_limit, Ctl* ctl,
+                                                    const uint32_t* __restrict__ only /* when not null: only lists marked kNsRedo */) {
   extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
   __shared__ NsQueue queues[BLEND ? kWavesPerBlock : 1];
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
   const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
   if (w >= n_dst) return;
+  if (only != nullptr && only[w] != kNsRedo) return;
   const uint32_t lane = (uint32_t)lane_id();
   const int64_t o = eptr[w];
   if (eptr[w + 1] > edge_limit) return;  // the wave writes [o, eptr[w + 1]) only; no room: the caller redoes the layer
@@ -286,55 +353,166 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
     if (lane == 0) atomicOr(&ctl->err_capacity, 1);
     return;
   }
+  ns_rank_write(n_c, k, cand_r, cand_j, cand_k, cand_t, o, beg, col_global, eid);
+}
+
+// ---- c > 0 in two kernels ----------------------------------------------------------------------------------------
+// The exact blend (two inverse normal distribution functions and one forward, in fp64) needs four times the registers of
+// the traversal and is wanted for a few dozen candidates per list only.  So the traversal kernel stops at the fp32
+// filter and leaves what passes, (list position, vertex) pairs, in a row of row_cap entries per destination; a second
+// kernel evaluates those exactly, drops the ones above the bound and selects.  A destination whose row overflows, or
+// that ends up with fewer than k candidates (about one in 10^4), is marked and done again by k_ns_fill, which adjusts
+// the bound.
+struct NsCand { uint32_t j; int32_t t; };
+
+template <bool VEC4>
+__global__ __launch_bounds__(kBlock) void k_ns_collect(const int32_t* __restrict__ g_indices, const NsRecord* __restrict__ rec,
+                                                       const NsBlendThr* __restrict__ bthr, int64_t n_dst, uint32_t k, uint32_t cap,
+                                                       int waves_per_block, VariateParams vp, const int64_t* __restrict__ eptr,
+                                                       int32_t* __restrict__ col_global, int64_t* __restrict__ eid, int64_t edge_limit,
+                                                       Ctl* ctl, NsCand* __restrict__ rows, uint32_t row_cap, uint32_t* __restrict__ n_cand) {
+  extern __shared__ uint32_t lds_words[];
+  __shared__ NsQueue queues[kWavesPerBlock];
+  const int wib = uniform_wave_in_block();
+  if (wib >= waves_per_block) return;
+  const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
+  if (w >= n_dst) return;
+  const uint32_t lane = (uint32_t)lane_id();
+  if (lane == 0) n_cand[w] = 0;  // nothing left to do for this destination, unless said otherwise below
+  const int64_t o = eptr[w];
+  if (eptr[w + 1] > edge_limit) return;
+  const NsRecord g = rec[w];
+  if (g.d == 0) return;
+  if (g.d <= k) {
+    for (uint32_t j = lane; j < g.d; j += kWave) {
+      col_global[o + j] = g_indices[g.beg + j];
+      eid[o + j] = g.beg + j;
+    }
+    return;
+  }
+  if (k > kNsMaxSelect) {
+    if (lane == 0) atomicOr(&ctl->err_capacity, 1);
+    return;
+  }
+  uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;
+  uint32_t* cand_j = cand_r + cap;
+  int32_t* cand_t = reinterpret_cast<int32_t*>(cand_j + 2 * cap);
+  const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)g.s), sigma_b = ns_sigma(vp.K.Kb, (uint32_t)g.s);
+  const uint32_t n_c = ns_collect<true, VEC4, true>(g_indices, g.beg, g.d, g.bound, bthr[w], vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap,
+                                                    &queues[wib]);
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
-  if (n_c <= (uint32_t)kWave) {
-    // the usual case: one candidate per lane, ranked through lane reads (no LDS round trips in the loops)
-    const bool has = lane < n_c;
-    const uint32_t my_r = has ? cand_r[lane] : 0xFFFFFFFFu;
-    const uint32_t my_j = has ? cand_j[lane] : 0xFFFFFFFFu;
-    const int32_t my_t = has ? cand_t[lane] : 0;
-    const uint64_t my_key = ((uint64_t)my_r << 32) | my_j;  // order by (variate, list position)
-    uint32_t rank = 0;
-    for (uint32_t q = 0; q < n_c; ++q) {
-      const uint64_t key = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)my_r, (int)q) << 32) |
-                           (uint32_t)__builtin_amdgcn_readlane((int)my_j, (int)q);
-      rank += key < my_key;
+  if (n_c < k || n_c > row_cap || n_c > cap) {  // (too few even before the exact test, or no room)
+    if (lane == 0) n_cand[w] = kNsRedo;
+    return;
+  }
+  NsCand* row = rows + (size_t)w * row_cap;
+  for (uint32_t i = lane; i < n_c; i += kWave) row[i] = NsCand{cand_j[i], cand_t[i]};
+  if (lane == 0) n_cand[w] = n_c;
+}
+
+__global__ __launch_bounds__(kBlock) void k_ns_select(const NsRecord* __restrict__ rec, int64_t n_dst, uint32_t k, uint32_t cap,
+                                                      int waves_per_block, VariateParams vp, const int64_t* __restrict__ eptr,
+                                                      int32_t* __restrict__ col_global, int64_t* __restrict__ eid,
+                                                      const NsCand* __restrict__ rows, uint32_t row_cap, uint32_t* __restrict__ n_cand,
+                                                      const NsBlendThr* __restrict__ bthr) {
+  extern __shared__ uint32_t lds_words[];
+  const int wib = uniform_wave_in_block();
+  if (wib >= waves_per_block) return;
+  const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
+  if (w >= n_dst) return;
+  const uint32_t n = n_cand[w];
+  if (n == 0 || n == kNsRedo) return;  // done by the collecting kernel, or left to k_ns_fill
+  const uint32_t lane = (uint32_t)lane_id();
+  const NsRecord g = rec[w];
+  uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;
+  uint32_t* cand_j = cand_r + cap;
+  uint32_t* cand_k = cand_j + cap;
+  int32_t* cand_t = reinterpret_cast<int32_t*>(cand_k + cap);
+  const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)g.s), sigma_b = ns_sigma(vp.K.Kb, (uint32_t)g.s);
+  const NsCand* row = rows + (size_t)w * row_cap;
+  if (n <= (uint32_t)kWave) {
+    // The usual case, one candidate per lane.  Only the set of the k smallest matters, so the fp32 blend (within
+    // `allow` / 10 of the exact one in normal space) decides wherever it can: with e_k the k-th smallest estimate and
+    // m = 2 allow, a candidate below e_k - m is among the k smallest, one above e_k + m is not, and the exact variates
+    // are needed only to choose among those in between, and only if there are more of them than places left.
+    const bool has = lane < n;
+    NsCand c{0xFFFFFFFFu, 0};
+    if (has) c = row[lane];
+    const uint32_t u1 = keyed_uniform<true>(vp.K.Ka, (uint32_t)c.t, sigma_a), u2 = keyed_uniform<true>(vp.K.Kb, (uint32_t)c.t, sigma_b);
+    const float est = has ? __builtin_fmaf((float)vp.cw, approx_phi_inv_f32(u1), (float)vp.sw * approx_phi_inv_f32(u2)) : __builtin_inff();
+    uint32_t rank_est = 0;
+    for (uint32_t q = 0; q < n; ++q) {
+      const float e = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(est), (int)q));
+      rank_est += (e < est) || (e == est && q < lane);
     }
-    const bool keep = has && rank < k;
+    const uint64_t kth = ballot64(has && rank_est == k - 1);  // exactly one lane (n >= k)
+    const float e_k = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(est), __builtin_ctzll(kth)));
+    const float allow = (float)((vp.cw + vp.sw) * 4e-3 + 2e-5);
+    const float m = 2.0f * allow;
+    // outside |e_k| <= 5 two different blends can share a 32-bit variate, and the estimate says nothing about ties; and
+    // e_k must lie safely below what the traversal's filter let through, or a neighbour that it dropped could belong
+    // to the k smallest
+    if (!(e_k >= -5.0f && e_k <= 5.0f) || !(e_k + m <= bthr[w].lim2 - m)) {
+      if (lane == 0) n_cand[w] = kNsRedo;
+      return;
+    }
+    const bool in = has && est < e_k - m;
+    const bool und = has && !in && est <= e_k + m;
+    const uint64_t und_mask = ballot64(und);
+    const uint32_t need = k - (uint32_t)__popcll(ballot64(in));  // >= 1: the k-th itself is undecided
+    bool keep = in || und;
+    if ((uint32_t)__popcll(und_mask) > need) {  // wave-uniform
+      uint32_t R = 0;
+      if (und) R = kit_phi_to_u32(__builtin_fma(vp.cw, kit_phi_inv_u32(u1), vp.sw * kit_phi_inv_u32(u2)));
+      const uint64_t my_key = ((uint64_t)R << 32) | c.j;
+      uint32_t rank_u = 0;
+      uint64_t rest = und_mask;
+      while (rest != 0) {
+        const int q = __builtin_ctzll(rest);
+        rest &= rest - 1;
+        const uint64_t key = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)R, q) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)c.j, q);
+        rank_u += key < my_key;
+      }
+      keep = in || (und && rank_u < need);
+    }
     const uint64_t kept = ballot64(keep);
     uint32_t place = 0;  // kept candidates in front of this one in the list
     uint64_t rest = kept;
     while (rest != 0) {
       const int q = __builtin_ctzll(rest);
       rest &= rest - 1;
-      place += (uint32_t)__builtin_amdgcn_readlane((int)my_j, q) < my_j;
+      place += (uint32_t)__builtin_amdgcn_readlane((int)c.j, q) < c.j;
     }
     if (keep) {
-      col_global[o + place] = my_t;
-      eid[o + place] = beg + my_j;
+      const int64_t o = eptr[w];
+      col_global[o + place] = c.t;
+      eid[o + place] = g.beg + c.j;
     }
     return;
   }
-  for (uint32_t i = lane; i < n_c; i += kWave) {
-    const uint32_t my_r = cand_r[i], my_j = cand_j[i];
-    uint32_t rank = 0;
-    for (uint32_t q = 0; q < n_c; ++q) {
-      const uint32_t r = cand_r[q];
-      rank += (r < my_r) || (r == my_r && cand_j[q] < my_j);
+  uint32_t n_c = 0;  // candidates with R <= bound, compacted into LDS
+  for (uint32_t base = 0; base < n; base += kWave) {
+    const uint32_t i = base + lane;
+    NsCand c{0u, 0};
+    uint32_t R = 0;
+    bool in = false;
+    if (i < n) {
+      c = row[i];
+      const uint32_t u1 = keyed_uniform<true>(vp.K.Ka, (uint32_t)c.t, sigma_a), u2 = keyed_uniform<true>(vp.K.Kb, (uint32_t)c.t, sigma_b);
+      R = kit_phi_to_u32(__builtin_fma(vp.cw, kit_phi_inv_u32(u1), vp.sw * kit_phi_inv_u32(u2)));
+      in = R <= g.bound;
     }
-    cand_k[i] = rank < k;
+    const uint64_t mask = ballot64(in);
+    const uint32_t at = n_c + lanes_below(mask);
+    if (in) { cand_r[at] = R; cand_j[at] = c.j; cand_t[at] = c.t; }  // (n <= cap)
+    n_c += (uint32_t)__popcll(mask);
   }
-  __builtin_amdgcn_wave_barrier();
-  __threadfence_block();
-  for (uint32_t i = lane; i < n_c; i += kWave) {
-    if (!cand_k[i]) continue;
-    const uint32_t my_j = cand_j[i];
-    uint32_t place = 0;
-    for (uint32_t q = 0; q < n_c; ++q) place += cand_k[q] && cand_j[q] < my_j;
-    col_global[o + place] = cand_t[i];
-    eid[o + place] = beg + my_j;
+  if (n_c < k) {
+    if (lane == 0) n_cand[w] = kNsRedo;
+    return;
   }
+  ns_rank_write(n_c, k, cand_r, cand_j, cand_k, cand_t, eptr[w], g.beg, col_global, eid);
 }
 
 int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk, int64_t edge_cap) {
@@ -388,11 +566,21 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
     const dim3 grid(blocks_for(n_dst, wpb));
 #define COOP_NS_ARGS cx.g->indices, rec, bthr, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, m, cx.d_ctl
     if (cx.blend) {
-      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
-      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
+      // rows of the two-kernel path: room for twice the expected candidates (at least 64, at most the LDS capacity)
+      uint32_t row_cap = 64;
+      while (row_cap < 2 * target && row_cap < cap) row_cap <<= 1;
+      NsCand* rows = alloc.get<NsCand>(n_dst * (int64_t)row_cap, COOP_TAG_SCRATCH);
+      uint32_t* n_cand = alloc.get<uint32_t>(n_dst, COOP_TAG_SCRATCH);
+      if (alloc.failed) return COOP_E_NOMEM;
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, k_ns_collect<true>, grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand);
+      else COOP_LAUNCH(K_NS_FILL, k_ns_collect<false>, grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand);
+      COOP_LAUNCH(K_NS_SELECT, k_ns_select, grid, dim3(kBlock), shmem, s, rec, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid,
+                  (const NsCand*)rows, row_cap, n_cand, (const NsBlendThr*)bthr);
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand);
+      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand);
     } else {
-      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
-      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS);
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr);
+      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr);
     }
 #undef COOP_NS_ARGS
   }
