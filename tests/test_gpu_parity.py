@@ -507,6 +507,11 @@ def test_ns_dependent_batches_go_through_the_filters(P, tiny, medium):
         compare(P, medium, hubs, (25, 3), R.NS, it=it, kappa=kappa, seed=42)
     compare(P, medium, hubs[:40], (1000, 2), R.NS, it=9, kappa=4, seed=43)      # fanout close to the degrees
     compare(P, tiny, synth.seed_batches(tiny.n, 400, seed=62)(0).numpy(), (1, 40, 7), R.NS, it=7, kappa=8, seed=44)
+    # fanout 1 over tens of thousands of lists: about one list in 10^4 collects no candidate at its first bound, or has
+    # its smallest estimate too close to the filter's limit, and goes through the one-kernel path again
+    many = synth.seed_batches(medium.n, 20000, seed=63)(0).numpy()
+    for it, kappa in ((3, 4), (9, 16)):
+        compare(P, medium, many, (1, 1), R.NS, it=it, kappa=kappa, seed=45)
 
 
 @pytest.mark.parametrize("mode", [0, 1, 2])
