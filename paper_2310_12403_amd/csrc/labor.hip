@@ -735,8 +735,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_staged(LayerChunks ch, in
   for (int i = 0; i < kPerLane; ++i) {
     const int slot = sub + (i << kFillLanesLog2);
     mine[i] = StageEntry{0, 0xFFFFFFFFu};
-    if (slot < c) mine[i] = row[slot];
-    js[slot] = mine[i].j;
+    if (slot < c) { mine[i] = row[slot]; js[slot] = mine[i].j; }  // (only js[0..c) is read below)
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();

@@ -306,9 +306,9 @@ __global__ __launch_bounds__(kFirstBlock) void k_part_first(const unsigned long 
       const uint32_t key = (uint32_t)(mine[u] >> 32);
       uint32_t h = table_slot_of_hash(hash_of_key(key));
       unsigned long long cur;
-      for (;;) {
+      for (;;) {  // (every key of the bucket was inserted above; an empty slot ends the search regardless)
         cur = table[h];
-        if ((uint32_t)(cur >> 32) == key) break;
+        if ((uint32_t)(cur >> 32) == key || cur == kEmptySlot) break;
         h = (h + 1) & (kPartSlots - 1);
       }
       const int64_t e = pos - n_dst;
