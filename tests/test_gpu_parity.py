@@ -575,3 +575,49 @@ def test_frontier_dedup_modes(P, tiny, medium, mode):
     finally:
         P.coop_tune(P.COOP_TUNE_UNIQUE, 0)
         P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
+
+
+def test_randomized_configurations(P):
+    """Seeded random draws of graph shape, batch, depth, fanouts, sampler, iteration / kappa and of the library's
+    internal modes (piece length, layer fusion, staging rows, read-back mode, dedup mode, lists per wave), every output
+    against the oracle: the code paths meet here in combinations that no other test spells out."""
+    rng = np.random.default_rng(20240)
+    fan_choices = (1, 2, 3, 5, 10, 25, 64, 65, 300)
+    knobs = (P.COOP_TUNE_PIECE_LEN, P.COOP_TUNE_FUSE_LAYERS, P.COOP_TUNE_STAGE_CAP, P.COOP_TUNE_DEFER_SIZES, P.COOP_TUNE_UNIQUE,
+             P.COOP_TUNE_LISTS_PER_WAVE)
+    defaults = (4096, 1, 0, 1, 0, 0)
+    graphs = []
+    for gi in range(6):
+        n = int(rng.choice((60, 900, 7000, 30000)))
+        m = int(n * rng.choice((1, 6, 30, 70)))
+        graphs.append(G(P, *synth.chung_lu_csr(n, max(m, n), float(rng.choice((1.9, 2.1, 2.6))), seed=100 + gi)))
+    try:
+        for case in range(160):
+            g = graphs[case % len(graphs)]
+            L = int(rng.integers(1, 5))
+            fanouts = tuple(int(rng.choice(fan_choices)) for _ in range(L))
+            b = int(min(g.n, rng.choice((1, 7, 64, 500, 3000))))
+            seeds = synth.seed_batches(g.n, b, seed=int(rng.integers(1 << 20)))(0).numpy()
+            sampler = int(rng.choice((R.NS, R.LABOR0, R.RW), p=(0.4, 0.45, 0.15)))
+            kappa = int(rng.choice((0, 1, 2, 16)))
+            it = int(rng.integers(0, 40))
+            sd = int(rng.integers(1 << 30))
+            values = (int(rng.choice((0, 256, 512, 4096))), int(rng.integers(0, 3)), int(rng.choice((0, 0, 4, 32))),
+                      int(rng.integers(0, 3)), int(rng.integers(0, 4)), int(rng.choice((0, 0, 1, 3, 8))))
+            for kn, v in zip(knobs, values):
+                P.coop_tune(kn, v)
+            label = (case, g.n, fanouts, b, sampler, kappa, it, values)
+            try:
+                if sampler == R.RW:
+                    fan = tuple(min(f, 64) for f in fanouts[:2])
+                    compare_rw(P, g, seeds[:min(b, 300)], fan, int(rng.integers(1, 4)), int(rng.integers(1, 40)), float(rng.choice((0.0, 0.3, 1.0))),
+                               it=it, seed=sd)
+                else:
+                    if sampler == R.NS and kappa != 1 and max(fanouts) > 64:
+                        fanouts = tuple(min(f, 64) for f in fanouts)  # (keeps the oracle's exact blends to a few seconds)
+                    compare(P, g, seeds, fanouts, sampler, it=it, kappa=kappa, seed=sd)
+            except AssertionError as e:
+                raise AssertionError("%s: %s" % (label, e))
+    finally:
+        for kn, v in zip(knobs, defaults):
+            P.coop_tune(kn, v)
