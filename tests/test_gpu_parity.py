@@ -577,11 +577,11 @@ def test_frontier_dedup_modes(P, tiny, medium, mode):
         P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
 
 
-def test_randomized_configurations(P):
+def test_randomized_configurations(P, draw_seed=20240, cases=160):
     """Seeded random draws of graph shape, batch, depth, fanouts, sampler, iteration / kappa and of the library's
     internal modes (piece length, layer fusion, staging rows, read-back mode, dedup mode, lists per wave), every output
     against the oracle: the code paths meet here in combinations that no other test spells out."""
-    rng = np.random.default_rng(20240)
+    rng = np.random.default_rng(draw_seed)
     fan_choices = (1, 2, 3, 5, 10, 25, 64, 65, 300)
     knobs = (P.COOP_TUNE_PIECE_LEN, P.COOP_TUNE_FUSE_LAYERS, P.COOP_TUNE_STAGE_CAP, P.COOP_TUNE_DEFER_SIZES, P.COOP_TUNE_UNIQUE,
              P.COOP_TUNE_LISTS_PER_WAVE)
@@ -592,7 +592,7 @@ def test_randomized_configurations(P):
         m = int(n * rng.choice((1, 6, 30, 70)))
         graphs.append(G(P, *synth.chung_lu_csr(n, max(m, n), float(rng.choice((1.9, 2.1, 2.6))), seed=100 + gi)))
     try:
-        for case in range(160):
+        for case in range(cases):
             g = graphs[case % len(graphs)]
             L = int(rng.integers(1, 5))
             fanouts = tuple(int(rng.choice(fan_choices)) for _ in range(L))
