@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
                                                      const int32_t* __restrict__ dst, int64_t n, int nf,
                                                      uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, Segment* __restrict__ seg,
                                                      uint32_t* __restrict__ thr, PreThr* __restrict__ pthr, float* __restrict__ lim2,
-                                                     double cw, double sw, int queued, int fast_rows, Ctl* ctl,
+                                                     double cw, double sw, int queued, Ctl* ctl,
                                                      uint32_t piece_len, Piece* __restrict__ pieces, uint32_t piece_cap,
                                                      uint32_t* __restrict__ piece_count, ScanOut out) {
   __shared__ uint32_t s_wave_at[kSegBlock / kWave];
@@ -84,9 +84,6 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
         }
         if (queued) out.cnt[f][i] = 0;  // kept edges are counted by atomics
       }
-    // the row is filled in no particular order (blended passes; the fast scan of lists longer than a wave step): the
-    // fill pass ranks it
-    if (queued || (fast_rows && sampled && g.d > (uint32_t)kWave)) g.split = 2;
   }
   if (piece_len == 0) {  // wave-uniform
     if (live) seg[i] = g;
@@ -127,7 +124,7 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
         if (at + q < piece_cap) pieces[at + q] = fits ? Piece{list, q} : Piece{kNoPiece, 0u};
     }
     if (fits && np != 0) {
-      g.split |= 1;
+      g.split = 1;
 #pragma unroll
       for (int f = 0; f < kMaxFuse; ++f)
         if (f < nf) out.cnt[f][i] = 0;  // the pieces add their counts
@@ -607,7 +604,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
     const int64_t beg = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)beg_hi, i) << 32) |
                                   (uint32_t)__builtin_amdgcn_readlane((int)beg_lo, i));
     const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)g.d, i);
-    if ((__builtin_amdgcn_readlane((int)g.split, i) & 1) != 0) continue;  // cut into pieces, scanned by other waves
+    if (__builtin_amdgcn_readlane((int)g.split, i) != 0) continue;  // cut into pieces, scanned by other waves
     uint32_t thr[NF];
     bool any_all = false;
 #pragma unroll
@@ -652,7 +649,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
     blend_flush_first<NF>(bst, lbw, keys, stage_cap, out, ctl);
     return;  // (the counters were kept by atomics, here and in the exact stage)
   }
-  if (has && (g.split & 1) == 0) {  // (the pieces of a cut list add their counts themselves)
+  if (has && g.split == 0) {  // (the pieces of a cut list add their counts themselves)
 #pragma unroll
     for (int l = 0; l < NF; ++l) {
       out.cnt[l][mine] = (int32_t)my_count[l];
@@ -716,18 +713,10 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_staged(LayerChunks ch, in
   const StageEntry* __restrict__ row = ch.stage[p] + (size_t)local * stage_cap;
   const Segment g = ch.seg[p][local];
   const int sub = (int)(idx & ((1 << kFillLanesLog2) - 1));
-  if (g.split == 0) {
-    for (int64_t slot = sub; slot < c; slot += 1 << kFillLanesLog2) {
-      const StageEntry e = row[slot];
-      if (o + slot < edge_limit) {
-        col_global[o + slot] = e.t;
-        eid[o + slot] = g.beg + e.j;
-      }
-    }
-    return;
-  }
-  // The pieces of a cut list left their entries in no particular order: an entry's place is its rank by list
-  // position.  The lane group (all in one wave) shares the positions through LDS.
+  // A row may hold its entries in any order (the fast scan writes them as they come, the pieces of a cut list and the
+  // blended passes take slots by atomics): an entry's place is its rank by list position.  The lane group (all in one
+  // wave) shares the positions through LDS.  Rows that happen to be in order go the same way: two paths side by side
+  // in a wave cost more than ranking a dozen entries.
   uint32_t* js = row_j[threadIdx.x >> kFillLanesLog2];
   constexpr int kPerLane = kWave >> kFillLanesLog2;
   StageEntry mine[kPerLane];
@@ -895,7 +884,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       }
       COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
                   dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, cx.cw, cx.sw,
-                  cx.blend && cx.vec4 ? 1 : 0, cx.vec4 ? 1 : 0, cx.d_ctl,
+                  cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
                   piece_len, pieces, piece_cap, cx.d_piece_count + l, out);
       // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
       int lpw = g_lists_per_wave;
