@@ -12,9 +12,15 @@ __global__ __launch_bounds__(kBlock) void k_copy_i32(const int32_t* __restrict__
   if (i < n) out[i] = in[i];
 }
 
-__global__ void k_clear_ctl(Ctl* ctl, uint32_t* piece_count, int L) {
-  *ctl = Ctl{};
-  for (int l = 0; l < L; ++l) piece_count[l] = 0;
+// start of a sampling call: the seed list is copied to the first block's dst_ids and the control data cleared
+__global__ __launch_bounds__(kBlock) void k_begin_call(const int32_t* __restrict__ seeds, int32_t* __restrict__ seed_copy, int64_t n_seeds,
+                                                       Ctl* ctl, uint32_t* piece_count, int L) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n_seeds) seed_copy[i] = seeds[i];
+  if (i == 0) {
+    *ctl = Ctl{};
+    for (int l = 0; l < L; ++l) piece_count[l] = 0;
+  }
 }
 
 // The control block travels to the host by a one-thread kernel that stores it into mapped pinned memory and then a
@@ -153,9 +159,8 @@ static int sample_layers(const coop_graph* g, const int32_t* seeds, int64_t n_se
   cx.d_piece_count = alloc.get<uint32_t>(L, COOP_TAG_SCRATCH);
   int32_t* seed_copy = alloc.get<int32_t>(n_seeds, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
-  COOP_LAUNCH(K_FILL, k_clear_ctl, dim3(1), dim3(1), 0, s, cx.d_ctl, cx.d_piece_count, L);
-  if (n_seeds > 0)
-    COOP_LAUNCH(K_COPY_IDS, k_copy_i32, dim3(blocks_for(n_seeds, kBlock)), dim3(kBlock), 0, s, seeds, seed_copy, n_seeds);
+  COOP_LAUNCH(K_COPY_IDS, k_begin_call, dim3(n_seeds > 0 ? blocks_for(n_seeds, kBlock) : 1u), dim3(kBlock), 0, s, seeds, seed_copy, n_seeds,
+              cx.d_ctl, cx.d_piece_count, L);
 
   LaborState labor;
   bool defer_ok = true;
