@@ -121,8 +121,9 @@ typedef struct {
  *   fanouts    host int32 [L], each >= 1; NS needs fanout <= 1024 wherever a degree exceeds it (else COOP_E_CAPACITY)
  *   blocks_out host coop_block [L], filled on success
  * Waits on `stream` once per layer, for |E^l| and |S^{l+1}| together: with a fanout of at most 64 the edge arrays are
- * obtained from the allocator with room for a bound on |E^l| (fanout x |S^l|, plus a little for LABOR-0), so they may
- * be longer than n_edges entries; a layer whose bound falls short is redone.  With a larger fanout |E^l| is read back
+ * obtained from the allocator with room for a bound on |E^l| (fanout x |S^l|, plus a little for LABOR-0) and src_ids
+ * with room for |S^l| plus that bound, so they may be longer than n_edges / n_src entries; a layer whose bound falls
+ * short is redone.  With a larger fanout |E^l| is read back
  * first (a second wait) and the arrays have exactly n_edges entries.  When it returns all
  * sizes in blocks_out are final, while the kernels that fill the last layer's col_local / src_ids may still be running
  * on `stream`: work queued on the same stream sees complete blocks, anything else must synchronise the stream first.

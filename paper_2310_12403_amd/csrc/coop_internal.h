@@ -132,23 +132,33 @@ int wait_ctl(const Publish& pub, Ctl* h_ctl, hipStream_t s);
 int read_ctl(Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
 
 // Dedup + relabel of one layer (Eq. 2), in two halves around the size read-back.
-//   front: inserts [dst ; col_global] into a hash table, finds every edge's first occurrence and counts the new
-//          vertices; ends by reading the control block back (synchronises the stream).  `m` is the number of edges, or,
-//          when m_dev is given, an upper bound of it known to the host (the exact number is then *m_dev, on the device,
-//          and comes back in the control block's total_edges together with everything else: one read-back serves the
-//          sampler and the dedup).
-//   back:  with the exact m: allocates src_ids[n_src] and writes it and col_local[m].
+//   front: finds every edge's first occurrence in [dst ; col_global] and counts the new vertices.  `m` is the number of
+//          edges, or, when m_dev is given, an upper bound of it known to the host (the exact number is then *m_dev, on
+//          the device, and comes back in the control block's total_edges together with everything else: one read-back
+//          serves the sampler and the dedup).
+//   back:  writes src_ids and col_local.
 extern int g_unique_mode;  // COOP_TUNE_UNIQUE
 struct UniqueWork {
   uint32_t* first = nullptr;
   uint64_t* bits = nullptr;
   uint32_t* word_rank = nullptr;
+  void* scan_tmp = nullptr;
+  int64_t n_buckets = 0;
+  bool by_partition = false;
+  Publish pub{};
   int64_t n_new = 0;
 };
-int unique_front(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w, Alloc& alloc,
-                 Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
-int unique_back(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const UniqueWork& w, int32_t* col_local,
-                int32_t** src_out, int64_t* n_src_out, Alloc& alloc, hipStream_t s);
+// launch: every kernel of the front half, ending with the scan that sends the sizes to the host; does not wait.
+int unique_front_launch(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w,
+                        Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s);
+// finish: waits for the sizes (h_ctl then holds total_edges, total_new and the flags; w->n_new is set).  If the dedup
+// had to be run again (*redone), a relabelling launched in between has to be launched again.
+int unique_front_finish(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w,
+                        Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s, bool* redone);
+// back: writes src_ids (S^l, then the new vertices) and col_local[m]; src must have room for n_dst + (number of new
+// vertices) entries.  May be launched between launch and finish with room for n_dst + m entries.
+int unique_back(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, const UniqueWork& w,
+                int32_t* col_local, int32_t* src, hipStream_t s);
 
 }  // namespace coop
 

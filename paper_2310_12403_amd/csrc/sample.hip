@@ -193,15 +193,28 @@ static int sample_layers(const coop_graph* g, const int32_t* seeds, int64_t n_se
                                     : rw_layer(cx, *rw, l, dst, n_dst, &blk, cap);
     };
     UniqueWork uw{};
-    bool done = false;
+    int32_t* src = nullptr;
+    int64_t n_src = 0;
+    bool done = false, redone = false;
     if (edge_cap > 0) {
       rc = sample_layer(edge_cap);
       if (rc != COOP_OK) break;
-      rc = unique_front(dst, n_dst, blk.col_global, edge_cap, &cx.d_ctl->total_edges, &uw, alloc, cx.d_ctl, h_ctl, s);
+      const int64_t* m_dev = &cx.d_ctl->total_edges;
+      rc = unique_front_launch(dst, n_dst, blk.col_global, edge_cap, m_dev, &uw, alloc, cx.d_ctl, h_ctl, s);
+      if (rc != COOP_OK) break;
+      // S^{l+1} and local ids (Eq. 2) are queued before the sizes are back, with room for the bound, so that the device
+      // is at work while the host waits for the sizes and sets up the next layer
+      src = alloc.get<int32_t>(n_dst + edge_cap, COOP_TAG_OUTPUT);
+      if (alloc.failed) { rc = COOP_E_NOMEM; break; }
+      rc = unique_back(dst, n_dst, blk.col_global, edge_cap, m_dev, uw, blk.col_local, src, s);
+      if (rc != COOP_OK) break;
+      rc = unique_front_finish(dst, n_dst, blk.col_global, edge_cap, m_dev, &uw, alloc, cx.d_ctl, h_ctl, s, &redone);
       if (rc != COOP_OK) break;
       if (h_ctl->n_overflow > 0) defer_ok = false;  // the counter is never reset: the overflow pass runs from here on
       if (h_ctl->total_edges <= edge_cap && h_ctl->n_overflow == 0 && h_ctl->cand_overflow == 0) {
         blk.n_edges = h_ctl->total_edges;
+        if (redone) rc = unique_back(dst, n_dst, blk.col_global, edge_cap, m_dev, uw, blk.col_local, src, s);
+        if (rc != COOP_OK) break;
         done = true;
       } else {
         labor = labor_before;
@@ -215,15 +228,16 @@ static int sample_layers(const coop_graph* g, const int32_t* seeds, int64_t n_se
       rc = sample_layer(0);
       if (rc != COOP_OK) break;
       if (n_dst + blk.n_edges >= ((int64_t)1 << 32) - 1) { rc = COOP_E_CAPACITY; break; }
-      rc = unique_front(dst, n_dst, blk.col_global, blk.n_edges, nullptr, &uw, alloc, cx.d_ctl, h_ctl, s);
+      rc = unique_front_launch(dst, n_dst, blk.col_global, blk.n_edges, nullptr, &uw, alloc, cx.d_ctl, h_ctl, s);
+      if (rc != COOP_OK) break;
+      rc = unique_front_finish(dst, n_dst, blk.col_global, blk.n_edges, nullptr, &uw, alloc, cx.d_ctl, h_ctl, s, &redone);
+      if (rc != COOP_OK) break;
+      src = alloc.get<int32_t>(n_dst + uw.n_new, COOP_TAG_OUTPUT);
+      if (alloc.failed) { rc = COOP_E_NOMEM; break; }
+      rc = unique_back(dst, n_dst, blk.col_global, blk.n_edges, nullptr, uw, blk.col_local, src, s);
       if (rc != COOP_OK) break;
     }
-
-    // S^{l+1} and local ids (Eq. 2)
-    int32_t* src = nullptr;
-    int64_t n_src = 0;
-    rc = unique_back(dst, n_dst, blk.col_global, blk.n_edges, uw, blk.col_local, &src, &n_src, alloc, s);
-    if (rc != COOP_OK) break;
+    n_src = n_dst + uw.n_new;
     blk.src_ids = src;
     blk.n_src = n_src;
     blocks_out[l] = blk;

@@ -76,14 +76,21 @@ __global__ __launch_bounds__(kBlock) void k_uniq_flag(const int32_t* __restrict_
 }
 
 // col_local and the tail of src_ids; the threads of the first n_dst positions also copy S^l to the front of src_ids
+// (m_dev, optional: the exact number of edges, on the device; m is then the capacity of col.  The kernel may be
+// launched before the host has seen the dedup's error and overflow flags, on a `first` that a failed dedup left
+// partly unwritten: positions outside [0, n_dst + m) are skipped, so that every access stays inside the arrays whatever
+// `first` holds; the caller discards the result in that case.)
 __global__ __launch_bounds__(kBlock) void k_uniq_relabel(const int32_t* __restrict__ dst, const int32_t* __restrict__ col, int64_t m,
-                                                         int64_t n_dst, const uint32_t* __restrict__ first,
-                                                         const uint64_t* __restrict__ bits, const uint32_t* __restrict__ word_rank,
-                                                         int32_t* __restrict__ src, int32_t* __restrict__ col_local) {
+                                                         const int64_t* __restrict__ m_dev, int64_t n_dst,
+                                                         const uint32_t* __restrict__ first, const uint64_t* __restrict__ bits,
+                                                         const uint32_t* __restrict__ word_rank, int32_t* __restrict__ src,
+                                                         int32_t* __restrict__ col_local) {
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (m_dev != nullptr && *m_dev < m) m = *m_dev;
   if (e < n_dst) src[e] = dst[e];
   if (e >= m) return;
   const int64_t f = first[e];
+  if (f >= n_dst + m) return;
   int64_t local = f;
   if (f >= n_dst) {
     const int64_t at = f - n_dst;  // the edge at which this vertex first appears
@@ -333,80 +340,91 @@ static inline unsigned nblocks(int64_t n) { return (unsigned)((n + kBlock - 1) /
 
 int g_unique_mode = 0;  // COOP_TUNE_UNIQUE: 0 automatic, 1 table in HBM, 2 partition whenever it applies, 3 as 2 with buckets 16 times too large
 
-int unique_front(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w, Alloc& alloc,
-                 Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
+// launches the dedup's kernels up to the scan that ranks the new vertices and sends the control block to the host
+static int unique_launch(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w,
+                         bool by_partition, Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
+  const int64_t n_all = n_dst + m;
+  const int64_t n_words = (m + 63) / 64;
+  if (by_partition) {
+    const int64_t n_buckets = w->n_buckets;
+    const int64_t by_size = (n_all + 4 * kPartBlock - 1) / (4 * kPartBlock);
+    const uint32_t G = (uint32_t)(by_size < kPartMaxBlocks ? (by_size + 7) / 8 * 8 : kPartMaxBlocks);  // a multiple of 8
+    const int64_t n_counts = n_buckets * G;
+    uint32_t* counts = alloc.get<uint32_t>(n_counts, COOP_TAG_SCRATCH);
+    uint32_t* place = alloc.get<uint32_t>(n_counts + 1, COOP_TAG_SCRATCH);
+    unsigned long long* pairs = alloc.get<unsigned long long>(n_all, COOP_TAG_SCRATCH);
+    void* tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_counts), COOP_TAG_SCRATCH);
+    if (alloc.failed) return COOP_E_NOMEM;
+    const size_t lds = (size_t)n_buckets * sizeof(uint32_t);
+    COOP_LAUNCH(K_PART_COUNT, k_part_count, dim3(G), dim3(kPartBlock), lds, s, dst, n_dst, col_global, m, m_dev, (uint32_t)n_buckets, counts);
+    scan_u32_to_u32(counts, n_counts, place, tmp, s);
+    COOP_LAUNCH(K_PART_SCATTER, k_part_scatter, dim3(G), dim3(kPartBlock), 2 * lds, s, dst, n_dst, col_global, m, m_dev, (uint32_t)n_buckets,
+                (const uint32_t*)place, pairs);
+    COOP_LAUNCH(K_PART_FIRST, k_part_first, dim3((unsigned)n_buckets), dim3(kFirstBlock), 0, s, pairs, place, G, n_dst, n_all, w->first, d_ctl);
+    if (hipGetLastError() != hipSuccess) return COOP_E_HIP;  // (a launch that did not happen would leave `first` unwritten)
+    COOP_LAUNCH(K_UNIQ_FLAG, k_flag_from_first, dim3(nblocks(m)), dim3(kBlock), 0, s, w->first, m, m_dev, n_dst, w->bits);
+  } else {
+    // at most half full; an even number of slots (the clear uses 16-byte stores)
+    const int64_t cap = 2 * n_all + 1024;
+    unsigned long long* table = alloc.get<unsigned long long>(cap, COOP_TAG_SCRATCH);
+    if (alloc.failed) return COOP_E_NOMEM;
+    if (n_all > 0) {
+      fill_u64((uint64_t*)table, cap, kEmptySlot, s);
+      COOP_LAUNCH(K_UNIQ_INSERT, k_uniq_insert, dim3(nblocks(n_all)), dim3(kBlock), 0, s, dst, n_dst, col_global, m, m_dev, table, (uint64_t)cap,
+                  d_ctl);
+    }
+    if (m > 0)
+      COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, m_dev, n_dst, table, (uint64_t)cap, w->first,
+                  w->bits);
+  }
+  // sizes (and the duplicate / range flags) back to the host, sent by the scan's last thread when there is a scan
+  w->pub = begin_publish(d_ctl, h_ctl);
+  if (m > 0) scan_popc_to_u32(w->bits, n_words, w->word_rank, &d_ctl->total_new, w->scan_tmp, s, &w->pub, m_dev);
+  else if (launch_publish(w->pub, s) != COOP_OK) return COOP_E_HIP;
+  w->by_partition = by_partition;
+  return COOP_OK;
+}
+
+int unique_front_launch(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w,
+                        Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s) {
   const int64_t n_all = n_dst + m;
   w->first = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
   const int64_t n_words = (m + 63) / 64;
   w->word_rank = alloc.get<uint32_t>(n_words, COOP_TAG_SCRATCH);
   w->bits = alloc.get<uint64_t>(n_words, COOP_TAG_SCRATCH);
-  void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_words), COOP_TAG_SCRATCH);
+  w->scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_words), COOP_TAG_SCRATCH);
   if (alloc.failed) return COOP_E_NOMEM;
-
   // by partition from a few hundred thousand entries on (below that its five launches cost more than the table's
   // three), as long as a block's counters fit LDS
-  int64_t pairs_per_bucket = g_unique_mode == 3 ? 16 * kPartPairs : kPartPairs;
-  const int64_t n_buckets = (n_all + pairs_per_bucket - 1) / pairs_per_bucket;
-  bool by_partition = m > 0 && n_buckets <= kPartMaxBuckets && g_unique_mode != 1 && (g_unique_mode >= 2 || n_all >= 262144);
-  for (;;) {
-    if (by_partition) {
-      const int64_t by_size = (n_all + 4 * kPartBlock - 1) / (4 * kPartBlock);
-      const uint32_t G = (uint32_t)(by_size < kPartMaxBlocks ? (by_size + 7) / 8 * 8 : kPartMaxBlocks);  // a multiple of 8
-      const int64_t n_counts = n_buckets * G;
-      uint32_t* counts = alloc.get<uint32_t>(n_counts, COOP_TAG_SCRATCH);
-      uint32_t* place = alloc.get<uint32_t>(n_counts + 1, COOP_TAG_SCRATCH);
-      unsigned long long* pairs = alloc.get<unsigned long long>(n_all, COOP_TAG_SCRATCH);
-      void* tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_counts), COOP_TAG_SCRATCH);
-      if (alloc.failed) return COOP_E_NOMEM;
-      const size_t lds = (size_t)n_buckets * sizeof(uint32_t);
-      COOP_LAUNCH(K_PART_COUNT, k_part_count, dim3(G), dim3(kPartBlock), lds, s, dst, n_dst, col_global, m, m_dev, (uint32_t)n_buckets,
-                  counts);
-      scan_u32_to_u32(counts, n_counts, place, tmp, s);
-      COOP_LAUNCH(K_PART_SCATTER, k_part_scatter, dim3(G), dim3(kPartBlock), 2 * lds, s, dst,
-                  n_dst, col_global, m, m_dev, (uint32_t)n_buckets, (const uint32_t*)place, pairs);
-      COOP_LAUNCH(K_PART_FIRST, k_part_first, dim3((unsigned)n_buckets), dim3(kFirstBlock), 0, s, pairs, place, G, n_dst, n_all, w->first, d_ctl);
-      if (hipGetLastError() != hipSuccess) return COOP_E_HIP;  // (a launch that did not happen would leave `first` unwritten)
-      COOP_LAUNCH(K_UNIQ_FLAG, k_flag_from_first, dim3(nblocks(m)), dim3(kBlock), 0, s, w->first, m, m_dev, n_dst, w->bits);
-    } else {
-      // at most half full; an even number of slots (the clear uses 16-byte stores)
-      const int64_t cap = 2 * n_all + 1024;
-      unsigned long long* table = alloc.get<unsigned long long>(cap, COOP_TAG_SCRATCH);
-      if (alloc.failed) return COOP_E_NOMEM;
-      if (n_all > 0) {
-        fill_u64((uint64_t*)table, cap, kEmptySlot, s);
-        COOP_LAUNCH(K_UNIQ_INSERT, k_uniq_insert, dim3(nblocks(n_all)), dim3(kBlock), 0, s, dst, n_dst, col_global, m, m_dev, table,
-                    (uint64_t)cap, d_ctl);
-      }
-      if (m > 0) {
-        COOP_LAUNCH(K_UNIQ_FLAG, k_uniq_flag, dim3(nblocks(m)), dim3(kBlock), 0, s, col_global, m, m_dev, n_dst, table, (uint64_t)cap,
-                    w->first, w->bits);
-      }
-    }
-    // sizes (and the duplicate / range flags) back to the host, sent by the scan's last thread when there is a scan
-    const Publish pub = begin_publish(d_ctl, h_ctl);
-    if (m > 0) scan_popc_to_u32(w->bits, n_words, w->word_rank, &d_ctl->total_new, scan_tmp, s, &pub, m_dev);
-    else if (launch_publish(pub, s) != COOP_OK) return COOP_E_HIP;
-    const int rc = wait_ctl(pub, h_ctl, s);
-    if (rc != COOP_OK) return rc;
-    if (!by_partition || h_ctl->uniq_overflow == 0) break;
+  const int64_t pairs_per_bucket = g_unique_mode == 3 ? 16 * kPartPairs : kPartPairs;
+  w->n_buckets = (n_all + pairs_per_bucket - 1) / pairs_per_bucket;
+  const bool by_partition = m > 0 && w->n_buckets <= kPartMaxBuckets && g_unique_mode != 1 && (g_unique_mode >= 2 || n_all >= 262144);
+  return unique_launch(dst, n_dst, col_global, m, m_dev, w, by_partition, alloc, d_ctl, h_ctl, s);
+}
+
+int unique_front_finish(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, UniqueWork* w,
+                        Alloc& alloc, Ctl* d_ctl, Ctl* h_ctl, hipStream_t s, bool* redone) {
+  *redone = false;
+  int rc = wait_ctl(w->pub, h_ctl, s);
+  if (rc != COOP_OK) return rc;
+  if (w->by_partition && h_ctl->uniq_overflow != 0) {  // a bucket's table overflowed: once more through the table in HBM
     hipLaunchKernelGGL(k_clear_uniq_overflow, dim3(1), dim3(1), 0, s, d_ctl);
-    by_partition = false;
+    rc = unique_launch(dst, n_dst, col_global, m, m_dev, w, false, alloc, d_ctl, h_ctl, s);
+    if (rc != COOP_OK) return rc;
+    rc = wait_ctl(w->pub, h_ctl, s);
+    if (rc != COOP_OK) return rc;
+    *redone = true;
   }
   w->n_new = m > 0 ? h_ctl->total_new : 0;
   return COOP_OK;
 }
 
-int unique_back(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const UniqueWork& w, int32_t* col_local,
-                int32_t** src_out, int64_t* n_src_out, Alloc& alloc, hipStream_t s) {
-  const int64_t n_src = n_dst + w.n_new;
-  int32_t* src = alloc.get<int32_t>(n_src, COOP_TAG_OUTPUT);
-  if (alloc.failed) return COOP_E_NOMEM;
+int unique_back(const int32_t* dst, int64_t n_dst, const int32_t* col_global, int64_t m, const int64_t* m_dev, const UniqueWork& w,
+                int32_t* col_local, int32_t* src, hipStream_t s) {
   const int64_t n_threads = m > n_dst ? m : n_dst;
   if (n_threads > 0)
-    COOP_LAUNCH(K_UNIQ_RELABEL, k_uniq_relabel, dim3(nblocks(n_threads)), dim3(kBlock), 0, s, dst, col_global, m, n_dst, w.first, w.bits,
+    COOP_LAUNCH(K_UNIQ_RELABEL, k_uniq_relabel, dim3(nblocks(n_threads)), dim3(kBlock), 0, s, dst, col_global, m, m_dev, n_dst, w.first, w.bits,
                 w.word_rank, src, col_local);
-  *src_out = src;
-  *n_src_out = n_src;
   return COOP_OK;
 }
 
