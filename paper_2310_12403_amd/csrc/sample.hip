@@ -25,7 +25,7 @@ __global__ __launch_bounds__(kBlock) void k_begin_call(const int32_t* __restrict
 
 // The control block travels to the host by a one-thread kernel that stores it into mapped pinned memory and then a
 // ticket; the host polls the ticket.  That is a few microseconds quicker per read-back than an asynchronous copy
-// followed by a stream synchronisation, and a sampling call has one or two read-backs per layer.  The wait is bounded: after
+// followed by a stream synchronisation, and a sampling call has one read-back per layer (two for a layer that is redone or has a large fanout).  The wait is bounded: after
 // a while the host falls back to synchronising the stream.
 __global__ void k_publish_ctl(const Ctl* __restrict__ d_ctl, HostCtl* h, uint64_t ticket) {
   h->ctl = *d_ctl;

@@ -1,6 +1,8 @@
-// Frontier dedup and relabelling (Eq. 2: S^{l+1} = S^l ∪ sampled sources) with an open-addressing hash table in HBM.
+// Frontier dedup and relabelling (Eq. 2: S^{l+1} = S^l ∪ sampled sources): every edge's source vertex gets the FIRST
+// position of that vertex in the list [S^l ; col_global], through hash tables in LDS after a partition of the list into
+// buckets (long lists, further down) or through one open-addressing hash table in HBM (short lists, and the fallback).
 //
-// The list [S^l ; col_global] is inserted into a table of 8-byte slots (key << 32 | position in that list).  A slot is
+// The table in HBM: the list is inserted into a table of 8-byte slots (key << 32 | position in that list).  A slot is
 // claimed with atomicCAS; every further occurrence of the key lowers the slot's position with atomicMin, so after
 // the insert kernel each slot holds the FIRST position of its key, whichever thread won the race.  A vertex is
 // "new" exactly at the edge whose position equals that first position (and is not a seed position).  The new-flags
