@@ -87,7 +87,8 @@ def main():
     torch.cuda.synchronize()
     log("features: [%d, %d] %s = %.1f GB" % (n, dim, cfg["dtype"], n * dim * esize / 1e9))
     get_seeds = synth.seed_batches(n, batch, seed=0, device=dev)
-    graph = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE)
+    # (the synthetic graphs are undirected, stored both ways with sorted lists, like the bidirected benchmark graphs of the paper)
+    graph = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE | P.COOP_SYMMETRIC)
     arena = P.Arena(4 << 30)
     deg = indptr[1:] - indptr[:-1]
 
@@ -273,7 +274,8 @@ def report_batch_sweep(args, torch, synth, P):
     cfg = synth.CONFIGS[name]
     indptr, indices = synth.make_graph(name, device=dev, scale_down=args.scale_down, log=log)
     n = indptr.numel() - 1
-    graph = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE)
+    # (the synthetic graphs are undirected, stored both ways with sorted lists, like the bidirected benchmark graphs of the paper)
+    graph = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE | P.COOP_SYMMETRIC)
     arena = P.Arena(2 << 30)
     sizes = [1024, 4096, 16384, 65536]
     perms = 8
@@ -360,7 +362,7 @@ def report_kappa_cache(args, torch, synth, P):
     cfg = synth.CONFIGS["papers100M"]
     indptr, indices = synth.make_graph("papers100M", device=dev, scale_down=args.scale_down, log=log)
     n = indptr.numel() - 1
-    graph = P.coop_graph_load(indptr, indices)
+    graph = P.coop_graph_load(indptr, indices, P.COOP_SYMMETRIC)
     feat = synth.features(n, cfg["dim"], torch.float16, seed=0, device=dev)
     get_seeds = synth.seed_batches(n, cfg["batch"], seed=0, device=dev)
     iters = args.iters or 512
@@ -381,7 +383,7 @@ def report_host_cache(args, torch, synth, P):
     cfg = synth.CONFIGS["mag240M"]
     indptr, indices = synth.make_graph("mag240M", device=dev, scale_down=args.scale_down, log=log)
     n = indptr.numel() - 1
-    graph = P.coop_graph_load(indptr, indices)
+    graph = P.coop_graph_load(indptr, indices, P.COOP_SYMMETRIC)
     R_rows = (32 << 20) // args.scale_down
     log("pinned host table: %d rows x %d fp16 = %.1f GB" % (R_rows, cfg["dim"], R_rows * cfg["dim"] * 2 / 1e9))
     table = torch.empty((R_rows, cfg["dim"]), dtype=torch.float16, pin_memory=True)
@@ -413,7 +415,7 @@ def report_mean_agg(args, torch, synth, P):
     cfg = synth.CONFIGS["papers100M"]
     indptr, indices = synth.make_graph("papers100M", device=dev, scale_down=args.scale_down, log=log)
     n = indptr.numel() - 1
-    graph = P.coop_graph_load(indptr, indices)
+    graph = P.coop_graph_load(indptr, indices, P.COOP_SYMMETRIC)
     feat = synth.features(n, cfg["dim"], torch.float16, seed=0, device=dev)
     get_seeds = synth.seed_batches(n, cfg["batch"], seed=0, device=dev)
     arena = P.Arena(4 << 30)

@@ -36,7 +36,7 @@ extern "C" {
 #define COOP_E_NOMEM (-5)     /* the allocator callback returned NULL */
 #define COOP_E_CAPACITY (-6)  /* a fixed-size workspace would overflow */
 #define COOP_E_HIP (-7)       /* a HIP runtime call failed */
-#define COOP_E_GRAPH (-8)     /* COOP_VALIDATE found a malformed CSR */
+#define COOP_E_GRAPH (-8)     /* malformed CSR (COOP_VALIDATE), or a graph registered with COOP_SYMMETRIC is not symmetric */
 
 /* samplers (App. A.1) */
 #define COOP_NS 0       /* neighbour sampling: d_s <= k -> all neighbours, else k uniform without replacement */
@@ -49,6 +49,9 @@ extern "C" {
 
 /* coop_graph_load flags */
 #define COOP_VALIDATE 1
+#define COOP_SYMMETRIC 2 /* the caller states that every list is strictly ascending and that t is in N(s) exactly when s is
+                            in N(t) (an undirected graph stored both ways); lets LABOR-0 serve its longest lists from the
+                            other side */
 
 /* allocator tags: what the requested buffer is for */
 #define COOP_TAG_OUTPUT 0   /* referenced by a coop_block; lives as long as the caller wants */
@@ -76,7 +79,10 @@ typedef struct coop_cache coop_cache; /* opaque */
  *   indptr  device int64 [n_vertices + 1], indptr[0] = 0, nondecreasing, indptr[n_vertices] = n_edges
  *   indices device int32 [n_edges], each in [0, n_vertices)
  * Both arrays are borrowed for the lifetime of the handle.  With COOP_VALIDATE the arrays are
- * checked on the GPU (on `stream`, synchronously) and COOP_E_GRAPH is returned if malformed.
+ * checked on the GPU (on `stream`, synchronously) and COOP_E_GRAPH is returned if malformed.  With COOP_SYMMETRIC the
+ * arrays are checked as well, together with the caller's statement (COOP_E_GRAPH if it does not hold), and the library
+ * builds an index of reverse-edge positions on the device: 4 bytes per edge, allocated with hipMalloc, one bisection per
+ * edge (about a second per billion edges), released by coop_graph_free.
  */
 int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_vertices, int64_t n_edges,
                     int flags, void* stream, coop_graph** out);
@@ -267,6 +273,10 @@ const char* coop_strerror(int code);
                                       shorter ones through a hash table in HBM; 1: always the table in HBM; 2: by partition
                                       whatever the length; 3: as 2 with buckets 16 times too large, so that buckets overflow
                                       and the call falls back to the table (exercises the fallback) */
+#define COOP_TUNE_ENUM_DEGREE 8    /* LABOR-0 with independent variates on a graph registered with COOP_SYMMETRIC: lists
+                                      longer than this many entries are not read; their kept neighbours are found from the
+                                      neighbours' side (default 8192; 0: never; otherwise at least 64).  Applies while no
+                                      fanout exceeds 64 */
 int coop_tune(int knob, int64_t value);
 
 /* out[i] = in[i] for a device id list (a plain streaming copy on `stream`: 4n bytes read, 4n written).  Besides its

@@ -10,6 +10,7 @@ _LIB_PATH = os.path.join(_HERE, "libcoop.so")
 COOP_NS, COOP_LABOR0, COOP_RW = 0, 1, 2
 COOP_F32, COOP_F16 = 0, 1
 COOP_VALIDATE = 1
+COOP_SYMMETRIC = 2
 TAG_OUTPUT, TAG_SCRATCH = 0, 1
 
 ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_void_p, C.c_size_t, C.c_int)
@@ -385,6 +386,7 @@ COOP_TUNE_PIECE_LEN = 4
 COOP_TUNE_BLEND_CANDIDATES = 5
 COOP_TUNE_DEFER_SIZES = 6
 COOP_TUNE_UNIQUE = 7
+COOP_TUNE_ENUM_DEGREE = 8
 
 
 def coop_tune(knob, value):

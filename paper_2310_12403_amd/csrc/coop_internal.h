@@ -15,6 +15,8 @@ enum KernelId {
   K_LABOR_OVERFLOW,  // LABOR-0 second scan of overflowed rows
   K_LABOR_EXACT,     // LABOR-0, c > 0: exact blend of the candidates
   K_SEGMENTS,        // LABOR-0 per-destination list records and keep thresholds
+  K_ENUM_LIST,       // LABOR-0 from the other side: vertices with a small variate, listed through the inverse mixer
+  K_ENUM_WALK,       // LABOR-0 from the other side: their lists walked, kept edges of the long destinations found
   K_NS_COUNT,        // NS count pass (min(k, d))
   K_NS_FILL,         // NS selection + fill pass
   K_NS_SELECT,       // NS, c > 0: exact blend of the candidates + selection
@@ -68,6 +70,7 @@ struct Ctl {
   int32_t n_overflow;    // LABOR-0 destinations whose staging row overflowed (this layer and earlier)
   int32_t cand_overflow; // blended LABOR-0: the candidate buffer of the exact stage was too small (the pass is redone)
   int32_t uniq_overflow; // dedup by partition: a bucket held more distinct vertices than its table (redone with the table in HBM)
+  int32_t pad[2];
 };
 
 // Landing pad of the control block in mapped pinned host memory (see read_ctl).
@@ -166,4 +169,6 @@ struct coop_graph {
   const int64_t* indptr;
   const int32_t* indices;
   int64_t n_vertices, n_edges;
+  bool symmetric;     // COOP_SYMMETRIC: sorted lists, every edge stored both ways
+  uint32_t* rev_pos;  // then: for the edge t -> s at position e of indices, the position of s in t's list (owned, device)
 };

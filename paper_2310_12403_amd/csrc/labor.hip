@@ -45,6 +45,150 @@ struct LayerChunks {
   }
 };
 
+// ---- LABOR-0 from the other side (c = 0, symmetric graph) ----------------------------------------------------------
+// R_t = mix(t ^ K0) ^ K1 is a bijection of the 32-bit integers, so the vertices with R_t <= u_max can be listed without
+// looking at the graph: t = unmix(u ^ K1) ^ K0 for u = 0 .. u_max, kept if t < |V|.  A destination s with a list longer
+// than D keeps exactly the neighbours with R_t <= floor(k 2^32 / d_s) < k 2^32 / D: all of them are among the
+// |V| k / D vertices listed for u_max = floor(k 2^32 / (D + 1)).  On a symmetric graph "t is a neighbour of s" can be
+// decided from t's side: the kernel walks the (mostly short) lists of the listed vertices, looks every entry s up in the
+// table of long destinations, and where R_t is within that destination's threshold it has found a kept edge, whose
+// position in the destination's own list comes from the graph handle's index of reverse positions.  The long lists,
+// most of the entries that a scan would have to read, are never read.
+__device__ __forceinline__ uint32_t long_slot(uint32_t s) { return (uint32_t)(((uint64_t)s * 0x9E3779B97F4A7C15ull) >> 32); }
+// a slot of the table of long destinations: key = vertex + 1 (0: empty), its list index, its thresholds; one 32-byte
+// sector.  Open addressing, and no key lies further than kLongProbes slots from its home: a table too full for that
+// makes the pass fall back to the ordinary scan.
+struct alignas(32) LongSlot { uint32_t key, list, thr[kMaxFuse], pad[2]; };
+constexpr uint32_t kLongProbes = 64;
+
+struct EnumItem { int64_t beg; uint32_t len, t, u, pad; };  // up to kEnumItem entries of listed vertex t's list; u = R_t
+constexpr uint32_t kEnumItem = 64;         // entries per item: 16 lanes walk it, 4 entries each, loaded together
+constexpr uint32_t kEnumListSpan = 16384;   // variates per block of k_enum_list
+constexpr uint32_t kEnumListBuf = 1024;    // vertices a block collects before it writes their items out
+
+struct EnumOut {
+  EnumItem* item[kMaxFuse];   // [item_cap] per covered layer
+  uint32_t* n_item;           // [kMaxFuse]
+  uint32_t item_cap;
+};
+
+// blockIdx.y = covered layer f: lists the vertices with R_t <= u_max[f].  A block takes kEnumListSpan consecutive
+// variates, collects the vertices they belong to in LDS, fetches their list bounds, and writes their lists, cut into
+// items, to the layer's item list: one reservation (a same-address atomic) per flush (one in 40 of the variates of a
+// papers100M-sized graph gives a vertex).
+__global__ __launch_bounds__(kBlock) void k_enum_list(FusedKeys keys, uint32_t um0, uint32_t um1, uint32_t um2, uint32_t um3,
+                                                      int64_t n_vertices, const int64_t* __restrict__ g_indptr, EnumOut eo, Ctl* ctl) {
+  __shared__ uint2 buf[kEnumListBuf];     // (t, u)
+  __shared__ int64_t s_beg[kEnumListBuf];
+  __shared__ uint32_t s_d[kEnumListBuf], s_at[kEnumListBuf];
+  __shared__ uint16_t s_long[kEnumListBuf];  // the collected vertices that give more than one item
+  __shared__ uint32_t n_buf, n_local, n_long, base;
+  const int f = blockIdx.y;
+  const uint32_t u_max = f == 0 ? um0 : f == 1 ? um1 : f == 2 ? um2 : um3;
+  const uint32_t K0 = keys.K[f].Ka[0], K1 = keys.K[f].Ka[1];
+  const uint64_t first = (uint64_t)blockIdx.x * kEnumListSpan;
+  if (first > u_max) return;  // block-uniform
+  if (threadIdx.x == 0) { n_buf = 0; n_local = 0; n_long = 0; }
+  __syncthreads();
+  auto flush = [&]() {  // block-uniform call, after a barrier
+    const uint32_t nb = n_buf;  // <= kEnumListBuf: a step adds at most kBlock and is taken only when that many fit
+    for (uint32_t i = threadIdx.x; i < nb; i += kBlock) {
+      const uint32_t t = buf[i].x;
+      const int64_t beg = g_indptr[t];
+      const uint32_t d = (uint32_t)(g_indptr[t + 1] - beg);  // (0: a vertex without neighbours is nobody's neighbour)
+      s_beg[i] = beg;
+      s_d[i] = d;
+      if (d != 0) s_at[i] = atomicAdd(&n_local, (d + kEnumItem - 1) / kEnumItem);
+      if (d > kEnumItem) s_long[atomicAdd(&n_long, 1u)] = (uint16_t)i;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) base = n_local ? atomicAdd(&eo.n_item[f], n_local) : 0u;
+    __syncthreads();
+    if (base + n_local > eo.item_cap) {
+      if (threadIdx.x == 0) atomicOr(&ctl->cand_overflow, 1);  // (the pass is redone without this shortcut)
+    } else {
+      for (uint32_t i = threadIdx.x; i < nb; i += kBlock) {  // a thread per vertex with one item
+        const uint32_t d = s_d[i];
+        if (d != 0 && d <= kEnumItem) eo.item[f][base + s_at[i]] = EnumItem{s_beg[i], d, buf[i].x, buf[i].y, 0u};
+      }
+      for (uint32_t v = 0; v < n_long; ++v) {                // the block together for each of the others
+        const uint32_t i = s_long[v];
+        const uint32_t d = s_d[i];
+        const uint2 tu = buf[i];
+        const int64_t beg = s_beg[i];
+        EnumItem* to = eo.item[f] + base + s_at[i];
+        for (uint32_t q = threadIdx.x; q * kEnumItem < d; q += kBlock) {
+          const uint32_t off = q * kEnumItem;
+          to[q] = EnumItem{beg + off, d - off < kEnumItem ? d - off : kEnumItem, tu.x, tu.y, 0u};
+        }
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { n_buf = 0; n_local = 0; n_long = 0; }
+    __syncthreads();
+  };
+  for (uint32_t step = 0; step < kEnumListSpan; step += kBlock) {
+    const uint64_t u = first + step + threadIdx.x;
+    const uint32_t t = unmix32((uint32_t)u ^ K1) ^ K0;
+    if (u <= u_max && (uint64_t)t < (uint64_t)n_vertices) buf[atomicAdd(&n_buf, 1u)] = make_uint2(t, (uint32_t)u);
+    __syncthreads();
+    const bool nearly_full = n_buf > kEnumListBuf - kBlock;  // read by everyone before anyone adds again
+    __syncthreads();
+    if (nearly_full) flush();
+  }
+  flush();
+}
+
+// one entry s of the list of listed vertex t (variate u, layer f), whose home slot `head` of the table of long
+// destinations has been loaded: a kept edge t -> s if s is a long destination of this pass and u is within its threshold
+__device__ __forceinline__ void enum_visit(const uint32_t* __restrict__ rev_pos, const LongSlot* __restrict__ long_tab, uint32_t long_mask,
+                                           uint32_t stage_cap, const ScanOut& out, Ctl* ctl, int f, uint32_t t, uint32_t u, uint32_t s,
+                                           int64_t pos, uint32_t h, uint4 head) {
+  for (uint32_t probe = 1; head.x != s + 1; ++probe) {  // (rarely more than one round)
+    if (head.x == 0 || probe >= kLongProbes) return;    // not a long destination
+    h = (h + 1) & long_mask;
+    head = *reinterpret_cast<const uint4*>(&long_tab[h]);
+  }
+  const uint32_t thr = f == 0 ? head.z : f == 1 ? head.w : long_tab[h].thr[f];
+  if (u > thr) return;
+  const uint32_t list = head.y;
+  const uint32_t j = rev_pos[pos];  // where t stands in the destination's own list
+  const uint32_t at = (uint32_t)atomicAdd(&out.cnt[f][list], 1);
+  if (at < stage_cap) out.stage[f][(size_t)list * stage_cap + at] = StageEntry{(int32_t)t, j};
+  else if (at == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
+}
+
+// blockIdx.y = covered layer f: 16 lanes per item; a lane's four entries are requested together, and so are their
+// four table slots
+__global__ __launch_bounds__(kBlock) void k_enum_walk(const int32_t* __restrict__ g_indices, const uint32_t* __restrict__ rev_pos,
+                                                      const LongSlot* __restrict__ long_tab, uint32_t long_mask,
+                                                      uint32_t stage_cap, ScanOut out, EnumOut eo, Ctl* ctl) {
+  const int f = blockIdx.y;
+  if (ctl->cand_overflow != 0) return;  // (some items were not written, or some destinations not entered: the pass is redone)
+  uint32_t total = eo.n_item[f];
+  if (total > eo.item_cap) total = eo.item_cap;
+  const uint32_t sub = threadIdx.x & 15u;
+  for (uint64_t c = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) >> 4; c < total; c += ((uint64_t)gridDim.x * kBlock) >> 4) {
+    const EnumItem it = eo.item[f][c];
+    uint32_t s4[4], h4[4];
+    uint4 head4[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t j = (uint32_t)e * 16u + sub;
+      s4[e] = (uint32_t)g_indices[it.beg + (j < it.len ? j : it.len - 1)];  // (len >= 1; a lane past the end repeats the last entry)
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      h4[e] = long_slot(s4[e]) & long_mask;
+      head4[e] = *reinterpret_cast<const uint4*>(&long_tab[h4[e]]);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if ((uint32_t)e * 16u + sub < it.len)
+        enum_visit(rev_pos, long_tab, long_mask, stage_cap, out, ctl, f, it.t, it.u, s4[e], it.beg + (uint32_t)e * 16u + sub, h4[e], head4[e]);
+  }
+}
+
 // list records of the destinations scanned in this pass, and their keep thresholds for the nf covered layers
 // (pthr, lim2: the blended path's first and second filter thresholds, null when c = 0)
 constexpr int kSegBlock = 1024;  // large blocks: one queue reservation (a same-address atomic) per 1024 destinations
@@ -54,13 +198,15 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
                                                      uint32_t* __restrict__ thr, PreThr* __restrict__ pthr, float* __restrict__ lim2,
                                                      double cw, double sw, int queued, Ctl* ctl,
                                                      uint32_t piece_len, Piece* __restrict__ pieces, uint32_t piece_cap,
-                                                     uint32_t* __restrict__ piece_count, ScanOut out) {
+                                                     uint32_t* __restrict__ piece_count, ScanOut out, uint32_t enum_degree,
+                                                     LongSlot* __restrict__ long_tab, uint32_t long_mask) {
   __shared__ uint32_t s_wave_at[kSegBlock / kWave];
   __shared__ uint32_t s_base, s_total;
   const int64_t i = (int64_t)blockIdx.x * kSegBlock + threadIdx.x;
   const bool live = i < n;
   Segment g{0, 0, 0};
   bool sampled = live;  // every covered layer keeps a proper subset (d > k)
+  uint32_t thr_mine[kMaxFuse] = {0, 0, 0, 0};
   if (live) {
     const int32_t s = dst[i];
     if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
@@ -76,6 +222,7 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
         const uint32_t t = g.d > ks[f] ? (uint32_t)(((uint64_t)ks[f] << 32) / (uint64_t)g.d) : kAllThr;
         sampled &= t != kAllThr;
         thr[(int64_t)f * n + i] = t;
+        thr_mine[f] = t;
         if (pthr) {
           PreThr pt = blend_first_thresholds(t, cw, sw);
           pt.keep2 = blend_keep_threshold(t, cw + sw);
@@ -84,6 +231,29 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
         }
         if (queued) out.cnt[f][i] = 0;  // kept edges are counted by atomics
       }
+  }
+  // A list longer than enum_degree (when that is not 0) is not scanned at all: its kept neighbours are found from the
+  // other side (k_enum_*).  The destination is entered in the table that maps such vertices to their list.
+  const bool from_other_side = enum_degree != 0 && sampled && g.d > enum_degree;
+  if (from_other_side) {
+    g.split = 1;  // (the scan leaves it alone, like a list cut into pieces)
+#pragma unroll
+    for (int f = 0; f < kMaxFuse; ++f)
+      if (f < nf) out.cnt[f][i] = 0;  // kept edges are counted by atomics
+    const unsigned long long mine = ((unsigned long long)(uint32_t)i << 32) | ((uint32_t)dst[i] + 1u);  // (key, list)
+    uint32_t h = long_slot((uint32_t)dst[i]) & long_mask;
+    bool entered = false;
+    for (uint32_t probe = 0; probe < kLongProbes && !entered; ++probe) {
+      if (atomicCAS(reinterpret_cast<unsigned long long*>(&long_tab[h]), 0ull, mine) == 0ull) {
+        entered = true;
+#pragma unroll
+        for (int f = 0; f < kMaxFuse; ++f)
+          if (f < nf) long_tab[h].thr[f] = thr_mine[f];
+      }
+      h = (h + 1) & long_mask;
+    }
+    if (!entered) atomicOr(&ctl->cand_overflow, 1);  // (the pass is redone without this shortcut)
+    sampled = false;  // no pieces
   }
   if (piece_len == 0) {  // wave-uniform
     if (live) seg[i] = g;
@@ -687,6 +857,11 @@ __global__ __launch_bounds__(kBlock) void k_labor_exact(CandOut cand, const uint
   }
 }
 
+__global__ void k_enum_redo(Ctl* ctl, uint32_t* piece_count) {
+  ctl->cand_overflow = 0;
+  *piece_count = 0;
+}
+
 __global__ void k_labor_redo(Ctl* ctl, uint32_t* piece_count, uint32_t* cand_count) {  // kCandSub threads
   if (threadIdx.x == 0) {
     ctl->cand_overflow = 0;
@@ -871,7 +1046,9 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
   if (nc == 0) { ch.seg[0] = ps.seg; ch.thr[0] = ps.thr; ch.stage[0] = ps.stage[0]; counts.ptr[0] = ps.cnt[0]; nc = 1; }  // n_dst == 0
   ch.n_chunks = counts.n_chunks = nc;
 
+  bool no_enum = false, used_enum = false;
   for (;;) {
+    used_enum = false;
     if (n_new > 0) {
       ScanOut out{};
       for (int f = 0; f < ps.nf; ++f) { out.stage[f] = ps.stage[f]; out.cnt[f] = ps.cnt[f]; }
@@ -882,10 +1059,57 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
         cand.count = cand_count;
         if (alloc.failed) return COOP_E_NOMEM;
       }
+      // ---- the longest lists from the other side (see k_enum_list) ---------------------------------------------------
+      uint32_t kmax_pass = 0;
+      for (int f = 0; f < ps.nf; ++f) kmax_pass = ks[f] > kmax_pass ? ks[f] : kmax_pass;
+      // (the walk costs the same whatever the number of destinations: it pays only for a pass over many lists; the test
+      // knob value below 8192 applies always)
+      const bool enough = n_new >= 65536 || g_enum_degree < 8192;
+      const uint32_t enum_degree = cx.g->symmetric && !cx.blend && !no_enum && kmax_pass <= 64 && enough ? (uint32_t)g_enum_degree : 0u;
+      used_enum = enum_degree != 0;
+      LongSlot* long_tab = nullptr;
+      uint32_t long_mask = 0;
+      EnumOut eo{};
+      uint32_t u_max[kMaxFuse] = {0, 0, 0, 0}, um_most = 0;
+      if (enum_degree != 0) {
+        // the table of long destinations: twice the number there can be (|E| / D lists are that long, at most), but no
+        // more than 65536 slots or a quarter of the destinations, whichever is more: the table then stays in L2, and a
+        // pass with more long lists than that is redone the ordinary way
+        int64_t most = cx.g->n_edges / enum_degree + 1;
+        if (most > n_new) most = n_new;
+        const int64_t ceiling = n_new / 4 > 65536 ? n_new / 4 : 65536;
+        uint32_t slots = 1024;
+        while ((int64_t)slots < 2 * most && (int64_t)slots * 2 <= ceiling) slots <<= 1;
+        long_mask = slots - 1;
+        eo.n_item = (uint32_t*)alloc.get<LongSlot>((int64_t)slots + 1, COOP_TAG_SCRATCH);  // the counters, then the table
+        long_tab = (LongSlot*)eo.n_item + 1;
+        for (int f = 0; f < ps.nf; ++f) {
+          u_max[f] = (uint32_t)(((uint64_t)ks[f] << 32) / ((uint64_t)enum_degree + 1));
+          um_most = u_max[f] > um_most ? u_max[f] : um_most;
+        }
+        const double expect = (double)cx.g->n_vertices * ((double)um_most + 1.0) / 4294967296.0;  // listed vertices
+        // items: a listed vertex gives d / kEnumItem + 1 of them; the listed vertices' lists hold |E| u_max / 2^32 entries
+        // in expectation, and four times that is allowed for (a pass that needs more, because some huge hub is listed,
+        // is redone the ordinary way)
+        const double entries = (double)cx.g->n_edges * ((double)um_most + 1.0) / 4294967296.0;
+        const double items = expect + 8.0 * sqrt(expect) + 1024.0 + 4.0 * entries / kEnumItem;
+        eo.item_cap = (uint32_t)(items < 268435456.0 ? items : 268435456.0);
+        for (int f = 0; f < ps.nf; ++f) eo.item[f] = alloc.get<EnumItem>(eo.item_cap, COOP_TAG_SCRATCH);
+        if (alloc.failed) return COOP_E_NOMEM;
+        fill_u64((uint64_t*)eo.n_item, ((int64_t)slots + 1) * (sizeof(LongSlot) / 8), 0, s);
+      }
       COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
                   dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, cx.cw, cx.sw,
                   cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
-                  piece_len, pieces, piece_cap, cx.d_piece_count + l, out);
+                  piece_len, pieces, piece_cap, cx.d_piece_count + l, out, enum_degree, long_tab, long_mask);
+      if (enum_degree != 0) {
+        const unsigned list_blocks = blocks_for((int64_t)um_most + 1, kEnumListSpan);
+        COOP_LAUNCH(K_ENUM_LIST, k_enum_list, dim3(list_blocks, ps.nf), dim3(kBlock), 0, s, keys, u_max[0], u_max[1], u_max[2], u_max[3],
+                    cx.g->n_vertices, cx.g->indptr, eo, cx.d_ctl);
+        const int64_t walk_blocks = blocks_for((int64_t)eo.item_cap * 16, kBlock);
+        COOP_LAUNCH(K_ENUM_WALK, k_enum_walk, dim3((unsigned)(walk_blocks < 16384 ? walk_blocks : 16384), ps.nf), dim3(kBlock), 0, s,
+                    cx.g->indices, (const uint32_t*)cx.g->rev_pos, (const LongSlot*)long_tab, long_mask, cap, out, eo, cx.d_ctl);
+      }
       // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
       int lpw = g_lists_per_wave;
       if (lpw == 0) lpw = n_new >= 65536 ? (cx.blend && cx.vec4 ? 8 : 4) : 1;  // blended: fuller waves at the fp32 stage
@@ -917,6 +1141,11 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     scan_chunks_to_i64(counts, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, &pub);  // m_l = indptr[n_dst]
     const int rc = wait_ctl(pub, cx.h_ctl, s);
     if (rc != COOP_OK) return rc;
+    if (used_enum && cx.h_ctl->cand_overflow != 0) {  // the lists of the listed vertices did not fit: once more, every list scanned
+      no_enum = true;
+      hipLaunchKernelGGL(k_enum_redo, dim3(1), dim3(1), 0, s, cx.d_ctl, cx.d_piece_count + l);
+      continue;
+    }
     if (!queued || cx.h_ctl->cand_overflow == 0) break;
     // the candidate buffer of the exact stage was too small (counts are incomplete): once more with 8 times the room
     if (cand_cap >= ((int64_t)1 << 30)) return COOP_E_CAPACITY;

@@ -23,7 +23,7 @@ struct Prof {
 } g_prof;
 
 const char* const kKernelNames[K_COUNT_] = {
-    "fill", "labor_scan", "labor_fill", "labor_fill_overflow", "labor_exact", "segments", "ns_count", "ns_fill", "ns_select", "rw_walk", "rw_fill", "scan_local", "scan_offset",
+    "fill", "labor_scan", "labor_fill", "labor_fill_overflow", "labor_exact", "segments", "enum_list", "enum_walk", "ns_count", "ns_fill", "ns_select", "rw_walk", "rw_fill", "scan_local", "scan_offset",
     "unique_insert", "unique_flag", "unique_relabel", "unique_part_count", "unique_part_scatter", "unique_part_first", "copy_ids", "gather", "gather_mean", "validate_csr",
     "cache_lookup", "cache_select_hist", "cache_select_pick", "cache_evict", "cache_miss_rows", "cache_hit_rows"};
 
@@ -312,6 +312,33 @@ __global__ __launch_bounds__(kBlock) void k_validate_csr(const int64_t* __restri
   if (b) atomicOr(bad, 1);
 }
 
+// COOP_SYMMETRIC: checks that the lists are strictly ascending and that every edge t in N(s) has its reverse s in N(t),
+// and records where: rev[e] = position of s in t's list, for the edge at position e of the indices array (bisection).
+__global__ __launch_bounds__(kBlock) void k_build_reverse(const int64_t* __restrict__ indptr, const int32_t* __restrict__ indices,
+                                                          int64_t nv, uint32_t* __restrict__ rev, int32_t* bad) {
+  // one wave per vertex at a time, lanes over its list
+  if (*bad != 0) return;  // (a malformed CSR was reported by the kernel before this one: its offsets cannot be trusted)
+  const int64_t n_waves = ((int64_t)gridDim.x * kBlock) >> 6;
+  bool b = false;
+  for (int64_t s = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6; s < nv; s += n_waves) {
+    const int64_t beg = indptr[s], end = indptr[s + 1];
+    for (int64_t e = beg + lane_id(); e < end; e += kWave) {
+      const int32_t t = indices[e];
+      if (e > beg && indices[e - 1] >= t) b = true;
+      const int64_t tb = indptr[t];
+      const int64_t td = indptr[t + 1] - tb;
+      int64_t lo = 0, hi = td;
+      while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (indices[tb + mid] < (int32_t)s) lo = mid + 1; else hi = mid;
+      }
+      if (lo >= td || indices[tb + lo] != (int32_t)s) { b = true; lo = 0; }
+      rev[e] = (uint32_t)lo;
+    }
+  }
+  if (b) atomicOr(bad, 1);
+}
+
 }  // namespace coop
 
 using namespace coop;
@@ -351,29 +378,47 @@ int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_ver
   if (!out) return COOP_E_NULL;
   *out = nullptr;
   if (!indptr || (!indices && n_edges > 0)) return COOP_E_NULL;
-  if (n_vertices < 0 || n_vertices >= ((int64_t)1 << 31) || n_edges < 0 || (flags & ~COOP_VALIDATE)) return COOP_E_ARG;
-  if (flags & COOP_VALIDATE) {
+  if (n_vertices < 0 || n_vertices >= ((int64_t)1 << 31) || n_edges < 0 || (flags & ~(COOP_VALIDATE | COOP_SYMMETRIC))) return COOP_E_ARG;
+  uint32_t* rev = nullptr;
+  if (flags & (COOP_VALIDATE | COOP_SYMMETRIC)) {  // (the reverse index is built from offsets and ids that have been checked)
     hipStream_t s = (hipStream_t)stream;
     int32_t* d_bad = nullptr;
     COOP_HIP_TRY(hipMalloc((void**)&d_bad, sizeof(int32_t)));
+    if ((flags & COOP_SYMMETRIC) && n_edges > 0 && hipMalloc((void**)&rev, (size_t)n_edges * sizeof(uint32_t)) != hipSuccess) {
+      (void)hipFree(d_bad);
+      return COOP_E_NOMEM;
+    }
     int32_t h_bad = 0;
     hipError_t e = hipMemcpyAsync(d_bad, &h_bad, sizeof(int32_t), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) {
       COOP_LAUNCH(K_VALIDATE, k_validate_csr, dim3(256 * 16), dim3(kBlock), 0, s, indptr, indices, n_vertices, n_edges, d_bad);
-      e = hipMemcpyAsync(&h_bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+      if ((flags & COOP_SYMMETRIC) && n_vertices > 0 && n_edges > 0) {
+        // (a grid holds fewer than 2^32 threads: the waves stride over the vertices)
+        const int64_t want = (n_vertices * kWave + kBlock - 1) / kBlock;
+        COOP_LAUNCH(K_VALIDATE, k_build_reverse, dim3((unsigned)(want < (1 << 22) ? want : (1 << 22))), dim3(kBlock), 0, s, indptr, indices,
+                    n_vertices, rev, d_bad);
+      }
+      e = hipGetLastError();
+      if (e == hipSuccess) e = hipMemcpyAsync(&h_bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost, s);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     (void)hipFree(d_bad);
-    if (e != hipSuccess) return COOP_E_HIP;
-    if (h_bad) return COOP_E_GRAPH;
+    if (e != hipSuccess || h_bad) {
+      if (rev) (void)hipFree(rev);
+      return e != hipSuccess ? COOP_E_HIP : COOP_E_GRAPH;
+    }
   }
-  coop_graph* g = new (std::nothrow) coop_graph{indptr, indices, n_vertices, n_edges};
-  if (!g) return COOP_E_NOMEM;
+  coop_graph* g = new (std::nothrow) coop_graph{indptr, indices, n_vertices, n_edges, (flags & COOP_SYMMETRIC) != 0 && n_edges > 0, rev};
+  if (!g) {
+    if (rev) (void)hipFree(rev);
+    return COOP_E_NOMEM;
+  }
   *out = g;
   return COOP_OK;
 }
 
 int coop_graph_free(coop_graph* g) {
+  if (g && g->rev_pos) (void)hipFree(g->rev_pos);
   delete g;
   return COOP_OK;
 }

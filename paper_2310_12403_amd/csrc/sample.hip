@@ -74,6 +74,7 @@ int g_fuse_layers = 1;         // COOP_TUNE_FUSE_LAYERS
 int g_piece_len = 4096;        // COOP_TUNE_PIECE_LEN
 int64_t g_blend_candidates = 0;  // COOP_TUNE_BLEND_CANDIDATES (0 = automatic)
 int g_defer_sizes = 1;         // COOP_TUNE_DEFER_SIZES
+int g_enum_degree = 8192;      // COOP_TUNE_ENUM_DEGREE
 
 // puts back what a LABOR-0 pass at layer l changed in the control data, before the pass is run again
 __global__ void k_reset_layer(Ctl* ctl, uint32_t* piece_count) {
@@ -110,6 +111,10 @@ extern "C" int coop_tune(int knob, int64_t value) {
     case COOP_TUNE_UNIQUE:
       if (value < 0 || value > 3) return COOP_E_ARG;
       g_unique_mode = (int)value;
+      return COOP_OK;
+    case COOP_TUNE_ENUM_DEGREE:
+      if (value != 0 && (value < 64 || value > ((int64_t)1 << 30))) return COOP_E_ARG;
+      g_enum_degree = (int)value;
       return COOP_OK;
     case COOP_TUNE_DEFER_SIZES:
       if (value < 0 || value > 2) return COOP_E_ARG;

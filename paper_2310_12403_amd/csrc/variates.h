@@ -37,6 +37,16 @@ __host__ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
   return x;
 }
 
+// the mixer is a bijection of the 32-bit integers: its inverse (0x43021123, 0x1D69E2A5: the multipliers' inverses mod 2^32)
+__host__ __device__ __forceinline__ uint32_t unmix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x43021123u;
+  x ^= (x >> 15) ^ (x >> 30);
+  x *= 0x1D69E2A5u;
+  x ^= x >> 16;
+  return x;
+}
+
 // Philox4x32-10 (Salmon et al., SC'11); host side, once per layer, for the key words.
 inline void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
   uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];

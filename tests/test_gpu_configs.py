@@ -20,7 +20,9 @@ def P():
 
 def load(P, name):
     indptr, indices = synth.make_graph(name, device="cuda")
-    g = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE)
+    # (the generator's graphs store every edge both ways in sorted lists: registered as such, as bench.py does, so that
+    # LABOR-0 with independent variates takes the path that bench.py times)
+    g = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE | P.COOP_SYMMETRIC)
     return g, indptr.cpu().numpy(), indices.cpu().numpy()
 
 

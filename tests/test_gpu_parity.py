@@ -19,12 +19,12 @@ def P():
 
 
 class G:
-    def __init__(self, P, indptr, indices):
+    def __init__(self, P, indptr, indices, flags=None):
         self.indptr_h = indptr.cpu().numpy()
         self.indices_h = indices.cpu().numpy()
         self.indptr_d = indptr.cuda()
         self.indices_d = indices.cuda()
-        self.graph = P.coop_graph_load(self.indptr_d, self.indices_d, P.COOP_VALIDATE)
+        self.graph = P.coop_graph_load(self.indptr_d, self.indices_d, P.COOP_VALIDATE if flags is None else flags)
         self.n = len(self.indptr_h) - 1
 
 
@@ -621,3 +621,70 @@ def test_randomized_configurations(P, draw_seed=20240, cases=160):
     finally:
         for kn, v in zip(knobs, defaults):
             P.coop_tune(kn, v)
+
+
+@pytest.mark.parametrize("degree", [64, 300, 8192])
+def test_labor_long_lists_from_the_other_side(P, tiny, medium, degree):
+    """Graphs registered as symmetric: LABOR-0 with independent variates finds the kept neighbours of lists longer than
+    `degree` from the neighbours' side (inverse mixer, walk of the listed vertices' lists, bisection for the position);
+    the bytes must not change.  Dependent variates and NS take the ordinary path on the same handle."""
+    try:
+        P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, degree)
+        flags = P.COOP_VALIDATE | P.COOP_SYMMETRIC
+        gm = G(P, torch.from_numpy(medium.indptr_h), torch.from_numpy(medium.indices_h), flags)
+        gt = G(P, torch.from_numpy(tiny.indptr_h), torch.from_numpy(tiny.indices_h), flags)
+        seeds = synth.seed_batches(gm.n, 4000, seed=91)(0).numpy()
+        small = synth.seed_batches(gt.n, 700, seed=92)(0).numpy()
+        hubs = np.argsort(-np.diff(gm.indptr_h))[:300].astype(np.int32)
+        for mode in (1, 0, 2):
+            P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, mode)
+            compare(P, gm, seeds, (10, 10, 10), R.LABOR0, it=3, seed=91)
+            compare(P, gm, hubs, (5, 25), R.LABOR0, it=4, seed=92)
+            compare(P, gt, small, (10, 10, 10), R.LABOR0, it=5, seed=93)
+        P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, 1)
+        compare(P, gm, seeds, (64, 3), R.LABOR0, it=6, seed=94)             # the largest fanout that is served this way
+        compare(P, gm, seeds[:500], (65, 3), R.LABOR0, it=6, seed=95)       # the first that is not
+        compare(P, gm, seeds[:800], (10, 10), R.LABOR0, it=7, kappa=4, seed=96)
+        compare(P, gm, seeds[:800], (10, 10), R.NS, it=8, seed=97)
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 4)                               # rows overflow: the ordered second scan takes over
+        compare(P, gm, hubs, (10, 10), R.LABOR0, it=9, seed=98)
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 0)
+        for defer in (0, 2):
+            P.coop_tune(P.COOP_TUNE_DEFER_SIZES, defer)
+            compare(P, gm, seeds[:1500], (10, 10, 10), R.LABOR0, it=10, seed=99)
+    finally:
+        P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, 8192)
+        P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, 1)
+        P.coop_tune(P.COOP_TUNE_STAGE_CAP, 0)
+        P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
+
+
+def test_symmetric_flag_is_checked(P, tiny):
+    """COOP_SYMMETRIC: a graph with one edge that lacks its reverse, or with an unsorted list, is refused."""
+    flags = P.COOP_VALIDATE | P.COOP_SYMMETRIC
+    P.coop_graph_load(tiny.indptr_d, tiny.indices_d, flags)  # the tiny graph is symmetric
+    ip, ix = tiny.indptr_h, tiny.indices_h
+    deg = np.diff(ip)
+    v = int(np.argmax(deg))                      # the hub: drop the hub from the list of one of its neighbours
+    w = int(ix[ip[v]])
+    keep = np.ones(len(ix), dtype=bool)
+    pos = ip[w] + int(np.searchsorted(ix[ip[w]:ip[w + 1]], v))
+    assert ix[pos] == v
+    keep[pos] = False
+    ix2 = ix[keep]
+    ip2 = ip.copy()
+    ip2[w + 1:] -= 1
+    d_ip, d_ix = torch.from_numpy(ip2).cuda(), torch.from_numpy(ix2).cuda()
+    with pytest.raises(P.CoopError) as e:
+        P.coop_graph_load(d_ip, d_ix, flags)
+    assert e.value.code == -8
+    swapped = ix.copy()
+    a = int(ip[v])
+    swapped[a], swapped[a + 1] = swapped[a + 1], swapped[a]
+    with pytest.raises(P.CoopError) as e:
+        P.coop_graph_load(tiny.indptr_d, torch.from_numpy(swapped).cuda(), flags)
+    assert e.value.code == -8
+    # COOP_SYMMETRIC alone checks as much (the index of reverse positions cannot be built otherwise)
+    with pytest.raises(P.CoopError) as e:
+        P.coop_graph_load(d_ip, d_ix, P.COOP_SYMMETRIC)
+    assert e.value.code == -8
