@@ -60,11 +60,17 @@ __device__ __forceinline__ uint32_t long_slot(uint32_t s) { return (uint32_t)(((
 // makes the pass fall back to the ordinary scan.
 struct alignas(32) LongSlot { uint32_t key, list, thr[kMaxFuse], pad[2]; };
 constexpr uint32_t kLongProbes = 64;
+// In front of the table, a bit per hash value says whether any long destination has it: the walk keeps these bits in
+// LDS, and goes to the table (in L2) only for the entries that pass, the long destinations' own and a few per cent more.
+constexpr uint32_t kLongBits = 1u << 18;  // 32 KB
+constexpr int kWalkBlock = 512;           // three blocks per CU, each with the bits in LDS
+__device__ __forceinline__ uint32_t long_bit(uint32_t s) { return long_slot(s) >> 14; }
 
 struct EnumItem { int64_t beg; uint32_t len, t, u, pad; };  // up to kEnumItem entries of listed vertex t's list; u = R_t
 constexpr uint32_t kEnumItem = 64;         // entries per item: 16 lanes walk it, 4 entries each, loaded together
 constexpr uint32_t kEnumListSpan = 16384;   // variates per block of k_enum_list
-constexpr uint32_t kEnumListBuf = 1024;    // vertices a block collects before it writes their items out
+constexpr uint32_t kEnumListStep = 1024;   // variates per step of a block (4 per thread), between two barriers
+constexpr uint32_t kEnumListBuf = 2048;    // vertices a block collects before it writes their items out
 
 struct EnumOut {
   EnumItem* item[kMaxFuse];   // [item_cap] per covered layer
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(kBlock) void k_enum_list(FusedKeys keys, uint32_t u
   if (threadIdx.x == 0) { n_buf = 0; n_local = 0; n_long = 0; }
   __syncthreads();
   auto flush = [&]() {  // block-uniform call, after a barrier
-    const uint32_t nb = n_buf;  // <= kEnumListBuf: a step adds at most kBlock and is taken only when that many fit
+    const uint32_t nb = n_buf;  // <= kEnumListBuf: a step adds at most kEnumListStep and is taken only when that many fit
     for (uint32_t i = threadIdx.x; i < nb; i += kBlock) {
       const uint32_t t = buf[i].x;
       const int64_t beg = g_indptr[t];
@@ -127,65 +133,102 @@ __global__ __launch_bounds__(kBlock) void k_enum_list(FusedKeys keys, uint32_t u
     if (threadIdx.x == 0) { n_buf = 0; n_local = 0; n_long = 0; }
     __syncthreads();
   };
-  for (uint32_t step = 0; step < kEnumListSpan; step += kBlock) {
-    const uint64_t u = first + step + threadIdx.x;
-    const uint32_t t = unmix32((uint32_t)u ^ K1) ^ K0;
-    if (u <= u_max && (uint64_t)t < (uint64_t)n_vertices) buf[atomicAdd(&n_buf, 1u)] = make_uint2(t, (uint32_t)u);
+  for (uint32_t step = 0; step < kEnumListSpan; step += kEnumListStep) {
+#pragma unroll
+    for (uint32_t q = 0; q < kEnumListStep; q += kBlock) {
+      const uint64_t u = first + step + q + threadIdx.x;
+      const uint32_t t = unmix32((uint32_t)u ^ K1) ^ K0;
+      if (u <= u_max && (uint64_t)t < (uint64_t)n_vertices) buf[atomicAdd(&n_buf, 1u)] = make_uint2(t, (uint32_t)u);
+    }
     __syncthreads();
-    const bool nearly_full = n_buf > kEnumListBuf - kBlock;  // read by everyone before anyone adds again
+    const bool nearly_full = n_buf > kEnumListBuf - kEnumListStep;  // read by everyone before anyone adds again
     __syncthreads();
     if (nearly_full) flush();
   }
   flush();
 }
 
-// one entry s of the list of listed vertex t (variate u, layer f), whose home slot `head` of the table of long
-// destinations has been loaded: a kept edge t -> s if s is a long destination of this pass and u is within its threshold
-__device__ __forceinline__ void enum_visit(const uint32_t* __restrict__ rev_pos, const LongSlot* __restrict__ long_tab, uint32_t long_mask,
-                                           uint32_t stage_cap, const ScanOut& out, Ctl* ctl, int f, uint32_t t, uint32_t u, uint32_t s,
-                                           int64_t pos, uint32_t h, uint4 head) {
-  for (uint32_t probe = 1; head.x != s + 1; ++probe) {  // (rarely more than one round)
-    if (head.x == 0 || probe >= kLongProbes) return;    // not a long destination
-    h = (h + 1) & long_mask;
-    head = *reinterpret_cast<const uint4*>(&long_tab[h]);
-  }
-  const uint32_t thr = f == 0 ? head.z : f == 1 ? head.w : long_tab[h].thr[f];
-  if (u > thr) return;
-  const uint32_t list = head.y;
-  const uint32_t j = rev_pos[pos];  // where t stands in the destination's own list
-  const uint32_t at = (uint32_t)atomicAdd(&out.cnt[f][list], 1);
-  if (at < stage_cap) out.stage[f][(size_t)list * stage_cap + at] = StageEntry{(int32_t)t, j};
-  else if (at == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
-}
-
-// blockIdx.y = covered layer f: 16 lanes per item; a lane's four entries are requested together, and so are their
-// four table slots
-__global__ __launch_bounds__(kBlock) void k_enum_walk(const int32_t* __restrict__ g_indices, const uint32_t* __restrict__ rev_pos,
-                                                      const LongSlot* __restrict__ long_tab, uint32_t long_mask,
-                                                      uint32_t stage_cap, ScanOut out, EnumOut eo, Ctl* ctl) {
+// blockIdx.y = covered layer f: 16 lanes per item; a lane's four entries are requested together, and so are the table
+// slots of those that pass the bit test
+__global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __restrict__ g_indices, const uint32_t* __restrict__ rev_pos,
+                                                          const uint32_t* __restrict__ long_bits, const LongSlot* __restrict__ long_tab,
+                                                          uint32_t long_mask, uint32_t stage_cap, ScanOut out, EnumOut eo, Ctl* ctl) {
+  __shared__ uint32_t bits[kLongBits / 32];
   const int f = blockIdx.y;
   if (ctl->cand_overflow != 0) return;  // (some items were not written, or some destinations not entered: the pass is redone)
+  for (uint32_t i = threadIdx.x; i < kLongBits / 128; i += kWalkBlock)
+    reinterpret_cast<uint4*>(bits)[i] = reinterpret_cast<const uint4*>(long_bits)[i];
+  __syncthreads();
   uint32_t total = eo.n_item[f];
   if (total > eo.item_cap) total = eo.item_cap;
+  const EnumItem* __restrict__ item_f = f == 0 ? eo.item[0] : f == 1 ? eo.item[1] : f == 2 ? eo.item[2] : eo.item[3];
+  int32_t* __restrict__ cnt_f = f == 0 ? out.cnt[0] : f == 1 ? out.cnt[1] : f == 2 ? out.cnt[2] : out.cnt[3];
+  StageEntry* __restrict__ stage_f = f == 0 ? out.stage[0] : f == 1 ? out.stage[1] : f == 2 ? out.stage[2] : out.stage[3];
   const uint32_t sub = threadIdx.x & 15u;
-  for (uint64_t c = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) >> 4; c < total; c += ((uint64_t)gridDim.x * kBlock) >> 4) {
-    const EnumItem it = eo.item[f][c];
-    uint32_t s4[4], h4[4];
-    uint4 head4[4];
+  const uint32_t groups = (gridDim.x * kWalkBlock) >> 4;
+  for (uint32_t c = (blockIdx.x * kWalkBlock + threadIdx.x) >> 4; c < total; c += groups) {
+    const EnumItem it = item_f[c];
+    uint32_t s4[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const uint32_t j = (uint32_t)e * 16u + sub;
       s4[e] = (uint32_t)g_indices[it.beg + (j < it.len ? j : it.len - 1)];  // (len >= 1; a lane past the end repeats the last entry)
     }
+    uint32_t h4[4];
+    bool maybe[4];
+    uint4 head4[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
+      const uint32_t b = long_bit(s4[e]);
+      maybe[e] = (uint32_t)e * 16u + sub < it.len && ((bits[b >> 5] >> (b & 31u)) & 1u) != 0;
       h4[e] = long_slot(s4[e]) & long_mask;
-      head4[e] = *reinterpret_cast<const uint4*>(&long_tab[h4[e]]);
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-      if ((uint32_t)e * 16u + sub < it.len)
-        enum_visit(rev_pos, long_tab, long_mask, stage_cap, out, ctl, f, it.t, it.u, s4[e], it.beg + (uint32_t)e * 16u + sub, h4[e], head4[e]);
+      if (maybe[e]) head4[e] = *reinterpret_cast<const uint4*>(&long_tab[h4[e]]);
+    // Which entries are long destinations of this pass (the key in a slot is the vertex + 1, 0 an empty slot), and is
+    // R_t within their threshold?  An entry whose home slot holds another key moves on to the next slot; the entries
+    // of a lane do so together, a round of requests at a time.
+    uint32_t list4[4], j4[4], at4[4];
+    bool open4[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) open4[e] = maybe[e];
+    for (uint32_t probe = 1;; ++probe) {
+      bool again = false;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (open4[e]) {
+          if (head4[e].x == s4[e] + 1) {
+            open4[e] = false;
+            list4[e] = head4[e].y;
+            maybe[e] = it.u <= (f == 0 ? head4[e].z : f == 1 ? head4[e].w : long_tab[h4[e]].thr[f]);
+          } else if (head4[e].x == 0 || probe >= kLongProbes) {
+            open4[e] = false;
+            maybe[e] = false;
+          } else {
+            h4[e] = (h4[e] + 1) & long_mask;
+            again = true;
+          }
+        }
+      if (!again) break;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (open4[e]) head4[e] = *reinterpret_cast<const uint4*>(&long_tab[h4[e]]);
+    }
+    // kept edges t -> s: their positions in the destinations' own lists and their places in the staging rows are
+    // requested together
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (maybe[e]) {
+        j4[e] = rev_pos[it.beg + (uint32_t)e * 16u + sub];
+        at4[e] = (uint32_t)atomicAdd(&cnt_f[list4[e]], 1);
+      }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (maybe[e]) {
+        if (at4[e] < stage_cap) stage_f[(size_t)list4[e] * stage_cap + at4[e]] = StageEntry{(int32_t)it.t, j4[e]};
+        else if (at4[e] == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
+      }
   }
 }
 
@@ -199,7 +242,7 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
                                                      double cw, double sw, int queued, Ctl* ctl,
                                                      uint32_t piece_len, Piece* __restrict__ pieces, uint32_t piece_cap,
                                                      uint32_t* __restrict__ piece_count, ScanOut out, uint32_t enum_degree,
-                                                     LongSlot* __restrict__ long_tab, uint32_t long_mask) {
+                                                     uint32_t* __restrict__ long_bits, LongSlot* __restrict__ long_tab, uint32_t long_mask) {
   __shared__ uint32_t s_wave_at[kSegBlock / kWave];
   __shared__ uint32_t s_base, s_total;
   const int64_t i = (int64_t)blockIdx.x * kSegBlock + threadIdx.x;
@@ -253,6 +296,8 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
       h = (h + 1) & long_mask;
     }
     if (!entered) atomicOr(&ctl->cand_overflow, 1);  // (the pass is redone without this shortcut)
+    const uint32_t b = long_bit((uint32_t)dst[i]);
+    atomicOr(&long_bits[b >> 5], 1u << (b & 31u));
     sampled = false;  // no pieces
   }
   if (piece_len == 0) {  // wave-uniform
@@ -1068,6 +1113,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       const uint32_t enum_degree = cx.g->symmetric && !cx.blend && !no_enum && kmax_pass <= 64 && enough ? (uint32_t)g_enum_degree : 0u;
       used_enum = enum_degree != 0;
       LongSlot* long_tab = nullptr;
+      uint32_t* long_bits = nullptr;
       uint32_t long_mask = 0;
       EnumOut eo{};
       uint32_t u_max[kMaxFuse] = {0, 0, 0, 0}, um_most = 0;
@@ -1081,8 +1127,10 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
         uint32_t slots = 1024;
         while ((int64_t)slots < 2 * most && (int64_t)slots * 2 <= ceiling) slots <<= 1;
         long_mask = slots - 1;
-        eo.n_item = (uint32_t*)alloc.get<LongSlot>((int64_t)slots + 1, COOP_TAG_SCRATCH);  // the counters, then the table
-        long_tab = (LongSlot*)eo.n_item + 1;
+        constexpr int64_t kBitSlots = kLongBits / 8 / sizeof(LongSlot);
+        eo.n_item = (uint32_t*)alloc.get<LongSlot>(1 + kBitSlots + (int64_t)slots, COOP_TAG_SCRATCH);  // counters, bits, table
+        long_bits = (uint32_t*)((LongSlot*)eo.n_item + 1);
+        long_tab = (LongSlot*)eo.n_item + 1 + kBitSlots;
         for (int f = 0; f < ps.nf; ++f) {
           u_max[f] = (uint32_t)(((uint64_t)ks[f] << 32) / ((uint64_t)enum_degree + 1));
           um_most = u_max[f] > um_most ? u_max[f] : um_most;
@@ -1096,19 +1144,21 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
         eo.item_cap = (uint32_t)(items < 268435456.0 ? items : 268435456.0);
         for (int f = 0; f < ps.nf; ++f) eo.item[f] = alloc.get<EnumItem>(eo.item_cap, COOP_TAG_SCRATCH);
         if (alloc.failed) return COOP_E_NOMEM;
-        fill_u64((uint64_t*)eo.n_item, ((int64_t)slots + 1) * (sizeof(LongSlot) / 8), 0, s);
+        fill_u64((uint64_t*)eo.n_item, (1 + kLongBits / 8 / sizeof(LongSlot) + (int64_t)slots) * (sizeof(LongSlot) / 8), 0, s);
       }
       COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
                   dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, cx.cw, cx.sw,
                   cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
-                  piece_len, pieces, piece_cap, cx.d_piece_count + l, out, enum_degree, long_tab, long_mask);
+                  piece_len, pieces, piece_cap, cx.d_piece_count + l, out, enum_degree, long_bits, long_tab, long_mask);
       if (enum_degree != 0) {
         const unsigned list_blocks = blocks_for((int64_t)um_most + 1, kEnumListSpan);
         COOP_LAUNCH(K_ENUM_LIST, k_enum_list, dim3(list_blocks, ps.nf), dim3(kBlock), 0, s, keys, u_max[0], u_max[1], u_max[2], u_max[3],
                     cx.g->n_vertices, cx.g->indptr, eo, cx.d_ctl);
-        const int64_t walk_blocks = blocks_for((int64_t)eo.item_cap * 16, kBlock);
-        COOP_LAUNCH(K_ENUM_WALK, k_enum_walk, dim3((unsigned)(walk_blocks < 16384 ? walk_blocks : 16384), ps.nf), dim3(kBlock), 0, s,
-                    cx.g->indices, (const uint32_t*)cx.g->rev_pos, (const LongSlot*)long_tab, long_mask, cap, out, eo, cx.d_ctl);
+        // (three blocks fit a CU: one round of resident blocks strides over the items)
+        const int64_t walk_blocks = blocks_for((int64_t)eo.item_cap * 16, kWalkBlock);
+        COOP_LAUNCH(K_ENUM_WALK, k_enum_walk, dim3((unsigned)(walk_blocks < 768 ? walk_blocks : 768), ps.nf), dim3(kWalkBlock), 0, s,
+                    cx.g->indices, (const uint32_t*)cx.g->rev_pos, (const uint32_t*)long_bits, (const LongSlot*)long_tab, long_mask, cap, out,
+                    eo, cx.d_ctl);
       }
       // lists per wave: a few amortise the record fetch once there are plenty of lists (the knob overrides)
       int lpw = g_lists_per_wave;

@@ -579,18 +579,21 @@ def test_frontier_dedup_modes(P, tiny, medium, mode):
 
 def test_randomized_configurations(P, draw_seed=20240, cases=160):
     """Seeded random draws of graph shape, batch, depth, fanouts, sampler, iteration / kappa and of the library's
-    internal modes (piece length, layer fusion, staging rows, read-back mode, dedup mode, lists per wave), every output
-    against the oracle: the code paths meet here in combinations that no other test spells out."""
+    internal modes (piece length, layer fusion, staging rows, read-back mode, dedup mode, lists per wave; every other
+    graph registered as symmetric, with a random degree above which LABOR-0 works from the neighbours' side), every
+    output against the oracle: the code paths meet here in combinations that no other test spells out."""
     rng = np.random.default_rng(draw_seed)
+    rng2 = np.random.default_rng(draw_seed + 1)
     fan_choices = (1, 2, 3, 5, 10, 25, 64, 65, 300)
     knobs = (P.COOP_TUNE_PIECE_LEN, P.COOP_TUNE_FUSE_LAYERS, P.COOP_TUNE_STAGE_CAP, P.COOP_TUNE_DEFER_SIZES, P.COOP_TUNE_UNIQUE,
-             P.COOP_TUNE_LISTS_PER_WAVE)
-    defaults = (4096, 1, 0, 1, 0, 0)
+             P.COOP_TUNE_LISTS_PER_WAVE, P.COOP_TUNE_ENUM_DEGREE)
+    defaults = (4096, 1, 0, 1, 0, 0, 8192)
     graphs = []
     for gi in range(6):
         n = int(rng.choice((60, 900, 7000, 30000)))
         m = int(n * rng.choice((1, 6, 30, 70)))
-        graphs.append(G(P, *synth.chung_lu_csr(n, max(m, n), float(rng.choice((1.9, 2.1, 2.6))), seed=100 + gi)))
+        graphs.append(G(P, *synth.chung_lu_csr(n, max(m, n), float(rng.choice((1.9, 2.1, 2.6))), seed=100 + gi),
+                        flags=P.COOP_VALIDATE | (P.COOP_SYMMETRIC if gi % 2 else 0)))
     try:
         for case in range(cases):
             g = graphs[case % len(graphs)]
@@ -603,7 +606,8 @@ def test_randomized_configurations(P, draw_seed=20240, cases=160):
             it = int(rng.integers(0, 40))
             sd = int(rng.integers(1 << 30))
             values = (int(rng.choice((0, 256, 512, 4096))), int(rng.integers(0, 3)), int(rng.choice((0, 0, 4, 32))),
-                      int(rng.integers(0, 3)), int(rng.integers(0, 4)), int(rng.choice((0, 0, 1, 3, 8))))
+                      int(rng.integers(0, 3)), int(rng.integers(0, 4)), int(rng.choice((0, 0, 1, 3, 8))),
+                      int(rng2.choice((0, 64, 64, 150, 1000, 8192))))
             for kn, v in zip(knobs, values):
                 P.coop_tune(kn, v)
             label = (case, g.n, fanouts, b, sampler, kappa, it, values)
@@ -626,7 +630,7 @@ def test_randomized_configurations(P, draw_seed=20240, cases=160):
 @pytest.mark.parametrize("degree", [64, 300, 8192])
 def test_labor_long_lists_from_the_other_side(P, tiny, medium, degree):
     """Graphs registered as symmetric: LABOR-0 with independent variates finds the kept neighbours of lists longer than
-    `degree` from the neighbours' side (inverse mixer, walk of the listed vertices' lists, bisection for the position);
+    `degree` from the neighbours' side (inverse mixer, walk of the listed vertices' lists, index of reverse positions);
     the bytes must not change.  Dependent variates and NS take the ordinary path on the same handle."""
     try:
         P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, degree)
