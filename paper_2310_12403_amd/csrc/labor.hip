@@ -1107,9 +1107,10 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       // ---- the longest lists from the other side (see k_enum_list) ---------------------------------------------------
       uint32_t kmax_pass = 0;
       for (int f = 0; f < ps.nf; ++f) kmax_pass = ks[f] > kmax_pass ? ks[f] : kmax_pass;
-      // (the walk costs the same whatever the number of destinations: it pays only for a pass over many lists; the test
-      // knob value below 8192 applies always)
-      const bool enough = n_new >= 65536 || g_enum_degree < 8192;
+      // (listing and walking cost the same whatever the number of destinations and the shape of the graph: it pays only
+      // for a pass over many lists of a graph whose long lists hold a good part (an eighth, here) of the edges; a knob
+      // value below the default is for tests and applies always)
+      const bool enough = g_enum_degree < kLongListDegree || (n_new >= 65536 && cx.g->long_mass * 8 >= cx.g->n_edges);
       const uint32_t enum_degree = cx.g->symmetric && !cx.blend && !no_enum && kmax_pass <= 64 && enough ? (uint32_t)g_enum_degree : 0u;
       used_enum = enum_degree != 0;
       LongSlot* long_tab = nullptr;

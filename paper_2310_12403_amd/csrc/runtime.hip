@@ -314,14 +314,18 @@ __global__ __launch_bounds__(kBlock) void k_validate_csr(const int64_t* __restri
 
 // COOP_SYMMETRIC: checks that the lists are strictly ascending and that every edge t in N(s) has its reverse s in N(t),
 // and records where: rev[e] = position of s in t's list, for the edge at position e of the indices array (bisection).
+// Also adds up the entries of the lists longer than kLongListDegree: LABOR-0 works from the neighbours' side only on
+// graphs where such lists hold a good part of the edges.
 __global__ __launch_bounds__(kBlock) void k_build_reverse(const int64_t* __restrict__ indptr, const int32_t* __restrict__ indices,
-                                                          int64_t nv, uint32_t* __restrict__ rev, int32_t* bad) {
+                                                          int64_t nv, uint32_t* __restrict__ rev, int32_t* bad,
+                                                          unsigned long long* long_mass) {
   // one wave per vertex at a time, lanes over its list
   if (*bad != 0) return;  // (a malformed CSR was reported by the kernel before this one: its offsets cannot be trusted)
   const int64_t n_waves = ((int64_t)gridDim.x * kBlock) >> 6;
   bool b = false;
   for (int64_t s = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6; s < nv; s += n_waves) {
     const int64_t beg = indptr[s], end = indptr[s + 1];
+    if (lane_id() == 0 && end - beg > kLongListDegree) atomicAdd(long_mass, (unsigned long long)(end - beg));
     for (int64_t e = beg + lane_id(); e < end; e += kWave) {
       const int32_t t = indices[e];
       if (e > beg && indices[e - 1] >= t) b = true;
@@ -380,35 +384,38 @@ int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_ver
   if (!indptr || (!indices && n_edges > 0)) return COOP_E_NULL;
   if (n_vertices < 0 || n_vertices >= ((int64_t)1 << 31) || n_edges < 0 || (flags & ~(COOP_VALIDATE | COOP_SYMMETRIC))) return COOP_E_ARG;
   uint32_t* rev = nullptr;
+  int64_t long_mass = 0;
   if (flags & (COOP_VALIDATE | COOP_SYMMETRIC)) {  // (the reverse index is built from offsets and ids that have been checked)
     hipStream_t s = (hipStream_t)stream;
-    int32_t* d_bad = nullptr;
-    COOP_HIP_TRY(hipMalloc((void**)&d_bad, sizeof(int32_t)));
+    struct Check { int32_t bad, pad; unsigned long long long_mass; };
+    Check* d_chk = nullptr;
+    COOP_HIP_TRY(hipMalloc((void**)&d_chk, sizeof(Check)));
     if ((flags & COOP_SYMMETRIC) && n_edges > 0 && hipMalloc((void**)&rev, (size_t)n_edges * sizeof(uint32_t)) != hipSuccess) {
-      (void)hipFree(d_bad);
+      (void)hipFree(d_chk);
       return COOP_E_NOMEM;
     }
-    int32_t h_bad = 0;
-    hipError_t e = hipMemcpyAsync(d_bad, &h_bad, sizeof(int32_t), hipMemcpyHostToDevice, s);
+    Check h_chk{0, 0, 0};
+    hipError_t e = hipMemcpyAsync(d_chk, &h_chk, sizeof(Check), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) {
-      COOP_LAUNCH(K_VALIDATE, k_validate_csr, dim3(256 * 16), dim3(kBlock), 0, s, indptr, indices, n_vertices, n_edges, d_bad);
+      COOP_LAUNCH(K_VALIDATE, k_validate_csr, dim3(256 * 16), dim3(kBlock), 0, s, indptr, indices, n_vertices, n_edges, &d_chk->bad);
       if ((flags & COOP_SYMMETRIC) && n_vertices > 0 && n_edges > 0) {
         // (a grid holds fewer than 2^32 threads: the waves stride over the vertices)
         const int64_t want = (n_vertices * kWave + kBlock - 1) / kBlock;
         COOP_LAUNCH(K_VALIDATE, k_build_reverse, dim3((unsigned)(want < (1 << 22) ? want : (1 << 22))), dim3(kBlock), 0, s, indptr, indices,
-                    n_vertices, rev, d_bad);
+                    n_vertices, rev, &d_chk->bad, &d_chk->long_mass);
       }
       e = hipGetLastError();
-      if (e == hipSuccess) e = hipMemcpyAsync(&h_bad, d_bad, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+      if (e == hipSuccess) e = hipMemcpyAsync(&h_chk, d_chk, sizeof(Check), hipMemcpyDeviceToHost, s);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(s);
-    (void)hipFree(d_bad);
-    if (e != hipSuccess || h_bad) {
+    (void)hipFree(d_chk);
+    if (e != hipSuccess || h_chk.bad) {
       if (rev) (void)hipFree(rev);
       return e != hipSuccess ? COOP_E_HIP : COOP_E_GRAPH;
     }
+    long_mass = (int64_t)h_chk.long_mass;
   }
-  coop_graph* g = new (std::nothrow) coop_graph{indptr, indices, n_vertices, n_edges, (flags & COOP_SYMMETRIC) != 0 && n_edges > 0, rev};
+  coop_graph* g = new (std::nothrow) coop_graph{indptr, indices, n_vertices, n_edges, (flags & COOP_SYMMETRIC) != 0 && n_edges > 0, rev, long_mass};
   if (!g) {
     if (rev) (void)hipFree(rev);
     return COOP_E_NOMEM;
