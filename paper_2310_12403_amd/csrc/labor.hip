@@ -68,7 +68,8 @@ __device__ __forceinline__ uint32_t long_bit(uint32_t s) { return long_slot(s) >
 
 struct EnumItem { int64_t beg; uint32_t len, t, u, pad; };  // up to kEnumItem entries of listed vertex t's list; u = R_t
 constexpr uint32_t kEnumItem = 64;         // entries per item: 16 lanes walk it, 4 entries each, loaded together
-constexpr uint32_t kEnumListSpan = 16384;   // variates per block of k_enum_list
+constexpr int kListBlock = 256;            // threads per block of k_enum_list
+constexpr uint32_t kEnumListSpan = 8192;   // variates per block of k_enum_list
 constexpr uint32_t kEnumListStep = 1024;   // variates per step of a block (4 per thread), between two barriers
 constexpr uint32_t kEnumListBuf = 2048;    // vertices a block collects before it writes their items out
 
@@ -82,10 +83,9 @@ struct EnumOut {
 // variates, collects the vertices they belong to in LDS, fetches their list bounds, and writes their lists, cut into
 // items, to the layer's item list: one reservation (a same-address atomic) per flush (one in 40 of the variates of a
 // papers100M-sized graph gives a vertex).
-__global__ __launch_bounds__(kBlock) void k_enum_list(FusedKeys keys, uint32_t um0, uint32_t um1, uint32_t um2, uint32_t um3,
+__global__ __launch_bounds__(kListBlock) void k_enum_list(FusedKeys keys, uint32_t um0, uint32_t um1, uint32_t um2, uint32_t um3,
                                                       int64_t n_vertices, const int64_t* __restrict__ g_indptr, EnumOut eo, Ctl* ctl) {
   __shared__ uint2 buf[kEnumListBuf];     // (t, u)
-  __shared__ int64_t s_beg[kEnumListBuf];
   __shared__ uint32_t s_d[kEnumListBuf], s_at[kEnumListBuf];
   __shared__ uint16_t s_long[kEnumListBuf];  // the collected vertices that give more than one item
   __shared__ uint32_t n_buf, n_local, n_long, base;
@@ -98,11 +98,10 @@ __global__ __launch_bounds__(kBlock) void k_enum_list(FusedKeys keys, uint32_t u
   __syncthreads();
   auto flush = [&]() {  // block-uniform call, after a barrier
     const uint32_t nb = n_buf;  // <= kEnumListBuf: a step adds at most kEnumListStep and is taken only when that many fit
-    for (uint32_t i = threadIdx.x; i < nb; i += kBlock) {
+    for (uint32_t i = threadIdx.x; i < nb; i += kListBlock) {
       const uint32_t t = buf[i].x;
       const int64_t beg = g_indptr[t];
       const uint32_t d = (uint32_t)(g_indptr[t + 1] - beg);  // (0: a vertex without neighbours is nobody's neighbour)
-      s_beg[i] = beg;
       s_d[i] = d;
       if (d != 0) s_at[i] = atomicAdd(&n_local, (d + kEnumItem - 1) / kEnumItem);
       if (d > kEnumItem) s_long[atomicAdd(&n_long, 1u)] = (uint16_t)i;
@@ -113,17 +112,17 @@ __global__ __launch_bounds__(kBlock) void k_enum_list(FusedKeys keys, uint32_t u
     if (base + n_local > eo.item_cap) {
       if (threadIdx.x == 0) atomicOr(&ctl->cand_overflow, 1);  // (the pass is redone without this shortcut)
     } else {
-      for (uint32_t i = threadIdx.x; i < nb; i += kBlock) {  // a thread per vertex with one item
+      for (uint32_t i = threadIdx.x; i < nb; i += kListBlock) {  // a thread per vertex with one item
         const uint32_t d = s_d[i];
-        if (d != 0 && d <= kEnumItem) eo.item[f][base + s_at[i]] = EnumItem{s_beg[i], d, buf[i].x, buf[i].y, 0u};
+        if (d != 0 && d <= kEnumItem) eo.item[f][base + s_at[i]] = EnumItem{g_indptr[buf[i].x], d, buf[i].x, buf[i].y, 0u};
       }
       for (uint32_t v = 0; v < n_long; ++v) {                // the block together for each of the others
         const uint32_t i = s_long[v];
         const uint32_t d = s_d[i];
         const uint2 tu = buf[i];
-        const int64_t beg = s_beg[i];
+        const int64_t beg = g_indptr[tu.x];
         EnumItem* to = eo.item[f] + base + s_at[i];
-        for (uint32_t q = threadIdx.x; q * kEnumItem < d; q += kBlock) {
+        for (uint32_t q = threadIdx.x; q * kEnumItem < d; q += kListBlock) {
           const uint32_t off = q * kEnumItem;
           to[q] = EnumItem{beg + off, d - off < kEnumItem ? d - off : kEnumItem, tu.x, tu.y, 0u};
         }
@@ -135,7 +134,7 @@ __global__ __launch_bounds__(kBlock) void k_enum_list(FusedKeys keys, uint32_t u
   };
   for (uint32_t step = 0; step < kEnumListSpan; step += kEnumListStep) {
 #pragma unroll
-    for (uint32_t q = 0; q < kEnumListStep; q += kBlock) {
+    for (uint32_t q = 0; q < kEnumListStep; q += kListBlock) {
       const uint64_t u = first + step + q + threadIdx.x;
       const uint32_t t = unmix32((uint32_t)u ^ K1) ^ K0;
       if (u <= u_max && (uint64_t)t < (uint64_t)n_vertices) buf[atomicAdd(&n_buf, 1u)] = make_uint2(t, (uint32_t)u);
@@ -166,14 +165,20 @@ __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __re
   StageEntry* __restrict__ stage_f = f == 0 ? out.stage[0] : f == 1 ? out.stage[1] : f == 2 ? out.stage[2] : out.stage[3];
   const uint32_t sub = threadIdx.x & 15u;
   const uint32_t groups = (gridDim.x * kWalkBlock) >> 4;
-  for (uint32_t c = (blockIdx.x * kWalkBlock + threadIdx.x) >> 4; c < total; c += groups) {
-    const EnumItem it = item_f[c];
-    uint32_t s4[4];
+  // (the next item's record and entries are requested while the current one's table slots and commits are in flight)
+  uint32_t c = (blockIdx.x * kWalkBlock + threadIdx.x) >> 4;
+  if (c >= total) return;
+  EnumItem it = item_f[c];
+  uint32_t s4[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t j = (uint32_t)e * 16u + sub;
-      s4[e] = (uint32_t)g_indices[it.beg + (j < it.len ? j : it.len - 1)];  // (len >= 1; a lane past the end repeats the last entry)
-    }
+  for (int e = 0; e < 4; ++e) {
+    const uint32_t j = (uint32_t)e * 16u + sub;
+    s4[e] = (uint32_t)g_indices[it.beg + (j < it.len ? j : it.len - 1)];  // (len >= 1; a lane past the end repeats the last entry)
+  }
+  for (;;) {
+    const bool more = c + groups < total;
+    EnumItem it_next = it;
+    if (more) it_next = item_f[c + groups];
     uint32_t h4[4];
     bool maybe[4];
     uint4 head4[4];
@@ -215,6 +220,14 @@ __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __re
       for (int e = 0; e < 4; ++e)
         if (open4[e]) head4[e] = *reinterpret_cast<const uint4*>(&long_tab[h4[e]]);
     }
+    uint32_t s4_next[4] = {0, 0, 0, 0};
+    if (more) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t j = (uint32_t)e * 16u + sub;
+        s4_next[e] = (uint32_t)g_indices[it_next.beg + (j < it_next.len ? j : it_next.len - 1)];
+      }
+    }
     // kept edges t -> s: their positions in the destinations' own lists and their places in the staging rows are
     // requested together
 #pragma unroll
@@ -229,6 +242,11 @@ __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __re
         if (at4[e] < stage_cap) stage_f[(size_t)list4[e] * stage_cap + at4[e]] = StageEntry{(int32_t)it.t, j4[e]};
         else if (at4[e] == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
       }
+    if (!more) break;
+    c += groups;
+    it = it_next;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s4[e] = s4_next[e];
   }
 }
 
@@ -1153,7 +1171,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
                   piece_len, pieces, piece_cap, cx.d_piece_count + l, out, enum_degree, long_bits, long_tab, long_mask);
       if (enum_degree != 0) {
         const unsigned list_blocks = blocks_for((int64_t)um_most + 1, kEnumListSpan);
-        COOP_LAUNCH(K_ENUM_LIST, k_enum_list, dim3(list_blocks, ps.nf), dim3(kBlock), 0, s, keys, u_max[0], u_max[1], u_max[2], u_max[3],
+        COOP_LAUNCH(K_ENUM_LIST, k_enum_list, dim3(list_blocks, ps.nf), dim3(kListBlock), 0, s, keys, u_max[0], u_max[1], u_max[2], u_max[3],
                     cx.g->n_vertices, cx.g->indptr, eo, cx.d_ctl);
         // (three blocks fit a CU: one round of resident blocks strides over the items)
         const int64_t walk_blocks = blocks_for((int64_t)eo.item_cap * 16, kWalkBlock);
