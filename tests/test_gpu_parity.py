@@ -663,6 +663,35 @@ def test_labor_long_lists_from_the_other_side(P, tiny, medium, degree):
         P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
 
 
+def test_labor_other_side_falls_back_when_a_hub_is_listed(P):
+    """A star with 200,000 leaves: the hub's list is the one long list, and in about one iteration out of 65 (fanout 1,
+    degree limit 64) the hub itself is among the vertices with a small variate.  Its 3,125 items do not fit the room that
+    was sized for four times the expected number, so the pass is done again with every list scanned.  Every iteration
+    must give the oracle's bytes; the kernel launch counts show that the second attempt took place."""
+    n_leaf = 200_000
+    ip = np.concatenate([[0, n_leaf], n_leaf + 1 + np.arange(n_leaf)]).astype(np.int64)
+    ix = np.concatenate([1 + np.arange(n_leaf), np.zeros(n_leaf)]).astype(np.int32)
+    g = G(P, torch.from_numpy(ip), torch.from_numpy(ix), flags=P.COOP_VALIDATE | P.COOP_SYMMETRIC)
+    seeds = (1 + 37 * np.arange(64)).astype(np.int32)
+    redone = 0
+    try:
+        P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, 64)
+        P.profile_enable(True)
+        for it in range(400):
+            P.profile_reset()
+            compare(P, g, seeds, (1, 1), R.LABOR0, it=it, seed=5)
+            counts = P.profile_read_all()
+            lists, scans = counts.get("enum_list", (0, 0))[1], counts.get("labor_scan", (0, 0))[1]
+            assert lists >= 1
+            redone += scans > 2          # (one scan pass per layer when nothing is redone)
+            if redone >= 2:
+                break
+    finally:
+        P.profile_enable(False)
+        P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, 8192)
+    assert redone >= 1
+
+
 def test_symmetric_flag_is_checked(P, tiny):
     """COOP_SYMMETRIC: a graph with one edge that lacks its reverse, or with an unsorted list, is refused."""
     flags = P.COOP_VALIDATE | P.COOP_SYMMETRIC
