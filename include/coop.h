@@ -276,7 +276,9 @@ const char* coop_strerror(int code);
 #define COOP_TUNE_ENUM_DEGREE 8    /* LABOR-0 with independent variates on a graph registered with COOP_SYMMETRIC: lists
                                       longer than this many entries are not read; their kept neighbours are found from the
                                       neighbours' side (default 8192; 0: never; otherwise at least 64).  Applies while no
-                                      fanout exceeds 64 */
+                                      fanout exceeds 64; at 8192 and above only to passes over 65536 lists or more of a
+                                      graph whose lists above 8192 entries hold an eighth of its edges (below that the
+                                      listing costs more than it saves); smaller values, meant for tests, apply always */
 int coop_tune(int knob, int64_t value);
 
 /* out[i] = in[i] for a device id list (a plain streaming copy on `stream`: 4n bytes read, 4n written).  Besides its
