@@ -74,9 +74,9 @@ constexpr uint32_t kEnumListStep = 1024;   // variates per step of a block (4 pe
 constexpr uint32_t kEnumListBuf = 2048;    // vertices a block collects before it writes their items out
 
 struct EnumOut {
-  EnumItem* item[kMaxFuse];   // [item_cap] per covered layer
-  uint32_t* n_item;           // [kMaxFuse]
-  uint32_t item_cap;
+  EnumItem* item[kMaxFuse];    // [item_cap[f]] per covered layer
+  uint32_t* n_item[kMaxFuse];  // one counter each
+  uint32_t item_cap[kMaxFuse];
 };
 
 // blockIdx.y = covered layer f: lists the vertices with R_t <= u_max[f].  A block takes kEnumListSpan consecutive
@@ -84,7 +84,8 @@ struct EnumOut {
 // items, to the layer's item list: one reservation (a same-address atomic) per flush (one in 40 of the variates of a
 // papers100M-sized graph gives a vertex).
 __global__ __launch_bounds__(kListBlock) void k_enum_list(FusedKeys keys, uint32_t um0, uint32_t um1, uint32_t um2, uint32_t um3,
-                                                      int64_t n_vertices, const int64_t* __restrict__ g_indptr, EnumOut eo, Ctl* ctl) {
+                                                      int64_t n_vertices, const int64_t* __restrict__ g_indptr, EnumOut eo, Ctl* ctl,
+                                                      uint32_t todo /* bit f: layer f is to be listed (the others have their lists) */) {
   __shared__ uint2 buf[kEnumListBuf];     // (t, u)
   __shared__ uint32_t s_d[kEnumListBuf], s_at[kEnumListBuf];
   __shared__ uint16_t s_long[kEnumListBuf];  // the collected vertices that give more than one item
@@ -93,7 +94,10 @@ __global__ __launch_bounds__(kListBlock) void k_enum_list(FusedKeys keys, uint32
   const uint32_t u_max = f == 0 ? um0 : f == 1 ? um1 : f == 2 ? um2 : um3;
   const uint32_t K0 = keys.K[f].Ka[0], K1 = keys.K[f].Ka[1];
   const uint64_t first = (uint64_t)blockIdx.x * kEnumListSpan;
-  if (first > u_max) return;  // block-uniform
+  if (first > u_max || ((todo >> f) & 1u) == 0) return;  // block-uniform
+  EnumItem* __restrict__ item_f = f == 0 ? eo.item[0] : f == 1 ? eo.item[1] : f == 2 ? eo.item[2] : eo.item[3];
+  uint32_t* n_item_f = f == 0 ? eo.n_item[0] : f == 1 ? eo.n_item[1] : f == 2 ? eo.n_item[2] : eo.n_item[3];
+  const uint32_t item_cap_f = f == 0 ? eo.item_cap[0] : f == 1 ? eo.item_cap[1] : f == 2 ? eo.item_cap[2] : eo.item_cap[3];
   if (threadIdx.x == 0) { n_buf = 0; n_local = 0; n_long = 0; }
   __syncthreads();
   auto flush = [&]() {  // block-uniform call, after a barrier
@@ -107,21 +111,21 @@ __global__ __launch_bounds__(kListBlock) void k_enum_list(FusedKeys keys, uint32
       if (d > kEnumItem) s_long[atomicAdd(&n_long, 1u)] = (uint16_t)i;
     }
     __syncthreads();
-    if (threadIdx.x == 0) base = n_local ? atomicAdd(&eo.n_item[f], n_local) : 0u;
+    if (threadIdx.x == 0) base = n_local ? atomicAdd(n_item_f, n_local) : 0u;
     __syncthreads();
-    if (base + n_local > eo.item_cap) {
+    if (base + n_local > item_cap_f) {
       if (threadIdx.x == 0) atomicOr(&ctl->cand_overflow, 1);  // (the pass is redone without this shortcut)
     } else {
       for (uint32_t i = threadIdx.x; i < nb; i += kListBlock) {  // a thread per vertex with one item
         const uint32_t d = s_d[i];
-        if (d != 0 && d <= kEnumItem) eo.item[f][base + s_at[i]] = EnumItem{g_indptr[buf[i].x], d, buf[i].x, buf[i].y, 0u};
+        if (d != 0 && d <= kEnumItem) item_f[base + s_at[i]] = EnumItem{g_indptr[buf[i].x], d, buf[i].x, buf[i].y, 0u};
       }
       for (uint32_t v = 0; v < n_long; ++v) {                // the block together for each of the others
         const uint32_t i = s_long[v];
         const uint32_t d = s_d[i];
         const uint2 tu = buf[i];
         const int64_t beg = g_indptr[tu.x];
-        EnumItem* to = eo.item[f] + base + s_at[i];
+        EnumItem* to = item_f + base + s_at[i];
         for (uint32_t q = threadIdx.x; q * kEnumItem < d; q += kListBlock) {
           const uint32_t off = q * kEnumItem;
           to[q] = EnumItem{beg + off, d - off < kEnumItem ? d - off : kEnumItem, tu.x, tu.y, 0u};
@@ -158,8 +162,9 @@ __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __re
   for (uint32_t i = threadIdx.x; i < kLongBits / 128; i += kWalkBlock)
     reinterpret_cast<uint4*>(bits)[i] = reinterpret_cast<const uint4*>(long_bits)[i];
   __syncthreads();
-  uint32_t total = eo.n_item[f];
-  if (total > eo.item_cap) total = eo.item_cap;
+  uint32_t total = *(f == 0 ? eo.n_item[0] : f == 1 ? eo.n_item[1] : f == 2 ? eo.n_item[2] : eo.n_item[3]);
+  const uint32_t item_cap_f = f == 0 ? eo.item_cap[0] : f == 1 ? eo.item_cap[1] : f == 2 ? eo.item_cap[2] : eo.item_cap[3];
+  if (total > item_cap_f) total = item_cap_f;
   const EnumItem* __restrict__ item_f = f == 0 ? eo.item[0] : f == 1 ? eo.item[1] : f == 2 ? eo.item[2] : eo.item[3];
   int32_t* __restrict__ cnt_f = f == 0 ? out.cnt[0] : f == 1 ? out.cnt[1] : f == 2 ? out.cnt[2] : out.cnt[3];
   StageEntry* __restrict__ stage_f = f == 0 ? out.stage[0] : f == 1 ? out.stage[1] : f == 2 ? out.stage[2] : out.stage[3];
@@ -1135,7 +1140,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       uint32_t* long_bits = nullptr;
       uint32_t long_mask = 0;
       EnumOut eo{};
-      uint32_t u_max[kMaxFuse] = {0, 0, 0, 0}, um_most = 0;
+      uint32_t u_max[kMaxFuse] = {0, 0, 0, 0}, um_most = 0, list_todo = 0;
       if (enum_degree != 0) {
         // the table of long destinations: twice the number there can be (|E| / D lists are that long, at most), but no
         // more than 65536 slots or a quarter of the destinations, whichever is more: the table then stays in L2, and a
@@ -1147,34 +1152,51 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
         while ((int64_t)slots < 2 * most && (int64_t)slots * 2 <= ceiling) slots <<= 1;
         long_mask = slots - 1;
         constexpr int64_t kBitSlots = kLongBits / 8 / sizeof(LongSlot);
-        eo.n_item = (uint32_t*)alloc.get<LongSlot>(1 + kBitSlots + (int64_t)slots, COOP_TAG_SCRATCH);  // counters, bits, table
-        long_bits = (uint32_t*)((LongSlot*)eo.n_item + 1);
-        long_tab = (LongSlot*)eo.n_item + 1 + kBitSlots;
+        uint32_t* zeroed = (uint32_t*)alloc.get<LongSlot>(1 + kBitSlots + (int64_t)slots, COOP_TAG_SCRATCH);  // counters, bits, table
+        long_bits = (uint32_t*)((LongSlot*)zeroed + 1);
+        long_tab = (LongSlot*)zeroed + 1 + kBitSlots;
+        // The vertices listed for a layer depend on the layer's keys and fanout only: a later pass that covers the same
+        // layer (the pass at layer 2 after the pass at layer 1 that covered layers 1 and 2) walks the same items.
         for (int f = 0; f < ps.nf; ++f) {
           u_max[f] = (uint32_t)(((uint64_t)ks[f] << 32) / ((uint64_t)enum_degree + 1));
+          LaborState::Listed* had = l + f < LaborState::kMaxListed ? &st.listed[l + f] : nullptr;
+          if (had != nullptr && had->item != nullptr && had->u_max == u_max[f]) {
+            eo.item[f] = had->item;
+            eo.n_item[f] = had->n;
+            eo.item_cap[f] = had->cap;
+            continue;
+          }
+          // items: a listed vertex gives d / kEnumItem + 1 of them; the listed vertices' lists hold |E| u_max / 2^32
+          // entries in expectation, and four times that is allowed for (a pass that needs more, because some huge hub is
+          // listed, is redone the ordinary way)
+          const double expect = (double)cx.g->n_vertices * ((double)u_max[f] + 1.0) / 4294967296.0;  // listed vertices
+          const double entries = (double)cx.g->n_edges * ((double)u_max[f] + 1.0) / 4294967296.0;
+          const double items = expect + 8.0 * sqrt(expect) + 1024.0 + 4.0 * entries / kEnumItem;
+          eo.item_cap[f] = (uint32_t)(items < 268435456.0 ? items : 268435456.0);
+          eo.item[f] = alloc.get<EnumItem>(eo.item_cap[f], COOP_TAG_SCRATCH);
+          eo.n_item[f] = zeroed + f;
+          list_todo |= 1u << f;
           um_most = u_max[f] > um_most ? u_max[f] : um_most;
+          if (had != nullptr) *had = LaborState::Listed{eo.item[f], eo.n_item[f], eo.item_cap[f], u_max[f]};
         }
-        const double expect = (double)cx.g->n_vertices * ((double)um_most + 1.0) / 4294967296.0;  // listed vertices
-        // items: a listed vertex gives d / kEnumItem + 1 of them; the listed vertices' lists hold |E| u_max / 2^32 entries
-        // in expectation, and four times that is allowed for (a pass that needs more, because some huge hub is listed,
-        // is redone the ordinary way)
-        const double entries = (double)cx.g->n_edges * ((double)um_most + 1.0) / 4294967296.0;
-        const double items = expect + 8.0 * sqrt(expect) + 1024.0 + 4.0 * entries / kEnumItem;
-        eo.item_cap = (uint32_t)(items < 268435456.0 ? items : 268435456.0);
-        for (int f = 0; f < ps.nf; ++f) eo.item[f] = alloc.get<EnumItem>(eo.item_cap, COOP_TAG_SCRATCH);
+        for (int f = ps.nf; f < kMaxFuse; ++f) { eo.item[f] = eo.item[0]; eo.n_item[f] = eo.n_item[0]; eo.item_cap[f] = 0; }
         if (alloc.failed) return COOP_E_NOMEM;
-        fill_u64((uint64_t*)eo.n_item, (1 + kLongBits / 8 / sizeof(LongSlot) + (int64_t)slots) * (sizeof(LongSlot) / 8), 0, s);
+        fill_u64((uint64_t*)zeroed, (1 + kLongBits / 8 / sizeof(LongSlot) + (int64_t)slots) * (sizeof(LongSlot) / 8), 0, s);
       }
       COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
                   dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, cx.cw, cx.sw,
                   cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
                   piece_len, pieces, piece_cap, cx.d_piece_count + l, out, enum_degree, long_bits, long_tab, long_mask);
       if (enum_degree != 0) {
-        const unsigned list_blocks = blocks_for((int64_t)um_most + 1, kEnumListSpan);
-        COOP_LAUNCH(K_ENUM_LIST, k_enum_list, dim3(list_blocks, ps.nf), dim3(kListBlock), 0, s, keys, u_max[0], u_max[1], u_max[2], u_max[3],
-                    cx.g->n_vertices, cx.g->indptr, eo, cx.d_ctl);
+        if (list_todo != 0) {
+          const unsigned list_blocks = blocks_for((int64_t)um_most + 1, kEnumListSpan);
+          COOP_LAUNCH(K_ENUM_LIST, k_enum_list, dim3(list_blocks, ps.nf), dim3(kListBlock), 0, s, keys, u_max[0], u_max[1], u_max[2], u_max[3],
+                      cx.g->n_vertices, cx.g->indptr, eo, cx.d_ctl, list_todo);
+        }
         // (three blocks fit a CU: one round of resident blocks strides over the items)
-        const int64_t walk_blocks = blocks_for((int64_t)eo.item_cap * 16, kWalkBlock);
+        uint32_t cap_most = 0;
+        for (int f = 0; f < ps.nf; ++f) cap_most = eo.item_cap[f] > cap_most ? eo.item_cap[f] : cap_most;
+        const int64_t walk_blocks = blocks_for((int64_t)cap_most * 16, kWalkBlock);
         COOP_LAUNCH(K_ENUM_WALK, k_enum_walk, dim3((unsigned)(walk_blocks < 768 ? walk_blocks : 768), ps.nf), dim3(kWalkBlock), 0, s,
                     cx.g->indices, (const uint32_t*)cx.g->rev_pos, (const uint32_t*)long_bits, (const LongSlot*)long_tab, long_mask, cap, out,
                     eo, cx.d_ctl);
@@ -1212,6 +1234,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
     if (rc != COOP_OK) return rc;
     if (used_enum && cx.h_ctl->cand_overflow != 0) {  // the lists of the listed vertices did not fit: once more, every list scanned
       no_enum = true;
+      for (auto& had : st.listed) had = LaborState::Listed{};  // (what was listed may be incomplete)
       hipLaunchKernelGGL(k_enum_redo, dim3(1), dim3(1), 0, s, cx.d_ctl, cx.d_piece_count + l);
       continue;
     }

@@ -51,6 +51,11 @@ struct LaborState {
   int64_t covered = 0;       // destinations [0, covered) have every remaining layer staged by those passes
   bool fuse = false;
   uint32_t stage_cap = 32;
+  // LABOR-0 from the neighbours' side: the item list of the vertices with a small variate, per layer, for passes that
+  // come later and cover the same layer (device memory of this call's scratch)
+  struct Listed { struct EnumItem* item = nullptr; uint32_t* n = nullptr; uint32_t cap = 0, u_max = 0; };
+  static constexpr int kMaxListed = 8;
+  Listed listed[kMaxListed];
 };
 
 // Parameters of the random-walk sampler (App. A.1.3).
