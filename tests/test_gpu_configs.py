@@ -84,6 +84,12 @@ def test_papers100m_shaped_full_batch(P):
     get = synth.seed_batches(n, 16384, seed=0, device="cuda")
     arena = P.Arena(4 << 30)
     compare(P, g, ip, ix, get(7), (10, 10, 10), R.LABOR0, it=7, kappa=1, seed=0, arena=arena)
+    try:  # the same batch with every list scanned (the long ones cut into pieces), as on a graph not registered as symmetric
+        P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, 0)
+        arena.reset()
+        compare(P, g, ip, ix, get(7), (10, 10, 10), R.LABOR0, it=7, kappa=1, seed=0, arena=arena)
+    finally:
+        P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, 8192)
     compare(P, g, ip, ix, get(8)[:1024].contiguous(), (10, 10), R.LABOR0, it=8 * 16 + 5, kappa=16, seed=0)
     compare(P, g, ip, ix, get(9)[:512].contiguous(), (10, 10), R.NS, it=9, kappa=1, seed=0)
     # dependent batches around group boundaries and at the last iteration of a 512-iteration run
