@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--sampler", default=None, choices=[None, "labor0", "ns", "rw"],
                     help="rw: random walks with the paper's parameters (length 3, 100 walks, restart probability 0.5)")
     ap.add_argument("--batch", type=int, default=None)
-    ap.add_argument("--mode", default="step", choices=["step", "batch-sweep", "kappa-cache", "host-cache", "mean-agg"],
+    ap.add_argument("--mode", default="step", choices=["step", "batch-sweep", "kappa-cache", "host-cache", "mean-agg", "owner-bucket"],
                     help="step: the benchmark contract (default).  batch-sweep: |S^l| against batch size on nested seed prefixes "
                          "(products-shaped).  kappa-cache: LRU miss rate against kappa over consecutive dependent batches "
                          "(papers100M-shaped, 4M-row cache).  host-cache: pinned-host feature table behind a 32M-row cache "
@@ -465,7 +465,44 @@ def report_mean_agg(args, torch, synth, P):
                       "kernels": res}), flush=True)
 
 
-REPORTS = {"mean-agg": report_mean_agg, "batch-sweep": report_batch_sweep, "kappa-cache": report_kappa_cache, "host-cache": report_host_cache}
+def report_owner_bucket(args, torch, synth, P):
+    """The local half of the id redistribution (Sec. 3.1): the input frontier S^3 of a papers100M-shaped batch grouped by
+    the owning PE of an 8-way vertex partition (contiguous ranges, and the random partition)."""
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["papers100M"]
+    indptr, indices = synth.make_graph("papers100M", device=dev, scale_down=args.scale_down, log=log)
+    n = indptr.numel() - 1
+    graph = P.coop_graph_load(indptr, indices, P.COOP_SYMMETRIC)
+    get_seeds = synth.seed_batches(n, cfg["batch"], seed=0, device=dev)
+    arena = P.Arena(4 << 30)
+    blocks = P.coop_sample(graph, get_seeds(0), cfg["fanouts"], P.COOP_LABOR0, it=0, kappa=1, seed=0, arena=arena)
+    ids = blocks[-1].src_ids.clone()
+    n_ids, n_parts = ids.numel(), 8
+    work = torch.empty(1 << 22, dtype=torch.uint8, device=dev)
+    res = {}
+    for name, scheme in (("ranges", P.COOP_OWNER_RANGE), ("hashed", P.COOP_OWNER_HASH)):
+        for _ in range(3):
+            out = P.coop_bucket_by_owner(ids, n, n_parts, scheme, seed=1, workspace=work)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(20):
+            out = P.coop_bucket_by_owner(ids, n, n_parts, scheme, seed=1, workspace=work)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t) / 20 * 1e3
+        nbytes = 16 * n_ids   # the ids read twice (count, place), the grouped ids and their origins written
+        res[name] = {"ms": round(ms, 4), "ids_per_s": round(n_ids / ms * 1e3, 1), "algorithmic_GB": round(nbytes / 1e9, 4),
+                     "GBps": round(nbytes / ms / 1e6, 1), "group_sizes": [int(x) for x in torch.diff(out[2]).cpu()]}
+        if not args.no_cpu_baseline:
+            from oracle import coopref as R
+            import numpy as np
+            want = R.bucket_by_owner(ids.cpu().numpy(), n, n_parts, scheme, seed=1)
+            res[name]["matches_oracle"] = all(np.array_equal(a.cpu().numpy(), w) for a, w in zip(out, want))
+    P.coop_gather_status()
+    print(json.dumps({"report": "owner-bucket", "workload": "papers100M-shaped graph, S^3 of a 3-layer LABOR-0 batch of %d: %d ids, "
+                      "%d owners" % (cfg["batch"], n_ids, n_parts), "partitions": res}), flush=True)
+
+
+REPORTS = {"owner-bucket": report_owner_bucket, "mean-agg": report_mean_agg, "batch-sweep": report_batch_sweep, "kappa-cache": report_kappa_cache, "host-cache": report_host_cache}
 
 
 def _stored_traffic(kernel, args):

@@ -183,9 +183,33 @@ int coop_gather(const void* feat, int64_t n_rows, int32_t dim, int dtype, const 
 int coop_gather_mean(const void* feat, int64_t n_rows, int32_t dim, int dtype, const int64_t* indptr,
                      const int32_t* col_global, int64_t n_dst, void* out, void* stream);
 
-/* Synchronises `stream` and returns COOP_E_RANGE if any coop_gather / coop_gather_mean since the last call of this function met an
- * id outside [0, n_rows) (such rows of `out` are left zero-filled), else COOP_OK.  Clears the condition. */
+/* Synchronises `stream` and returns COOP_E_RANGE if any coop_gather / coop_gather_mean / coop_bucket_by_owner since the
+ * last call of this function met an id outside its range (such rows of `out` are left zero-filled; such ids are left
+ * out of every group), else COOP_OK.  Clears the condition. */
 int coop_gather_status(void* stream);
+
+/* vertex partitions of Sec. 3.1 (1-D: every vertex, with its in-edges, belongs to one PE) */
+#define COOP_OWNER_RANGE 0  /* contiguous ranges: owner(v) = floor(v * n_parts / n_vertices) */
+#define COOP_OWNER_HASH 1   /* random partition: owner(v) = floor(mix(v ^ key) * n_parts / 2^32), mix = the 32-bit mixer of
+                               the variates, key = low word of seed xor high word */
+
+/*
+ * The local half of the id redistribution of Algorithm 1 (every PE sends the vertices of its frontier to the PEs that
+ * own them; Sec. 3.1): the ids grouped by owner, in their original order within each group.  What one GPU does before
+ * the all-to-all; the exchange itself is not part of this library.
+ *   ids          device int32 [n], each in [0, n_vertices) (others: left out, reported by coop_gather_status)
+ *   n_parts      1 .. 64
+ *   ids_out      device int32 [n]: group p is [offsets_out[p], offsets_out[p + 1])
+ *   origin_out   device int32 [n] or NULL: the position that each entry of ids_out had in ids (the way back for what the
+ *                owner returns)
+ *   offsets_out  device int64 [n_parts + 1]
+ *   workspace    device, 8-byte aligned, at least coop_bucket_workspace_bytes(n, n_parts) bytes; contents undefined after
+ * Asynchronous on `stream`; allocates nothing.
+ */
+size_t coop_bucket_workspace_bytes(int64_t n, int n_parts);
+int coop_bucket_by_owner(const int32_t* ids, int64_t n, int64_t n_vertices, int n_parts, int scheme, uint64_t seed,
+                         int32_t* ids_out, int32_t* origin_out, int64_t* offsets_out, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /*
  * LRU vertex cache on the GPU in front of a feature table that the device can read but that is slow to read

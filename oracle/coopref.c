@@ -613,6 +613,34 @@ int coopref_gather(const void* feat, int64_t n_rows, int64_t row_bytes, const in
   return COOPREF_OK;
 }
 
+/* Sec. 3.1 / Algorithm 1: the vertices of a frontier grouped by the PE that owns them, in their original order within
+ * each group.  scheme 0: PE p owns a contiguous range, owner(v) = floor(v P / |V|); scheme 1: a random partition,
+ * owner(v) = floor(mix32(v ^ key) P / 2^32) with key = the low word of seed xor its high word.  ids_out and origin_out
+ * (the position that each entry had in ids) get n entries, offsets_out P + 1: group p is [offsets[p], offsets[p+1]). */
+int coopref_bucket_by_owner(const int32_t* ids, int64_t n, int64_t n_vertices, int n_parts, int scheme, uint64_t seed,
+                            int32_t* ids_out, int32_t* origin_out, int64_t* offsets_out) {
+  if ((!ids && n > 0) || !offsets_out) return COOPREF_E_NULL;
+  if (n < 0 || n_vertices < 1 || n_parts < 1 || (scheme != 0 && scheme != 1)) return COOPREF_E_ARG;
+  const uint32_t key = (uint32_t)(seed ^ (seed >> 32));
+  int64_t at = 0;
+  for (int p = 0; p < n_parts; ++p) {       /* one sweep over the list per PE: group p is what the sweep finds */
+    offsets_out[p] = at;
+    for (int64_t i = 0; i < n; ++i) {
+      if (ids[i] < 0 || ids[i] >= n_vertices) return COOPREF_E_RANGE;
+      const uint64_t v = (uint64_t)ids[i];
+      const uint64_t owner = scheme == 0 ? (v * (uint64_t)n_parts) / (uint64_t)n_vertices
+                                         : ((uint64_t)coopref_mix32((uint32_t)v ^ key) * (uint64_t)n_parts) >> 32;
+      if (owner == (uint64_t)p) {
+        ids_out[at] = ids[i];
+        origin_out[at] = (int32_t)i;
+        ++at;
+      }
+    }
+  }
+  offsets_out[n_parts] = at;
+  return COOPREF_OK;
+}
+
 /* IEEE binary16 -> double, from the bit fields (no compiler half type needed). */
 static double half_to_double(uint16_t h) {
   int sign = h >> 15, ex = (h >> 10) & 31, man = h & 1023;

@@ -171,6 +171,23 @@ def gather(feat, ids):
     return out
 
 
+def bucket_by_owner(ids, n_vertices, n_parts, scheme, seed=0):
+    """(ids grouped by owner, their original positions, group offsets [n_parts + 1]); scheme 0 = ranges, 1 = hashed."""
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    out = np.empty(len(ids), dtype=np.int32)
+    origin = np.empty(len(ids), dtype=np.int32)
+    offsets = np.empty(n_parts + 1, dtype=np.int64)
+    L = lib()
+    L.coopref_bucket_by_owner.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
+    L.coopref_bucket_by_owner.restype = C.c_int
+    rc = L.coopref_bucket_by_owner(ids.ctypes.data, len(ids), int(n_vertices), int(n_parts), int(scheme), int(seed),
+                                   out.ctypes.data, origin.ctypes.data, offsets.ctypes.data)
+    if rc != OK:
+        raise OracleError(rc)
+    return out, origin, offsets
+
+
 def gather_mean(feat, indptr, col):
     """float64 [n_dst, dim]: mean of feat[col[e], :] over the edges of every destination (0 where there are none)."""
     feat = np.ascontiguousarray(feat)

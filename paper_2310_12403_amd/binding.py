@@ -258,6 +258,35 @@ def coop_sample_rw(graph, seeds, fanouts, walk_length, n_walks, restart_p, it=0,
     return [Block(blocks[l], al) for l in range(L)]
 
 
+COOP_OWNER_RANGE, COOP_OWNER_HASH = 0, 1
+
+
+def coop_bucket_by_owner(ids, n_vertices, n_parts, scheme=COOP_OWNER_RANGE, seed=0, want_origin=True, workspace=None, stream=None):
+    """The ids grouped by owner (stable): returns (ids_out, origin_out or None, offsets int64 [n_parts + 1]), all on the device."""
+    L = lib()
+    L.coop_bucket_workspace_bytes.argtypes = [C.c_int64, C.c_int]
+    L.coop_bucket_workspace_bytes.restype = C.c_size_t
+    L.coop_bucket_by_owner.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.coop_bucket_by_owner.restype = C.c_int
+    n = ids.numel()
+    need = L.coop_bucket_workspace_bytes(n, n_parts)
+    if need == 0:
+        raise CoopError(-4)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=ids.device)
+    assert workspace.numel() * workspace.element_size() >= need
+    out = torch.empty_like(ids)
+    origin = torch.empty_like(ids) if want_origin else None
+    offsets = torch.empty(n_parts + 1, dtype=torch.int64, device=ids.device)
+    rc = L.coop_bucket_by_owner(_dev_ptr(ids, torch.int32) if n else None, n, n_vertices, n_parts, scheme, seed,
+                                C.c_void_p(out.data_ptr()) if n else None, C.c_void_p(origin.data_ptr()) if want_origin and n else None,
+                                C.c_void_p(offsets.data_ptr()), C.c_void_p(workspace.data_ptr()),
+                                workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(rc)
+    return out, origin, offsets
+
+
 def coop_copy_ids(ids, out=None, stream=None):
     """A plain copy of a device int32 list on the stream."""
     if out is None:

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcoop.so")
-SOURCES = ["runtime.hip", "sample.hip", "labor.hip", "ns.hip", "rw.hip", "unique.hip", "gather.hip", "cache.hip"]
+SOURCES = ["runtime.hip", "sample.hip", "labor.hip", "ns.hip", "rw.hip", "unique.hip", "gather.hip", "owner.hip", "cache.hip"]
 
 # -ffp-contract=off: the variate kit spells every fused multiply-add out; nothing may be contracted behind its back.
 # packed-fp32-ops off: keep the compiler from forming packed fp32 instructions.

@@ -33,6 +33,8 @@ enum KernelId {
   K_COPY_IDS,        // seed copy / src_ids prefix copy
   K_GATHER,          // feature row gather
   K_GATHER_MEAN,     // neighbour mean fused with the feature load
+  K_OWNER_COUNT,     // ids by owner: per-wave counts
+  K_OWNER_SCATTER,   // ids by owner: stable placement
   K_VALIDATE,        // CSR validation
   K_CACHE_LOOKUP,
   K_CACHE_SELECT,
@@ -110,6 +112,9 @@ void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int6
                       const Publish* pub = nullptr, const int64_t* n_bits_dev = nullptr);
 
 void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
+
+// The current device's sticky "an id was out of range" word (device memory; read and cleared by coop_gather_status).
+int32_t* bad_flag();
 
 // Per-call scratch allocator wrapper: 256-byte rounding, NULL check.
 struct Alloc {

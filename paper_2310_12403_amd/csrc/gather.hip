@@ -134,6 +134,8 @@ constexpr int kMaxDevices = 64;
 std::mutex g_bad_mu;
 int32_t* g_bad_flag[kMaxDevices] = {};  // per device: a device word, sticky "an id was out of range"
 
+}  // namespace
+
 // the current device's flag word, created on first use (a few bytes, kept for the life of the process)
 int32_t* bad_flag() {
   int dev = 0;
@@ -147,6 +149,8 @@ int32_t* bad_flag() {
   }
   return g_bad_flag[dev];
 }
+
+namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));

@@ -462,7 +462,7 @@ def test_random_walk_sampler_errors(P, tiny):
     assert e.value.code == -4
     with pytest.raises(P.CoopError) as e:
         P.coop_sample_rw(tiny.graph, torch.tensor([1, 1], dtype=torch.int32).cuda(), (5,), 3, 10, 0.5)
-    assert e.value.code == -3
+    assert e.value.code == -2
     with pytest.raises(P.CoopError) as e:
         P.coop_sample_rw(tiny.graph, torch.tensor([tiny.n], dtype=torch.int32).cuda(), (5,), 3, 10, 0.5)
     assert e.value.code == -2
@@ -721,3 +721,38 @@ def test_symmetric_flag_is_checked(P, tiny):
     with pytest.raises(P.CoopError) as e:
         P.coop_graph_load(d_ip, d_ix, P.COOP_SYMMETRIC)
     assert e.value.code == -8
+
+
+@pytest.mark.parametrize("scheme", [0, 1])
+def test_bucket_by_owner(P, scheme):
+    """The local half of the id redistribution (Sec. 3.1, Algorithm 1): ids grouped by owner, original order kept, against
+    the oracle's sweep per owner: sizes that span one wave, several stretches and a ragged tail, 1 to 64 owners, an empty
+    list, and an id out of range (left out of every group, reported by coop_gather_status)."""
+    rng = np.random.default_rng(17 + scheme)
+    nv = 1_000_003
+    for n, n_parts in ((0, 4), (1, 1), (63, 3), (64, 64), (5000, 8), (70001, 5), (600_000, 8), (5_000_011, 64)):
+        ids = rng.integers(0, nv, size=n).astype(np.int32)
+        if n > 100:
+            ids[: n // 3] = np.sort(ids[: n // 3])            # a sorted stretch: long runs of one owner
+        want = R.bucket_by_owner(ids, nv, n_parts, scheme, seed=99)
+        got = P.coop_bucket_by_owner(torch.from_numpy(ids).cuda(), nv, n_parts, scheme, seed=99)
+        P.coop_gather_status()
+        for a, w, name in zip(got, want, ("ids", "origin", "offsets")):
+            assert np.array_equal(a.cpu().numpy(), w), (n, n_parts, name)
+    # without the way back
+    ids = rng.integers(0, nv, size=3000).astype(np.int32)
+    got = P.coop_bucket_by_owner(torch.from_numpy(ids).cuda(), nv, 8, scheme, seed=1, want_origin=False)
+    assert got[1] is None and np.array_equal(got[0].cpu().numpy(), R.bucket_by_owner(ids, nv, 8, scheme, seed=1)[0])
+    # an id outside [0, |V|)
+    bad = ids.copy()
+    bad[17] = nv
+    out, origin, offsets = P.coop_bucket_by_owner(torch.from_numpy(bad).cuda(), nv, 8, scheme, seed=1)
+    with pytest.raises(P.CoopError) as e:
+        P.coop_gather_status()
+    assert e.value.code == -2
+    keep = np.delete(ids, 17)
+    want = R.bucket_by_owner(keep, nv, 8, scheme, seed=1)
+    assert int(offsets[-1]) == len(keep) and np.array_equal(out.cpu().numpy()[: len(keep)], want[0])
+    for args in ((nv, 0), (nv, 65), (0, 4)):
+        with pytest.raises(P.CoopError):
+            P.coop_bucket_by_owner(torch.from_numpy(ids).cuda(), args[0], args[1], scheme)

@@ -703,3 +703,42 @@ def test_rw_error_codes_and_kappa_free(tiny):
     a = R.sample(indptr, indices, seeds, (5, 5), R.RW, it=3, seed=1, rw=(3, 10, 0.5))
     b = R.sample(indptr, indices, seeds, (5, 5), R.RW, it=4, seed=1, rw=(3, 10, 0.5))
     assert any(not np.array_equal(x["col_global"], y["col_global"]) for x, y in zip(a, b))   # fresh draws per iteration
+
+
+# ---- ids grouped by owner (Sec. 3.1, Algorithm 1: the local half of the id redistribution) ----------------------------
+@pytest.mark.parametrize("n_parts", [1, 3, 8, 64])
+def test_bucket_by_owner_ranges_closed_form(n_parts):
+    """owner(v) = floor(v P / |V|) = p exactly when ceil(p |V| / P) <= v < ceil((p + 1) |V| / P): the oracle's groups
+    against those boundaries, and against a stable argsort of the owners (a library routine)."""
+    rng = np.random.default_rng(5)
+    nv = 100003
+    ids = rng.integers(0, nv, size=20011).astype(np.int32)
+    out, origin, offsets = R.bucket_by_owner(ids, nv, n_parts, 0)
+    assert offsets[0] == 0 and offsets[-1] == len(ids) and np.all(np.diff(offsets) >= 0)
+    assert np.array_equal(out, ids[origin])
+    bounds = [-(-p * nv // n_parts) for p in range(n_parts + 1)]   # ceil(p |V| / P)
+    for p in range(n_parts):
+        grp, org = out[offsets[p]:offsets[p + 1]], origin[offsets[p]:offsets[p + 1]]
+        assert np.all((grp >= bounds[p]) & (grp < bounds[p + 1]))
+        assert np.all(np.diff(org) > 0)                            # original order kept within the group
+    owner = (ids.astype(np.int64) * n_parts) // nv
+    assert np.array_equal(origin, np.argsort(owner, kind="stable").astype(np.int32))
+    assert np.array_equal(offsets, np.concatenate([[0], np.cumsum(np.bincount(owner, minlength=n_parts))]))
+
+
+def test_bucket_by_owner_hashed_against_independent_mixer():
+    """The random partition: owners recomputed with the pure-Python mixer of this file; groups of about equal size."""
+    rng = np.random.default_rng(6)
+    nv, n_parts, seed = 50000, 8, (7 << 32) | 12345
+    ids = rng.permutation(nv)[:12000].astype(np.int32)
+    out, origin, offsets = R.bucket_by_owner(ids, nv, n_parts, 1, seed=seed)
+    key = (seed ^ (seed >> 32)) & 0xFFFFFFFF
+    owner = np.array([(py_mix32(int(v) ^ key) * n_parts) >> 32 for v in ids], dtype=np.int64)
+    assert np.array_equal(origin, np.argsort(owner, kind="stable").astype(np.int32))
+    assert np.array_equal(out, ids[origin])
+    sizes = np.diff(offsets)
+    assert sizes.sum() == len(ids) and np.all(np.abs(sizes - len(ids) / n_parts) < 6 * np.sqrt(len(ids) / n_parts))
+    with pytest.raises(R.OracleError):
+        R.bucket_by_owner(np.array([nv], dtype=np.int32), nv, n_parts, 0)
+    empty = R.bucket_by_owner(np.zeros(0, dtype=np.int32), nv, n_parts, 0)
+    assert len(empty[0]) == 0 and np.array_equal(empty[2], np.zeros(n_parts + 1, dtype=np.int64))
