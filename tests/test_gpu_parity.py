@@ -462,7 +462,7 @@ def test_random_walk_sampler_errors(P, tiny):
     assert e.value.code == -4
     with pytest.raises(P.CoopError) as e:
         P.coop_sample_rw(tiny.graph, torch.tensor([1, 1], dtype=torch.int32).cuda(), (5,), 3, 10, 0.5)
-    assert e.value.code == -2
+    assert e.value.code == -3
     with pytest.raises(P.CoopError) as e:
         P.coop_sample_rw(tiny.graph, torch.tensor([tiny.n], dtype=torch.int32).cuda(), (5,), 3, 10, 0.5)
     assert e.value.code == -2
