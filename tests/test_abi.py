@@ -46,6 +46,23 @@ def test_host_checked_arguments():
     assert L.coop_gather(None, 10, 4, 0, None, 5, None, None) == -1                 # NULL tables
 
 
+def test_bucket_by_owner_host_checks():
+    L = P.lib()
+    L.coop_bucket_workspace_bytes.argtypes = [C.c_int64, C.c_int]
+    L.coop_bucket_workspace_bytes.restype = C.c_size_t
+    L.coop_bucket_by_owner.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    need = L.coop_bucket_workspace_bytes(1000, 8)
+    assert 0 < need < (1 << 22) and L.coop_bucket_workspace_bytes(1 << 30, 64) < (1 << 23)   # a few MB whatever n
+    assert L.coop_bucket_workspace_bytes(1000, 0) == 0 and L.coop_bucket_workspace_bytes(1000, 65) == 0
+    assert L.coop_bucket_workspace_bytes(-1, 8) == 0
+    assert L.coop_bucket_by_owner(None, 10, 100, 0, 0, 0, None, None, None, None, 0, None) == -4    # no owners
+    assert L.coop_bucket_by_owner(None, 10, 100, 8, 2, 0, None, None, None, None, 0, None) == -4    # unknown partition
+    assert L.coop_bucket_by_owner(None, 10, 0, 8, 0, 0, None, None, None, None, 0, None) == -4      # no vertices
+    assert L.coop_bucket_by_owner(None, 10, 100, 8, 0, 0, None, None, None, None, 0, None) == -1    # NULL buffers
+    assert L.coop_bucket_by_owner(None, 0, 100, 8, 0, 0, None, None, 0x1000, 0x2000, 16, None) == -4  # workspace too small
+
+
 def test_arena_bump_allocator():
     L = P.lib()
     a = binding._CArena(0x10000, 1000, 0)
