@@ -206,6 +206,7 @@ def main():
         # reads them, and they are not counted here.
         Lf = len(fanouts)
         per_step = 0
+        per_step_every_list = 0
         covered = 0                    # the library's pass rule: a pass over fewer than 32768 lists covers its own layer only
         # (and only on a graph whose lists above 8192 hold an eighth of the edges or more)
         other_side = (symmetric and sampler == P.COOP_LABOR0 and args.kappa == 1 and max(fanouts) <= 64
@@ -213,16 +214,25 @@ def main():
         for l in range(Lf):
             n_new = n_last[l] - covered
             d_new = deg[blocks[l].dst_ids[covered:].long()]
-            if other_side and n_new >= 65536:
-                d_new = d_new[d_new <= 8192]
             fused = n_new >= 32768 or l == Lf - 1
             nf = Lf - l if fused else 1
+            per_step_every_list += 16 * n_new + 8 * nf * n_new + 4 * int(d_new.sum())
+            if other_side and n_new >= 65536:
+                d_new = d_new[d_new <= 8192]
             per_step += 16 * n_new + 8 * nf * n_new + 4 * int(d_new.sum())
             if fused:
                 covered = n_last[l]
         alg_dom = per_step / Lf
         roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
                         unit="GB/s")
+        # Beside it: the count stage as a whole (the scan and, on a symmetric graph, the two kernels that stand in for the
+        # scan of the longest lists) against the bytes of a scan that reads every list once, the survey's algorithmic
+        # figure for this stage.  Times from the per-kernel pass (HIP events around every launch).
+        stage_ms = sum(breakdown.get(k, 0.0) for k in ("labor_scan", "enum_list", "enum_walk"))
+        count_stage = dict(kernels=[k for k in ("labor_scan", "enum_list", "enum_walk") if k in breakdown], ms_per_step=round(stage_ms, 4),
+                           bytes_every_list_once=per_step_every_list,
+                           effective_GBps=round(per_step_every_list / (stage_ms * 1e-3) / 1e9, 1),
+                           effective_frac=round(per_step_every_list / (stage_ms * 1e-3) / HBM_PEAK, 4))
     elif dominant == "rw_walk":
         alg_dom = sum(rw_walk_bytes(n_last[l]) + 4 * n_last[l] + 8 * m_last[l] for l in range(len(fanouts))) / len(fanouts)
         roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
@@ -270,6 +280,8 @@ def main():
         "step_hbm_frac": round(step_frac, 4),
         "roofline": roofline,
     }
+    if dominant == "labor_scan":
+        result["count_stage"] = count_stage
 
     # ---- CPU baseline: the oracle as it stands, on the host cores of this machine ----------------------------------------
     if not args.no_cpu_baseline:
