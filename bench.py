@@ -91,7 +91,10 @@ def main():
     get_seeds = synth.seed_batches(n, batch, seed=0, device=dev)
     # (the synthetic graphs are undirected, stored both ways with sorted lists, like the bidirected benchmark graphs of the paper)
     symmetric = not args.plain_graph
+    torch.cuda.synchronize()
+    t_load = time.perf_counter()
     graph = P.coop_graph_load(indptr, indices, P.COOP_VALIDATE | (P.COOP_SYMMETRIC if symmetric else 0))
+    load_ms = (time.perf_counter() - t_load) * 1e3
     arena = P.Arena(4 << 30)
     deg = indptr[1:] - indptr[:-1]
 
@@ -252,6 +255,7 @@ def main():
     roofline["launches"] = dom_launches
     roofline["algorithmic_bytes_per_launch"] = alg_dom
     roofline["traffic"] = _stored_traffic(dominant + ("_plain_graph" if dominant == "labor_scan" and not symmetric else ""), args)
+    step_traffic = _stored_traffic("step_all_kernels", args) if (symmetric and sampler == P.COOP_LABOR0 and args.kappa == 1) else None
     roofline["achieved"] = round(roofline["achieved"], 2)
     roofline["frac"] = round(roofline["frac"], 4)
 
@@ -276,12 +280,55 @@ def main():
                             "n_src": [b.n_src for b in blocks]},
         "per_kernel_ms_per_step": breakdown,
         "gather_GBps": round((2 * row_bytes) * (stats["n_in"] / K) / (breakdown.get("gather", float("nan")) * 1e-3) / 1e9, 1),
-        "step_algorithmic_bytes": alg_sample + alg_gather,
-        "step_hbm_frac": round(step_frac, 4),
+        # two views of the whole step.  "survey" = the per-layer algorithmic bytes of the scope table (every list of S^l
+        # charged at every layer l: what a layer-by-layer sampler must move), divided by the step time: an EFFECTIVE rate,
+        # which the fused scan and the lists served from the neighbours' side undercut.  "measured" = HBM bytes actually
+        # moved by all kernels of a step (rocprofv3 FETCH_SIZE / WRITE_SIZE summary under profiles/), divided by the same
+        # step time: the achieved bandwidth.
+        "step_survey_bytes": alg_sample + alg_gather,
+        "step_hbm_frac_effective_survey_bytes": round(step_frac, 4),
+        "step_traffic_bytes": step_traffic,
+        "step_hbm_frac_measured": None if step_traffic is None else round(step_traffic / (ms_per_step * 1e-3) / HBM_PEAK, 4),
         "roofline": roofline,
     }
     if dominant == "labor_scan":
         result["count_stage"] = count_stage
+    if symmetric and sampler == P.COOP_LABOR0:
+        result["reverse_index"] = {"bytes": 4 * nnz, "build_ms": round(load_ms, 1),
+                                   "note": "COOP_SYMMETRIC registration: one uint32 per edge, built once per graph, outside the timed region"}
+
+    # ---- the configuration's other workloads, timed the same way (K steps between two synchronisations) ----------------
+    if args.config == "papers100M" and sampler == P.COOP_LABOR0 and args.kappa == 1 and not args.plain_graph:
+        def timed(sample_fn):
+            arena.reset()
+            rows = torch.empty((int(sample_fn(0)[-1].n_src * 1.25) + 1024, dim), dtype=dtype, device=dev)   # sized from a dry run
+
+            def one(i):
+                arena.reset()
+                P.coop_gather(feat, sample_fn(i)[-1].src_ids, out=rows)
+
+            for i in range(3):
+                one(i)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for i in range(K):
+                one(args.warmup + i)
+            torch.cuda.synchronize()
+            return round((time.perf_counter() - t) / K * 1e3, 4)
+
+        def dependent(kappa):
+            return lambda i: P.coop_sample(graph, get_seeds(i), fanouts, P.COOP_LABOR0, it=i * kappa + kappa // 3 + 1, kappa=kappa, seed=0,
+                                           arena=arena)
+
+        def ns_step(i):
+            return P.coop_sample(graph, get_seeds(i), fanouts, P.COOP_NS, it=i, kappa=1, seed=0, arena=arena)
+
+        result["kappa16_ms_per_step"] = timed(dependent(16))     # dependent variates, c = 6/16 (every step inside a group)
+        result["kappa256_ms_per_step"] = timed(dependent(256))   # c = 86/256
+        result["ns_ms_per_step"] = timed(ns_step)                # NS 10/10/10 on the same batches
+        P.coop_gather_status()
+        log("kappa 16: %.3f ms, kappa 256: %.3f ms, NS: %.3f ms per step" % (result["kappa16_ms_per_step"], result["kappa256_ms_per_step"],
+                                                                           result["ns_ms_per_step"]))
 
     # ---- CPU baseline: the oracle as it stands, on the host cores of this machine ----------------------------------------
     if not args.no_cpu_baseline:
@@ -569,9 +616,31 @@ def cpu_baseline(args, indptr, indices, feat, get_seeds, fanouts, sampler, last_
         batches += 1
         i -= 1
         del rows, blocks
-    return {"value": round(edges / spent, 1), "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
-            "sample": "%d whole batches of the same workload (sampling + gather), %.1f s of single-thread CPU time" % (batches, spent),
-            "matches_gpu_last_step": parity}
+    single = {"value": round(edges / spent, 1), "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
+              "sample": "%d whole batches of the same workload (sampling + gather), %.1f s of single-thread CPU time" % (batches, spent),
+              "matches_gpu_last_step": parity}
+    # The same oracle on all host cores of this machine's share: one whole batch per thread, different batches side by side
+    # (the oracle's C call releases the interpreter lock; the oracle itself stays the plain single-threaded code).
+    from concurrent.futures import ThreadPoolExecutor
+    cores = max(1, min(16, os.cpu_count() or 1))
+
+    if args.kappa not in (0, 1):   # (with dependent variates one batch takes the oracle minutes: the single-thread figure stands alone)
+        return single
+    seeds_all = [get_seeds(args.warmup + K + j).cpu().numpy() for j in range(cores)]
+
+    def one(j):
+        blocks = R.sample(ip_h, ix_h, seeds_all[j], fanouts, sampler, it=args.warmup + K + j, kappa=args.kappa, seed=0, rw=RW_PARAMS)
+        R.gather(feat_h, blocks[-1]["src_ids"])
+        return sum(len(b["col_global"]) for b in blocks)
+
+    t = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        total = sum(pool.map(one, range(cores)))
+    wall = time.perf_counter() - t
+    single["all_cores"] = {"value": round(total / wall, 1), "unit": "sampled edges/s", "cores": cores, "kind": "oracle",
+                           "sample": "%d whole batches, one per thread, side by side: %.1f s wall" % (cores, wall)}
+    log("cpu baseline: %d threads, %.1f s wall, %.3g sampled edges/s" % (cores, wall, total / wall))
+    return single
 
 
 if __name__ == "__main__":

@@ -309,6 +309,20 @@ int coop_tune(int knob, int64_t value);
  * use for snapshotting seed lists it is the known-size reference that the byte counters of a profiler are scaled by. */
 int coop_copy_ids(const int32_t* in, int32_t* out, int64_t n, void* stream);
 
+/*
+ * Self-check of the arithmetic behind the dependent variates of App. A.7 (c > 0): the kernels settle most neighbours
+ * with Phi^-1 evaluated in fp32 by this GPU's own logarithm, square root and reciprocal instructions, and take the exact
+ * binary64 evaluation only where the fp32 value lies within a margin of the decision.  That margin presumes a bound on
+ * the distance between the two evaluations; this call measures the distance for the 32-bit uniforms
+ * U = first .. first + count - 1 (first + count <= 2^32; the whole range takes a fraction of a second).
+ *   max_gap_out host: max |fp32 Phi^-1((U + 1/2) / 2^32) - binary64 Phi^-1((U + 1/2) / 2^32)|
+ *   arg_out     host, may be NULL: a U at which a maximum was seen
+ *   workspace   device, 8-byte aligned, 16 bytes, contents undefined after
+ * Synchronises `stream`.
+ */
+int coop_selftest_phi_inv_gap(uint64_t first, uint64_t count, double* max_gap_out, uint32_t* arg_out, void* workspace,
+                              void* stream);
+
 /* Library ABI version (bumped when a signature in this file changes). */
 int coop_version(void);
 

@@ -13,6 +13,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "coopref.c")
 _LIB = os.path.join(_HERE, "libcoopref.so")
+_OVERRIDE = os.environ.get("COOPREF_LIBRARY_PATH")   # another build of coopref.c (the sanitizer build), loaded as it is
 
 NS, LABOR0, RW = 0, 1, 2
 OK, E_NULL, E_RANGE, E_DUPSEED, E_ARG, E_NOMEM = 0, -1, -2, -3, -4, -5
@@ -40,8 +41,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        if not _OVERRIDE:
+            build()
+        L = C.CDLL(_OVERRIDE or _LIB)
         L.coopref_philox4x32_10.argtypes = [C.POINTER(C.c_uint32)] * 3
         L.coopref_philox4x32_10.restype = None
         L.coopref_mix32.argtypes = [C.c_uint32]

@@ -5,7 +5,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libcoop.so")
+# (COOP_LIBRARY_PATH: another build of the same sources, e.g. the host-sanitizer build of `python -m paper_2310_12403_amd.build --sanitize`)
+_LIB_PATH = os.environ.get("COOP_LIBRARY_PATH") or os.path.join(_HERE, "libcoop.so")
 
 COOP_NS, COOP_LABOR0, COOP_RW = 0, 1, 2
 COOP_F32, COOP_F16 = 0, 1
@@ -406,6 +407,17 @@ class Cache:
             self.close()
         except Exception:
             pass
+
+
+def coop_selftest_phi_inv_gap(first=0, count=1 << 32, stream=None):
+    """(largest |fp32 Phi^-1 - binary64 Phi^-1| over the uniforms first .. first + count - 1, a uniform where a maximum was seen)."""
+    L = lib()
+    L.coop_selftest_phi_inv_gap.argtypes = [C.c_uint64, C.c_uint64, C.POINTER(C.c_double), C.POINTER(C.c_uint32), C.c_void_p, C.c_void_p]
+    L.coop_selftest_phi_inv_gap.restype = C.c_int
+    work = torch.empty(2, dtype=torch.int64, device="cuda")
+    gap, arg = C.c_double(), C.c_uint32()
+    _check(L.coop_selftest_phi_inv_gap(first, count, C.byref(gap), C.byref(arg), C.c_void_p(work.data_ptr()), _stream_ptr(stream)))
+    return gap.value, arg.value
 
 
 COOP_TUNE_STAGE_CAP = 1

@@ -448,7 +448,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_select(const NsRecord* __restrict
     }
     const uint64_t kth = ballot64(has && rank_est == k - 1);  // exactly one lane (n >= k)
     const float e_k = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(est), __builtin_ctzll(kth)));
-    const float allow = (float)((vp.cw + vp.sw) * 4e-3 + 2e-5);
+    const float allow = (float)((vp.cw + vp.sw) * kPhiInvF32Allow + 2.0 * kBlendAbsWiden);
     const float m = 2.0f * allow;
     // outside |e_k| <= 5 two different blends can share a 32-bit variate, and the estimate says nothing about ties; and
     // e_k must lie safely below what the traversal's filter let through, or a neighbour that it dropped could belong

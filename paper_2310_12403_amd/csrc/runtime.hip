@@ -364,7 +364,7 @@ const char* coop_strerror(int code) {
   }
 }
 
-int coop_version(void) { return 1; }
+int coop_version(void) { return 2; }
 
 void* coop_arena_alloc(void* arena, size_t bytes, int tag) {
   (void)tag;

@@ -185,8 +185,9 @@ __device__ __forceinline__ double kit_phi_inv_u32(uint32_t U) {
 }
 
 // The same rational form in fp32 with the hardware's logarithm, square root and reciprocal: within 4e-4 of
-// kit_phi_inv_u32 (the central branch's large alternating coefficients cancel in fp32).  Only ever used to discard
-// candidates that are safely outside a threshold; never decides anything by itself.
+// kit_phi_inv_u32 for every U (kPhiInvF32Gap in blend_filters.h; coop_selftest_phi_inv_gap measures the distance over
+// all 2^32 inputs; the central branch's large alternating coefficients cancel in fp32).  Used by the filters in front
+// of the exact blend, which settle a candidate with it only where ten times that distance cannot change the outcome.
 __device__ __forceinline__ float approx_phi_inv_f32(uint32_t U) {
   const bool upper = U >= 0x80000000u;
   const uint32_t Ul = upper ? (0xFFFFFFFFu - U) : U;

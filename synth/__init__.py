@@ -187,6 +187,23 @@ def chung_lu_csr(n, m_undirected, exponent, seed=0, device="cpu", chunk=1 << 26,
     return indptr, indices[:nnz]
 
 
+def directed_from_symmetric(indptr, indices, stream=0):
+    """A directed graph out of an undirected one stored both ways: of every pair of opposite edges exactly one
+    survives, chosen by a hash of the unordered pair, so that N(s) (in-neighbours) and the out-neighbourhood of s
+    differ.  Lists stay ascending.  Returns (indptr int64, indices int32) on the input's device."""
+    n = indptr.numel() - 1
+    deg = indptr[1:] - indptr[:-1]
+    rows = torch.repeat_interleave(torch.arange(n, dtype=torch.int64, device=indptr.device), deg)
+    cols = indices.to(torch.int64)
+    lo, hi = torch.minimum(rows, cols), torch.maximum(rows, cols)
+    bit = hash_u53(lo * n + hi, 4000 + stream) & 1          # one coin per unordered pair
+    keep = (bit == 1) == (rows < cols)                       # heads: the edge into the larger id survives, tails: the other
+    new_deg = torch.bincount(rows[keep], minlength=n)
+    out_ptr = torch.zeros(n + 1, dtype=torch.int64, device=indptr.device)
+    out_ptr[1:] = torch.cumsum(new_deg, 0)
+    return out_ptr, indices[keep].contiguous()
+
+
 # --------------------------------------------------------------------------- #
 # features, seeds
 # --------------------------------------------------------------------------- #

@@ -4,12 +4,41 @@ safety margin.  This checks, on the CPU and with the oracle's bit-identical arit
 necessary condition: whenever the exact variate keeps an edge, the filter passes it.  (The GPU parity tests then check
 the kernel that uses them.)"""
 import math
+import os
+import re
 
 import numpy as np
 
 from oracle import coopref as R
 
 M32 = 0xFFFFFFFF
+
+# The margins are the HIP path's own: read from the header that the kernels are compiled from, so that a margin that
+# drifts there is the margin that is checked here.
+_HDR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2310_12403_amd", "csrc", "blend_filters.h")
+
+
+def header_constants():
+    text = open(_HDR).read()
+    found = dict(re.findall(r"constexpr (?:double|uint32_t) (k[A-Za-z0-9]+) = ([0-9.eE+-]+)u?;", text))
+    return {k: float(v) for k, v in found.items()}
+
+
+_K = header_constants()
+GAP = _K["kPhiInvF32Gap"]          # claimed distance between the fp32 and the binary64 Phi^-1 (measured on the GPU for every input)
+REL, ABS = _K["kBlendRelWiden"], _K["kBlendAbsWiden"]
+THR_WIDEN = int(_K["kThrWiden"])
+
+
+def test_header_margins_are_the_ones_the_kernels_use():
+    """Every margin named in the header is used by the threshold functions in it (and not replaced by a literal), and the
+    allowance leaves room: ten times the claimed distance."""
+    text = open(_HDR).read()
+    for name in ("kPhiInvF32Allow", "kBlendRelWiden", "kBlendAbsWiden", "kStripShift", "kThrWiden"):
+        assert len(re.findall(r"\b%s\b" % name, text)) >= 2, name
+    body = text[text.index("blend_second_threshold"):]
+    assert not re.search(r"[^0-9a-zA-Z_.](4e-3|1e-5|0\.6)[^0-9]", body)
+    assert _K["kPhiInvF32Allow"] >= 10 * GAP > 0 and REL >= 1e-7 and THR_WIDEN >= 1
 
 
 def pre_threshold(L, thr, cw, sw):
@@ -68,8 +97,8 @@ def test_pre_threshold_is_selective():
 # --------------------------------------------------------------------------- #
 # Second filter: the blend itself in fp32 with a safety margin
 # --------------------------------------------------------------------------- #
-EPS2 = 4e-3          # allowance for one fp32 Phi^-1 against the fp64 kit's (the measured gap is below 4e-4: the
-                     # central branch's large alternating coefficients cancel in fp32)
+EPS2 = _K["kPhiInvF32Allow"]   # allowance for one fp32 Phi^-1 against the fp64 kit's (the distance itself stays below
+                               # kPhiInvF32Gap: the central branch's large alternating coefficients cancel in fp32)
 
 
 def approx_phi_inv_f32(U):
@@ -103,11 +132,11 @@ def approx_phi_inv_f32(U):
 
 
 def second_threshold(L, thr, cw, sw):
-    """Restatement of blend_second_threshold() in csrc/labor.hip: keep needs n = cw n1 + sw n2 below this."""
+    """Restatement of blend_second_threshold() in csrc/blend_filters.h: keep needs n = cw n1 + sw n2 below this."""
     if thr >= 0x7FFFFFF0:
         return np.float32(np.inf)
-    tau = L.coopref_phi_inv_u32(thr + 8)
-    lim = tau * (1.0 - 1e-6) + (cw + sw) * EPS2 + 1e-5
+    tau = L.coopref_phi_inv_u32(thr + THR_WIDEN)
+    lim = tau * (1.0 - REL) + (cw + sw) * EPS2 + ABS
     t = np.float32(lim)
     return np.nextafter(t, np.float32(np.inf)) if float(t) < lim else t
 
@@ -121,7 +150,7 @@ def test_fp32_phi_inv_is_close_to_the_kit():
     Us += [int(10 ** rng.uniform(0, 9.6)) for _ in range(20000)]
     for U in Us:
         worst = max(worst, abs(float(approx_phi_inv_f32(U)) - L.coopref_phi_inv_u32(U)))
-    assert worst < 4e-4, worst
+    assert worst < GAP, worst
 
 
 def test_second_filter_never_rejects_a_kept_edge():
@@ -177,23 +206,23 @@ def test_second_filter_is_selective():
 # --------------------------------------------------------------------------- #
 # First filter, refined: a strip and a corner rectangle instead of the L-shaped region
 # --------------------------------------------------------------------------- #
-STRIP_SHIFT = 0.6     # the strip's edge lies this far (in standard deviations) below the L-shape's
+STRIP_SHIFT = _K["kStripShift"]     # the strip's edge lies this far (in standard deviations) below the L-shape's
 
 
 def first_thresholds(L, thr, cw, sw):
-    """Restatement of blend_first_thresholds() in csrc/labor.hip: with lo = min(U1, U2), hi = max(U1, U2), a kept edge
+    """Restatement of blend_first_thresholds() in csrc/blend_filters.h: with lo = min(U1, U2), hi = max(U1, U2), a kept edge
     has lo <= a1, or lo <= a2 and hi <= b2."""
     if thr >= 0x7FFFFFF0:
         return M32, M32, M32
-    tau_s = L.coopref_phi_inv_u32(thr + 8) * (1.0 - 1e-6)
-    widen = lambda R: M32 if float(R) * 1.000001 + 16.0 >= 4294967295.0 else int(float(R) * 1.000001 + 16.0)
+    tau_s = L.coopref_phi_inv_u32(thr + THR_WIDEN) * (1.0 - REL)
+    widen = lambda R: M32 if float(R) * (1.0 + REL) + 16.0 >= 4294967295.0 else int(float(R) * (1.0 + REL) + 16.0)
     x2 = tau_s * L.coopref_rcp(cw + sw)
     a2 = widen(L.coopref_phi_to_u32(x2))
     a1 = L.coopref_phi_to_u32(x2 - STRIP_SHIFT)
     x1 = L.coopref_phi_inv_u32(a1)
     cM, cm = max(cw, sw), min(cw, sw)
     y2 = (tau_s - cM * x1) * L.coopref_rcp(cm)
-    y2 = y2 + 1e-6 * abs(y2) + 1e-9
+    y2 = y2 + REL * abs(y2) + 1e-9
     b2 = M32 if y2 >= 6.0 else widen(L.coopref_phi_to_u32(y2))
     return a1, a2, b2
 
@@ -256,14 +285,14 @@ def test_refined_first_filter_is_more_selective():
 # The fp32 blend also settles most candidates the other way: safely below the threshold means kept
 # --------------------------------------------------------------------------- #
 def keep_threshold(L, thr, cw, sw):
-    """Restatement of blend_keep_threshold() in csrc/labor.hip: an fp32 estimate at or below this means the exact blend
+    """Restatement of blend_keep_threshold() in csrc/blend_filters.h: an fp32 estimate at or below this means the exact blend
     keeps the edge."""
     if thr == M32:
         return np.float32(np.inf)           # the whole list is kept
     if thr < 64:
         return np.float32(-np.inf)
-    tau_lo = L.coopref_phi_inv_u32(thr - 8)
-    lim = tau_lo - 1e-6 * abs(tau_lo) - (cw + sw) * EPS2 - 1e-5
+    tau_lo = L.coopref_phi_inv_u32(thr - THR_WIDEN)
+    lim = tau_lo - REL * abs(tau_lo) - (cw + sw) * EPS2 - ABS
     t = np.float32(lim)
     return np.nextafter(t, np.float32(-np.inf)) if float(t) > lim else t
 

@@ -756,3 +756,55 @@ def test_bucket_by_owner(P, scheme):
     for args in ((nv, 0), (nv, 65), (0, 4)):
         with pytest.raises(P.CoopError):
             P.coop_bucket_by_owner(torch.from_numpy(ids).cuda(), args[0], args[1], scheme)
+
+
+def test_directed_graph(P, medium):
+    """Sec. 2 defines N(s) as the in-neighbours of s: on a directed graph (of every pair of opposite edges of the medium
+    graph one survives) the lists that the samplers read are not the lists of the vertices that they lead to.  NS, LABOR-0
+    (independent and dependent variates) and random walks against the oracle, the graph registered as it is; stating
+    that it is symmetric is refused."""
+    dp, dx = synth.directed_from_symmetric(torch.from_numpy(medium.indptr_h), torch.from_numpy(medium.indices_h), stream=3)
+    assert dx.numel() * 2 == len(medium.indices_h)
+    g = G(P, dp, dx)
+    deg = np.diff(g.indptr_h)
+    assert (deg == 0).sum() > 0 and deg.max() > 300
+    seeds = synth.seed_batches(g.n, 3000, seed=41)(2).numpy()
+    hubs = np.argsort(-deg)[:40].astype(np.int32)
+    for sampler in (R.NS, R.LABOR0):
+        compare(P, g, seeds, (10, 10, 10), sampler, it=4, kappa=1, seed=19)
+        compare(P, g, seeds[:700], (5, 10), sampler, it=21, kappa=16, seed=19)
+        compare(P, g, hubs, (25, 10), sampler, it=2, kappa=1, seed=20)
+    try:  # long lists cut into pieces, on lists that are nobody's mirror image
+        P.coop_tune(P.COOP_TUNE_PIECE_LEN, 256)
+        compare(P, g, np.concatenate([hubs, seeds[:2000][~np.isin(seeds[:2000], hubs)]]), (10, 10, 10), R.LABOR0, it=6, kappa=1, seed=21)
+    finally:
+        P.coop_tune(P.COOP_TUNE_PIECE_LEN, 4096)
+    compare_rw(P, g, seeds[:1500], (10, 10), 3, 100, 0.5, it=3, seed=22)
+    with pytest.raises(P.CoopError) as e:
+        P.coop_graph_load(g.indptr_d, g.indices_d, P.COOP_SYMMETRIC)
+    assert e.value.code == -8
+
+
+def test_fp32_phi_inv_stays_within_the_margin_for_every_input(P):
+    """The filters in front of the exact blend (App. A.7, c > 0) settle a candidate by Phi^-1 in fp32 wherever ten times
+    kPhiInvF32Gap cannot change the outcome.  The distance between that fp32 evaluation (this GPU's log, sqrt and
+    reciprocal instructions) and the binary64 definition is measured here for all 2^32 uniforms and must stay below the
+    constant that the kernels are compiled with.  Spot values of the measurement are checked against the oracle's kit and
+    a numpy restatement of the fp32 form, so that the measurement itself is pinned to something outside the library."""
+    from test_blend_prefilter import GAP, approx_phi_inv_f32
+    gap, arg = P.coop_selftest_phi_inv_gap(0, 1 << 32)
+    assert 0.0 < gap < GAP, (gap, arg)
+    L = R.lib()
+    # the reported maximum is reproduced at the reported input by the oracle's binary64 kit and numpy's fp32 arithmetic
+    # (numpy's log / sqrt / division are correctly rounded, the GPU's are good to an ulp or so: agreement to 2e-6)
+    at_arg = abs(float(approx_phi_inv_f32(arg)) - L.coopref_phi_inv_u32(arg))
+    assert abs(at_arg - gap) < 2e-6, (gap, arg, at_arg)
+    rng = np.random.default_rng(3)
+    for U in [0, 1, 0xFFFFFFFF, 0x7FFFFFFF, 0x80000000, int(0.02425 * 2**32), int(0.02425 * 2**32) + 1] + [int(x) for x in rng.integers(0, 1 << 32, 40)]:
+        one, _ = P.coop_selftest_phi_inv_gap(U, 1)
+        assert abs(one - abs(float(approx_phi_inv_f32(U)) - L.coopref_phi_inv_u32(U))) < 2e-6, U
+        assert one <= gap
+    # sub-ranges: the maximum over the halves is the maximum over the whole; an empty range gives 0
+    lo, _ = P.coop_selftest_phi_inv_gap(0, 1 << 31)
+    hi, _ = P.coop_selftest_phi_inv_gap(1 << 31, 1 << 31)
+    assert max(lo, hi) == gap and P.coop_selftest_phi_inv_gap(5, 0)[0] == 0.0
