@@ -316,7 +316,7 @@ int coop_copy_ids(const int32_t* in, int32_t* out, int64_t n, void* stream);
  * the distance between the two evaluations; this call measures the distance for the 32-bit uniforms
  * U = first .. first + count - 1 (first + count <= 2^32; the whole range takes a fraction of a second).
  *   max_gap_out host: max |fp32 Phi^-1((U + 1/2) / 2^32) - binary64 Phi^-1((U + 1/2) / 2^32)|
- *   arg_out     host, may be NULL: a U at which a maximum was seen
+ *   arg_out     host, may be NULL: the smallest U at which the maximum is reached (0xFFFFFFFF for an empty range)
  *   workspace   device, 8-byte aligned, 16 bytes, contents undefined after
  * Synchronises `stream`.
  */

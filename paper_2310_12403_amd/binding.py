@@ -410,7 +410,7 @@ class Cache:
 
 
 def coop_selftest_phi_inv_gap(first=0, count=1 << 32, stream=None):
-    """(largest |fp32 Phi^-1 - binary64 Phi^-1| over the uniforms first .. first + count - 1, a uniform where a maximum was seen)."""
+    """(largest |fp32 Phi^-1 - binary64 Phi^-1| over the uniforms first .. first + count - 1, the smallest uniform that reaches it)."""
     L = lib()
     L.coop_selftest_phi_inv_gap.argtypes = [C.c_uint64, C.c_uint64, C.POINTER(C.c_double), C.POINTER(C.c_uint32), C.c_void_p, C.c_void_p]
     L.coop_selftest_phi_inv_gap.restype = C.c_int

@@ -28,8 +28,11 @@ def build(verbose=False, sanitize=False):
     sanitize_check)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = [f for f in FLAGS if f != "-O3"] + SAN_FLAGS if sanitize else FLAGS
+    flags = flags + os.environ.get("COOP_EXTRA_FLAGS", "").split()   # (experiments: -D switches of the kernels)
     obj_dir = SAN_DIR if sanitize else CSRC
-    lib = os.path.join(SAN_DIR, "libcoop_san.so") if sanitize else LIB
+    lib = os.path.join(SAN_DIR, "libcoop_san.so") if sanitize else os.environ.get("COOP_BUILD_LIB", LIB)
+    if os.environ.get("COOP_BUILD_LIB"):
+        obj_dir = os.environ["COOP_BUILD_LIB"] + ".objs"
     os.makedirs(obj_dir, exist_ok=True)
     objs = []
     procs = []

@@ -9,32 +9,36 @@
 
 namespace coop {
 
-// max over U in [first, first + count) of |approx_phi_inv_f32(U) - kit_phi_inv_u32(U)|, folded into *max_bits by
-// atomicMax on the bit pattern (nonnegative doubles order like their bit patterns); *arg_u follows the maximum loosely
-// (it names an input that reached a block's maximum, for error messages)
-__global__ __launch_bounds__(kBlock) void k_phi_inv_gap(uint64_t first, uint64_t count, unsigned long long* max_bits,
-                                                        unsigned long long* arg_u) {
+__device__ __forceinline__ double phi_inv_gap(uint32_t U) {
+  const double gap = __builtin_fabs((double)approx_phi_inv_f32(U) - kit_phi_inv_u32(U));
+  return gap == gap ? gap : __builtin_inf();  // (a NaN on either side counts as an unbounded distance)
+}
+
+// *max_bits = max over U in [first, first + count) of |approx_phi_inv_f32(U) - kit_phi_inv_u32(U)|, by atomicMax on the bit
+// pattern (nonnegative doubles order like their bit patterns)
+__global__ __launch_bounds__(kBlock) void k_phi_inv_gap(uint64_t first, uint64_t count, unsigned long long* max_bits) {
   double worst = 0.0;
-  uint32_t worst_u = 0;
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += stride) {
+    const double gap = phi_inv_gap((uint32_t)(first + i));
+    worst = gap > worst ? gap : worst;
+  }
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) {  // wave maximum, then one atomic per wave
+    const double o = __shfl_xor(worst, off, kWave);
+    worst = o > worst ? o : worst;
+  }
+  if (lane_id() == 0) atomicMax(max_bits, (unsigned long long)__double_as_longlong(worst));
+}
+
+// second pass: *arg_u = the smallest U of the range whose distance equals the maximum found by the first pass
+__global__ __launch_bounds__(kBlock) void k_phi_inv_gap_where(uint64_t first, uint64_t count, const unsigned long long* max_bits,
+                                                              unsigned long long* arg_u) {
+  const unsigned long long want = *max_bits;
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
   for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < count; i += stride) {
     const uint32_t U = (uint32_t)(first + i);
-    const double exact = kit_phi_inv_u32(U);
-    const double gap = __builtin_fabs((double)approx_phi_inv_f32(U) - exact);
-    if (gap > worst || !(gap == gap)) { worst = gap == gap ? gap : __builtin_inf(); worst_u = U; }
-  }
-  // wave maximum, then one atomic per wave
-  double wave_worst = worst;
-#pragma unroll
-  for (int off = kWave / 2; off > 0; off >>= 1) {
-    const double o = __shfl_xor(wave_worst, off, kWave);
-    wave_worst = o > wave_worst ? o : wave_worst;
-  }
-  const uint64_t holders = ballot64(worst == wave_worst);
-  if (lane_id() == __builtin_ctzll(holders)) {
-    const unsigned long long bits = (unsigned long long)__double_as_longlong(wave_worst);
-    const unsigned long long old = atomicMax(max_bits, bits);
-    if (bits > old) *arg_u = worst_u;
+    if ((unsigned long long)__double_as_longlong(phi_inv_gap(U)) == want) atomicMin(arg_u, (unsigned long long)U);
   }
 }
 
@@ -49,12 +53,14 @@ extern "C" int coop_selftest_phi_inv_gap(uint64_t first, uint64_t count, double*
       first + count > ((uint64_t)1 << 32))
     return COOP_E_ARG;
   hipStream_t s = (hipStream_t)stream;
-  unsigned long long* d = (unsigned long long*)workspace;  // [0] the maximum's bit pattern, [1] an input that reached it
-  fill_u64((uint64_t*)d, 2, 0, s);
+  unsigned long long* d = (unsigned long long*)workspace;  // [0] the maximum's bit pattern, [1] the first input that reaches it
+  fill_u64((uint64_t*)d, 1, 0, s);
+  fill_u64((uint64_t*)d + 1, 1, ~0ull, s);
   if (count > 0) {
     uint64_t blocks = (count + kBlock - 1) / kBlock;
     if (blocks > 256 * 64) blocks = 256 * 64;
-    hipLaunchKernelGGL(k_phi_inv_gap, dim3((unsigned)blocks), dim3(kBlock), 0, s, first, count, d, d + 1);
+    hipLaunchKernelGGL(k_phi_inv_gap, dim3((unsigned)blocks), dim3(kBlock), 0, s, first, count, d);
+    hipLaunchKernelGGL(k_phi_inv_gap_where, dim3((unsigned)blocks), dim3(kBlock), 0, s, first, count, (const unsigned long long*)d, d + 1);
   }
   unsigned long long h[2] = {0, 0};
   COOP_HIP_TRY(hipMemcpyAsync(h, d, sizeof(h), hipMemcpyDeviceToHost, s));

@@ -101,10 +101,17 @@ EPS2 = _K["kPhiInvF32Allow"]   # allowance for one fp32 Phi^-1 against the fp64 
                                # kPhiInvF32Gap: the central branch's large alternating coefficients cancel in fp32)
 
 
+def fmaf(a, b, c):
+    """Single-rounding fused multiply-add of float32 values: the product of two 24-bit significands is exact in binary64, and
+    the sum is rounded to binary64 and then to float32 (a double rounding that differs from the fused result only in
+    vanishingly rare ties)."""
+    return np.float32(np.float64(a) * np.float64(b) + np.float64(c))
+
+
 def approx_phi_inv_f32(U):
     """Restatement of approx_phi_inv_f32() in csrc/variates.h: Acklam's rational form of Phi^-1((U + 1/2) / 2^32)
-    evaluated in fp32 (the GPU uses its hardware log2 / sqrt / reciprocal, each good to about one ulp; numpy's are
-    correctly rounded: the difference is far inside EPS2)."""
+    evaluated in fp32 with fused multiply-adds (the GPU uses its hardware log2 / sqrt / reciprocal, each good to about one
+    ulp; numpy's are correctly rounded: the difference is far inside the margin)."""
     f = np.float32
     upper = U >= 0x80000000
     Ul = (M32 - U) if upper else U
@@ -113,21 +120,21 @@ def approx_phi_inv_f32(U):
         q = np.sqrt(f(-2.0) * np.log(p, dtype=np.float32), dtype=np.float32)
         num = f(-7.784894002430293e-03)
         for c in (-3.223964580411365e-01, -2.400758277161838e+00, -2.549732539343734e+00, 4.374664141464968e+00, 2.938163982698783e+00):
-            num = f(num * q + f(c))
+            num = fmaf(num, q, f(c))
         den = f(7.784695709041462e-03)
         for c in (3.224671290700398e-01, 2.445134137142996e+00, 3.754408661907416e+00, 1.0):
-            den = f(den * q + f(c))
-        x = f(num / den)
+            den = fmaf(den, q, f(c))
+        x = f(num * (f(1.0) / den))
     else:
         q = f(p - f(0.5))
         r = f(q * q)
         num = f(-3.969683028665376e+01)
         for c in (2.209460984245205e+02, -2.759285104469687e+02, 1.383577518672690e+02, -3.066479806614716e+01, 2.506628277459239e+00):
-            num = f(num * r + f(c))
+            num = fmaf(num, r, f(c))
         den = f(-5.447609879822406e+01)
         for c in (1.615858368580409e+02, -1.556989798598866e+02, 6.680131188771972e+01, -1.328068155288572e+01, 1.0):
-            den = f(den * r + f(c))
-        x = f(f(q * num) / den)
+            den = fmaf(den, r, f(c))
+        x = f(f(q * num) * (f(1.0) / den))
     return f(-x) if upper else x
 
 

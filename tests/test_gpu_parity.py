@@ -796,13 +796,14 @@ def test_fp32_phi_inv_stays_within_the_margin_for_every_input(P):
     assert 0.0 < gap < GAP, (gap, arg)
     L = R.lib()
     # the reported maximum is reproduced at the reported input by the oracle's binary64 kit and numpy's fp32 arithmetic
-    # (numpy's log / sqrt / division are correctly rounded, the GPU's are good to an ulp or so: agreement to 2e-6)
+    # (numpy's log / sqrt / division are correctly rounded, the GPU's are good to an ulp or so, and the rational form
+    # amplifies an ulp a hundredfold where its terms cancel: agreement to 2e-5, a twentieth of the margin)
     at_arg = abs(float(approx_phi_inv_f32(arg)) - L.coopref_phi_inv_u32(arg))
-    assert abs(at_arg - gap) < 2e-6, (gap, arg, at_arg)
+    assert abs(at_arg - gap) < 2e-5, (gap, arg, at_arg)
     rng = np.random.default_rng(3)
     for U in [0, 1, 0xFFFFFFFF, 0x7FFFFFFF, 0x80000000, int(0.02425 * 2**32), int(0.02425 * 2**32) + 1] + [int(x) for x in rng.integers(0, 1 << 32, 40)]:
         one, _ = P.coop_selftest_phi_inv_gap(U, 1)
-        assert abs(one - abs(float(approx_phi_inv_f32(U)) - L.coopref_phi_inv_u32(U))) < 2e-6, U
+        assert abs(one - abs(float(approx_phi_inv_f32(U)) - L.coopref_phi_inv_u32(U))) < 2e-5, U
         assert one <= gap
     # sub-ranges: the maximum over the halves is the maximum over the whole; an empty range gives 0
     lo, _ = P.coop_selftest_phi_inv_gap(0, 1 << 31)
