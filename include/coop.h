@@ -212,6 +212,22 @@ int coop_bucket_by_owner(const int32_t* ids, int64_t n, int64_t n_vertices, int 
                          size_t workspace_bytes, void* stream);
 
 /*
+ * coop_bucket_by_owner for callers that cannot allocate and have no workspace to pass: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as coop_bucket_by_owner,
+ * without `workspace`: the counter matrix, its scan and the scan's tile sums live in a device array that is part of the
+ * library's code object (4 MiB + 64 KiB; every GPU that the library runs on holds its copy until the process ends).
+ * The call allocates nothing (no hipMalloc / hipFree, no allocating library routine), launches the same kernels on
+ * `stream` and returns after the launches.
+ * Limits: n < 2^31 ids, n_parts <= 64, as for coop_bucket_by_owner (COOP_E_ARG beyond them); a call whose workspace
+ * would not fit the array gets COOP_E_CAPACITY (none does within those limits).
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams, different threads) race
+ * and give wrong groups; calls queued on one stream, or ordered by events, are fine.  Nothing in the array has to
+ * survive from call to call or start at zero.
+ */
+int coop_bucket_by_owner_static(const int32_t* ids, int64_t n, int64_t n_vertices, int n_parts, int scheme, uint64_t seed,
+                                int32_t* ids_out, int32_t* origin_out, int64_t* offsets_out, void* stream);
+
+/*
  * LRU vertex cache on the GPU in front of a feature table that the device can read but that is slow to read
  * (pinned host memory over the host link; Sec. 4.2 measures this cache's miss rate as kappa grows).
  *

@@ -288,6 +288,30 @@ def coop_bucket_by_owner(ids, n_vertices, n_parts, scheme=COOP_OWNER_RANGE, seed
     return out, origin, offsets
 
 
+def coop_bucket_by_owner_static(ids, n_vertices, n_parts, scheme=COOP_OWNER_RANGE, seed=0, out=None, origin=None, offsets=None,
+                                stream=None):
+    """coop_bucket_by_owner without a workspace and without any allocation inside the library (its scratch is a device array
+    of the library).  `out`, `origin`, `offsets` may be preallocated tensors (then nothing at all is allocated); returns
+    (ids_out, origin_out, offsets)."""
+    L = lib()
+    L.coop_bucket_by_owner_static.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p]
+    L.coop_bucket_by_owner_static.restype = C.c_int
+    n = ids.numel()
+    if out is None:
+        out = torch.empty_like(ids)
+    if origin is None:
+        origin = torch.empty_like(ids)
+    if offsets is None:
+        offsets = torch.empty(n_parts + 1, dtype=torch.int64, device=ids.device)
+    assert out.numel() >= n and origin.numel() >= n and offsets.numel() >= n_parts + 1
+    rc = L.coop_bucket_by_owner_static(_dev_ptr(ids, torch.int32) if n else None, n, n_vertices, n_parts, scheme, seed,
+                                       C.c_void_p(out.data_ptr()) if n else None, C.c_void_p(origin.data_ptr()) if n else None,
+                                       C.c_void_p(offsets.data_ptr()), _stream_ptr(stream))
+    _check(rc)
+    return out, origin, offsets
+
+
 def coop_copy_ids(ids, out=None, stream=None):
     """A plain copy of a device int32 list on the stream."""
     if out is None:

@@ -132,20 +132,26 @@ __global__ __launch_bounds__(kBlock) void k_gather_mean(const V* __restrict__ fe
 namespace {
 constexpr int kMaxDevices = 64;
 std::mutex g_bad_mu;
-int32_t* g_bad_flag[kMaxDevices] = {};  // per device: a device word, sticky "an id was out of range"
+// Sticky "an id was out of range" word.  A device variable of this library's code object (zero when the code object is
+// loaded): every GPU has its own copy at its own address, which hipGetSymbolAddress gives for the current device.
+// Nothing is allocated for it, so the entry points that promise not to allocate can report through it as well.
+static __device__ int32_t g_bad_word;
+int32_t* g_bad_flag[kMaxDevices] = {};  // per device: the address of that device's copy
 
 }  // namespace
 
-// the current device's flag word, created on first use (a few bytes, kept for the life of the process)
+// the current device's flag word (its address is looked up on first use and kept for the life of the process)
 int32_t* bad_flag() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
   std::lock_guard<std::mutex> lk(g_bad_mu);
   if (!g_bad_flag[dev]) {
-    int32_t* p = nullptr;
-    if (hipMalloc((void**)&p, sizeof(int32_t)) != hipSuccess) return nullptr;
-    if (hipMemset(p, 0, sizeof(int32_t)) != hipSuccess) { (void)hipFree(p); return nullptr; }
-    g_bad_flag[dev] = p;
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_bad_word)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_bad_flag[dev] = (int32_t*)p;
   }
   return g_bad_flag[dev];
 }

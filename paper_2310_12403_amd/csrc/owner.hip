@@ -5,6 +5,8 @@
 // Every wave owns a contiguous stretch of the list.  Pass 1 counts the stretch's ids per owner (a column of the matrix
 // [owner][wave]); the exclusive scan of the matrix in row-major order gives every (owner, wave) its place in the output;
 // pass 2 walks the stretch again, 64 ids at a time, and places each id behind the ids of the same owner that precede it.
+#include <mutex>
+
 #include "coop_internal.h"
 #include "device_utils.h"
 #include "variates.h"
@@ -107,14 +109,10 @@ extern "C" size_t coop_bucket_workspace_bytes(int64_t n, int n_parts) {
   return (size_t)(2 * cells) * sizeof(uint32_t) + scan_tmp_bytes(cells) + 512;
 }
 
-extern "C" int coop_bucket_by_owner(const int32_t* ids, int64_t n, int64_t n_vertices, int n_parts, int scheme, uint64_t seed,
-                                    int32_t* ids_out, int32_t* origin_out, int64_t* offsets_out, void* workspace,
-                                    size_t workspace_bytes, void* stream) {
-  if (n < 0 || n >= ((int64_t)1 << 31) || n_vertices < 1 || n_vertices >= ((int64_t)1 << 31)) return COOP_E_ARG;
-  if (n_parts < 1 || n_parts > kMaxParts || (scheme != COOP_OWNER_RANGE && scheme != COOP_OWNER_HASH)) return COOP_E_ARG;
-  if (!offsets_out || !workspace || (n > 0 && (!ids || !ids_out))) return COOP_E_NULL;
-  if (workspace_bytes < coop_bucket_workspace_bytes(n, n_parts) || ((uintptr_t)workspace & 7) != 0) return COOP_E_ARG;
-  hipStream_t s = (hipStream_t)stream;
+namespace {
+// the checks and launches shared by the two entry points; `workspace` holds coop_bucket_workspace_bytes(n, n_parts) bytes
+int bucket_launch(const int32_t* ids, int64_t n, int64_t n_vertices, int n_parts, int scheme, uint64_t seed, int32_t* ids_out,
+                  int32_t* origin_out, int64_t* offsets_out, void* workspace, hipStream_t s) {
   int32_t* bad = bad_flag();
   if (!bad) return COOP_E_HIP;
   int64_t n_waves = (n + kMinStretch - 1) / kMinStretch;
@@ -131,4 +129,66 @@ extern "C" int coop_bucket_by_owner(const int32_t* ids, int64_t n, int64_t n_ver
               offsets_out);
   if (hipGetLastError() != hipSuccess) return COOP_E_HIP;
   return COOP_OK;
+}
+
+int bucket_check(const int32_t* ids, int64_t n, int64_t n_vertices, int n_parts, int scheme, const int32_t* ids_out,
+                 const int64_t* offsets_out) {
+  if (n < 0 || n >= ((int64_t)1 << 31) || n_vertices < 1 || n_vertices >= ((int64_t)1 << 31)) return COOP_E_ARG;
+  if (n_parts < 1 || n_parts > kMaxParts || (scheme != COOP_OWNER_RANGE && scheme != COOP_OWNER_HASH)) return COOP_E_ARG;
+  if (!offsets_out || (n > 0 && (!ids || !ids_out))) return COOP_E_NULL;
+  return COOP_OK;
+}
+
+// ---- the workspace of coop_bucket_by_owner_static ---------------------------------------------------------------------
+// The counter matrix, its scan and the scan's tile sums for the largest call (64 owners): 4 MiB and a little, a device
+// array of this library's code object.  Every GPU holds its own copy at its own address until the process ends; the
+// name below is only the host-side handle by which hipGetSymbolAddress finds the current device's copy.
+constexpr size_t kStaticScratchBytes = (size_t)4 * 1024 * 1024 + 65536;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};  // per device: the device address of that device's `scratch`
+
+// device address of the current device's scratch array (looked up once per device; allocates nothing)
+int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return COOP_E_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return COOP_E_CAPACITY;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return COOP_E_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return COOP_OK;
+}
+}  // namespace
+
+extern "C" int coop_bucket_by_owner(const int32_t* ids, int64_t n, int64_t n_vertices, int n_parts, int scheme, uint64_t seed,
+                                    int32_t* ids_out, int32_t* origin_out, int64_t* offsets_out, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  const int rc = bucket_check(ids, n, n_vertices, n_parts, scheme, ids_out, offsets_out);
+  if (rc != COOP_OK) return rc;
+  if (!workspace) return COOP_E_NULL;
+  if (workspace_bytes < coop_bucket_workspace_bytes(n, n_parts) || ((uintptr_t)workspace & 7) != 0) return COOP_E_ARG;
+  return bucket_launch(ids, n, n_vertices, n_parts, scheme, seed, ids_out, origin_out, offsets_out, workspace, (hipStream_t)stream);
+}
+
+extern "C" int coop_bucket_by_owner_static(const int32_t* ids, int64_t n, int64_t n_vertices, int n_parts, int scheme, uint64_t seed,
+                                           int32_t* ids_out, int32_t* origin_out, int64_t* offsets_out, void* stream) {
+  const int rc = bucket_check(ids, n, n_vertices, n_parts, scheme, ids_out, offsets_out);
+  if (rc != COOP_OK) return rc;
+  // (a call whose workspace would not fit the array is refused; with the limits above, 64 owners and 2^31 - 1 ids, none is)
+  if (coop_bucket_workspace_bytes(n, n_parts) > kStaticScratchBytes) return COOP_E_CAPACITY;
+  void* ws = nullptr;
+  const int rs = static_scratch(&ws);
+  if (rs != COOP_OK) return rs;
+  // Nothing in the workspace has to start at zero: the first kernel stores every cell of the matrix that the scan reads,
+  // the scan stores every tile sum and every place that the second kernel reads.
+  return bucket_launch(ids, n, n_vertices, n_parts, scheme, seed, ids_out, origin_out, offsets_out, ws, (hipStream_t)stream);
 }
