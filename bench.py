@@ -55,6 +55,9 @@ def main():
                     help="also run three plain 1 GiB copies with the library's copy kernel (coop::k_copy_i32): the known-size "
                          "reference that rocprofv3 --pmc byte counters are scaled by")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
+                    help="coop_tune knob by number (see include/coop.h), e.g. --tune 2=16 for sixteen lists per wave; results never "
+                         "depend on the knobs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one MI355X plays the single processor that owns the whole "
@@ -66,6 +69,9 @@ def main():
     import paper_2310_12403_amd as P
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    for kv in args.tune:
+        knob, value = kv.split("=")
+        P.coop_tune(int(knob), int(value))
     if args.mode != "step":
         return REPORTS[args.mode](args, torch, synth, P)
     dev = torch.device("cuda:0")

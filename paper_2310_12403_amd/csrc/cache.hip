@@ -27,7 +27,7 @@ namespace coop {
 
 constexpr int kSelBits = 13;  // most bits per radix-select pass (8192 LDS counters)
 constexpr int kSelBins = 1 << kSelBits;
-constexpr int kRowUnroll = 2;
+constexpr int kRowUnroll = 4;  // rows per thread in flight (as in the plain gather)
 
 struct CacheCtl {
   uint64_t prefix;     // radix select: digits chosen so far; after the last pass, the E-th smallest (stamp - base)
@@ -56,13 +56,16 @@ __global__ __launch_bounds__(kBlock) void k_cache_lookup(const int32_t* __restri
 }
 
 // order[r] = index of the r-th hit for r < n_hit; order[n_ids - 1 - q] = index of the q-th miss: the row movers then
-// run over dense lists of hits and of misses instead of idling through the other kind
-__global__ __launch_bounds__(kBlock) void k_cache_split(const int32_t* __restrict__ slot_i, const uint32_t* __restrict__ rank_h,
+// run over dense lists of hits and of misses instead of idling through the other kind.  An id's rank among the hits is
+// the scanned bit count of the 64-id words in front of its word plus the bits below it in its own word (the scan runs
+// over n_ids / 64 words, not over n_ids flags).
+__global__ __launch_bounds__(kBlock) void k_cache_split(const uint64_t* __restrict__ hit_bits, const uint32_t* __restrict__ word_rank,
                                                         int64_t n_ids, int32_t* __restrict__ order) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_ids) return;
-  const int64_t h = rank_h[i];
-  if (slot_i[i] >= 0) order[h] = (int32_t)i;
+  const uint64_t word = hit_bits[i >> 6];
+  const int64_t h = (int64_t)word_rank[i >> 6] + __popcll(word & ((1ull << (i & 63)) - 1ull));
+  if ((word >> (i & 63)) & 1ull) order[h] = (int32_t)i;
   else order[n_ids - 1 - (i - h)] = (int32_t)i;
 }
 
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ row
     V x[kRowUnroll];
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u)
-      if (src[u] >= 0) x[u] = rows[src[u] * vecs + v];
+      if (src[u] >= 0) x[u] = __builtin_nontemporal_load(rows + src[u] * vecs + v);  // (a cached row is read at most once per call)
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u)
       if (src[u] >= 0) __builtin_nontemporal_store(x[u], out + dst[u] * vecs + v);
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
     for (int u = 0; u < kRowUnroll; ++u) {
       if (src[u] >= 0) {
         __builtin_nontemporal_store(x[u], out + dst[u] * vecs + v);
-        if (dst_slot[u] >= 0) rows[dst_slot[u] * vecs + v] = x[u];
+        if (dst_slot[u] >= 0) __builtin_nontemporal_store(x[u], rows + dst_slot[u] * vecs + v);  // (not read again before a later call)
       }
     }
   }
@@ -543,9 +546,9 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
   COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)0);
   COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_lookup, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, ids, n_ids,
               c->n_vertices, c->slot_of, c->slot_i, c->hit_bits, c->d_ctl);
-  scan_bits_to_u32(c->hit_bits, n_ids, c->rank_h, &c->d_ctl->n_hit, c->scan_tmp, s);
-  COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_split, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, c->slot_i, c->rank_h,
-              n_ids, c->order);
+  scan_popc_to_u32(c->hit_bits, (n_ids + 63) / 64, c->rank_h, &c->d_ctl->n_hit, c->scan_tmp, s);
+  COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_split, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, (const uint64_t*)c->hit_bits,
+              (const uint32_t*)c->rank_h, n_ids, c->order);
   COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
   // 2. hits: rows out of the cache, new stamps (runs while the host waits for the counts)
   dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, 0, 0, 0, 0, true, s);
