@@ -56,6 +56,7 @@ extern "C" {
 /* allocator tags: what the requested buffer is for */
 #define COOP_TAG_OUTPUT 0   /* referenced by a coop_block; lives as long as the caller wants */
 #define COOP_TAG_SCRATCH 1  /* dead once the call that asked for it has returned */
+#define COOP_TAG_GRAPH 2    /* belongs to a graph handle (coop_graph_load_with): must stay valid until coop_graph_free */
 
 /* Returns a device pointer to at least `bytes` bytes, 256-byte aligned, or NULL. */
 typedef void* (*coop_alloc_fn)(void* ctx, size_t bytes, int tag);
@@ -86,6 +87,12 @@ typedef struct coop_cache coop_cache; /* opaque */
  */
 int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_vertices, int64_t n_edges,
                     int flags, void* stream, coop_graph** out);
+/* The same, with every byte of device memory from the caller's allocator (Sec. 2's graph is the caller's; so is what is built
+ * on it): the index of reverse positions of a COOP_SYMMETRIC graph (4 * n_edges bytes, tag COOP_TAG_GRAPH, the caller keeps
+ * it alive until coop_graph_free and frees it afterwards) and a few bytes for the checks (tag COOP_TAG_SCRATCH).  With a
+ * NULL allocator it is coop_graph_load.  COOP_E_NOMEM if the allocator returns NULL. */
+int coop_graph_load_with(const int64_t* indptr, const int32_t* indices, int64_t n_vertices, int64_t n_edges, int flags,
+                         coop_alloc_fn alloc, void* alloc_ctx, void* stream, coop_graph** out);
 int coop_graph_free(coop_graph* g);
 
 /*

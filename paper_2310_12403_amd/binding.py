@@ -51,6 +51,9 @@ def lib():
     L.coop_graph_load.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p,
                                   C.POINTER(C.c_void_p)]
     L.coop_graph_load.restype = C.c_int
+    L.coop_graph_load_with.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.POINTER(C.c_void_p)]
+    L.coop_graph_load_with.restype = C.c_int
     L.coop_graph_free.argtypes = [C.c_void_p]
     L.coop_graph_free.restype = C.c_int
     L.coop_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_uint64,
@@ -143,9 +146,21 @@ class Graph:
             pass
 
 
-def coop_graph_load(indptr, indices, flags=0, stream=None):
-    """indptr: cuda int64 [n+1]; indices: cuda int32 [nnz] (borrowed for the life of the Graph)."""
+def coop_graph_load(indptr, indices, flags=0, stream=None, torch_memory=False):
+    """indptr: cuda int64 [n+1]; indices: cuda int32 [nnz] (borrowed for the life of the Graph).
+    torch_memory: what the library builds on the graph (the reverse index of a COOP_SYMMETRIC graph) comes from torch's
+    allocator through coop_graph_load_with and lives as long as the Graph object."""
     h = C.c_void_p()
+    if torch_memory:
+        al = _TorchAllocator(indptr.device)
+        rc = lib().coop_graph_load_with(_dev_ptr(indptr, torch.int64), _dev_ptr(indices, torch.int32), indptr.numel() - 1,
+                                        indices.numel(), flags, al.fn, al.ctx, _stream_ptr(stream), C.byref(h))
+        if rc != 0 and al.error is not None:
+            raise al.error
+        _check(rc)
+        g = Graph(h, indptr, indices)
+        g._memory = al          # the tensors behind the handle
+        return g
     rc = lib().coop_graph_load(_dev_ptr(indptr, torch.int64), _dev_ptr(indices, torch.int32), indptr.numel() - 1,
                                indices.numel(), flags, _stream_ptr(stream), C.byref(h))
     _check(rc)

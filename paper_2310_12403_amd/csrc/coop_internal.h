@@ -177,5 +177,6 @@ struct coop_graph {
   bool symmetric;     // COOP_SYMMETRIC: sorted lists, every edge stored both ways
   uint32_t* rev_pos;  // then: for the edge t -> s at position e of indices, the position of s in t's list (owned, device)
   int64_t long_mass;  // then: entries in lists longer than kLongListDegree
+  bool own_rev;       // rev_pos was allocated by the library (hipMalloc) and is released by coop_graph_free
 };
 constexpr int64_t kLongListDegree = 8192;  // default of COOP_TUNE_ENUM_DEGREE

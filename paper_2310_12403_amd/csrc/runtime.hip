@@ -377,22 +377,35 @@ void* coop_arena_alloc(void* arena, size_t bytes, int tag) {
   return p;
 }
 
-int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_vertices, int64_t n_edges, int flags,
-                    void* stream, coop_graph** out) {
+int coop_graph_load_with(const int64_t* indptr, const int32_t* indices, int64_t n_vertices, int64_t n_edges, int flags,
+                         coop_alloc_fn alloc, void* alloc_ctx, void* stream, coop_graph** out) {
   if (!out) return COOP_E_NULL;
   *out = nullptr;
   if (!indptr || (!indices && n_edges > 0)) return COOP_E_NULL;
   if (n_vertices < 0 || n_vertices >= ((int64_t)1 << 31) || n_edges < 0 || (flags & ~(COOP_VALIDATE | COOP_SYMMETRIC))) return COOP_E_ARG;
   uint32_t* rev = nullptr;
+  bool own_rev = false;  // the reverse index came from hipMalloc (no allocator given): coop_graph_free releases it
   int64_t long_mass = 0;
   if (flags & (COOP_VALIDATE | COOP_SYMMETRIC)) {  // (the reverse index is built from offsets and ids that have been checked)
     hipStream_t s = (hipStream_t)stream;
     struct Check { int32_t bad, pad; unsigned long long long_mass; };
     Check* d_chk = nullptr;
-    COOP_HIP_TRY(hipMalloc((void**)&d_chk, sizeof(Check)));
-    if ((flags & COOP_SYMMETRIC) && n_edges > 0 && hipMalloc((void**)&rev, (size_t)n_edges * sizeof(uint32_t)) != hipSuccess) {
-      (void)hipFree(d_chk);
-      return COOP_E_NOMEM;
+    if (alloc) {
+      d_chk = (Check*)alloc(alloc_ctx, 256, COOP_TAG_SCRATCH);
+      if (!d_chk) return COOP_E_NOMEM;
+      if ((flags & COOP_SYMMETRIC) && n_edges > 0) {
+        rev = (uint32_t*)alloc(alloc_ctx, (((size_t)n_edges * sizeof(uint32_t)) + 255) & ~(size_t)255, COOP_TAG_GRAPH);
+        if (!rev) return COOP_E_NOMEM;
+      }
+    } else {
+      COOP_HIP_TRY(hipMalloc((void**)&d_chk, sizeof(Check)));
+      if ((flags & COOP_SYMMETRIC) && n_edges > 0) {
+        if (hipMalloc((void**)&rev, (size_t)n_edges * sizeof(uint32_t)) != hipSuccess) {
+          (void)hipFree(d_chk);
+          return COOP_E_NOMEM;
+        }
+        own_rev = true;
+      }
     }
     Check h_chk{0, 0, 0};
     hipError_t e = hipMemcpyAsync(d_chk, &h_chk, sizeof(Check), hipMemcpyHostToDevice, s);
@@ -408,24 +421,29 @@ int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_ver
       if (e == hipSuccess) e = hipMemcpyAsync(&h_chk, d_chk, sizeof(Check), hipMemcpyDeviceToHost, s);
     }
     if (e == hipSuccess) e = hipStreamSynchronize(s);
-    (void)hipFree(d_chk);
+    if (!alloc) (void)hipFree(d_chk);
     if (e != hipSuccess || h_chk.bad) {
-      if (rev) (void)hipFree(rev);
+      if (own_rev) (void)hipFree(rev);
       return e != hipSuccess ? COOP_E_HIP : COOP_E_GRAPH;
     }
     long_mass = (int64_t)h_chk.long_mass;
   }
-  coop_graph* g = new (std::nothrow) coop_graph{indptr, indices, n_vertices, n_edges, (flags & COOP_SYMMETRIC) != 0 && n_edges > 0, rev, long_mass};
+  coop_graph* g = new (std::nothrow) coop_graph{indptr, indices, n_vertices, n_edges, (flags & COOP_SYMMETRIC) != 0 && n_edges > 0, rev, long_mass, own_rev};
   if (!g) {
-    if (rev) (void)hipFree(rev);
+    if (own_rev) (void)hipFree(rev);
     return COOP_E_NOMEM;
   }
   *out = g;
   return COOP_OK;
 }
 
+int coop_graph_load(const int64_t* indptr, const int32_t* indices, int64_t n_vertices, int64_t n_edges, int flags,
+                    void* stream, coop_graph** out) {
+  return coop_graph_load_with(indptr, indices, n_vertices, n_edges, flags, nullptr, nullptr, stream, out);
+}
+
 int coop_graph_free(coop_graph* g) {
-  if (g && g->rev_pos) (void)hipFree(g->rev_pos);
+  if (g && g->rev_pos && g->own_rev) (void)hipFree(g->rev_pos);
   delete g;
   return COOP_OK;
 }

@@ -37,6 +37,8 @@ def test_host_checked_arguments():
     h = C.c_void_p()
     assert L.coop_graph_load(None, None, 10, 0, 0, None, C.byref(h)) == -1          # NULL indptr
     assert L.coop_graph_load(None, None, 10, 0, 0, None, None) == -1                # NULL out
+    assert L.coop_graph_load_with(None, None, 10, 0, 0, None, None, None, C.byref(h)) == -1   # NULL indptr, whoever allocates
+    assert L.coop_graph_load_with(None, None, -1, 0, 0, None, None, None, None) == -1         # NULL out comes first
     fan = (C.c_int32 * 2)(3, 3)
     blocks = (binding._CBlock * 2)()
     assert L.coop_sample(None, None, 0, fan, 2, 0, 0, 1, 0, None, None, None, blocks) == -1   # NULL graph

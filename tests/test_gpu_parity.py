@@ -809,3 +809,28 @@ def test_fp32_phi_inv_stays_within_the_margin_for_every_input(P):
     lo, _ = P.coop_selftest_phi_inv_gap(0, 1 << 31)
     hi, _ = P.coop_selftest_phi_inv_gap(1 << 31, 1 << 31)
     assert max(lo, hi) == gap and P.coop_selftest_phi_inv_gap(5, 0)[0] == 0.0
+
+
+def test_graph_memory_from_the_callers_allocator(P, medium):
+    """coop_graph_load_with: the index of reverse positions of a COOP_SYMMETRIC graph is obtained from the caller's allocator
+    (here torch's), not from hipMalloc; sampling through it (lists above 64 entries served from the neighbours' side) gives the
+    oracle's blocks, and an allocator that fails gives COOP_E_NOMEM."""
+    import ctypes as C
+    from paper_2310_12403_amd import binding
+    before = torch.cuda.memory_allocated()
+    g = P.coop_graph_load(medium.indptr_d, medium.indices_d, P.COOP_VALIDATE | P.COOP_SYMMETRIC, torch_memory=True)
+    assert torch.cuda.memory_allocated() - before >= 4 * len(medium.indices_h)
+    class Wrapped:
+        indptr_h, indices_h, graph, n = medium.indptr_h, medium.indices_h, g, medium.n
+    seeds = synth.seed_batches(medium.n, 3000, seed=71)(1).numpy()
+    try:
+        P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, 64)
+        compare(P, Wrapped, seeds, (10, 10, 10), R.LABOR0, it=2, kappa=1, seed=5)
+    finally:
+        P.coop_tune(P.COOP_TUNE_ENUM_DEGREE, 8192)
+    g.close()
+    failing = binding.ALLOC_FN(lambda ctx, nbytes, tag: None)
+    h = C.c_void_p()
+    rc = P.lib().coop_graph_load_with(C.c_void_p(medium.indptr_d.data_ptr()), C.c_void_p(medium.indices_d.data_ptr()), medium.n,
+                                      len(medium.indices_h), P.COOP_SYMMETRIC, C.cast(failing, C.c_void_p), None, None, C.byref(h))
+    assert rc == -5 and not h.value
