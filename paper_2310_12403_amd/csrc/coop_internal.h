@@ -72,7 +72,8 @@ struct Ctl {
   int32_t n_overflow;    // LABOR-0 destinations whose staging row overflowed (this layer and earlier)
   int32_t cand_overflow; // blended LABOR-0: the candidate buffer of the exact stage was too small (the pass is redone)
   int32_t uniq_overflow; // dedup by partition: a bucket held more distinct vertices than its table (redone with the table in HBM)
-  int32_t pad[2];
+  uint32_t scan_done;    // one-kernel scans: tiles finished so far (the block that finishes last puts it back to zero)
+  int32_t pad[1];
 };
 
 // Landing pad of the control block in mapped pinned host memory (see read_ctl).
@@ -110,6 +111,28 @@ void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* t
 // (n_bits_dev, device, optional: only bits [0, *n_bits_dev) count; n_words is then an upper bound known to the host)
 void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s,
                       const Publish* pub = nullptr, const int64_t* n_bits_dev = nullptr);
+
+// One-kernel exclusive scans for the library's own consumers.  Every block scans its tile and leaves the tile's sum; the
+// block that finishes last (a counter in the call's control block tells it) scans the tile sums.  The result stays in two
+// parts, the position inside the tile and the sum of the tiles in front, and a consumer adds them when it reads an
+// element: the second kernel of the two-kernel scan, which only did that addition, is gone.  No block waits for another.
+constexpr int kScanTileLog2 = 11;  // elements per tile (2048)
+template <typename T>
+struct TiledScan {
+  const T* local;        // [n + 1] exclusive scan inside each tile; local[n] = the total
+  const T* tile_prefix;  // [tiles] sum of the tiles in front, or null when `local` is already the whole scan (short inputs)
+  int64_t n;
+#ifdef __HIPCC__
+  __device__ __forceinline__ T at(int64_t i) const {
+    const T v = local[i];
+    return (tile_prefix != nullptr && i < n) ? (T)(v + tile_prefix[i >> kScanTileLog2]) : v;
+  }
+#endif
+};
+// (`done` points at a zeroed uint32 that no other scan in flight uses; it is zero again when the scan has run.)
+TiledScan<uint32_t> scan_u32_tiled(const uint32_t* in, int64_t n, uint32_t* out, void* tmp, uint32_t* done, hipStream_t s);
+TiledScan<uint32_t> scan_popc_tiled(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, uint32_t* done,
+                                    hipStream_t s, const Publish* pub = nullptr, const int64_t* n_bits_dev = nullptr);
 
 void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
 
@@ -150,6 +173,7 @@ struct UniqueWork {
   uint32_t* first = nullptr;
   uint64_t* bits = nullptr;
   uint32_t* word_rank = nullptr;
+  TiledScan<uint32_t> rank{nullptr, nullptr, 0};  // scanned bit counts of the words of `bits` (over word_rank)
   void* scan_tmp = nullptr;
   int64_t n_buckets = 0;
   bool by_partition = false;

@@ -98,6 +98,7 @@ void fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s) {
 // from L2) and shifts its tile by that offset; the last block also publishes the grand total.
 constexpr int kItems = 8;
 constexpr int kTile = kBlock * kItems;  // 2048
+static_assert(kTile == (1 << kScanTileLog2), "TiledScan::at() finds an element's tile by a shift");
 
 // inclusive block scan of one int64 per thread; returns the thread's inclusive prefix, *total = block sum
 __device__ __forceinline__ int64_t block_incl_scan(int64_t v, int64_t* total, int64_t* lds /* [kWavesPerBlock] */) {
@@ -212,6 +213,57 @@ __global__ __launch_bounds__(kBlock) void k_scan_offset(int64_t n, Out* __restri
   }
 }
 
+// The same per-tile scan, and the scan of the tile sums by whichever block finishes last: one launch.  The consumer adds
+// tile_prefix[tile] to an element when it reads it (TiledScan::at).
+template <typename Load, typename Out>
+__global__ __launch_bounds__(kBlock) void k_scan_tiled(Load load, int64_t n, Out* __restrict__ out, int64_t* __restrict__ tile_sum,
+                                                       Out* __restrict__ tile_prefix, uint32_t* done, int64_t* total_out, Publish pub) {
+  __shared__ int64_t lds[kWavesPerBlock];
+  __shared__ uint32_t s_last;
+  const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;  // a thread owns 8 in a row
+  int64_t x[kItems];
+  int64_t sum = 0;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int64_t i = base + j;
+    x[j] = i < n ? load(i) : 0;
+    sum += x[j];
+  }
+  int64_t tot;
+  const int64_t incl = block_incl_scan(sum, &tot, lds);
+  int64_t run = incl - sum;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int64_t i = base + j;
+    if (i < n) out[i] = (Out)run;
+    run += x[j];
+  }
+  if (threadIdx.x == 0) {
+    __hip_atomic_store(&tile_sum[blockIdx.x], tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();  // the tile's sum is visible device-wide before the tile counts as finished
+    s_last = atomicAdd(done, 1u) == gridDim.x - 1 ? 1u : 0u;
+  }
+  __syncthreads();
+  if (s_last == 0) return;
+  __threadfence();  // every other tile's sum was published before its block counted itself
+  const int64_t tiles = gridDim.x;
+  int64_t carry = 0;
+  for (int64_t first = 0; first < tiles; first += kBlock) {
+    const int64_t t = first + threadIdx.x;
+    const int64_t v = t < tiles ? __hip_atomic_load(&tile_sum[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    int64_t all;
+    const int64_t upto = block_incl_scan(v, &all, lds);
+    if (t < tiles) tile_prefix[t] = (Out)(carry + upto - v);
+    carry += all;
+  }
+  if (threadIdx.x == 0) {
+    out[n] = (Out)carry;  // the entry one past the end holds the grand total
+    if (total_out) *total_out = carry;
+    *done = 0;            // ready for the next scan of this call (the stream keeps them apart)
+    publish_ctl(pub);
+  }
+}
+
 // Short inputs: one block walks over the tiles with a running carry (one launch instead of two).
 constexpr int64_t kScanSmall = 2 * kTile;  // 4096 elements (beyond that two parallel launches are quicker)
 template <typename Load, typename Out>
@@ -247,9 +299,25 @@ __global__ __launch_bounds__(kBlock) void k_scan_small(Load load, int64_t n, Out
   }
 }
 
-size_t scan_tmp_bytes(int64_t n) {
+size_t scan_tmp_bytes(int64_t n) {  // tile sums, and the one-kernel scans' tile prefixes
   const int64_t tiles = (n + kTile - 1) / kTile;
-  return (size_t)(tiles + 2) * sizeof(int64_t);
+  return (size_t)(tiles + 2) * sizeof(int64_t) * 2;
+}
+
+template <typename Load>
+static TiledScan<uint32_t> scan_tiled_impl(Load load, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, uint32_t* done, hipStream_t s,
+                                           const Publish* p) {
+  const Publish pub = p ? *p : Publish{};
+  if (n <= kScanSmall) {  // one block; `out` is the whole scan
+    COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_small<Load, uint32_t>), dim3(1), dim3(kBlock), 0, s, load, n, out, out + n, total_out, pub);
+    return TiledScan<uint32_t>{out, nullptr, n};
+  }
+  const int64_t tiles = (n + kTile - 1) / kTile;
+  int64_t* tile_sum = (int64_t*)tmp;
+  uint32_t* tile_prefix = (uint32_t*)(tile_sum + tiles + 2);
+  COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_tiled<Load, uint32_t>), dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, out, tile_sum, tile_prefix, done,
+              total_out, pub);
+  return TiledScan<uint32_t>{out, tile_prefix, n};
 }
 
 template <typename Load, typename Out>
@@ -289,6 +357,15 @@ void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* 
 
 void scan_u32_to_u32(const uint32_t* in, int64_t n, uint32_t* out, void* tmp, hipStream_t s) {
   scan_impl<LoadU32, uint32_t>(LoadU32{in}, n, out, out + n, nullptr, tmp, s, nullptr);
+}
+
+TiledScan<uint32_t> scan_u32_tiled(const uint32_t* in, int64_t n, uint32_t* out, void* tmp, uint32_t* done, hipStream_t s) {
+  return scan_tiled_impl<LoadU32>(LoadU32{in}, n, out, nullptr, tmp, done, s, nullptr);
+}
+
+TiledScan<uint32_t> scan_popc_tiled(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, uint32_t* done,
+                                    hipStream_t s, const Publish* pub, const int64_t* n_bits_dev) {
+  return scan_tiled_impl<LoadPopc>(LoadPopc{bits, n_bits_dev}, n_words, out, total_out, tmp, done, s, pub);
 }
 
 void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {

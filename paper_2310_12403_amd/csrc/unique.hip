@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kBlock) void k_uniq_flag(const int32_t* __restrict_
 __global__ __launch_bounds__(kBlock) void k_uniq_relabel(const int32_t* __restrict__ dst, const int32_t* __restrict__ col, int64_t m,
                                                          const int64_t* __restrict__ m_dev, int64_t n_dst,
                                                          const uint32_t* __restrict__ first, const uint64_t* __restrict__ bits,
-                                                         const uint32_t* __restrict__ word_rank, int32_t* __restrict__ src,
+                                                         TiledScan<uint32_t> word_rank, int32_t* __restrict__ src,
                                                          int32_t* __restrict__ col_local) {
   const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (m_dev != nullptr && *m_dev < m) m = *m_dev;
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kBlock) void k_uniq_relabel(const int32_t* __restri
   if (f >= n_dst) {
     const int64_t at = f - n_dst;  // the edge at which this vertex first appears
     const uint64_t below = bits[at >> 6] & ((1ull << (at & 63)) - 1ull);
-    local = n_dst + word_rank[at >> 6] + __popcll(below);
+    local = n_dst + word_rank.at(at >> 6) + __popcll(below);
     if (at == e) src[local] = col[e];
   }
   col_local[e] = (int32_t)local;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kPartBlock) void k_part_count(const int32_t* __rest
 constexpr int kTilePairs = 8 * kPartBlock;
 __global__ __launch_bounds__(kPartBlock) void k_part_scatter(const int32_t* __restrict__ dst, int64_t n_dst, const int32_t* __restrict__ col,
                                                              int64_t m, const int64_t* __restrict__ m_dev, uint32_t n_buckets,
-                                                             const uint32_t* __restrict__ place, unsigned long long* __restrict__ pairs) {
+                                                             TiledScan<uint32_t> place, unsigned long long* __restrict__ pairs) {
   __shared__ unsigned long long staged[kTilePairs];  // the round's pairs, by bucket
   extern __shared__ uint32_t cursor[];               // [n_buckets] next free place of the bucket's column
   uint32_t* off = cursor + n_buckets;                // [n_buckets] the round's tallies, then run starts
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kPartBlock) void k_part_scatter(const int32_t* __re
   int64_t lo, hi;
   part_stretch(n_dst + m, gridDim.x, blockIdx.x, &lo, &hi);
   const uint32_t column = part_column();
-  for (uint32_t b = threadIdx.x; b < n_buckets; b += kPartBlock) cursor[b] = place[(size_t)b * gridDim.x + column];
+  for (uint32_t b = threadIdx.x; b < n_buckets; b += kPartBlock) cursor[b] = place.at((int64_t)b * gridDim.x + column);
   const uint32_t per = (n_buckets + kPartBlock - 1) / kPartBlock;  // tallies that a thread scans (at most 8)
   const int lane = lane_id(), wave = wave_in_block();
   for (int64_t tile = lo; tile < hi; tile += kTilePairs) {
@@ -251,12 +251,12 @@ __global__ __launch_bounds__(kPartBlock) void k_part_scatter(const int32_t* __re
 }
 
 // One bucket per block: first positions of the bucket's keys through a table in LDS, then first[] of the bucket's edges.
-__global__ __launch_bounds__(kFirstBlock) void k_part_first(const unsigned long long* __restrict__ pairs, const uint32_t* __restrict__ place,
+__global__ __launch_bounds__(kFirstBlock) void k_part_first(const unsigned long long* __restrict__ pairs, TiledScan<uint32_t> place,
                                                             uint32_t G, int64_t n_dst, int64_t n_all, uint32_t* __restrict__ first,
                                                             Ctl* ctl) {
   __shared__ unsigned long long table[kPartSlots];
   __shared__ uint32_t n_claimed, full;
-  uint32_t lo = place[(size_t)blockIdx.x * G], hi = place[(size_t)(blockIdx.x + 1) * G];
+  uint32_t lo = place.at((int64_t)blockIdx.x * G), hi = place.at((int64_t)(blockIdx.x + 1) * G);
   if ((int64_t)hi > n_all) hi = (uint32_t)n_all;  // (holds by construction; keeps every access inside the arrays regardless)
   if (lo > hi) lo = hi;
   for (uint32_t i = threadIdx.x; i < kPartSlots; i += kFirstBlock) table[i] = kEmptySlot;
@@ -359,10 +359,10 @@ static int unique_launch(const int32_t* dst, int64_t n_dst, const int32_t* col_g
     if (alloc.failed) return COOP_E_NOMEM;
     const size_t lds = (size_t)n_buckets * sizeof(uint32_t);
     COOP_LAUNCH(K_PART_COUNT, k_part_count, dim3(G), dim3(kPartBlock), lds, s, dst, n_dst, col_global, m, m_dev, (uint32_t)n_buckets, counts);
-    scan_u32_to_u32(counts, n_counts, place, tmp, s);
+    const TiledScan<uint32_t> places = scan_u32_tiled(counts, n_counts, place, tmp, &d_ctl->scan_done, s);
     COOP_LAUNCH(K_PART_SCATTER, k_part_scatter, dim3(G), dim3(kPartBlock), 2 * lds, s, dst, n_dst, col_global, m, m_dev, (uint32_t)n_buckets,
-                (const uint32_t*)place, pairs);
-    COOP_LAUNCH(K_PART_FIRST, k_part_first, dim3((unsigned)n_buckets), dim3(kFirstBlock), 0, s, pairs, place, G, n_dst, n_all, w->first, d_ctl);
+                places, pairs);
+    COOP_LAUNCH(K_PART_FIRST, k_part_first, dim3((unsigned)n_buckets), dim3(kFirstBlock), 0, s, pairs, places, G, n_dst, n_all, w->first, d_ctl);
     if (hipGetLastError() != hipSuccess) return COOP_E_HIP;  // (a launch that did not happen would leave `first` unwritten)
     COOP_LAUNCH(K_UNIQ_FLAG, k_flag_from_first, dim3(nblocks(m)), dim3(kBlock), 0, s, w->first, m, m_dev, n_dst, w->bits);
   } else {
@@ -381,7 +381,7 @@ static int unique_launch(const int32_t* dst, int64_t n_dst, const int32_t* col_g
   }
   // sizes (and the duplicate / range flags) back to the host, sent by the scan's last thread when there is a scan
   w->pub = begin_publish(d_ctl, h_ctl);
-  if (m > 0) scan_popc_to_u32(w->bits, n_words, w->word_rank, &d_ctl->total_new, w->scan_tmp, s, &w->pub, m_dev);
+  if (m > 0) w->rank = scan_popc_tiled(w->bits, n_words, w->word_rank, &d_ctl->total_new, w->scan_tmp, &d_ctl->scan_done, s, &w->pub, m_dev);
   else if (launch_publish(w->pub, s) != COOP_OK) return COOP_E_HIP;
   w->by_partition = by_partition;
   return COOP_OK;
@@ -392,7 +392,7 @@ int unique_front_launch(const int32_t* dst, int64_t n_dst, const int32_t* col_gl
   const int64_t n_all = n_dst + m;
   w->first = alloc.get<uint32_t>(m, COOP_TAG_SCRATCH);
   const int64_t n_words = (m + 63) / 64;
-  w->word_rank = alloc.get<uint32_t>(n_words, COOP_TAG_SCRATCH);
+  w->word_rank = alloc.get<uint32_t>(n_words + 1, COOP_TAG_SCRATCH);
   w->bits = alloc.get<uint64_t>(n_words, COOP_TAG_SCRATCH);
   w->scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_words), COOP_TAG_SCRATCH);
   if (alloc.failed) return COOP_E_NOMEM;
@@ -426,7 +426,7 @@ int unique_back(const int32_t* dst, int64_t n_dst, const int32_t* col_global, in
   const int64_t n_threads = m > n_dst ? m : n_dst;
   if (n_threads > 0)
     COOP_LAUNCH(K_UNIQ_RELABEL, k_uniq_relabel, dim3(nblocks(n_threads)), dim3(kBlock), 0, s, dst, col_global, m, m_dev, n_dst, w.first, w.bits,
-                w.word_rank, src, col_local);
+                w.rank, src, col_local);
   return COOP_OK;
 }
 
