@@ -106,8 +106,6 @@ void scan_chunks_to_i64(const ChunkedI32& in, int64_t n, int64_t* out, int64_t* 
                         const Publish* pub = nullptr);
 // exclusive scan of n uint32 (sum below 2^32); out has n + 1 entries, the last one the total
 void scan_u32_to_u32(const uint32_t* in, int64_t n, uint32_t* out, void* tmp, hipStream_t s);
-// bit flags packed 64 per word -> uint32 exclusive ranks (out has n entries) and the total in *total_out (device)
-void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s);
 // (n_bits_dev, device, optional: only bits [0, *n_bits_dev) count; n_words is then an upper bound known to the host)
 void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s,
                       const Publish* pub = nullptr, const int64_t* n_bits_dev = nullptr);

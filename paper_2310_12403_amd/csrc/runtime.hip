@@ -148,10 +148,6 @@ struct LoadU32 {
   const uint32_t* in;
   __device__ __forceinline__ int64_t operator()(int64_t i) const { return in[i]; }
 };
-struct LoadBit {
-  const uint64_t* bits;
-  __device__ __forceinline__ int64_t operator()(int64_t i) const { return (bits[i >> 6] >> (i & 63)) & 1ull; }
-};
 struct LoadPopc {  // element i = number of set bits of word i
   const uint64_t* bits;
   const int64_t* n_bits;  // when not null: only the words that hold bits [0, *n_bits) count (a size that the host does not know yet)
@@ -304,6 +300,7 @@ size_t scan_tmp_bytes(int64_t n) {  // tile sums, and the one-kernel scans' tile
   return (size_t)(tiles + 2) * sizeof(int64_t) * 2;
 }
 
+constexpr int64_t kScanTiledMax = 64;  // tiles (131,072 elements) up to which the one-kernel scan is used
 template <typename Load>
 static TiledScan<uint32_t> scan_tiled_impl(Load load, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, uint32_t* done, hipStream_t s,
                                            const Publish* p) {
@@ -314,6 +311,11 @@ static TiledScan<uint32_t> scan_tiled_impl(Load load, int64_t n, uint32_t* out, 
   }
   const int64_t tiles = (n + kTile - 1) / kTile;
   int64_t* tile_sum = (int64_t*)tmp;
+  if (tiles > kScanTiledMax) {  // long inputs: two kernels (measured: the fences of many tiles cost more than the second launch)
+    COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_local<Load, uint32_t>), dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, out, tile_sum);
+    COOP_LAUNCH(K_SCAN_OFFSET, k_scan_offset<uint32_t>, dim3((unsigned)tiles), dim3(kBlock), 0, s, n, out, (const int64_t*)tile_sum, out + n, total_out, pub);
+    return TiledScan<uint32_t>{out, nullptr, n};
+  }
   uint32_t* tile_prefix = (uint32_t*)(tile_sum + tiles + 2);
   COOP_LAUNCH(K_SCAN_LOCAL, (k_scan_tiled<Load, uint32_t>), dim3((unsigned)tiles), dim3(kBlock), 0, s, load, n, out, tile_sum, tile_prefix, done,
               total_out, pub);
@@ -366,10 +368,6 @@ TiledScan<uint32_t> scan_u32_tiled(const uint32_t* in, int64_t n, uint32_t* out,
 TiledScan<uint32_t> scan_popc_tiled(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, uint32_t* done,
                                     hipStream_t s, const Publish* pub, const int64_t* n_bits_dev) {
   return scan_tiled_impl<LoadPopc>(LoadPopc{bits, n_bits_dev}, n_words, out, total_out, tmp, done, s, pub);
-}
-
-void scan_bits_to_u32(const uint64_t* bits, int64_t n, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s) {
-  scan_impl<LoadBit, uint32_t>(LoadBit{bits}, n, out, (uint32_t*)nullptr, total_out, tmp, s, nullptr);
 }
 
 void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int64_t* total_out, void* tmp, hipStream_t s,
