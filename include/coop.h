@@ -131,7 +131,8 @@ typedef struct {
  *
  *   g          graph handle
  *   seeds      device int32 [n_seeds], distinct, in range (else COOP_E_DUPSEED / COOP_E_RANGE)
- *   fanouts    host int32 [L], each >= 1; NS needs fanout <= 1024 wherever a degree exceeds it (else COOP_E_CAPACITY)
+ *   fanouts    host int32 [L], each >= 1, no upper limit (NS with a fanout above 1024: the lists longer than the fanout
+ *              go through a slower selection that bisects on the variate instead of collecting candidates)
  *   blocks_out host coop_block [L], filled on success
  * Waits on `stream` once per layer, for |E^l| and |S^{l+1}| together: with a fanout of at most 64 the edge arrays are
  * obtained from the allocator with room for a bound on |E^l| (fanout x |S^l|, plus a little for LABOR-0) and src_ids

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__
   if (bthr) bthr[i] = d > (int64_t)k ? ns_blend_thresholds((uint32_t)bound, cw, sw) : NsBlendThr{0u, 0u, 0u, 0.0f};
 }
 
-constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list can be subsampled
+constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list is subsampled through the candidate arrays
 constexpr uint32_t kNsRedo = 0xFFFFFFFFu;  // candidate count of a destination that the two-kernel path leaves to k_ns_fill
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -316,10 +316,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
     }
     return;
   }
-  if (k > kNsMaxSelect) {  // a degree above a fanout that the candidate buffer cannot serve
-    if (lane == 0) atomicOr(&ctl->err_capacity, 1);
-    return;
-  }
+  if (k > kNsMaxSelect) return;  // a degree above a fanout that the candidate buffer cannot serve: left to k_ns_fill_wide
   uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;  // [cap] variates
   uint32_t* cand_j = cand_r + cap;                       // [cap] positions (d < 2^31)
   uint32_t* cand_k = cand_j + cap;                       // [cap] 1 = among the k smallest
@@ -390,10 +387,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_collect(const int32_t* __restrict
     }
     return;
   }
-  if (k > kNsMaxSelect) {
-    if (lane == 0) atomicOr(&ctl->err_capacity, 1);
-    return;
-  }
+  if (k > kNsMaxSelect) return;  // (k_ns_fill_wide)
   uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;
   uint32_t* cand_j = cand_r + cap;
   int32_t* cand_t = reinterpret_cast<int32_t*>(cand_j + 2 * cap);
@@ -515,6 +509,70 @@ __global__ __launch_bounds__(kBlock) void k_ns_select(const NsRecord* __restrict
   ns_rank_write(n_c, k, cand_r, cand_j, cand_k, cand_t, eptr[w], g.beg, col_global, eid);
 }
 
+// ---- fanouts above kNsMaxSelect ----------------------------------------------------------------------------------
+// The k smallest (R, j) of a list longer than k, for a k that the candidate arrays in LDS cannot hold: no candidates are
+// stored at all.  A bisection over the 32-bit variates finds the smallest B with #{R <= B} >= k (one pass over the list
+// per step, 32 steps); everything below B is kept, and of the entries with R = B (normally one) the first
+// k - #{R < B} in list order.  The last pass writes the kept entries in adjacency order, 64 at a time, each at the
+// running count plus its rank in the ballot.  One wave per destination; 34 passes over a list, variates recomputed in
+// each: a path for the rare call with a fanout in the thousands, not for speed.
+template <bool BLEND>
+__global__ __launch_bounds__(kBlock) void k_ns_fill_wide(const int32_t* __restrict__ g_indices, const NsRecord* __restrict__ rec,
+                                                         int64_t n_dst, uint32_t k, VariateParams vp, const int64_t* __restrict__ eptr,
+                                                         int32_t* __restrict__ col_global, int64_t* __restrict__ eid, int64_t edge_limit) {
+  const int64_t w = (int64_t)blockIdx.x * kWavesPerBlock + uniform_wave_in_block();
+  if (w >= n_dst) return;
+  const NsRecord g = rec[w];
+  if (g.d <= k) return;  // (copied whole by the fill kernel)
+  if (eptr[w + 1] > edge_limit) return;
+  const uint32_t lane = (uint32_t)lane_id();
+  const int32_t* __restrict__ list = g_indices + g.beg;
+  const uint32_t d = g.d;
+  const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)g.s);
+  const uint32_t sigma_b = BLEND ? ns_sigma(vp.K.Kb, (uint32_t)g.s) : 0u;
+  auto count_le = [&](uint32_t B) -> uint32_t {
+    uint32_t n = 0;
+    for (uint32_t base = 0; base < d; base += kWave) {
+      const uint32_t j = base + lane;
+      bool in = false;
+      if (j < d) in = variate<true, BLEND>(vp, (uint32_t)list[j], sigma_a, sigma_b) <= B;
+      n += (uint32_t)__popcll(ballot64(in));
+    }
+    return n;
+  };
+  uint64_t lo = 0, hi = 0xFFFFFFFFull;  // #{R <= hi} >= k throughout (d > k)
+  while (lo < hi) {
+    const uint64_t mid = lo + (hi - lo) / 2;
+    if (count_le((uint32_t)mid) >= k) hi = mid;
+    else lo = mid + 1;
+  }
+  const uint32_t B = (uint32_t)lo;
+  const uint32_t below = B == 0 ? 0u : count_le(B - 1);
+  const uint32_t need = k - below;  // of the entries with R = B, the first `need` in list order (>= 1)
+  const int64_t o = eptr[w];
+  uint32_t placed = 0, ties = 0;
+  for (uint32_t base = 0; base < d; base += kWave) {
+    const uint32_t j = base + lane;
+    int32_t t = 0;
+    uint32_t R = 0xFFFFFFFFu;
+    if (j < d) {
+      t = list[j];
+      R = variate<true, BLEND>(vp, (uint32_t)t, sigma_a, sigma_b);
+    }
+    const bool eq = j < d && R == B;
+    const uint64_t eq_mask = ballot64(eq);
+    const bool keep = j < d && (R < B || (eq && ties + lanes_below(eq_mask) < need));
+    const uint64_t keep_mask = ballot64(keep);
+    if (keep) {
+      const uint32_t at = placed + lanes_below(keep_mask);  // below k: exactly k entries are kept
+      col_global[o + at] = t;
+      eid[o + at] = g.beg + j;
+    }
+    placed += (uint32_t)__popcll(keep_mask);
+    ties += (uint32_t)__popcll(eq_mask);
+  }
+}
+
 int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop_block* blk, int64_t edge_cap) {
   const bool defer = edge_cap > 0;
   hipStream_t s = cx.s;
@@ -531,8 +589,8 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   NsBlendThr* bthr = cx.blend ? alloc.get<NsBlendThr>(n_dst, COOP_TAG_SCRATCH) : nullptr;
   void* scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(n_dst), COOP_TAG_SCRATCH);
   if (alloc.failed) return COOP_E_NOMEM;
-  // candidate buffer: cap >= 4k (power of two, at least 256).  A fanout above kNsMaxSelect is served only while no
-  // degree exceeds it (the fill kernel reports the first that does).
+  // candidate buffer: cap >= 4k (power of two, at least 256).  With a fanout above kNsMaxSelect the lists longer than
+  // the fanout are left to k_ns_fill_wide, which keeps no candidates.
   const uint32_t k_sel = k < kNsMaxSelect ? k : kNsMaxSelect;
   uint32_t cap = 256;
   while (cap < 4 * k_sel) cap <<= 1;
@@ -585,6 +643,13 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
       else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr);
     }
 #undef COOP_NS_ARGS
+    if (k > kNsMaxSelect) {  // the lists longer than such a fanout (the kernels above skip them)
+      const dim3 grid_w(blocks_for(n_dst, kWavesPerBlock));
+      if (cx.blend) COOP_LAUNCH(K_NS_FILL, k_ns_fill_wide<true>, grid_w, dim3(kBlock), 0, s, cx.g->indices, rec, n_dst, k, vp, blk->indptr,
+                                blk->col_global, blk->eid, m);
+      else COOP_LAUNCH(K_NS_FILL, k_ns_fill_wide<false>, grid_w, dim3(kBlock), 0, s, cx.g->indices, rec, n_dst, k, vp, blk->indptr,
+                       blk->col_global, blk->eid, m);
+    }
   }
   return COOP_OK;
 }
