@@ -1,6 +1,8 @@
 """The entry point that allocates nothing (coop_bucket_by_owner_static: its workspace is a device array of the library)
 against the entry point it is a variant of (coop_bucket_by_owner, workspace passed in), through the C ABI: two calls in
 a row, the second with a smaller input, every output bit-equal; then the oracle's grouping as well."""
+import gc
+
 import numpy as np
 import pytest
 import torch
@@ -31,12 +33,14 @@ def test_static_entry_equals_workspace_entry_twice_second_smaller(P):
         out.fill_(-1)
         origin.fill_(-1)
         offsets.fill_(-1)
+        gc.collect()                 # (garbage of earlier tests goes now, not while the two readings below are apart)
         torch.cuda.synchronize()
         before = torch.cuda.memory_allocated()
         free_before = torch.cuda.mem_get_info()[0]
         got = P.coop_bucket_by_owner_static(ids, nv, n_parts, scheme, seed=7, out=out, origin=origin, offsets=offsets)
         torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before and torch.cuda.mem_get_info()[0] >= free_before
+        # nothing new from torch's allocator and nothing new from the driver (a collection in between can only lower the first)
+        assert torch.cuda.memory_allocated() <= before and torch.cuda.mem_get_info()[0] >= free_before
         P.coop_gather_status()
         assert torch.equal(got[0][:n], want[0]) and torch.equal(got[1][:n], want[1])
         assert torch.equal(got[2][: n_parts + 1], want[2])
