@@ -8,9 +8,9 @@
 //     inserted misses  = the last min(M, capacity) misses,
 //     evicted entries  = the E = max(0, size + min(M, capacity) - capacity) smallest stamps among current entries
 //                        (hits were just re-stamped, so they go last).
-// The E-th smallest stamp is found exactly by a most-significant-digit radix select over the stamp array (up to 13
+// The E-th smallest stamp is found exactly by a most-significant-digit radix select over the stamp array (up to 8
 // bits per pass, the bits of the live range split evenly over the passes; all live stamps lie in [previous eviction
-// threshold, clock), so two passes are typical).
+// threshold, clock), so three passes are typical; each pass is one kernel, whose last block picks the digit).
 //
 // Data layout: slot_of[n_vertices] (int32, -1 = not cached), vertex_of[capacity], stamp[capacity] (0 = free),
 // rows[capacity][row_bytes], free_list[capacity] (stack of free slots).  Which free slot a miss lands in is
@@ -25,8 +25,10 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 namespace coop {
 
-constexpr int kSelBits = 13;  // most bits per radix-select pass (8192 LDS counters)
-constexpr int kSelBins = 1 << kSelBits;
+constexpr int kSelBits = 8;  // most bits per radix-select pass: 256 counters, so that merging the blocks' counts into the
+constexpr int kSelBins = 1 << kSelBits;  // global ones takes at most 256 atomics per block
+constexpr int kSelBlock = 1024;    // threads of a select block
+constexpr int kSelMaxBlocks = 256; // one per compute unit
 constexpr int kRowUnroll = 4;  // rows per thread in flight (as in the plain gather)
 
 struct CacheCtl {
@@ -35,6 +37,8 @@ struct CacheCtl {
   int64_t n_hit;
   int32_t n_push;      // slots pushed on the free list by the current eviction
   int32_t err_range;
+  uint32_t sel_done;   // radix select: blocks of the current pass that have merged their counts (back to 0 after each pass)
+  uint32_t pad;
 };
 
 // ---- lookup ---------------------------------------------------------------------------------------------------
@@ -55,25 +59,31 @@ __global__ __launch_bounds__(kBlock) void k_cache_lookup(const int32_t* __restri
   if (lane_id() == 0 && (i & ~(int64_t)63) < n_ids) hit_bits[i >> 6] = b;
 }
 
-// order[r] = index of the r-th hit for r < n_hit; order[n_ids - 1 - q] = index of the q-th miss: the row movers then
-// run over dense lists of hits and of misses instead of idling through the other kind.  An id's rank among the hits is
-// the scanned bit count of the 64-id words in front of its word plus the bits below it in its own word (the scan runs
-// over n_ids / 64 words, not over n_ids flags).
+// order[r] = the r-th hit for r < n_hit; order[n_ids - 1 - q] = the q-th miss: the row movers then run over dense lists
+// of hits and of misses instead of idling through the other kind.  An entry holds the id's index in the batch and what
+// its mover reads from (the cache slot of a hit, the vertex of a miss), so that a mover reaches its row with one
+// dependent load.  An id's rank among the hits is the scanned bit count of the 64-id words in front of its word plus the
+// bits below it in its own word (the scan runs over n_ids / 64 words, not over n_ids flags).
+struct OrderEntry {
+  int32_t i;     // index in the batch: row i of `out`
+  int32_t from;  // hit: cache slot; miss: vertex id
+};
 __global__ __launch_bounds__(kBlock) void k_cache_split(const uint64_t* __restrict__ hit_bits, const uint32_t* __restrict__ word_rank,
-                                                        int64_t n_ids, int32_t* __restrict__ order) {
+                                                        const int32_t* __restrict__ ids, const int32_t* __restrict__ slot_i,
+                                                        int64_t n_ids, OrderEntry* __restrict__ order) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_ids) return;
   const uint64_t word = hit_bits[i >> 6];
   const int64_t h = (int64_t)word_rank[i >> 6] + __popcll(word & ((1ull << (i & 63)) - 1ull));
-  if ((word >> (i & 63)) & 1ull) order[h] = (int32_t)i;
-  else order[n_ids - 1 - (i - h)] = (int32_t)i;
+  if ((word >> (i & 63)) & 1ull) order[h] = OrderEntry{(int32_t)i, slot_i[i]};
+  else order[n_ids - 1 - (i - h)] = OrderEntry{(int32_t)i, ids[i]};
 }
 
 // ---- row movers -----------------------------------------------------------------------------------------------
 // Rows are moved by lpr = 2^lpr_log2 adjacent lanes, V-sized vectors, kRowUnroll rows per thread in flight.
 template <typename V>
 __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ rows, int32_t vecs, int lpr_log2,
-                                                       const int32_t* __restrict__ slot_i, const int32_t* __restrict__ order,
+                                                       const OrderEntry* __restrict__ order,
                                                        const CacheCtl* __restrict__ ctl, V* __restrict__ out,
                                                        uint64_t* __restrict__ stamp, uint64_t clock) {
   const int64_t n_hit = ctl->n_hit;  // known on the device before the host has read it
@@ -89,11 +99,10 @@ __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ row
     src[u] = -1;
     dst[u] = 0;
     if (r < n_hit) {
-      const int32_t i = order[r];
-      const int32_t slot = slot_i[i];
-      src[u] = slot;
-      dst[u] = i;
-      if (sub == 0) stamp[slot] = clock + (uint64_t)r;
+      const OrderEntry e = order[r];
+      src[u] = e.from;
+      dst[u] = e.i;
+      if (sub == 0) stamp[e.from] = clock + (uint64_t)r;
     }
   }
   for (int32_t v = sub; v < vecs; v += lpr) {
@@ -109,7 +118,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ row
 
 template <typename V>
 __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ table, int32_t vecs, int lpr_log2,
-                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ order,
+                                                         const OrderEntry* __restrict__ order,
                                                          int64_t n_ids, V* __restrict__ out, V* __restrict__ rows,
                                                          int32_t* __restrict__ slot_of, int32_t* __restrict__ vertex_of,
                                                          uint64_t* __restrict__ stamp, const int32_t* __restrict__ free_list,
@@ -127,8 +136,8 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
     dst[u] = 0;
     dst_slot[u] = -1;
     if (rank_m < n_miss) {
-      const int32_t i = order[n_ids - 1 - rank_m];
-      const int32_t id = ids[i];
+      const OrderEntry e = order[n_ids - 1 - rank_m];
+      const int32_t i = e.i, id = e.from;
       if (id >= 0) {  // ids out of range were reported by the lookup; negative ones are skipped here
         src[u] = id < table_rows ? id : id % table_rows;
         dst[u] = i;
@@ -136,7 +145,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
         if (q >= 0) {
           const int32_t slot = free_list[n_free - 1 - q];
           dst_slot[u] = slot;
-          if (sub == 0) {
+          if (sub == 0) {  // (a kernel of its own for these three stores costs more than it takes off this one)
             slot_of[id] = slot;
             vertex_of[slot] = id;
             stamp[slot] = clock_miss + (uint64_t)rank_m;
@@ -161,48 +170,76 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
 }
 
 // ---- eviction: radix select of the E-th smallest stamp, then sweep -----------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_cache_sel_hist(const uint64_t* __restrict__ stamp, int64_t capacity, uint64_t base,
-                                                           int shift, int bits, int prev_shift, const CacheCtl* __restrict__ ctl,
-                                                           uint32_t* __restrict__ hist) {
+// One pass of the select: counts, per value of the next `bits` bits, the live entries whose leading digits equal the
+// prefix found so far; the block that merges its counts last (a counter in the control block; nobody waits) finds the
+// digit that holds the `remaining`-th entry, extends the prefix and clears the counters for the next pass.
+__global__ __launch_bounds__(kSelBlock) void k_cache_sel_pass(const uint64_t* __restrict__ stamp, int64_t capacity, uint64_t base,
+                                                              int shift, int bits, int prev_shift, CacheCtl* ctl,
+                                                              uint32_t* __restrict__ hist) {
   __shared__ uint32_t lh[kSelBins];
-  for (int b = threadIdx.x; b < kSelBins; b += kBlock) lh[b] = 0;
+  __shared__ uint32_t wave_tot[kSelBins / kWave];
+  __shared__ uint32_t s_last;
+  if (threadIdx.x < kSelBins) lh[threadIdx.x] = 0;
   __syncthreads();
   const uint64_t prefix = ctl->prefix;
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const int64_t stride = (int64_t)gridDim.x * kBlock;
-  for (; i < capacity; i += stride) {
-    const uint64_t st = stamp[i];
-    if (st == 0) continue;
-    const uint64_t x = st - base;
-    if (prev_shift >= 0 && (x >> prev_shift) != prefix) continue;
-    atomicAdd(&lh[(x >> shift) & ((1u << bits) - 1)], 1u);
+  const uint32_t digit_mask = (1u << bits) - 1u;
+  const int64_t stride = (int64_t)gridDim.x * kSelBlock;
+  constexpr int U = 4;  // stamps per thread in flight
+  for (int64_t first = (int64_t)blockIdx.x * kSelBlock + threadIdx.x; first < capacity; first += U * stride) {
+    uint64_t st[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = first + u * stride;
+      st[u] = i < capacity ? stamp[i] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint64_t x = st[u] - base;
+      const bool in = st[u] != 0 && (prev_shift < 0 || (x >> prev_shift) == prefix);
+      const uint32_t digit = (uint32_t)(x >> shift) & digit_mask;
+      // neighbouring slots were mostly filled by the same call and share a digit: one add for the wave then
+      const uint64_t m = ballot64(in);
+      if (m == 0) continue;
+      const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)digit, __builtin_ctzll(m));
+      if (ballot64(in && digit == d0) == m) {
+        if ((uint32_t)lane_id() == (uint32_t)__builtin_ctzll(m)) atomicAdd(&lh[d0], (uint32_t)__popcll(m));
+      } else if (in) {
+        atomicAdd(&lh[digit], 1u);
+      }
+    }
   }
   __syncthreads();
-  for (int b = threadIdx.x; b < kSelBins; b += kBlock) {
-    const uint32_t c = lh[b];
-    if (c) atomicAdd(&hist[b], c);
+  if (threadIdx.x < kSelBins) {
+    const uint32_t c = lh[threadIdx.x];
+    if (c) atomicAdd(&hist[threadIdx.x], c);
   }
-}
-
-// one block: the bin that holds the `remaining`-th entry; extends the prefix, clears the histogram
-__global__ __launch_bounds__(kBlock) void k_cache_sel_pick(uint32_t* __restrict__ hist, int bits, CacheCtl* ctl) {
-  __shared__ uint64_t part[kBlock];
-  constexpr int per = kSelBins / kBlock;  // consecutive bins per thread
-  uint64_t s = 0;
-  for (int j = 0; j < per; ++j) s += hist[threadIdx.x * per + j];
-  part[threadIdx.x] = s;
-  __syncthreads();
+  __syncthreads();  // the block's adds have been performed (each wave waits for its own before the barrier)
   if (threadIdx.x == 0) {
-    uint64_t remaining = ctl->remaining, cum = 0;
-    int t = 0;
-    while (t < kBlock - 1 && cum + part[t] < remaining) { cum += part[t]; ++t; }
-    int b = t * per;
-    while (b < t * per + per - 1 && cum + hist[b] < remaining) { cum += hist[b]; ++b; }
-    ctl->prefix = (ctl->prefix << bits) | (uint64_t)b;
-    ctl->remaining = remaining - cum;
+    __threadfence();  // ... and are ordered before the block counts as done
+    s_last = atomicAdd(&ctl->sel_done, 1u) == gridDim.x - 1 ? 1u : 0u;
+    __threadfence();  // every other block merged its counts before it counted itself
   }
   __syncthreads();
-  for (int j = 0; j < per; ++j) hist[threadIdx.x * per + j] = 0;
+  if (s_last == 0) return;
+  const bool has = threadIdx.x < kSelBins;  // (the first kSelBins / 64 waves, whole)
+  const uint32_t v = has ? __hip_atomic_load(&hist[threadIdx.x % kSelBins], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+  uint32_t incl = wave_incl_scan(v);
+  if (has && lane_id() == kWave - 1) wave_tot[threadIdx.x / kWave] = incl;
+  __syncthreads();
+  if (!has) return;
+  for (int w = 0; w < (int)threadIdx.x / kWave; ++w) incl += wave_tot[w];
+  uint32_t total = 0;
+  for (int w = 0; w < kSelBins / kWave; ++w) total += wave_tot[w];
+  const uint64_t remaining = ctl->remaining;
+  const uint64_t before = (uint64_t)(incl - v);
+  // the digit that holds the remaining-th entry; if the counts fall short of it (they do not), the last digit
+  const bool mine = remaining > (uint64_t)total ? threadIdx.x == digit_mask : (before < remaining && remaining <= (uint64_t)incl);
+  if (mine) {
+    ctl->prefix = (prefix << bits) | (uint64_t)threadIdx.x;
+    ctl->remaining = remaining - before;
+    ctl->sel_done = 0;
+  }
+  __hip_atomic_store(&hist[threadIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Evicts every entry with stamp - base <= threshold (or every entry, if evict_all) and pushes the freed slots on the
@@ -264,7 +301,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_evict(uint64_t* __restrict__ s
 }
 
 __global__ void k_cache_ctl_set(CacheCtl* ctl, uint64_t remaining) {
-  ctl->prefix = 0; ctl->remaining = remaining; ctl->n_push = 0;
+  ctl->prefix = 0; ctl->remaining = remaining; ctl->n_push = 0; ctl->sel_done = 0;
 }
 
 __global__ void k_cache_clear_err(CacheCtl* ctl) { ctl->err_range = 0; }
@@ -291,7 +328,7 @@ struct coop_cache {
   int32_t* slot_i;
   uint64_t* hit_bits;
   uint32_t* rank_h;
-  int32_t* order;         // hits from the front, misses from the back
+  OrderEntry* order;      // hits from the front, misses from the back
   void* scan_tmp;
   uint32_t* hist;
   CacheCtl* d_ctl;
@@ -331,7 +368,7 @@ extern "C" int coop_cache_create(int64_t capacity_rows, int64_t n_vertices, int3
   c->slot_i = alloc.get<int32_t>(max_ids, COOP_TAG_OUTPUT);
   c->hit_bits = alloc.get<uint64_t>((max_ids + 63) / 64, COOP_TAG_OUTPUT);
   c->rank_h = alloc.get<uint32_t>(max_ids, COOP_TAG_OUTPUT);
-  c->order = alloc.get<int32_t>(max_ids, COOP_TAG_OUTPUT);
+  c->order = alloc.get<OrderEntry>(max_ids, COOP_TAG_OUTPUT);
   c->scan_tmp = alloc.get<char>((int64_t)scan_tmp_bytes(max_ids), COOP_TAG_OUTPUT);
   c->hist = alloc.get<uint32_t>(kSelBins, COOP_TAG_OUTPUT);
   c->d_ctl = alloc.get<CacheCtl>(1, COOP_TAG_OUTPUT);
@@ -508,11 +545,11 @@ void launch_rows(coop_cache* c, const void* table, int64_t table_rows, const int
   const int64_t rows_per_launch_block = (int64_t)(kBlock >> lpr_log2) * kRowUnroll;
   const unsigned grid = (unsigned)((n_ids + rows_per_launch_block - 1) / rows_per_launch_block);
   if (hits) {
-    COOP_LAUNCH(K_CACHE_GATHER, k_cache_hits<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)c->rows, vecs, lpr_log2, c->slot_i, c->order,
+    COOP_LAUNCH(K_CACHE_GATHER, k_cache_hits<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)c->rows, vecs, lpr_log2, (const OrderEntry*)c->order,
                 c->d_ctl, (V*)out, c->stamp, c->clock);
   } else {
     const unsigned grid_m = (unsigned)((n_miss + rows_per_launch_block - 1) / rows_per_launch_block);
-    COOP_LAUNCH(K_CACHE_UPDATE, k_cache_misses<V>, dim3(grid_m), dim3(kBlock), 0, s, (const V*)table, vecs, lpr_log2, ids, c->order, n_ids,
+    COOP_LAUNCH(K_CACHE_UPDATE, k_cache_misses<V>, dim3(grid_m), dim3(kBlock), 0, s, (const V*)table, vecs, lpr_log2, (const OrderEntry*)c->order, n_ids,
                 (V*)out, (V*)c->rows, c->slot_of, c->vertex_of, c->stamp, c->free_list, n_free, n_miss, n_ins,
                 c->clock + (uint64_t)n_hit, table_rows);
   }
@@ -548,7 +585,7 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
               c->n_vertices, c->slot_of, c->slot_i, c->hit_bits, c->d_ctl);
   scan_popc_to_u32(c->hit_bits, (n_ids + 63) / 64, c->rank_h, &c->d_ctl->n_hit, c->scan_tmp, s);
   COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_split, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, (const uint64_t*)c->hit_bits,
-              (const uint32_t*)c->rank_h, n_ids, c->order);
+              (const uint32_t*)c->rank_h, ids, (const int32_t*)c->slot_i, n_ids, c->order);
   COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
   // 2. hits: rows out of the cache, new stamps (runs while the host waits for the counts)
   dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, 0, 0, 0, 0, true, s);
@@ -578,17 +615,15 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
       while (nbits < 64 && (range >> nbits) != 0) ++nbits;
       const int passes = (nbits + kSelBits - 1) / kSelBits;
       COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)n_evict);
-      // the bits of the range are split evenly over the passes, so that every pass spreads the entries over many
-      // counters (a narrow leading digit would pile every entry onto a handful of LDS words)
+      // the bits of the range are split evenly over the passes
       int prev_shift = -1, shift = nbits;
       for (int p = 0; p < passes; ++p) {
         const int bits = (shift + (passes - p) - 1) / (passes - p);
         shift -= bits;
-        int64_t blocks = (c->capacity + kBlock * 64 - 1) / (kBlock * 64);  // >= 64 entries per thread: few flushes of the counters
-        if (blocks > 1024) blocks = 1024;
-        COOP_LAUNCH(K_CACHE_SELECT, k_cache_sel_hist, dim3((unsigned)(blocks > 0 ? blocks : 1)), dim3(kBlock), 0, s, c->stamp, c->capacity,
+        int64_t blocks = (c->capacity + kSelBlock * 4 - 1) / (kSelBlock * 4);
+        if (blocks > kSelMaxBlocks) blocks = kSelMaxBlocks;
+        COOP_LAUNCH(K_CACHE_SELECT, k_cache_sel_pass, dim3((unsigned)(blocks > 0 ? blocks : 1)), dim3(kSelBlock), 0, s, c->stamp, c->capacity,
                     c->base, shift, bits, prev_shift, c->d_ctl, c->hist);
-        COOP_LAUNCH(K_CACHE_PICK, k_cache_sel_pick, dim3(1), dim3(kBlock), 0, s, c->hist, bits, c->d_ctl);
         prev_shift = shift;
       }
       threshold_known = true;
