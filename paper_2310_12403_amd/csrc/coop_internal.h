@@ -37,8 +37,7 @@ enum KernelId {
   K_OWNER_SCATTER,   // ids by owner: stable placement
   K_VALIDATE,        // CSR validation
   K_CACHE_LOOKUP,
-  K_CACHE_SELECT,
-  K_CACHE_PICK,
+  K_CACHE_SELECT,    // one pass of the radix select of the eviction threshold
   K_CACHE_EVICT,
   K_CACHE_UPDATE,
   K_CACHE_GATHER,

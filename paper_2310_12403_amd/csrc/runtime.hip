@@ -25,7 +25,7 @@ struct Prof {
 const char* const kKernelNames[K_COUNT_] = {
     "fill", "labor_scan", "labor_fill", "labor_fill_overflow", "labor_exact", "segments", "enum_list", "enum_walk", "ns_count", "ns_fill", "ns_select", "rw_walk", "rw_fill", "scan_local", "scan_offset",
     "unique_insert", "unique_flag", "unique_relabel", "unique_part_count", "unique_part_scatter", "unique_part_first", "copy_ids", "gather", "gather_mean", "owner_count", "owner_scatter", "validate_csr",
-    "cache_lookup", "cache_select_hist", "cache_select_pick", "cache_evict", "cache_miss_rows", "cache_hit_rows"};
+    "cache_lookup", "cache_select", "cache_evict", "cache_miss_rows", "cache_hit_rows"};
 
 hipEvent_t take_event() {
   if (!g_prof.pool.empty()) { hipEvent_t e = g_prof.pool.back(); g_prof.pool.pop_back(); return e; }

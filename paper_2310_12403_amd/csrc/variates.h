@@ -37,17 +37,6 @@ __host__ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
   return x;
 }
 
-// The mixer without its last step: mix32(x) = h ^ (h >> 16) with h = mix32_head(x), so h and mix32(x) have the same upper
-// 16 bits.  A test "mix32(x) ^ K <= T" can therefore only hold if (mix32_head(x) ^ K) <= (T | 0xFFFF): a necessary
-// condition that is one instruction cheaper per evaluation, for scans that discard almost every entry they look at.
-__host__ __device__ __forceinline__ uint32_t mix32_head(uint32_t x) {
-  x ^= x >> 16;
-  x *= 0x7FEB352Du;
-  x ^= x >> 15;
-  x *= 0x846CA68Bu;
-  return x;
-}
-
 // the mixer is a bijection of the 32-bit integers: its inverse (0x43021123, 0x1D69E2A5: the multipliers' inverses mod 2^32)
 __host__ __device__ __forceinline__ uint32_t unmix32(uint32_t x) {
   x ^= x >> 16;
