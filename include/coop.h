@@ -327,6 +327,10 @@ const char* coop_strerror(int code);
                                       fanout exceeds 64; at 8192 and above only to passes over 65536 lists or more of a
                                       graph whose lists above 8192 entries hold an eighth of its edges (below that the
                                       listing costs more than it saves); smaller values, meant for tests, apply always */
+#define COOP_TUNE_NS_LONG_LIST 9   /* NS with independent variates: destinations whose list is longer than this many entries
+                                      are queued and taken by the first waves of the traversal, so that no hub starts late
+                                      (default 2048, for passes over 32768 destinations or more; 0: never; other values,
+                                      64..2^30, meant for tests, apply to every pass) */
 int coop_tune(int knob, int64_t value);
 
 /* out[i] = in[i] for a device id list (a plain streaming copy on `stream`: 4n bytes read, 4n written).  Besides its

@@ -27,32 +27,59 @@ struct NsRecord {
   uint32_t pad;
 };
 
+// (long_min > 0: the destinations whose list is longer than long_min entries, and than k, are also queued in long_list,
+// in no particular order, *n_long counting them: the traversal kernels give those to their first waves, see there)
 __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__ g_indptr, int64_t n_vertices,
                                                      const int32_t* __restrict__ dst, int64_t n_dst, uint32_t k, uint32_t target,
                                                      int32_t* __restrict__ cnt, NsRecord* __restrict__ rec,
-                                                     NsBlendThr* __restrict__ bthr /* null when c = 0 */, double cw, double sw, Ctl* ctl) {
+                                                     NsBlendThr* __restrict__ bthr /* null when c = 0 */, double cw, double sw, Ctl* ctl,
+                                                     uint32_t long_min, uint32_t* __restrict__ long_list, uint32_t* __restrict__ n_long) {
+  __shared__ uint32_t wave_long[kWavesPerBlock];
+  __shared__ uint32_t block_base;
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= n_dst) return;
-  const int32_t s = dst[i];
-  if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
-    atomicOr(&ctl->err_range, 1);
-    cnt[i] = 0;
-    rec[i] = NsRecord{0, 0u, 0, 0u, 0u};
-    if (bthr) bthr[i] = NsBlendThr{0u, 0u, 0u, 0.0f};
-    return;
+  bool is_long = false;
+  if (i < n_dst) {
+    const int32_t s = dst[i];
+    if ((uint64_t)(uint32_t)s >= (uint64_t)n_vertices) {
+      atomicOr(&ctl->err_range, 1);
+      cnt[i] = 0;
+      rec[i] = NsRecord{0, 0u, 0, 0u, 0u};
+      if (bthr) bthr[i] = NsBlendThr{0u, 0u, 0u, 0.0f};
+    } else {
+      const int64_t beg = g_indptr[s];
+      const int64_t d = g_indptr[s + 1] - beg;
+      cnt[i] = (int32_t)(d < (int64_t)k ? d : (int64_t)k);
+      // bound such that E[#candidates] = target: R <= bound with probability (bound + 1) / 2^32 (one 64-bit division per
+      // list, here where every lane has a list of its own)
+      uint64_t bound = d > 0 ? ((uint64_t)target << 32) / (uint64_t)d : 0xFFFFFFFFull;
+      if (bound > 0xFFFFFFFFull) bound = 0xFFFFFFFFull;  // d <= target: every neighbour is a candidate
+      rec[i] = NsRecord{beg, (uint32_t)d, s, (uint32_t)bound, 0u};
+      if (bthr) bthr[i] = d > (int64_t)k ? ns_blend_thresholds((uint32_t)bound, cw, sw) : NsBlendThr{0u, 0u, 0u, 0.0f};
+      is_long = long_min != 0 && d > (int64_t)long_min && d > (int64_t)k;
+    }
   }
-  const int64_t beg = g_indptr[s];
-  const int64_t d = g_indptr[s + 1] - beg;
-  cnt[i] = (int32_t)(d < (int64_t)k ? d : (int64_t)k);
-  // bound such that E[#candidates] = target: R <= bound with probability (bound + 1) / 2^32 (one 64-bit division per
-  // list, here where every lane has a list of its own)
-  uint64_t bound = d > 0 ? ((uint64_t)target << 32) / (uint64_t)d : 0xFFFFFFFFull;
-  if (bound > 0xFFFFFFFFull) bound = 0xFFFFFFFFull;  // d <= target: every neighbour is a candidate
-  rec[i] = NsRecord{beg, (uint32_t)d, s, (uint32_t)bound, 0u};
-  if (bthr) bthr[i] = d > (int64_t)k ? ns_blend_thresholds((uint32_t)bound, cw, sw) : NsBlendThr{0u, 0u, 0u, 0.0f};
+  if (long_min == 0) return;  // (the same for every thread)
+  const uint64_t m = ballot64(is_long);
+  const int wib = wave_in_block();
+  if (lane_id() == 0) wave_long[wib] = (uint32_t)__popcll(m);
+  __syncthreads();
+  if (threadIdx.x == 0) {  // one reservation per block
+    uint32_t total = 0;
+    for (int w = 0; w < kWavesPerBlock; ++w) total += wave_long[w];
+    block_base = total ? atomicAdd(n_long, total) : 0u;
+  }
+  __syncthreads();
+  if (is_long) {
+    uint32_t at = block_base + lanes_below(m);
+    for (int w = 0; w < wib; ++w) at += wave_long[w];
+    long_list[at] = (uint32_t)i;  // (at < n_dst: every destination is queued at most once)
+  }
 }
 
 constexpr uint32_t kNsMaxSelect = 1024;  // largest fanout for which a longer list is subsampled through the candidate arrays
+constexpr int64_t kNsQueueFrom = 32768;  // destinations from which the long lists are queued for the first waves
+constexpr int kNsLongDefault = 2048;
+int g_ns_long_min = kNsLongDefault;      // COOP_TUNE_NS_LONG_LIST: lists longer than this are queued (0 = none)
 constexpr uint32_t kNsRedo = 0xFFFFFFFFu;  // candidate count of a destination that the two-kernel path leaves to k_ns_fill
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -187,22 +214,25 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
         ok[gq] = base + (uint32_t)(gq * kWave * 4) + lane * 4 < vec_end;
       }
       if (!BLEND && base + kStep < vec_end) fetch(base + kStep);
-#pragma unroll
-      for (int gq = 0; gq < kNsGroups; ++gq) {
-        if (base + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the rest of this step lies behind the list
+      auto group = [&](int gq, bool valid) {
         const uint32_t r = base + (uint32_t)(gq * kWave * 4) + lane * 4;
         uint32_t R[4], U2[4];
         bool flag[4];
         bool any = false;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          flag[e] = first_look(ok[gq], buf[gq][e], R[e], U2[e]);
+          flag[e] = first_look(valid, buf[gq][e], R[e], U2[e]);
           any |= flag[e];
         }
         if (ballot64(any) != 0) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) take(flag[e], buf[gq][e], r + e - head, R[e], U2[e]);
         }
+      };
+#pragma unroll
+      for (int gq = 0; gq < kNsGroups; ++gq) {
+        if (base + (uint32_t)(gq * kWave * 4) >= vec_end) break;  // wave-uniform: the rest of this step lies behind the list
+        group(gq, ok[gq]);
       }
     }
     {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
@@ -286,21 +316,17 @@ __device__ __forceinline__ void ns_rank_write(uint32_t n_c, uint32_t k, const ui
 //   2. if fewer than k or more than cap candidates turn up, the bound is bisected and the pass repeated (rare);
 //   3. every candidate's rank by (R, j) among the candidates is counted: ranks below k are kept;
 //   4. every kept candidate's place is the number of kept candidates in front of it in the list.
+//
+// The degree distribution is heavy-tailed and a wave takes a whole list, so the lists longer than long_min entries
+// are not left where the destination order puts them (a hub that starts late would keep the kernel waiting for one
+// wave): k_ns_count queues them, the first long_blocks blocks of the grid stride over the queue (its length is read from
+// device memory; every wave ends after a bounded number of steps), and the other blocks take the destinations in order
+// and skip the queued ones.
 template <bool BLEND, bool VEC4>
-__global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ g_indices,
-                                                    const NsRecord* __restrict__ rec, const NsBlendThr* __restrict__ bthr,
-                                                    int64_t n_dst, uint32_t k,
-                                                    uint32_t cap, int waves_per_block, VariateParams vp,
-                                                    const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
-                                                    int64_t* __restrict__ eid, int64_t edge_limit, Ctl* ctl,
-                                                    const uint32_t* __restrict__ only /* when not null: only lists marked kNsRedo */) {
-  extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
-  __shared__ NsQueue queues[BLEND ? kWavesPerBlock : 1];
-  const int wib = uniform_wave_in_block();
-  if (wib >= waves_per_block) return;
-  const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
-  if (w >= n_dst) return;
-  if (only != nullptr && only[w] != kNsRedo) return;
+__device__ __forceinline__ void ns_fill_one(int64_t w, int wib, uint32_t* lds_words, NsQueue* queue, const int32_t* __restrict__ g_indices,
+                                            const NsRecord* __restrict__ rec, const NsBlendThr* __restrict__ bthr, uint32_t k, uint32_t cap,
+                                            const VariateParams& vp, const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
+                                            int64_t* __restrict__ eid, int64_t edge_limit, Ctl* ctl, uint32_t skip_above) {
   const uint32_t lane = (uint32_t)lane_id();
   const int64_t o = eptr[w];
   if (eptr[w + 1] > edge_limit) return;  // the wave writes [o, eptr[w + 1]) only; no room: the caller redoes the layer
@@ -316,6 +342,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
     }
     return;
   }
+  if (d > skip_above) return;    // queued: one of the first waves takes it
   if (k > kNsMaxSelect) return;  // a degree above a fanout that the candidate buffer cannot serve: left to k_ns_fill_wide
   uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;  // [cap] variates
   uint32_t* cand_j = cand_r + cap;                       // [cap] positions (d < 2^31)
@@ -330,7 +357,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
   if constexpr (BLEND) bt = bthr[w];
   uint32_t n_c = 0;
   for (int attempt = 0; attempt < 40; ++attempt) {
-    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, bt, vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap, &queues[BLEND ? wib : 0]);
+    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, bt, vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap, queue);
     if (n_c >= k && n_c <= cap) break;
     // cannot be bracketed (more than cap - k equal variates): report instead of guessing
     if (n_c < k) {
@@ -353,6 +380,39 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
   ns_rank_write(n_c, k, cand_r, cand_j, cand_k, cand_t, o, beg, col_global, eid);
 }
 
+template <bool BLEND, bool VEC4>
+__global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ g_indices,
+                                                    const NsRecord* __restrict__ rec, const NsBlendThr* __restrict__ bthr,
+                                                    int64_t n_dst, uint32_t k,
+                                                    uint32_t cap, int waves_per_block, VariateParams vp,
+                                                    const int64_t* __restrict__ eptr, int32_t* __restrict__ col_global,
+                                                    int64_t* __restrict__ eid, int64_t edge_limit, Ctl* ctl,
+                                                    const uint32_t* __restrict__ only /* when not null: only lists marked kNsRedo */,
+                                                    uint32_t long_min, const uint32_t* __restrict__ long_list,
+                                                    const uint32_t* __restrict__ n_long, int long_blocks) {
+  extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
+  __shared__ NsQueue queues[BLEND ? kWavesPerBlock : 1];
+  const int wib = uniform_wave_in_block();
+  if (wib >= waves_per_block) return;
+  NsQueue* queue = &queues[BLEND ? wib : 0];
+  const bool queue_wave = (int)blockIdx.x < long_blocks;
+  int64_t w;
+  if (queue_wave) {  // the q-th queued long list
+    const int64_t q = (int64_t)blockIdx.x * waves_per_block + wib;
+    int64_t n_queued = (int64_t)*n_long;
+    if (n_queued > n_dst) n_queued = n_dst;  // (holds by construction; keeps every access inside the queue regardless)
+    if (q >= n_queued) return;
+    // (the same in every lane; said so, or everything derived from it would be kept per lane)
+    w = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)long_list[q]);
+  } else {
+    w = (int64_t)((int)blockIdx.x - long_blocks) * waves_per_block + wib;
+    if (only != nullptr && w < n_dst && only[w] != kNsRedo) return;
+  }
+  if (w >= n_dst) return;
+  ns_fill_one<BLEND, VEC4>(w, wib, lds_words, queue, g_indices, rec, bthr, k, cap, vp, eptr, col_global, eid, edge_limit, ctl,
+                           !queue_wave && long_min != 0 ? long_min : 0xFFFFFFFFu);
+}
+
 // ---- c > 0 in two kernels ----------------------------------------------------------------------------------------
 // The exact blend (two inverse normal distribution functions and one forward, in fp64) needs four times the registers of
 // the traversal and is wanted for a few dozen candidates per list only.  So the traversal kernel stops at the fp32
@@ -367,18 +427,31 @@ __global__ __launch_bounds__(kBlock) void k_ns_collect(const int32_t* __restrict
                                                        const NsBlendThr* __restrict__ bthr, int64_t n_dst, uint32_t k, uint32_t cap,
                                                        int waves_per_block, VariateParams vp, const int64_t* __restrict__ eptr,
                                                        int32_t* __restrict__ col_global, int64_t* __restrict__ eid, int64_t edge_limit,
-                                                       Ctl* ctl, NsCand* __restrict__ rows, uint32_t row_cap, uint32_t* __restrict__ n_cand) {
+                                                       Ctl* ctl, NsCand* __restrict__ rows, uint32_t row_cap, uint32_t* __restrict__ n_cand,
+                                                       uint32_t long_min, const uint32_t* __restrict__ long_list,
+                                                       const uint32_t* __restrict__ n_long, int long_blocks) {
   extern __shared__ uint32_t lds_words[];
   __shared__ NsQueue queues[kWavesPerBlock];
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
-  const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
+  const bool queue_wave = (int)blockIdx.x < long_blocks;  // the queued long lists first, as in k_ns_fill
+  int64_t w;
+  if (queue_wave) {
+    const int64_t q = (int64_t)blockIdx.x * waves_per_block + wib;
+    int64_t n_queued = (int64_t)*n_long;
+    if (n_queued > n_dst) n_queued = n_dst;
+    if (q >= n_queued) return;
+    w = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)long_list[q]);
+  } else {
+    w = (int64_t)((int)blockIdx.x - long_blocks) * waves_per_block + wib;
+  }
   if (w >= n_dst) return;
   const uint32_t lane = (uint32_t)lane_id();
+  const NsRecord g = rec[w];
+  if (!queue_wave && long_min != 0 && g.d > long_min && g.d > k) return;  // queued: one of the first waves takes it
   if (lane == 0) n_cand[w] = 0;  // nothing left to do for this destination, unless said otherwise below
   const int64_t o = eptr[w];
   if (eptr[w + 1] > edge_limit) return;
-  const NsRecord g = rec[w];
   if (g.d == 0) return;
   if (g.d <= k) {
     for (uint32_t j = lane; j < g.d; j += kWave) {
@@ -602,9 +675,19 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   while (root * root < k_sel) ++root;
   uint32_t target = cx.blend ? k_sel + 4 * root + 4 : k_sel + 2 * root + 2;
   if (target > 2 * k_sel + 16) target = 2 * k_sel + 16;
+  // long lists first (see k_ns_fill): worth its queue from a few tens of thousands of destinations on
+  // (default: passes over many destinations of a graph with hubs; where the registration has added the entries of the
+  // lists above kLongListDegree up, a graph on which they hold less than an eighth of the edges is left alone: the queue
+  // costs the count pass a reservation per block and buys nothing there)
+  const bool hubs = !cx.g->symmetric || cx.g->long_mass >= cx.g->n_edges / 8;
+  const bool queue_long = g_ns_long_min != 0 && (g_ns_long_min != kNsLongDefault || (n_dst >= kNsQueueFrom && hubs));
+  const uint32_t long_min = queue_long ? (uint32_t)g_ns_long_min : 0u;
+  uint32_t* long_list = queue_long ? alloc.get<uint32_t>(n_dst, COOP_TAG_SCRATCH) : nullptr;
+  uint32_t* n_long = cx.d_piece_count + l;  // (zero at the start of the call and whenever the layer is redone)
+  if (alloc.failed) return COOP_E_NOMEM;
   if (n_dst > 0)
     COOP_LAUNCH(K_NS_COUNT, k_ns_count, dim3(blocks_for(n_dst, kBlock)), dim3(kBlock), 0, s, cx.g->indptr, cx.g->n_vertices, dst, n_dst,
-                k, target, cnt, rec, bthr, cx.cw, cx.sw, cx.d_ctl);
+                k, target, cnt, rec, bthr, cx.cw, cx.sw, cx.d_ctl, long_min, long_list, n_long);
   if (defer) {
     scan_i32_to_i64(cnt, n_dst, blk->indptr, &cx.d_ctl->total_edges, scan_tmp, s, nullptr);  // the count stays on the device
   } else {
@@ -625,6 +708,11 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
     const size_t shmem = (size_t)wpb * cap * 16;
     const dim3 grid(blocks_for(n_dst, wpb));
 #define COOP_NS_ARGS cx.g->indices, rec, bthr, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, m, cx.d_ctl
+    // the queue's waves, one per queued list: as many as there can be lists that long (the unused ones end at once)
+    int64_t most_long = cx.g->n_edges / (int64_t)(long_min ? long_min : 1) + 1;
+    if (most_long > n_dst) most_long = n_dst;
+    const int long_blocks = queue_long ? (int)blocks_for(most_long, wpb) : 0;
+    const dim3 grid_q(grid.x + (unsigned)long_blocks);
     if (cx.blend) {
       // rows of the two-kernel path: room for twice the expected candidates (at least 64, at most the LDS capacity)
       uint32_t row_cap = 64;
@@ -632,15 +720,21 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
       NsCand* rows = alloc.get<NsCand>(n_dst * (int64_t)row_cap, COOP_TAG_SCRATCH);
       uint32_t* n_cand = alloc.get<uint32_t>(n_dst, COOP_TAG_SCRATCH);
       if (alloc.failed) return COOP_E_NOMEM;
-      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, k_ns_collect<true>, grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand);
-      else COOP_LAUNCH(K_NS_FILL, k_ns_collect<false>, grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand);
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, k_ns_collect<true>, grid_q, dim3(kBlock), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand, long_min,
+                               (const uint32_t*)long_list, (const uint32_t*)n_long, long_blocks);
+      else COOP_LAUNCH(K_NS_FILL, k_ns_collect<false>, grid_q, dim3(kBlock), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand, long_min,
+                       (const uint32_t*)long_list, (const uint32_t*)n_long, long_blocks);
       COOP_LAUNCH(K_NS_SELECT, k_ns_select, grid, dim3(kBlock), shmem, s, rec, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid,
                   (const NsCand*)rows, row_cap, n_cand, (const NsBlendThr*)bthr);
-      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand);
-      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand);
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand, 0u,
+                               (const uint32_t*)nullptr, (const uint32_t*)nullptr, 0);
+      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand, 0u,
+                       (const uint32_t*)nullptr, (const uint32_t*)nullptr, 0);
     } else {
-      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr);
-      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr);
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, true>), grid_q, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr, long_min,
+                               (const uint32_t*)long_list, (const uint32_t*)n_long, long_blocks);
+      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, false>), grid_q, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr, long_min,
+                       (const uint32_t*)long_list, (const uint32_t*)n_long, long_blocks);
     }
 #undef COOP_NS_ARGS
     if (k > kNsMaxSelect) {  // the lists longer than such a fanout (the kernels above skip them)

@@ -120,6 +120,10 @@ extern "C" int coop_tune(int knob, int64_t value) {
       if (value < 0 || value > 2) return COOP_E_ARG;
       g_defer_sizes = (int)value;
       return COOP_OK;
+    case COOP_TUNE_NS_LONG_LIST:
+      if (value != 0 && (value < 64 || value > ((int64_t)1 << 30))) return COOP_E_ARG;
+      g_ns_long_min = (int)value;
+      return COOP_OK;
     default:
       return COOP_E_ARG;
   }

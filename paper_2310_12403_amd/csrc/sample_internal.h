@@ -83,6 +83,7 @@ extern int g_piece_len;
 extern int64_t g_blend_candidates;
 extern int g_defer_sizes;
 extern int g_enum_degree;
+extern int g_ns_long_min;   // COOP_TUNE_NS_LONG_LIST (defined in ns.hip)
 
 static inline unsigned blocks_for(int64_t n, int64_t per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 

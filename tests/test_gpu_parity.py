@@ -482,6 +482,29 @@ def test_limits_of_the_interface(P, tiny):
     assert e.value.code == -4
 
 
+@pytest.mark.parametrize("long_min", [64, 300, 0])
+def test_ns_long_lists_taken_by_the_first_waves(P, tiny, medium, long_min):
+    """The NS traversal hands the destinations with long lists to the first waves of its grid (a queue filled by the count
+    pass) and leaves the rest in destination order.  With the knob at 64 or 300 every pass of these small graphs takes
+    that path (by default only passes over 32,768 destinations or more do): same bytes as the oracle, also with a fanout
+    above the candidate arrays, whose long lists go on to the bisection kernel, and with the queue switched off."""
+    deg = np.diff(medium.indptr_h)
+    hubs = np.argsort(-deg)[:30].astype(np.int32)
+    rest = synth.seed_batches(medium.n, 3000, seed=12)(0).numpy()
+    seeds = np.concatenate([hubs, rest[~np.isin(rest, hubs)]])
+    try:
+        P.coop_tune(P.COOP_TUNE_NS_LONG_LIST, long_min)
+        compare(P, medium, seeds, (10, 10, 10), R.NS, it=3, kappa=1, seed=31)
+        compare(P, medium, seeds[:500], (25, 10), R.NS, it=16, kappa=16, seed=31)   # (a group boundary: c = 0)
+        compare(P, medium, seeds[:400], (10, 5), R.NS, it=21, kappa=16, seed=31)    # (c = 5/16: the blended kernels)
+        compare(P, medium, hubs, (1100, 2), R.NS, it=2, kappa=1, seed=32)
+        compare(P, tiny, synth.seed_batches(tiny.n, 1024, seed=0)(2).numpy(), (10, 10, 10), R.NS, it=1, kappa=1, seed=33)
+    finally:
+        P.coop_tune(P.COOP_TUNE_NS_LONG_LIST, 2048)
+    with pytest.raises(P.CoopError):
+        P.coop_tune(P.COOP_TUNE_NS_LONG_LIST, 5)
+
+
 def test_ns_fanouts_above_the_candidate_arrays(P, medium):
     """App. A.1.1 has no upper limit on the fanout.  Up to 1,024 the k smallest variates of a list are found among
     candidates kept in LDS; above that, lists longer than the fanout take the selection by bisection on the variate.  Hubs
