@@ -331,6 +331,10 @@ const char* coop_strerror(int code);
                                       are queued and taken by the first waves of the traversal, so that no hub starts late
                                       (default 2048, for passes over 32768 destinations or more; 0: never; other values,
                                       64..2^30, meant for tests, apply to every pass) */
+#define COOP_TUNE_SPLIT_MIN 10     /* LABOR-0: lists longer than this many entries are handed to the piece waves (in pieces of
+                                      about COOP_TUNE_PIECE_LEN entries, a single piece if they are shorter than that);
+                                      0 (default): twice the piece length with independent variates, 2048 with dependent
+                                      ones; otherwise 64..2^30 */
 int coop_tune(int knob, int64_t value);
 
 /* out[i] = in[i] for a device id list (a plain streaming copy on `stream`: 4n bytes read, 4n written).  Besides its

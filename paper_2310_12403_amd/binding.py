@@ -468,6 +468,7 @@ COOP_TUNE_DEFER_SIZES = 6
 COOP_TUNE_UNIQUE = 7
 COOP_TUNE_ENUM_DEGREE = 8
 COOP_TUNE_NS_LONG_LIST = 9
+COOP_TUNE_SPLIT_MIN = 10
 
 
 def coop_tune(knob, value):

@@ -263,7 +263,7 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
                                                      uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, Segment* __restrict__ seg,
                                                      uint32_t* __restrict__ thr, PreThr* __restrict__ pthr, float* __restrict__ lim2,
                                                      double cw, double sw, int queued, Ctl* ctl,
-                                                     uint32_t piece_len, Piece* __restrict__ pieces, uint32_t piece_cap,
+                                                     uint32_t piece_len, uint32_t split_min, Piece* __restrict__ pieces, uint32_t piece_cap,
                                                      uint32_t* __restrict__ piece_count, ScanOut out, uint32_t enum_degree,
                                                      uint32_t* __restrict__ long_bits, LongSlot* __restrict__ long_tab, uint32_t long_mask) {
   __shared__ uint32_t s_wave_at[kSegBlock / kWave];
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(kSegBlock) void k_segments(const int64_t* __restric
   // A long list is cut into pieces of about piece_len entries (equal lengths, multiples of 4), each scanned by a wave
   // of its own: the waves of the scan then all have about the same amount of work whatever the degree distribution.
   // The block reserves queue slots for all its long lists with one atomic; each wave then writes its pieces together.
-  uint32_t np = sampled && g.d > 2 * piece_len ? (g.d + piece_len - 1) / piece_len : 0u;
+  uint32_t np = sampled && g.d > split_min ? (g.d + piece_len - 1) / piece_len : 0u;
   if (np > (1u << 20)) np = 0;  // keeps the block's sum below 2^30 (only lists of 2^28 entries and more, at the smallest piece length)
   const uint32_t incl = wave_incl_scan(np);
   const uint32_t lane = (uint32_t)lane_id();
@@ -1070,11 +1070,17 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
   }
   // long lists are cut into pieces (k_segments queues them); room for every piece the graph's edges could make
   const uint32_t piece_len = cx.vec4 ? (uint32_t)g_piece_len : 0u;
+  // Lists longer than split_min go to the piece waves, which come first in the grid.  With independent variates that is
+  // for the lists worth cutting (twice the piece length).  The blended scan costs three times as much per entry, and a
+  // wave that meets a few lists of several thousand entries late in the kernel keeps it waiting: there every list above
+  // 2,048 entries goes first, whole if it is shorter than two pieces (papers100M-shaped, kappa 16: scan 1.44 -> 1.32 ms;
+  // no difference with independent variates).
+  const uint32_t split_min = g_split_min != 0 ? (uint32_t)g_split_min : (cx.blend && piece_len >= 2048u ? 2048u : 2u * piece_len);
   uint32_t piece_cap = 0;
   Piece* pieces = nullptr;
   if (piece_len != 0 && n_new > 0) {
     const int64_t by_edges = cx.g->n_edges / piece_len;
-    const int64_t long_lists = cx.g->n_edges / (2 * (int64_t)piece_len) + 1;
+    const int64_t long_lists = cx.g->n_edges / (int64_t)split_min + 1;
     const int64_t cap64 = by_edges + (n_new < long_lists ? n_new : long_lists) + 1;
     piece_cap = (uint32_t)(cap64 < ((int64_t)1 << 30) ? cap64 : ((int64_t)1 << 30));
     pieces = alloc.get<Piece>(piece_cap, COOP_TAG_SCRATCH);
@@ -1186,7 +1192,7 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       COOP_LAUNCH(K_SEGMENTS, k_segments, dim3(blocks_for(n_new, kSegBlock)), dim3(kSegBlock), 0, s, cx.g->indptr, cx.g->n_vertices,
                   dst + ps.start, n_new, ps.nf, ks[0], ks[1], ks[2], ks[3], ps.seg, ps.thr, pthr, lim2, cx.cw, cx.sw,
                   cx.blend && cx.vec4 ? 1 : 0, cx.d_ctl,
-                  piece_len, pieces, piece_cap, cx.d_piece_count + l, out, enum_degree, long_bits, long_tab, long_mask);
+                  piece_len, split_min, pieces, piece_cap, cx.d_piece_count + l, out, enum_degree, long_bits, long_tab, long_mask);
       if (enum_degree != 0) {
         if (list_todo != 0) {
           const unsigned list_blocks = blocks_for((int64_t)um_most + 1, kEnumListSpan);

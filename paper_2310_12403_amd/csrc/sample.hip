@@ -72,6 +72,7 @@ int g_stage_cap_override = 0;  // COOP_TUNE_STAGE_CAP
 int g_lists_per_wave = 0;      // COOP_TUNE_LISTS_PER_WAVE (0 = automatic)
 int g_fuse_layers = 1;         // COOP_TUNE_FUSE_LAYERS
 int g_piece_len = 4096;        // COOP_TUNE_PIECE_LEN
+int g_split_min = 0;           // COOP_TUNE_SPLIT_MIN (0 = twice the piece length)
 int64_t g_blend_candidates = 0;  // COOP_TUNE_BLEND_CANDIDATES (0 = automatic)
 int g_defer_sizes = 1;         // COOP_TUNE_DEFER_SIZES
 int g_enum_degree = 8192;      // COOP_TUNE_ENUM_DEGREE
@@ -119,6 +120,10 @@ extern "C" int coop_tune(int knob, int64_t value) {
     case COOP_TUNE_DEFER_SIZES:
       if (value < 0 || value > 2) return COOP_E_ARG;
       g_defer_sizes = (int)value;
+      return COOP_OK;
+    case COOP_TUNE_SPLIT_MIN:
+      if (value != 0 && (value < 64 || value > ((int64_t)1 << 30))) return COOP_E_ARG;
+      g_split_min = (int)value;
       return COOP_OK;
     case COOP_TUNE_NS_LONG_LIST:
       if (value != 0 && (value < 64 || value > ((int64_t)1 << 30))) return COOP_E_ARG;

@@ -80,6 +80,7 @@ extern int g_stage_cap_override;
 extern int g_lists_per_wave;
 extern int g_fuse_layers;
 extern int g_piece_len;
+extern int g_split_min;
 extern int64_t g_blend_candidates;
 extern int g_defer_sizes;
 extern int g_enum_degree;

@@ -375,6 +375,30 @@ def test_labor_long_lists_cut_into_pieces(P, tiny, medium, piece_len):
         P.coop_tune(P.COOP_TUNE_STAGE_CAP, 0)
 
 
+@pytest.mark.parametrize("split_min,piece_len", [(64, 4096), (200, 512), (1000, 256)])
+def test_labor_lists_handed_to_the_piece_waves_whole(P, tiny, medium, split_min, piece_len):
+    """Lists longer than COOP_TUNE_SPLIT_MIN go to the waves that come first in the scan's grid: as a single piece when they
+    are shorter than the piece length, in several otherwise (the default does this with dependent variates from 2,048
+    entries on).  Independent and dependent variates, both fusion modes; the bytes do not change."""
+    try:
+        P.coop_tune(P.COOP_TUNE_SPLIT_MIN, split_min)
+        P.coop_tune(P.COOP_TUNE_PIECE_LEN, piece_len)
+        hubs_m = np.argsort(-np.diff(medium.indptr_h))[:200].astype(np.int32)
+        seeds = synth.seed_batches(medium.n, 3000, seed=15)(1).numpy()
+        for mode in (1, 2):
+            P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, mode)
+            compare(P, medium, seeds, (10, 10, 10), R.LABOR0, it=5, kappa=16, seed=24)
+            compare(P, medium, seeds, (10, 10, 10), R.LABOR0, it=4, kappa=1, seed=24)
+            compare(P, medium, hubs_m, (25, 10), R.LABOR0, it=9, kappa=4, seed=25)
+            compare(P, tiny, synth.seed_batches(tiny.n, 1024, seed=0)(3).numpy(), (10, 10, 10), R.LABOR0, it=3, kappa=2, seed=26)
+    finally:
+        P.coop_tune(P.COOP_TUNE_SPLIT_MIN, 0)
+        P.coop_tune(P.COOP_TUNE_PIECE_LEN, 4096)
+        P.coop_tune(P.COOP_TUNE_FUSE_LAYERS, 1)
+    with pytest.raises(P.CoopError):
+        P.coop_tune(P.COOP_TUNE_SPLIT_MIN, 7)
+
+
 def test_cache_export_import_resumes_exactly(P):
     """A cache rebuilt from an export answers the following batches exactly as the original does."""
     n, dim = 4000, 32
