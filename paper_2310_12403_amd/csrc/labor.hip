@@ -152,13 +152,27 @@ __global__ __launch_bounds__(kListBlock) void k_enum_list(FusedKeys keys, uint32
 }
 
 // blockIdx.y = covered layer f: 16 lanes per item; a lane's four entries are requested together, and so are the table
-// slots of those that pass the bit test
+// slots of those that pass the bit test.
+// A kept edge costs a chain of three dependent memory operations (its reverse position, a returning atomic on its
+// destination's counter, the store into the staging row), and a step of 256 entries finds only a handful: committed on
+// the spot they would make the wave wait out that chain in every step with a few lanes at work.  So the kept edges of a
+// wave wait in a queue in LDS and are committed 64 at a time, every lane with a chain of its own, and once more when the
+// wave is through its items.
+struct WalkQueue {
+  uint32_t n;  // entries waiting (below 128; the same for every lane of the wave)
+  uint32_t list[2 * kWave];
+  int32_t t[2 * kWave];
+  uint32_t pos_lo[2 * kWave], pos_hi[2 * kWave];  // position of the entry in the graph's indices
+};
 __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __restrict__ g_indices, const uint32_t* __restrict__ rev_pos,
                                                           const uint32_t* __restrict__ long_bits, const LongSlot* __restrict__ long_tab,
                                                           uint32_t long_mask, uint32_t stage_cap, ScanOut out, EnumOut eo, Ctl* ctl) {
   __shared__ uint32_t bits[kLongBits / 32];
+  __shared__ WalkQueue queues[kWalkBlock / kWave];
   const int f = blockIdx.y;
   if (ctl->cand_overflow != 0) return;  // (some items were not written, or some destinations not entered: the pass is redone)
+  WalkQueue& wq = queues[threadIdx.x / kWave];
+  if ((threadIdx.x & (kWave - 1)) == 0) wq.n = 0;
   for (uint32_t i = threadIdx.x; i < kLongBits / 128; i += kWalkBlock)
     reinterpret_cast<uint4*>(bits)[i] = reinterpret_cast<const uint4*>(long_bits)[i];
   __syncthreads();
@@ -170,10 +184,26 @@ __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __re
   StageEntry* __restrict__ stage_f = f == 0 ? out.stage[0] : f == 1 ? out.stage[1] : f == 2 ? out.stage[2] : out.stage[3];
   const uint32_t sub = threadIdx.x & 15u;
   const uint32_t groups = (gridDim.x * kWalkBlock) >> 4;
-  // (the next item's record and entries are requested while the current one's table slots and commits are in flight)
+  // The first `n` queued edges (n <= 64), shared out among the lanes that are still here (the 16-lane groups of a wave
+  // run out of items at different times): reverse position, place in the row, store.
+  auto commit = [&](uint32_t n) {
+    const uint64_t here = ballot64(true);
+    const uint32_t n_here = (uint32_t)__popcll(here);
+    for (uint32_t i = lanes_below(here); i < n; i += n_here) {
+      const uint32_t list = wq.list[i];
+      const uint32_t j = rev_pos[((uint64_t)wq.pos_hi[i] << 32) | wq.pos_lo[i]];
+      const uint32_t at = (uint32_t)atomicAdd(&cnt_f[list], 1);
+      if (at < stage_cap) stage_f[(size_t)list * stage_cap + at] = StageEntry{wq.t[i], j};
+      else if (at == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
+    }
+  };
+  // (two items ahead: while the table slots of the current item are in flight, so are the entries of the next one and the
+  // record of the one after it)
   uint32_t c = (blockIdx.x * kWalkBlock + threadIdx.x) >> 4;
   if (c >= total) return;
   EnumItem it = item_f[c];
+  EnumItem it_next = it;
+  if (c + groups < total) it_next = item_f[c + groups];
   uint32_t s4[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -182,8 +212,6 @@ __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __re
   }
   for (;;) {
     const bool more = c + groups < total;
-    EnumItem it_next = it;
-    if (more) it_next = item_f[c + groups];
     uint32_t h4[4];
     bool maybe[4];
     uint4 head4[4];
@@ -196,10 +224,24 @@ __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __re
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       if (maybe[e]) head4[e] = *reinterpret_cast<const uint4*>(&long_tab[h4[e]]);
+    // The requests for the next rounds go out behind the table slots, not in front of them: loads come back in the
+    // order in which they were sent, and the slots (in L2) must not wait for these (in HBM).
+    asm volatile("" ::: "memory");
+    EnumItem it_next2 = it_next;
+    if ((uint64_t)c + 2ull * groups < total) it_next2 = item_f[c + 2u * groups];
+    uint32_t s4_next[4] = {0, 0, 0, 0};
+    if (more) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t j = (uint32_t)e * 16u + sub;
+        s4_next[e] = (uint32_t)g_indices[it_next.beg + (j < it_next.len ? j : it_next.len - 1)];
+      }
+    }
+    asm volatile("" ::: "memory");
     // Which entries are long destinations of this pass (the key in a slot is the vertex + 1, 0 an empty slot), and is
     // R_t within their threshold?  An entry whose home slot holds another key moves on to the next slot; the entries
     // of a lane do so together, a round of requests at a time.
-    uint32_t list4[4], j4[4], at4[4];
+    uint32_t list4[4];
     bool open4[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) open4[e] = maybe[e];
@@ -225,34 +267,53 @@ __global__ __launch_bounds__(kWalkBlock, 6) void k_enum_walk(const int32_t* __re
       for (int e = 0; e < 4; ++e)
         if (open4[e]) head4[e] = *reinterpret_cast<const uint4*>(&long_tab[h4[e]]);
     }
-    uint32_t s4_next[4] = {0, 0, 0, 0};
-    if (more) {
+    // kept edges t -> s join the wave's queue; a full wave of them is committed at once
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t j = (uint32_t)e * 16u + sub;
-        s4_next[e] = (uint32_t)g_indices[it_next.beg + (j < it_next.len ? j : it_next.len - 1)];
+    for (int e = 0; e < 4; ++e) {
+      const uint64_t mask = ballot64(maybe[e]);
+      if (mask == 0) continue;
+      uint32_t nq = wq.n;  // (below 64 here)
+      if (maybe[e]) {
+        const uint32_t at = nq + lanes_below(mask);
+        const uint64_t pos = (uint64_t)it.beg + (uint32_t)e * 16u + sub;
+        wq.list[at] = list4[e];
+        wq.t[at] = (int32_t)it.t;
+        wq.pos_lo[at] = (uint32_t)pos;
+        wq.pos_hi[at] = (uint32_t)(pos >> 32);
       }
+      nq += (uint32_t)__popcll(mask);
+      __builtin_amdgcn_wave_barrier();
+      if (nq >= (uint32_t)kWave) {
+        commit(kWave);
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t rest = nq - kWave;  // fewer than 64: to the front
+        const uint64_t here = ballot64(true);
+        const uint32_t n_here = (uint32_t)__popcll(here);
+        // (in rounds of the lanes that are here, each round read before it is written: a round only writes below what it read)
+        for (uint32_t first = 0; first < rest; first += n_here) {
+          const uint32_t i = first + lanes_below(here);
+          uint32_t ml = 0, mlo = 0, mhi = 0;
+          int32_t mt = 0;
+          if (i < rest) { ml = wq.list[kWave + i]; mt = wq.t[kWave + i]; mlo = wq.pos_lo[kWave + i]; mhi = wq.pos_hi[kWave + i]; }
+          __builtin_amdgcn_wave_barrier();
+          if (i < rest) { wq.list[i] = ml; wq.t[i] = mt; wq.pos_lo[i] = mlo; wq.pos_hi[i] = mhi; }
+          __builtin_amdgcn_wave_barrier();
+        }
+        nq = rest;
+      }
+      if (lanes_below(ballot64(true)) == 0) wq.n = nq;
+      __builtin_amdgcn_wave_barrier();
     }
-    // kept edges t -> s: their positions in the destinations' own lists and their places in the staging rows are
-    // requested together
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (maybe[e]) {
-        j4[e] = rev_pos[it.beg + (uint32_t)e * 16u + sub];
-        at4[e] = (uint32_t)atomicAdd(&cnt_f[list4[e]], 1);
-      }
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (maybe[e]) {
-        if (at4[e] < stage_cap) stage_f[(size_t)list4[e] * stage_cap + at4[e]] = StageEntry{(int32_t)it.t, j4[e]};
-        else if (at4[e] == stage_cap) atomicAdd(&ctl->n_overflow, 1);  // exactly one entry sees the row fill up
-      }
     if (!more) break;
     c += groups;
     it = it_next;
+    it_next = it_next2;
 #pragma unroll
     for (int e = 0; e < 4; ++e) s4[e] = s4_next[e];
   }
+  // what still waits, fewer than 64 (every lane that had an item arrives here, whenever its group ran out)
+  __builtin_amdgcn_wave_barrier();
+  commit(wq.n);
 }
 
 // list records of the destinations scanned in this pass, and their keep thresholds for the nf covered layers
