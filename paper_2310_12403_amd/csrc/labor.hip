@@ -533,6 +533,13 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
 #pragma unroll
   for (int gq = 0; gq < kScanGroups; ++gq) nbuf[gq] = i32x4{0, 0, 0, 0};
   if (vec_beg < vec_end) fetch(vec_beg);
+  // The ragged ends (lanes 0..2: the entries in front of the first whole group; lanes 3..5: those behind the last one)
+  // are requested right behind the first step, not when the whole groups are done: a list of one or two steps, and
+  // most lists are, then waits for memory once, not twice.
+  const uint32_t end_pos = lane < 3 ? head + lane : vec_end + (lane - 3);
+  const bool end_valid = lane < 3 ? (head != 0 && end_pos < 4 && end_pos < total) : (lane < 6 && end_pos < total && vec_end >= vec_beg);
+  int32_t end_t = 0;
+  if (end_valid) end_t = p[end_pos];
   for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
     i32x4 buf[kScanGroups];
     bool ok[kScanGroups];
@@ -568,17 +575,11 @@ __device__ __forceinline__ void labor_scan_fast(const int32_t* __restrict__ g_in
       }
     }
   }
-  {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
-    const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
-    const bool valid = lane < 3 ? (head != 0 && pos < 4 && pos < total) : (lane < 6 && pos < total && vec_end >= vec_beg);
-    int32_t t = 0;
-    if (valid) t = p[pos];
 #pragma unroll
-    for (int l = 0; l < NF; ++l) {
-      const bool fl = valid && variate<false, BLEND>(keys.K[l], keys.cw, keys.sw, (uint32_t)t, 0u, 0u) <= thr[l];
-      const uint64_t mm = ballot64(fl);
-      if (mm != 0) sink.take(l, mm, fl, t, (int32_t)(pos - head + j0), lane);
-    }
+  for (int l = 0; l < NF; ++l) {  // the ragged ends
+    const bool fl = end_valid && variate<false, BLEND>(keys.K[l], keys.cw, keys.sw, (uint32_t)end_t, 0u, 0u) <= thr[l];
+    const uint64_t mm = ballot64(fl);
+    if (mm != 0) sink.take(l, mm, fl, end_t, (int32_t)(end_pos - head + j0), lane);
   }
 }
 
@@ -737,6 +738,12 @@ __device__ __forceinline__ void labor_scan_blend(const int32_t* __restrict__ g_i
   const int32_t* __restrict__ p = g_indices + abeg;
   const uint32_t lane = (uint32_t)lane_id();
   const float cwf = (float)keys.cw, swf = (float)keys.sw;
+  // the ragged ends (lanes 0..2: the entries in front of the first whole group; lanes 3..5: those behind the last one) are
+  // requested now, so that a short list waits for memory once
+  const uint32_t end_pos = lane < 3 ? head + lane : vec_end + (lane - 3);
+  const bool end_valid = lane < 3 ? (head != 0 && end_pos < 4 && end_pos < total) : (lane < 6 && end_pos < total && vec_end >= vec_beg);
+  int32_t end_t = 0;
+  if (end_valid) end_t = p[end_pos];
 
   for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
     i32x4 buf[kScanGroups];
@@ -774,19 +781,13 @@ __device__ __forceinline__ void labor_scan_blend(const int32_t* __restrict__ g_i
       }
     }
   }
-  {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
-    const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
-    const bool valid = lane < 3 ? (head != 0 && pos < 4 && pos < total) : (lane < 6 && pos < total && vec_end >= vec_beg);
-    int32_t t = 0;
-    if (valid) t = p[pos];
 #pragma unroll
-    for (int l = 0; l < NF; ++l) {
-      const uint32_t a = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)t, 0u);
-      const uint32_t b = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)t, 0u);
-      const uint32_t lo = a < b ? a : b, hi = a < b ? b : a;
-      blend_first<NF>(st, l, valid && (lo <= pthr[l].a1 || (lo <= pthr[l].a2 && hi <= pthr[l].b2)), t, pos - head + j0, slot, lb, keys, cwf,
-                      swf, stage_cap, out, ctl);
-    }
+  for (int l = 0; l < NF; ++l) {  // the ragged ends
+    const uint32_t a = keyed_uniform<false>(keys.K[l].Ka, (uint32_t)end_t, 0u);
+    const uint32_t b = keyed_uniform<false>(keys.K[l].Kb, (uint32_t)end_t, 0u);
+    const uint32_t lo = a < b ? a : b, hi = a < b ? b : a;
+    blend_first<NF>(st, l, end_valid && (lo <= pthr[l].a1 || (lo <= pthr[l].a2 && hi <= pthr[l].b2)), end_t, end_pos - head + j0, slot, lb, keys,
+                    cwf, swf, stage_cap, out, ctl);
   }
 }
 

@@ -204,6 +204,12 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
     };
     // (not with c > 0: the blended path needs the registers more than the overlap)
     if (!BLEND && vec_beg < vec_end) fetch(vec_beg);
+    // the ragged ends (lanes 0..2: the entries in front of the first whole group; lanes 3..5: those behind the last one) are
+    // requested now, not when the whole groups are done, so that a short list waits for memory once
+    const uint32_t end_pos = lane < 3 ? head + lane : vec_end + (lane - 3);
+    const bool end_valid = lane < 3 ? (head != 0 && end_pos < 4) : (lane < 6 && end_pos < total);
+    int32_t end_t = 0;
+    if (end_valid) end_t = p[end_pos];
     for (uint32_t base = vec_beg; base < vec_end; base += kStep) {
       if (BLEND) fetch(base);
       i32x4 buf[kNsGroups];
@@ -235,14 +241,10 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
         group(gq, ok[gq]);
       }
     }
-    {  // lanes 0..2: the entries in front of the first whole group; lanes 3..5: the entries behind the last one
-      const uint32_t pos = lane < 3 ? head + lane : vec_end + (lane - 3);
-      const bool valid = lane < 3 ? (head != 0 && pos < 4) : (lane < 6 && pos < total);
-      int32_t t = 0;
-      if (valid) t = p[pos];
+    {  // the ragged ends
       uint32_t r = 0, u2 = 0;
-      const bool flag = first_look(valid, t, r, u2);
-      take(flag, t, pos - head, r, u2);
+      const bool flag = first_look(end_valid, end_t, r, u2);
+      take(flag, end_t, end_pos - head, r, u2);
     }
   }
   if constexpr (BLEND) {
