@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_count(const int64_t* __restrict__
   if (is_long) {
     uint32_t at = block_base + lanes_below(m);
     for (int w = 0; w < wib; ++w) at += wave_long[w];
-    long_list[at] = (uint32_t)i;  // (at < n_dst: every destination is queued at most once)
+    if ((int64_t)at < n_dst) long_list[at] = (uint32_t)i;  // (always: every destination is queued at most once; the queue has n_dst places)
   }
 }
 

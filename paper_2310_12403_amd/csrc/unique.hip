@@ -263,6 +263,9 @@ __global__ __launch_bounds__(kFirstBlock) void k_part_first(const unsigned long 
   if (threadIdx.x == 0) { n_claimed = 0; full = 0; }
   __syncthreads();
   constexpr int U = 4;  // pairs per thread and round, loaded together
+  unsigned long long first_round[U];  // the pairs of the first round, kept for the look-up phase
+#pragma unroll
+  for (int u = 0; u < U; ++u) first_round[u] = kEmptySlot;
   for (uint32_t base = lo; base < hi; base += U * kFirstBlock) {
     if (*(volatile uint32_t*)&full) break;
     unsigned long long mine[U];
@@ -270,6 +273,7 @@ __global__ __launch_bounds__(kFirstBlock) void k_part_first(const unsigned long 
     for (int u = 0; u < U; ++u) {
       const uint32_t i = base + u * kFirstBlock + threadIdx.x;
       mine[u] = i < hi ? pairs[i] : kEmptySlot;
+      if (base == lo) first_round[u] = mine[u];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -301,12 +305,13 @@ __global__ __launch_bounds__(kFirstBlock) void k_part_first(const unsigned long 
     if (threadIdx.x == 0) atomicOr(&ctl->uniq_overflow, 1);
     return;
   }
+  const bool one_round = hi - lo <= (uint32_t)(U * kFirstBlock);  // (the usual bucket: its pairs are still in the registers)
   for (uint32_t base = lo; base < hi; base += U * kFirstBlock) {
     unsigned long long mine[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t i = base + u * kFirstBlock + threadIdx.x;
-      mine[u] = i < hi ? pairs[i] : kEmptySlot;
+      mine[u] = one_round ? first_round[u] : (i < hi ? pairs[i] : kEmptySlot);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {

@@ -523,8 +523,11 @@ def test_ns_long_lists_taken_by_the_first_waves(P, tiny, medium, long_min):
         compare(P, medium, seeds[:400], (10, 5), R.NS, it=21, kappa=16, seed=31)    # (c = 5/16: the blended kernels)
         compare(P, medium, hubs, (1100, 2), R.NS, it=2, kappa=1, seed=32)
         compare(P, tiny, synth.seed_batches(tiny.n, 1024, seed=0)(2).numpy(), (10, 10, 10), R.NS, it=1, kappa=1, seed=33)
+        P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 2)      # every layer is run twice: the queue starts empty both times
+        compare(P, medium, seeds, (10, 10, 10), R.NS, it=3, kappa=1, seed=31)
     finally:
         P.coop_tune(P.COOP_TUNE_NS_LONG_LIST, 2048)
+        P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
     with pytest.raises(P.CoopError):
         P.coop_tune(P.COOP_TUNE_NS_LONG_LIST, 5)
 
