@@ -199,5 +199,16 @@ struct coop_graph {
   uint32_t* rev_pos;  // then: for the edge t -> s at position e of indices, the position of s in t's list (owned, device)
   int64_t long_mass;  // then: entries in lists longer than kLongListDegree
   bool own_rev;       // rev_pos was allocated by the library (hipMalloc) and is released by coop_graph_free
+  bool have_census = false;  // the graph was looked at when it was registered (COOP_VALIDATE or COOP_SYMMETRIC); then:
+  int64_t census[32] = {};   // census[k] = vertices whose list has at least 2^k and fewer than 2^(k+1) entries
+  // at most this many vertices have a list longer than `len` entries (len >= 1); n_vertices if the graph was not looked at
+  int64_t lists_longer_than(uint32_t len) const {
+    if (!have_census) return n_vertices;
+    int k = 0;
+    while (k < 31 && (2u << k) <= len) ++k;  // 2^k <= len < 2^(k+1): the counters from k on cover every list longer than len
+    int64_t n = 0;
+    for (; k < 32; ++k) n += census[k];
+    return n;
+  }
 };
 constexpr int64_t kLongListDegree = 8192;  // default of COOP_TUNE_ENUM_DEGREE

@@ -710,9 +710,11 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
     const size_t shmem = (size_t)wpb * cap * 16;
     const dim3 grid(blocks_for(n_dst, wpb));
 #define COOP_NS_ARGS cx.g->indices, rec, bthr, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, m, cx.d_ctl
-    // the queue's waves, one per queued list: as many as there can be lists that long (the unused ones end at once)
+    // the queue's waves, one per queued list: as many as there can be lists that long, by the degree census of the
+    // registration and by the number of edges (the unused ones end at once)
     int64_t most_long = cx.g->n_edges / (int64_t)(long_min ? long_min : 1) + 1;
     if (most_long > n_dst) most_long = n_dst;
+    if (long_min != 0 && most_long > cx.g->lists_longer_than(long_min)) most_long = cx.g->lists_longer_than(long_min);
     const int long_blocks = queue_long ? (int)blocks_for(most_long, wpb) : 0;
     const dim3 grid_q(grid.x + (unsigned)long_blocks);
     if (cx.blend) {

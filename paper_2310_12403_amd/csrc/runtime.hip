@@ -376,15 +376,31 @@ void scan_popc_to_u32(const uint64_t* bits, int64_t n_words, uint32_t* out, int6
 }
 
 // ---- CSR validation -------------------------------------------------------------------------------------------
+// Also a census of the degrees: census[k] = number of vertices whose list has 2^k entries or more but fewer than 2^(k+1)
+// (k = 0..31; lists of 2^31 entries and more in the last counter).  The samplers size the part of a grid that is set
+// aside for long lists from it.
 __global__ __launch_bounds__(kBlock) void k_validate_csr(const int64_t* __restrict__ indptr, const int32_t* __restrict__ indices,
-                                                         int64_t nv, int64_t ne, int32_t* __restrict__ bad) {
+                                                         int64_t nv, int64_t ne, int32_t* __restrict__ bad,
+                                                         unsigned long long* __restrict__ census) {
+  __shared__ uint32_t tally[32];
+  if (threadIdx.x < 32) tally[threadIdx.x] = 0;
+  __syncthreads();
   int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * kBlock;
   bool b = false;
-  for (int64_t v = i; v < nv; v += stride) b |= indptr[v] > indptr[v + 1];
+  for (int64_t v = i; v < nv; v += stride) {
+    const int64_t d = indptr[v + 1] - indptr[v];
+    b |= d < 0;
+    if (d > 0) {
+      const int k = 63 - __builtin_clzll((unsigned long long)d);
+      atomicAdd(&tally[k < 31 ? k : 31], 1u);
+    }
+  }
   for (int64_t e = i; e < ne; e += stride) b |= (uint32_t)indices[e] >= (uint64_t)nv;
   if (i == 0) b |= indptr[0] != 0 || indptr[nv] != ne;
   if (b) atomicOr(bad, 1);
+  __syncthreads();
+  if (threadIdx.x < 32 && tally[threadIdx.x] != 0) atomicAdd(&census[threadIdx.x], (unsigned long long)tally[threadIdx.x]);
 }
 
 // COOP_SYMMETRIC: checks that the lists are strictly ascending and that every edge t in N(s) has its reverse s in N(t),
@@ -461,12 +477,14 @@ int coop_graph_load_with(const int64_t* indptr, const int32_t* indices, int64_t 
   uint32_t* rev = nullptr;
   bool own_rev = false;  // the reverse index came from hipMalloc (no allocator given): coop_graph_free releases it
   int64_t long_mass = 0;
+  bool have_census = false;
+  int64_t census[32] = {};
   if (flags & (COOP_VALIDATE | COOP_SYMMETRIC)) {  // (the reverse index is built from offsets and ids that have been checked)
     hipStream_t s = (hipStream_t)stream;
-    struct Check { int32_t bad, pad; unsigned long long long_mass; };
+    struct Check { int32_t bad, pad; unsigned long long long_mass; unsigned long long census[32]; };
     Check* d_chk = nullptr;
     if (alloc) {
-      d_chk = (Check*)alloc(alloc_ctx, 256, COOP_TAG_SCRATCH);
+      d_chk = (Check*)alloc(alloc_ctx, (sizeof(Check) + 255) & ~(size_t)255, COOP_TAG_SCRATCH);
       if (!d_chk) return COOP_E_NOMEM;
       if ((flags & COOP_SYMMETRIC) && n_edges > 0) {
         rev = (uint32_t*)alloc(alloc_ctx, (((size_t)n_edges * sizeof(uint32_t)) + 255) & ~(size_t)255, COOP_TAG_GRAPH);
@@ -482,10 +500,11 @@ int coop_graph_load_with(const int64_t* indptr, const int32_t* indices, int64_t 
         own_rev = true;
       }
     }
-    Check h_chk{0, 0, 0};
+    Check h_chk{};
     hipError_t e = hipMemcpyAsync(d_chk, &h_chk, sizeof(Check), hipMemcpyHostToDevice, s);
     if (e == hipSuccess) {
-      COOP_LAUNCH(K_VALIDATE, k_validate_csr, dim3(256 * 16), dim3(kBlock), 0, s, indptr, indices, n_vertices, n_edges, &d_chk->bad);
+      COOP_LAUNCH(K_VALIDATE, k_validate_csr, dim3(256 * 16), dim3(kBlock), 0, s, indptr, indices, n_vertices, n_edges, &d_chk->bad,
+                  d_chk->census);
       if ((flags & COOP_SYMMETRIC) && n_vertices > 0 && n_edges > 0) {
         // (a grid holds fewer than 2^32 threads: the waves stride over the vertices)
         const int64_t want = (n_vertices * kWave + kBlock - 1) / kBlock;
@@ -502,12 +521,16 @@ int coop_graph_load_with(const int64_t* indptr, const int32_t* indices, int64_t 
       return e != hipSuccess ? COOP_E_HIP : COOP_E_GRAPH;
     }
     long_mass = (int64_t)h_chk.long_mass;
+    have_census = true;
+    for (int k = 0; k < 32; ++k) census[k] = (int64_t)h_chk.census[k];
   }
   coop_graph* g = new (std::nothrow) coop_graph{indptr, indices, n_vertices, n_edges, (flags & COOP_SYMMETRIC) != 0 && n_edges > 0, rev, long_mass, own_rev};
   if (!g) {
     if (own_rev) (void)hipFree(rev);
     return COOP_E_NOMEM;
   }
+  g->have_census = have_census;
+  for (int k = 0; k < 32; ++k) g->census[k] = census[k];
   *out = g;
   return COOP_OK;
 }
