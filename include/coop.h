@@ -160,7 +160,8 @@ int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, cons
  * U_c = mix(mix(c ^ K0) ^ K1 ^ mix(s ^ K2)) ^ K3; step i of walk w picks neighbour floor(U_{2(w o + i)} d / 2^32) of
  * its base vertex (d = that vertex's degree) and, for i >= 1, restarts iff U_{2(w o + i) + 1} < floor(restart_p 2^32).
  *
- *   walk_length >= 1, n_walks >= 1, walk_length * n_walks <= 1024, 0 <= restart_p <= 1 (else COOP_E_ARG)
+ *   walk_length >= 1, n_walks >= 1, walk_length * n_walks <= 2^20, 0 <= restart_p <= 1 (else COOP_E_ARG); with more than
+ *   1024 steps per destination the visit tallies live in device memory (a slower kernel)
  * Everything else (arguments, ownership, synchronisation, errors) is as for coop_sample.
  */
 int coop_sample_rw(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,

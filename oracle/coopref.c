@@ -525,7 +525,7 @@ int coopref_sample_rw(const int64_t* g_indptr, const int32_t* g_indices, int64_t
   if (!g_indptr || (!g_indices && n_edges > 0) || (!seeds && n_seeds > 0) || !fanouts || !blocks_out)
     return COOPREF_E_NULL;
   if (L < 1 || L > 255 || n_seeds < 0 || n_vertices < 0) return COOPREF_E_ARG;
-  if (walk_length < 1 || n_walks < 1 || (int64_t)walk_length * n_walks > 1024) return COOPREF_E_ARG;
+  if (walk_length < 1 || n_walks < 1 || (int64_t)walk_length * n_walks > ((int64_t)1 << 20)) return COOPREF_E_ARG;
   if (!(restart_p >= 0.0 && restart_p <= 1.0)) return COOPREF_E_ARG;
   for (int l = 0; l < L; ++l) if (fanouts[l] < 1) return COOPREF_E_ARG;
   memset(blocks_out, 0, sizeof(coopref_block) * (size_t)L);

@@ -275,7 +275,7 @@ extern "C" int coop_sample(const coop_graph* g, const int32_t* seeds, int64_t n_
 extern "C" int coop_sample_rw(const coop_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int L,
                               int32_t walk_length, int32_t n_walks, double restart_p, uint64_t iter, uint64_t seed,
                               coop_alloc_fn alloc_fn, void* alloc_ctx, void* stream, coop_block* blocks_out) {
-  if (walk_length < 1 || n_walks < 1 || (int64_t)walk_length * n_walks > 1024) return COOP_E_ARG;
+  if (walk_length < 1 || n_walks < 1 || (int64_t)walk_length * n_walks > ((int64_t)1 << 20)) return COOP_E_ARG;
   if (!(restart_p >= 0.0 && restart_p <= 1.0)) return COOP_E_ARG;
   RwConfig rw{};
   rw.walk_length = walk_length;

@@ -475,9 +475,22 @@ def test_random_walk_sampler_medium_and_degenerate(P, tiny, medium):
     assert all(torch.equal(x, y.col_global) for x, y in zip(first, b))
 
 
+@pytest.mark.parametrize("o,a,p", [(33, 32, 0.5), (3, 600, 0.3), (1500, 1, 0.0), (40, 40, 0.9)])
+def test_random_walks_with_more_than_1024_steps(P, tiny, medium, o, a, p):
+    """App. A.1.3 puts no bound on the number of walks or their length.  Above 1,024 steps per destination the visit
+    tallies live in device memory (a kernel of its own): fanouts below, around and above the number of distinct vertices
+    a destination reaches, a second layer on top, hubs and isolated vertices among the destinations."""
+    seeds = synth.seed_batches(tiny.n, 96, seed=61)(0).numpy()
+    compare_rw(P, tiny, seeds, (10, 5), o, a, p, it=2, seed=41)
+    compare_rw(P, tiny, seeds[:24], (300,), o, a, p, it=3, seed=41)
+    compare_rw(P, tiny, seeds[:8], (1 << 20,), o, a, p, it=4, seed=41)
+    hubs = np.argsort(-np.diff(medium.indptr_h))[:12].astype(np.int32)
+    compare_rw(P, medium, hubs, (25, 3), o, a, p, it=5, seed=42)
+
+
 def test_random_walk_sampler_errors(P, tiny):
     seeds = torch.arange(4, dtype=torch.int32).cuda()
-    for bad in ((0, 10, 0.5), (3, 0, 0.5), (3, 10, 1.5), (3, 10, -0.1), (33, 32, 0.5), (3, 10, float("nan"))):
+    for bad in ((0, 10, 0.5), (3, 0, 0.5), (3, 10, 1.5), (3, 10, -0.1), (1 << 11, 1 << 10, 0.5), (3, 10, float("nan"))):
         with pytest.raises(P.CoopError) as e:
             P.coop_sample_rw(tiny.graph, seeds, (5,), *bad)
         assert e.value.code == -4
