@@ -593,7 +593,8 @@ def brute_rw(indptr, indices, seeds, fanouts, o, a, p, seed, it):
     return out
 
 
-@pytest.mark.parametrize("o,a,p,fanouts", [(3, 100, 0.5, (10, 10)), (1, 7, 0.0, (3,)), (4, 20, 0.25, (5, 2, 4)), (2, 50, 1.0, (8,))])
+@pytest.mark.parametrize("o,a,p,fanouts", [(3, 100, 0.5, (10, 10)), (1, 7, 0.0, (3,)), (4, 20, 0.25, (5, 2, 4)), (2, 50, 1.0, (8,)),
+                                            (33, 32, 0.5, (6, 3)), (3, 600, 0.3, (40,))])   # (the last two: more than 1,024 steps per destination)
 def test_rw_equals_brute_force(o, a, p, fanouts):
     indptr, indices = small_graph()
     seeds = np.array([5, 0, 17, 33, 60, 2], dtype=np.int32)
@@ -693,7 +694,7 @@ def test_rw_restart_probability_and_first_step():
 def test_rw_error_codes_and_kappa_free(tiny):
     indptr, indices = tiny
     seeds = np.array([1, 2, 3], dtype=np.int32)
-    for bad in ((0, 10, 0.5), (3, 0, 0.5), (3, 10, 1.5), (3, 10, -0.1), (33, 32, 0.5)):
+    for bad in ((0, 10, 0.5), (3, 0, 0.5), (3, 10, 1.5), (3, 10, -0.1), (1 << 11, 1 << 10, 0.5)):
         with pytest.raises(R.OracleError) as e:
             R.sample(indptr, indices, seeds, (5,), R.RW, rw=bad)
         assert e.value.code == R.E_ARG
