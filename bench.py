@@ -238,8 +238,8 @@ def main():
         roofline = dict(bound="hbm", kernel=dominant, achieved=alg_dom / (avg_dom_ms * 1e-3) / 1e9, peak=HBM_PEAK / 1e9,
                         unit="GB/s")
         # Beside it: the count stage as a whole (the scan and, on a symmetric graph, the two kernels that stand in for the
-        # scan of the longest lists) against the bytes of a scan that reads every list once, the survey's algorithmic
-        # figure for this stage.  Times from the per-kernel pass (HIP events around every launch).
+        # scan of the longest lists) against the bytes of a scan that reads every list once (4 bytes per neighbour of
+        # every destination of the last layer).  Times from the per-kernel pass (HIP events around every launch).
         stage_ms = sum(breakdown.get(k, 0.0) for k in ("labor_scan", "enum_list", "enum_walk"))
         count_stage = dict(kernels=[k for k in ("labor_scan", "enum_list", "enum_walk") if k in breakdown], ms_per_step=round(stage_ms, 4),
                            bytes_every_list_once=per_step_every_list,
@@ -289,13 +289,13 @@ def main():
                             "n_src": [b.n_src for b in blocks]},
         "per_kernel_ms_per_step": breakdown,
         "gather_GBps": round((2 * row_bytes) * (stats["n_in"] / K) / (breakdown.get("gather", float("nan")) * 1e-3) / 1e9, 1),
-        # two views of the whole step.  "survey" = the per-layer algorithmic bytes of the scope table (every list of S^l
-        # charged at every layer l: what a layer-by-layer sampler must move), divided by the step time: an EFFECTIVE rate,
+        # two views of the whole step.  "layerwise" = the algorithmic bytes of a sampler that works layer by layer (every
+        # list of S^l charged at every layer l), divided by the step time: an EFFECTIVE rate,
         # which the fused scan and the lists served from the neighbours' side undercut.  "measured" = HBM bytes actually
         # moved by all kernels of a step (rocprofv3 FETCH_SIZE / WRITE_SIZE summary under profiles/), divided by the same
         # step time: the achieved bandwidth.
-        "step_survey_bytes": alg_sample + alg_gather,
-        "step_hbm_frac_effective_survey_bytes": round(step_frac, 4),
+        "step_layerwise_bytes": alg_sample + alg_gather,
+        "step_hbm_frac_effective_layerwise_bytes": round(step_frac, 4),
         "step_traffic_bytes": step_traffic,
         "step_hbm_frac_measured": None if step_traffic is None else round(step_traffic / (ms_per_step * 1e-3) / HBM_PEAK, 4),
         "roofline": roofline,
