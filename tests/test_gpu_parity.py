@@ -656,17 +656,19 @@ def test_frontier_dedup_modes(P, tiny, medium, mode):
         P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
 
 
-def test_randomized_configurations(P, draw_seed=20240, cases=160):
+def test_randomized_configurations(P, draw_seed=20240, cases=400):
     """Seeded random draws of graph shape, batch, depth, fanouts, sampler, iteration / kappa and of the library's
-    internal modes (piece length, layer fusion, staging rows, read-back mode, dedup mode, lists per wave; every other
+    internal modes (piece length, layer fusion, staging rows, read-back mode, dedup mode, lists per wave, the lengths from
+    which NS queues a list and LABOR-0 hands it to the piece waves; every other
     graph registered as symmetric, with a random degree above which LABOR-0 works from the neighbours' side), every
     output against the oracle: the code paths meet here in combinations that no other test spells out."""
     rng = np.random.default_rng(draw_seed)
     rng2 = np.random.default_rng(draw_seed + 1)
+    rng3 = np.random.default_rng(draw_seed + 2)
     fan_choices = (1, 2, 3, 5, 10, 25, 64, 65, 300)
     knobs = (P.COOP_TUNE_PIECE_LEN, P.COOP_TUNE_FUSE_LAYERS, P.COOP_TUNE_STAGE_CAP, P.COOP_TUNE_DEFER_SIZES, P.COOP_TUNE_UNIQUE,
-             P.COOP_TUNE_LISTS_PER_WAVE, P.COOP_TUNE_ENUM_DEGREE)
-    defaults = (4096, 1, 0, 1, 0, 0, 8192)
+             P.COOP_TUNE_LISTS_PER_WAVE, P.COOP_TUNE_ENUM_DEGREE, P.COOP_TUNE_NS_LONG_LIST, P.COOP_TUNE_SPLIT_MIN)
+    defaults = (4096, 1, 0, 1, 0, 0, 8192, 2048, 0)
     graphs = []
     for gi in range(6):
         n = int(rng.choice((60, 900, 7000, 30000)))
@@ -686,7 +688,7 @@ def test_randomized_configurations(P, draw_seed=20240, cases=160):
             sd = int(rng.integers(1 << 30))
             values = (int(rng.choice((0, 256, 512, 4096))), int(rng.integers(0, 3)), int(rng.choice((0, 0, 4, 32))),
                       int(rng.integers(0, 3)), int(rng.integers(0, 4)), int(rng.choice((0, 0, 1, 3, 8))),
-                      int(rng2.choice((0, 64, 64, 150, 1000, 8192))))
+                      int(rng2.choice((0, 64, 64, 150, 1000, 8192))), int(rng3.choice((2048, 0, 64, 200))), int(rng3.choice((0, 0, 64, 700))))
             for kn, v in zip(knobs, values):
                 P.coop_tune(kn, v)
             label = (case, g.n, fanouts, b, sampler, kappa, it, values)
