@@ -45,6 +45,8 @@ struct CacheCtl {
 __global__ __launch_bounds__(kBlock) void k_cache_lookup(const int32_t* __restrict__ ids, int64_t n_ids, int64_t n_vertices,
                                                          const int32_t* __restrict__ slot_of, int32_t* __restrict__ slot_i,
                                                          uint64_t* __restrict__ hit_bits, CacheCtl* ctl) {
+  // (several ids per thread do not make this faster: the scattered reads of slot_of, a table of one word per vertex of
+  // the graph, are what it waits for, not their latency)
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   bool hit = false;
   if (i < n_ids) {
@@ -102,7 +104,6 @@ __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ row
       const OrderEntry e = order[r];
       src[u] = e.from;
       dst[u] = e.i;
-      if (sub == 0) stamp[e.from] = clock + (uint64_t)r;
     }
   }
   for (int32_t v = sub; v < vecs; v += lpr) {
@@ -113,6 +114,13 @@ __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ row
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u)
       if (src[u] >= 0) __builtin_nontemporal_store(x[u], out + dst[u] * vecs + v);
+  }
+  // the new stamps go out behind the rows: memory operations complete in the order in which they were sent, and the row
+  // loads must not wait for these scattered stores
+  if (sub == 0) {
+#pragma unroll
+    for (int u = 0; u < kRowUnroll; ++u)
+      if (src[u] >= 0) stamp[src[u]] = clock + (uint64_t)(row0 + (int64_t)u * rows_per_block);
   }
 }
 
@@ -129,28 +137,23 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
   const int sub = threadIdx.x & (lpr - 1);
   const int64_t row0 = ((int64_t)blockIdx.x * kRowUnroll) * rows_per_block + (threadIdx.x >> lpr_log2);
   int64_t src[kRowUnroll], dst[kRowUnroll], dst_slot[kRowUnroll];
+  int32_t src_id[kRowUnroll];  // the vertex itself (src is its row in the table, which may be aliased)
 #pragma unroll
   for (int u = 0; u < kRowUnroll; ++u) {
     const int64_t rank_m = row0 + (int64_t)u * rows_per_block;  // rank_m-th miss
     src[u] = -1;
     dst[u] = 0;
     dst_slot[u] = -1;
+    src_id[u] = 0;
     if (rank_m < n_miss) {
       const OrderEntry e = order[n_ids - 1 - rank_m];
       const int32_t i = e.i, id = e.from;
       if (id >= 0) {  // ids out of range were reported by the lookup; negative ones are skipped here
         src[u] = id < table_rows ? id : id % table_rows;
+        src_id[u] = id;
         dst[u] = i;
         const int64_t q = rank_m - (n_miss - n_ins);  // the last n_ins misses enter the cache
-        if (q >= 0) {
-          const int32_t slot = free_list[n_free - 1 - q];
-          dst_slot[u] = slot;
-          if (sub == 0) {  // (a kernel of its own for these three stores costs more than it takes off this one)
-            slot_of[id] = slot;
-            vertex_of[slot] = id;
-            stamp[slot] = clock_miss + (uint64_t)rank_m;
-          }
-        }
+        if (q >= 0) dst_slot[u] = free_list[n_free - 1 - q];
       }
     }
   }
@@ -166,6 +169,17 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
         if (dst_slot[u] >= 0) __builtin_nontemporal_store(x[u], rows + dst_slot[u] * vecs + v);  // (not read again before a later call)
       }
     }
+  }
+  // the books of the rows that entered the cache, behind the row traffic (see k_cache_hits; a kernel of its own for these
+  // three stores costs more than it takes off this one)
+  if (sub == 0) {
+#pragma unroll
+    for (int u = 0; u < kRowUnroll; ++u)
+      if (dst_slot[u] >= 0) {
+        slot_of[src_id[u]] = (int32_t)dst_slot[u];
+        vertex_of[dst_slot[u]] = src_id[u];
+        stamp[dst_slot[u]] = clock_miss + (uint64_t)(row0 + (int64_t)u * rows_per_block);
+      }
   }
 }
 
