@@ -72,13 +72,19 @@ struct OrderEntry {
 };
 __global__ __launch_bounds__(kBlock) void k_cache_split(const uint64_t* __restrict__ hit_bits, const uint32_t* __restrict__ word_rank,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ slot_i,
-                                                        int64_t n_ids, OrderEntry* __restrict__ order) {
+                                                        int64_t n_ids, OrderEntry* __restrict__ order,
+                                                        uint64_t* __restrict__ stamp, uint64_t clock) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_ids) return;
   const uint64_t word = hit_bits[i >> 6];
   const int64_t h = (int64_t)word_rank[i >> 6] + __popcll(word & ((1ull << (i & 63)) - 1ull));
-  if ((word >> (i & 63)) & 1ull) order[h] = OrderEntry{(int32_t)i, slot_i[i]};
-  else order[n_ids - 1 - (i - h)] = OrderEntry{(int32_t)i, ids[i]};
+  if ((word >> (i & 63)) & 1ull) {
+    const int32_t slot = slot_i[i];
+    order[h] = OrderEntry{(int32_t)i, slot};
+    stamp[slot] = clock + (uint64_t)h;  // the h-th hit of the call; set here so that the eviction need not wait for the hit rows
+  } else {
+    order[n_ids - 1 - (i - h)] = OrderEntry{(int32_t)i, ids[i]};
+  }
 }
 
 // ---- row movers -----------------------------------------------------------------------------------------------
@@ -86,8 +92,7 @@ __global__ __launch_bounds__(kBlock) void k_cache_split(const uint64_t* __restri
 template <typename V>
 __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ rows, int32_t vecs, int lpr_log2,
                                                        const OrderEntry* __restrict__ order,
-                                                       const CacheCtl* __restrict__ ctl, V* __restrict__ out,
-                                                       uint64_t* __restrict__ stamp, uint64_t clock) {
+                                                       const CacheCtl* __restrict__ ctl, V* __restrict__ out) {
   const int64_t n_hit = ctl->n_hit;  // known on the device before the host has read it
   const int lpr = 1 << lpr_log2;
   const int rows_per_block = kBlock >> lpr_log2;
@@ -114,13 +119,6 @@ __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ row
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u)
       if (src[u] >= 0) __builtin_nontemporal_store(x[u], out + dst[u] * vecs + v);
-  }
-  // the new stamps go out behind the rows: memory operations complete in the order in which they were sent, and the row
-  // loads must not wait for these scattered stores
-  if (sub == 0) {
-#pragma unroll
-    for (int u = 0; u < kRowUnroll; ++u)
-      if (src[u] >= 0) stamp[src[u]] = clock + (uint64_t)(row0 + (int64_t)u * rows_per_block);
   }
 }
 
@@ -170,8 +168,9 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
       }
     }
   }
-  // the books of the rows that entered the cache, behind the row traffic (see k_cache_hits; a kernel of its own for these
-  // three stores costs more than it takes off this one)
+  // the books of the rows that entered the cache, behind the row traffic: memory operations complete in the order in which
+  // they were sent, and the row loads must not wait for these scattered stores (a kernel of its own for them costs more
+  // than it takes off this one)
   if (sub == 0) {
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u)
@@ -346,12 +345,35 @@ struct coop_cache {
   void* scan_tmp;
   uint32_t* hist;
   CacheCtl* d_ctl;
-  CacheCtl* h_ctl;        // pinned
+  CacheCtl* h_ctl;        // pinned, two of them: [0] the counts of the call under way, [1] the threshold of the last eviction
+  hipStream_t aux;        // the hit rows move on this stream while the eviction runs on the caller's
+  hipEvent_t ev_counts;   // counts of the call have landed in h_ctl[0]
+  hipEvent_t ev_hits;     // hit rows of the call are in `out`
+  hipEvent_t ev_threshold;  // threshold of the last eviction has landed in h_ctl[1]
+  bool base_pending;      // ... and has not been added to base yet
   // host-side state
   int64_t size;           // entries held
   uint64_t clock;         // next stamp
   uint64_t base;          // every live stamp is >= base (last eviction threshold + 1)
 };
+
+// Pinned memory, stream and events of a cache; whatever was created is released.
+static void release_host_side(coop_cache* c) {
+  if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
+  if (c->ev_threshold) { (void)hipEventSynchronize(c->ev_threshold); (void)hipEventDestroy(c->ev_threshold); }
+  if (c->ev_counts) (void)hipEventDestroy(c->ev_counts);
+  if (c->ev_hits) (void)hipEventDestroy(c->ev_hits);
+  if (c->h_ctl) (void)hipHostFree(c->h_ctl);
+}
+
+// The threshold of the last eviction, once it has arrived: everything at or below it is gone.
+static int settle_base(coop_cache* c) {
+  if (!c->base_pending) return COOP_OK;
+  COOP_HIP_TRY(hipEventSynchronize(c->ev_threshold));
+  c->base += c->h_ctl[1].prefix + 1;
+  c->base_pending = false;
+  return COOP_OK;
+}
 
 static unsigned grid_for(int64_t n) {
   int64_t b = (n + kBlock - 1) / kBlock;
@@ -387,7 +409,15 @@ extern "C" int coop_cache_create(int64_t capacity_rows, int64_t n_vertices, int3
   c->hist = alloc.get<uint32_t>(kSelBins, COOP_TAG_OUTPUT);
   c->d_ctl = alloc.get<CacheCtl>(1, COOP_TAG_OUTPUT);
   if (alloc.failed) { delete c; return COOP_E_NOMEM; }
-  if (hipHostMalloc((void**)&c->h_ctl, sizeof(CacheCtl), hipHostMallocDefault) != hipSuccess) { delete c; return COOP_E_HIP; }
+  if (hipHostMalloc((void**)&c->h_ctl, 2 * sizeof(CacheCtl), hipHostMallocDefault) != hipSuccess ||
+      hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) != hipSuccess ||  // (default priority)
+      hipEventCreateWithFlags(&c->ev_counts, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_hits, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_threshold, hipEventDisableTiming) != hipSuccess) {
+    release_host_side(c);
+    delete c;
+    return COOP_E_HIP;
+  }
   c->size = 0; c->clock = 1; c->base = 1;
   if (n_vertices > 0) COOP_LAUNCH(K_FILL, k_fill_i32, dim3(grid_for(n_vertices)), dim3(kBlock), 0, s, c->slot_of, n_vertices, -1, false);
   if (capacity_rows > 0) {
@@ -398,14 +428,14 @@ extern "C" int coop_cache_create(int64_t capacity_rows, int64_t n_vertices, int3
   fill_u64((uint64_t*)c->hist, kSelBins / 2, 0, s);
   COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)0);
   COOP_LAUNCH(K_FILL, k_cache_clear_err, dim3(1), dim3(1), 0, s, c->d_ctl);
-  if (hipStreamSynchronize(s) != hipSuccess) { (void)hipHostFree(c->h_ctl); delete c; return COOP_E_HIP; }
+  if (hipStreamSynchronize(s) != hipSuccess) { release_host_side(c); delete c; return COOP_E_HIP; }
   *out = c;
   return COOP_OK;
 }
 
 extern "C" int coop_cache_free(coop_cache* c) {
   if (!c) return COOP_OK;
-  (void)hipHostFree(c->h_ctl);
+  release_host_side(c);
   delete c;
   return COOP_OK;
 }
@@ -476,6 +506,7 @@ extern "C" int coop_cache_export(coop_cache* c, int32_t* vertices_out, uint64_t*
     COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_export, dim3((unsigned)((c->capacity + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, c->vertex_of,
                 c->stamp, c->capacity, vertices_out, stamps_out, c->d_ctl);
   COOP_HIP_TRY(hipStreamSynchronize(s));
+  if (int rc = settle_base(c)) return rc;
   state_out->size = c->size;
   state_out->clock = c->clock;
   state_out->base = c->base;
@@ -488,6 +519,7 @@ extern "C" int coop_cache_import(coop_cache* c, const void* table, int64_t table
   if (state->size < 0 || state->size > c->capacity || table_rows < 1 || state->clock == 0 || state->base == 0) return COOP_E_ARG;
   if (state->size > 0 && (!table || !vertices || !stamps)) return COOP_E_NULL;
   hipStream_t s = (hipStream_t)stream;
+  if (int rc = settle_base(c)) return rc;
   // back to the empty state (n_live slots reserved at the front), then the listed entries into slots 0 .. size-1
   auto reset = [&](int64_t n_live) {
     if (c->n_vertices > 0) COOP_LAUNCH(K_FILL, k_fill_i32, dim3(grid_for(c->n_vertices)), dim3(kBlock), 0, s, c->slot_of, c->n_vertices, -1, false);
@@ -560,7 +592,7 @@ void launch_rows(coop_cache* c, const void* table, int64_t table_rows, const int
   const unsigned grid = (unsigned)((n_ids + rows_per_launch_block - 1) / rows_per_launch_block);
   if (hits) {
     COOP_LAUNCH(K_CACHE_GATHER, k_cache_hits<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)c->rows, vecs, lpr_log2, (const OrderEntry*)c->order,
-                c->d_ctl, (V*)out, c->stamp, c->clock);
+                c->d_ctl, (V*)out);
   } else {
     const unsigned grid_m = (unsigned)((n_miss + rows_per_launch_block - 1) / rows_per_launch_block);
     COOP_LAUNCH(K_CACHE_UPDATE, k_cache_misses<V>, dim3(grid_m), dim3(kBlock), 0, s, (const V*)table, vecs, lpr_log2, (const OrderEntry*)c->order, n_ids,
@@ -593,25 +625,34 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
   const int vec_bytes = align % 16 == 0 ? 16 : align % 8 == 0 ? 8 : align % 4 == 0 ? 4 : 2;
   if (align % 2 != 0) return COOP_E_ARG;
 
-  // 1. lookup, hit ranks
+  // (a call on another stream than the last one's: the threshold of that one is still to be copied out of the control block)
+  if (c->base_pending) COOP_HIP_TRY(hipStreamWaitEvent(s, c->ev_threshold, 0));
+  // 1. lookup, hit ranks, new stamps of the hits
   COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)0);
   COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_lookup, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, ids, n_ids,
               c->n_vertices, c->slot_of, c->slot_i, c->hit_bits, c->d_ctl);
   scan_popc_to_u32(c->hit_bits, (n_ids + 63) / 64, c->rank_h, &c->d_ctl->n_hit, c->scan_tmp, s);
   COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_split, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, (const uint64_t*)c->hit_bits,
-              (const uint32_t*)c->rank_h, ids, (const int32_t*)c->slot_i, n_ids, c->order);
-  COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
-  // 2. hits: rows out of the cache, new stamps (runs while the host waits for the counts)
-  dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, 0, 0, 0, 0, true, s);
-  COOP_HIP_TRY(hipStreamSynchronize(s));
-  if (c->h_ctl->err_range) {
+              (const uint32_t*)c->rank_h, ids, (const int32_t*)c->slot_i, n_ids, c->order, c->stamp, c->clock);
+  COOP_HIP_TRY(hipMemcpyAsync(&c->h_ctl[0], c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
+  COOP_HIP_TRY(hipEventRecord(c->ev_counts, s));
+  // 2. hits: rows out of the cache, on the second stream: they touch nothing that the eviction or the miss rows write
+  //    (a slot that was hit carries the newest stamps and is not evicted, except when everything is: see below), so they
+  //    run beside the select passes and the sweep, which leave most of the chip idle
+  COOP_HIP_TRY(hipStreamWaitEvent(c->aux, c->ev_counts, 0));
+  dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, 0, 0, 0, 0, true, c->aux);
+  COOP_HIP_TRY(hipEventRecord(c->ev_hits, c->aux));
+  COOP_HIP_TRY(hipEventSynchronize(c->ev_counts));
+  if (int rc = settle_base(c)) return rc;
+  if (c->h_ctl[0].err_range) {
     // the cached ids of this call were already served and re-stamped: keep the stamps unique, insert nothing
     COOP_LAUNCH(K_FILL, k_cache_clear_err, dim3(1), dim3(1), 0, s, c->d_ctl);
     c->clock += (uint64_t)n_ids;
+    (void)hipStreamWaitEvent(s, c->ev_hits, 0);
     (void)hipStreamSynchronize(s);
     return COOP_E_RANGE;
   }
-  const int64_t n_hit = c->h_ctl->n_hit;
+  const int64_t n_hit = c->h_ctl[0].n_hit;
   const int64_t n_miss = n_ids - n_hit;
   const int64_t n_ins = n_miss < c->capacity ? n_miss : c->capacity;
   int64_t n_evict = c->size + n_ins - c->capacity;
@@ -623,6 +664,7 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
   bool threshold_known = false;
   if (n_evict > 0) {
     const bool evict_all = n_evict >= c->size;
+    if (evict_all) COOP_HIP_TRY(hipStreamWaitEvent(s, c->ev_hits, 0));  // the hit slots are given away as well: after their rows are out
     if (!evict_all) {
       uint64_t range = clock_after - c->base;  // live stamps minus base lie in [0, range)
       int nbits = 1;
@@ -660,11 +702,12 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
   c->size += n_ins;
   c->clock = clock_after;
 
-  if (threshold_known) {
-    COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
-    COOP_HIP_TRY(hipStreamSynchronize(s));
-    c->base += c->h_ctl->prefix + 1;  // everything at or below the threshold is gone
+  if (threshold_known) {  // read when it is next needed: the call does not wait for its own row copies
+    COOP_HIP_TRY(hipMemcpyAsync(&c->h_ctl[1], c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
+    COOP_HIP_TRY(hipEventRecord(c->ev_threshold, s));
+    c->base_pending = true;
   }
+  COOP_HIP_TRY(hipStreamWaitEvent(s, c->ev_hits, 0));  // work behind this call on the caller's stream sees all of `out`
   if (n_miss_out) *n_miss_out = n_miss;
   return COOP_OK;
 }

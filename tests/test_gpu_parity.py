@@ -263,6 +263,40 @@ def test_cache_on_sampled_batches_with_kappa(P, medium):
     assert totals[16] < totals[1]
 
 
+def test_cache_on_a_side_stream_without_host_waits(P):
+    """The hit rows move on a stream of the cache's own and the eviction threshold is read back one call late: work
+    queued behind a call on the caller's stream must still see all of `out`, and a sequence of calls with no host
+    synchronisation between them must keep the textbook LRU's books (also across an export, which needs the threshold
+    of the call before it)."""
+    n, dim, cap = 6000, 64, 1500
+    rng = np.random.default_rng(77)
+    feat = synth.features(n, dim, torch.float16, seed=6, device="cpu")
+    table = feat.cuda()
+    batches = [rng.choice(n, int(rng.integers(200, 1400)), replace=False).astype(np.int32) for _ in range(20)]
+    cache = P.Cache(cap, n, dim, torch.float16, 1500)
+    oracle = R.Cache(cap, n)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    copies, misses, keep = [], [], []
+    for ids in batches:
+        t = torch.from_numpy(ids).cuda()
+        keep.append(t)
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            out, n_miss = cache.gather(table, t, stream=side)
+            copies.append(out.clone())          # queued on the side stream right behind the call
+        misses.append(n_miss)
+    _, _, state = cache.export_state(stream=side)
+    side.synchronize()
+    for it, (ids, got, n_miss) in enumerate(zip(batches, copies, misses)):
+        want_miss, _ = oracle.access(ids)
+        assert n_miss == want_miss, it
+        assert got.cpu().numpy().tobytes() == R.gather(feat.numpy(), ids).tobytes(), it
+    held = cache.vertices().cpu().numpy()
+    assert len(held) == oracle.size() == state[0] and all(oracle.contains(int(v)) for v in held)
+    cache.close()
+
+
 def test_cache_errors(P):
     cache = P.Cache(10, 100, 8, torch.float32, 50)
     table = synth.features(100, 8, torch.float32, seed=1).cuda()
