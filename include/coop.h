@@ -263,11 +263,10 @@ int coop_cache_free(coop_cache* c);
  *              (else COOP_E_CAPACITY)
  *   out        device [n_ids, dim]
  *   n_miss_out host, number of ids that were not cached when the call started (may be NULL)
- * Returns once the hit / miss counts are known (the host waits for that much of `stream`); the eviction and the row
- * copies may still be running when it returns.  The hit rows are moved on a second stream that the cache owns, beside
- * the eviction; `stream` is made to wait for them before the call returns, so work queued on `stream` afterwards sees
- * all of `out`, and a host that wants `out` synchronises `stream`.  Calls on one cache must not overlap, and follow
- * one another on one stream or are ordered by the caller.  After COOP_E_RANGE the in-range cached ids of the
+ * Returns once the hit / miss counts are known (the host waits for that much of `stream`, no more); the eviction and
+ * the copies of the miss rows are queued on `stream` and may still be running when it returns: a host that wants `out`
+ * synchronises `stream`.  Calls on one cache must not overlap, and follow one another on one stream or are ordered by
+ * the caller.  After COOP_E_RANGE the in-range cached ids of the
  * call count as touched and nothing was inserted; `out` is then unspecified.
  */
 int coop_cache_gather(coop_cache* c, const void* table, int64_t table_rows, const int32_t* ids, int64_t n_ids, void* out,

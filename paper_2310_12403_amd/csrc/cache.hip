@@ -72,19 +72,13 @@ struct OrderEntry {
 };
 __global__ __launch_bounds__(kBlock) void k_cache_split(const uint64_t* __restrict__ hit_bits, const uint32_t* __restrict__ word_rank,
                                                         const int32_t* __restrict__ ids, const int32_t* __restrict__ slot_i,
-                                                        int64_t n_ids, OrderEntry* __restrict__ order,
-                                                        uint64_t* __restrict__ stamp, uint64_t clock) {
+                                                        int64_t n_ids, OrderEntry* __restrict__ order) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n_ids) return;
   const uint64_t word = hit_bits[i >> 6];
   const int64_t h = (int64_t)word_rank[i >> 6] + __popcll(word & ((1ull << (i & 63)) - 1ull));
-  if ((word >> (i & 63)) & 1ull) {
-    const int32_t slot = slot_i[i];
-    order[h] = OrderEntry{(int32_t)i, slot};
-    stamp[slot] = clock + (uint64_t)h;  // the h-th hit of the call; set here so that the eviction need not wait for the hit rows
-  } else {
-    order[n_ids - 1 - (i - h)] = OrderEntry{(int32_t)i, ids[i]};
-  }
+  if ((word >> (i & 63)) & 1ull) order[h] = OrderEntry{(int32_t)i, slot_i[i]};
+  else order[n_ids - 1 - (i - h)] = OrderEntry{(int32_t)i, ids[i]};
 }
 
 // ---- row movers -----------------------------------------------------------------------------------------------
@@ -92,7 +86,8 @@ __global__ __launch_bounds__(kBlock) void k_cache_split(const uint64_t* __restri
 template <typename V>
 __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ rows, int32_t vecs, int lpr_log2,
                                                        const OrderEntry* __restrict__ order,
-                                                       const CacheCtl* __restrict__ ctl, V* __restrict__ out) {
+                                                       const CacheCtl* __restrict__ ctl, V* __restrict__ out,
+                                                       uint64_t* __restrict__ stamp, uint64_t clock) {
   const int64_t n_hit = ctl->n_hit;  // known on the device before the host has read it
   const int lpr = 1 << lpr_log2;
   const int rows_per_block = kBlock >> lpr_log2;
@@ -119,6 +114,13 @@ __global__ __launch_bounds__(kBlock) void k_cache_hits(const V* __restrict__ row
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u)
       if (src[u] >= 0) __builtin_nontemporal_store(x[u], out + dst[u] * vecs + v);
+  }
+  // the new stamps go out behind the rows: memory operations complete in the order in which they were sent, and the row
+  // loads must not wait for these scattered stores
+  if (sub == 0) {
+#pragma unroll
+    for (int u = 0; u < kRowUnroll; ++u)
+      if (src[u] >= 0) stamp[src[u]] = clock + (uint64_t)(row0 + (int64_t)u * rows_per_block);
   }
 }
 
@@ -168,9 +170,8 @@ __global__ __launch_bounds__(kBlock) void k_cache_misses(const V* __restrict__ t
       }
     }
   }
-  // the books of the rows that entered the cache, behind the row traffic: memory operations complete in the order in which
-  // they were sent, and the row loads must not wait for these scattered stores (a kernel of its own for them costs more
-  // than it takes off this one)
+  // the books of the rows that entered the cache, behind the row traffic as well (a kernel of its own for these three
+  // stores costs more than it takes off this one)
   if (sub == 0) {
 #pragma unroll
     for (int u = 0; u < kRowUnroll; ++u)
@@ -319,6 +320,20 @@ __global__ void k_cache_ctl_set(CacheCtl* ctl, uint64_t remaining) {
 
 __global__ void k_cache_clear_err(CacheCtl* ctl) { ctl->err_range = 0; }
 
+// Landing pad in mapped pinned host memory.  The counts of a call reach the host by a one-thread kernel that stores the
+// control block and then a ticket, which the host polls: quicker than an asynchronous copy and a wait for it.
+struct CachePad {
+  CacheCtl ctl;          // counts of the call under way; must stay the first member
+  uint64_t ticket;       // written by the device after ctl
+  uint64_t next_ticket;  // host side only
+  CacheCtl threshold;    // control block after the last eviction (copied, read one call late)
+};
+__global__ void k_cache_publish(const CacheCtl* __restrict__ ctl, CachePad* pad, uint64_t ticket) {
+  pad->ctl = *ctl;
+  __threadfence_system();
+  __hip_atomic_store(&pad->ticket, ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __global__ __launch_bounds__(kBlock) void k_fill_i32(int32_t* __restrict__ p, int64_t n, int32_t v, bool iota) {
   int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * kBlock;
@@ -345,11 +360,8 @@ struct coop_cache {
   void* scan_tmp;
   uint32_t* hist;
   CacheCtl* d_ctl;
-  CacheCtl* h_ctl;        // pinned, two of them: [0] the counts of the call under way, [1] the threshold of the last eviction
-  hipStream_t aux;        // the hit rows move on this stream while the eviction runs on the caller's
-  hipEvent_t ev_counts;   // counts of the call have landed in h_ctl[0]
-  hipEvent_t ev_hits;     // hit rows of the call are in `out`
-  hipEvent_t ev_threshold;  // threshold of the last eviction has landed in h_ctl[1]
+  CachePad* pad;          // mapped pinned
+  hipEvent_t ev_threshold;  // threshold of the last eviction has landed in pad->threshold
   bool base_pending;      // ... and has not been added to base yet
   // host-side state
   int64_t size;           // entries held
@@ -357,20 +369,17 @@ struct coop_cache {
   uint64_t base;          // every live stamp is >= base (last eviction threshold + 1)
 };
 
-// Pinned memory, stream and events of a cache; whatever was created is released.
+// Pinned memory and event of a cache; whatever was created is released.
 static void release_host_side(coop_cache* c) {
-  if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
   if (c->ev_threshold) { (void)hipEventSynchronize(c->ev_threshold); (void)hipEventDestroy(c->ev_threshold); }
-  if (c->ev_counts) (void)hipEventDestroy(c->ev_counts);
-  if (c->ev_hits) (void)hipEventDestroy(c->ev_hits);
-  if (c->h_ctl) (void)hipHostFree(c->h_ctl);
+  if (c->pad) (void)hipHostFree(c->pad);
 }
 
 // The threshold of the last eviction, once it has arrived: everything at or below it is gone.
 static int settle_base(coop_cache* c) {
   if (!c->base_pending) return COOP_OK;
   COOP_HIP_TRY(hipEventSynchronize(c->ev_threshold));
-  c->base += c->h_ctl[1].prefix + 1;
+  c->base += c->pad->threshold.prefix + 1;
   c->base_pending = false;
   return COOP_OK;
 }
@@ -409,15 +418,13 @@ extern "C" int coop_cache_create(int64_t capacity_rows, int64_t n_vertices, int3
   c->hist = alloc.get<uint32_t>(kSelBins, COOP_TAG_OUTPUT);
   c->d_ctl = alloc.get<CacheCtl>(1, COOP_TAG_OUTPUT);
   if (alloc.failed) { delete c; return COOP_E_NOMEM; }
-  if (hipHostMalloc((void**)&c->h_ctl, 2 * sizeof(CacheCtl), hipHostMallocDefault) != hipSuccess ||
-      hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) != hipSuccess ||  // (default priority)
-      hipEventCreateWithFlags(&c->ev_counts, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&c->ev_hits, hipEventDisableTiming) != hipSuccess ||
+  if (hipHostMalloc((void**)&c->pad, sizeof(CachePad), hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess ||
       hipEventCreateWithFlags(&c->ev_threshold, hipEventDisableTiming) != hipSuccess) {
     release_host_side(c);
     delete c;
     return COOP_E_HIP;
   }
+  *c->pad = CachePad{};
   c->size = 0; c->clock = 1; c->base = 1;
   if (n_vertices > 0) COOP_LAUNCH(K_FILL, k_fill_i32, dim3(grid_for(n_vertices)), dim3(kBlock), 0, s, c->slot_of, n_vertices, -1, false);
   if (capacity_rows > 0) {
@@ -549,9 +556,9 @@ extern "C" int coop_cache_import(coop_cache* c, const void* table, int64_t table
     COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_import_check, dim3(grid_for(state->size)), dim3(kBlock), 0, s, c->slot_of, c->vertex_of, state->size,
                 c->d_ctl);
   }
-  COOP_HIP_TRY(hipMemcpyAsync(c->h_ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
+  COOP_HIP_TRY(hipMemcpyAsync(&c->pad->ctl, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
   COOP_HIP_TRY(hipStreamSynchronize(s));
-  if (c->h_ctl->err_range) {  // a bad list (vertex out of range or listed twice, zero stamp): leave an empty cache
+  if (c->pad->ctl.err_range) {  // a bad list (vertex out of range or listed twice, zero stamp): leave an empty cache
     reset(0);
     COOP_HIP_TRY(hipStreamSynchronize(s));
     c->size = 0; c->clock = 1; c->base = 1;
@@ -592,7 +599,7 @@ void launch_rows(coop_cache* c, const void* table, int64_t table_rows, const int
   const unsigned grid = (unsigned)((n_ids + rows_per_launch_block - 1) / rows_per_launch_block);
   if (hits) {
     COOP_LAUNCH(K_CACHE_GATHER, k_cache_hits<V>, dim3(grid), dim3(kBlock), 0, s, (const V*)c->rows, vecs, lpr_log2, (const OrderEntry*)c->order,
-                c->d_ctl, (V*)out);
+                c->d_ctl, (V*)out, c->stamp, c->clock);
   } else {
     const unsigned grid_m = (unsigned)((n_miss + rows_per_launch_block - 1) / rows_per_launch_block);
     COOP_LAUNCH(K_CACHE_UPDATE, k_cache_misses<V>, dim3(grid_m), dim3(kBlock), 0, s, (const V*)table, vecs, lpr_log2, (const OrderEntry*)c->order, n_ids,
@@ -627,32 +634,38 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
 
   // (a call on another stream than the last one's: the threshold of that one is still to be copied out of the control block)
   if (c->base_pending) COOP_HIP_TRY(hipStreamWaitEvent(s, c->ev_threshold, 0));
-  // 1. lookup, hit ranks, new stamps of the hits
+  // 1. lookup, hit ranks
   COOP_LAUNCH(K_FILL, k_cache_ctl_set, dim3(1), dim3(1), 0, s, c->d_ctl, (uint64_t)0);
   COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_lookup, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, ids, n_ids,
               c->n_vertices, c->slot_of, c->slot_i, c->hit_bits, c->d_ctl);
   scan_popc_to_u32(c->hit_bits, (n_ids + 63) / 64, c->rank_h, &c->d_ctl->n_hit, c->scan_tmp, s);
+  const uint64_t ticket = ++c->pad->next_ticket;  // the counts are known from here on: on their way while the split runs
+  COOP_LAUNCH(K_FILL, k_cache_publish, dim3(1), dim3(1), 0, s, (const CacheCtl*)c->d_ctl, c->pad, ticket);
   COOP_LAUNCH(K_CACHE_LOOKUP, k_cache_split, dim3((unsigned)((n_ids + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, (const uint64_t*)c->hit_bits,
-              (const uint32_t*)c->rank_h, ids, (const int32_t*)c->slot_i, n_ids, c->order, c->stamp, c->clock);
-  COOP_HIP_TRY(hipMemcpyAsync(&c->h_ctl[0], c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
-  COOP_HIP_TRY(hipEventRecord(c->ev_counts, s));
-  // 2. hits: rows out of the cache, on the second stream: they touch nothing that the eviction or the miss rows write
-  //    (a slot that was hit carries the newest stamps and is not evicted, except when everything is: see below), so they
-  //    run beside the select passes and the sweep, which leave most of the chip idle
-  COOP_HIP_TRY(hipStreamWaitEvent(c->aux, c->ev_counts, 0));
-  dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, 0, 0, 0, 0, true, c->aux);
-  COOP_HIP_TRY(hipEventRecord(c->ev_hits, c->aux));
-  COOP_HIP_TRY(hipEventSynchronize(c->ev_counts));
+              (const uint32_t*)c->rank_h, ids, (const int32_t*)c->slot_i, n_ids, c->order);
+  // 2. hits: rows out of the cache, new stamps (runs while the host waits for the counts and queues the rest)
+  dispatch_rows(c, vec_bytes, table, table_rows, ids, n_ids, out, 0, 0, 0, 0, true, s);
+  {  // the wait is bounded: after a while, or once the stream has run dry, the host synchronises instead
+    bool seen = false;
+    for (int64_t spin = 0; spin < ((int64_t)1 << 26); ++spin) {
+      if (__atomic_load_n(&c->pad->ticket, __ATOMIC_ACQUIRE) == ticket) { seen = true; break; }
+      if ((spin & 0xFFFF) == 0xFFFF && hipStreamQuery(s) == hipSuccess) break;
+      __builtin_ia32_pause();
+    }
+    if (!seen) {
+      COOP_HIP_TRY(hipStreamSynchronize(s));
+      if (__atomic_load_n(&c->pad->ticket, __ATOMIC_ACQUIRE) != ticket) return COOP_E_HIP;
+    }
+  }
   if (int rc = settle_base(c)) return rc;
-  if (c->h_ctl[0].err_range) {
+  if (c->pad->ctl.err_range) {
     // the cached ids of this call were already served and re-stamped: keep the stamps unique, insert nothing
     COOP_LAUNCH(K_FILL, k_cache_clear_err, dim3(1), dim3(1), 0, s, c->d_ctl);
     c->clock += (uint64_t)n_ids;
-    (void)hipStreamWaitEvent(s, c->ev_hits, 0);
     (void)hipStreamSynchronize(s);
     return COOP_E_RANGE;
   }
-  const int64_t n_hit = c->h_ctl[0].n_hit;
+  const int64_t n_hit = c->pad->ctl.n_hit;
   const int64_t n_miss = n_ids - n_hit;
   const int64_t n_ins = n_miss < c->capacity ? n_miss : c->capacity;
   int64_t n_evict = c->size + n_ins - c->capacity;
@@ -664,7 +677,6 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
   bool threshold_known = false;
   if (n_evict > 0) {
     const bool evict_all = n_evict >= c->size;
-    if (evict_all) COOP_HIP_TRY(hipStreamWaitEvent(s, c->ev_hits, 0));  // the hit slots are given away as well: after their rows are out
     if (!evict_all) {
       uint64_t range = clock_after - c->base;  // live stamps minus base lie in [0, range)
       int nbits = 1;
@@ -703,11 +715,10 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
   c->clock = clock_after;
 
   if (threshold_known) {  // read when it is next needed: the call does not wait for its own row copies
-    COOP_HIP_TRY(hipMemcpyAsync(&c->h_ctl[1], c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
+    COOP_HIP_TRY(hipMemcpyAsync(&c->pad->threshold, c->d_ctl, sizeof(CacheCtl), hipMemcpyDeviceToHost, s));
     COOP_HIP_TRY(hipEventRecord(c->ev_threshold, s));
     c->base_pending = true;
   }
-  COOP_HIP_TRY(hipStreamWaitEvent(s, c->ev_hits, 0));  // work behind this call on the caller's stream sees all of `out`
   if (n_miss_out) *n_miss_out = n_miss;
   return COOP_OK;
 }

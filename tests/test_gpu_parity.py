@@ -264,10 +264,10 @@ def test_cache_on_sampled_batches_with_kappa(P, medium):
 
 
 def test_cache_on_a_side_stream_without_host_waits(P):
-    """The hit rows move on a stream of the cache's own and the eviction threshold is read back one call late: work
-    queued behind a call on the caller's stream must still see all of `out`, and a sequence of calls with no host
-    synchronisation between them must keep the textbook LRU's books (also across an export, which needs the threshold
-    of the call before it)."""
+    """A call returns once its counts are known, with the eviction and the miss rows still queued, and the eviction
+    threshold is read back one call late: work queued behind a call on the caller's stream must see all of `out`, and
+    a sequence of calls with no host synchronisation between them must keep the textbook LRU's books (also across an
+    export, which needs the threshold of the call before it)."""
     n, dim, cap = 6000, 64, 1500
     rng = np.random.default_rng(77)
     feat = synth.features(n, dim, torch.float16, seed=6, device="cpu")
