@@ -811,12 +811,13 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
     bst.cand = cand;
   }
   const uint32_t lane = (uint32_t)lane_id();
+  const uint32_t wpb = blockDim.x / kWave;  // waves per block (at most kWavesPerBlock)
   if constexpr (VEC == 4) {
     if ((int)blockIdx.x < piece_blocks) {
       uint32_t n_pieces = *piece_count;
       if (n_pieces > piece_cap) n_pieces = piece_cap;
-      const uint32_t n_waves = (uint32_t)piece_blocks * kWavesPerBlock;
-      for (uint32_t p = blockIdx.x * kWavesPerBlock + (uint32_t)uniform_wave_in_block(); p < n_pieces; p += n_waves) {
+      const uint32_t n_waves = (uint32_t)piece_blocks * wpb;
+      for (uint32_t p = blockIdx.x * wpb + (uint32_t)uniform_wave_in_block(); p < n_pieces; p += n_waves) {
         const Piece pc = pieces[p];
         const uint32_t list = (uint32_t)__builtin_amdgcn_readfirstlane((int)pc.list);
         if (list == kNoPiece) continue;
@@ -872,7 +873,7 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
       return;
     }
   }
-  const int64_t wave = ((int64_t)blockIdx.x - piece_blocks) * kWavesPerBlock + uniform_wave_in_block();
+  const int64_t wave = ((int64_t)blockIdx.x - piece_blocks) * wpb + uniform_wave_in_block();
   const int64_t first = wave * lists_per_wave;
   if (first >= n) return;
   const int64_t mine = first + lane;
@@ -1068,14 +1069,14 @@ __global__ __launch_bounds__(kBlock) void k_labor_fill_overflow(const int32_t* _
 }
 
 template <bool BLEND, int VEC>
-static void launch_scan(int nf, dim3 grid, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, const PreThr* pthr, const float* lim2, int64_t n,
+static void launch_scan(int nf, dim3 grid, dim3 block, hipStream_t s, const int32_t* indices, const Segment* seg, const uint32_t* thr, const PreThr* pthr, const float* lim2, int64_t n,
                         int lpw, const FusedKeys& keys, uint32_t cap, const ScanOut& out, Ctl* ctl, int piece_blocks, const Piece* pieces,
                         const uint32_t* piece_count, uint32_t piece_cap, uint32_t piece_len, const CandOut& cand) {
   switch (nf) {
-    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
-    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
-    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
-    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, dim3(kBlock), 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, block, 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, block, 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, block, 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, block, 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
   }
 }
 
@@ -1275,15 +1276,22 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       const int64_t n_waves = (n_new + lpw - 1) / lpw;
       // the piece waves come first in the grid: one round of resident blocks, fewer if there cannot be that many pieces
       constexpr int64_t kPieceBlocks = 2048;
-      const int piece_blocks = (int)(blocks_for(piece_cap, kWavesPerBlock) < kPieceBlocks ? blocks_for(piece_cap, kWavesPerBlock) : kPieceBlocks);
-      const dim3 grid(blocks_for(n_waves, kWavesPerBlock) + (unsigned)piece_blocks);
+      // waves per block: a block leaves the CU when its slowest wave is done, and the lists differ in length by orders
+      // of magnitude, so with four waves a block's slots stand empty for much of its life; two waves per block take 8 %
+      // off the scan with independent variates (one: 5 %).  The blended kernel has its first-stage queues in static LDS,
+      // four per block whatever the block size, and loses waves per CU with smaller blocks (1.27 -> 1.73 / 2.60 ms).
+      const int wpb = cx.blend ? kWavesPerBlock : 2;
+      const dim3 block((unsigned)(wpb * kWave));
+      const int64_t piece_waves = (int64_t)piece_cap < kPieceBlocks * kWavesPerBlock ? (int64_t)piece_cap : kPieceBlocks * kWavesPerBlock;
+      const int piece_blocks = (int)blocks_for(piece_waves, wpb);
+      const dim3 grid(blocks_for(n_waves, wpb) + (unsigned)piece_blocks);
       const uint32_t* pcount = cx.d_piece_count + l;
       if (cx.blend) {
-        if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len, cand);
-        else launch_scan<true, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u, cand);
+        if (cx.vec4) launch_scan<true, 4>(ps.nf, grid, block, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len, cand);
+        else launch_scan<true, 1>(ps.nf, grid, block, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u, cand);
       } else {
-        if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len, cand);
-        else launch_scan<false, 1>(ps.nf, grid, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u, cand);
+        if (cx.vec4) launch_scan<false, 4>(ps.nf, grid, block, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, piece_blocks, pieces, pcount, piece_cap, piece_len, cand);
+        else launch_scan<false, 1>(ps.nf, grid, block, s, cx.g->indices, ps.seg, ps.thr, pthr, lim2, n_new, lpw, keys, cap, out, cx.d_ctl, 0, pieces, pcount, 0u, 0u, cand);
       }
       if (queued) {  // stage 3: the exact blend for the candidates that the scan appended
         const unsigned blocks = blocks_for(cand.cap_each, kBlock) < 16 ? blocks_for(cand.cap_each, kBlock) : 16;

@@ -705,7 +705,10 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
   if (m > 0 && n_dst > 0) {
-    int wpb = kWavesPerBlock;
+    // waves per block: with independent variates one (a block leaves the CU when its slowest wave is done, and a wave
+    // takes one list, short or long: 1.59 -> 1.52 ms on the papers100M-shaped layer); the kernels of the blended path keep
+    // their queues in static LDS, four per block whatever the block size
+    int wpb = cx.blend ? kWavesPerBlock : 1;
     while (wpb > 1 && (size_t)wpb * cap * 16 > 65536) wpb >>= 1;
     const size_t shmem = (size_t)wpb * cap * 16;
     const dim3 grid(blocks_for(n_dst, wpb));
@@ -735,9 +738,9 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
       else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand, 0u,
                        (const uint32_t*)nullptr, (const uint32_t*)nullptr, 0);
     } else {
-      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, true>), grid_q, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr, long_min,
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, true>), grid_q, dim3(wpb * kWave), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr, long_min,
                                (const uint32_t*)long_list, (const uint32_t*)n_long, long_blocks);
-      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, false>), grid_q, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr, long_min,
+      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, false>), grid_q, dim3(wpb * kWave), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr, long_min,
                        (const uint32_t*)long_list, (const uint32_t*)n_long, long_blocks);
     }
 #undef COOP_NS_ARGS
