@@ -804,10 +804,10 @@ __global__ __launch_bounds__(kBlock) void k_labor_scan(const int32_t* __restrict
                                                        const uint32_t* __restrict__ piece_count, uint32_t piece_cap, uint32_t piece_len,
                                                        CandOut cand) {
   constexpr bool kQueued = BLEND && VEC == 4;  // blended variates through the staged filters
-  __shared__ FirstQueue first_queues[kQueued ? kWavesPerBlock : 1];
+  extern __shared__ __align__(16) uint32_t scan_lds[];  // with kQueued: a FirstQueue per wave of the block
   BlendState bst{};
   if constexpr (kQueued) {
-    bst.q1 = &first_queues[uniform_wave_in_block()];
+    bst.q1 = reinterpret_cast<FirstQueue*>(scan_lds) + uniform_wave_in_block();
     bst.cand = cand;
   }
   const uint32_t lane = (uint32_t)lane_id();
@@ -1073,10 +1073,10 @@ static void launch_scan(int nf, dim3 grid, dim3 block, hipStream_t s, const int3
                         int lpw, const FusedKeys& keys, uint32_t cap, const ScanOut& out, Ctl* ctl, int piece_blocks, const Piece* pieces,
                         const uint32_t* piece_count, uint32_t piece_cap, uint32_t piece_len, const CandOut& cand) {
   switch (nf) {
-    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, block, 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
-    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, block, 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
-    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, block, 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
-    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, block, 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    case 1: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 1>), grid, block, (BLEND && VEC == 4) ? (size_t)(block.x / kWave) * sizeof(FirstQueue) : 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    case 2: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 2>), grid, block, (BLEND && VEC == 4) ? (size_t)(block.x / kWave) * sizeof(FirstQueue) : 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    case 3: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 3>), grid, block, (BLEND && VEC == 4) ? (size_t)(block.x / kWave) * sizeof(FirstQueue) : 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
+    default: COOP_LAUNCH(K_LABOR_COUNT, (k_labor_scan<BLEND, VEC, 4>), grid, block, (BLEND && VEC == 4) ? (size_t)(block.x / kWave) * sizeof(FirstQueue) : 0, s, indices, seg, thr, pthr, lim2, n, lpw, keys, cap, out, ctl, piece_blocks, pieces, piece_count, piece_cap, piece_len, cand); break;
   }
 }
 
@@ -1277,10 +1277,10 @@ int labor_layer(LaborState& st, const SampleCtx& cx, int l, const int32_t* dst, 
       // the piece waves come first in the grid: one round of resident blocks, fewer if there cannot be that many pieces
       constexpr int64_t kPieceBlocks = 2048;
       // waves per block: a block leaves the CU when its slowest wave is done, and the lists differ in length by orders
-      // of magnitude, so with four waves a block's slots stand empty for much of its life; two waves per block take 8 %
-      // off the scan with independent variates (one: 5 %).  The blended kernel has its first-stage queues in static LDS,
-      // four per block whatever the block size, and loses waves per CU with smaller blocks (1.27 -> 1.73 / 2.60 ms).
-      const int wpb = cx.blend ? kWavesPerBlock : 2;
+      // of magnitude, so with four waves a block's slots stand empty for much of its life; two waves per block take 3 to
+      // 8 % off the scan with independent variates (one: 2 to 5 %), one wave per block 2 % off the blended one, which
+      // is bound by its arithmetic (its first-stage queues are dynamic LDS, one per wave of the block)
+      const int wpb = cx.blend ? 1 : 2;
       const dim3 block((unsigned)(wpb * kWave));
       const int64_t piece_waves = (int64_t)piece_cap < kPieceBlocks * kWavesPerBlock ? (int64_t)piece_cap : kPieceBlocks * kWavesPerBlock;
       const int piece_blocks = (int)blocks_for(piece_waves, wpb);

@@ -393,7 +393,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
                                                     uint32_t long_min, const uint32_t* __restrict__ long_list,
                                                     const uint32_t* __restrict__ n_long, int long_blocks) {
   extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
-  __shared__ NsQueue queues[BLEND ? kWavesPerBlock : 1];
+  NsQueue* queues = reinterpret_cast<NsQueue*>(lds_words + (size_t)waves_per_block * cap * 4);  // (with c > 0; behind the candidates)
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
   NsQueue* queue = &queues[BLEND ? wib : 0];
@@ -433,7 +433,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_collect(const int32_t* __restrict
                                                        uint32_t long_min, const uint32_t* __restrict__ long_list,
                                                        const uint32_t* __restrict__ n_long, int long_blocks) {
   extern __shared__ uint32_t lds_words[];
-  __shared__ NsQueue queues[kWavesPerBlock];
+  NsQueue* queues = reinterpret_cast<NsQueue*>(lds_words + (size_t)waves_per_block * cap * 4);  // (behind the candidates)
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
   const bool queue_wave = (int)blockIdx.x < long_blocks;  // the queued long lists first, as in k_ns_fill
@@ -705,12 +705,11 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
   blk->col_local = alloc.get<int32_t>(m, COOP_TAG_OUTPUT);
   if (alloc.failed) return COOP_E_NOMEM;
   if (m > 0 && n_dst > 0) {
-    // waves per block: with independent variates one (a block leaves the CU when its slowest wave is done, and a wave
-    // takes one list, short or long: 1.59 -> 1.52 ms on the papers100M-shaped layer); the kernels of the blended path keep
-    // their queues in static LDS, four per block whatever the block size
-    int wpb = cx.blend ? kWavesPerBlock : 1;
-    while (wpb > 1 && (size_t)wpb * cap * 16 > 65536) wpb >>= 1;
-    const size_t shmem = (size_t)wpb * cap * 16;
+    // one wave per block: a block leaves the CU when its slowest wave is done, and a wave takes one list, short or long;
+    // with four waves a block's slots stood empty for much of its life (fill 1.61 -> 1.52 ms on the papers100M-shaped
+    // layer; with dependent variates the traversal 3.0 -> 2.57 ms and the selection 0.99 -> 0.91)
+    const int wpb = 1;
+    const size_t shmem = (size_t)wpb * cap * 16 + (cx.blend ? (size_t)wpb * sizeof(NsQueue) : 0);
     const dim3 grid(blocks_for(n_dst, wpb));
 #define COOP_NS_ARGS cx.g->indices, rec, bthr, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid, m, cx.d_ctl
     // the queue's waves, one per queued list: as many as there can be lists that long, by the degree census of the
@@ -727,15 +726,15 @@ int ns_layer(const SampleCtx& cx, int l, const int32_t* dst, int64_t n_dst, coop
       NsCand* rows = alloc.get<NsCand>(n_dst * (int64_t)row_cap, COOP_TAG_SCRATCH);
       uint32_t* n_cand = alloc.get<uint32_t>(n_dst, COOP_TAG_SCRATCH);
       if (alloc.failed) return COOP_E_NOMEM;
-      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, k_ns_collect<true>, grid_q, dim3(kBlock), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand, long_min,
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, k_ns_collect<true>, grid_q, dim3(wpb * kWave), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand, long_min,
                                (const uint32_t*)long_list, (const uint32_t*)n_long, long_blocks);
-      else COOP_LAUNCH(K_NS_FILL, k_ns_collect<false>, grid_q, dim3(kBlock), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand, long_min,
+      else COOP_LAUNCH(K_NS_FILL, k_ns_collect<false>, grid_q, dim3(wpb * kWave), shmem, s, COOP_NS_ARGS, rows, row_cap, n_cand, long_min,
                        (const uint32_t*)long_list, (const uint32_t*)n_long, long_blocks);
-      COOP_LAUNCH(K_NS_SELECT, k_ns_select, grid, dim3(kBlock), shmem, s, rec, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid,
+      COOP_LAUNCH(K_NS_SELECT, k_ns_select, grid, dim3(wpb * kWave), shmem, s, rec, n_dst, k, cap, wpb, vp, blk->indptr, blk->col_global, blk->eid,
                   (const NsCand*)rows, row_cap, n_cand, (const NsBlendThr*)bthr);
-      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand, 0u,
+      if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, true>), grid, dim3(wpb * kWave), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand, 0u,
                                (const uint32_t*)nullptr, (const uint32_t*)nullptr, 0);
-      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(kBlock), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand, 0u,
+      else COOP_LAUNCH(K_NS_FILL, (k_ns_fill<true, false>), grid, dim3(wpb * kWave), shmem, s, COOP_NS_ARGS, (const uint32_t*)n_cand, 0u,
                        (const uint32_t*)nullptr, (const uint32_t*)nullptr, 0);
     } else {
       if (cx.vec4) COOP_LAUNCH(K_NS_FILL, (k_ns_fill<false, true>), grid_q, dim3(wpb * kWave), shmem, s, COOP_NS_ARGS, (const uint32_t*)nullptr, long_min,
