@@ -95,7 +95,8 @@ struct NsQueue {
 };
 
 // One pass over the list [beg, beg + d): every neighbour whose variate is <= bound is appended to the candidate
-// arrays (variate, list position, vertex) in LDS, in no particular order; returns how many qualified (entries beyond
+// arrays in LDS (key = variate in the upper, list position in the lower half of 64 bits: the order of the selection;
+// vertex), in no particular order; returns how many qualified (entries beyond
 // `cap` are counted but not stored).  Long lists in a 16-byte aligned array are read as aligned groups of four
 // entries, kNsGroups groups per lane and step, whole groups in the main loop and the ragged ends in one extra step.
 // With c > 0 the variate of an entry is evaluated exactly only if the integer bounds and then the fp32 blend cannot
@@ -105,15 +106,20 @@ struct NsQueue {
 template <bool BLEND, bool VEC4, bool STAGED = false>
 __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_indices, int64_t beg, uint32_t d, uint32_t bound,
                                                const NsBlendThr& bt, const VariateParams& vp, uint32_t sigma_a, uint32_t sigma_b,
-                                               uint32_t* __restrict__ cand_r, uint32_t* __restrict__ cand_j,
-                                               int32_t* __restrict__ cand_t, uint32_t cap, NsQueue* __restrict__ q) {
+                                               uint64_t* __restrict__ cand_key, int32_t* __restrict__ cand_t, uint32_t cap,
+                                               NsQueue* __restrict__ q) {
   const uint32_t lane = (uint32_t)lane_id();
   uint32_t n_c = 0;
   auto append = [&](bool in, uint32_t r, uint32_t j, int32_t t) {
     const uint64_t mask = ballot64(in);
     if (mask == 0) return;
     const uint32_t p = n_c + lanes_below(mask);
-    if (in && p < cap) { cand_r[p] = r; cand_j[p] = j; cand_t[p] = t; }
+    if (in && p < cap) {
+      uint32_t* half = reinterpret_cast<uint32_t*>(cand_key + p);  // two 32-bit stores: no register pair needed in the hot loop
+      half[0] = j;
+      half[1] = r;
+      cand_t[p] = t;
+    }
     n_c += (uint32_t)__popcll(mask);
   };
   // ---- blended path: queue, and evaluation of its first n entries --------------------------------------------------
@@ -257,25 +263,22 @@ __device__ __forceinline__ uint32_t ns_collect(const int32_t* __restrict__ g_ind
 // The k smallest by (variate, list position) among the n_c candidates in LDS (k <= n_c <= cap), written to the edge arrays
 // from o on in adjacency order: every candidate's rank among the candidates is counted, ranks below k are kept, and a
 // kept candidate's place is the number of kept candidates in front of it in the list.
-__device__ __forceinline__ void ns_rank_write(uint32_t n_c, uint32_t k, const uint32_t* cand_r, const uint32_t* cand_j, uint32_t* cand_k,
-                                              const int32_t* cand_t, int64_t o, int64_t beg, int32_t* __restrict__ col_global,
-                                              int64_t* __restrict__ eid) {
+__device__ __forceinline__ void ns_rank_write(uint32_t n_c, uint32_t k, const uint64_t* cand_key, uint32_t* cand_k, const int32_t* cand_t,
+                                              int64_t o, int64_t beg, int32_t* __restrict__ col_global, int64_t* __restrict__ eid) {
   const uint32_t lane = (uint32_t)lane_id();
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
   if (n_c <= (uint32_t)kWave) {
-    // the usual case: one candidate per lane, ranked through lane reads (no LDS round trips in the loops)
+    // the usual case: one candidate per lane; every lane reads the keys one after the other from LDS (the same address
+    // for all lanes: a broadcast), two vector instructions per candidate where reading variate and position out of the
+    // other lanes' registers cost seven
     const bool has = lane < n_c;
-    const uint32_t my_r = has ? cand_r[lane] : 0xFFFFFFFFu;
-    const uint32_t my_j = has ? cand_j[lane] : 0xFFFFFFFFu;
+    const uint64_t my_key = has ? cand_key[lane] : ~0ull;
+    const uint32_t my_j = (uint32_t)my_key;
     const int32_t my_t = has ? cand_t[lane] : 0;
-    const uint64_t my_key = ((uint64_t)my_r << 32) | my_j;  // order by (variate, list position)
     uint32_t rank = 0;
-    for (uint32_t q = 0; q < n_c; ++q) {
-      const uint64_t key = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)my_r, (int)q) << 32) |
-                           (uint32_t)__builtin_amdgcn_readlane((int)my_j, (int)q);
-      rank += key < my_key;
-    }
+    const uint32_t n_u = (uint32_t)__builtin_amdgcn_readfirstlane((int)n_c);
+    for (uint32_t q = 0; q < n_u; ++q) rank += cand_key[q] < my_key;
     const bool keep = has && rank < k;
     const uint64_t kept = ballot64(keep);
     uint32_t place = 0;  // kept candidates in front of this one in the list
@@ -292,21 +295,18 @@ __device__ __forceinline__ void ns_rank_write(uint32_t n_c, uint32_t k, const ui
     return;
   }
   for (uint32_t i = lane; i < n_c; i += kWave) {
-    const uint32_t my_r = cand_r[i], my_j = cand_j[i];
+    const uint64_t my_key = cand_key[i];
     uint32_t rank = 0;
-    for (uint32_t q = 0; q < n_c; ++q) {
-      const uint32_t r = cand_r[q];
-      rank += (r < my_r) || (r == my_r && cand_j[q] < my_j);
-    }
+    for (uint32_t q = 0; q < n_c; ++q) rank += cand_key[q] < my_key;
     cand_k[i] = rank < k;
   }
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
   for (uint32_t i = lane; i < n_c; i += kWave) {
     if (!cand_k[i]) continue;
-    const uint32_t my_j = cand_j[i];
+    const uint32_t my_j = (uint32_t)cand_key[i];
     uint32_t place = 0;
-    for (uint32_t q = 0; q < n_c; ++q) place += cand_k[q] && cand_j[q] < my_j;
+    for (uint32_t q = 0; q < n_c; ++q) place += cand_k[q] && (uint32_t)cand_key[q] < my_j;
     col_global[o + place] = cand_t[i];
     eid[o + place] = beg + my_j;
   }
@@ -346,10 +346,9 @@ __device__ __forceinline__ void ns_fill_one(int64_t w, int wib, uint32_t* lds_wo
   }
   if (d > skip_above) return;    // queued: one of the first waves takes it
   if (k > kNsMaxSelect) return;  // a degree above a fanout that the candidate buffer cannot serve: left to k_ns_fill_wide
-  uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;  // [cap] variates
-  uint32_t* cand_j = cand_r + cap;                       // [cap] positions (d < 2^31)
-  uint32_t* cand_k = cand_j + cap;                       // [cap] 1 = among the k smallest
-  int32_t* cand_t = reinterpret_cast<int32_t*>(cand_k + cap);  // [cap] the neighbours themselves
+  uint64_t* cand_key = reinterpret_cast<uint64_t*>(lds_words + (size_t)wib * cap * 4);  // [cap] (variate, position), d < 2^31
+  uint32_t* cand_k = lds_words + (size_t)wib * cap * 4 + 2 * cap;                       // [cap] 1 = among the k smallest
+  int32_t* cand_t = reinterpret_cast<int32_t*>(cand_k + cap);                           // [cap] the neighbours themselves
   const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)s);
   const uint32_t sigma_b = BLEND ? ns_sigma(vp.K.Kb, (uint32_t)s) : 0u;
 
@@ -359,7 +358,7 @@ __device__ __forceinline__ void ns_fill_one(int64_t w, int wib, uint32_t* lds_wo
   if constexpr (BLEND) bt = bthr[w];
   uint32_t n_c = 0;
   for (int attempt = 0; attempt < 40; ++attempt) {
-    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, bt, vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap, queue);
+    n_c = ns_collect<BLEND, VEC4>(g_indices, beg, d, (uint32_t)bound, bt, vp, sigma_a, sigma_b, cand_key, cand_t, cap, queue);
     if (n_c >= k && n_c <= cap) break;
     // cannot be bracketed (more than cap - k equal variates): report instead of guessing
     if (n_c < k) {
@@ -379,7 +378,7 @@ __device__ __forceinline__ void ns_fill_one(int64_t w, int wib, uint32_t* lds_wo
     if (lane == 0) atomicOr(&ctl->err_capacity, 1);
     return;
   }
-  ns_rank_write(n_c, k, cand_r, cand_j, cand_k, cand_t, o, beg, col_global, eid);
+  ns_rank_write(n_c, k, cand_key, cand_k, cand_t, o, beg, col_global, eid);
 }
 
 template <bool BLEND, bool VEC4>
@@ -392,7 +391,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_fill(const int32_t* __restrict__ 
                                                     const uint32_t* __restrict__ only /* when not null: only lists marked kNsRedo */,
                                                     uint32_t long_min, const uint32_t* __restrict__ long_list,
                                                     const uint32_t* __restrict__ n_long, int long_blocks) {
-  extern __shared__ uint32_t lds_words[];  // per wave: cap variates, cap list positions, cap keep flags, cap vertex ids
+  extern __shared__ __align__(16) uint32_t lds_words[];  // per wave: cap 64-bit keys, cap keep flags, cap vertex ids
   NsQueue* queues = reinterpret_cast<NsQueue*>(lds_words + (size_t)waves_per_block * cap * 4);  // (with c > 0; behind the candidates)
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
@@ -432,7 +431,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_collect(const int32_t* __restrict
                                                        Ctl* ctl, NsCand* __restrict__ rows, uint32_t row_cap, uint32_t* __restrict__ n_cand,
                                                        uint32_t long_min, const uint32_t* __restrict__ long_list,
                                                        const uint32_t* __restrict__ n_long, int long_blocks) {
-  extern __shared__ uint32_t lds_words[];
+  extern __shared__ __align__(16) uint32_t lds_words[];
   NsQueue* queues = reinterpret_cast<NsQueue*>(lds_words + (size_t)waves_per_block * cap * 4);  // (behind the candidates)
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
@@ -463,11 +462,10 @@ __global__ __launch_bounds__(kBlock) void k_ns_collect(const int32_t* __restrict
     return;
   }
   if (k > kNsMaxSelect) return;  // (k_ns_fill_wide)
-  uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;
-  uint32_t* cand_j = cand_r + cap;
-  int32_t* cand_t = reinterpret_cast<int32_t*>(cand_j + 2 * cap);
+  uint64_t* cand_key = reinterpret_cast<uint64_t*>(lds_words + (size_t)wib * cap * 4);
+  int32_t* cand_t = reinterpret_cast<int32_t*>(lds_words + (size_t)wib * cap * 4 + 3 * cap);
   const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)g.s), sigma_b = ns_sigma(vp.K.Kb, (uint32_t)g.s);
-  const uint32_t n_c = ns_collect<true, VEC4, true>(g_indices, g.beg, g.d, g.bound, bthr[w], vp, sigma_a, sigma_b, cand_r, cand_j, cand_t, cap,
+  const uint32_t n_c = ns_collect<true, VEC4, true>(g_indices, g.beg, g.d, g.bound, bthr[w], vp, sigma_a, sigma_b, cand_key, cand_t, cap,
                                                     &queues[wib]);
   __builtin_amdgcn_wave_barrier();
   __threadfence_block();
@@ -476,7 +474,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_collect(const int32_t* __restrict
     return;
   }
   NsCand* row = rows + (size_t)w * row_cap;
-  for (uint32_t i = lane; i < n_c; i += kWave) row[i] = NsCand{cand_j[i], cand_t[i]};
+  for (uint32_t i = lane; i < n_c; i += kWave) row[i] = NsCand{(uint32_t)cand_key[i], cand_t[i]};
   if (lane == 0) n_cand[w] = n_c;
 }
 
@@ -485,7 +483,7 @@ __global__ __launch_bounds__(kBlock) void k_ns_select(const NsRecord* __restrict
                                                       int32_t* __restrict__ col_global, int64_t* __restrict__ eid,
                                                       const NsCand* __restrict__ rows, uint32_t row_cap, uint32_t* __restrict__ n_cand,
                                                       const NsBlendThr* __restrict__ bthr) {
-  extern __shared__ uint32_t lds_words[];
+  extern __shared__ __align__(16) uint32_t lds_words[];
   const int wib = uniform_wave_in_block();
   if (wib >= waves_per_block) return;
   const int64_t w = (int64_t)blockIdx.x * waves_per_block + wib;
@@ -494,9 +492,8 @@ __global__ __launch_bounds__(kBlock) void k_ns_select(const NsRecord* __restrict
   if (n == 0 || n == kNsRedo) return;  // done by the collecting kernel, or left to k_ns_fill
   const uint32_t lane = (uint32_t)lane_id();
   const NsRecord g = rec[w];
-  uint32_t* cand_r = lds_words + (size_t)wib * cap * 4;
-  uint32_t* cand_j = cand_r + cap;
-  uint32_t* cand_k = cand_j + cap;
+  uint64_t* cand_key = reinterpret_cast<uint64_t*>(lds_words + (size_t)wib * cap * 4);
+  uint32_t* cand_k = lds_words + (size_t)wib * cap * 4 + 2 * cap;
   int32_t* cand_t = reinterpret_cast<int32_t*>(cand_k + cap);
   const uint32_t sigma_a = ns_sigma(vp.K.Ka, (uint32_t)g.s), sigma_b = ns_sigma(vp.K.Kb, (uint32_t)g.s);
   const NsCand* row = rows + (size_t)w * row_cap;
@@ -574,14 +571,14 @@ __global__ __launch_bounds__(kBlock) void k_ns_select(const NsRecord* __restrict
     }
     const uint64_t mask = ballot64(in);
     const uint32_t at = n_c + lanes_below(mask);
-    if (in) { cand_r[at] = R; cand_j[at] = c.j; cand_t[at] = c.t; }  // (n <= cap)
+    if (in) { cand_key[at] = ((uint64_t)R << 32) | c.j; cand_t[at] = c.t; }  // (n <= cap)
     n_c += (uint32_t)__popcll(mask);
   }
   if (n_c < k) {
     if (lane == 0) n_cand[w] = kNsRedo;
     return;
   }
-  ns_rank_write(n_c, k, cand_r, cand_j, cand_k, cand_t, eptr[w], g.beg, col_global, eid);
+  ns_rank_write(n_c, k, cand_key, cand_k, cand_t, eptr[w], g.beg, col_global, eid);
 }
 
 // ---- fanouts above kNsMaxSelect ----------------------------------------------------------------------------------
