@@ -507,11 +507,16 @@ __global__ __launch_bounds__(kBlock) void k_ns_select(const NsRecord* __restrict
     if (has) c = row[lane];
     const uint32_t u1 = keyed_uniform<true>(vp.K.Ka, (uint32_t)c.t, sigma_a), u2 = keyed_uniform<true>(vp.K.Kb, (uint32_t)c.t, sigma_b);
     const float est = has ? __builtin_fmaf((float)vp.cw, approx_phi_inv_f32(u1), (float)vp.sw * approx_phi_inv_f32(u2)) : __builtin_inff();
+    // rank by (estimate, lane): the estimates (finite for every candidate) go to LDS as 64-bit keys, their bits mapped so
+    // that unsigned order is numeric order, and every lane reads them back as broadcasts (as in ns_rank_write)
+    const uint32_t eb = __float_as_uint(est);
+    const uint64_t est_key = ((uint64_t)(eb ^ ((uint32_t)((int32_t)eb >> 31) | 0x80000000u)) << 32) | lane;
+    if (has) cand_key[lane] = est_key;
+    __builtin_amdgcn_wave_barrier();
+    __threadfence_block();
     uint32_t rank_est = 0;
-    for (uint32_t q = 0; q < n; ++q) {
-      const float e = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(est), (int)q));
-      rank_est += (e < est) || (e == est && q < lane);
-    }
+    const uint32_t n_u = (uint32_t)__builtin_amdgcn_readfirstlane((int)n);
+    for (uint32_t q = 0; q < n_u; ++q) rank_est += cand_key[q] < est_key;
     const uint64_t kth = ballot64(has && rank_est == k - 1);  // exactly one lane (n >= k)
     const float e_k = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(est), __builtin_ctzll(kth)));
     const float allow = (float)((vp.cw + vp.sw) * kPhiInvF32Allow + 2.0 * kBlendAbsWiden);
