@@ -690,6 +690,31 @@ def test_frontier_dedup_modes(P, tiny, medium, mode):
         P.coop_tune(P.COOP_TUNE_DEFER_SIZES, 1)
 
 
+def test_repeated_neighbours_and_unsorted_lists(P):
+    """A multigraph with unsorted lists (legal without COOP_SYMMETRIC): a neighbour that occurs several times in a list
+    has the same variate each time, so NS must break the tie by list position (in the candidate ranking, in the
+    two-kernel path with dependent variates, and in the bisection of the wide-fanout path), LABOR-0 keeps every copy or
+    none, and the walks see the copies as separate edges.  Every array against the oracle."""
+    rng = np.random.default_rng(404)
+    n = 3000
+    deg = np.where(rng.random(n) < 0.5, rng.integers(0, 400, n), np.minimum(rng.zipf(1.6, n), 2500)).astype(np.int64)
+    deg[:4] = (6000, 2200, 1500, 0)                                  # hubs above the wide-fanout limit, and an empty list
+    ip = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    # each list draws from a pool a quarter of its length: most neighbours occur several times, in random order
+    ix = np.concatenate([rng.integers(0, n, max(1, d // 4))[rng.integers(0, max(1, d // 4), d)] for d in deg]).astype(np.int32)
+    g = G(P, torch.from_numpy(ip), torch.from_numpy(ix))
+    seeds = np.concatenate([np.arange(4), synth.seed_batches(n, 600, seed=7)(0).numpy()])
+    seeds = np.unique(seeds).astype(np.int32)
+    hubs = np.arange(3, dtype=np.int32)
+    for kappa, it in ((1, 0), (4, 6), (0, 9)):
+        compare(P, g, seeds, (10, 5), R.NS, it=it, kappa=kappa, seed=11)
+        compare(P, g, seeds, (10, 5), R.LABOR0, it=it, kappa=kappa, seed=12)
+        compare(P, g, hubs, (40, 3), R.NS, it=it, kappa=kappa, seed=13)       # more than 64 candidates per list
+    compare(P, g, hubs, (2000,), R.NS, it=1, seed=14)                         # above the candidate arrays: bisection
+    compare(P, g, hubs, (1500, 2), R.NS, it=2, kappa=4, seed=15)
+    compare_rw(P, g, seeds[:200], (5, 5), 3, 20, 0.3, it=3, seed=16)
+
+
 def test_randomized_configurations(P, draw_seed=20240, cases=400):
     """Seeded random draws of graph shape, batch, depth, fanouts, sampler, iteration / kappa and of the library's
     internal modes (piece length, layer fusion, staging rows, read-back mode, dedup mode, lists per wave, the lengths from

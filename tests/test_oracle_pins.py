@@ -216,6 +216,27 @@ def test_sample_equals_brute_force(sampler, fanouts):
                 assert b[name].tolist() == w[name], name
 
 
+@pytest.mark.parametrize("sampler", [R.NS, R.LABOR0])
+def test_repeated_neighbours_against_brute_force(sampler):
+    """A multigraph with unsorted lists: a neighbour listed several times has one variate, so NS breaks the tie by list
+    position (the brute force sorts (variate, position) pairs) and LABOR-0 keeps every copy or none."""
+    rng = np.random.default_rng(23)
+    n = 60
+    deg = rng.integers(0, 30, n)
+    deg[0] = 90
+    indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    indices = np.concatenate([rng.integers(0, n, max(1, d // 4))[rng.integers(0, max(1, d // 4), d)] for d in deg]).astype(np.int32)
+    assert any(len(set(indices[indptr[v]:indptr[v + 1]])) < deg[v] // 2 for v in range(n))       # the copies are there
+    for trial, fanouts in enumerate([(3, 2), (7,), (2, 2, 2)]):
+        seeds = np.concatenate([[0], 1 + rng.choice(n - 1, 8, replace=False)]).astype(np.int32)
+        seed, g = 77 + trial, 3 * trial
+        got = R.sample(indptr, indices, seeds, fanouts, sampler, it=g, kappa=1, seed=seed)
+        want = brute_sample(indptr, indices, seeds, fanouts, sampler, seed, g)
+        for b, w in zip(got, want):
+            for name in ("dst_ids", "indptr", "col_global", "eid", "src_ids", "col_local"):
+                assert b[name].tolist() == w[name], name
+
+
 def check_invariants(indptr, indices, blocks, seeds, fanouts, sampler):
     deg = np.diff(indptr)
     prev = np.asarray(seeds)
