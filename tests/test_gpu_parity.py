@@ -238,6 +238,16 @@ def test_cache_matches_textbook_lru(P, cap, table_dev):
     run_cache_sequence(P, cap, n, 64, torch.float32, batches, table_dev)
 
 
+@pytest.mark.parametrize("dtype,dim", [(torch.float16, 3), (torch.float16, 1), (torch.float16, 100), (torch.float32, 1),
+                                       (torch.float32, 602), (torch.float16, 1025)])
+def test_cache_row_shapes(P, dtype, dim):
+    """Rows whose size leaves the movers only 2-, 4- or 8-byte vectors, and rows longer than one pass of a lane group."""
+    n = 2500
+    rng = np.random.default_rng(dim)
+    batches = [rng.choice(n, int(rng.integers(1, 700)), replace=False).astype(np.int32) for _ in range(12)]
+    run_cache_sequence(P, 400, n, dim, dtype, batches, "cuda" if dim % 2 else "pinned")
+
+
 def test_cache_on_sampled_batches_with_kappa(P, medium):
     """Input sets of consecutive dependent LABOR-0 batches through the cache: misses equal the oracle's on every
     iteration, and a larger kappa lowers the miss count (temporal locality of Sec. 4.2)."""
