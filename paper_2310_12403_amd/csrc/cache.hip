@@ -697,8 +697,12 @@ extern "C" int coop_cache_gather(coop_cache* c, const void* table, int64_t table
       threshold_known = true;
     }
     {
+      // at most 1,024 blocks: every block reserves its places with an atomic on one counter, which takes them one after
+      // the other (some 20 ns each), and the longer runs of neighbouring slots that a block hands out make the rows that
+      // the miss mover writes next lie closer together (with 2,048 blocks the sweep takes 0.086 instead of 0.077 ms and
+      // the mover 0.38 instead of 0.34 to 0.36; with 256 the sweep itself takes 0.117)
       int64_t blocks = (c->capacity + kBlock - 1) / kBlock;
-      if (blocks > 2048) blocks = 2048;
+      if (blocks > 1024) blocks = 1024;
       int64_t chunk = (c->capacity + blocks - 1) / blocks;
       chunk = (chunk + kBlock - 1) / kBlock * kBlock;
       blocks = (c->capacity + chunk - 1) / chunk;
